@@ -1,0 +1,114 @@
+/*
+ * gka.h -- C ABI of libgka: the Gated KalmaNet (GKA) layer forward pass on AMD MI355X (gfx950).
+ *
+ * The library evaluates, for every (batch, head) pair and token t, the recurrence of the paper's
+ * Eq. (CH) (Section 4.1, "Forward Recurrence"):
+ *
+ *     H_t = gamma_t H_{t-1} + k_t k_t^T,      U_t = gamma_t U_{t-1} + v_t k_t^T,
+ *     xhat_t = CH(H_t + lambda_t I, q_t, r),  y_t = U_t xhat_t,
+ *
+ * where CH is r passes of the Chebyshev Iteration (Algorithm 1) with eigenvalue bounds
+ * L = ||H_t||_F + lambda_t and mu = lambda_t (Section 4.1, "Adaptive Regularization").
+ * gka_forward processes whole sequences chunk-wise (Section 4.2.1); gka_decode_step advances
+ * stored states by one token.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers. The caller owns every buffer; the library never
+ *     allocates, frees or synchronises. All work is enqueued on the given HIP stream
+ *     (a hipStream_t passed as void*; NULL is the default stream).
+ *   - Every call returns a gka_status. Argument errors are detected on the host before any
+ *     kernel is launched, and leave all buffers untouched.
+ *   - Value preconditions are NOT checked: gamma in (0, 1], lambda > 0, finite inputs.
+ *     Gates below exp(-100) are treated as exp(-100).
+ *   - State layout: H[b][h][i][j] (d_k x d_k) and U[b][h][i_v][j_k] (d_v x d_k, U = sum v k^T),
+ *     row-major float32.
+ */
+#ifndef GKA_H_
+#define GKA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GKA_OK = 0,
+    GKA_ERR_NULL = 1,         /* a required pointer is NULL                                   */
+    GKA_ERR_SHAPE = 2,        /* non-positive or inconsistent size / stride                   */
+    GKA_ERR_UNSUPPORTED = 3,  /* head dimension, chunk, dtype or compute mode not supported   */
+    GKA_ERR_WORKSPACE = 4,    /* workspace NULL, misaligned or smaller than the query says    */
+    GKA_ERR_LAUNCH = 5        /* a HIP call or kernel launch reported an error                */
+} gka_status;
+
+typedef enum { GKA_F32 = 0, GKA_BF16 = 1 } gka_dtype;
+
+/* Arithmetic of the matrix products.
+ * GKA_COMPUTE_F32 : float32 operands on the float32 MFMA path (required for GKA_F32 tensors; also
+ *                   the mode for ill-conditioned problems with bf16 tensors).
+ * GKA_COMPUTE_BF16: bf16 operands with float32 accumulation on the bf16 MFMA path; the Chebyshev
+ *                   iterate, the residual and all per-token scalars stay float32. */
+typedef enum { GKA_COMPUTE_F32 = 0, GKA_COMPUTE_BF16 = 1 } gka_compute;
+
+typedef struct {
+    int32_t B;            /* batch (gka_decode_step: number of sequences)                      */
+    int32_t H;            /* heads                                                             */
+    int32_t T;            /* tokens per sequence (ignored by gka_decode_step); any T >= 1      */
+    int32_t d_k;          /* head dimension of q, k: 64 or 128                                 */
+    int32_t d_v;          /* head dimension of v, o: must equal d_k                            */
+    int32_t chunk;        /* chunk size C of Section 4.2.1: 64 (T need not be a multiple)      */
+    int32_t n_iter;       /* r of Algorithm 1 = number of loop passes; 0 returns U_t xi_0      */
+    int32_t io_dtype;     /* gka_dtype of q, k, v, o                                           */
+    int32_t compute;      /* gka_compute                                                       */
+    int32_t reserved;     /* must be 0                                                         */
+    int64_t stride_b;     /* element strides of q, k, v, o between batches, tokens and heads;  */
+    int64_t stride_t;     /*   the head dimension is contiguous. 0,0,0 selects the packed      */
+    int64_t stride_h;     /*   [B,T,H,d] layout of the paper's tensors (Appendix D)            */
+} gka_params;
+
+/* Bytes of scratch gka_forward needs for these parameters (0 if they are invalid). The buffer must
+ * be 256-byte aligned. It holds the chunk initial states H_[n], U_[n] of Section 4.2.1 in the
+ * operand layout of the solve kernel; its contents after a call are unspecified. */
+size_t gka_forward_workspace_bytes(const gka_params *p);
+
+/* Whole-sequence forward, Eq. (CH).
+ *   q, k     [B,T,H,d_k]  io_dtype           v  [B,T,H,d_v]  io_dtype
+ *   gate     [B,T,H] float32, gamma_t        lambda [B,T,H] float32, lambda_t > 0
+ *   o        [B,T,H,d_v]  io_dtype (written)
+ *   H_init   [B,H,d_k,d_k], U_init [B,H,d_v,d_k] float32, or NULL for zero initial states;
+ *            gamma of the first token multiplies the initial state
+ *   H_final, U_final      same shapes, written if not NULL (state after the last token)
+ *   fro_out  [B,T,H] float32 ||H_t||_F, written if not NULL
+ *   workspace, workspace_bytes: see gka_forward_workspace_bytes
+ * gate and lambda are packed [B,T,H] regardless of the q/k/v strides. */
+gka_status gka_forward(const gka_params *p,
+                       const void *q, const void *k, const void *v,
+                       const float *gate, const float *lambda,
+                       void *o,
+                       const float *H_init, const float *U_init,
+                       float *H_final, float *U_final,
+                       float *fro_out,
+                       void *workspace, size_t workspace_bytes,
+                       void *hip_stream);
+
+/* One recurrent step of Eq. (CH) on stored states (T is ignored).
+ *   H_state [B,H,d_k,d_k], U_state [B,H,d_v,d_k] float32, updated IN PLACE
+ *   q, k [B,H,d_k], v [B,H,d_v] io_dtype (packed); gate, lambda [B,H] float32
+ *   o [B,H,d_v] io_dtype (written)
+ * The arithmetic is float32 for either compute mode. */
+gka_status gka_decode_step(const gka_params *p,
+                           float *H_state, float *U_state,
+                           const void *q, const void *k, const void *v,
+                           const float *gate, const float *lambda,
+                           void *o, void *hip_stream);
+
+const char *gka_status_string(gka_status s);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int gka_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GKA_H_ */

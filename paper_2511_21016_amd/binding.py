@@ -1,0 +1,164 @@
+"""Thin ctypes binding of libgka (include/gka.h). Argument marshalling only: every step of the path
+runs in the library's HIP kernels. PyTorch is used for device memory and streams, nothing else.
+
+The library must have been built (python -m paper_2511_21016_amd.build, or __graft_entry__.build());
+loading fails loudly otherwise. There is no CPU fallback.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgka.so")
+
+GKA_OK, GKA_ERR_NULL, GKA_ERR_SHAPE, GKA_ERR_UNSUPPORTED, GKA_ERR_WORKSPACE, GKA_ERR_LAUNCH = range(6)
+GKA_F32, GKA_BF16 = 0, 1
+GKA_COMPUTE_F32, GKA_COMPUTE_BF16 = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "gka_forward_workspace_bytes",
+    "gka_forward",
+    "gka_decode_step",
+    "gka_status_string",
+    "gka_version",
+)
+
+
+class GkaParams(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("T", ctypes.c_int32),
+        ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32), ("chunk", ctypes.c_int32),
+        ("n_iter", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("compute", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
+        ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
+    ]
+
+
+class GkaError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"libgka status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library():
+    """Load libgka.so once; raise if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it first (python -m paper_2511_21016_amd.build)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, fp = ctypes.c_void_p, ctypes.c_void_p
+        lib.gka_forward_workspace_bytes.argtypes = [ctypes.POINTER(GkaParams)]
+        lib.gka_forward_workspace_bytes.restype = ctypes.c_size_t
+        lib.gka_forward.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, vp,
+                                    ctypes.c_size_t, vp]
+        lib.gka_forward.restype = ctypes.c_int
+        lib.gka_decode_step.argtypes = [ctypes.POINTER(GkaParams), fp, fp, vp, vp, vp, fp, fp, vp, vp]
+        lib.gka_decode_step.restype = ctypes.c_int
+        lib.gka_status_string.argtypes = [ctypes.c_int]
+        lib.gka_status_string.restype = ctypes.c_char_p
+        lib.gka_version.argtypes = []
+        lib.gka_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def status_string(status):
+    return load_library().gka_status_string(int(status)).decode()
+
+
+def version():
+    return int(load_library().gka_version())
+
+
+def make_params(B, H, T, d, n_iter, io_dtype, compute, chunk=64, d_v=None, strides=(0, 0, 0)):
+    return GkaParams(B=B, H=H, T=T, d_k=d, d_v=d if d_v is None else d_v, chunk=chunk, n_iter=n_iter,
+                     io_dtype=io_dtype, compute=compute, reserved=0,
+                     stride_b=strides[0], stride_t=strides[1], stride_h=strides[2])
+
+
+def forward_workspace_bytes(params):
+    return int(load_library().gka_forward_workspace_bytes(ctypes.byref(params)))
+
+
+def forward_raw(params, q, k, v, gate, lam, o, H_init=None, U_init=None, H_final=None, U_final=None,
+                fro_out=None, workspace=None, workspace_bytes=0, stream=None):
+    """gka_forward on raw device addresses (ints or None). Returns the gka_status."""
+    pp = None if params is None else ctypes.byref(params)
+    return int(load_library().gka_forward(pp, q, k, v, gate, lam, o, H_init, U_init, H_final,
+                                          U_final, fro_out, workspace, workspace_bytes, stream))
+
+
+def decode_step_raw(params, H_state, U_state, q, k, v, gate, lam, o, stream=None):
+    pp = None if params is None else ctypes.byref(params)
+    return int(load_library().gka_decode_step(pp, H_state, U_state, q, k, v, gate, lam, o, stream))
+
+
+def _check(status):
+    if status != GKA_OK:
+        raise GkaError(status, status_string(status))
+
+
+def _io_dtype(t):
+    import torch
+    if t.dtype == torch.float32:
+        return GKA_F32
+    if t.dtype == torch.bfloat16:
+        return GKA_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=None, U_init=None,
+                return_state=False, return_fro=False, workspace=None, out=None):
+    """gka_forward on torch CUDA tensors: q, k, v [B,T,H,d] (float32 or bfloat16, contiguous),
+    gate, lam [B,T,H] float32. Enqueues on torch's current stream and returns o (and a dict of the
+    requested extras). Nothing here computes: it allocates outputs and passes pointers."""
+    import torch
+    if not (q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
+        raise ValueError("q, k, v must be contiguous CUDA tensors")
+    B, T, H, d = q.shape
+    io = _io_dtype(q)
+    if compute is None:
+        compute = GKA_COMPUTE_BF16 if io == GKA_BF16 else GKA_COMPUTE_F32
+    params = make_params(B, H, T, d, n_iter, io, compute, chunk=chunk, d_v=v.shape[-1])
+    nbytes = forward_workspace_bytes(params)
+    if nbytes == 0:
+        # let the library name the error
+        _check(forward_raw(params, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam), _ptr(q)))
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    o = torch.empty_like(v) if out is None else out
+    extras = {}
+    Hf = Uf = fro = None
+    if return_state:
+        Hf = torch.empty((B, H, d, d), dtype=torch.float32, device=q.device)
+        Uf = torch.empty((B, H, d, d), dtype=torch.float32, device=q.device)
+        extras["H_final"], extras["U_final"] = Hf, Uf
+    if return_fro:
+        fro = torch.empty((B, T, H), dtype=torch.float32, device=q.device)
+        extras["fro"] = fro
+    stream = torch.cuda.current_stream(q.device).cuda_stream
+    _check(forward_raw(params, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam), _ptr(o), _ptr(H_init),
+                       _ptr(U_init), _ptr(Hf), _ptr(Uf), _ptr(fro), _ptr(workspace), workspace.numel(), stream))
+    return (o, extras) if extras else o
+
+
+def gka_decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None):
+    """gka_decode_step on torch CUDA tensors: states [B,H,d,d] float32 (updated in place), q, k, v [B,H,d],
+    gate, lam [B,H] float32."""
+    import torch
+    B, H, d = q.shape
+    io = _io_dtype(q)
+    params = make_params(B, H, 1, d, n_iter, io, GKA_COMPUTE_F32)
+    o = torch.empty_like(v) if out is None else out
+    stream = torch.cuda.current_stream(q.device).cuda_stream
+    _check(decode_step_raw(params, _ptr(H_state), _ptr(U_state), _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam),
+                           _ptr(o), stream))
+    return o

@@ -1,0 +1,142 @@
+// Host side of the C ABI declared in include/gka.h: argument validation, workspace carving and kernel
+// launches on the caller's stream. No allocation, no synchronisation, no global state.
+#include "../../include/gka.h"
+#include "gka_kernels.hpp"
+
+namespace {
+
+struct Plan {
+    int n_pairs, n_chunks, d;
+    bool io_bf16, compute_bf16;
+    int64_t stride_b, stride_t, stride_h;
+    size_t off_H, off_U, off_hn, total;
+};
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+gka_status check_common(const gka_params *p, bool decode)
+{
+    if (!p) return GKA_ERR_NULL;
+    if (p->B <= 0 || p->H <= 0 || p->n_iter < 0) return GKA_ERR_SHAPE;
+    if (!decode && p->T <= 0) return GKA_ERR_SHAPE;
+    if (p->d_k <= 0 || p->d_v <= 0) return GKA_ERR_SHAPE;
+    if (p->reserved != 0) return GKA_ERR_SHAPE;
+    if (p->d_k != p->d_v) return GKA_ERR_UNSUPPORTED;
+    if (p->d_k != 64 && p->d_k != 128) return GKA_ERR_UNSUPPORTED;
+    if (p->io_dtype != GKA_F32 && p->io_dtype != GKA_BF16) return GKA_ERR_UNSUPPORTED;
+    if (p->compute != GKA_COMPUTE_F32 && p->compute != GKA_COMPUTE_BF16) return GKA_ERR_UNSUPPORTED;
+    if (p->io_dtype == GKA_F32 && p->compute == GKA_COMPUTE_BF16) return GKA_ERR_UNSUPPORTED;
+    if (!decode && p->chunk != gka::kChunk) return GKA_ERR_UNSUPPORTED;
+    if ((int64_t)p->B * p->H > (int64_t)1 << 24) return GKA_ERR_SHAPE;
+    return GKA_OK;
+}
+
+gka_status make_plan(const gka_params *p, Plan *pl)
+{
+    gka_status s = check_common(p, false);
+    if (s != GKA_OK) return s;
+    pl->d = p->d_k;
+    pl->n_pairs = p->B * p->H;
+    pl->n_chunks = (p->T + gka::kChunk - 1) / gka::kChunk;
+    pl->io_bf16 = p->io_dtype == GKA_BF16;
+    pl->compute_bf16 = p->compute == GKA_COMPUTE_BF16;
+    if ((int64_t)pl->n_pairs * pl->n_chunks > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
+    if (p->stride_b == 0 && p->stride_t == 0 && p->stride_h == 0) {
+        pl->stride_h = p->d_k;
+        pl->stride_t = (int64_t)p->H * p->d_k;
+        pl->stride_b = (int64_t)p->T * p->H * p->d_k;
+    } else {
+        if (p->stride_b <= 0 || p->stride_t <= 0 || p->stride_h <= 0) return GKA_ERR_SHAPE;
+        if (p->stride_h < p->d_k && p->H > 1) return GKA_ERR_SHAPE;
+        if (p->stride_t % 4 || p->stride_h % 4 || p->stride_b % 4) return GKA_ERR_SHAPE;  // vector stores
+        pl->stride_b = p->stride_b;
+        pl->stride_t = p->stride_t;
+        pl->stride_h = p->stride_h;
+    }
+    const size_t nc = (size_t)pl->n_pairs * pl->n_chunks;
+    pl->off_H = 0;
+    pl->off_U = align_up(pl->off_H + nc * gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
+    pl->off_hn = align_up(pl->off_U + nc * gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
+    pl->total = align_up(pl->off_hn + nc * gka::ws_hn_bytes_per_chunk(pl->d), 256);
+    return GKA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t gka_forward_workspace_bytes(const gka_params *p)
+{
+    Plan pl;
+    if (make_plan(p, &pl) != GKA_OK) return 0;
+    return pl.total;
+}
+
+gka_status gka_forward(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
+                       const float *lambda, void *o, const float *H_init, const float *U_init, float *H_final,
+                       float *U_final, float *fro_out, void *workspace, size_t workspace_bytes,
+                       void *hip_stream)
+{
+    Plan pl;
+    gka_status s = make_plan(p, &pl);
+    if (s != GKA_OK) return s;
+    if (!q || !k || !v || !gate || !lambda || !o) return GKA_ERR_NULL;
+    if ((H_init == nullptr) != (U_init == nullptr)) return GKA_ERR_NULL;
+    if ((H_final == nullptr) != (U_final == nullptr)) return GKA_ERR_NULL;
+    if (!workspace || workspace_bytes < pl.total || ((uintptr_t)workspace & 255)) return GKA_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+
+    gka::StatePassArgs sa;
+    sa.k = k; sa.v = v; sa.gate = gate;
+    sa.H_init = H_init; sa.U_init = U_init;
+    sa.H_final = H_final; sa.U_final = U_final;
+    sa.ws_H = ws + pl.off_H; sa.ws_U = ws + pl.off_U; sa.ws_hn = (float *)(ws + pl.off_hn);
+    sa.stride_b = pl.stride_b; sa.stride_t = pl.stride_t; sa.stride_h = pl.stride_h;
+    sa.H = p->H; sa.T = p->T;
+    sa.n_chunks = pl.n_chunks; sa.chunk0 = 0; sa.n_chunks_total = pl.n_chunks;
+    if (gka::launch_state_pass(sa, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
+        return GKA_ERR_LAUNCH;
+
+    gka::SolveArgs so;
+    so.q = q; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
+    so.ws_H = sa.ws_H; so.ws_U = sa.ws_U; so.ws_hn = sa.ws_hn;
+    so.stride_b = pl.stride_b; so.stride_t = pl.stride_t; so.stride_h = pl.stride_h;
+    so.H = p->H; so.T = p->T; so.n_chunks_total = pl.n_chunks; so.n_iter = p->n_iter;
+    if (gka::launch_chunk_solve(so, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
+        return GKA_ERR_LAUNCH;
+    return GKA_OK;
+}
+
+gka_status gka_decode_step(const gka_params *p, float *H_state, float *U_state, const void *q, const void *k,
+                           const void *v, const float *gate, const float *lambda, void *o, void *hip_stream)
+{
+    gka_status s = check_common(p, true);
+    if (s != GKA_OK) return s;
+    if (!H_state || !U_state || !q || !k || !v || !gate || !lambda || !o) return GKA_ERR_NULL;
+    gka::DecodeArgs da;
+    da.H_state = H_state; da.U_state = U_state;
+    da.q = q; da.k = k; da.v = v; da.gate = gate; da.lambda = lambda; da.o = o;
+    da.n_iter = p->n_iter;
+    if (gka::launch_decode_step(da, p->B * p->H, p->d_k, p->io_dtype == GKA_BF16, (hipStream_t)hip_stream) !=
+        hipSuccess)
+        return GKA_ERR_LAUNCH;
+    return GKA_OK;
+}
+
+const char *gka_status_string(gka_status s)
+{
+    switch (s) {
+    case GKA_OK: return "ok";
+    case GKA_ERR_NULL: return "required pointer is NULL";
+    case GKA_ERR_SHAPE: return "invalid size or stride";
+    case GKA_ERR_UNSUPPORTED: return "unsupported head dimension, chunk, dtype or compute mode";
+    case GKA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case GKA_ERR_LAUNCH: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+int gka_version(void) { return 100; }
+
+}  // extern "C"

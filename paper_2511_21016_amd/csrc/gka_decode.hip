@@ -1,0 +1,134 @@
+// One recurrent step of Eq. (CH) per (sequence, head) pair: state update, ||H_t||_F, Algorithm 1 with the
+// matrix held in registers, readout. One workgroup of 256 threads per pair; all arithmetic fp32.
+//
+// The d x d states are distributed as float4 pieces in flat row-major order, piece (it*256 + t) on thread
+// t, so that state reads and writes are fully coalesced: thread t holds, for each of its ITS pieces, row
+// i = it*RPI + t / C4 and columns 4*(t % C4) .. +3 (C4 = d/4 pieces per row, RPI = 256/C4 rows per sweep).
+// H is symmetric, so H x is evaluated column-wise, (H x)_j = sum_i H[i][j] x_i: every thread accumulates
+// its rows into its four columns, and the 256/C4 partial sums per column are combined through LDS.
+#include "gka_device.hpp"
+#include "gka_kernels.hpp"
+
+namespace gka {
+
+template <class IO, int D>
+__global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
+{
+    constexpr int C4 = D / 4;
+    constexpr int RPI = 256 / C4;
+    constexpr int ITS = D / RPI;
+    const int t = threadIdx.x;
+    const int pair = blockIdx.x;
+    const int col4 = t % C4, rgrp = t / C4;
+
+    __shared__ float s_q[D], s_k[D], s_v[D];
+    __shared__ float s_x[D];                 // operand of the current product (delta_i or xhat)
+    __shared__ float s_part[RPI][D];         // per row-group partial column sums
+    __shared__ float s_red[4];
+
+    float *Hs = a.H_state + (int64_t)pair * D * D;
+    float *Us = a.U_state + (int64_t)pair * D * D;
+    if (t < D) {
+        s_q[t] = IO::load(a.q, (int64_t)pair * D + t);
+        s_k[t] = IO::load(a.k, (int64_t)pair * D + t);
+        s_v[t] = IO::load(a.v, (int64_t)pair * D + t);
+    }
+    const float gamma = a.gate[pair];
+    const float lam = a.lambda[pair];
+    f32x4 hreg[ITS], ureg[ITS];
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+        hreg[it] = *(const f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4);
+        ureg[it] = *(const f32x4 *)(Us + (int64_t)(it * 256 + t) * 4);
+    }
+    __syncthreads();
+
+    // ---- state update (Eq. (CH)) and ||H_t||_F^2
+    float kc[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) kc[e] = s_k[4 * col4 + e];
+    float ss = 0.0f;
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+        const int row = it * RPI + rgrp;
+        const float kr = s_k[row], vr = s_v[row];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            hreg[it][e] = gamma * hreg[it][e] + kr * kc[e];
+            ureg[it][e] = gamma * ureg[it][e] + vr * kc[e];
+            ss += hreg[it][e] * hreg[it][e];
+        }
+        *(f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4) = hreg[it];
+        *(f32x4 *)(Us + (int64_t)(it * 256 + t) * 4) = ureg[it];
+    }
+    ss = wave_sum(ss);
+    if ((t & 63) == 0) s_red[t >> 6] = ss;
+    __syncthreads();
+    const float fro = sqrtf(s_red[0] + s_red[1] + s_red[2] + s_red[3]);
+
+    // ---- Algorithm 1 in residual form; thread j < D owns component j of xi, delta, r
+    const float L = fro + lam, mu = lam;
+    const float s0 = 2.0f / (L + mu);
+    const float rho = (L - mu) / (L + mu);
+    const float rho2 = rho * rho;
+    float xi = 0.0f, dl = 0.0f, rs = 0.0f;
+    if (t < D) {
+        xi = s0 * s_q[t];
+        dl = xi;
+        rs = s_q[t];
+        s_x[t] = dl;
+    }
+    float omega = 2.0f;
+    __syncthreads();
+    for (int i = 0; i < a.n_iter; ++i) {
+        float p[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const float xr = s_x[it * RPI + rgrp];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) p[e] += hreg[it][e] * xr;
+        }
+        *(f32x4 *)&s_part[rgrp][4 * col4] = f32x4{p[0], p[1], p[2], p[3]};
+        __syncthreads();
+        omega = 4.0f / (4.0f - rho2 * omega);
+        if (t < D) {
+            float hx = 0.0f;
+#pragma unroll
+            for (int rg = 0; rg < RPI; ++rg) hx += s_part[rg][t];
+            rs -= hx + lam * dl;
+            dl = (omega - 1.0f) * dl + omega * s0 * rs;
+            xi += dl;
+            s_x[t] = dl;
+        }
+        __syncthreads();
+    }
+
+    // ---- readout y = U xhat (rows of U are not symmetric: reduce each row over its C4 lanes)
+    if (t < D) s_x[t] = xi;
+    __syncthreads();
+    float xc[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) xc[e] = s_x[4 * col4 + e];
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+        float y = ureg[it][0] * xc[0] + ureg[it][1] * xc[1] + ureg[it][2] * xc[2] + ureg[it][3] * xc[3];
+#pragma unroll
+        for (int off = C4 / 2; off > 0; off >>= 1) y += __shfl_xor(y, off, 64);
+        if (col4 == 0) IO::store1(a.o, (int64_t)pair * D + it * RPI + rgrp, y);
+    }
+}
+
+hipError_t launch_decode_step(const DecodeArgs &a, int n_pairs, int d, bool io_bf16, hipStream_t stream)
+{
+    dim3 grid((unsigned)n_pairs), block(256);
+    if (io_bf16) {
+        if (d == 128) hipLaunchKernelGGL((decode_step_kernel<IOBF16, 128>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((decode_step_kernel<IOBF16, 64>), grid, block, 0, stream, a);
+    } else {
+        if (d == 128) hipLaunchKernelGGL((decode_step_kernel<IOF32, 128>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((decode_step_kernel<IOF32, 64>), grid, block, 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace gka

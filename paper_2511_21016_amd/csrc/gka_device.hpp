@@ -1,0 +1,138 @@
+// Device-side building blocks shared by the libgka kernels (gfx950 only).
+//
+// Everything is organised around the 32x32 MFMA accumulator layout. For a wave64 lane
+// l = 32*g + n (g in {0,1}, n in 0..31) and accumulator register r in 0..15, a 32x32 output
+// tile holds element (row = kidx(r, g), column = n). The kernels keep one token per lane
+// column, so a token's feature vector lives in the registers of its two lanes; a tile of
+// such accumulators can be fed back as the B operand of the next MFMA without leaving
+// registers, provided the A operand enumerates the contraction index in the same kidx order.
+// "Fragment order" below is that order: fragment (.., blk, h) lane (n, g) element p holds the
+// matrix entry at row n and column 32*blk + kidx(h*VEC + p, g).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gka_kernels.hpp"
+
+namespace gka {
+
+constexpr float kMinLogGate = -100.0f;
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+
+// Row (contraction index within a 32-block) of accumulator register r on lane half g.
+__device__ __forceinline__ constexpr int kidx(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round to nearest even, as the hardware conversion does.
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float x)
+{
+    __bf16 h = (__bf16)x;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+// ---- tensor element types of q, k, v, o ---------------------------------------------------
+struct IOF32 {
+    typedef float type;
+    static __device__ __forceinline__ float load(const void *p, int64_t i) { return ((const float *)p)[i]; }
+    static __device__ __forceinline__ void store4(void *p, int64_t i, float a, float b, float c, float d)
+    {
+        f32x4 v = {a, b, c, d};
+        *(f32x4 *)((float *)p + i) = v;
+    }
+    static __device__ __forceinline__ void store1(void *p, int64_t i, float a) { ((float *)p)[i] = a; }
+};
+struct IOBF16 {
+    typedef uint16_t type;
+    static __device__ __forceinline__ float load(const void *p, int64_t i)
+    {
+        return bf16_bits_to_f32(((const uint16_t *)p)[i]);
+    }
+    static __device__ __forceinline__ void store4(void *p, int64_t i, float a, float b, float c, float d)
+    {
+        u16x4 v = {f32_to_bf16_bits(a), f32_to_bf16_bits(b), f32_to_bf16_bits(c), f32_to_bf16_bits(d)};
+        *(u16x4 *)((uint16_t *)p + i) = v;
+    }
+    static __device__ __forceinline__ void store1(void *p, int64_t i, float a)
+    {
+        ((uint16_t *)p)[i] = f32_to_bf16_bits(a);
+    }
+};
+
+// ---- arithmetic of the matrix products ------------------------------------------------------
+// VEC = operand elements per lane per MFMA; HS = MFMA steps per 32-block of the contraction.
+struct MmaBF16 {
+    static constexpr int VEC = 8;
+    static constexpr int HS = 2;
+    static constexpr bool kSplitReadout = true;   // readout uses hi+lo operands
+    typedef bf16x8 frag;
+    static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    // operand fragment from VEC consecutive float values
+    static __device__ __forceinline__ frag pack(const float *x)
+    {
+        frag f;
+#pragma unroll
+        for (int p = 0; p < VEC; ++p) f[p] = (__bf16)x[p];
+        return f;
+    }
+    static __device__ __forceinline__ float elem(frag f, int p) { return (float)f[p]; }
+    static __device__ __forceinline__ frag zero()
+    {
+        frag f;
+#pragma unroll
+        for (int p = 0; p < VEC; ++p) f[p] = (__bf16)0.0f;
+        return f;
+    }
+};
+struct MmaF32 {
+    static constexpr int VEC = 1;
+    static constexpr int HS = 16;
+    static constexpr bool kSplitReadout = false;
+    typedef float frag;
+    static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ frag pack(const float *x) { return x[0]; }
+    static __device__ __forceinline__ float elem(frag f, int) { return f; }
+    static __device__ __forceinline__ frag zero() { return 0.0f; }
+};
+
+__device__ __forceinline__ f32x16 zero16()
+{
+    f32x16 z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.0f;
+    return z;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ float wave_inclusive_scan(float x, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        float y = __shfl_up(x, off, 64);
+        if (lane >= off) x += y;
+    }
+    return x;
+}
+
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// log(gamma) with the documented floor; gamma of padded tail tokens is 1.
+__device__ __forceinline__ float log_gate(float gamma) { return fmaxf(logf(gamma), kMinLogGate); }
+
+}  // namespace gka

@@ -1,0 +1,54 @@
+// Host-visible argument blocks and launchers of the libgka kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gka {
+
+constexpr int kChunk = 64;   // chunk size C of Section 4.2.1
+
+struct StatePassArgs {
+    const void *k, *v;            // [B,T,H,d] tensors (element strides below)
+    const float *gate;            // [B,T,H]
+    const float *H_init, *U_init; // [pairs,d,d] or nullptr
+    float *H_final, *U_final;     // [pairs,d,d] or nullptr
+    void *ws_H, *ws_U;            // chunk initial states, fragment order
+    float *ws_hn;                 // partial sums of ||H_[n]||_F^2
+    int64_t stride_b, stride_t, stride_h;
+    int H, T;
+    int n_chunks;                 // chunks walked by this launch
+    int chunk0;                   // index of the first of them
+    int n_chunks_total;           // chunks per pair (workspace pitch)
+};
+
+struct SolveArgs {
+    const void *q, *k, *v;
+    const float *gate, *lambda;
+    void *o;
+    float *fro_out;               // [B,T,H] or nullptr
+    const void *ws_H, *ws_U;
+    const float *ws_hn;
+    int64_t stride_b, stride_t, stride_h;
+    int H, T, n_chunks_total, n_iter;
+};
+
+struct DecodeArgs {
+    float *H_state, *U_state;     // [pairs,d,d], in place
+    const void *q, *k, *v;        // [pairs,d]
+    const float *gate, *lambda;   // [pairs]
+    void *o;                      // [pairs,d]
+    int n_iter;
+};
+
+hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
+                             hipStream_t stream);
+hipError_t launch_chunk_solve(const SolveArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
+                              hipStream_t stream);
+hipError_t launch_decode_step(const DecodeArgs &a, int n_pairs, int d, bool io_bf16, hipStream_t stream);
+
+// Workspace sizes in bytes per (pair, chunk).
+size_t ws_H_bytes_per_chunk(int d, bool compute_bf16);
+size_t ws_U_bytes_per_chunk(int d, bool compute_bf16);
+size_t ws_hn_bytes_per_chunk(int d);
+
+}  // namespace gka

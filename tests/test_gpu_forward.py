@@ -1,0 +1,86 @@
+"""GPU parity: gka_forward (through the C ABI) against the fp64 oracle on identical seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_21016_amd import binding, synth
+from gka_testutil import pair_rel_err, to_device, to_host, upload_inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4     # max relative error, fp32 configurations
+TOL_BF16 = 2e-2    # max relative error, bf16 configurations
+
+
+def run_forward(w, x, compute=None, **kw):
+    import torch
+    dev = upload_inputs(x, w.dtype)
+    out = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=compute,
+                              chunk=w.chunk, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def oracle_forward(w, x, **kw):
+    return oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, **kw)
+
+
+def test_cfg1_tiny_f32():
+    w = synth.CFG1
+    x = synth.make_inputs(w)
+    o, ex = run_forward(w, x, return_fro=True, return_state=True)
+    ref, rex = oracle_forward(w, x, return_fro=True, return_state=True)
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 1e-5 * rex["fro"].max()
+    assert pair_rel_err(to_host(o), ref) <= TOL_F32
+    np.testing.assert_allclose(to_host(ex["H_final"]), rex["H_final"], rtol=0, atol=1e-5 * np.abs(rex["H_final"]).max())
+    np.testing.assert_allclose(to_host(ex["U_final"]), rex["U_final"], rtol=0, atol=1e-5 * np.abs(rex["U_final"]).max())
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("T", [1, 37, 64, 200])
+@pytest.mark.parametrize("n_iter", [0, 1, 5])
+def test_f32_small_shapes(d, T, n_iter):
+    w = synth.CFG1.scaled(B=2, H=3, T=T, d=d, n_iter=n_iter, seed=100 + T + d + n_iter)
+    x = synth.make_inputs(w)
+    o, ex = run_forward(w, x, return_fro=True)
+    ref, rex = oracle_forward(w, x, return_fro=True)
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 1e-5 * rex["fro"].max()
+    assert pair_rel_err(to_host(o), ref) <= TOL_F32
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("T", [50, 256, 333])
+def test_bf16_small_shapes(d, T):
+    w = synth.CFG2.scaled(B=2, H=2, T=T, d=d, seed=200 + T + d)
+    x = synth.make_inputs(w)
+    o, ex = run_forward(w, x, return_fro=True)
+    ref, rex = oracle_forward(w, x, return_fro=True)
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+    assert pair_rel_err(to_host(o), ref) <= TOL_BF16
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_bf16_io_f32_compute(d):
+    w = synth.CFG4.scaled(B=1, H=2, T=300, d=d)
+    x = synth.make_inputs(w)
+    o = run_forward(w, x, compute=binding.GKA_COMPUTE_F32)
+    ref = oracle_forward(w, x)
+    assert pair_rel_err(to_host(o), ref) <= TOL_BF16
+
+
+def test_initial_and_final_state_handoff():
+    """forward(T) == forward(T1) followed by forward(T - T1) started from the returned state."""
+    w = synth.CFG1.scaled(B=1, H=2, T=300, d=64, n_iter=6, seed=7)
+    x = synth.make_inputs(w)
+    T1 = 130
+    xa = {n: a[:, :T1] for n, a in x.items()}
+    xb = {n: np.ascontiguousarray(a[:, T1:]) for n, a in x.items()}
+    xa = {n: np.ascontiguousarray(a) for n, a in xa.items()}
+    o_full, ex_full = run_forward(w, x, return_state=True)
+    o_a, ex_a = run_forward(w.scaled(T=T1), xa, return_state=True)
+    o_b, ex_b = run_forward(w.scaled(T=w.T - T1), xb, H_init=ex_a["H_final"], U_init=ex_a["U_final"], return_state=True)
+    ref = oracle_forward(w, x)
+    y = np.concatenate([to_host(o_a), to_host(o_b)], axis=1)
+    assert pair_rel_err(y, ref) <= TOL_F32
+    assert pair_rel_err(to_host(o_full), ref) <= TOL_F32
+    np.testing.assert_allclose(to_host(ex_b["H_final"]), to_host(ex_full["H_final"]), rtol=0, atol=1e-5)

@@ -1,0 +1,76 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and rejects bad
+arguments on the host before any launch (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_21016_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_21016_amd import build
+        build.build_library(verbose=False)
+    return binding.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    header = open(os.path.join(ROOT, "include", "gka.h")).read()
+    declared = set(re.findall(r"\b(gka_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(lib):
+    assert binding.version() >= 100
+    for s in range(6):
+        assert binding.status_string(s)
+    assert binding.status_string(binding.GKA_OK) == "ok"
+
+
+def _p(**kw):
+    base = dict(B=2, H=2, T=100, d=128, n_iter=4, io_dtype=binding.GKA_BF16, compute=binding.GKA_COMPUTE_BF16)
+    base.update(kw)
+    return binding.make_params(**base)
+
+
+def test_workspace_query(lib):
+    assert binding.forward_workspace_bytes(_p()) > 0
+    assert binding.forward_workspace_bytes(_p()) % 256 == 0
+    # two chunks of a longer sequence need more scratch
+    assert binding.forward_workspace_bytes(_p(T=1000)) > binding.forward_workspace_bytes(_p(T=100))
+    assert binding.forward_workspace_bytes(_p(d=96)) == 0
+    assert binding.forward_workspace_bytes(_p(T=0)) == 0
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    fake = 0x1000  # never dereferenced: every case below fails validation on the host
+    ok_ws = binding.forward_workspace_bytes(_p())
+
+    def fwd(p, q=fake, gate=fake, ws=0x100000, ws_bytes=ok_ws, H_init=None, U_init=None):
+        return binding.forward_raw(p, q, fake, fake, gate, fake, fake, H_init=H_init, U_init=U_init,
+                                   workspace=ws, workspace_bytes=ws_bytes)
+
+    assert fwd(_p(B=0)) == binding.GKA_ERR_SHAPE
+    assert fwd(_p(n_iter=-1)) == binding.GKA_ERR_SHAPE
+    assert fwd(_p(d=96)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(chunk=32)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(d_v=64)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(io_dtype=binding.GKA_F32)) == binding.GKA_ERR_UNSUPPORTED     # f32 tensors need f32 compute
+    assert fwd(_p(io_dtype=7)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(strides=(1, -1, 1))) == binding.GKA_ERR_SHAPE
+    assert fwd(_p(), q=None) == binding.GKA_ERR_NULL
+    assert fwd(_p(), gate=None) == binding.GKA_ERR_NULL
+    assert fwd(_p(), H_init=fake) == binding.GKA_ERR_NULL                        # H_init without U_init
+    assert fwd(_p(), ws=None) == binding.GKA_ERR_WORKSPACE
+    assert fwd(_p(), ws_bytes=ok_ws - 1) == binding.GKA_ERR_WORKSPACE
+    assert fwd(_p(), ws=0x100010) == binding.GKA_ERR_WORKSPACE                   # misaligned
+    assert binding.decode_step_raw(_p(), None, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
+    assert binding.decode_step_raw(_p(d=32), fake, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_UNSUPPORTED
+    assert binding.forward_raw(None, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
