@@ -1,0 +1,141 @@
+"""Benchmark of the GKA layer forward hot path (libgka) on one MI355X.
+
+One step = one gka_forward over the single-layer bf16 workload (B=4, H=16, T=4096, d=128, chunk 64,
+n_iter=10), inputs resident in HBM. Prints one JSON line: layer tokens/s, the roofline of the dominant
+kernel (the per-chunk solve kernel, bf16 MFMA bound) from per-phase HIP-event timings, and the fp64 CPU
+oracle timed on this machine's host cores on the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+N_INPUT_SETS = 3                   # rotated so that the 256 MiB of q,k,v,o do not sit in the last-level cache
+
+
+def algorithmic_flops_per_chunk(d, C, r):
+    """Causal algorithmic FLOPs of one (pair, chunk): S2 chunk deltas, S4 Frobenius, S5 r Chebyshev
+    passes, S6 readout. delta = number of causal (j <= c) pairs."""
+    delta = C * (C + 1) // 2
+    f_s2 = 4 * C * d * d
+    f_s4 = 2 * C * d * d + 2 * delta * d + 2 * C * delta
+    f_s5 = r * (2 * C * d * d + 4 * delta * d)
+    f_s6 = 2 * C * d * d + 4 * delta * d
+    return f_s2, f_s4, f_s5, f_s6
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); every (batch, head) pair is independent, "
+              "so more GPUs would shard pairs with no communication.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_21016_amd import binding, synth
+    from gka_testutil import pair_rel_err, to_host, upload_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU available", file=sys.stderr)
+        sys.exit(1)
+    binding.load_library()          # fails loudly when the HIP library has not been built
+
+    w = synth.CFG2
+    sets_host = [synth.make_inputs(w.scaled(seed=w.seed + 100 * i)) for i in range(N_INPUT_SETS)]
+    sets = [upload_inputs(x, w.dtype) for x in sets_host]
+    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16)
+    ws = torch.empty(binding.forward_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    outs = [torch.empty_like(s["v"]) for s in sets]
+
+    def step(i, phase=binding.GKA_PHASE_ALL):
+        s = sets[i % N_INPUT_SETS]
+        binding.gka_forward(s["q"], s["k"], s["v"], s["gate"], s["lam"], w.n_iter, workspace=ws,
+                            out=outs[i % N_INPUT_SETS], phase=phase)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K whole forward passes
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(args.steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    # ---- per-phase timing on the same stream: events between the two phases of every step
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        evs[i][0].record()
+        step(i, binding.GKA_PHASE_STATES)
+        evs[i][1].record()
+        step(i, binding.GKA_PHASE_SOLVE)
+        evs[i][2].record()
+    torch.cuda.synchronize()
+    ms_states = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    ms_solve = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+
+    n_chunks = w.B * w.H * (w.T // w.chunk)
+    f_s2, f_s4, f_s5, f_s6 = algorithmic_flops_per_chunk(w.d, w.chunk, w.n_iter)
+    flops_total = n_chunks * (f_s2 + f_s4 + f_s5 + f_s6)
+    flops_solve = n_chunks * (f_s4 + f_s5 + f_s6)
+    tokens = w.B * w.T
+    tflops_total = flops_total / (ms_per_step * 1e-3) / 1e12
+    tflops_solve = flops_solve / (ms_solve * 1e-3) / 1e12
+
+    result = {
+        "metric": "GKA layer forward tokens/sec + % bf16 MFMA peak (H=16,d=128,T=4096)",
+        "value": tokens / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "T": w.T, "d": w.d, "chunk": w.chunk,
+                   "n_iter": w.n_iter, "input_sets_rotated": N_INPUT_SETS},
+        "tflops_algorithmic": tflops_total,
+        "frac_bf16_mfma_peak": tflops_total / MFMA_BF16_PEAK_TFLOPS,
+        "phase_ms": {"states": ms_states, "solve": ms_solve},
+        "roofline": {"kernel": "chunk_solve_kernel<MmaBF16,IOBF16,128>", "bound": "mfma",
+                     "achieved": tflops_solve, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tflops_solve / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        x = sets_host[0]
+        t0 = time.time()
+        ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+        dt = time.time() - t0
+        result["cpu_baseline"] = {"value": tokens / dt, "unit": "tokens/s", "cores": oracle.num_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"the whole workload once ({w.B * w.H} pairs x {w.T} tokens), {dt:.1f} s"}
+        step(0)
+        torch.cuda.synchronize()
+        result["max_rel_err_vs_oracle"] = pair_rel_err(to_host(outs[0]), ref)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

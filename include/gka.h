@@ -51,6 +51,14 @@ typedef enum { GKA_F32 = 0, GKA_BF16 = 1 } gka_dtype;
  *                   iterate, the residual and all per-token scalars stay float32. */
 typedef enum { GKA_COMPUTE_F32 = 0, GKA_COMPUTE_BF16 = 1 } gka_compute;
 
+/* Which part of gka_forward to enqueue. The forward pass has two phases (Section 4.2.1): first the
+ * chunk initial states H_[n], U_[n] are computed and stored in the workspace (this phase also writes
+ * H_final / U_final), then every chunk is solved independently from its stored state (this phase writes
+ * o and fro_out). GKA_PHASE_SOLVE alone is valid only on a workspace that still holds the states of a
+ * GKA_PHASE_STATES (or GKA_PHASE_ALL) call with the same parameters and inputs; it exists so that
+ * callers can time, or overlap, the two phases separately. */
+typedef enum { GKA_PHASE_ALL = 0, GKA_PHASE_STATES = 1, GKA_PHASE_SOLVE = 2 } gka_phase;
+
 typedef struct {
     int32_t B;            /* batch (gka_decode_step: number of sequences)                      */
     int32_t H;            /* heads                                                             */
@@ -61,7 +69,7 @@ typedef struct {
     int32_t n_iter;       /* r of Algorithm 1 = number of loop passes; 0 returns U_t xi_0      */
     int32_t io_dtype;     /* gka_dtype of q, k, v, o                                           */
     int32_t compute;      /* gka_compute                                                       */
-    int32_t reserved;     /* must be 0                                                         */
+    int32_t phase;        /* gka_phase; GKA_PHASE_ALL (0) for a complete forward pass          */
     int64_t stride_b;     /* element strides of q, k, v, o between batches, tokens and heads;  */
     int64_t stride_t;     /*   the head dimension is contiguous. 0,0,0 selects the packed      */
     int64_t stride_h;     /*   [B,T,H,d] layout of the paper's tensors (Appendix D)            */

@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libgka.so")
 GKA_OK, GKA_ERR_NULL, GKA_ERR_SHAPE, GKA_ERR_UNSUPPORTED, GKA_ERR_WORKSPACE, GKA_ERR_LAUNCH = range(6)
 GKA_F32, GKA_BF16 = 0, 1
 GKA_COMPUTE_F32, GKA_COMPUTE_BF16 = 0, 1
+GKA_PHASE_ALL, GKA_PHASE_STATES, GKA_PHASE_SOLVE = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
     "gka_forward_workspace_bytes",
@@ -28,7 +29,7 @@ class GkaParams(ctypes.Structure):
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("T", ctypes.c_int32),
         ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32), ("chunk", ctypes.c_int32),
         ("n_iter", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("compute", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("phase", ctypes.c_int32),
         ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
     ]
 
@@ -49,6 +50,10 @@ def load_library():
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(
                 f"{LIB_PATH} not found: build it first (python -m paper_2511_21016_amd.build)")
+        # PyTorch ships its own HIP runtime (SONAME libamdhip64.so.7). Importing torch first makes libgka
+        # bind to that same copy; loading libgka first would bring a second runtime into the process and
+        # kernels launched on torch's streams would fail.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         vp, fp = ctypes.c_void_p, ctypes.c_void_p
         lib.gka_forward_workspace_bytes.argtypes = [ctypes.POINTER(GkaParams)]
@@ -74,9 +79,9 @@ def version():
     return int(load_library().gka_version())
 
 
-def make_params(B, H, T, d, n_iter, io_dtype, compute, chunk=64, d_v=None, strides=(0, 0, 0)):
+def make_params(B, H, T, d, n_iter, io_dtype, compute, chunk=64, d_v=None, strides=(0, 0, 0), phase=0):
     return GkaParams(B=B, H=H, T=T, d_k=d, d_v=d if d_v is None else d_v, chunk=chunk, n_iter=n_iter,
-                     io_dtype=io_dtype, compute=compute, reserved=0,
+                     io_dtype=io_dtype, compute=compute, phase=phase,
                      stride_b=strides[0], stride_t=strides[1], stride_h=strides[2])
 
 
@@ -116,7 +121,7 @@ def _ptr(t):
 
 
 def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=None, U_init=None,
-                return_state=False, return_fro=False, workspace=None, out=None):
+                return_state=False, return_fro=False, workspace=None, out=None, phase=GKA_PHASE_ALL):
     """gka_forward on torch CUDA tensors: q, k, v [B,T,H,d] (float32 or bfloat16, contiguous),
     gate, lam [B,T,H] float32. Enqueues on torch's current stream and returns o (and a dict of the
     requested extras). Nothing here computes: it allocates outputs and passes pointers."""
@@ -127,7 +132,7 @@ def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=No
     io = _io_dtype(q)
     if compute is None:
         compute = GKA_COMPUTE_BF16 if io == GKA_BF16 else GKA_COMPUTE_F32
-    params = make_params(B, H, T, d, n_iter, io, compute, chunk=chunk, d_v=v.shape[-1])
+    params = make_params(B, H, T, d, n_iter, io, compute, chunk=chunk, d_v=v.shape[-1], phase=phase)
     nbytes = forward_workspace_bytes(params)
     if nbytes == 0:
         # let the library name the error

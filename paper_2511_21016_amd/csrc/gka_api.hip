@@ -20,7 +20,7 @@ gka_status check_common(const gka_params *p, bool decode)
     if (p->B <= 0 || p->H <= 0 || p->n_iter < 0) return GKA_ERR_SHAPE;
     if (!decode && p->T <= 0) return GKA_ERR_SHAPE;
     if (p->d_k <= 0 || p->d_v <= 0) return GKA_ERR_SHAPE;
-    if (p->reserved != 0) return GKA_ERR_SHAPE;
+    if (p->phase < GKA_PHASE_ALL || p->phase > GKA_PHASE_SOLVE) return GKA_ERR_UNSUPPORTED;
     if (p->d_k != p->d_v) return GKA_ERR_UNSUPPORTED;
     if (p->d_k != 64 && p->d_k != 128) return GKA_ERR_UNSUPPORTED;
     if (p->io_dtype != GKA_F32 && p->io_dtype != GKA_BF16) return GKA_ERR_UNSUPPORTED;
@@ -95,7 +95,8 @@ gka_status gka_forward(const gka_params *p, const void *q, const void *k, const 
     sa.stride_b = pl.stride_b; sa.stride_t = pl.stride_t; sa.stride_h = pl.stride_h;
     sa.H = p->H; sa.T = p->T;
     sa.n_chunks = pl.n_chunks; sa.chunk0 = 0; sa.n_chunks_total = pl.n_chunks;
-    if (gka::launch_state_pass(sa, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
+    if (p->phase != GKA_PHASE_SOLVE &&
+        gka::launch_state_pass(sa, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
         return GKA_ERR_LAUNCH;
 
     gka::SolveArgs so;
@@ -103,7 +104,8 @@ gka_status gka_forward(const gka_params *p, const void *q, const void *k, const 
     so.ws_H = sa.ws_H; so.ws_U = sa.ws_U; so.ws_hn = sa.ws_hn;
     so.stride_b = pl.stride_b; so.stride_t = pl.stride_t; so.stride_h = pl.stride_h;
     so.H = p->H; so.T = p->T; so.n_chunks_total = pl.n_chunks; so.n_iter = p->n_iter;
-    if (gka::launch_chunk_solve(so, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
+    if (p->phase != GKA_PHASE_STATES &&
+        gka::launch_chunk_solve(so, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
         return GKA_ERR_LAUNCH;
     return GKA_OK;
 }

@@ -64,6 +64,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(_p(d_v=64)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(io_dtype=binding.GKA_F32)) == binding.GKA_ERR_UNSUPPORTED     # f32 tensors need f32 compute
     assert fwd(_p(io_dtype=7)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(phase=3)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(strides=(1, -1, 1))) == binding.GKA_ERR_SHAPE
     assert fwd(_p(), q=None) == binding.GKA_ERR_NULL
     assert fwd(_p(), gate=None) == binding.GKA_ERR_NULL
