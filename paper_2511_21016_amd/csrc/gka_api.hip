@@ -9,7 +9,8 @@ struct Plan {
     int n_pairs, n_chunks, d;
     bool io_bf16, compute_bf16;
     int64_t stride_b, stride_t, stride_h;
-    size_t off_H, off_U, off_hn, total;
+    size_t off_H, off_U, off_hn, off_seg, off_segdecay, total;
+    int n_segs, seg_len;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -57,7 +58,16 @@ gka_status make_plan(const gka_params *p, Plan *pl)
     pl->off_H = 0;
     pl->off_U = align_up(pl->off_H + nc * gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
     pl->off_hn = align_up(pl->off_U + nc * gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
-    pl->total = align_up(pl->off_hn + nc * gka::ws_hn_bytes_per_chunk(pl->d), 256);
+    pl->off_seg = align_up(pl->off_hn + nc * gka::ws_hn_bytes_per_chunk(pl->d), 256);
+    // Segments of the chunk scan: enough workgroups to fill the chip, at least two chunks per segment.
+    const int wg_per_seg = pl->n_pairs * (pl->d / 32);
+    int n_segs = 2048 / wg_per_seg;
+    if (n_segs > pl->n_chunks / 2) n_segs = pl->n_chunks / 2;
+    if (n_segs < 1) n_segs = 1;
+    pl->seg_len = (pl->n_chunks + n_segs - 1) / n_segs;
+    pl->n_segs = (pl->n_chunks + pl->seg_len - 1) / pl->seg_len;
+    pl->off_segdecay = align_up(pl->off_seg + (size_t)pl->n_pairs * pl->n_segs * 2 * pl->d * pl->d * sizeof(float), 256);
+    pl->total = align_up(pl->off_segdecay + (size_t)pl->n_pairs * pl->n_segs * sizeof(float), 256);
     return GKA_OK;
 }
 
@@ -94,7 +104,10 @@ gka_status gka_forward(const gka_params *p, const void *q, const void *k, const 
     sa.ws_H = ws + pl.off_H; sa.ws_U = ws + pl.off_U; sa.ws_hn = (float *)(ws + pl.off_hn);
     sa.stride_b = pl.stride_b; sa.stride_t = pl.stride_t; sa.stride_h = pl.stride_h;
     sa.H = p->H; sa.T = p->T;
-    sa.n_chunks = pl.n_chunks; sa.chunk0 = 0; sa.n_chunks_total = pl.n_chunks;
+    sa.n_chunks_total = pl.n_chunks;
+    sa.n_segs = pl.n_segs; sa.seg_len = pl.seg_len;
+    sa.seg_buf = (float *)(ws + pl.off_seg); sa.seg_logdecay = (float *)(ws + pl.off_segdecay);
+    sa.init_mode = 0; sa.final_mode = 0; sa.write_frags = 1;
     if (p->phase != GKA_PHASE_SOLVE &&
         gka::launch_state_pass(sa, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
         return GKA_ERR_LAUNCH;

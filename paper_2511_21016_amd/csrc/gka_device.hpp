@@ -40,6 +40,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x)
 struct IOF32 {
     typedef float type;
     static __device__ __forceinline__ float load(const void *p, int64_t i) { return ((const float *)p)[i]; }
+    // four consecutive elements, 16-byte aligned
+    static __device__ __forceinline__ f32x4 load4(const void *p, int64_t i) { return *(const f32x4 *)((const float *)p + i); }
+    // the same without conversion, so that the load stays asynchronous until its first use
+    typedef f32x4 raw4;
+    static __device__ __forceinline__ raw4 load_raw4(const void *p, int64_t i) { return load4(p, i); }
+    static __device__ __forceinline__ f32x4 cvt4(raw4 r) { return r; }
     static __device__ __forceinline__ void store4(void *p, int64_t i, float a, float b, float c, float d)
     {
         f32x4 v = {a, b, c, d};
@@ -53,6 +59,22 @@ struct IOBF16 {
     {
         return bf16_bits_to_f32(((const uint16_t *)p)[i]);
     }
+    // four consecutive elements, 8-byte aligned
+    static __device__ __forceinline__ f32x4 load4(const void *p, int64_t i)
+    {
+        return cvt4(load_raw4(p, i));
+    }
+    // the same without conversion, so that the load stays asynchronous until its first use
+    typedef u16x4 raw4;
+    static __device__ __forceinline__ raw4 load_raw4(const void *p, int64_t i)
+    {
+        return *(const u16x4 *)((const uint16_t *)p + i);
+    }
+    static __device__ __forceinline__ f32x4 cvt4(raw4 b)
+    {
+        f32x4 v = {bf16_bits_to_f32(b[0]), bf16_bits_to_f32(b[1]), bf16_bits_to_f32(b[2]), bf16_bits_to_f32(b[3])};
+        return v;
+    }
     static __device__ __forceinline__ void store4(void *p, int64_t i, float a, float b, float c, float d)
     {
         u16x4 v = {f32_to_bf16_bits(a), f32_to_bf16_bits(b), f32_to_bf16_bits(c), f32_to_bf16_bits(d)};
@@ -64,6 +86,39 @@ struct IOBF16 {
     }
 };
 
+// Transposed operand fragment from a row-major LDS tile (features contiguous, `rs` elements per token row).
+// Returns, for this lane, the VEC elements x[token(p)][col] with token(p) = tok_base(p), where the caller
+// enumerates the tokens through `tok_of(p)`. Generic version: one LDS read per element.
+template <class MMA, class TokOf>
+__device__ __forceinline__ typename MMA::frag gather_transposed(const typename MMA::elem_t *tile, int rs, int col,
+                                                                TokOf tok_of)
+{
+    typename MMA::elem_t e[MMA::VEC];
+#pragma unroll
+    for (int p = 0; p < MMA::VEC; ++p) e[p] = tile[tok_of(p) * rs + col];
+    return MMA::pack_elems(e);
+}
+
+// bf16 fast path for fragments whose 8 tokens are two runs of 4 consecutive tokens (t0 .. t0+3, t1 .. t1+3):
+// two ds_read_b64_tr_b16 transpose reads. Within each block of 16 lanes the instruction hands lane i the four
+// 16-bit values found at element (i % 4) of the addresses supplied by lanes (i / 4), (i / 4) + 4, + 8, + 12 of
+// the block. So lane i supplies the address of token run[i / 4] at the 4-column group (i % 4) of its block's 16
+// columns, and receives tokens run[0..3] at its own column. `col16` is the first of the block's 16 columns.
+__device__ __forceinline__ bf16x8 gather_transposed_bf16(const uint16_t *tile, int rs, int col16, int lane, int t0,
+                                                         int t1)
+{
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const int i = lane & 15;
+    const uint16_t *p0 = tile + (t0 + (i >> 2)) * rs + col16 + 4 * (i & 3);
+    const uint16_t *p1 = tile + (t1 + (i >> 2)) * rs + col16 + 4 * (i & 3);
+    s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p0);
+    s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p1);
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+    return __builtin_bit_cast(bf16x8, r);
+}
+
 // ---- arithmetic of the matrix products ------------------------------------------------------
 // VEC = operand elements per lane per MFMA; HS = MFMA steps per 32-block of the contraction.
 struct MmaBF16 {
@@ -71,6 +126,20 @@ struct MmaBF16 {
     static constexpr int HS = 2;
     static constexpr bool kSplitReadout = true;   // readout uses hi+lo operands
     typedef bf16x8 frag;
+    typedef uint16_t elem_t;                      // operand element as stored in LDS rows
+    static __device__ __forceinline__ elem_t to_elem(float x) { return f32_to_bf16_bits(x); }
+    static __device__ __forceinline__ float from_elem(elem_t e) { return bf16_bits_to_f32(e); }
+    // fragment from VEC stored elements
+    static __device__ __forceinline__ frag pack_elems(const elem_t *e)
+    {
+        u16x8 u = {e[0], e[1], e[2], e[3], e[4], e[5], e[6], e[7]};
+        return __builtin_bit_cast(frag, u);
+    }
+    static __device__ __forceinline__ void store4(elem_t *dst, f32x4 v)
+    {
+        u16x4 u = {f32_to_bf16_bits(v[0]), f32_to_bf16_bits(v[1]), f32_to_bf16_bits(v[2]), f32_to_bf16_bits(v[3])};
+        *(u16x4 *)dst = u;
+    }
     static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -97,6 +166,11 @@ struct MmaF32 {
     static constexpr int HS = 16;
     static constexpr bool kSplitReadout = false;
     typedef float frag;
+    typedef float elem_t;
+    static __device__ __forceinline__ elem_t to_elem(float x) { return x; }
+    static __device__ __forceinline__ float from_elem(elem_t e) { return e; }
+    static __device__ __forceinline__ frag pack_elems(const elem_t *e) { return e[0]; }
+    static __device__ __forceinline__ void store4(elem_t *dst, f32x4 v) { *(f32x4 *)dst = v; }
     static __device__ __forceinline__ f32x16 mma(frag a, frag b, f32x16 c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);

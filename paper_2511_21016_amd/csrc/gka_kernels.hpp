@@ -16,9 +16,14 @@ struct StatePassArgs {
     float *ws_hn;                 // partial sums of ||H_[n]||_F^2
     int64_t stride_b, stride_t, stride_h;
     int H, T;
-    int n_chunks;                 // chunks walked by this launch
-    int chunk0;                   // index of the first of them
-    int n_chunks_total;           // chunks per pair (workspace pitch)
+    int n_chunks_total;           // chunks per pair
+    int n_segs, seg_len;          // segments per pair and chunks per segment (n_segs <= 1: one pass)
+    float *seg_buf;               // [pairs, n_segs, 2, d*d] segment summaries / start states
+    float *seg_logdecay;          // [pairs, n_segs] sum of log gates over each segment
+    // set by the launcher:
+    int init_mode;                // 0 zero, 1 H_init/U_init (row-major), 2 segment start states
+    int final_mode;               // 0 none, 1 H_final/U_final (row-major), 2 segment summaries
+    int write_frags;              // store chunk states to ws_H / ws_U / ws_hn
 };
 
 struct SolveArgs {
