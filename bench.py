@@ -60,10 +60,10 @@ def main():
     ws = torch.empty(binding.forward_workspace_bytes(params), dtype=torch.uint8, device="cuda")
     outs = [torch.empty_like(s["v"]) for s in sets]
 
-    def step(i, phase=binding.GKA_PHASE_ALL):
+    def step(i):
         s = sets[i % N_INPUT_SETS]
         binding.gka_forward(s["q"], s["k"], s["v"], s["gate"], s["lam"], w.n_iter, workspace=ws,
-                            out=outs[i % N_INPUT_SETS], phase=phase)
+                            out=outs[i % N_INPUT_SETS])
 
     for i in range(args.warmup):
         step(i)
@@ -79,17 +79,20 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = e0.elapsed_time(e1) / args.steps
 
-    # ---- per-phase timing on the same stream: events between the two phases of every step
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    # ---- per-kernel timing: the library brackets its launches with HIP events on the same stream
+    ms_states = ms_solve = 0.0
+    n_launches = 1
     for i in range(args.steps):
-        evs[i][0].record()
-        step(i, binding.GKA_PHASE_STATES)
-        evs[i][1].record()
-        step(i, binding.GKA_PHASE_SOLVE)
-        evs[i][2].record()
-    torch.cuda.synchronize()
-    ms_states = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    ms_solve = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+        s = sets[i % N_INPUT_SETS]
+        st, a, b, n_launches = binding.forward_profile_raw(
+            params, s["q"].data_ptr(), s["k"].data_ptr(), s["v"].data_ptr(), s["gate"].data_ptr(),
+            s["lam"].data_ptr(), outs[i % N_INPUT_SETS].data_ptr(), ws.data_ptr(), ws.numel(),
+            torch.cuda.current_stream().cuda_stream)
+        if st != binding.GKA_OK:
+            raise binding.GkaError(st, binding.status_string(st))
+        ms_states += a / args.steps
+        ms_solve += b / args.steps
+    ms_solve_launch = ms_solve / n_launches
 
     n_chunks = w.B * w.H * (w.T // w.chunk)
     f_s2, f_s4, f_s5, f_s6 = algorithmic_flops_per_chunk(w.d, w.chunk, w.n_iter)
@@ -116,7 +119,8 @@ def main():
                    "n_iter": w.n_iter, "input_sets_rotated": N_INPUT_SETS},
         "tflops_algorithmic": tflops_total,
         "frac_bf16_mfma_peak": tflops_total / MFMA_BF16_PEAK_TFLOPS,
-        "phase_ms": {"states": ms_states, "solve": ms_solve},
+        "phase_ms": {"states": ms_states, "solve": ms_solve, "solve_launches_per_step": n_launches,
+                     "solve_ms_per_launch": ms_solve_launch},
         "roofline": {"kernel": "chunk_solve_kernel<MmaBF16,IOBF16,128>", "bound": "mfma",
                      "achieved": tflops_solve, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tflops_solve / MFMA_BF16_PEAK_TFLOPS, "traffic": None},

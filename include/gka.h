@@ -56,7 +56,8 @@ typedef enum { GKA_COMPUTE_F32 = 0, GKA_COMPUTE_BF16 = 1 } gka_compute;
  * H_final / U_final), then every chunk is solved independently from its stored state (this phase writes
  * o and fro_out). GKA_PHASE_SOLVE alone is valid only on a workspace that still holds the states of a
  * GKA_PHASE_STATES (or GKA_PHASE_ALL) call with the same parameters and inputs; it exists so that
- * callers can time, or overlap, the two phases separately. */
+ * callers can overlap the two phases. A single phase can be requested only when the problem is small
+ * enough to be processed as one batch of pairs (otherwise GKA_ERR_UNSUPPORTED). */
 typedef enum { GKA_PHASE_ALL = 0, GKA_PHASE_STATES = 1, GKA_PHASE_SOLVE = 2 } gka_phase;
 
 typedef struct {
@@ -77,7 +78,9 @@ typedef struct {
 
 /* Bytes of scratch gka_forward needs for these parameters (0 if they are invalid). The buffer must
  * be 256-byte aligned. It holds the chunk initial states H_[n], U_[n] of Section 4.2.1 in the
- * operand layout of the solve kernel; its contents after a call are unspecified. */
+ * operand layout of the solve kernel, for one batch of (batch, head) pairs at a time: large problems
+ * are processed in batches of pairs so that the workspace stays bounded (about 1 GiB). Its contents
+ * after a call are unspecified. */
 size_t gka_forward_workspace_bytes(const gka_params *p);
 
 /* Whole-sequence forward, Eq. (CH).
@@ -99,6 +102,23 @@ gka_status gka_forward(const gka_params *p,
                        float *fro_out,
                        void *workspace, size_t workspace_bytes,
                        void *hip_stream);
+
+/* gka_forward for profiling: the same work with the same arguments, bracketed per phase by HIP events on the
+ * given stream. Unlike every other entry point this one creates and destroys events and BLOCKS until the work
+ * has finished. It returns the time spent in the chunk-state phase and in the per-chunk solve phase
+ * (milliseconds, summed over the launches of this call) and the number of solve-kernel launches the call was
+ * split into (pairs are processed in batches, see gka_forward_workspace_bytes). Host pointers:
+ * ms_states, ms_solve, n_solve_launches. */
+gka_status gka_forward_profile(const gka_params *p,
+                               const void *q, const void *k, const void *v,
+                               const float *gate, const float *lambda,
+                               void *o,
+                               const float *H_init, const float *U_init,
+                               float *H_final, float *U_final,
+                               float *fro_out,
+                               void *workspace, size_t workspace_bytes,
+                               void *hip_stream,
+                               float *ms_states, float *ms_solve, int32_t *n_solve_launches);
 
 /* One recurrent step of Eq. (CH) on stored states (T is ignored).
  *   H_state [B,H,d_k,d_k], U_state [B,H,d_v,d_k] float32, updated IN PLACE

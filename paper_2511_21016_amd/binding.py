@@ -18,6 +18,7 @@ GKA_PHASE_ALL, GKA_PHASE_STATES, GKA_PHASE_SOLVE = 0, 1, 2
 EXPORTED_SYMBOLS = (
     "gka_forward_workspace_bytes",
     "gka_forward",
+    "gka_forward_profile",
     "gka_decode_step",
     "gka_status_string",
     "gka_version",
@@ -61,6 +62,10 @@ def load_library():
         lib.gka_forward.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, vp,
                                     ctypes.c_size_t, vp]
         lib.gka_forward.restype = ctypes.c_int
+        lib.gka_forward_profile.argtypes = lib.gka_forward.argtypes + [ctypes.POINTER(ctypes.c_float),
+                                                                       ctypes.POINTER(ctypes.c_float),
+                                                                       ctypes.POINTER(ctypes.c_int32)]
+        lib.gka_forward_profile.restype = ctypes.c_int
         lib.gka_decode_step.argtypes = [ctypes.POINTER(GkaParams), fp, fp, vp, vp, vp, fp, fp, vp, vp]
         lib.gka_decode_step.restype = ctypes.c_int
         lib.gka_status_string.argtypes = [ctypes.c_int]
@@ -95,6 +100,15 @@ def forward_raw(params, q, k, v, gate, lam, o, H_init=None, U_init=None, H_final
     pp = None if params is None else ctypes.byref(params)
     return int(load_library().gka_forward(pp, q, k, v, gate, lam, o, H_init, U_init, H_final,
                                           U_final, fro_out, workspace, workspace_bytes, stream))
+
+
+def forward_profile_raw(params, q, k, v, gate, lam, o, workspace, workspace_bytes, stream=None):
+    """gka_forward_profile on raw device addresses. Returns (status, ms_states, ms_solve, n_solve_launches)."""
+    a, b, n = ctypes.c_float(0), ctypes.c_float(0), ctypes.c_int32(0)
+    st = int(load_library().gka_forward_profile(ctypes.byref(params), q, k, v, gate, lam, o, None, None, None, None,
+                                                None, workspace, workspace_bytes, stream, ctypes.byref(a),
+                                                ctypes.byref(b), ctypes.byref(n)))
+    return st, a.value, b.value, n.value
 
 
 def decode_step_raw(params, H_state, U_state, q, k, v, gate, lam, o, stream=None):

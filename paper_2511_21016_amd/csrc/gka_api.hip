@@ -3,6 +3,8 @@
 #include "../../include/gka.h"
 #include "gka_kernels.hpp"
 
+#include <vector>
+
 namespace {
 
 struct Plan {
@@ -11,9 +13,15 @@ struct Plan {
     int64_t stride_b, stride_t, stride_h;
     size_t off_H, off_U, off_hn, off_seg, off_segdecay, total;
     int n_segs, seg_len;
+    int pairs_per_batch;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+#ifndef GKA_BATCH_STATE_BYTES
+#define GKA_BATCH_STATE_BYTES (1024u << 20)
+#endif
+constexpr size_t kBatchStateBytes = GKA_BATCH_STATE_BYTES;   // chunk states per batch of pairs
 
 gka_status check_common(const gka_params *p, bool decode)
 {
@@ -54,20 +62,27 @@ gka_status make_plan(const gka_params *p, Plan *pl)
         pl->stride_t = p->stride_t;
         pl->stride_h = p->stride_h;
     }
-    const size_t nc = (size_t)pl->n_pairs * pl->n_chunks;
+    // Pairs are processed in batches that bound the workspace; the workspace is reused per batch.
+    const size_t per_pair = (size_t)pl->n_chunks * (gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16) +
+                                                    gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16));
+    size_t ppb = kBatchStateBytes / per_pair;
+    if (ppb < 1) ppb = 1;
+    if (ppb > (size_t)pl->n_pairs) ppb = pl->n_pairs;
+    pl->pairs_per_batch = (int)ppb;
+    const size_t nc = ppb * pl->n_chunks;
     pl->off_H = 0;
     pl->off_U = align_up(pl->off_H + nc * gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
     pl->off_hn = align_up(pl->off_U + nc * gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
     pl->off_seg = align_up(pl->off_hn + nc * gka::ws_hn_bytes_per_chunk(pl->d), 256);
     // Segments of the chunk scan: enough workgroups to fill the chip, at least two chunks per segment.
-    const int wg_per_seg = pl->n_pairs * (pl->d / 32);
+    const int wg_per_seg = pl->pairs_per_batch * (pl->d / 32);
     int n_segs = 2048 / wg_per_seg;
     if (n_segs > pl->n_chunks / 2) n_segs = pl->n_chunks / 2;
     if (n_segs < 1) n_segs = 1;
     pl->seg_len = (pl->n_chunks + n_segs - 1) / n_segs;
     pl->n_segs = (pl->n_chunks + pl->seg_len - 1) / pl->seg_len;
-    pl->off_segdecay = align_up(pl->off_seg + (size_t)pl->n_pairs * pl->n_segs * 2 * pl->d * pl->d * sizeof(float), 256);
-    pl->total = align_up(pl->off_segdecay + (size_t)pl->n_pairs * pl->n_segs * sizeof(float), 256);
+    pl->off_segdecay = align_up(pl->off_seg + (size_t)pl->pairs_per_batch * pl->n_segs * 2 * pl->d * pl->d * sizeof(float), 256);
+    pl->total = align_up(pl->off_segdecay + (size_t)pl->pairs_per_batch * pl->n_segs * sizeof(float), 256);
     return GKA_OK;
 }
 
@@ -82,10 +97,31 @@ size_t gka_forward_workspace_bytes(const gka_params *p)
     return pl.total;
 }
 
-gka_status gka_forward(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
-                       const float *lambda, void *o, const float *H_init, const float *U_init, float *H_final,
-                       float *U_final, float *fro_out, void *workspace, size_t workspace_bytes,
-                       void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// Events around the two phases of every batch (profiling entry point only).
+struct PhaseEvents {
+    std::vector<hipEvent_t> ev;
+    bool ok = true;
+    void mark(hipStream_t stream)
+    {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { ok = false; return; }
+        if (hipEventRecord(e, stream) != hipSuccess) ok = false;
+        ev.push_back(e);
+    }
+    ~PhaseEvents()
+    {
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    }
+};
+
+gka_status forward_impl(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
+                        const float *lambda, void *o, const float *H_init, const float *U_init, float *H_final,
+                        float *U_final, float *fro_out, void *workspace, size_t workspace_bytes,
+                        void *hip_stream, PhaseEvents *prof)
 {
     Plan pl;
     gka_status s = make_plan(p, &pl);
@@ -108,18 +144,67 @@ gka_status gka_forward(const gka_params *p, const void *q, const void *k, const 
     sa.n_segs = pl.n_segs; sa.seg_len = pl.seg_len;
     sa.seg_buf = (float *)(ws + pl.off_seg); sa.seg_logdecay = (float *)(ws + pl.off_segdecay);
     sa.init_mode = 0; sa.final_mode = 0; sa.write_frags = 1;
-    if (p->phase != GKA_PHASE_SOLVE &&
-        gka::launch_state_pass(sa, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
-        return GKA_ERR_LAUNCH;
-
     gka::SolveArgs so;
     so.q = q; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
     so.ws_H = sa.ws_H; so.ws_U = sa.ws_U; so.ws_hn = sa.ws_hn;
     so.stride_b = pl.stride_b; so.stride_t = pl.stride_t; so.stride_h = pl.stride_h;
     so.H = p->H; so.T = p->T; so.n_chunks_total = pl.n_chunks; so.n_iter = p->n_iter;
-    if (p->phase != GKA_PHASE_STATES &&
-        gka::launch_chunk_solve(so, pl.n_pairs, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
-        return GKA_ERR_LAUNCH;
+    const bool one_batch = pl.pairs_per_batch >= pl.n_pairs;
+    // With a single phase requested the workspace must cover every pair: only possible when all pairs fit one batch.
+    if (p->phase != GKA_PHASE_ALL && !one_batch) return GKA_ERR_UNSUPPORTED;
+    for (int pair0 = 0; pair0 < pl.n_pairs; pair0 += pl.pairs_per_batch) {
+        const int np = pl.n_pairs - pair0 < pl.pairs_per_batch ? pl.n_pairs - pair0 : pl.pairs_per_batch;
+        sa.pair0 = pair0;
+        so.pair0 = pair0;
+        if (prof) prof->mark(stream);
+        if (p->phase != GKA_PHASE_SOLVE &&
+            gka::launch_state_pass(sa, np, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
+            return GKA_ERR_LAUNCH;
+        if (prof) prof->mark(stream);
+        if (p->phase != GKA_PHASE_STATES &&
+            gka::launch_chunk_solve(so, np, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
+            return GKA_ERR_LAUNCH;
+        if (prof) prof->mark(stream);
+    }
+    return GKA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+gka_status gka_forward(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
+                       const float *lambda, void *o, const float *H_init, const float *U_init, float *H_final,
+                       float *U_final, float *fro_out, void *workspace, size_t workspace_bytes,
+                       void *hip_stream)
+{
+    return forward_impl(p, q, k, v, gate, lambda, o, H_init, U_init, H_final, U_final, fro_out, workspace,
+                        workspace_bytes, hip_stream, nullptr);
+}
+
+gka_status gka_forward_profile(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
+                               const float *lambda, void *o, const float *H_init, const float *U_init,
+                               float *H_final, float *U_final, float *fro_out, void *workspace,
+                               size_t workspace_bytes, void *hip_stream, float *ms_states, float *ms_solve,
+                               int32_t *n_solve_launches)
+{
+    if (!ms_states || !ms_solve || !n_solve_launches) return GKA_ERR_NULL;
+    PhaseEvents prof;
+    gka_status s = forward_impl(p, q, k, v, gate, lambda, o, H_init, U_init, H_final, U_final, fro_out, workspace,
+                                workspace_bytes, hip_stream, &prof);
+    if (s != GKA_OK) return s;
+    if (!prof.ok || prof.ev.empty() || hipEventSynchronize(prof.ev.back()) != hipSuccess) return GKA_ERR_LAUNCH;
+    float t_states = 0.0f, t_solve = 0.0f;
+    for (size_t i = 0; i + 2 < prof.ev.size(); i += 3) {
+        float a = 0.0f, b = 0.0f;
+        if (hipEventElapsedTime(&a, prof.ev[i], prof.ev[i + 1]) != hipSuccess) return GKA_ERR_LAUNCH;
+        if (hipEventElapsedTime(&b, prof.ev[i + 1], prof.ev[i + 2]) != hipSuccess) return GKA_ERR_LAUNCH;
+        t_states += a;
+        t_solve += b;
+    }
+    *ms_states = t_states;
+    *ms_solve = t_solve;
+    *n_solve_launches = (int32_t)(prof.ev.size() / 3);
     return GKA_OK;
 }
 

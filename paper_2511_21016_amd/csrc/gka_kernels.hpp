@@ -16,6 +16,7 @@ struct StatePassArgs {
     float *ws_hn;                 // partial sums of ||H_[n]||_F^2
     int64_t stride_b, stride_t, stride_h;
     int H, T;
+    int pair0;                    // first (batch, head) pair of this launch; workspace is indexed from 0
     int n_chunks_total;           // chunks per pair
     int n_segs, seg_len;          // segments per pair and chunks per segment (n_segs <= 1: one pass)
     float *seg_buf;               // [pairs, n_segs, 2, d*d] segment summaries / start states
@@ -35,6 +36,7 @@ struct SolveArgs {
     const float *ws_hn;
     int64_t stride_b, stride_t, stride_h;
     int H, T, n_chunks_total, n_iter;
+    int pair0;                    // first (batch, head) pair of this launch; workspace is indexed from 0
 };
 
 struct DecodeArgs {

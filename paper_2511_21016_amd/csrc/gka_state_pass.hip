@@ -38,10 +38,24 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
     const int lane = tid & 63;
     const int w = tid >> 6;                       // column block of the slab owned by this wave
     const int n = lane & 31, g = lane >> 5;
-    const int rb = blockIdx.x % NB;               // slab index (row block of H0 / U0)
-    const int seg = (blockIdx.x / NB) % a.n_segs;
-    const int pair = blockIdx.x / (NB * a.n_segs);
-    const int b = pair / a.H, h = pair % a.H;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2. The NB slabs of one (pair, segment)
+    // read the same k rows, so they are given block indices that are equal modulo 8.
+    int rb, group;
+    {
+        const int id = blockIdx.x;
+        const int full = (gridDim.x / (8 * NB)) * (8 * NB);
+        if (id < full) {
+            const int within = id % (8 * NB);
+            rb = within / 8;                       // slab index (row block of H0 / U0)
+            group = (id / (8 * NB)) * 8 + within % 8;
+        } else {
+            rb = (id - full) % NB;
+            group = full / NB + (id - full) / NB;
+        }
+    }
+    const int seg = group % a.n_segs;
+    const int pair = group / a.n_segs;            // within this launch; indexes the workspace
+    const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
 
     __shared__ __attribute__((aligned(16))) elem_t s_k[kChunk * RS];    // k rows of the chunk
     __shared__ __attribute__((aligned(16))) elem_t s_ks[kChunk * RS];   // k rows scaled by zeta_C / zeta_j
@@ -57,8 +71,8 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
     // accumulators: element (row = 32*w + kidx(r,g), col n) = S0[32*rb + n][32*w + kidx(r,g)]
     f32x16 accH = zero16(), accU = zero16();
     if (a.init_mode == 1) {
-        const float *Hi = a.H_init + (int64_t)pair * D * D;
-        const float *Ui = a.U_init + (int64_t)pair * D * D;
+        const float *Hi = a.H_init + (int64_t)(a.pair0 + pair) * D * D;
+        const float *Ui = a.U_init + (int64_t)(a.pair0 + pair) * D * D;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             int col = 32 * w + kidx(r, g);
@@ -188,8 +202,8 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
     }
 
     if (a.final_mode == 1) {
-        float *Hf = a.H_final + (int64_t)pair * D * D;
-        float *Uf = a.U_final + (int64_t)pair * D * D;
+        float *Hf = a.H_final + (int64_t)(a.pair0 + pair) * D * D;
+        float *Uf = a.U_final + (int64_t)(a.pair0 + pair) * D * D;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             int col = 32 * w + kidx(r, g);
@@ -223,8 +237,8 @@ __global__ __launch_bounds__(D * 2) void segment_combine_kernel(StatePassArgs a)
         sU[r] = 0.0f;
         if (a.H_init) {
             int col = 32 * w + kidx(r, g);
-            sH[r] = a.H_init[(int64_t)pair * D * D + (int64_t)(32 * rb + n) * D + col];
-            sU[r] = a.U_init[(int64_t)pair * D * D + (int64_t)(32 * rb + n) * D + col];
+            sH[r] = a.H_init[(int64_t)(a.pair0 + pair) * D * D + (int64_t)(32 * rb + n) * D + col];
+            sU[r] = a.U_init[(int64_t)(a.pair0 + pair) * D * D + (int64_t)(32 * rb + n) * D + col];
         }
     }
     for (int seg = 0; seg < a.n_segs; ++seg) {
@@ -244,8 +258,8 @@ __global__ __launch_bounds__(D * 2) void segment_combine_kernel(StatePassArgs a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             int col = 32 * w + kidx(r, g);
-            a.H_final[(int64_t)pair * D * D + (int64_t)(32 * rb + n) * D + col] = sH[r];
-            a.U_final[(int64_t)pair * D * D + (int64_t)(32 * rb + n) * D + col] = sU[r];
+            a.H_final[(int64_t)(a.pair0 + pair) * D * D + (int64_t)(32 * rb + n) * D + col] = sH[r];
+            a.U_final[(int64_t)(a.pair0 + pair) * D * D + (int64_t)(32 * rb + n) * D + col] = sU[r];
         }
     }
 }

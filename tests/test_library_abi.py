@@ -65,6 +65,10 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(_p(io_dtype=binding.GKA_F32)) == binding.GKA_ERR_UNSUPPORTED     # f32 tensors need f32 compute
     assert fwd(_p(io_dtype=7)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(phase=3)) == binding.GKA_ERR_UNSUPPORTED
+    # a single phase needs the whole problem in one batch of pairs: this one is far too large for that
+    big = _p(B=64, H=32, T=32768, phase=binding.GKA_PHASE_SOLVE)
+    assert binding.forward_raw(big, fake, fake, fake, fake, fake, fake, workspace=0x100000,
+                               workspace_bytes=binding.forward_workspace_bytes(big)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(strides=(1, -1, 1))) == binding.GKA_ERR_SHAPE
     assert fwd(_p(), q=None) == binding.GKA_ERR_NULL
     assert fwd(_p(), gate=None) == binding.GKA_ERR_NULL
