@@ -31,6 +31,22 @@ namespace gka {
 
 constexpr int kSolveThreads = 256;
 
+// Optional phase timestamps of a few mid-grid workgroups (debug builds only).
+#ifdef GKA_DEBUG_TIMERS
+__device__ unsigned long long g_dbg_timers[64 * 16];
+#define GKA_TSTAMP(i)                                                                            \
+    do {                                                                                         \
+        if (threadIdx.x == 0 && blockIdx.x >= 2048 && blockIdx.x < 2112)                         \
+            g_dbg_timers[(blockIdx.x - 2048) * 16 + (i)] = __builtin_amdgcn_s_memtime();         \
+    } while (0)
+extern "C" int gka_debug_read_timers(unsigned long long *host)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_timers), sizeof(g_dbg_timers));
+}
+#else
+#define GKA_TSTAMP(i) do {} while (0)
+#endif
+
 template <class MMA, int D>
 struct SolveShape {
     typedef typename MMA::frag frag;
@@ -44,7 +60,7 @@ struct SolveShape {
     static constexpr int KT_FRAGS = NB * JB * HS;
     static constexpr int X_FRAGS = 2 * NB * HS;     // operand exchange: [token block][blk][h]
     // row-major staging tile of one chunk of k or v rows, padded against bank conflicts
-    static constexpr int RS = D + 16 / (int)sizeof(elem_t);
+    static constexpr int RS = D + MMA::kRowPad;
     static constexpr size_t row_bytes = (size_t)kChunk * RS * sizeof(elem_t);
     static constexpr size_t h_bytes = (size_t)H_FRAGS * 64 * sizeof(frag);
     static constexpr size_t k_bytes = (size_t)K_FRAGS * 64 * sizeof(frag);
@@ -56,76 +72,69 @@ struct SolveShape {
     static constexpr size_t lds_bytes = h_bytes + k_bytes + kt_bytes + x_bytes + (row_aliases_h ? 0 : row_bytes);
 };
 
-// acc += sum_{blk,h} A[mt][blk][h] * X[blk][h]      (A = H_[n] or U_[n] fragments in LDS)
-template <class MMA, int NB>
-__device__ __forceinline__ f32x16 gemm_state_mt(const typename MMA::frag *sA, int mt,
-                                                const typename MMA::frag (&X)[NB][MMA::HS], f32x16 acc, int lane)
+// acc[a] += sum_s A[a][s] * B[s] over NSTEPS contraction steps; all operands are LDS fragment arrays
+// (fragment s of a set at [s * 64 + lane]). The fragments of step s + 1 are requested before the MFMAs of
+// step s are issued, so LDS latency is paid once per call, not once per MFMA.
+template <class MMA, int NSTEPS, int NA>
+__device__ __forceinline__ void fused_gemm(const typename MMA::frag *const (&A)[NA], const typename MMA::frag *B,
+                                           f32x16 (&acc)[NA], int lane)
 {
+    typename MMA::frag abuf[2][NA], bbuf[2];
 #pragma unroll
-    for (int blk = 0; blk < NB; ++blk)
+    for (int x = 0; x < NA; ++x) abuf[0][x] = A[x][lane];
+    bbuf[0] = B[lane];
 #pragma unroll
-        for (int hh = 0; hh < MMA::HS; ++hh)
-            acc = MMA::mma(sA[((mt * NB + blk) * MMA::HS + hh) * 64 + lane], X[blk][hh], acc);
-    return acc;
-}
-
-// pacc[jt] += sum_{blk,h} K[jt][blk][h] * X[blk][h] for the key blocks jt <= tw (causal)
-template <class MMA, int NB>
-__device__ __forceinline__ void gemm_p(const typename MMA::frag *sK, const typename MMA::frag (&X)[NB][MMA::HS],
-                                       f32x16 (&pacc)[2], int tw, int lane)
-{
+    for (int s = 0; s < NSTEPS; ++s) {
+        const int cur = s & 1, nxt = cur ^ 1;
+        if (s + 1 < NSTEPS) {
 #pragma unroll
-    for (int blk = 0; blk < NB; ++blk)
+            for (int x = 0; x < NA; ++x) abuf[nxt][x] = A[x][(s + 1) * 64 + lane];
+            bbuf[nxt] = B[(s + 1) * 64 + lane];
+        }
+        __builtin_amdgcn_sched_barrier(0);     // keep the requests for step s + 1 ahead of the MFMAs of step s
 #pragma unroll
-        for (int hh = 0; hh < MMA::HS; ++hh)
-            pacc[0] = MMA::mma(sK[((0 * NB + blk) * MMA::HS + hh) * 64 + lane], X[blk][hh], pacc[0]);
-    if (tw == 1) {
-#pragma unroll
-        for (int blk = 0; blk < NB; ++blk)
-#pragma unroll
-            for (int hh = 0; hh < MMA::HS; ++hh)
-                pacc[1] = MMA::mma(sK[((1 * NB + blk) * MMA::HS + hh) * 64 + lane], X[blk][hh], pacc[1]);
+        for (int x = 0; x < NA; ++x) acc[x] = MMA::mma(abuf[cur][x], bbuf[cur], acc[x]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-// (P o M) as B-operand fragments
-template <class MMA>
-__device__ __forceinline__ void mask_p(const f32x16 (&pacc)[2], const f32x16 (&mreg)[2],
-                                       typename MMA::frag (&pm)[2][MMA::HS], int tw)
+// (P o M) as B-operand fragments, key blocks jt <= TW
+template <class MMA, int TW>
+__device__ __forceinline__ void mask_p(const f32x16 (&pacc)[TW + 1], const f32x16 (&mreg)[TW + 1],
+                                       typename MMA::frag (&pm)[TW + 1][MMA::HS])
 {
     constexpr int VEC = MMA::VEC, HS = MMA::HS;
 #pragma unroll
-    for (int hh = 0; hh < HS; ++hh) {
-        float t[VEC];
-#pragma unroll
-        for (int p = 0; p < VEC; ++p) t[p] = pacc[0][hh * VEC + p] * mreg[0][hh * VEC + p];
-        pm[0][hh] = MMA::pack(t);
-    }
-    if (tw == 1) {
+    for (int jt = 0; jt <= TW; ++jt)
 #pragma unroll
         for (int hh = 0; hh < HS; ++hh) {
             float t[VEC];
 #pragma unroll
-            for (int p = 0; p < VEC; ++p) t[p] = pacc[1][hh * VEC + p] * mreg[1][hh * VEC + p];
-            pm[1][hh] = MMA::pack(t);
+            for (int p = 0; p < VEC; ++p) t[p] = pacc[jt][hh * VEC + p] * mreg[jt][hh * VEC + p];
+            pm[jt][hh] = MMA::pack(t);
         }
-    }
 }
 
-// acc += sum_{jt<=tw,h} AT[mt][jt][h] * pm[jt][h]     (AT = K^T or V^T fragments)
-template <class MMA>
-__device__ __forceinline__ f32x16 gemm_intra_mt(const typename MMA::frag *sAT, int mt,
-                                                const typename MMA::frag (&pm)[2][MMA::HS], f32x16 acc, int tw,
-                                                int lane)
+// acc[i] += sum_{jt<=TW,h} AT[mt0 + i][jt][h] * pm[jt][h]     (AT = K^T or V^T fragments in LDS)
+template <class MMA, int NBH, int TW>
+__device__ __forceinline__ void gemm_intra(const typename MMA::frag *sAT, int mt0,
+                                           const typename MMA::frag (&pm)[TW + 1][MMA::HS], f32x16 (&acc)[NBH],
+                                           int lane)
 {
     constexpr int HS = MMA::HS;
+    typename MMA::frag af[NBH][TW + 1][HS];
 #pragma unroll
-    for (int hh = 0; hh < HS; ++hh) acc = MMA::mma(sAT[((mt * 2 + 0) * HS + hh) * 64 + lane], pm[0][hh], acc);
-    if (tw == 1) {
+    for (int i = 0; i < NBH; ++i)
 #pragma unroll
-        for (int hh = 0; hh < HS; ++hh) acc = MMA::mma(sAT[((mt * 2 + 1) * HS + hh) * 64 + lane], pm[1][hh], acc);
-    }
-    return acc;
+        for (int jt = 0; jt <= TW; ++jt)
+#pragma unroll
+            for (int hh = 0; hh < HS; ++hh) af[i][jt][hh] = sAT[(((mt0 + i) * 2 + jt) * HS + hh) * 64 + lane];
+#pragma unroll
+    for (int i = 0; i < NBH; ++i)
+#pragma unroll
+        for (int jt = 0; jt <= TW; ++jt)
+#pragma unroll
+            for (int hh = 0; hh < HS; ++hh) acc[i] = MMA::mma(af[i][jt][hh], pm[jt][hh], acc[i]);
 }
 
 // A block of N16 * kSolveThreads 16-byte units copied global -> registers -> LDS by the workgroup. The two
@@ -225,35 +234,30 @@ __device__ __forceinline__ void build_transposed_frags(typename MMA::frag *sAT, 
     }
 }
 
-// The two waves of a token block swap the halves of an operand: each writes the fragments of its own row
-// blocks, and after the barrier reads all of them. The second barrier frees the region for the next write.
+// This wave's halves of an operand go to the exchange region: fragments [token block][row block][h].
 template <class MMA, int NB>
-__device__ __forceinline__ void exchange_operand(typename MMA::frag *sX, const typename MMA::frag (&own)[NB / 2][MMA::HS],
-                                                 typename MMA::frag (&X)[NB][MMA::HS], int tw, int fh, int lane)
+__device__ __forceinline__ void publish_operand(typename MMA::frag *sX, const typename MMA::frag (&own)[NB / 2][MMA::HS],
+                                                int tw, int mt0, int lane)
 {
-    constexpr int HS = MMA::HS, NBH = NB / 2;
 #pragma unroll
-    for (int i = 0; i < NBH; ++i)
+    for (int i = 0; i < NB / 2; ++i)
 #pragma unroll
-        for (int hh = 0; hh < HS; ++hh) sX[((tw * NB + fh * NBH + i) * HS + hh) * 64 + lane] = own[i][hh];
-    __syncthreads();
-#pragma unroll
-    for (int blk = 0; blk < NB; ++blk)
-#pragma unroll
-        for (int hh = 0; hh < HS; ++hh) X[blk][hh] = sX[((tw * NB + blk) * HS + hh) * 64 + lane];
-    __syncthreads();
+        for (int hh = 0; hh < MMA::HS; ++hh) sX[((tw * NB + mt0 + i) * MMA::HS + hh) * 64 + lane] = own[i][hh];
 }
 
-template <class MMA, class IO, int D>
-__device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
+// The work of one wave. TW (token block) is a template parameter so that the causal structure (key blocks
+// jt <= TW) is resolved at compile time; fh (feature half) only enters through mt0.
+template <class MMA, class IO, int D, int TW>
+__device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned char *smem, int fh)
 {
     typedef SolveShape<MMA, D> SH;
     constexpr int NB = SH::NB, NBH = SH::NBH;
     constexpr int VEC = MMA::VEC, HS = MMA::HS;
+    constexpr int NSTEPS = NB * HS;            // MFMA steps of a contraction over all D features
+    constexpr int NJ = TW + 1;                 // key blocks visible to this token block
     typedef typename MMA::frag frag;
     typedef typename MMA::elem_t elem_t;
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     frag *sH = (frag *)smem;
     frag *sK = (frag *)(smem + SH::h_bytes);
     frag *sKT = (frag *)(smem + SH::h_bytes + SH::k_bytes);
@@ -265,20 +269,22 @@ __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
-    const int tw = w & 1, fh = w >> 1;
     const int mt0 = fh * NBH;
     const int n = lane & 31, g = lane >> 5;
-    const int chunk = blockIdx.x % a.n_chunks_total;
-    const int pair = blockIdx.x / a.n_chunks_total;
+    // Consecutive workgroups take the same chunk index of consecutive (batch, head) pairs: in the [B,T,H,d]
+    // layout the heads of a token are adjacent, so workgroups that run together read adjacent memory.
+    const int pair = blockIdx.x % a.n_pairs;
+    const int chunk = blockIdx.x / a.n_pairs;
     const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
     const int64_t chunk_id = (int64_t)pair * a.n_chunks_total + chunk;    // workspace index within this launch
     const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
     const int64_t gate_base = (int64_t)b * a.T * a.H + h;
     const int tok0 = chunk * kChunk;
-    const int c_local = 32 * tw + n;
+    const int c_local = 32 * TW + n;
     const int tok = tok0 + c_local;
     const bool valid = tok < a.T;
 
+    GKA_TSTAMP(0);
     // ---------------- staging ----------------
     constexpr int H16 = (int)(SH::h_bytes / 16 / kSolveThreads);   // 16-byte units of a state block per thread
     const int64_t tok_off = base_bh + (int64_t)min(tok, a.T - 1) * a.stride_t;
@@ -288,6 +294,8 @@ __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
         // every global read of the prologue is issued here, before the first wait
         RowStage<MMA, IO, D> krows;
         BlockCopy<H16> hcopy;
+        float gm = 1.0f;
+        if (w == 0) gm = a.gate[gate_base + (int64_t)min(tok0 + lane, a.T - 1) * a.H];
         krows.load(a.k, base_bh, a.stride_t, tok0, a.T, tid);
         hcopy.load((const frag *)a.ws_H + chunk_id * (SH::H_FRAGS * 64), tid);
 #pragma unroll
@@ -299,75 +307,80 @@ __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
         float hn[NB * NB];
 #pragma unroll
         for (int i = 0; i < NB * NB; ++i) hn[i] = a.ws_hn[chunk_id * (NB * NB) + i];
-        if (w == 0) {
-            const int t = tok0 + lane;
-            const float gm = a.gate[gate_base + (int64_t)min(t, a.T - 1) * a.H];
-            const float lg = (t < a.T) ? log_gate(gm) : 0.0f;
+        if (w == 0) {                          // the gate was requested first: its wait does not cover the rest
+            const float lg = (tok0 + lane < a.T) ? log2_gate(gm) : 0.0f;
             sG[lane] = wave_inclusive_scan(lg, lane);
         }
+        GKA_TSTAMP(1);
+        krows.store(sRow, tok0, a.T, tid);
+        __syncthreads();
+        GKA_TSTAMP(2);
+        build_row_frags<MMA, D>(sK, sRow, w, lane);
+        build_transposed_frags<MMA, D>(sKT, sRow, w, lane);
         if (!valid) lam = 1.0f;
 #pragma unroll
         for (int i = 0; i < NB * NB; ++i) hn2 += hn[i];
-        krows.store(sRow, tok0, a.T, tid);
-        __syncthreads();
-        build_row_frags<MMA, D>(sK, sRow, w, lane);
-        build_transposed_frags<MMA, D>(sKT, sRow, w, lane);
         __syncthreads();                       // the staging tile may alias the state region
+        GKA_TSTAMP(3);
         hcopy.store(sH, tid);
     }
     __syncthreads();
+    GKA_TSTAMP(4);
 
-    // ---------------- decay mask (Section 4.2.1; log-space form of Appendix B.2) ----------------
+    // ---------------- decay mask (Section 4.2.1; log-space form of Appendix B.2, base 2) ----------------
     const float Gc = sG[c_local];
-    const float zeta = expf(Gc);
-    f32x16 mreg[2];
+    const float zeta = exp2f(Gc);
+    f32x16 mreg[NJ];
 #pragma unroll
-    for (int jt = 0; jt < 2; ++jt)
+    for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int j = 32 * jt + kidx(r, g);
-            mreg[jt][r] = (j <= c_local) ? expf(Gc - sG[j]) : 0.0f;
+            mreg[jt][r] = (j <= c_local) ? exp2f(Gc - sG[j]) : 0.0f;
         }
 
+    GKA_TSTAMP(5);
     // ---------------- chunk-wise Frobenius norm ----------------
     // ||H_c||^2 = zeta_c^2 ||H_[n]||^2 + sum_{j<=c} M[j,c]^2 w_j,
     // w_j = 2 (zeta_j k_j^T H_[n] k_j + sum_{i<j} M[i,j] G_ij^2) + G_jj^2,  G = K K^T:
     // the three-term expansion of Section 4.2.1 with its double sum over (i, j) folded by
     // M[i,c] M[j,c] = M[j,c]^2 M[i,j] (i < j).
-    f32x16 pacc[2];
-    frag X[NB][HS];
+    // Operand sets of the fused contractions: key blocks jt <= TW first, then this wave's row blocks of the state.
+    const frag *Aset[NJ + NBH];
+#pragma unroll
+    for (int jt = 0; jt < NJ; ++jt) Aset[jt] = sK + (jt * NSTEPS) * 64;
+#pragma unroll
+    for (int i = 0; i < NBH; ++i) Aset[NJ + i] = sH + ((mt0 + i) * NSTEPS) * 64;
+    const frag *Kset[NJ], *Hset[NBH];
+#pragma unroll
+    for (int jt = 0; jt < NJ; ++jt) Kset[jt] = Aset[jt];
+#pragma unroll
+    for (int i = 0; i < NBH; ++i) Hset[i] = Aset[NJ + i];
+    const frag *myK = sK + (TW * NSTEPS) * 64;         // this token block's keys as a B operand
     {
+        f32x16 acc[NJ + NBH];
 #pragma unroll
-        for (int blk = 0; blk < NB; ++blk)
-#pragma unroll
-            for (int hh = 0; hh < HS; ++hh) X[blk][hh] = sK[((tw * NB + blk) * HS + hh) * 64 + lane];
+        for (int x = 0; x < NJ + NBH; ++x) acc[x] = zero16();
+        fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myK, acc, lane);
         // k_c^T H_[n] k_c: this wave's rows of H_[n] k_c, then summed over the two feature halves
         float a_part = 0.0f;
 #pragma unroll
-        for (int i = 0; i < NBH; ++i) {
-            f32x16 acc = gemm_state_mt<MMA, NB>(sH, mt0 + i, X, zero16(), lane);
+        for (int i = 0; i < NBH; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                // same row of the same token: element (mt0 + i, r) of the B operand
-                float kv = 0.0f;
+            for (int hh = 0; hh < HS; ++hh) {
+                const frag kf = myK[((mt0 + i) * HS + hh) * 64 + lane];   // rows kidx(hh*VEC + p, g) of block mt0 + i
 #pragma unroll
-                for (int blk = 0; blk < NB; ++blk)
-                    if (blk == mt0 + i) kv = MMA::elem(X[blk][r / VEC], r % VEC);
-                a_part += acc[r] * kv;
+                for (int p = 0; p < VEC; ++p) a_part += acc[NJ + i][hh * VEC + p] * MMA::elem(kf, p);
             }
-        }
         a_part += __shfl_xor(a_part, 32, 64);
         if (g == 0) sA[fh * kChunk + c_local] = a_part;
-        pacc[0] = zero16();
-        pacc[1] = zero16();
-        gemm_p<MMA, NB>(sK, X, pacc, tw, lane);
         float b_part = 0.0f, d_part = 0.0f;
 #pragma unroll
-        for (int jt = 0; jt < 2; ++jt)
+        for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int j = 32 * jt + kidx(r, g);
-                const float g2 = pacc[jt][r] * pacc[jt][r];
+                const float g2 = acc[jt][r] * acc[jt][r];
                 if (j < c_local) b_part += mreg[jt][r] * g2;
                 if (j == c_local) d_part += g2;
             }
@@ -382,15 +395,15 @@ __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
     {
         float f_part = 0.0f;
 #pragma unroll
-        for (int jt = 0; jt < 2; ++jt)
+        for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) f_part += mreg[jt][r] * mreg[jt][r] * sW[32 * jt + kidx(r, g)];
         f_part += __shfl_xor(f_part, 32, 64);
         fro = sqrtf(fmaxf(zeta * zeta * hn2 + f_part, 0.0f));
     }
     if (a.fro_out && valid && fh == 0 && g == 0) a.fro_out[gate_base + (int64_t)tok * a.H] = fro;
-    __syncthreads();                           // sG, sW, sA are dead: the region becomes the operand exchange
 
+    GKA_TSTAMP(6);
     // ---------------- Chebyshev iteration (Algorithm 1), residual form ----------------
     const float L = fro + lam, mu = lam;       // Section 4.1: L = ||H_t||_F + lambda_t, mu = lambda_t
     const float s0 = 2.0f / (L + mu);
@@ -416,22 +429,28 @@ __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
 #pragma unroll
         for (int hh = 0; hh < HS; ++hh) own[i][hh] = MMA::pack(&dl[i][hh * VEC]);
     }
+    const frag *myX = sX + (TW * NSTEPS) * 64;         // this token block's operand in the exchange region
     float omega = 2.0f;
+    __syncthreads();                           // sG, sW, sA are dead: the region becomes the operand exchange
     for (int it = 0; it < a.n_iter; ++it) {
-        // A operands are re-read from LDS in every pass (they are not kept in registers across passes)
+        // operands are re-read from LDS in every pass (they are not kept in registers across passes)
         asm volatile("" ::: "memory");
-        exchange_operand<MMA, NB>(sX, own, X, tw, fh, lane);
-        pacc[0] = zero16();
-        pacc[1] = zero16();
-        gemm_p<MMA, NB>(sK, X, pacc, tw, lane);
-        frag pm[2][HS];
-        mask_p<MMA>(pacc, mreg, pm, tw);
+        publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
+        __syncthreads();
+        // two sweeps over the D features of delta: P = K delta^T (key blocks jt <= TW), then the state product
+        f32x16 pacc[NJ];
+#pragma unroll
+        for (int jt = 0; jt < NJ; ++jt) pacc[jt] = zero16();
+        fused_gemm<MMA, NSTEPS, NJ>(Kset, myX, pacc, lane);
+        fused_gemm<MMA, NSTEPS, NBH>(Hset, myX, gS, lane);
+        __syncthreads();                       // the exchange region may be overwritten from here on
+        frag pm[NJ][HS];
+        mask_p<MMA, TW>(pacc, mreg, pm);
+        gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, gI, lane);
         omega = 4.0f / (4.0f - rho2 * omega);                      // weight schedule
         const float cm = omega - 1.0f, ncs = -omega * s0;
 #pragma unroll
         for (int i = 0; i < NBH; ++i) {
-            gS[i] = gemm_state_mt<MMA, NB>(sH, mt0 + i, X, gS[i], lane);
-            gI[i] = gemm_intra_mt<MMA>(sKT, mt0 + i, pm, gI[i], tw, lane);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const float nres = zeta * gS[i][r] + gI[i][r] + lam * xi[i][r];   // -r_{i-1}
@@ -443,6 +462,7 @@ __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
         }
     }
 
+    GKA_TSTAMP(7);
     // ---------------- readout y_c = zeta_c U_[n] xhat_c + sum_{j<=c} M[j,c] v_j (k_j . xhat_c) ----------------
     constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
     const frag *Uw = (const frag *)a.ws_U + chunk_id * (NSPL * SH::H_FRAGS * 64);
@@ -451,64 +471,89 @@ __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
     vrows.load(a.v, base_bh, a.stride_t, tok0, a.T, tid);
     ucopy.load(Uw, tid);
     if (NSPL == 2) ulocopy.load(Uw + SH::H_FRAGS * 64, tid);
-    // xhat as B operand: hi part, and for the bf16 path the rounding remainder as a second operand
-    frag Xlo[NB][HS];
-    {
-        frag ownlo[NBH][HS];
+    // xhat as B operand: the rounded value and, on the bf16 path, the rounding remainder as a second operand
+    frag ownlo[NBH][HS];
 #pragma unroll
-        for (int i = 0; i < NBH; ++i)
+    for (int i = 0; i < NBH; ++i)
 #pragma unroll
-            for (int hh = 0; hh < HS; ++hh) {
-                own[i][hh] = MMA::pack(&xi[i][hh * VEC]);
-                if (NSPL == 2) {
-                    float lo[VEC];
+        for (int hh = 0; hh < HS; ++hh) {
+            own[i][hh] = MMA::pack(&xi[i][hh * VEC]);
+            if (NSPL == 2) {
+                float lo[VEC];
 #pragma unroll
-                    for (int p = 0; p < VEC; ++p) lo[p] = xi[i][hh * VEC + p] - MMA::elem(own[i][hh], p);
-                    ownlo[i][hh] = MMA::pack(lo);
-                }
+                for (int p = 0; p < VEC; ++p) lo[p] = xi[i][hh * VEC + p] - MMA::elem(own[i][hh], p);
+                ownlo[i][hh] = MMA::pack(lo);
             }
-        exchange_operand<MMA, NB>(sX, own, X, tw, fh, lane);      // its first barrier also ends all use of sH, sKT
-        if (NSPL == 2) exchange_operand<MMA, NB>(sX, ownlo, Xlo, tw, fh, lane);
-    }
+        }
+    __syncthreads();                           // every wave is done with H_[n] and K^T
+    GKA_TSTAMP(8);
     vrows.store(sRow, tok0, a.T, tid);
-    pacc[0] = zero16();
-    pacc[1] = zero16();
-    gemm_p<MMA, NB>(sK, X, pacc, tw, lane);
-    if (NSPL == 2) gemm_p<MMA, NB>(sK, Xlo, pacc, tw, lane);
-    frag pm[2][HS];
-    mask_p<MMA>(pacc, mreg, pm, tw);
     __syncthreads();
-    build_transposed_frags<MMA, D>(sKT, sRow, w, lane);
+    build_transposed_frags<MMA, D>(sKT, sRow, w, lane);      // V^T replaces K^T
+    __syncthreads();                           // the staging tile may alias the state region
+    GKA_TSTAMP(9);
+    ucopy.store(sH, tid);                      // U_[n] (rounded part) replaces H_[n]
+    publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
     __syncthreads();
-    ucopy.store(sH, tid);
-    __syncthreads();
-    f32x16 acc[NBH];
+    f32x16 acc[NJ + NBH];
 #pragma unroll
-    for (int i = 0; i < NBH; ++i) {
-        acc[i] = gemm_state_mt<MMA, NB>(sH, mt0 + i, X, zero16(), lane);
-        if (NSPL == 2) acc[i] = gemm_state_mt<MMA, NB>(sH, mt0 + i, Xlo, acc[i], lane);
-    }
+    for (int x = 0; x < NJ + NBH; ++x) acc[x] = zero16();
+    fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);          // K xhat^T and U xhat
     if (NSPL == 2) {
         __syncthreads();
-        ulocopy.store(sH, tid);
+        publish_operand<MMA, NB>(sX, ownlo, TW, mt0, lane);
         __syncthreads();
+        fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);      // the same on the remainder of xhat
+        __syncthreads();
+        ulocopy.store(sH, tid);                // remainder of U_[n]
+        publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
+        __syncthreads();
+        const frag *Uset[NBH];
+        f32x16 accU[NBH];
 #pragma unroll
-        for (int i = 0; i < NBH; ++i) acc[i] = gemm_state_mt<MMA, NB>(sH, mt0 + i, X, acc[i], lane);
+        for (int i = 0; i < NBH; ++i) {
+            Uset[i] = Aset[NJ + i];
+            accU[i] = acc[NJ + i];
+        }
+        fused_gemm<MMA, NSTEPS, NBH>(Uset, myX, accU, lane);
+#pragma unroll
+        for (int i = 0; i < NBH; ++i) acc[NJ + i] = accU[i];
+    }
+    frag pm[NJ][HS];
+    f32x16 y[NBH];
+    {
+        f32x16 pacc[NJ];
+#pragma unroll
+        for (int jt = 0; jt < NJ; ++jt) pacc[jt] = acc[jt];
+        mask_p<MMA, TW>(pacc, mreg, pm);
     }
 #pragma unroll
-    for (int i = 0; i < NBH; ++i) {
+    for (int i = 0; i < NBH; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] *= zeta;
-        acc[i] = gemm_intra_mt<MMA>(sKT, mt0 + i, pm, acc[i], tw, lane);
-    }
+        for (int r = 0; r < 16; ++r) y[i][r] = acc[NJ + i][r] * zeta;
+    gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, y, lane);
+    GKA_TSTAMP(10);
     if (valid) {
 #pragma unroll
         for (int i = 0; i < NBH; ++i)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4)
-                IO::store4(a.o, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g, acc[i][4 * q4], acc[i][4 * q4 + 1],
-                           acc[i][4 * q4 + 2], acc[i][4 * q4 + 3]);
+                IO::store4(a.o, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g, y[i][4 * q4], y[i][4 * q4 + 1],
+                           y[i][4 * q4 + 2], y[i][4 * q4 + 3]);
     }
+    GKA_TSTAMP(11);
+}
+
+template <class MMA, class IO, int D>
+__device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // wave-uniform: token block and feature half of this wave
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (w & 1)
+        chunk_solve_wave<MMA, IO, D, 1>(a, smem, w >> 1);
+    else
+        chunk_solve_wave<MMA, IO, D, 0>(a, smem, w >> 1);
 }
 
 // bf16 path: capped at 256 registers so that two workgroups (two waves per SIMD) share a CU.
@@ -545,8 +590,16 @@ static hipError_t launch_chunk_solve_t(const SolveArgs &a, int n_pairs, hipStrea
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)SH::lds_bytes);
     if (e != hipSuccess) return e;
+    SolveArgs args = a;
+    args.n_pairs = n_pairs;
     dim3 grid((unsigned)(n_pairs * a.n_chunks_total)), block(kSolveThreads);
-    hipLaunchKernelGGL(kern, grid, block, SH::lds_bytes, stream, a);
+#ifdef GKA_DEBUG_LDS_PAD
+    const size_t lds = SH::lds_bytes + GKA_DEBUG_LDS_PAD;
+    (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+#else
+    const size_t lds = SH::lds_bytes;
+#endif
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
     return hipGetLastError();
 }
 

@@ -16,7 +16,7 @@
 
 namespace gka {
 
-constexpr float kMinLogGate = -100.0f;
+constexpr float kMinLog2Gate = -144.269504f;   // log2 of the smallest gate, exp(-100)
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -127,6 +127,9 @@ struct MmaBF16 {
     static constexpr bool kSplitReadout = true;   // readout uses hi+lo operands
     typedef bf16x8 frag;
     typedef uint16_t elem_t;                      // operand element as stored in LDS rows
+    // Padding of a row-major LDS tile (elements): rows 32 bytes apart modulo 256, so that the four rows
+    // addressed by a 16-lane block of a transpose read fall into disjoint banks.
+    static constexpr int kRowPad = 16;
     static __device__ __forceinline__ elem_t to_elem(float x) { return f32_to_bf16_bits(x); }
     static __device__ __forceinline__ float from_elem(elem_t e) { return bf16_bits_to_f32(e); }
     // fragment from VEC stored elements
@@ -167,6 +170,7 @@ struct MmaF32 {
     static constexpr bool kSplitReadout = false;
     typedef float frag;
     typedef float elem_t;
+    static constexpr int kRowPad = 4;
     static __device__ __forceinline__ elem_t to_elem(float x) { return x; }
     static __device__ __forceinline__ float from_elem(elem_t e) { return e; }
     static __device__ __forceinline__ frag pack_elems(const elem_t *e) { return e[0]; }
@@ -206,7 +210,8 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
-// log(gamma) with the documented floor; gamma of padded tail tokens is 1.
-__device__ __forceinline__ float log_gate(float gamma) { return fmaxf(logf(gamma), kMinLogGate); }
+// log2(gamma) with the documented floor. Decays are kept in base-2 log space (the hardware's exp and log are
+// base 2): cumulative sums of these, and exp2 of their differences.
+__device__ __forceinline__ float log2_gate(float gamma) { return fmaxf(log2f(gamma), kMinLog2Gate); }
 
 }  // namespace gka

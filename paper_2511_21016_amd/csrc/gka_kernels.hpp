@@ -19,8 +19,9 @@ struct StatePassArgs {
     int pair0;                    // first (batch, head) pair of this launch; workspace is indexed from 0
     int n_chunks_total;           // chunks per pair
     int n_segs, seg_len;          // segments per pair and chunks per segment (n_segs <= 1: one pass)
+    int n_pairs;                  // pairs of this launch (set by the launcher)
     float *seg_buf;               // [pairs, n_segs, 2, d*d] segment summaries / start states
-    float *seg_logdecay;          // [pairs, n_segs] sum of log gates over each segment
+    float *seg_logdecay;          // [pairs, n_segs] sum of log2 gates over each segment
     // set by the launcher:
     int init_mode;                // 0 zero, 1 H_init/U_init (row-major), 2 segment start states
     int final_mode;               // 0 none, 1 H_final/U_final (row-major), 2 segment summaries
@@ -36,6 +37,7 @@ struct SolveArgs {
     const float *ws_hn;
     int64_t stride_b, stride_t, stride_h;
     int H, T, n_chunks_total, n_iter;
+    int n_pairs;                  // pairs of this launch (set by the launcher)
     int pair0;                    // first (batch, head) pair of this launch; workspace is indexed from 0
 };
 

@@ -27,8 +27,8 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
     constexpr int HS = MMA::HS;
     constexpr int STEPS = kChunk / (2 * VEC);     // MFMA steps over the chunk's tokens
     constexpr int NT = D * 2;                     // threads
-    constexpr int RS = D + 16 / (int)sizeof(typename MMA::elem_t);
-    constexpr int RSV = 32 + 16 / (int)sizeof(typename MMA::elem_t);
+    constexpr int RS = D + MMA::kRowPad;
+    constexpr int RSV = 32 + MMA::kRowPad;
     constexpr int KP = kChunk * (D / 4) / NT;     // 4-element pieces of k per thread (= 8)
     constexpr int VP = kChunk * 8 / NT;           // 4-element pieces of the v slab per thread
     typedef typename MMA::frag frag;
@@ -53,8 +53,9 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
             group = full / NB + (id - full) / NB;
         }
     }
-    const int seg = group % a.n_segs;
-    const int pair = group / a.n_segs;            // within this launch; indexes the workspace
+    // pairs vary fastest: workgroups that run together then read adjacent memory ([B,T,H,d]: heads are adjacent)
+    const int pair = group % a.n_pairs;           // within this launch; indexes the workspace
+    const int seg = group / a.n_pairs;
     const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
 
     __shared__ __attribute__((aligned(16))) elem_t s_k[kChunk * RS];    // k rows of the chunk
@@ -115,11 +116,11 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
 
     for (int c = chunk_begin; c < chunk_end; ++c) {
         // ---- gates of the chunk: G_j = sum_{i<=j} log gamma_i, weights exp(G_C - G_j)
-        const float lg = (c * kChunk + lane < a.T) ? log_gate(gate_next) : 0.0f;
+        const float lg = (c * kChunk + lane < a.T) ? log2_gate(gate_next) : 0.0f;
         const float G = wave_inclusive_scan(lg, lane);
         const float Gtot = __shfl(G, 63, 64);
         Gseg += Gtot;
-        const float wd = expf(Gtot - G);          // lane j: zeta_C / zeta_j
+        const float wd = exp2f(Gtot - G);          // lane j: zeta_C / zeta_j
         __syncthreads();                          // previous chunk's LDS readers are done
 #pragma unroll
         for (int i = 0; i < KP; ++i) {
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
             MMA::store4(s_v + (piece / 8) * RSV + 4 * (piece % 8), vv);
         }
         if (c + 1 < chunk_end) fetch(c + 1);      // in flight while this chunk is processed
-        const float zetaC = expf(Gtot);
+        const float zetaC = exp2f(Gtot);
 
         // ---- write the state before the chunk, fragment order
         if (a.write_frags) {
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(D * 2) void segment_combine_kernel(StatePassArgs a)
     for (int seg = 0; seg < a.n_segs; ++seg) {
         float *segH = a.seg_buf + ((((int64_t)(pair * a.n_segs + seg) * NB + rb) * NB + w) * 2 + 0) * 1024;
         float *segU = segH + 1024;
-        const float decay = expf(a.seg_logdecay[pair * a.n_segs + seg]);
+        const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + seg]);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const float dH = segH[r * 64 + lane], dU = segU[r * 64 + lane];
@@ -270,6 +271,7 @@ static hipError_t launch_state_pass_t(const StatePassArgs &a0, int n_pairs, hipS
     constexpr int NB = D / 32;
     dim3 block(D * 2);
     StatePassArgs a = a0;
+    a.n_pairs = n_pairs;
     if (a.n_segs <= 1) {
         a.n_segs = 1;
         a.seg_len = a.n_chunks_total;
