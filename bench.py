@@ -60,10 +60,18 @@ def main():
     ws = torch.empty(binding.forward_workspace_bytes(params), dtype=torch.uint8, device="cuda")
     outs = [torch.empty_like(s["v"]) for s in sets]
 
+    # raw device addresses, marshalled once: a step is then a single C call that enqueues the kernels
+    stream = torch.cuda.current_stream().cuda_stream
+    ptrs = [tuple(s[name].data_ptr() for name in ("q", "k", "v", "gate", "lam")) + (o.data_ptr(),)
+            for s, o in zip(sets, outs)]
+    ws_ptr, ws_bytes = ws.data_ptr(), ws.numel()
+
     def step(i):
-        s = sets[i % N_INPUT_SETS]
-        binding.gka_forward(s["q"], s["k"], s["v"], s["gate"], s["lam"], w.n_iter, workspace=ws,
-                            out=outs[i % N_INPUT_SETS])
+        q, k, v, gate, lam, o = ptrs[i % N_INPUT_SETS]
+        st = binding.forward_raw(params, q, k, v, gate, lam, o, workspace=ws_ptr, workspace_bytes=ws_bytes,
+                                 stream=stream)
+        if st != binding.GKA_OK:
+            raise binding.GkaError(st, binding.status_string(st))
 
     for i in range(args.warmup):
         step(i)
@@ -83,11 +91,8 @@ def main():
     ms_states = ms_solve = 0.0
     n_launches = 1
     for i in range(args.steps):
-        s = sets[i % N_INPUT_SETS]
-        st, a, b, n_launches = binding.forward_profile_raw(
-            params, s["q"].data_ptr(), s["k"].data_ptr(), s["v"].data_ptr(), s["gate"].data_ptr(),
-            s["lam"].data_ptr(), outs[i % N_INPUT_SETS].data_ptr(), ws.data_ptr(), ws.numel(),
-            torch.cuda.current_stream().cuda_stream)
+        q, k, v, gate, lam, o = ptrs[i % N_INPUT_SETS]
+        st, a, b, n_launches = binding.forward_profile_raw(params, q, k, v, gate, lam, o, ws_ptr, ws_bytes, stream)
         if st != binding.GKA_OK:
             raise binding.GkaError(st, binding.status_string(st))
         ms_states += a / args.steps

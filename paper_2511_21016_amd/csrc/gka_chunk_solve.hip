@@ -59,17 +59,15 @@ struct SolveShape {
     static constexpr int K_FRAGS = JB * NB * HS;
     static constexpr int KT_FRAGS = NB * JB * HS;
     static constexpr int X_FRAGS = 2 * NB * HS;     // operand exchange: [token block][blk][h]
-    // row-major staging tile of one chunk of k or v rows, padded against bank conflicts
-    static constexpr int RS = D + MMA::kRowPad;
-    static constexpr size_t row_bytes = (size_t)kChunk * RS * sizeof(elem_t);
     static constexpr size_t h_bytes = (size_t)H_FRAGS * 64 * sizeof(frag);
     static constexpr size_t k_bytes = (size_t)K_FRAGS * 64 * sizeof(frag);
     static constexpr size_t kt_bytes = (size_t)KT_FRAGS * 64 * sizeof(frag);
     static constexpr size_t x_bytes = (size_t)X_FRAGS * 64 * sizeof(frag);
-    static constexpr bool row_aliases_h = row_bytes <= h_bytes;   // staging tile reuses the state region
-    static constexpr size_t misc_bytes = 4 * kChunk * sizeof(float);   // sG, sW, sA[2]; aliases the exchange region
-    static_assert(misc_bytes <= x_bytes, "per-token scalars must fit the exchange region");
-    static constexpr size_t lds_bytes = h_bytes + k_bytes + kt_bytes + x_bytes + (row_aliases_h ? 0 : row_bytes);
+    // Row-major staging tile of one chunk of k or v rows: unpadded and swizzled, exactly the size of the
+    // operand-exchange region, which it shares (the two are never live together).
+    typedef SwizzledRows<D * (int)sizeof(elem_t), (int)sizeof(elem_t)> Rows;
+    static_assert((size_t)kChunk * D * sizeof(elem_t) == x_bytes, "staging tile and exchange region coincide");
+    static constexpr size_t lds_bytes = h_bytes + k_bytes + kt_bytes + x_bytes;
 };
 
 // acc[a] += sum_s A[a][s] * B[s] over NSTEPS contraction steps; all operands are LDS fragment arrays
@@ -137,30 +135,23 @@ __device__ __forceinline__ void gemm_intra(const typename MMA::frag *sAT, int mt
             for (int hh = 0; hh < HS; ++hh) acc[i] = MMA::mma(af[i][jt][hh], pm[jt][hh], acc[i]);
 }
 
-// A block of N16 * kSolveThreads 16-byte units copied global -> registers -> LDS by the workgroup. The two
-// halves are separate calls so that the global loads can be issued long before the LDS region is free.
+// A block of N16 * kSolveThreads 16-byte units copied global -> LDS by the workgroup, asynchronously and without
+// staging registers (w = wave index, wave-uniform).
 template <int N16>
-struct BlockCopy {
-    uint4 r[N16];
-    __device__ __forceinline__ void load(const void *src, int tid)
-    {
-        const uint4 *s = (const uint4 *)src;
+__device__ __forceinline__ void async_block_copy(void *lds_dst, const void *gsrc, int w, int lane)
+{
 #pragma unroll
-        for (int i = 0; i < N16; ++i) r[i] = s[i * kSolveThreads + tid];
+    for (int i = 0; i < N16; ++i) {
+        const int unit0 = (i * (kSolveThreads / 64) + w) * 64;
+        async_copy16_to_lds((char *)lds_dst + (size_t)unit0 * 16, (const char *)gsrc + (size_t)(unit0 + lane) * 16);
     }
-    __device__ __forceinline__ void store(void *dst, int tid) const
-    {
-        uint4 *d = (uint4 *)dst;
-#pragma unroll
-        for (int i = 0; i < N16; ++i) d[i * kSolveThreads + tid] = r[i];
-    }
-};
+}
 
 // One chunk of rows of x (k or v): global -> registers (load), registers -> row-major LDS tile of operand
 // elements (store).
 template <class MMA, class IO, int D>
 struct RowStage {
-    static constexpr int RS = SolveShape<MMA, D>::RS;
+    typedef typename SolveShape<MMA, D>::Rows Rows;
     static constexpr int P4 = D / 4;
     static constexpr int NP = kChunk * P4 / kSolveThreads;
     typename IO::raw4 r[NP];
@@ -183,7 +174,7 @@ struct RowStage {
             const int piece = i * kSolveThreads + tid;
             f32x4 v = IO::cvt4(r[i]);
             if (tok0 + piece / P4 >= T) v = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            MMA::store4(sRow + (piece / P4) * RS + 4 * (piece % P4), v);
+            MMA::store4(sRow + Rows()(piece / P4, 4 * (piece % P4)), v);
         }
     }
 };
@@ -194,20 +185,21 @@ __device__ __forceinline__ void build_row_frags(typename MMA::frag *sK, const ty
                                                 int lane)
 {
     typedef SolveShape<MMA, D> SH;
-    constexpr int VEC = MMA::VEC, HS = MMA::HS, NB = SH::NB, RS = SH::RS;
+    constexpr int VEC = MMA::VEC, HS = MMA::HS, NB = SH::NB;
+    const typename SH::Rows at;
     const int n = lane & 31, g = lane >> 5;
     for (int f = w; f < SH::K_FRAGS; f += 4) {
         const int hh = f % HS, blk = (f / HS) % NB, jt = f / (HS * NB);
         if constexpr (VEC == 8) {
             // kidx(8*hh + p, g) = 16*hh + 8*(p/4) + 4*g + p%4: two runs of four consecutive features
-            const typename MMA::elem_t *src = sRow + (32 * jt + n) * RS + 32 * blk + 16 * hh + 4 * g;
-            u16x4 lo = *(const u16x4 *)src, hi = *(const u16x4 *)(src + 8);
+            const int col = 32 * blk + 16 * hh + 4 * g;
+            u16x4 lo = *(const u16x4 *)(sRow + at(32 * jt + n, col)), hi = *(const u16x4 *)(sRow + at(32 * jt + n, col + 8));
             u16x8 u = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
             sK[f * 64 + lane] = __builtin_bit_cast(typename MMA::frag, u);
         } else {
             typename MMA::elem_t e[VEC];
 #pragma unroll
-            for (int p = 0; p < VEC; ++p) e[p] = sRow[(32 * jt + n) * RS + 32 * blk + kidx(hh * VEC + p, g)];
+            for (int p = 0; p < VEC; ++p) e[p] = sRow[at(32 * jt + n, 32 * blk + kidx(hh * VEC + p, g))];
             sK[f * 64 + lane] = MMA::pack_elems(e);
         }
     }
@@ -219,17 +211,18 @@ __device__ __forceinline__ void build_transposed_frags(typename MMA::frag *sAT, 
                                                        int w, int lane)
 {
     typedef SolveShape<MMA, D> SH;
-    constexpr int VEC = MMA::VEC, HS = MMA::HS, RS = SH::RS;
+    constexpr int VEC = MMA::VEC, HS = MMA::HS;
+    const typename SH::Rows at;
     const int n = lane & 31, g = lane >> 5;
     for (int f = w; f < SH::KT_FRAGS; f += 4) {
         const int hh = f % HS, jt = (f / HS) % 2, mt = f / (2 * HS);
         if constexpr (VEC == 8) {
             const int t0 = 32 * jt + 16 * hh + 4 * g;       // kidx(8*hh + p, g) = 16*hh + 8*(p/4) + 4*g + p%4
             sAT[f * 64 + lane] =
-                gather_transposed_bf16(sRow, RS, 32 * mt + 16 * ((lane >> 4) & 1), lane, t0, t0 + 8);
+                gather_transposed_bf16(sRow, at, 32 * mt + 16 * ((lane >> 4) & 1), lane, t0, t0 + 8);
         } else {
             auto tok_of = [&](int p) { return 32 * jt + kidx(hh * VEC + p, g); };
-            sAT[f * 64 + lane] = gather_transposed<MMA>(sRow, RS, 32 * mt + n, tok_of);
+            sAT[f * 64 + lane] = gather_transposed<MMA>(sRow, at, 32 * mt + n, tok_of);
         }
     }
 }
@@ -248,7 +241,7 @@ __device__ __forceinline__ void publish_operand(typename MMA::frag *sX, const ty
 // The work of one wave. TW (token block) is a template parameter so that the causal structure (key blocks
 // jt <= TW) is resolved at compile time; fh (feature half) only enters through mt0.
 template <class MMA, class IO, int D, int TW>
-__device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned char *smem, int fh)
+__device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned char *smem, int w)
 {
     typedef SolveShape<MMA, D> SH;
     constexpr int NB = SH::NB, NBH = SH::NBH;
@@ -262,13 +255,13 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     frag *sK = (frag *)(smem + SH::h_bytes);
     frag *sKT = (frag *)(smem + SH::h_bytes + SH::k_bytes);
     frag *sX = (frag *)(smem + SH::h_bytes + SH::k_bytes + SH::kt_bytes);
-    elem_t *sRow = SH::row_aliases_h ? (elem_t *)smem : (elem_t *)(smem + SH::h_bytes + SH::k_bytes + SH::kt_bytes + SH::x_bytes);
-    float *sG = (float *)sX;                   // per-token scalars live in the exchange region before the passes
-    float *sW = sG + kChunk;
+    elem_t *sRow = (elem_t *)sX;               // staging tile of k (then v) rows shares the exchange region
+    float *sW = (float *)sX;                   // so do the per-token scalars of the Frobenius phase
     float *sA = sW + kChunk;                   // [2][kChunk]
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, w = tid >> 6;
+    const int lane = tid & 63;
+    const int fh = w >> 1;                     // w: wave index, wave-uniform
     const int mt0 = fh * NBH;
     const int n = lane & 31, g = lane >> 5;
     // Consecutive workgroups take the same chunk index of consecutive (batch, head) pairs: in the [B,T,H,d]
@@ -289,15 +282,14 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     constexpr int H16 = (int)(SH::h_bytes / 16 / kSolveThreads);   // 16-byte units of a state block per thread
     const int64_t tok_off = base_bh + (int64_t)min(tok, a.T - 1) * a.stride_t;
     float lam, hn2 = 0.0f;
+    float Gall;                                // lane j: G_j = sum_{i<=j} log2 gamma_i over the chunk
     typename IO::raw4 qraw[NBH][4];            // q of this lane's token, rows of this wave's feature half
     {
         // every global read of the prologue is issued here, before the first wait
+        async_block_copy<H16>(sH, (const frag *)a.ws_H + chunk_id * (SH::H_FRAGS * 64), w, lane);   // H_[n] -> LDS
+        const float gm = a.gate[gate_base + (int64_t)min(tok0 + lane, a.T - 1) * a.H];
         RowStage<MMA, IO, D> krows;
-        BlockCopy<H16> hcopy;
-        float gm = 1.0f;
-        if (w == 0) gm = a.gate[gate_base + (int64_t)min(tok0 + lane, a.T - 1) * a.H];
         krows.load(a.k, base_bh, a.stride_t, tok0, a.T, tid);
-        hcopy.load((const frag *)a.ws_H + chunk_id * (SH::H_FRAGS * 64), tid);
 #pragma unroll
         for (int i = 0; i < NBH; ++i)
 #pragma unroll
@@ -307,28 +299,21 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         float hn[NB * NB];
 #pragma unroll
         for (int i = 0; i < NB * NB; ++i) hn[i] = a.ws_hn[chunk_id * (NB * NB) + i];
-        if (w == 0) {                          // the gate was requested first: its wait does not cover the rest
-            const float lg = (tok0 + lane < a.T) ? log2_gate(gm) : 0.0f;
-            sG[lane] = wave_inclusive_scan(lg, lane);
-        }
-        GKA_TSTAMP(1);
         krows.store(sRow, tok0, a.T, tid);
         __syncthreads();
-        GKA_TSTAMP(2);
+        GKA_TSTAMP(1);
         build_row_frags<MMA, D>(sK, sRow, w, lane);
         build_transposed_frags<MMA, D>(sKT, sRow, w, lane);
+        // every wave scans the chunk's gates itself: no LDS round trip for the per-token decays
+        Gall = wave_inclusive_scan((tok0 + lane < a.T) ? log2_gate(gm) : 0.0f, lane);
         if (!valid) lam = 1.0f;
 #pragma unroll
         for (int i = 0; i < NB * NB; ++i) hn2 += hn[i];
-        __syncthreads();                       // the staging tile may alias the state region
-        GKA_TSTAMP(3);
-        hcopy.store(sH, tid);
+        GKA_TSTAMP(2);
     }
-    __syncthreads();
-    GKA_TSTAMP(4);
 
     // ---------------- decay mask (Section 4.2.1; log-space form of Appendix B.2, base 2) ----------------
-    const float Gc = sG[c_local];
+    const float Gc = __shfl(Gall, c_local, 64);
     const float zeta = exp2f(Gc);
     f32x16 mreg[NJ];
 #pragma unroll
@@ -336,8 +321,13 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int j = 32 * jt + kidx(r, g);
-            mreg[jt][r] = (j <= c_local) ? exp2f(Gc - sG[j]) : 0.0f;
+            const float Gj = __shfl(Gall, j, 64);
+            mreg[jt][r] = (j <= c_local) ? exp2f(Gc - Gj) : 0.0f;
         }
+    GKA_TSTAMP(3);
+    wait_all_memory();                         // H_[n] has landed in LDS
+    __syncthreads();                           // fragments and H_[n] visible; the staging tile is free
+    GKA_TSTAMP(4);
 
     GKA_TSTAMP(5);
     // ---------------- chunk-wise Frobenius norm ----------------
@@ -431,7 +421,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     }
     const frag *myX = sX + (TW * NSTEPS) * 64;         // this token block's operand in the exchange region
     float omega = 2.0f;
-    __syncthreads();                           // sG, sW, sA are dead: the region becomes the operand exchange
+    __syncthreads();                           // sW, sA are dead: the region becomes the operand exchange
     for (int it = 0; it < a.n_iter; ++it) {
         // operands are re-read from LDS in every pass (they are not kept in registers across passes)
         asm volatile("" ::: "memory");
@@ -467,10 +457,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
     const frag *Uw = (const frag *)a.ws_U + chunk_id * (NSPL * SH::H_FRAGS * 64);
     RowStage<MMA, IO, D> vrows;
-    BlockCopy<H16> ucopy, ulocopy;
     vrows.load(a.v, base_bh, a.stride_t, tok0, a.T, tid);
-    ucopy.load(Uw, tid);
-    if (NSPL == 2) ulocopy.load(Uw + SH::H_FRAGS * 64, tid);
     // xhat as B operand: the rounded value and, on the bf16 path, the rounding remainder as a second operand
     frag ownlo[NBH][HS];
 #pragma unroll
@@ -485,15 +472,16 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
                 ownlo[i][hh] = MMA::pack(lo);
             }
         }
-    __syncthreads();                           // every wave is done with H_[n] and K^T
+    __syncthreads();                           // every wave is done with H_[n], K^T and the exchange region
     GKA_TSTAMP(8);
+    async_block_copy<H16>(sH, Uw, w, lane);    // U_[n] (rounded part) replaces H_[n]
     vrows.store(sRow, tok0, a.T, tid);
     __syncthreads();
     build_transposed_frags<MMA, D>(sKT, sRow, w, lane);      // V^T replaces K^T
-    __syncthreads();                           // the staging tile may alias the state region
+    __syncthreads();                           // the staging tile becomes the exchange region again
     GKA_TSTAMP(9);
-    ucopy.store(sH, tid);                      // U_[n] (rounded part) replaces H_[n]
     publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
+    wait_all_memory();
     __syncthreads();
     f32x16 acc[NJ + NBH];
 #pragma unroll
@@ -505,17 +493,14 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         __syncthreads();
         fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);      // the same on the remainder of xhat
         __syncthreads();
-        ulocopy.store(sH, tid);                // remainder of U_[n]
+        async_block_copy<H16>(sH, Uw + SH::H_FRAGS * 64, w, lane);    // remainder of U_[n]
         publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
+        wait_all_memory();
         __syncthreads();
-        const frag *Uset[NBH];
         f32x16 accU[NBH];
 #pragma unroll
-        for (int i = 0; i < NBH; ++i) {
-            Uset[i] = Aset[NJ + i];
-            accU[i] = acc[NJ + i];
-        }
-        fused_gemm<MMA, NSTEPS, NBH>(Uset, myX, accU, lane);
+        for (int i = 0; i < NBH; ++i) accU[i] = acc[NJ + i];
+        fused_gemm<MMA, NSTEPS, NBH>(Hset, myX, accU, lane);
 #pragma unroll
         for (int i = 0; i < NBH; ++i) acc[NJ + i] = accU[i];
     }
@@ -551,9 +536,9 @@ __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
     // wave-uniform: token block and feature half of this wave
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (w & 1)
-        chunk_solve_wave<MMA, IO, D, 1>(a, smem, w >> 1);
+        chunk_solve_wave<MMA, IO, D, 1>(a, smem, w);
     else
-        chunk_solve_wave<MMA, IO, D, 0>(a, smem, w >> 1);
+        chunk_solve_wave<MMA, IO, D, 0>(a, smem, w);
 }
 
 // bf16 path: capped at 256 registers so that two workgroups (two waves per SIMD) share a CU.

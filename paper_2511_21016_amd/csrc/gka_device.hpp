@@ -86,16 +86,34 @@ struct IOBF16 {
     }
 };
 
-// Transposed operand fragment from a row-major LDS tile (features contiguous, `rs` elements per token row).
-// Returns, for this lane, the VEC elements x[token(p)][col] with token(p) = tok_base(p), where the caller
-// enumerates the tokens through `tok_of(p)`. Generic version: one LDS read per element.
-template <class MMA, class TokOf>
-__device__ __forceinline__ typename MMA::frag gather_transposed(const typename MMA::elem_t *tile, int rs, int col,
+// Row-major LDS tiles of k or v rows (features contiguous) come in two layouts, both a functor (row, col) ->
+// element offset: rows padded so that consecutive rows start 32 bytes apart modulo 256, or unpadded rows whose
+// 32-byte granules are XOR-swizzled with the row number. Either way the four rows addressed by a 16-lane block of
+// a transpose read (below) fall into disjoint banks.
+struct PaddedRows {
+    int rs;                                        // elements per row including the padding
+    __device__ __forceinline__ int operator()(int row, int col) const { return row * rs + col; }
+};
+template <int ROW_BYTES, int ELEM_BYTES>
+struct SwizzledRows {
+    static constexpr int kGranules = ROW_BYTES / 32;
+    static constexpr int kMask = (kGranules < 8 ? kGranules : 8) - 1;
+    __device__ __forceinline__ int operator()(int row, int col) const
+    {
+        const int byte = col * ELEM_BYTES;
+        return (row * ROW_BYTES + (byte ^ ((row & kMask) << 5))) / ELEM_BYTES;
+    }
+};
+
+// Transposed operand fragment from a row-major LDS tile: the VEC elements x[tok_of(p)][col] of this lane.
+// Generic version: one LDS read per element.
+template <class MMA, class Layout, class TokOf>
+__device__ __forceinline__ typename MMA::frag gather_transposed(const typename MMA::elem_t *tile, Layout at, int col,
                                                                 TokOf tok_of)
 {
     typename MMA::elem_t e[MMA::VEC];
 #pragma unroll
-    for (int p = 0; p < MMA::VEC; ++p) e[p] = tile[tok_of(p) * rs + col];
+    for (int p = 0; p < MMA::VEC; ++p) e[p] = tile[at(tok_of(p), col)];
     return MMA::pack_elems(e);
 }
 
@@ -104,20 +122,31 @@ __device__ __forceinline__ typename MMA::frag gather_transposed(const typename M
 // 16-bit values found at element (i % 4) of the addresses supplied by lanes (i / 4), (i / 4) + 4, + 8, + 12 of
 // the block. So lane i supplies the address of token run[i / 4] at the 4-column group (i % 4) of its block's 16
 // columns, and receives tokens run[0..3] at its own column. `col16` is the first of the block's 16 columns.
-__device__ __forceinline__ bf16x8 gather_transposed_bf16(const uint16_t *tile, int rs, int col16, int lane, int t0,
+template <class Layout>
+__device__ __forceinline__ bf16x8 gather_transposed_bf16(const uint16_t *tile, Layout at, int col16, int lane, int t0,
                                                          int t1)
 {
     typedef short s16x4 __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const int i = lane & 15;
-    const uint16_t *p0 = tile + (t0 + (i >> 2)) * rs + col16 + 4 * (i & 3);
-    const uint16_t *p1 = tile + (t1 + (i >> 2)) * rs + col16 + 4 * (i & 3);
+    const uint16_t *p0 = tile + at(t0 + (i >> 2), col16 + 4 * (i & 3));
+    const uint16_t *p1 = tile + at(t1 + (i >> 2), col16 + 4 * (i & 3));
     s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p0);
     s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p1);
     typedef short s16x8 __attribute__((ext_vector_type(8)));
     s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
     return __builtin_bit_cast(bf16x8, r);
 }
+
+// Asynchronous copy global -> LDS without staging registers: every lane moves 16 bytes, a wave's 64 pieces land
+// contiguously at the (wave-uniform) destination. Completion is tracked by the vector-memory counter: wait for it
+// (s_waitcnt vmcnt(0)) and pass a barrier before other waves read the data.
+__device__ __forceinline__ void async_copy16_to_lds(void *lds_wave_base, const void *gsrc_lane)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc_lane,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+__device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
 // ---- arithmetic of the matrix products ------------------------------------------------------
 // VEC = operand elements per lane per MFMA; HS = MFMA steps per 32-block of the contraction.

@@ -23,8 +23,8 @@ struct StatePassArgs {
     float *seg_buf;               // [pairs, n_segs, 2, d*d] segment summaries / start states
     float *seg_logdecay;          // [pairs, n_segs] sum of log2 gates over each segment
     // set by the launcher:
-    int init_mode;                // 0 zero, 1 H_init/U_init (row-major), 2 segment start states
-    int final_mode;               // 0 none, 1 H_final/U_final (row-major), 2 segment summaries
+    int init_mode;                // 0 zero state, 1 H_init/U_init (or zero) advanced over the earlier segments
+    int final_mode;               // 1 last segment writes H_final/U_final, 2 segment summary to seg_buf
     int write_frags;              // store chunk states to ws_H / ws_U / ws_hn
 };
 

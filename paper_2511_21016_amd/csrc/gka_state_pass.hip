@@ -11,16 +11,20 @@
 //      back transposed as MFMA operands; the next chunk's rows are fetched while the current one is used.
 //
 // The recurrence over chunks is an affine scan, S_[n+1] = zeta^(n) S_[n] + Delta_n. Long sequences are cut
-// into segments: a first launch reduces every segment to (prod zeta, Delta) from a zero state, a small
-// combine kernel scans the segment summaries into segment start states, and a second launch walks every
-// segment from its true start state and writes the chunk states.
+// into segments: a first launch reduces every segment to (prod zeta, Delta) from a zero state; a second launch
+// walks every segment again, from its true start state (a short scan over the summaries of the segments before
+// it), and writes the chunk states.
 #include "gka_device.hpp"
 #include "gka_kernels.hpp"
 
 namespace gka {
 
+#ifndef GKA_STATE_WAVES
+#define GKA_STATE_WAVES 2          // waves per SIMD the state-pass kernel is compiled for (register cap)
+#endif
+
 template <class MMA, class IO, int D>
-__global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
+__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE_WAVES))) void state_pass_kernel(StatePassArgs a)
 {
     constexpr int NB = D / 32;
     constexpr int VEC = MMA::VEC;
@@ -58,88 +62,94 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
     const int seg = group / a.n_pairs;
     const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
 
-    __shared__ __attribute__((aligned(16))) elem_t s_k[kChunk * RS];    // k rows of the chunk
-    __shared__ __attribute__((aligned(16))) elem_t s_ks[kChunk * RS];   // k rows scaled by zeta_C / zeta_j
-    __shared__ __attribute__((aligned(16))) elem_t s_v[kChunk * RSV];   // the slab's 32 columns of the v rows
+    // Both operands of S += sum_j w_j a_j k_j^T carry sqrt(w_j): (sqrt(w_j) a_j)(sqrt(w_j) k_j)^T.
+    __shared__ __attribute__((aligned(16))) elem_t s_k[kChunk * RS];    // k rows of the chunk, scaled
+    __shared__ __attribute__((aligned(16))) elem_t s_v[kChunk * RSV];   // the slab's 32 columns of the v rows, scaled
 
     const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
     const int64_t gate_base = (int64_t)b * a.T * a.H + h;
     const int chunk_begin = seg * a.seg_len;
     const int chunk_end = min(chunk_begin + a.seg_len, a.n_chunks_total);
-    float *segH = a.seg_buf + ((((int64_t)(pair * a.n_segs + seg) * NB + rb) * NB + w) * 2 + 0) * 1024;
-    float *segU = segH + 1024;
+    // per (pair, segment, slab, wave): two 16x64 float tiles in accumulator order
+    auto seg_tile = [&](int sg) {
+        return a.seg_buf + ((((int64_t)(pair * a.n_segs + sg) * NB + rb) * NB + w) * 2) * 1024;
+    };
 
     // accumulators: element (row = 32*w + kidx(r,g), col n) = S0[32*rb + n][32*w + kidx(r,g)]
     f32x16 accH = zero16(), accU = zero16();
-    if (a.init_mode == 1) {
-        const float *Hi = a.H_init + (int64_t)(a.pair0 + pair) * D * D;
-        const float *Ui = a.U_init + (int64_t)(a.pair0 + pair) * D * D;
+    if (a.init_mode != 0) {
+        if (a.H_init) {
+            const float *Hi = a.H_init + (int64_t)(a.pair0 + pair) * D * D;
+            const float *Ui = a.U_init + (int64_t)(a.pair0 + pair) * D * D;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int col = 32 * w + kidx(r, g);
-            accH[r] = Hi[(int64_t)(32 * rb + n) * D + col];
-            accU[r] = Ui[(int64_t)(32 * rb + n) * D + col];
+            for (int r = 0; r < 16; ++r) {
+                int col = 32 * w + kidx(r, g);
+                accH[r] = Hi[(int64_t)(32 * rb + n) * D + col];
+                accU[r] = Ui[(int64_t)(32 * rb + n) * D + col];
+            }
         }
-    } else if (a.init_mode == 2) {
+        // start state of this segment: scan of the summaries (decay, Delta) of the segments before it
+        for (int sg = 0; sg < seg; ++sg) {
+            const float *t = seg_tile(sg);
+            const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            accH[r] = segH[r * 64 + lane];
-            accU[r] = segU[r * 64 + lane];
+            for (int r = 0; r < 16; ++r) {
+                accH[r] = decay * accH[r] + t[r * 64 + lane];
+                accU[r] = decay * accU[r] + t[1024 + r * 64 + lane];
+            }
         }
     }
 
-    // prefetch registers for the next chunk's rows
-    // Rows past the end of the sequence are read from the last valid row (a divergent branch around a load
-    // would force a wait on it) and zeroed when they are stored to LDS.
-    typename IO::raw4 kreg[KP], vreg[VP];
-    float gate_next = 1.0f;
-    auto fetch = [&](int c) {
+    // Register prefetch, two chunks deep. Rows past the end of the sequence are read from the last valid row (a
+    // divergent branch around a load would force a wait on it) and zeroed when they are stored to LDS.
+    struct Fetch {
+        typename IO::raw4 k[KP], v[VP];
+        float gate;
+    };
+    auto fetch = [&](Fetch &f, int c) {
 #pragma unroll
         for (int i = 0; i < KP; ++i) {
             const int piece = i * NT + tid;
             const int row = piece / (D / 4), c4 = piece % (D / 4);
             const int t = min(c * kChunk + row, a.T - 1);
-            kreg[i] = IO::load_raw4(a.k, base_bh + (int64_t)t * a.stride_t + 4 * c4);
+            f.k[i] = IO::load_raw4(a.k, base_bh + (int64_t)t * a.stride_t + 4 * c4);
         }
 #pragma unroll
         for (int i = 0; i < VP; ++i) {
             const int piece = i * NT + tid;
             const int row = piece / 8, c4 = piece % 8;
             const int t = min(c * kChunk + row, a.T - 1);
-            vreg[i] = IO::load_raw4(a.v, base_bh + (int64_t)t * a.stride_t + 32 * rb + 4 * c4);
+            f.v[i] = IO::load_raw4(a.v, base_bh + (int64_t)t * a.stride_t + 32 * rb + 4 * c4);
         }
         const int t = min(c * kChunk + lane, a.T - 1);
-        gate_next = a.gate[gate_base + (int64_t)t * a.H];
+        f.gate = a.gate[gate_base + (int64_t)t * a.H];
     };
-    if (chunk_begin < chunk_end) fetch(chunk_begin);
     float Gseg = 0.0f;
 
-    for (int c = chunk_begin; c < chunk_end; ++c) {
-        // ---- gates of the chunk: G_j = sum_{i<=j} log gamma_i, weights exp(G_C - G_j)
-        const float lg = (c * kChunk + lane < a.T) ? log2_gate(gate_next) : 0.0f;
+    auto process = [&](const Fetch &f, int c) {
+        // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights 2^(G_C - G_j)
+        const float lg = (c * kChunk + lane < a.T) ? log2_gate(f.gate) : 0.0f;
         const float G = wave_inclusive_scan(lg, lane);
         const float Gtot = __shfl(G, 63, 64);
         Gseg += Gtot;
-        const float wd = exp2f(Gtot - G);          // lane j: zeta_C / zeta_j
+        const float swd = exp2f(0.5f * (Gtot - G));   // lane j: sqrt(zeta_C / zeta_j)
         __syncthreads();                          // previous chunk's LDS readers are done
 #pragma unroll
         for (int i = 0; i < KP; ++i) {
             const int piece = i * NT + tid;
             const int row = piece / (D / 4);
-            f32x4 kv = IO::cvt4(kreg[i]);
+            f32x4 kv = IO::cvt4(f.k[i]);
             if (c * kChunk + row >= a.T) kv = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            MMA::store4(s_k + row * RS + 4 * (piece % (D / 4)), kv);
-            const float wrow = __shfl(wd, row, 64);
-            MMA::store4(s_ks + row * RS + 4 * (piece % (D / 4)), kv * wrow);
+            MMA::store4(s_k + row * RS + 4 * (piece % (D / 4)), kv * __shfl(swd, row, 64));
         }
 #pragma unroll
         for (int i = 0; i < VP; ++i) {
             const int piece = i * NT + tid;
-            f32x4 vv = IO::cvt4(vreg[i]);
-            if (c * kChunk + piece / 8 >= a.T) vv = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            MMA::store4(s_v + (piece / 8) * RSV + 4 * (piece % 8), vv);
+            const int row = piece / 8;
+            f32x4 vv = IO::cvt4(f.v[i]);
+            if (c * kChunk + row >= a.T) vv = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            MMA::store4(s_v + row * RSV + 4 * (piece % 8), vv * __shfl(swd, row, 64));
         }
-        if (c + 1 < chunk_end) fetch(c + 1);      // in flight while this chunk is processed
         const float zetaC = exp2f(Gtot);
 
         // ---- write the state before the chunk, fragment order
@@ -163,11 +173,11 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
             for (int r = 0; r < 16; ++r) vals[r] = accU[r];
 #pragma unroll
             for (int hh = 0; hh < HS; ++hh) {
-                frag f = MMA::pack(vals + hh * VEC);
-                Uw[((rb * NB + w) * HS + hh) * 64 + lane] = f;
+                frag fr = MMA::pack(vals + hh * VEC);
+                Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
                 if (NSPL == 2) {
 #pragma unroll
-                    for (int p = 0; p < VEC; ++p) lo[hh * VEC + p] = vals[hh * VEC + p] - MMA::elem(f, p);
+                    for (int p = 0; p < VEC; ++p) lo[hh * VEC + p] = vals[hh * VEC + p] - MMA::elem(fr, p);
                 }
             }
             if (NSPL == 2) {
@@ -176,7 +186,7 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
                     Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(lo + hh * VEC);
             }
         }
-        __syncthreads();                          // s_k, s_ks, s_v visible
+        __syncthreads();                          // s_k, s_v visible
 
         // ---- S <- zeta_C S + sum_j w_j a_j k_j^T
 #pragma unroll
@@ -188,80 +198,52 @@ __global__ __launch_bounds__(D * 2) void state_pass_kernel(StatePassArgs a)
             frag fa, fk, fv;
             if constexpr (MMA::VEC == 8) {
                 const int sub = 16 * ((lane >> 4) & 1);      // this 16-lane block's columns within the 32
-                fa = gather_transposed_bf16(s_ks, RS, 32 * w + sub, lane, j0, j0 + 4);
-                fk = gather_transposed_bf16(s_k, RS, 32 * rb + sub, lane, j0, j0 + 4);
-                fv = gather_transposed_bf16(s_v, RSV, sub, lane, j0, j0 + 4);
+                fa = gather_transposed_bf16(s_k, PaddedRows{RS}, 32 * w + sub, lane, j0, j0 + 4);
+                fk = gather_transposed_bf16(s_k, PaddedRows{RS}, 32 * rb + sub, lane, j0, j0 + 4);
+                fv = gather_transposed_bf16(s_v, PaddedRows{RSV}, sub, lane, j0, j0 + 4);
             } else {
                 auto tok_of = [&](int p) { return j0 + p; };
-                fa = gather_transposed<MMA>(s_ks, RS, 32 * w + n, tok_of);
-                fk = gather_transposed<MMA>(s_k, RS, 32 * rb + n, tok_of);
-                fv = gather_transposed<MMA>(s_v, RSV, n, tok_of);
+                fa = gather_transposed<MMA>(s_k, PaddedRows{RS}, 32 * w + n, tok_of);
+                fk = gather_transposed<MMA>(s_k, PaddedRows{RS}, 32 * rb + n, tok_of);
+                fv = gather_transposed<MMA>(s_v, PaddedRows{RSV}, n, tok_of);
             }
             accH = MMA::mma(fa, fk, accH);
             accU = MMA::mma(fa, fv, accU);
         }
+    };
+
+    // two fetch buffers in flight: while chunk c is processed, chunks c + 1 and c + 2 are on their way
+    Fetch f0, f1;
+    if (chunk_begin < chunk_end) fetch(f0, chunk_begin);
+    if (chunk_begin + 1 < chunk_end) fetch(f1, chunk_begin + 1);
+    for (int c = chunk_begin; c < chunk_end; c += 2) {
+        process(f0, c);
+        if (c + 2 < chunk_end) fetch(f0, c + 2);
+        if (c + 1 < chunk_end) {
+            process(f1, c + 1);
+            if (c + 3 < chunk_end) fetch(f1, c + 3);
+        }
     }
 
     if (a.final_mode == 1) {
-        float *Hf = a.H_final + (int64_t)(a.pair0 + pair) * D * D;
-        float *Uf = a.U_final + (int64_t)(a.pair0 + pair) * D * D;
+        if (a.H_final && seg == a.n_segs - 1) {
+            float *Hf = a.H_final + (int64_t)(a.pair0 + pair) * D * D;
+            float *Uf = a.U_final + (int64_t)(a.pair0 + pair) * D * D;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int col = 32 * w + kidx(r, g);
-            Hf[(int64_t)(32 * rb + n) * D + col] = accH[r];
-            Uf[(int64_t)(32 * rb + n) * D + col] = accU[r];
+            for (int r = 0; r < 16; ++r) {
+                int col = 32 * w + kidx(r, g);
+                Hf[(int64_t)(32 * rb + n) * D + col] = accH[r];
+                Uf[(int64_t)(32 * rb + n) * D + col] = accU[r];
+            }
         }
     } else if (a.final_mode == 2) {
+        float *t = seg_tile(seg);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            segH[r * 64 + lane] = accH[r];
-            segU[r * 64 + lane] = accU[r];
+            t[r * 64 + lane] = accH[r];
+            t[1024 + r * 64 + lane] = accU[r];
         }
         if (rb == 0 && tid == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
-    }
-}
-
-// Scan of the segment summaries: seg_buf[s] holds Delta_s on entry and the start state of segment s on
-// exit; the state after the last segment goes to H_final / U_final when requested.
-template <int D>
-__global__ __launch_bounds__(D * 2) void segment_combine_kernel(StatePassArgs a)
-{
-    constexpr int NB = D / 32;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int n = lane & 31, g = lane >> 5;
-    const int rb = blockIdx.x % NB;
-    const int pair = blockIdx.x / NB;
-    float sH[16], sU[16];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        sH[r] = 0.0f;
-        sU[r] = 0.0f;
-        if (a.H_init) {
-            int col = 32 * w + kidx(r, g);
-            sH[r] = a.H_init[(int64_t)(a.pair0 + pair) * D * D + (int64_t)(32 * rb + n) * D + col];
-            sU[r] = a.U_init[(int64_t)(a.pair0 + pair) * D * D + (int64_t)(32 * rb + n) * D + col];
-        }
-    }
-    for (int seg = 0; seg < a.n_segs; ++seg) {
-        float *segH = a.seg_buf + ((((int64_t)(pair * a.n_segs + seg) * NB + rb) * NB + w) * 2 + 0) * 1024;
-        float *segU = segH + 1024;
-        const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + seg]);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float dH = segH[r * 64 + lane], dU = segU[r * 64 + lane];
-            segH[r * 64 + lane] = sH[r];
-            segU[r * 64 + lane] = sU[r];
-            sH[r] = decay * sH[r] + dH;
-            sU[r] = decay * sU[r] + dU;
-        }
-    }
-    if (a.H_final) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int col = 32 * w + kidx(r, g);
-            a.H_final[(int64_t)(a.pair0 + pair) * D * D + (int64_t)(32 * rb + n) * D + col] = sH[r];
-            a.U_final[(int64_t)(a.pair0 + pair) * D * D + (int64_t)(32 * rb + n) * D + col] = sU[r];
-        }
     }
 }
 
@@ -275,26 +257,20 @@ static hipError_t launch_state_pass_t(const StatePassArgs &a0, int n_pairs, hipS
     if (a.n_segs <= 1) {
         a.n_segs = 1;
         a.seg_len = a.n_chunks_total;
-        a.init_mode = a.H_init ? 1 : 0;
-        a.final_mode = a.H_final ? 1 : 0;
-        a.write_frags = 1;
-        hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * NB), block, 0, stream, a);
-        return hipGetLastError();
+    } else {
+        // summaries (decay, Delta from a zero state) of every segment but the last
+        a.init_mode = 0;
+        a.final_mode = 2;
+        a.write_frags = 0;
+        hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * NB * (a.n_segs - 1)), block, 0, stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    dim3 grid(n_pairs * NB * a.n_segs);
-    a.init_mode = 0;
-    a.final_mode = 2;
-    a.write_frags = 0;
-    hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), grid, block, 0, stream, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((segment_combine_kernel<D>), dim3(n_pairs * NB), block, 0, stream, a);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    a.init_mode = 2;
-    a.final_mode = 0;
+    // every segment from its true start state (H_init / U_init scanned with the summaries before it)
+    a.init_mode = 1;
+    a.final_mode = 1;
     a.write_frags = 1;
-    hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * NB * a.n_segs), block, 0, stream, a);
     return hipGetLastError();
 }
 
