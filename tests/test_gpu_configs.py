@@ -1,0 +1,99 @@
+"""GPU parity at the full sizes of the five benchmark configurations, through the C ABI, in the launch
+configuration bench.py times. The fp64 oracle runs on the host cores on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_21016_amd import binding, synth
+from gka_testutil import pair_rel_err, to_device, to_host, upload_inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4     # max relative error, fp32 configurations
+TOL_BF16 = 2e-2    # max relative error, bf16 configurations
+
+
+def _forward(w, x, compute, **kw):
+    import torch
+    dev = upload_inputs(x, w.dtype)
+    out = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=compute, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def test_cfg1_tiny_f32_full():
+    w = synth.CFG1
+    x = synth.make_inputs(w)
+    o = _forward(w, x, binding.GKA_COMPUTE_F32)
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    assert pair_rel_err(to_host(o), ref) <= TOL_F32
+
+
+def test_cfg2_layer_bf16_full():
+    w = synth.CFG2
+    x = synth.make_inputs(w)
+    o, ex = _forward(w, x, binding.GKA_COMPUTE_BF16, return_fro=True)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, return_fro=True)
+    err = pair_rel_err(to_host(o), ref)
+    print("cfg2 max rel err", err)
+    assert err <= TOL_BF16
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+
+
+def test_cfg3_long_bf16_full():
+    w = synth.CFG3
+    x = synth.make_inputs(w)
+    o = _forward(w, x, binding.GKA_COMPUTE_BF16)
+    y = to_host(o)
+    del o
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    err = pair_rel_err(y, ref)
+    print("cfg3 max rel err", err)
+    assert err <= TOL_BF16
+
+
+def test_cfg4_illconditioned_full():
+    """bf16 tensors, ill-conditioned H_t: run with float32 matrix products (the documented mode for such inputs)."""
+    w = synth.CFG4
+    x = synth.make_inputs(w)
+    o = _forward(w, x, binding.GKA_COMPUTE_F32)
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    err = pair_rel_err(to_host(o), ref)
+    print("cfg4 max rel err", err)
+    assert err <= TOL_BF16
+
+
+def test_cfg5_decode_subset():
+    """16 of the 256 sequences x 32 heads: prefill 2048 tokens with gka_forward, then 1024 single-token steps with
+    gka_decode_step; the oracle follows every step. (Pairs are independent, so a subset of sequences exercises the
+    same kernels; the full 256-sequence batch is what the decode benchmark times.)"""
+    import torch
+    w = synth.CFG5.scaled(B=16)
+    n_steps = synth.CFG5_DECODE_STEPS
+    x = synth.make_inputs(w)
+    o, ex = _forward(w, x, binding.GKA_COMPUTE_F32, return_state=True)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, return_state=True)
+    assert pair_rel_err(to_host(o), ref) <= TOL_BF16
+    Hd, Ud = ex["H_final"], ex["U_final"]
+    np.testing.assert_allclose(to_host(Hd), rex["H_final"], rtol=0, atol=2e-5 * np.abs(rex["H_final"]).max())
+    np.testing.assert_allclose(to_host(Ud), rex["U_final"], rtol=0, atol=2e-5 * np.abs(rex["U_final"]).max())
+    # both sides continue from the GPU's fp32 states
+    Hs, Us = to_host(Hd), to_host(Ud)
+    steps = synth.make_decode_tokens(w, n_steps)
+    dev = {name: to_device(steps[name], w.dtype if name in ("q", "k", "v") else "f32") for name in steps}
+    outs = torch.empty((n_steps, w.B, w.H, w.d), dtype=torch.bfloat16, device="cuda")
+    for s in range(n_steps):
+        binding.gka_decode_step(Hd, Ud, dev["q"][s], dev["k"][s], dev["v"][s], dev["gate"][s], dev["lam"][s],
+                                w.n_iter, out=outs[s])
+    torch.cuda.synchronize()
+    y = to_host(outs)
+    worst = 0.0
+    for s in range(n_steps):
+        r = oracle.decode_step(Hs, Us, steps["q"][s], steps["k"][s], steps["v"][s], steps["gate"][s],
+                               steps["lam"][s], w.n_iter)
+        e = np.abs(y[s] - r).max(axis=-1) / np.abs(r).max(axis=-1)
+        worst = max(worst, float(e.max()))
+    print("cfg5 decode max rel err over", n_steps, "steps:", worst)
+    assert worst <= TOL_BF16
+    np.testing.assert_allclose(to_host(Hd), Hs, rtol=0, atol=1e-4 * np.abs(Hs).max())
+    np.testing.assert_allclose(to_host(Ud), Us, rtol=0, atol=1e-4 * np.abs(Us).max())
