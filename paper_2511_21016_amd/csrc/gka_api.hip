@@ -18,6 +18,8 @@ struct Plan {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr int kStateMinWorkgroups = 256;   // one state-pass workgroup per CU
+constexpr int kStateMaxWalk = 64;          // chunks a state-pass workgroup walks before segments are added
 #ifndef GKA_BATCH_STATE_BYTES
 #define GKA_BATCH_STATE_BYTES (1024u << 20)
 #endif
@@ -74,9 +76,12 @@ gka_status make_plan(const gka_params *p, Plan *pl)
     pl->off_U = align_up(pl->off_H + nc * gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
     pl->off_hn = align_up(pl->off_U + nc * gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
     pl->off_seg = align_up(pl->off_hn + nc * gka::ws_hn_bytes_per_chunk(pl->d), 256);
-    // Segments of the chunk scan: enough workgroups to fill the chip, at least two chunks per segment.
+    // Segments of the chunk scan. A workgroup walks its chunks one after the other (a few microseconds each), and a
+    // segmented pass reads k and v twice, so: one segment unless that leaves CUs idle or makes the walk longer than
+    // about 64 chunks; never fewer than two chunks per segment.
     const int wg_per_seg = pl->pairs_per_batch * (pl->d / 32);
-    int n_segs = 2048 / wg_per_seg;
+    int n_segs = (kStateMinWorkgroups + wg_per_seg - 1) / wg_per_seg;
+    if (n_segs < pl->n_chunks / kStateMaxWalk) n_segs = pl->n_chunks / kStateMaxWalk;
     if (n_segs > pl->n_chunks / 2) n_segs = pl->n_chunks / 2;
     if (n_segs < 1) n_segs = 1;
     pl->seg_len = (pl->n_chunks + n_segs - 1) / n_segs;

@@ -19,6 +19,21 @@
 
 namespace gka {
 
+#ifdef GKA_DEBUG_TIMERS
+__device__ unsigned long long g_dbg_state_timers[64 * 16];
+#define GKA_STSTAMP(i)                                                                          \
+    do {                                                                                        \
+        if (threadIdx.x == 0 && blockIdx.x >= 1024 && blockIdx.x < 1088)                         \
+            g_dbg_state_timers[(blockIdx.x - 1024) * 16 + (i)] = __builtin_amdgcn_s_memtime();  \
+    } while (0)
+extern "C" int gka_debug_read_state_timers(unsigned long long *host)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_state_timers), sizeof(g_dbg_state_timers));
+}
+#else
+#define GKA_STSTAMP(i) do {} while (0)
+#endif
+
 #ifndef GKA_STATE_WAVES
 #define GKA_STATE_WAVES 2          // waves per SIMD the state-pass kernel is compiled for (register cap)
 #endif
@@ -127,13 +142,17 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
     float Gseg = 0.0f;
 
     auto process = [&](const Fetch &f, int c) {
+        const bool stamp = (c == chunk_begin + 2);
+        if (stamp) GKA_STSTAMP(1);
         // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights 2^(G_C - G_j)
         const float lg = (c * kChunk + lane < a.T) ? log2_gate(f.gate) : 0.0f;
         const float G = wave_inclusive_scan(lg, lane);
         const float Gtot = __shfl(G, 63, 64);
         Gseg += Gtot;
         const float swd = exp2f(0.5f * (Gtot - G));   // lane j: sqrt(zeta_C / zeta_j)
+        if (stamp) GKA_STSTAMP(2);
         __syncthreads();                          // previous chunk's LDS readers are done
+        if (stamp) GKA_STSTAMP(3);
 #pragma unroll
         for (int i = 0; i < KP; ++i) {
             const int piece = i * NT + tid;
@@ -151,6 +170,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
             MMA::store4(s_v + row * RSV + 4 * (piece % 8), vv * __shfl(swd, row, 64));
         }
         const float zetaC = exp2f(Gtot);
+        if (stamp) GKA_STSTAMP(4);
 
         // ---- write the state before the chunk, fragment order
         if (a.write_frags) {
@@ -186,7 +206,9 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
                     Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(lo + hh * VEC);
             }
         }
+        if (stamp) GKA_STSTAMP(5);
         __syncthreads();                          // s_k, s_v visible
+        if (stamp) GKA_STSTAMP(6);
 
         // ---- S <- zeta_C S + sum_j w_j a_j k_j^T
 #pragma unroll
@@ -210,10 +232,12 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
             accH = MMA::mma(fa, fk, accH);
             accU = MMA::mma(fa, fv, accU);
         }
+        if (stamp) GKA_STSTAMP(7);
     };
 
     // two fetch buffers in flight: while chunk c is processed, chunks c + 1 and c + 2 are on their way
     Fetch f0, f1;
+    GKA_STSTAMP(0);
     if (chunk_begin < chunk_end) fetch(f0, chunk_begin);
     if (chunk_begin + 1 < chunk_end) fetch(f1, chunk_begin + 1);
     for (int c = chunk_begin; c < chunk_end; c += 2) {
@@ -225,6 +249,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
         }
     }
 
+    GKA_STSTAMP(8);
     if (a.final_mode == 1) {
         if (a.H_final && seg == a.n_segs - 1) {
             float *Hf = a.H_final + (int64_t)(a.pair0 + pair) * D * D;
