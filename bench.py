@@ -17,6 +17,10 @@ if ROOT not in sys.path:
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak
+# HBM bytes of one solve-kernel launch on this workload, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/chunk_solve_and_state_pass_cfg2_hbm_traffic.md (648 MiB read + 124 MiB written). Update with the kernel.
+SOLVE_TRAFFIC_BYTES = (648 + 124) * (1 << 20)
 N_INPUT_SETS = 3                   # rotated so that the 256 MiB of q,k,v,o do not sit in the last-level cache
 
 
@@ -37,6 +41,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); every (batch, head) pair is independent, "
@@ -72,6 +77,12 @@ def main():
                                  stream=stream)
         if st != binding.GKA_OK:
             raise binding.GkaError(st, binding.status_string(st))
+
+    # A plain 1 GiB device copy, untimed: under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` it calibrates the counters.
+    calib_src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    del calib_src, calib_dst
 
     for i in range(args.warmup):
         step(i)
@@ -128,8 +139,38 @@ def main():
                      "solve_ms_per_launch": ms_solve_launch},
         "roofline": {"kernel": "chunk_solve_kernel<MmaBF16,IOBF16,128>", "bound": "mfma",
                      "achieved": tflops_solve, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops_solve / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                     "frac": tflops_solve / MFMA_BF16_PEAK_TFLOPS, "traffic": SOLVE_TRAFFIC_BYTES},
     }
+
+    # ---- recurrent decode (configuration 5 shape: 256 sequences x 32 heads, d = 128, n_iter = 10), HBM bound:
+    # 256 KiB of fp32 state read + written per (sequence, head) per step. Extra information, not the headline metric.
+    if not args.no_decode:
+        dB, dH, dd, d_steps = 256, 32, 128, 50
+        gen = torch.Generator(device="cuda").manual_seed(5)
+        Hs = torch.zeros((dB, dH, dd, dd), dtype=torch.float32, device="cuda")
+        Us = torch.randn((dB, dH, dd, dd), dtype=torch.float32, device="cuda", generator=gen)
+        qd = torch.nn.functional.normalize(torch.randn((dB, dH, dd), device="cuda", generator=gen), dim=-1).bfloat16()
+        kd = torch.nn.functional.normalize(torch.randn((dB, dH, dd), device="cuda", generator=gen), dim=-1).bfloat16()
+        vd = torch.randn((dB, dH, dd), device="cuda", generator=gen).bfloat16()
+        gd = torch.sigmoid(torch.randn((dB, dH), device="cuda", generator=gen) + 3.0)
+        ld = torch.nn.functional.softplus(torch.randn((dB, dH), device="cuda", generator=gen)) + 1e-2
+        od = torch.empty_like(vd)
+        for _ in range(5):
+            binding.gka_decode_step(Hs, Us, qd, kd, vd, gd, ld, 10, out=od)
+        torch.cuda.synchronize()
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        d0.record()
+        for _ in range(d_steps):
+            binding.gka_decode_step(Hs, Us, qd, kd, vd, gd, ld, 10, out=od)
+        d1.record()
+        torch.cuda.synchronize()
+        ms_decode = d0.elapsed_time(d1) / d_steps
+        state_bytes = dB * dH * 2 * dd * dd * 4 * 2          # H and U, read and written
+        result["decode"] = {"workload": "cfg5_decode_bf16 (256 seq x 32 heads, d=128, n_iter=10)",
+                            "ms_per_step": ms_decode, "sequence_tokens_per_s": dB / (ms_decode * 1e-3),
+                            "roofline": {"kernel": "decode_step_kernel<IOBF16,128>", "bound": "hbm",
+                                         "achieved": state_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                                         "unit": "GB/s", "frac": state_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS}}
 
     if not args.no_cpu_baseline:
         import oracle
