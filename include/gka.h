@@ -57,7 +57,7 @@ typedef enum { GKA_COMPUTE_F32 = 0, GKA_COMPUTE_BF16 = 1 } gka_compute;
  * o and fro_out). GKA_PHASE_SOLVE alone is valid only on a workspace that still holds the states of a
  * GKA_PHASE_STATES (or GKA_PHASE_ALL) call with the same parameters and inputs; it exists so that
  * callers can overlap the two phases. A single phase can be requested only when the problem is small
- * enough to be processed as one batch of pairs (otherwise GKA_ERR_UNSUPPORTED). */
+ * enough to be processed as one launch of each kernel (otherwise GKA_ERR_UNSUPPORTED). */
 typedef enum { GKA_PHASE_ALL = 0, GKA_PHASE_STATES = 1, GKA_PHASE_SOLVE = 2 } gka_phase;
 
 typedef struct {
@@ -73,14 +73,18 @@ typedef struct {
     int32_t phase;        /* gka_phase; GKA_PHASE_ALL (0) for a complete forward pass          */
     int64_t stride_b;     /* element strides of q, k, v, o between batches, tokens and heads;  */
     int64_t stride_t;     /*   the head dimension is contiguous. 0,0,0 selects the packed      */
-    int64_t stride_h;     /*   [B,T,H,d] layout of the paper's tensors (Appendix D)            */
+    int64_t stride_h;     /*   [B,T,H,d] layout of the paper's tensors (Appendix D). Explicit  */
+                          /*   strides: multiples of 4 elements (of 8 for GKA_COMPUTE_BF16,    */
+                          /*   where stride_t must also stay below 2^23); q, k, v, o 16-byte   */
+                          /*   aligned                                                          */
 } gka_params;
 
 /* Bytes of scratch gka_forward needs for these parameters (0 if they are invalid). The buffer must
  * be 256-byte aligned. It holds the chunk initial states H_[n], U_[n] of Section 4.2.1 in the
- * operand layout of the solve kernel, for one batch of (batch, head) pairs at a time: large problems
- * are processed in batches of pairs so that the workspace stays bounded (about 1 GiB). Its contents
- * after a call are unspecified. */
+ * operand layout of the solve kernel, for one batch of (batch, head) pairs and one slab of consecutive
+ * chunks at a time: large problems are processed as a sequence of such launches, the running states
+ * carried from slab to slab in float32, so that the workspace stays bounded (about 1 GiB). Its
+ * contents after a call are unspecified. */
 size_t gka_forward_workspace_bytes(const gka_params *p);
 
 /* Whole-sequence forward, Eq. (CH).
@@ -107,7 +111,7 @@ gka_status gka_forward(const gka_params *p,
  * given stream. Unlike every other entry point this one creates and destroys events and BLOCKS until the work
  * has finished. It returns the time spent in the chunk-state phase and in the per-chunk solve phase
  * (milliseconds, summed over the launches of this call) and the number of solve-kernel launches the call was
- * split into (pairs are processed in batches, see gka_forward_workspace_bytes). Host pointers:
+ * split into (batches of pairs and slabs of chunks, see gka_forward_workspace_bytes). Host pointers:
  * ms_states, ms_solve, n_solve_launches. */
 gka_status gka_forward_profile(const gka_params *p,
                                const void *q, const void *k, const void *v,

@@ -11,19 +11,22 @@ struct Plan {
     int n_pairs, n_chunks, d;
     bool io_bf16, compute_bf16;
     int64_t stride_b, stride_t, stride_h;
-    size_t off_H, off_U, off_hn, off_seg, off_segdecay, total;
+    size_t off_H, off_U, off_hn, off_seg, off_segdecay, off_carry, total;
     int n_segs, seg_len;
-    int pairs_per_batch;
+    int pairs_per_batch;          // (batch, head) pairs per launch
+    int slab_chunks;              // chunks of every pair per launch
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-constexpr int kStateMinWorkgroups = 256;   // one state-pass workgroup per CU
+constexpr int kStateMinWorkgroups = 512;   // two state-pass workgroups per CU
 constexpr int kStateMaxWalk = 64;          // chunks a state-pass workgroup walks before segments are added
-#ifndef GKA_BATCH_STATE_BYTES
-#define GKA_BATCH_STATE_BYTES (1024u << 20)
+#ifndef GKA_SLAB_STATE_BYTES
+#define GKA_SLAB_STATE_BYTES (1024u << 20)
 #endif
-constexpr size_t kBatchStateBytes = GKA_BATCH_STATE_BYTES;   // chunk states per batch of pairs
+constexpr size_t kSlabStateBytes = GKA_SLAB_STATE_BYTES;   // chunk states one launch pair keeps in the workspace
+constexpr size_t kMaxPairsPerBatch = 1024;
+constexpr size_t kMinSlabChunks = 4;
 
 gka_status check_common(const gka_params *p, bool decode)
 {
@@ -60,18 +63,26 @@ gka_status make_plan(const gka_params *p, Plan *pl)
         if (p->stride_b <= 0 || p->stride_t <= 0 || p->stride_h <= 0) return GKA_ERR_SHAPE;
         if (p->stride_h < p->d_k && p->H > 1) return GKA_ERR_SHAPE;
         if (p->stride_t % 4 || p->stride_h % 4 || p->stride_b % 4) return GKA_ERR_SHAPE;  // vector stores
+        // bf16 operands: k rows are copied 16 bytes at a time, addressed with 32-bit byte offsets within a chunk
+        if (pl->compute_bf16 && (p->stride_t % 8 || p->stride_h % 8 || p->stride_b % 8)) return GKA_ERR_SHAPE;
+        if (pl->compute_bf16 && p->stride_t >= (1 << 23)) return GKA_ERR_UNSUPPORTED;
         pl->stride_b = p->stride_b;
         pl->stride_t = p->stride_t;
         pl->stride_h = p->stride_h;
     }
-    // Pairs are processed in batches that bound the workspace; the workspace is reused per batch.
-    const size_t per_pair = (size_t)pl->n_chunks * (gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16) +
-                                                    gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16));
-    size_t ppb = kBatchStateBytes / per_pair;
-    if (ppb < 1) ppb = 1;
-    if (ppb > (size_t)pl->n_pairs) ppb = pl->n_pairs;
+    // The work is cut into launches of (a batch of pairs) x (a slab of consecutive chunks), slabs in sequence order,
+    // so that the chunk states one launch pair writes and reads (state pass, then solve) fit a bounded workspace,
+    // which every launch pair reuses; the running states are carried between slabs in fp32. (Slabs small enough to
+    // stay in the last-level cache were measured slower than one launch pair: more launches, shorter walks.)
+    const size_t per_chunk = gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16) +
+                             gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16);
+    size_t ppb = pl->n_pairs < kMaxPairsPerBatch ? pl->n_pairs : kMaxPairsPerBatch;
+    size_t slab = kSlabStateBytes / (ppb * per_chunk);
+    if (slab < kMinSlabChunks) slab = kMinSlabChunks;
+    if (slab > (size_t)pl->n_chunks) slab = pl->n_chunks;
     pl->pairs_per_batch = (int)ppb;
-    const size_t nc = ppb * pl->n_chunks;
+    pl->slab_chunks = (int)slab;
+    const size_t nc = ppb * slab;
     pl->off_H = 0;
     pl->off_U = align_up(pl->off_H + nc * gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
     pl->off_hn = align_up(pl->off_U + nc * gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16), 256);
@@ -79,15 +90,17 @@ gka_status make_plan(const gka_params *p, Plan *pl)
     // Segments of the chunk scan. A workgroup walks its chunks one after the other (a few microseconds each), and a
     // segmented pass reads k and v twice, so: one segment unless that leaves CUs idle or makes the walk longer than
     // about 64 chunks; never fewer than two chunks per segment.
-    const int wg_per_seg = pl->pairs_per_batch * (pl->d / 32);
+    const int wg_per_seg = pl->pairs_per_batch * 2 * (pl->d / 32);
     int n_segs = (kStateMinWorkgroups + wg_per_seg - 1) / wg_per_seg;
-    if (n_segs < pl->n_chunks / kStateMaxWalk) n_segs = pl->n_chunks / kStateMaxWalk;
-    if (n_segs > pl->n_chunks / 2) n_segs = pl->n_chunks / 2;
+    if (n_segs < pl->slab_chunks / kStateMaxWalk) n_segs = pl->slab_chunks / kStateMaxWalk;
+    if (n_segs > pl->slab_chunks / 2) n_segs = pl->slab_chunks / 2;
     if (n_segs < 1) n_segs = 1;
-    pl->seg_len = (pl->n_chunks + n_segs - 1) / n_segs;
-    pl->n_segs = (pl->n_chunks + pl->seg_len - 1) / pl->seg_len;
+    pl->seg_len = (pl->slab_chunks + n_segs - 1) / n_segs;
+    pl->n_segs = (pl->slab_chunks + pl->seg_len - 1) / pl->seg_len;
     pl->off_segdecay = align_up(pl->off_seg + (size_t)pl->pairs_per_batch * pl->n_segs * 2 * pl->d * pl->d * sizeof(float), 256);
-    pl->total = align_up(pl->off_segdecay + (size_t)pl->pairs_per_batch * pl->n_segs * sizeof(float), 256);
+    pl->off_carry = align_up(pl->off_segdecay + (size_t)pl->pairs_per_batch * pl->n_segs * sizeof(float), 256);
+    // two ping-pong pairs of fp32 (H, U) carried from slab to slab
+    pl->total = align_up(pl->off_carry + (size_t)4 * pl->pairs_per_batch * pl->d * pl->d * sizeof(float), 256);
     return GKA_OK;
 }
 
@@ -145,7 +158,6 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     sa.ws_H = ws + pl.off_H; sa.ws_U = ws + pl.off_U; sa.ws_hn = (float *)(ws + pl.off_hn);
     sa.stride_b = pl.stride_b; sa.stride_t = pl.stride_t; sa.stride_h = pl.stride_h;
     sa.H = p->H; sa.T = p->T;
-    sa.n_chunks_total = pl.n_chunks;
     sa.n_segs = pl.n_segs; sa.seg_len = pl.seg_len;
     sa.seg_buf = (float *)(ws + pl.off_seg); sa.seg_logdecay = (float *)(ws + pl.off_segdecay);
     sa.init_mode = 0; sa.final_mode = 0; sa.write_frags = 1;
@@ -153,23 +165,41 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     so.q = q; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
     so.ws_H = sa.ws_H; so.ws_U = sa.ws_U; so.ws_hn = sa.ws_hn;
     so.stride_b = pl.stride_b; so.stride_t = pl.stride_t; so.stride_h = pl.stride_h;
-    so.H = p->H; so.T = p->T; so.n_chunks_total = pl.n_chunks; so.n_iter = p->n_iter;
-    const bool one_batch = pl.pairs_per_batch >= pl.n_pairs;
-    // With a single phase requested the workspace must cover every pair: only possible when all pairs fit one batch.
-    if (p->phase != GKA_PHASE_ALL && !one_batch) return GKA_ERR_UNSUPPORTED;
+    so.H = p->H; so.T = p->T; so.n_iter = p->n_iter;
+    const bool one_launch = pl.pairs_per_batch >= pl.n_pairs && pl.slab_chunks >= pl.n_chunks;
+    // With a single phase requested the workspace must cover the whole problem.
+    if (p->phase != GKA_PHASE_ALL && !one_launch) return GKA_ERR_UNSUPPORTED;
+    const size_t state_elems = (size_t)pl.pairs_per_batch * pl.d * pl.d;
+    float *carry = (float *)(ws + pl.off_carry);               // [2][2][pairs_per_batch, d, d]
     for (int pair0 = 0; pair0 < pl.n_pairs; pair0 += pl.pairs_per_batch) {
         const int np = pl.n_pairs - pair0 < pl.pairs_per_batch ? pl.n_pairs - pair0 : pl.pairs_per_batch;
-        sa.pair0 = pair0;
-        so.pair0 = pair0;
-        if (prof) prof->mark(stream);
-        if (p->phase != GKA_PHASE_SOLVE &&
-            gka::launch_state_pass(sa, np, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
-            return GKA_ERR_LAUNCH;
-        if (prof) prof->mark(stream);
-        if (p->phase != GKA_PHASE_STATES &&
-            gka::launch_chunk_solve(so, np, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
-            return GKA_ERR_LAUNCH;
-        if (prof) prof->mark(stream);
+        int slab_index = 0;
+        for (int chunk0 = 0; chunk0 < pl.n_chunks; chunk0 += pl.slab_chunks, ++slab_index) {
+            const int nch = pl.n_chunks - chunk0 < pl.slab_chunks ? pl.n_chunks - chunk0 : pl.slab_chunks;
+            const bool first = chunk0 == 0, last = chunk0 + nch >= pl.n_chunks;
+            sa.pair0 = so.pair0 = pair0;
+            sa.chunk0 = so.chunk0 = chunk0;
+            sa.n_chunks = so.n_chunks = nch;
+            // states enter from the caller (first slab) or from the previous slab, and leave to the next slab or to
+            // the caller (last slab)
+            float *in = carry + (size_t)((slab_index + 1) & 1) * 2 * state_elems;
+            float *out = carry + (size_t)(slab_index & 1) * 2 * state_elems;
+            sa.H_init = first ? H_init : in;
+            sa.U_init = first ? U_init : in + state_elems;
+            sa.init_pair0 = first ? pair0 : 0;
+            sa.H_final = last ? H_final : out;
+            sa.U_final = last ? U_final : out + state_elems;
+            sa.final_pair0 = last ? pair0 : 0;
+            if (prof) prof->mark(stream);
+            if (p->phase != GKA_PHASE_SOLVE &&
+                gka::launch_state_pass(sa, np, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
+                return GKA_ERR_LAUNCH;
+            if (prof) prof->mark(stream);
+            if (p->phase != GKA_PHASE_STATES &&
+                gka::launch_chunk_solve(so, np, pl.d, pl.io_bf16, pl.compute_bf16, stream) != hipSuccess)
+                return GKA_ERR_LAUNCH;
+            if (prof) prof->mark(stream);
+        }
     }
     return GKA_OK;
 }

@@ -267,9 +267,10 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     // Consecutive workgroups take the same chunk index of consecutive (batch, head) pairs: in the [B,T,H,d]
     // layout the heads of a token are adjacent, so workgroups that run together read adjacent memory.
     const int pair = blockIdx.x % a.n_pairs;
-    const int chunk = blockIdx.x / a.n_pairs;
+    const int chunk_local = blockIdx.x / a.n_pairs;
+    const int chunk = a.chunk0 + chunk_local;
     const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
-    const int64_t chunk_id = (int64_t)pair * a.n_chunks_total + chunk;    // workspace index within this launch
+    const int64_t chunk_id = (int64_t)chunk_local * a.n_pairs + pair;     // workspace index within this launch
     const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
     const int64_t gate_base = (int64_t)b * a.T * a.H + h;
     const int tok0 = chunk * kChunk;
@@ -300,7 +301,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int i = 0; i < NB * NB; ++i) hn[i] = a.ws_hn[chunk_id * (NB * NB) + i];
         krows.store(sRow, tok0, a.T, tid);
-        __syncthreads();
+        lds_barrier();
         GKA_TSTAMP(1);
         build_row_frags<MMA, D>(sK, sRow, w, lane);
         build_transposed_frags<MMA, D>(sKT, sRow, w, lane);
@@ -321,12 +322,12 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int j = 32 * jt + kidx(r, g);
-            const float Gj = __shfl(Gall, j, 64);
+            const float Gj = g ? lane_value(Gall, 32 * jt + kidx(r, 1)) : lane_value(Gall, 32 * jt + kidx(r, 0));
             mreg[jt][r] = (j <= c_local) ? exp2f(Gc - Gj) : 0.0f;
         }
     GKA_TSTAMP(3);
     wait_all_memory();                         // H_[n] has landed in LDS
-    __syncthreads();                           // fragments and H_[n] visible; the staging tile is free
+    lds_barrier();                           // fragments and H_[n] visible; the staging tile is free
     GKA_TSTAMP(4);
 
     GKA_TSTAMP(5);
@@ -376,11 +377,11 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
             }
         b_part += __shfl_xor(b_part, 32, 64);
         d_part += __shfl_xor(d_part, 32, 64);
-        __syncthreads();
+        lds_barrier();
         if (fh == 0 && g == 0)
             sW[c_local] = 2.0f * (zeta * (sA[c_local] + sA[kChunk + c_local]) + b_part) + d_part;
     }
-    __syncthreads();
+    lds_barrier();
     float fro;
     {
         float f_part = 0.0f;
@@ -421,19 +422,19 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     }
     const frag *myX = sX + (TW * NSTEPS) * 64;         // this token block's operand in the exchange region
     float omega = 2.0f;
-    __syncthreads();                           // sW, sA are dead: the region becomes the operand exchange
+    lds_barrier();                           // sW, sA are dead: the region becomes the operand exchange
     for (int it = 0; it < a.n_iter; ++it) {
         // operands are re-read from LDS in every pass (they are not kept in registers across passes)
         asm volatile("" ::: "memory");
         publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
-        __syncthreads();
+        lds_barrier();
         // two sweeps over the D features of delta: P = K delta^T (key blocks jt <= TW), then the state product
         f32x16 pacc[NJ];
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt) pacc[jt] = zero16();
         fused_gemm<MMA, NSTEPS, NJ>(Kset, myX, pacc, lane);
         fused_gemm<MMA, NSTEPS, NBH>(Hset, myX, gS, lane);
-        __syncthreads();                       // the exchange region may be overwritten from here on
+        lds_barrier();                       // the exchange region may be overwritten from here on
         frag pm[NJ][HS];
         mask_p<MMA, TW>(pacc, mreg, pm);
         gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, gI, lane);
@@ -472,31 +473,31 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
                 ownlo[i][hh] = MMA::pack(lo);
             }
         }
-    __syncthreads();                           // every wave is done with H_[n], K^T and the exchange region
+    lds_barrier();                           // every wave is done with H_[n], K^T and the exchange region
     GKA_TSTAMP(8);
     async_block_copy<H16>(sH, Uw, w, lane);    // U_[n] (rounded part) replaces H_[n]
     vrows.store(sRow, tok0, a.T, tid);
-    __syncthreads();
+    lds_barrier();
     build_transposed_frags<MMA, D>(sKT, sRow, w, lane);      // V^T replaces K^T
-    __syncthreads();                           // the staging tile becomes the exchange region again
+    lds_barrier();                           // the staging tile becomes the exchange region again
     GKA_TSTAMP(9);
     publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
     wait_all_memory();
-    __syncthreads();
+    lds_barrier();
     f32x16 acc[NJ + NBH];
 #pragma unroll
     for (int x = 0; x < NJ + NBH; ++x) acc[x] = zero16();
     fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);          // K xhat^T and U xhat
     if (NSPL == 2) {
-        __syncthreads();
+        lds_barrier();
         publish_operand<MMA, NB>(sX, ownlo, TW, mt0, lane);
-        __syncthreads();
+        lds_barrier();
         fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);      // the same on the remainder of xhat
-        __syncthreads();
+        lds_barrier();
         async_block_copy<H16>(sH, Uw + SH::H_FRAGS * 64, w, lane);    // remainder of U_[n]
         publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
         wait_all_memory();
-        __syncthreads();
+        lds_barrier();
         f32x16 accU[NBH];
 #pragma unroll
         for (int i = 0; i < NBH; ++i) accU[i] = acc[NJ + i];
@@ -577,7 +578,7 @@ static hipError_t launch_chunk_solve_t(const SolveArgs &a, int n_pairs, hipStrea
     if (e != hipSuccess) return e;
     SolveArgs args = a;
     args.n_pairs = n_pairs;
-    dim3 grid((unsigned)(n_pairs * a.n_chunks_total)), block(kSolveThreads);
+    dim3 grid((unsigned)(n_pairs * a.n_chunks)), block(kSolveThreads);
 #ifdef GKA_DEBUG_LDS_PAD
     const size_t lds = SH::lds_bytes + GKA_DEBUG_LDS_PAD;
     (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

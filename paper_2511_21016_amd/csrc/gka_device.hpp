@@ -12,6 +12,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "gka_kernels.hpp"
 
 namespace gka {
@@ -148,6 +150,14 @@ __device__ __forceinline__ void async_copy16_to_lds(void *lds_wave_base, const v
 }
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
+// Workgroup barrier that orders LDS traffic only: this wave's LDS operations have completed (lgkmcnt(0)), then
+// s_barrier. Unlike __syncthreads() it carries no global-memory fence, so vector-memory loads that are still in
+// flight (prefetches for later steps) are not waited for.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // ---- arithmetic of the matrix products ------------------------------------------------------
 // VEC = operand elements per lane per MFMA; HS = MFMA steps per 32-block of the contraction.
 struct MmaBF16 {
@@ -221,15 +231,29 @@ __device__ __forceinline__ f32x16 zero16()
     return z;
 }
 
-// Inclusive prefix sum over the 64 lanes of a wave.
-__device__ __forceinline__ float wave_inclusive_scan(float x, int lane)
+// Inclusive prefix sum over the 64 lanes of a wave with DPP moves: shifts by 1, 2, 4, 8 inside each row of 16
+// lanes (lanes shifted in from outside the row contribute 0), then the last lane of row 0 / row 2 is broadcast into
+// row 1 / row 3, then lane 31 into rows 2 and 3.
+__device__ __forceinline__ float wave_inclusive_scan(float x, int /*lane*/)
 {
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        float y = __shfl_up(x, off, 64);
-        if (lane >= off) x += y;
-    }
+    auto dpp_add = [](float v, auto ctrl, auto row_mask) {
+        const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(ctrl)::value,
+                                                      decltype(row_mask)::value, 0xf, false);
+        return v + __int_as_float(moved);
+    };
+    x = dpp_add(x, std::integral_constant<int, 0x111>{}, std::integral_constant<int, 0xf>{});   // row_shr:1
+    x = dpp_add(x, std::integral_constant<int, 0x112>{}, std::integral_constant<int, 0xf>{});   // row_shr:2
+    x = dpp_add(x, std::integral_constant<int, 0x114>{}, std::integral_constant<int, 0xf>{});   // row_shr:4
+    x = dpp_add(x, std::integral_constant<int, 0x118>{}, std::integral_constant<int, 0xf>{});   // row_shr:8
+    x = dpp_add(x, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});   // row_bcast:15 -> rows 1, 3
+    x = dpp_add(x, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});   // row_bcast:31 -> rows 2, 3
     return x;
+}
+
+// Value of x on a lane known at compile time or wave-uniform (no LDS crossbar involved).
+__device__ __forceinline__ float lane_value(float x, int src_lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), src_lane));
 }
 
 __device__ __forceinline__ float wave_sum(float x)

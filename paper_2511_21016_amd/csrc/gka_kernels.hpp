@@ -17,7 +17,9 @@ struct StatePassArgs {
     int64_t stride_b, stride_t, stride_h;
     int H, T;
     int pair0;                    // first (batch, head) pair of this launch; workspace is indexed from 0
-    int n_chunks_total;           // chunks per pair
+    int chunk0, n_chunks;         // this launch covers chunks chunk0 .. chunk0 + n_chunks - 1 of every pair;
+                                  // the workspace is indexed from 0 in both pairs and chunks
+    int init_pair0, final_pair0;  // pair index of element 0 of H_init/U_init and of H_final/U_final
     int n_segs, seg_len;          // segments per pair and chunks per segment (n_segs <= 1: one pass)
     int n_pairs;                  // pairs of this launch (set by the launcher)
     float *seg_buf;               // [pairs, n_segs, 2, d*d] segment summaries / start states
@@ -36,7 +38,8 @@ struct SolveArgs {
     const void *ws_H, *ws_U;
     const float *ws_hn;
     int64_t stride_b, stride_t, stride_h;
-    int H, T, n_chunks_total, n_iter;
+    int H, T, n_iter;
+    int chunk0, n_chunks;         // chunks of every pair covered by this launch (workspace indexed from 0)
     int n_pairs;                  // pairs of this launch (set by the launcher)
     int pair0;                    // first (batch, head) pair of this launch; workspace is indexed from 0
 };

@@ -1,14 +1,17 @@
 // Chunk initial states of Section 4.2.1: H_[n], U_[n] for every chunk of every (batch, head) pair.
 //
-// One workgroup owns a 32-wide slab of both states of one pair: H0[32*rb .. +32][:] and
+// One workgroup owns a 32-wide slab of ONE of the two states of one pair, H0[32*rb .. +32][:] or
 // U0[32*rb .. +32][:], held as fp32 MFMA accumulators (wave w owns columns 32*w .. +32 of the slab),
 // and walks a contiguous run of the pair's chunks in order. Per chunk it
 //   1. (if asked) writes the slab, as it stands before the chunk, to the workspace in the fragment order
-//      the solve kernel consumes, plus the slab's contribution to ||H_[n]||_F^2,
+//      the solve kernel consumes (H: bf16 or fp32 operands plus the slab's share of ||H_[n]||_F^2; U: the operand
+//      and, for bf16, what the rounding left over as a second operand),
 //   2. applies the chunk: S <- zeta_C S + sum_j (zeta_C / zeta_j) a_j k_j^T  (a = k for H, a = v for U),
-//      the decay weights built in log space (Appendix B.2), as one MFMA contraction over the
-//      chunk's tokens. The chunk's k rows and the slab's v columns are staged row-major in LDS and read
-//      back transposed as MFMA operands; the next chunk's rows are fetched while the current one is used.
+//      the decay weights built in log space (Appendix B.2), as one MFMA contraction over the chunk's tokens.
+// Two bodies implement the walk. The generic one (fp32 operands) stages the k rows and the slab's columns of a,
+// each scaled by the square root of the weight, through registers into padded LDS tiles. The bf16 one copies the k
+// rows from global memory straight into LDS two chunks ahead and puts the whole weight on the small a tile; see
+// state_pass_body_bf16.
 //
 // The recurrence over chunks is an affine scan, S_[n+1] = zeta^(n) S_[n] + Delta_n. Long sequences are cut
 // into segments: a first launch reduces every segment to (prod zeta, Delta) from a zero state; a second launch
@@ -23,8 +26,8 @@ namespace gka {
 __device__ unsigned long long g_dbg_state_timers[64 * 16];
 #define GKA_STSTAMP(i)                                                                          \
     do {                                                                                        \
-        if (threadIdx.x == 0 && blockIdx.x >= 1024 && blockIdx.x < 1088)                         \
-            g_dbg_state_timers[(blockIdx.x - 1024) * 16 + (i)] = __builtin_amdgcn_s_memtime();  \
+        if (threadIdx.x == 0 && blockIdx.x >= 128 && blockIdx.x < 192)                         \
+            g_dbg_state_timers[(blockIdx.x - 128) * 16 + (i)] = __builtin_amdgcn_s_memtime();  \
     } while (0)
 extern "C" int gka_debug_read_state_timers(unsigned long long *host)
 {
@@ -38,8 +41,58 @@ extern "C" int gka_debug_read_state_timers(unsigned long long *host)
 #define GKA_STATE_WAVES 2          // waves per SIMD the state-pass kernel is compiled for (register cap)
 #endif
 
-template <class MMA, class IO, int D>
-__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE_WAVES))) void state_pass_kernel(StatePassArgs a)
+// Start state of a workgroup's slab: the caller's initial state scanned with the summaries (decay, Delta) of the
+// segments before this one. Accumulator element (r, lane (n, g)) = S0[32*rb + n][32*w + kidx(r, g)].
+template <int D>
+__device__ __forceinline__ float *segment_tile(const StatePassArgs &a, int pair, int sg, int rb, int w)
+{
+    constexpr int NB = D / 32;
+    return a.seg_buf + ((((int64_t)(pair * a.n_segs + sg) * NB + rb) * NB + w) * 2) * 1024;
+}
+template <int D, bool DOH>
+__device__ __forceinline__ void load_start_state(const StatePassArgs &a, f32x16 &acc, int pair, int seg, int rb, int w,
+                                                 int lane)
+{
+    if (a.init_mode == 0) return;
+    const int n = lane & 31, g = lane >> 5;
+    if (a.H_init) {
+        const float *Si = (DOH ? a.H_init : a.U_init) + (int64_t)(a.init_pair0 + pair) * D * D;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = Si[(int64_t)(32 * rb + n) * D + 32 * w + kidx(r, g)];
+    }
+    for (int sg = 0; sg < seg; ++sg) {
+        const float *t = segment_tile<D>(a, pair, sg, rb, w) + (DOH ? 0 : 1024);
+        const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = decay * acc[r] + t[r * 64 + lane];
+    }
+}
+// End of the walk: the final state (last segment of the full pass) or this segment's summary.
+template <int D, bool DOH>
+__device__ __forceinline__ void store_end_state(const StatePassArgs &a, const f32x16 &acc, float Gseg, int pair, int seg,
+                                                int rb, int w, int lane)
+{
+    const int n = lane & 31, g = lane >> 5;
+    if (a.final_mode == 1) {
+        if (a.H_final && seg == a.n_segs - 1) {
+            float *Sf = (DOH ? a.H_final : a.U_final) + (int64_t)(a.final_pair0 + pair) * D * D;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Sf[(int64_t)(32 * rb + n) * D + 32 * w + kidx(r, g)] = acc[r];
+        }
+    } else if (a.final_mode == 2) {
+        float *t = segment_tile<D>(a, pair, seg, rb, w) + (DOH ? 0 : 1024);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t[r * 64 + lane] = acc[r];
+        if (rb == 0 && DOH && threadIdx.x == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
+    }
+}
+
+// DOH: this workgroup owns the H slab (else the U slab); WRITE: chunk states are written to the workspace. Both are
+// compile-time so that the chunk loop is straight-line code and the in-flight prefetches are never drained by a
+// conservative wait.
+template <class MMA, class IO, int D, bool DOH, bool WRITE>
+__device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, int group,
+                                                typename MMA::elem_t *s_k, typename MMA::elem_t *s_v)
 {
     constexpr int NB = D / 32;
     constexpr int VEC = MMA::VEC;
@@ -55,63 +108,41 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int w = tid >> 6;                       // column block of the slab owned by this wave
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // column block of the slab owned by this wave (uniform)
     const int n = lane & 31, g = lane >> 5;
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2. The NB slabs of one (pair, segment)
-    // read the same k rows, so they are given block indices that are equal modulo 8.
-    int rb, group;
-    {
-        const int id = blockIdx.x;
-        const int full = (gridDim.x / (8 * NB)) * (8 * NB);
-        if (id < full) {
-            const int within = id % (8 * NB);
-            rb = within / 8;                       // slab index (row block of H0 / U0)
-            group = (id / (8 * NB)) * 8 + within % 8;
-        } else {
-            rb = (id - full) % NB;
-            group = full / NB + (id - full) / NB;
-        }
-    }
+    constexpr bool doH = DOH;
     // pairs vary fastest: workgroups that run together then read adjacent memory ([B,T,H,d]: heads are adjacent)
     const int pair = group % a.n_pairs;           // within this launch; indexes the workspace
     const int seg = group / a.n_pairs;
     const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
 
     // Both operands of S += sum_j w_j a_j k_j^T carry sqrt(w_j): (sqrt(w_j) a_j)(sqrt(w_j) k_j)^T.
-    __shared__ __attribute__((aligned(16))) elem_t s_k[kChunk * RS];    // k rows of the chunk, scaled
-    __shared__ __attribute__((aligned(16))) elem_t s_v[kChunk * RSV];   // the slab's 32 columns of the v rows, scaled
+    // s_k: k rows of the chunk, scaled; s_v: the slab's 32 columns of the v rows, scaled.
 
     const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
     const int64_t gate_base = (int64_t)b * a.T * a.H + h;
-    const int chunk_begin = seg * a.seg_len;
-    const int chunk_end = min(chunk_begin + a.seg_len, a.n_chunks_total);
+    const int chunk_begin = a.chunk0 + seg * a.seg_len;
+    const int chunk_end = min(chunk_begin + a.seg_len, a.chunk0 + a.n_chunks);
     // per (pair, segment, slab, wave): two 16x64 float tiles in accumulator order
     auto seg_tile = [&](int sg) {
         return a.seg_buf + ((((int64_t)(pair * a.n_segs + sg) * NB + rb) * NB + w) * 2) * 1024;
     };
 
     // accumulators: element (row = 32*w + kidx(r,g), col n) = S0[32*rb + n][32*w + kidx(r,g)]
-    f32x16 accH = zero16(), accU = zero16();
+    f32x16 acc = zero16();                        // this workgroup's state: H (doH) or U
+    const int tile_off = doH ? 0 : 1024;
     if (a.init_mode != 0) {
         if (a.H_init) {
-            const float *Hi = a.H_init + (int64_t)(a.pair0 + pair) * D * D;
-            const float *Ui = a.U_init + (int64_t)(a.pair0 + pair) * D * D;
+            const float *Si = (doH ? a.H_init : a.U_init) + (int64_t)(a.init_pair0 + pair) * D * D;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int col = 32 * w + kidx(r, g);
-                accH[r] = Hi[(int64_t)(32 * rb + n) * D + col];
-                accU[r] = Ui[(int64_t)(32 * rb + n) * D + col];
-            }
+            for (int r = 0; r < 16; ++r) acc[r] = Si[(int64_t)(32 * rb + n) * D + 32 * w + kidx(r, g)];
         }
         // start state of this segment: scan of the summaries (decay, Delta) of the segments before it
         for (int sg = 0; sg < seg; ++sg) {
             const float *t = seg_tile(sg);
             const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                accH[r] = decay * accH[r] + t[r * 64 + lane];
-                accU[r] = decay * accU[r] + t[1024 + r * 64 + lane];
-            }
+            for (int r = 0; r < 16; ++r) acc[r] = decay * acc[r] + t[tile_off + r * 64 + lane];
         }
     }
 
@@ -129,12 +160,14 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
             const int t = min(c * kChunk + row, a.T - 1);
             f.k[i] = IO::load_raw4(a.k, base_bh + (int64_t)t * a.stride_t + 4 * c4);
         }
+        if (!doH) {
 #pragma unroll
-        for (int i = 0; i < VP; ++i) {
-            const int piece = i * NT + tid;
-            const int row = piece / 8, c4 = piece % 8;
-            const int t = min(c * kChunk + row, a.T - 1);
-            f.v[i] = IO::load_raw4(a.v, base_bh + (int64_t)t * a.stride_t + 32 * rb + 4 * c4);
+            for (int i = 0; i < VP; ++i) {
+                const int piece = i * NT + tid;
+                const int row = piece / 8, c4 = piece % 8;
+                const int t = min(c * kChunk + row, a.T - 1);
+                f.v[i] = IO::load_raw4(a.v, base_bh + (int64_t)t * a.stride_t + 32 * rb + 4 * c4);
+            }
         }
         const int t = min(c * kChunk + lane, a.T - 1);
         f.gate = a.gate[gate_base + (int64_t)t * a.H];
@@ -142,16 +175,16 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
     float Gseg = 0.0f;
 
     auto process = [&](const Fetch &f, int c) {
-        const bool stamp = (c == chunk_begin + 2);
+        const bool stamp = (c == chunk_begin + 20);
         if (stamp) GKA_STSTAMP(1);
         // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights 2^(G_C - G_j)
         const float lg = (c * kChunk + lane < a.T) ? log2_gate(f.gate) : 0.0f;
         const float G = wave_inclusive_scan(lg, lane);
-        const float Gtot = __shfl(G, 63, 64);
+        const float Gtot = lane_value(G, 63);
         Gseg += Gtot;
         const float swd = exp2f(0.5f * (Gtot - G));   // lane j: sqrt(zeta_C / zeta_j)
         if (stamp) GKA_STSTAMP(2);
-        __syncthreads();                          // previous chunk's LDS readers are done
+        lds_barrier();                          // previous chunk's LDS readers are done
         if (stamp) GKA_STSTAMP(3);
 #pragma unroll
         for (int i = 0; i < KP; ++i) {
@@ -159,116 +192,435 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
             const int row = piece / (D / 4);
             f32x4 kv = IO::cvt4(f.k[i]);
             if (c * kChunk + row >= a.T) kv = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            MMA::store4(s_k + row * RS + 4 * (piece % (D / 4)), kv * __shfl(swd, row, 64));
+            // the wave's 64 pieces of this sweep lie in two consecutive rows
+            const int row0 = (i * NT + 64 * w) / (D / 4);
+            const float sw = (D / 4 == 32) ? ((lane < 32) ? lane_value(swd, row0) : lane_value(swd, row0 + 1))
+                                           : __shfl(swd, row, 64);
+            MMA::store4(s_k + row * RS + 4 * (piece % (D / 4)), kv * sw);
         }
+        if (!doH) {
 #pragma unroll
-        for (int i = 0; i < VP; ++i) {
-            const int piece = i * NT + tid;
-            const int row = piece / 8;
-            f32x4 vv = IO::cvt4(f.v[i]);
-            if (c * kChunk + row >= a.T) vv = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            MMA::store4(s_v + row * RSV + 4 * (piece % 8), vv * __shfl(swd, row, 64));
+            for (int i = 0; i < VP; ++i) {
+                const int piece = i * NT + tid;
+                const int row = piece / 8;
+                f32x4 vv = IO::cvt4(f.v[i]);
+                if (c * kChunk + row >= a.T) vv = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                MMA::store4(s_v + row * RSV + 4 * (piece % 8), vv * __shfl(swd, row, 64));
+            }
         }
         const float zetaC = exp2f(Gtot);
         if (stamp) GKA_STSTAMP(4);
 
         // ---- write the state before the chunk, fragment order
-        if (a.write_frags) {
-            const int64_t chunk_id = (int64_t)pair * a.n_chunks_total + c;
-            frag *Hw = (frag *)a.ws_H + chunk_id * (NB * NB * HS * 64);
+        if (WRITE) {
+            const int64_t chunk_id = (int64_t)(c - a.chunk0) * a.n_pairs + pair;   // chunk-major: pairs adjacent
             float vals[16];
-            float ss = 0.0f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) { vals[r] = accH[r]; ss += accH[r] * accH[r]; }
+            for (int r = 0; r < 16; ++r) vals[r] = acc[r];
+            if (doH) {
+                frag *Hw = (frag *)a.ws_H + chunk_id * (NB * NB * HS * 64);
+                float ss = 0.0f;
 #pragma unroll
-            for (int hh = 0; hh < HS; ++hh)
-                Hw[((rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(vals + hh * VEC);
-            ss = wave_sum(ss);
-            if (lane == 0) a.ws_hn[chunk_id * (NB * NB) + rb * NB + w] = ss;
-
-            constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
-            frag *Uw = (frag *)a.ws_U + chunk_id * (NSPL * NB * NB * HS * 64);
-            float lo[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) vals[r] = accU[r];
-#pragma unroll
-            for (int hh = 0; hh < HS; ++hh) {
-                frag fr = MMA::pack(vals + hh * VEC);
-                Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
-                if (NSPL == 2) {
-#pragma unroll
-                    for (int p = 0; p < VEC; ++p) lo[hh * VEC + p] = vals[hh * VEC + p] - MMA::elem(fr, p);
-                }
-            }
-            if (NSPL == 2) {
+                for (int r = 0; r < 16; ++r) ss += acc[r] * acc[r];
 #pragma unroll
                 for (int hh = 0; hh < HS; ++hh)
-                    Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(lo + hh * VEC);
+                    Hw[((rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(vals + hh * VEC);
+                ss = wave_sum(ss);
+                if (lane == 0) a.ws_hn[chunk_id * (NB * NB) + rb * NB + w] = ss;
+            } else {
+                constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
+                frag *Uw = (frag *)a.ws_U + chunk_id * (NSPL * NB * NB * HS * 64);
+                float lo[16];
+#pragma unroll
+                for (int hh = 0; hh < HS; ++hh) {
+                    frag fr = MMA::pack(vals + hh * VEC);
+                    Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
+                    if (NSPL == 2) {
+#pragma unroll
+                        for (int p = 0; p < VEC; ++p) lo[hh * VEC + p] = vals[hh * VEC + p] - MMA::elem(fr, p);
+                    }
+                }
+                if (NSPL == 2) {
+#pragma unroll
+                    for (int hh = 0; hh < HS; ++hh)
+                        Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(lo + hh * VEC);
+                }
             }
         }
         if (stamp) GKA_STSTAMP(5);
-        __syncthreads();                          // s_k, s_v visible
+        lds_barrier();                          // s_k, s_v visible
         if (stamp) GKA_STSTAMP(6);
 
         // ---- S <- zeta_C S + sum_j w_j a_j k_j^T
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { accH[r] *= zetaC; accU[r] *= zetaC; }
+        for (int r = 0; r < 16; ++r) acc[r] *= zetaC;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) {
             // lane (n, g): tokens j = s*2*VEC + g*VEC + p of the chunk
             const int j0 = s * 2 * VEC + g * VEC;
-            frag fa, fk, fv;
+            // B operand: the slab's columns of the scaled k rows (H) or of the scaled v rows (U)
+            const elem_t *bt = doH ? s_k : s_v;
+            const PaddedRows bl{doH ? RS : RSV};
+            const int bcol = doH ? 32 * rb : 0;
+            frag fa, fb;
             if constexpr (MMA::VEC == 8) {
                 const int sub = 16 * ((lane >> 4) & 1);      // this 16-lane block's columns within the 32
                 fa = gather_transposed_bf16(s_k, PaddedRows{RS}, 32 * w + sub, lane, j0, j0 + 4);
-                fk = gather_transposed_bf16(s_k, PaddedRows{RS}, 32 * rb + sub, lane, j0, j0 + 4);
-                fv = gather_transposed_bf16(s_v, PaddedRows{RSV}, sub, lane, j0, j0 + 4);
+                fb = gather_transposed_bf16(bt, bl, bcol + sub, lane, j0, j0 + 4);
             } else {
                 auto tok_of = [&](int p) { return j0 + p; };
                 fa = gather_transposed<MMA>(s_k, PaddedRows{RS}, 32 * w + n, tok_of);
-                fk = gather_transposed<MMA>(s_k, PaddedRows{RS}, 32 * rb + n, tok_of);
-                fv = gather_transposed<MMA>(s_v, PaddedRows{RSV}, n, tok_of);
+                fb = gather_transposed<MMA>(bt, bl, bcol + n, tok_of);
             }
-            accH = MMA::mma(fa, fk, accH);
-            accU = MMA::mma(fa, fv, accU);
+            acc = MMA::mma(fa, fb, acc);
         }
         if (stamp) GKA_STSTAMP(7);
     };
 
     // two fetch buffers in flight: while chunk c is processed, chunks c + 1 and c + 2 are on their way
-    Fetch f0, f1;
+    // (fetches past the end of the run re-read its last chunk: harmless, and it keeps the loop free of branches
+    // around memory operations)
+    // An odd chunk count is evened out in front of the loop, with a fetch of its own, so that the loop body is the
+    // only user of the two prefetch buffers.
     GKA_STSTAMP(0);
-    if (chunk_begin < chunk_end) fetch(f0, chunk_begin);
-    if (chunk_begin + 1 < chunk_end) fetch(f1, chunk_begin + 1);
-    for (int c = chunk_begin; c < chunk_end; c += 2) {
-        process(f0, c);
-        if (c + 2 < chunk_end) fetch(f0, c + 2);
-        if (c + 1 < chunk_end) {
+    const int c_last = max(chunk_end - 1, chunk_begin);
+    int c = chunk_begin;
+    if ((chunk_end - chunk_begin) & 1) {
+        Fetch fp;
+        fetch(fp, c);
+        process(fp, c);
+        ++c;
+    }
+    if (c < chunk_end) {
+        Fetch f0, f1;
+        fetch(f0, c);
+        fetch(f1, c + 1);
+        for (; c < chunk_end; c += 2) {
+            process(f0, c);
+            fetch(f0, min(c + 2, c_last));
             process(f1, c + 1);
-            if (c + 3 < chunk_end) fetch(f1, c + 3);
+            fetch(f1, min(c + 3, c_last));
         }
     }
 
     GKA_STSTAMP(8);
     if (a.final_mode == 1) {
         if (a.H_final && seg == a.n_segs - 1) {
-            float *Hf = a.H_final + (int64_t)(a.pair0 + pair) * D * D;
-            float *Uf = a.U_final + (int64_t)(a.pair0 + pair) * D * D;
+            float *Sf = (doH ? a.H_final : a.U_final) + (int64_t)(a.final_pair0 + pair) * D * D;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int col = 32 * w + kidx(r, g);
-                Hf[(int64_t)(32 * rb + n) * D + col] = accH[r];
-                Uf[(int64_t)(32 * rb + n) * D + col] = accU[r];
-            }
+            for (int r = 0; r < 16; ++r) Sf[(int64_t)(32 * rb + n) * D + 32 * w + kidx(r, g)] = acc[r];
         }
     } else if (a.final_mode == 2) {
         float *t = seg_tile(seg);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            t[r * 64 + lane] = accH[r];
-            t[1024 + r * 64 + lane] = accU[r];
+        for (int r = 0; r < 16; ++r) t[tile_off + r * 64 + lane] = acc[r];
+        if (rb == 0 && doH && tid == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
+    }
+}
+
+// vmcnt(n) wait with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4,
+// lgkmcnt 11:8). The compiler moves no memory operation across it.
+template <int N>
+__device__ __forceinline__ void wait_vector_memory_upto()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt %0" ::"n"((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8)) : "memory");
+}
+// Everything this wave has issued to vector memory has completed. The intrinsic tells the compiler's own wait
+// bookkeeping so (it does not look inside assembly statements); the assembly statement keeps memory operations
+// from moving across.
+__device__ __forceinline__ void drain_vector_memory()
+{
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));
+    asm volatile("" ::: "memory");
+}
+
+// The eight operand fragments of one chunk update (4 MFMA steps x A, B) as sixteen transpose reads in one block
+// that ends with the wait for them. Written as assembly so that the compiler does not tie these reads to the
+// copies into LDS that are in flight for later chunks (it would wait for those as well). ka0 / ka1: byte
+// addresses in the k tile of this lane's place for token runs j and j + 4 of step 0 (later steps are 16 rows
+// further: a constant offset, the swizzle repeats every 8 rows); kb0: the same in the B tile, whose padded rows
+// make both the run and the step a constant offset.
+#define GKA_TR_READ(dst, addr, off) "ds_read_b64_tr_b16 %" #dst ", %" #addr " offset:" #off "\n\t"
+#define GKA_GATHER_CHUNK(A1, A2, A3)                                                                         \
+    asm volatile(GKA_TR_READ(0, 16, 0) GKA_TR_READ(1, 17, 0) GKA_TR_READ(2, 18, 0) GKA_TR_READ(3, 18, 384)   \
+                 GKA_TR_READ(4, 16, A1) GKA_TR_READ(5, 17, A1) GKA_TR_READ(6, 18, 1536) GKA_TR_READ(7, 18, 1920) \
+                 GKA_TR_READ(8, 16, A2) GKA_TR_READ(9, 17, A2) GKA_TR_READ(10, 18, 3072) GKA_TR_READ(11, 18, 3456) \
+                 GKA_TR_READ(12, 16, A3) GKA_TR_READ(13, 17, A3) GKA_TR_READ(14, 18, 4608) GKA_TR_READ(15, 18, 4992) \
+                 "s_waitcnt lgkmcnt(0)"                                                                       \
+                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]),   \
+                   "=&v"(r[7]), "=&v"(r[8]), "=&v"(r[9]), "=&v"(r[10]), "=&v"(r[11]), "=&v"(r[12]), "=&v"(r[13]), \
+                   "=&v"(r[14]), "=&v"(r[15])                                                                  \
+                 : "v"(ka0), "v"(ka1), "v"(kb0)                                                               \
+                 : "memory")
+template <int D>
+__device__ __forceinline__ void gather_chunk_operands(uint32_t ka0, uint32_t ka1, uint32_t kb0, bf16x8 (&fa)[4],
+                                                      bf16x8 (&fb)[4])
+{
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    static_assert(D == 128 || D == 64, "row bytes 256 or 128");
+    static_assert(MmaBF16::kRowPad == 16, "B tile rows are 96 bytes");
+    u32x2 r[16];
+    if constexpr (D == 128) GKA_GATHER_CHUNK(4096, 8192, 12288);
+    else GKA_GATHER_CHUNK(2048, 4096, 6144);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const u32x4 ua = {r[4 * s][0], r[4 * s][1], r[4 * s + 1][0], r[4 * s + 1][1]};
+        const u32x4 ub = {r[4 * s + 2][0], r[4 * s + 2][1], r[4 * s + 3][0], r[4 * s + 3][1]};
+        fa[s] = __builtin_bit_cast(bf16x8, ua);
+        fb[s] = __builtin_bit_cast(bf16x8, ub);
+    }
+}
+#undef GKA_GATHER_CHUNK
+#undef GKA_TR_READ
+
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+// bf16 tensors with bf16 operands: the same walk with less work per chunk on the critical path.
+//   - The chunk's k rows go from global memory straight into LDS (no registers, no conversion), into one of three
+//     swizzled buffers, two chunks ahead of their use. They are the A operand, unscaled.
+//   - The decay weight w_j = zeta_C / zeta_j is carried by the B operand alone: the slab's 32 columns of the k
+//     rows (H) or v rows (U) are prefetched into registers, scaled and stored to a small padded tile.
+// Vector-memory operations of one wave complete in issue order, so "the copy of chunk c has landed" is a counted
+// wait: every iteration issues, in this order, NA copies, NS state stores, [wait], NL prefetch loads.
+template <class IO, int D, bool DOH, bool WRITE>
+__device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int rb, int group, uint16_t *s_k,
+                                                     uint16_t *s_b)
+{
+    typedef MmaBF16 MMA;
+    typedef typename MMA::frag frag;
+    constexpr int NB = D / 32;
+    constexpr int HS = MMA::HS;
+    constexpr int STEPS = kChunk / 16;            // MFMA steps over the chunk's tokens
+    constexpr int NT = D * 2;                     // threads
+    constexpr int NW = NT / 64;                   // waves
+    constexpr int RSB = 32 + MMA::kRowPad;        // row stride of the B tile
+    constexpr int ROWB = D * 2;                   // bytes per k row
+    constexpr int KBUF = kChunk * D;              // elements per k buffer
+    constexpr int NA = kChunk * ROWB / (NT * 16); // 16-byte copies per thread per chunk
+    constexpr int LPR = ROWB / 16;                // lanes (16-byte pieces) per row
+    constexpr int RPI = 64 / LPR;                 // rows per wave-wide copy instruction
+    constexpr int VP = kChunk * 8 / NT;           // 4-element pieces of the B tile per thread
+    constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
+    constexpr int NS = WRITE ? (DOH ? HS + 1 : HS * NSPL) : 0;   // state stores per chunk
+    constexpr int NL = VP + 1;                    // prefetch loads per chunk
+    typedef SwizzledRows<ROWB, 2> KRows;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // column block of the slab owned by this wave (uniform)
+    const int n = lane & 31, g = lane >> 5;
+    const int pair = group % a.n_pairs;
+    const int seg = group / a.n_pairs;
+    const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
+    const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    const int64_t gate_base = (int64_t)b * a.T * a.H + h;
+    const int chunk_begin = a.chunk0 + seg * a.seg_len;
+    const int chunk_end = min(chunk_begin + a.seg_len, a.chunk0 + a.n_chunks);
+    const int c_last = max(chunk_end - 1, chunk_begin);
+    const void *bsrc = DOH ? a.k : a.v;
+
+    f32x16 acc = zero16();
+    load_start_state<D, DOH>(a, acc, pair, seg, rb, w, lane);
+
+    // copy of chunk c's k rows into buffer `buf`: copy q of wave w fills rows (q NW + w) RPI .. + RPI of the tile
+    // (1 KiB); the lane picks the 16 source bytes that belong at its place of the swizzled row. Rows past the end
+    // of the sequence repeat the last row (finite values; their B rows are zero). The copies are buffer loads (a
+    // descriptor based at the chunk's first row, 32-bit byte offsets per lane).
+    const int lrow = lane / LPR, lbyte = (lane % LPR) * 16;
+    const int row_bytes = (int)a.stride_t * 2;
+    auto issue_k = [&](int c, int buf) {
+        const uint16_t *base = (const uint16_t *)a.k + base_bh + (int64_t)c * kChunk * a.stride_t;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0x7fffffff, 0x00020000);
+        const int last_row = a.T - 1 - c * kChunk;
+#pragma unroll
+        for (int q = 0; q < NA; ++q) {
+            const int row = (q * NW + w) * RPI + lrow;
+            const int sbyte = lbyte ^ ((row & KRows::kMask) << 5);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rsrc, (__attribute__((address_space(3))) void *)(s_k + buf * KBUF + (q * NW + w) * 512), 16,
+                min(row, last_row) * row_bytes + sbyte, 0, 0, 0);
         }
-        if (rb == 0 && tid == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
+    };
+    struct Fetch {
+        typename IO::raw4 b[VP];
+        float gate;
+    };
+    auto fetch = [&](Fetch &f, int c) {
+#pragma unroll
+        for (int i = 0; i < VP; ++i) {
+            const int piece = i * NT + tid;
+            const int t = min(c * kChunk + piece / 8, a.T - 1);
+            f.b[i] = IO::load_raw4(bsrc, base_bh + (int64_t)t * a.stride_t + 32 * rb + 4 * (piece % 8));
+        }
+        const int t = min(c * kChunk + lane, a.T - 1);
+        f.gate = a.gate[gate_base + (int64_t)t * a.H];
+    };
+    float Gseg = 0.0f;
+    int kb = 0;                                   // buffer that holds the chunk being processed
+    // Transpose-read addresses of this lane (see gather_transposed_bf16): lane (n, g) gets tokens 16 s + 8 g + p of
+    // step s; within its block of 16 lanes, lane i addresses token run[i / 4] at the 4-column group i % 4.
+    static_assert(STEPS == 4, "one gather block per chunk");
+    const int sub = 16 * ((lane >> 4) & 1);       // this 16-lane block's columns within the 32
+    const int li = lane & 15;
+    const uint32_t ka0 = lds_address(s_k + KRows{}(8 * g + (li >> 2), 32 * w + sub + 4 * (li & 3)));
+    const uint32_t ka1 = lds_address(s_k + KRows{}(8 * g + 4 + (li >> 2), 32 * w + sub + 4 * (li & 3)));
+    const uint32_t kb0 = lds_address(s_b + (8 * g + (li >> 2)) * RSB + sub + 4 * (li & 3));
+
+    auto process = [&](const Fetch &f, int c) {
+        // nothing of this chunk is scheduled into the previous one (its prefetched values arrive last)
+        __builtin_amdgcn_sched_barrier(0);
+        const bool stamp = (c == chunk_begin + 20);
+        if (stamp) GKA_STSTAMP(1);
+        // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights zeta_C / zeta_j = 2^(G_C - G_j)
+        const bool valid = c * kChunk + lane < a.T;
+        const float lg = valid ? log2_gate(f.gate) : 0.0f;
+        const float G = wave_inclusive_scan(lg, lane);
+        const float Gtot = lane_value(G, 63);
+        Gseg += Gtot;
+        const float wj = valid ? exp2f(Gtot - G) : 0.0f;     // lane j: weight of token j
+        const float zetaC = exp2f(Gtot);
+        if (stamp) GKA_STSTAMP(2);
+        lds_barrier();                          // the previous chunk's operand reads are done
+        if (stamp) GKA_STSTAMP(3);
+        const int kb2 = kb >= 1 ? kb - 1 : 2;   // (kb + 2) % 3: the previous chunk's buffer
+        issue_k(min(c + 2, c_last), kb2);
+#pragma unroll
+        for (int i = 0; i < VP; ++i) {
+            const int piece = i * NT + tid;
+            const int row = piece / 8;
+            MMA::store4(s_b + row * RSB + 4 * (piece % 8), IO::cvt4(f.b[i]) * __shfl(wj, row, 64));
+        }
+        if (stamp) GKA_STSTAMP(4);
+
+        // ---- write the state before the chunk, fragment order
+        if (WRITE) {
+            const int64_t chunk_id = (int64_t)(c - a.chunk0) * a.n_pairs + pair;   // chunk-major: pairs adjacent
+            float vals[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) vals[r] = acc[r];
+            if (DOH) {
+                frag *Hw = (frag *)a.ws_H + chunk_id * (NB * NB * HS * 64);
+                float ss = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) ss += acc[r] * acc[r];
+#pragma unroll
+                for (int hh = 0; hh < HS; ++hh)
+                    Hw[((rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(vals + hh * MMA::VEC);
+                ss = wave_inclusive_scan(ss, lane);           // lane 63: the wave's total
+                if (lane == 63) a.ws_hn[chunk_id * (NB * NB) + rb * NB + w] = ss;
+            } else {
+                frag *Uw = (frag *)a.ws_U + chunk_id * (NSPL * NB * NB * HS * 64);
+                float lo[16];
+#pragma unroll
+                for (int hh = 0; hh < HS; ++hh) {
+                    frag fr = MMA::pack(vals + hh * MMA::VEC);
+                    Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
+#pragma unroll
+                    for (int p = 0; p < MMA::VEC; ++p)
+                        lo[hh * MMA::VEC + p] = vals[hh * MMA::VEC + p] - MMA::elem(fr, p);
+                }
+                if (NSPL == 2) {
+#pragma unroll
+                    for (int hh = 0; hh < HS; ++hh)
+                        Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(lo + hh * MMA::VEC);
+                }
+            }
+        }
+        if (stamp) GKA_STSTAMP(5);
+        // This chunk's copy was issued two iterations ago; since then the wave has issued at least the copies and
+        // stores of this and the previous iteration and the prefetch loads of the previous one.
+        wait_vector_memory_upto<2 * NA + 2 * NS + NL>();
+        lds_barrier();                          // k rows (all waves' copies) and the B tile are visible
+        if (stamp) GKA_STSTAMP(6);
+
+        // ---- S <- zeta_C S + sum_j w_j a_j k_j^T
+        frag fa[STEPS], fb[STEPS];
+        gather_chunk_operands<D>(ka0 + kb * (KBUF * 2), ka1 + kb * (KBUF * 2), kb0, fa, fb);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] *= zetaC;
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) acc = MMA::mma(fa[s], fb[s], acc);
+        kb = kb == 2 ? 0 : kb + 1;
+        if (stamp) GKA_STSTAMP(7);
+    };
+
+    // Before the loop: copies of the first two chunks and their prefetches, all waited for once. An odd chunk
+    // count is evened out in front of the loop so that the loop body is the only user of its two prefetch buffers.
+    GKA_STSTAMP(0);
+    int c = chunk_begin;
+    issue_k(c, 0);
+    issue_k(min(c + 1, c_last), 1);
+    if ((chunk_end - chunk_begin) & 1) {
+        Fetch fp;
+        fetch(fp, c);
+        drain_vector_memory();
+        process(fp, c);
+        ++c;
+    }
+    if (c < chunk_end) {
+        Fetch f0, f1;
+        fetch(f0, c);
+        fetch(f1, c + 1);
+        drain_vector_memory();
+        for (; c < chunk_end; c += 2) {
+            process(f0, c);
+            fetch(f0, min(c + 2, c_last));
+            process(f1, c + 1);
+            fetch(f1, min(c + 3, c_last));
+        }
+    }
+    // no copy into this workgroup's LDS may still be in flight when it ends
+    drain_vector_memory();
+    GKA_STSTAMP(8);
+    store_end_state<D, DOH>(a, acc, Gseg, pair, seg, rb, w, lane);
+}
+
+template <class MMA, class IO, int D>
+__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE_WAVES))) void state_pass_kernel(StatePassArgs a)
+{
+    constexpr int NB = D / 32;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2. The 2 NB workgroups of one
+    // (pair, segment) read the same k rows, so they are given block indices that are equal modulo 8.
+    // Each workgroup owns one of the two states of its slab (H or U): twice the workgroups, each with half the
+    // accumulators and half the state writes per chunk.
+    constexpr int PER = 2 * NB;                    // workgroups per (pair, segment)
+    const int id = blockIdx.x;
+    const int full = (gridDim.x / (8 * PER)) * (8 * PER);
+    int sub, group;
+    if (id < full) {
+        const int within = id % (8 * PER);
+        sub = within / 8;
+        group = (id / (8 * PER)) * 8 + within % 8;
+    } else {
+        sub = (id - full) % PER;
+        group = full / PER + (id - full) / PER;
+    }
+    const int rb = sub >> 1;                       // slab index (row block of H0 / U0)
+    typedef typename MMA::elem_t elem_t;
+    constexpr bool kDirect = std::is_same<MMA, MmaBF16>::value;    // k rows copied straight into LDS
+    __shared__ __attribute__((aligned(1024))) elem_t s_k[kDirect ? 3 * kChunk * D : kChunk * (D + MMA::kRowPad)];
+    __shared__ __attribute__((aligned(16))) elem_t s_v[kChunk * (32 + MMA::kRowPad)];
+    if constexpr (kDirect) {
+        if (a.write_frags) {
+            if (sub & 1) state_pass_body_bf16<IO, D, false, true>(a, rb, group, s_k, s_v);
+            else state_pass_body_bf16<IO, D, true, true>(a, rb, group, s_k, s_v);
+        } else {
+            if (sub & 1) state_pass_body_bf16<IO, D, false, false>(a, rb, group, s_k, s_v);
+            else state_pass_body_bf16<IO, D, true, false>(a, rb, group, s_k, s_v);
+        }
+    } else {
+        if (a.write_frags) {
+            if (sub & 1) state_pass_body<MMA, IO, D, false, true>(a, rb, group, s_k, s_v);
+            else state_pass_body<MMA, IO, D, true, true>(a, rb, group, s_k, s_v);
+        } else {
+            if (sub & 1) state_pass_body<MMA, IO, D, false, false>(a, rb, group, s_k, s_v);
+            else state_pass_body<MMA, IO, D, true, false>(a, rb, group, s_k, s_v);
+        }
     }
 }
 
@@ -281,13 +633,13 @@ static hipError_t launch_state_pass_t(const StatePassArgs &a0, int n_pairs, hipS
     a.n_pairs = n_pairs;
     if (a.n_segs <= 1) {
         a.n_segs = 1;
-        a.seg_len = a.n_chunks_total;
+        a.seg_len = a.n_chunks;
     } else {
         // summaries (decay, Delta from a zero state) of every segment but the last
         a.init_mode = 0;
         a.final_mode = 2;
         a.write_frags = 0;
-        hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * NB * (a.n_segs - 1)), block, 0, stream, a);
+        hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * 2 * NB * (a.n_segs - 1)), block, 0, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -295,7 +647,7 @@ static hipError_t launch_state_pass_t(const StatePassArgs &a0, int n_pairs, hipS
     a.init_mode = 1;
     a.final_mode = 1;
     a.write_frags = 1;
-    hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * NB * a.n_segs), block, 0, stream, a);
+    hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * 2 * NB * a.n_segs), block, 0, stream, a);
     return hipGetLastError();
 }
 

@@ -84,3 +84,24 @@ def test_initial_and_final_state_handoff():
     assert pair_rel_err(y, ref) <= TOL_F32
     assert pair_rel_err(to_host(o_full), ref) <= TOL_F32
     np.testing.assert_allclose(to_host(ex_b["H_final"]), to_host(ex_full["H_final"]), rtol=0, atol=1e-5)
+
+
+@pytest.mark.parametrize("compute", ["bf16", "f32"])
+def test_multi_slab_with_state_carry(compute):
+    """Large enough that the library cuts the sequence into several chunk slabs (states carried between
+    launches), with a ragged tail and non-zero initial states; final states are checked too."""
+    w = synth.CFG2.scaled(B=8, H=16, T=1000, seed=77)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((w.B, w.H, w.d, 8)).astype(np.float32)
+    Hi = np.einsum("bhik,bhjk->bhij", A, A).astype(np.float32) / 8
+    Ui = rng.standard_normal((w.B, w.H, w.d, w.d)).astype(np.float32) * 0.1
+    cmode = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    o, ex = run_forward(w, x, compute=cmode, H_init=to_device(Hi, "f32"), U_init=to_device(Ui, "f32"),
+                        return_state=True)
+    ref, rex = oracle_forward(w, x, H_init=Hi, U_init=Ui, return_state=True)
+    err = pair_rel_err(to_host(o), ref)
+    assert err <= TOL_BF16, err
+    tol_state = 5e-3 if compute == "bf16" else 2e-5
+    assert np.abs(to_host(ex["H_final"]) - rex["H_final"]).max() <= tol_state * np.abs(rex["H_final"]).max()
+    assert np.abs(to_host(ex["U_final"]) - rex["U_final"]).max() <= tol_state * np.abs(rex["U_final"]).max()
