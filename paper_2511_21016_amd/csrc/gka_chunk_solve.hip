@@ -140,10 +140,11 @@ __device__ __forceinline__ void gemm_intra(const typename MMA::frag *sAT, int mt
 template <int N16>
 __device__ __forceinline__ void async_block_copy(void *lds_dst, const void *gsrc, int w, int lane)
 {
+    const buffer_rsrc src = make_raw_buffer(gsrc);
 #pragma unroll
     for (int i = 0; i < N16; ++i) {
         const int unit0 = (i * (kSolveThreads / 64) + w) * 64;
-        async_copy16_to_lds((char *)lds_dst + (size_t)unit0 * 16, (const char *)gsrc + (size_t)(unit0 + lane) * 16);
+        async_copy16_to_lds((char *)lds_dst + (size_t)unit0 * 16, src, lane * 16, unit0 * 16);
     }
 }
 
@@ -206,7 +207,8 @@ __device__ __forceinline__ void build_row_frags(typename MMA::frag *sK, const ty
 }
 
 // Fragments AT[mt][jt][h]: row 32*mt + n of X^T, contraction index = tokens j = 32*jt + kidx(h*VEC + p, g).
-template <class MMA, int D>
+// UNTRACKED: the tile is read with gather_transposed_bf16_untracked (a copy into another part of LDS is in flight).
+template <class MMA, int D, bool UNTRACKED = false>
 __device__ __forceinline__ void build_transposed_frags(typename MMA::frag *sAT, const typename MMA::elem_t *sRow,
                                                        int w, int lane)
 {
@@ -218,8 +220,9 @@ __device__ __forceinline__ void build_transposed_frags(typename MMA::frag *sAT, 
         const int hh = f % HS, jt = (f / HS) % 2, mt = f / (2 * HS);
         if constexpr (VEC == 8) {
             const int t0 = 32 * jt + 16 * hh + 4 * g;       // kidx(8*hh + p, g) = 16*hh + 8*(p/4) + 4*g + p%4
-            sAT[f * 64 + lane] =
-                gather_transposed_bf16(sRow, at, 32 * mt + 16 * ((lane >> 4) & 1), lane, t0, t0 + 8);
+            const int col16 = 32 * mt + 16 * ((lane >> 4) & 1);
+            sAT[f * 64 + lane] = UNTRACKED ? gather_transposed_bf16_untracked(sRow, at, col16, lane, t0, t0 + 8)
+                                           : gather_transposed_bf16(sRow, at, col16, lane, t0, t0 + 8);
         } else {
             auto tok_of = [&](int p) { return 32 * jt + kidx(hh * VEC + p, g); };
             sAT[f * 64 + lane] = gather_transposed<MMA>(sRow, at, 32 * mt + n, tok_of);
@@ -285,35 +288,25 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     float lam, hn2 = 0.0f;
     float Gall;                                // lane j: G_j = sum_{i<=j} log2 gamma_i over the chunk
     typename IO::raw4 qraw[NBH][4];            // q of this lane's token, rows of this wave's feature half
-    {
-        // every global read of the prologue is issued here, before the first wait
-        async_block_copy<H16>(sH, (const frag *)a.ws_H + chunk_id * (SH::H_FRAGS * 64), w, lane);   // H_[n] -> LDS
-        const float gm = a.gate[gate_base + (int64_t)min(tok0 + lane, a.T - 1) * a.H];
-        RowStage<MMA, IO, D> krows;
-        krows.load(a.k, base_bh, a.stride_t, tok0, a.T, tid);
+    // every global read of the prologue is issued here, before the first wait; the gates first: loads return in
+    // issue order, and the decay mask below needs nothing else, so it is built while the k rows are on their way
+    const float gm = a.gate[gate_base + (int64_t)min(tok0 + lane, a.T - 1) * a.H];
+    async_block_copy<H16>(sH, (const frag *)a.ws_H + chunk_id * (SH::H_FRAGS * 64), w, lane);   // H_[n] -> LDS
+    RowStage<MMA, IO, D> krows;
+    krows.load(a.k, base_bh, a.stride_t, tok0, a.T, tid);
 #pragma unroll
-        for (int i = 0; i < NBH; ++i)
+    for (int i = 0; i < NBH; ++i)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                qraw[i][q4] = IO::load_raw4(a.q, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g);
-        lam = a.lambda[gate_base + (int64_t)min(tok, a.T - 1) * a.H];
-        float hn[NB * NB];
+        for (int q4 = 0; q4 < 4; ++q4)
+            qraw[i][q4] = IO::load_raw4(a.q, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g);
+    lam = a.lambda[gate_base + (int64_t)min(tok, a.T - 1) * a.H];
+    float hn[NB * NB];
 #pragma unroll
-        for (int i = 0; i < NB * NB; ++i) hn[i] = a.ws_hn[chunk_id * (NB * NB) + i];
-        krows.store(sRow, tok0, a.T, tid);
-        lds_barrier();
-        GKA_TSTAMP(1);
-        build_row_frags<MMA, D>(sK, sRow, w, lane);
-        build_transposed_frags<MMA, D>(sKT, sRow, w, lane);
-        // every wave scans the chunk's gates itself: no LDS round trip for the per-token decays
-        Gall = wave_inclusive_scan((tok0 + lane < a.T) ? log2_gate(gm) : 0.0f, lane);
-        if (!valid) lam = 1.0f;
-#pragma unroll
-        for (int i = 0; i < NB * NB; ++i) hn2 += hn[i];
-        GKA_TSTAMP(2);
-    }
+    for (int i = 0; i < NB * NB; ++i) hn[i] = a.ws_hn[chunk_id * (NB * NB) + i];
 
     // ---------------- decay mask (Section 4.2.1; log-space form of Appendix B.2, base 2) ----------------
+    // every wave scans the chunk's gates itself: no LDS round trip for the per-token decays
+    Gall = wave_inclusive_scan((tok0 + lane < a.T) ? log2_gate(gm) : 0.0f, lane);
     const float Gc = __shfl(Gall, c_local, 64);
     const float zeta = exp2f(Gc);
     f32x16 mreg[NJ];
@@ -325,6 +318,16 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
             const float Gj = g ? lane_value(Gall, 32 * jt + kidx(r, 1)) : lane_value(Gall, 32 * jt + kidx(r, 0));
             mreg[jt][r] = (j <= c_local) ? exp2f(Gc - Gj) : 0.0f;
         }
+    __builtin_amdgcn_sched_barrier(0);         // the mask is not scheduled behind the wait for the k rows
+    GKA_TSTAMP(1);
+    krows.store(sRow, tok0, a.T, tid);
+    lds_barrier();
+    GKA_TSTAMP(2);
+    build_row_frags<MMA, D>(sK, sRow, w, lane);
+    build_transposed_frags<MMA, D>(sKT, sRow, w, lane);
+    if (!valid) lam = 1.0f;
+#pragma unroll
+    for (int i = 0; i < NB * NB; ++i) hn2 += hn[i];
     GKA_TSTAMP(3);
     wait_all_memory();                         // H_[n] has landed in LDS
     lds_barrier();                           // fragments and H_[n] visible; the staging tile is free
@@ -478,7 +481,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     async_block_copy<H16>(sH, Uw, w, lane);    // U_[n] (rounded part) replaces H_[n]
     vrows.store(sRow, tok0, a.T, tid);
     lds_barrier();
-    build_transposed_frags<MMA, D>(sKT, sRow, w, lane);      // V^T replaces K^T
+    build_transposed_frags<MMA, D, true>(sKT, sRow, w, lane);      // V^T replaces K^T
     lds_barrier();                           // the staging tile becomes the exchange region again
     GKA_TSTAMP(9);
     publish_operand<MMA, NB>(sX, own, TW, mt0, lane);

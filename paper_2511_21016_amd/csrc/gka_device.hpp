@@ -140,13 +140,43 @@ __device__ __forceinline__ bf16x8 gather_transposed_bf16(const uint16_t *tile, L
     return __builtin_bit_cast(bf16x8, r);
 }
 
+// The same two transpose reads written as assembly, including the wait for their data. The compiler orders every
+// LDS read it knows of behind all copies into LDS (below) that are in flight, whichever part of LDS they fill; a
+// read it does not see is not held back. For tiles that no copy in flight writes to.
+template <class Layout>
+__device__ __forceinline__ bf16x8 gather_transposed_bf16_untracked(const uint16_t *tile, Layout at, int col16, int lane,
+                                                                   int t0, int t1)
+{
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) const uint16_t lds_u16;
+    const int i = lane & 15;
+    const uint32_t p0 = (uint32_t)(uintptr_t)(lds_u16 *)(tile + at(t0 + (i >> 2), col16 + 4 * (i & 3)));
+    const uint32_t p1 = (uint32_t)(uintptr_t)(lds_u16 *)(tile + at(t1 + (i >> 2), col16 + 4 * (i & 3)));
+    u32x2 a, b;
+    asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(a), "=&v"(b)
+                 : "v"(p0), "v"(p1)
+                 : "memory");
+    const u32x4 r = {a[0], a[1], b[0], b[1]};
+    return __builtin_bit_cast(bf16x8, r);
+}
+
 // Asynchronous copy global -> LDS without staging registers: every lane moves 16 bytes, a wave's 64 pieces land
 // contiguously at the (wave-uniform) destination. Completion is tracked by the vector-memory counter: wait for it
-// (s_waitcnt vmcnt(0)) and pass a barrier before other waves read the data.
-__device__ __forceinline__ void async_copy16_to_lds(void *lds_wave_base, const void *gsrc_lane)
+// (s_waitcnt vmcnt) and pass a barrier before other waves read the data. The copies are buffer loads: a
+// descriptor over the source (wave-uniform base) and a 32-bit byte offset per lane. (The flat form of the same
+// copy makes the compiler turn every later vector-memory wait of the wave into a full drain.)
+typedef __amdgpu_buffer_rsrc_t buffer_rsrc;
+__device__ __forceinline__ buffer_rsrc make_raw_buffer(const void *base)
 {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc_lane,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0x7fffffff, 0x00020000);
+}
+__device__ __forceinline__ void async_copy16_to_lds(void *lds_wave_base, buffer_rsrc src, int lane_byte_offset,
+                                                    int wave_byte_offset)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (__attribute__((address_space(3))) void *)lds_wave_base, 16,
+                                             lane_byte_offset, wave_byte_offset, 0, 0);
 }
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 

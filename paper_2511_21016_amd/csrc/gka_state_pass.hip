@@ -435,15 +435,13 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
     const int row_bytes = (int)a.stride_t * 2;
     auto issue_k = [&](int c, int buf) {
         const uint16_t *base = (const uint16_t *)a.k + base_bh + (int64_t)c * kChunk * a.stride_t;
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, 0x7fffffff, 0x00020000);
+        const buffer_rsrc rsrc = make_raw_buffer(base);
         const int last_row = a.T - 1 - c * kChunk;
 #pragma unroll
         for (int q = 0; q < NA; ++q) {
             const int row = (q * NW + w) * RPI + lrow;
             const int sbyte = lbyte ^ ((row & KRows::kMask) << 5);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rsrc, (__attribute__((address_space(3))) void *)(s_k + buf * KBUF + (q * NW + w) * 512), 16,
-                min(row, last_row) * row_bytes + sbyte, 0, 0, 0);
+            async_copy16_to_lds(s_k + buf * KBUF + (q * NW + w) * 512, rsrc, min(row, last_row) * row_bytes + sbyte, 0);
         }
     };
     struct Fetch {
