@@ -3,6 +3,8 @@
 #include "../../include/gka.h"
 #include "gka_kernels.hpp"
 
+#include <stdlib.h>
+
 #include <vector>
 
 namespace {
@@ -21,10 +23,19 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kStateMinWorkgroups = 512;   // two state-pass workgroups per CU
 constexpr int kStateMaxWalk = 64;          // chunks a state-pass workgroup walks before segments are added
-#ifndef GKA_SLAB_STATE_BYTES
-#define GKA_SLAB_STATE_BYTES (1024u << 20)
-#endif
-constexpr size_t kSlabStateBytes = GKA_SLAB_STATE_BYTES;   // chunk states one launch pair keeps in the workspace
+// Chunk states one launch pair keeps in the workspace. The environment variable GKA_SLAB_STATE_BYTES overrides the
+// default (tests use it to force several slabs on small problems).
+constexpr size_t kDefaultSlabStateBytes = (size_t)1 << 30;
+size_t slab_state_bytes()
+{
+    const char *e = getenv("GKA_SLAB_STATE_BYTES");
+    if (e && *e) {
+        char *end = nullptr;
+        const unsigned long long v = strtoull(e, &end, 10);
+        if (end != e && v > 0) return (size_t)v;
+    }
+    return kDefaultSlabStateBytes;
+}
 constexpr size_t kMaxPairsPerBatch = 1024;
 constexpr size_t kMinSlabChunks = 4;
 
@@ -77,7 +88,7 @@ gka_status make_plan(const gka_params *p, Plan *pl)
     const size_t per_chunk = gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16) +
                              gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16);
     size_t ppb = pl->n_pairs < kMaxPairsPerBatch ? pl->n_pairs : kMaxPairsPerBatch;
-    size_t slab = kSlabStateBytes / (ppb * per_chunk);
+    size_t slab = slab_state_bytes() / (ppb * per_chunk);
     if (slab < kMinSlabChunks) slab = kMinSlabChunks;
     if (slab > (size_t)pl->n_chunks) slab = pl->n_chunks;
     pl->pairs_per_batch = (int)ppb;

@@ -470,9 +470,10 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         for (int hh = 0; hh < HS; ++hh) {
             own[i][hh] = MMA::pack(&xi[i][hh * VEC]);
             if (NSPL == 2) {
-                float lo[VEC];
+                float lo[VEC], back[VEC];
+                MMA::unpack(own[i][hh], back);
 #pragma unroll
-                for (int p = 0; p < VEC; ++p) lo[p] = xi[i][hh * VEC + p] - MMA::elem(own[i][hh], p);
+                for (int p = 0; p < VEC; ++p) lo[p] = xi[i][hh * VEC + p] - back[p];
                 ownlo[i][hh] = MMA::pack(lo);
             }
         }

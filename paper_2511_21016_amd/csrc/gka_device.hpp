@@ -225,6 +225,17 @@ struct MmaBF16 {
         return f;
     }
     static __device__ __forceinline__ float elem(frag f, int p) { return (float)f[p]; }
+    // all VEC elements as floats: one shift or mask per element of the packed words
+    static __device__ __forceinline__ void unpack(frag f, float *x)
+    {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 wds = __builtin_bit_cast(u32x4, f);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __uint_as_float(wds[i] << 16);
+            x[2 * i + 1] = __uint_as_float(wds[i] & 0xffff0000u);
+        }
+    }
     static __device__ __forceinline__ frag zero()
     {
         frag f;
@@ -250,6 +261,7 @@ struct MmaF32 {
     }
     static __device__ __forceinline__ frag pack(const float *x) { return x[0]; }
     static __device__ __forceinline__ float elem(frag f, int) { return f; }
+    static __device__ __forceinline__ void unpack(frag f, float *x) { x[0] = f; }
     static __device__ __forceinline__ frag zero() { return 0.0f; }
 };
 

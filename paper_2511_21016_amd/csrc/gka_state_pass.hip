@@ -518,9 +518,10 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
                 for (int hh = 0; hh < HS; ++hh) {
                     frag fr = MMA::pack(vals + hh * MMA::VEC);
                     Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
+                    float back[MMA::VEC];
+                    MMA::unpack(fr, back);
 #pragma unroll
-                    for (int p = 0; p < MMA::VEC; ++p)
-                        lo[hh * MMA::VEC + p] = vals[hh * MMA::VEC + p] - MMA::elem(fr, p);
+                    for (int p = 0; p < MMA::VEC; ++p) lo[hh * MMA::VEC + p] = vals[hh * MMA::VEC + p] - back[p];
                 }
                 if (NSPL == 2) {
 #pragma unroll

@@ -87,11 +87,17 @@ def test_initial_and_final_state_handoff():
 
 
 @pytest.mark.parametrize("compute", ["bf16", "f32"])
-def test_multi_slab_with_state_carry(compute):
-    """Large enough that the library cuts the sequence into several chunk slabs (states carried between
-    launches), with a ragged tail and non-zero initial states; final states are checked too."""
+def test_multi_slab_with_state_carry(compute, monkeypatch):
+    """The sequence is processed as several chunk slabs (states carried between launches), with a ragged tail
+    and non-zero initial states; final states are checked too."""
     w = synth.CFG2.scaled(B=8, H=16, T=1000, seed=77)
     x = synth.make_inputs(w)
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, cm)
+    one_slab = binding.forward_workspace_bytes(params)
+    # a workspace budget small enough that this problem is cut into slabs of four chunks
+    monkeypatch.setenv("GKA_SLAB_STATE_BYTES", str(48 << 20))
+    assert binding.forward_workspace_bytes(params) < one_slab // 2
     rng = np.random.default_rng(5)
     A = rng.standard_normal((w.B, w.H, w.d, 8)).astype(np.float32)
     Hi = np.einsum("bhik,bhjk->bhij", A, A).astype(np.float32) / 8
@@ -105,3 +111,27 @@ def test_multi_slab_with_state_carry(compute):
     tol_state = 5e-3 if compute == "bf16" else 2e-5
     assert np.abs(to_host(ex["H_final"]) - rex["H_final"]).max() <= tol_state * np.abs(rex["H_final"]).max()
     assert np.abs(to_host(ex["U_final"]) - rex["U_final"]).max() <= tol_state * np.abs(rex["U_final"]).max()
+
+
+@pytest.mark.parametrize("compute", ["bf16", "f32"])
+@pytest.mark.parametrize("d", [64, 128])
+def test_explicit_strides_head_major_layout(compute, d):
+    """q, k, v, o stored [B,H,T,d] (heads outermost) and passed through the stride arguments of the C ABI."""
+    import torch
+    w = synth.CFG2.scaled(B=2, H=3, T=200, d=d, seed=11)
+    x = synth.make_inputs(w)
+    dev = {n: to_device(np.ascontiguousarray(np.transpose(x[n], (0, 2, 1, 3))), "bf16") for n in ("q", "k", "v")}
+    gate, lam = to_device(x["gate"], "f32"), to_device(x["lam"], "f32")
+    o = torch.zeros_like(dev["v"])
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, cm,
+                                 strides=(w.H * w.T * w.d, w.d, w.T * w.d))
+    ws = torch.empty(binding.forward_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    st = binding.forward_raw(params, dev["q"].data_ptr(), dev["k"].data_ptr(), dev["v"].data_ptr(), gate.data_ptr(),
+                             lam.data_ptr(), o.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws.numel(),
+                             stream=torch.cuda.current_stream().cuda_stream)
+    assert st == binding.GKA_OK
+    torch.cuda.synchronize()
+    ref = oracle_forward(w, x)
+    y = np.transpose(to_host(o), (0, 2, 1, 3))
+    assert pair_rel_err(y, ref) <= TOL_BF16

@@ -70,6 +70,9 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert binding.forward_raw(big, fake, fake, fake, fake, fake, fake, workspace=0x100000,
                                workspace_bytes=binding.forward_workspace_bytes(big)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(strides=(1, -1, 1))) == binding.GKA_ERR_SHAPE
+    # bf16 operands: strides in units of 16 bytes, token stride below 2^23 elements
+    assert fwd(_p(strides=(64 * 130 * 4, 4 * 130, 132))) == binding.GKA_ERR_SHAPE
+    assert fwd(_p(strides=(1 << 40, 1 << 23, 128))) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(), q=None) == binding.GKA_ERR_NULL
     assert fwd(_p(), gate=None) == binding.GKA_ERR_NULL
     assert fwd(_p(), H_init=fake) == binding.GKA_ERR_NULL                        # H_init without U_init
