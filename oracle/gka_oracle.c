@@ -111,8 +111,10 @@ int gka_oracle_cholesky_solve(int D, double *A, const double *q, double *x)
 /* One token of Eq. (CH) on the explicit state of one pair.  Hs (d_k x d_k) and Us
  * (d_v x d_k) are updated in place.  lambda_given < 0 selects lambda = a * ||H_t||_F.
  * beta is the write gate of the beta-augmented variant (Remark in Section 4.1); beta = 1 is
- * the recurrence studied in the paper.  scratch holds d_k*d_k + 4*d_k doubles. */
-static int token_step(int d_k, int d_v, double *Hs, double *Us, double gamma, double beta,
+ * the recurrence studied in the paper.  alpha is the alpha-connection of Section 4.3: the
+ * readout is applied to the convex combination alpha * xhat_t + (1 - alpha) * q_t; alpha = 1
+ * is Eq. (CH) as printed.  scratch holds d_k*d_k + 4*d_k doubles. */
+static int token_step(int d_k, int d_v, double *Hs, double *Us, double gamma, double beta, double alpha,
                       const double *k, const double *v, const double *q,
                       double lambda_given, double a, int n_iter, int solver,
                       double *y, double *fro_out, double *xhat_out, double *scratch)
@@ -142,22 +144,23 @@ static int token_step(int d_k, int d_v, double *Hs, double *Us, double gamma, do
         rc = gka_oracle_cholesky_solve(d_k, A, q, xi);
     else
         gka_oracle_chebyshev(d_k, A, q, L, mu, n_iter, xi, work);
+    if (xhat_out) for (int j = 0; j < d_k; ++j) xhat_out[j] = xi[j];
+    for (int j = 0; j < d_k; ++j) xi[j] = alpha * xi[j] + (1.0 - alpha) * q[j];
     for (int i = 0; i < d_v; ++i) {
         double s = 0.0;
         for (int j = 0; j < d_k; ++j) s += Us[(size_t)i * d_k + j] * xi[j];
         y[i] = s;
     }
     if (fro_out) *fro_out = fro;
-    if (xhat_out) for (int j = 0; j < d_k; ++j) xhat_out[j] = xi[j];
     return rc;
 }
 
 /* Whole-sequence forward.  lambda may be NULL (then lambda_t = lambda_scale * ||H_t||_F);
- * beta, H_init, U_init, H_final, U_final, fro_out, xhat_out may each be NULL.
+ * beta, alpha (NULL = 1), H_init, U_init, H_final, U_final, fro_out, xhat_out may each be NULL.
  * Returns 0, or 1 if a Cholesky factorisation failed, or 2 on allocation failure. */
 int gka_oracle_forward(int B, int T, int H, int d_k, int d_v,
                        const double *q, const double *k, const double *v,
-                       const double *gate, const double *lambda, const double *beta,
+                       const double *gate, const double *lambda, const double *beta, const double *alpha,
                        double lambda_scale, int n_iter, int solver,
                        const double *H_init, const double *U_init,
                        double *y, double *H_final, double *U_final,
@@ -184,7 +187,7 @@ int gka_oracle_forward(int B, int T, int H, int d_k, int d_v,
         else memset(Us, 0, uu * sizeof(double));
         for (int t = 0; t < T; ++t) {
             size_t tok = ((size_t)b * T + t) * H + h;
-            int rc = token_step(d_k, d_v, Hs, Us, gate[tok], beta ? beta[tok] : 1.0,
+            int rc = token_step(d_k, d_v, Hs, Us, gate[tok], beta ? beta[tok] : 1.0, alpha ? alpha[tok] : 1.0,
                                 k + tok * d_k, v + tok * d_v, q + tok * d_k,
                                 lambda ? lambda[tok] : -1.0, lambda_scale, n_iter, solver,
                                 y + tok * d_v, fro_out ? fro_out + tok : NULL,
@@ -206,7 +209,7 @@ int gka_oracle_forward(int B, int T, int H, int d_k, int d_v,
 int gka_oracle_decode_step(int B, int H, int d_k, int d_v,
                            double *H_state, double *U_state,
                            const double *q, const double *k, const double *v,
-                           const double *gate, const double *lambda, const double *beta,
+                           const double *gate, const double *lambda, const double *beta, const double *alpha,
                            double lambda_scale, int n_iter, int solver,
                            double *y, double *fro_out)
 {
@@ -222,7 +225,7 @@ int gka_oracle_decode_step(int B, int H, int d_k, int d_v,
             continue;
         }
         int rc = token_step(d_k, d_v, H_state + (size_t)p * hh, U_state + (size_t)p * uu,
-                            gate[p], beta ? beta[p] : 1.0,
+                            gate[p], beta ? beta[p] : 1.0, alpha ? alpha[p] : 1.0,
                             k + (size_t)p * d_k, v + (size_t)p * d_v, q + (size_t)p * d_k,
                             lambda ? lambda[p] : -1.0, lambda_scale, n_iter, solver,
                             y + (size_t)p * d_v, fro_out ? fro_out + p : NULL, NULL, scratch);

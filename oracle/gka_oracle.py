@@ -40,9 +40,9 @@ def _load():
         lib.gka_oracle_chebyshev.restype = None
         lib.gka_oracle_cholesky_solve.argtypes = [ci, dp, dp, dp]
         lib.gka_oracle_cholesky_solve.restype = ci
-        lib.gka_oracle_forward.argtypes = [ci] * 5 + [dp] * 6 + [cd, ci, ci] + [dp] * 7
+        lib.gka_oracle_forward.argtypes = [ci] * 5 + [dp] * 7 + [cd, ci, ci] + [dp] * 7
         lib.gka_oracle_forward.restype = ci
-        lib.gka_oracle_decode_step.argtypes = [ci] * 4 + [dp] * 8 + [cd, ci, ci] + [dp] * 2
+        lib.gka_oracle_decode_step.argtypes = [ci] * 4 + [dp] * 9 + [cd, ci, ci] + [dp] * 2
         lib.gka_oracle_decode_step.restype = ci
         lib.gka_oracle_num_threads.argtypes = []
         lib.gka_oracle_num_threads.restype = ci
@@ -96,11 +96,12 @@ def cholesky_solve(A, q):
     return x
 
 
-def forward(q, k, v, gate, lam, n_iter, *, beta=None, lambda_scale=0.0, solver=SOLVER_CHEBYSHEV,
+def forward(q, k, v, gate, lam, n_iter, *, beta=None, alpha=None, lambda_scale=0.0, solver=SOLVER_CHEBYSHEV,
             H_init=None, U_init=None, return_state=False, return_fro=False, return_xhat=False):
     """Eq. (CH) over whole sequences.
 
-    q, k: [B,T,H,d_k]; v: [B,T,H,d_v]; gate, lam, beta: [B,T,H] (lam None -> lambda_scale*||H_t||_F).
+    q, k: [B,T,H,d_k]; v: [B,T,H,d_v]; gate, lam, beta, alpha: [B,T,H] (lam None -> lambda_scale*||H_t||_F;
+    beta: write gate of the beta-augmented recurrence; alpha: readout of alpha*xhat + (1-alpha)*q; None = 1).
     Returns y [B,T,H,d_v] (float64) and, on request, a dict with H_final, U_final, fro, xhat.
     """
     q = _f64(q)
@@ -112,6 +113,7 @@ def forward(q, k, v, gate, lam, n_iter, *, beta=None, lambda_scale=0.0, solver=S
     gate = _f64(gate, (B, T, H))
     lam = None if lam is None else _f64(lam, (B, T, H))
     beta = None if beta is None else _f64(beta, (B, T, H))
+    alpha = None if alpha is None else _f64(alpha, (B, T, H))
     H_init = None if H_init is None else _f64(H_init, (B, H, d_k, d_k))
     U_init = None if U_init is None else _f64(U_init, (B, H, d_v, d_k))
     y = np.empty((B, T, H, d_v), dtype=np.float64)
@@ -128,7 +130,7 @@ def forward(q, k, v, gate, lam, n_iter, *, beta=None, lambda_scale=0.0, solver=S
         xhat = np.empty((B, T, H, d_k), dtype=np.float64)
         extra["xhat"] = xhat
     rc = _load().gka_oracle_forward(B, T, H, d_k, d_v, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam),
-                                    _ptr(beta), float(lambda_scale), int(n_iter), int(solver),
+                                    _ptr(beta), _ptr(alpha), float(lambda_scale), int(n_iter), int(solver),
                                     _ptr(H_init), _ptr(U_init), _ptr(y), _ptr(Hf), _ptr(Uf), _ptr(fro),
                                     _ptr(xhat))
     if rc:
@@ -138,7 +140,7 @@ def forward(q, k, v, gate, lam, n_iter, *, beta=None, lambda_scale=0.0, solver=S
     return y
 
 
-def decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, beta=None, lambda_scale=0.0,
+def decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, beta=None, alpha=None, lambda_scale=0.0,
                 solver=SOLVER_CHEBYSHEV, return_fro=False):
     """One recurrent step on float64 states [B,H,d,d], updated IN PLACE. q,k,v: [B,H,d]."""
     if H_state.dtype != np.float64 or not H_state.flags.c_contiguous:
@@ -153,10 +155,11 @@ def decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, beta=None, lamb
     gate = _f64(gate, (B, H))
     lam = None if lam is None else _f64(lam, (B, H))
     beta = None if beta is None else _f64(beta, (B, H))
+    alpha = None if alpha is None else _f64(alpha, (B, H))
     y = np.empty((B, H, d_v), dtype=np.float64)
     fro = np.empty((B, H), dtype=np.float64) if return_fro else None
     rc = _load().gka_oracle_decode_step(B, H, d_k, d_v, _ptr(H_state), _ptr(U_state), _ptr(q), _ptr(k),
-                                        _ptr(v), _ptr(gate), _ptr(lam), _ptr(beta), float(lambda_scale),
+                                        _ptr(v), _ptr(gate), _ptr(lam), _ptr(beta), _ptr(alpha), float(lambda_scale),
                                         int(n_iter), int(solver), _ptr(y), _ptr(fro))
     if rc:
         raise RuntimeError(f"gka_oracle_decode_step failed with code {rc}")

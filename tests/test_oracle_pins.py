@@ -302,6 +302,60 @@ def test_beta_gate_reduces_to_plain_and_scales_writes():
     np.testing.assert_allclose(y2, y3, rtol=1e-12, atol=1e-14)
 
 
+@pytest.mark.parametrize("r", [0, 3, 8])
+def test_single_token_closed_form_with_gates(r):
+    """T = 1, ||k|| = 1, write gate beta, alpha-connection: H_1 = beta k k^T, ||H_1||_F = beta, L = beta + lambda is
+    the top eigenvalue, 1/rho = (beta + 2 lambda) / beta, and along k
+    xhat = (k^T q)(1 - (-1)^{r+1} / T_{r+1}(1/rho)) / (beta + lambda); y_1 = beta v k^T (alpha xhat + (1 - alpha) q)."""
+    rng = np.random.default_rng(120 + r)
+    d = 6
+    k = rng.standard_normal(d); k /= np.linalg.norm(k)
+    q = rng.standard_normal(d)
+    v = rng.standard_normal(d)
+    lam, beta, alpha = 0.21, 0.6, 0.3
+    one = lambda x: np.full((1, 1, 1), x)
+    y = oracle.forward(q.reshape(1, 1, 1, d), k.reshape(1, 1, 1, d), v.reshape(1, 1, 1, d), one(0.8), one(lam), r,
+                       beta=one(beta), alpha=one(alpha))
+    Tn = _cheb_T(r + 1, np.array([(beta + 2 * lam) / beta]))[0]
+    xk = (k @ q) * (1 - (-1) ** (r + 1) / Tn) / (beta + lam)
+    expected = beta * v * (alpha * xk + (1 - alpha) * (k @ q))
+    np.testing.assert_allclose(y.reshape(d), expected, rtol=1e-12, atol=1e-14)
+    # the paper's lambda rule on the same token: lambda = a ||H_1||_F = a beta
+    a = 0.35
+    y2 = oracle.forward(q.reshape(1, 1, 1, d), k.reshape(1, 1, 1, d), v.reshape(1, 1, 1, d), one(0.8), None, r,
+                        beta=one(beta), alpha=one(alpha), lambda_scale=a)
+    Tn2 = _cheb_T(r + 1, np.array([1 + 2 * a]))[0]
+    xk2 = (k @ q) * (1 - (-1) ** (r + 1) / Tn2) / (beta * (1 + a))
+    np.testing.assert_allclose(y2.reshape(d), beta * v * (alpha * xk2 + (1 - alpha) * (k @ q)), rtol=1e-12, atol=1e-14)
+
+
+def test_alpha_connection_interpolates_between_solve_and_linear_attention():
+    """y(alpha) = alpha * y(alpha = 1) + (1 - alpha) * U_t q_t, with U_t q_t summed directly from its definition
+    (gated linear attention), and alpha = 1 is the plain recurrence."""
+    rng = np.random.default_rng(31)
+    B, T, H, d = 1, 9, 2, 5
+    q, k, v, gate, lam = _rand_inputs(rng, B, T, H, d)
+    beta = rng.uniform(0.3, 1.0, (B, T, H))
+    alpha = rng.uniform(0.0, 1.0, (B, T, H))
+    y1 = oracle.forward(q, k, v, gate, lam, 6, beta=beta)
+    np.testing.assert_array_equal(y1, oracle.forward(q, k, v, gate, lam, 6, beta=beta, alpha=np.ones((B, T, H))))
+    ya = oracle.forward(q, k, v, gate, lam, 6, beta=beta, alpha=alpha)
+    for h in range(H):
+        for t in range(T):
+            lin = np.zeros(d)
+            for j in range(t + 1):
+                decay = np.prod(gate[0, j + 1:t + 1, h])
+                lin += decay * beta[0, j, h] * v[0, j, h] * (k[0, j, h] @ q[0, t, h])
+            want = alpha[0, t, h] * y1[0, t, h] + (1 - alpha[0, t, h]) * lin
+            np.testing.assert_allclose(ya[0, t, h], want, rtol=1e-11, atol=1e-13)
+    # decode step: same readout
+    Hs = np.zeros((B, H, d, d)); Us = np.zeros((B, H, d, d))
+    for t in range(T):
+        yd = oracle.decode_step(Hs, Us, q[:, t], k[:, t], v[:, t], gate[:, t], lam[:, t], 6, beta=beta[:, t],
+                                alpha=alpha[:, t])
+        np.testing.assert_allclose(yd, ya[:, t], rtol=1e-12, atol=1e-14)
+
+
 # --------------------------------------------------------------------------------------------
 # Chunk identities of Section 4.2.1 against the step-by-step recurrence
 # --------------------------------------------------------------------------------------------
