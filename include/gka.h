@@ -77,19 +77,30 @@ typedef struct {
                           /*   strides: multiples of 4 elements (of 8 for GKA_COMPUTE_BF16,    */
                           /*   where stride_t must also stay below 2^23); q, k, v, o 16-byte   */
                           /*   aligned                                                          */
+    /* Variants of the layer (Section 4.1 "Adaptive Regularization" and its Remark, Section 4.3). With
+     * lambda_scale = 0 and both pointers NULL the call is Eq. (CH) as printed. */
+    float   lambda_scale; /* a > 0 of lambda_t = a ||H_t||_F; used when the lambda argument is NULL     */
+    int32_t reserved;     /* 0                                                                          */
+    const float *beta;    /* DEVICE pointer or NULL (= 1): write gate beta_t in [0,1] of the            */
+                          /*   beta-augmented recurrence H_t = gamma_t H_{t-1} + beta_t k_t k_t^T,      */
+                          /*   U_t = gamma_t U_{t-1} + beta_t v_t k_t^T; [B,T,H] ([B,H] for decode)     */
+    const float *alpha;   /* DEVICE pointer or NULL (= 1): alpha-connection, the readout becomes        */
+                          /*   y_t = U_t (alpha_t xhat_t + (1 - alpha_t) q_t); same shape as beta       */
 } gka_params;
 
 /* Bytes of scratch gka_forward needs for these parameters (0 if they are invalid). The buffer must
  * be 256-byte aligned. It holds the chunk initial states H_[n], U_[n] of Section 4.2.1 in the
  * operand layout of the solve kernel, for one batch of (batch, head) pairs and one slab of consecutive
  * chunks at a time: large problems are processed as a sequence of such launches, the running states
- * carried from slab to slab in float32, so that the workspace stays bounded (about 1 GiB). Its
- * contents after a call are unspecified. */
+ * carried from slab to slab in float32, so that the workspace stays bounded (about 1 GiB of chunk
+ * states; the environment variable GKA_SLAB_STATE_BYTES, read by this query and by gka_forward,
+ * overrides that budget). Its contents after a call are unspecified. */
 size_t gka_forward_workspace_bytes(const gka_params *p);
 
 /* Whole-sequence forward, Eq. (CH).
  *   q, k     [B,T,H,d_k]  io_dtype           v  [B,T,H,d_v]  io_dtype
- *   gate     [B,T,H] float32, gamma_t        lambda [B,T,H] float32, lambda_t > 0
+ *   gate     [B,T,H] float32, gamma_t        lambda [B,T,H] float32, lambda_t > 0, or NULL with
+ *                                             p->lambda_scale > 0 (lambda_t = lambda_scale ||H_t||_F)
  *   o        [B,T,H,d_v]  io_dtype (written)
  *   H_init   [B,H,d_k,d_k], U_init [B,H,d_v,d_k] float32, or NULL for zero initial states;
  *            gamma of the first token multiplies the initial state
@@ -126,7 +137,7 @@ gka_status gka_forward_profile(const gka_params *p,
 
 /* One recurrent step of Eq. (CH) on stored states (T is ignored).
  *   H_state [B,H,d_k,d_k], U_state [B,H,d_v,d_k] float32, updated IN PLACE
- *   q, k [B,H,d_k], v [B,H,d_v] io_dtype (packed); gate, lambda [B,H] float32
+ *   q, k [B,H,d_k], v [B,H,d_v] io_dtype (packed); gate, lambda [B,H] float32 (lambda NULL as in gka_forward)
  *   o [B,H,d_v] io_dtype (written)
  * The arithmetic is float32 for either compute mode. */
 gka_status gka_decode_step(const gka_params *p,

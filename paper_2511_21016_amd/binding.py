@@ -32,6 +32,8 @@ class GkaParams(ctypes.Structure):
         ("n_iter", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("compute", ctypes.c_int32),
         ("phase", ctypes.c_int32),
         ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
+        ("lambda_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+        ("beta", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
     ]
 
 
@@ -84,10 +86,13 @@ def version():
     return int(load_library().gka_version())
 
 
-def make_params(B, H, T, d, n_iter, io_dtype, compute, chunk=64, d_v=None, strides=(0, 0, 0), phase=0):
+def make_params(B, H, T, d, n_iter, io_dtype, compute, chunk=64, d_v=None, strides=(0, 0, 0), phase=0,
+                lambda_scale=0.0, beta=None, alpha=None):
+    """beta, alpha: device addresses (ints) of the optional per-token gates, or None."""
     return GkaParams(B=B, H=H, T=T, d_k=d, d_v=d if d_v is None else d_v, chunk=chunk, n_iter=n_iter,
                      io_dtype=io_dtype, compute=compute, phase=phase,
-                     stride_b=strides[0], stride_t=strides[1], stride_h=strides[2])
+                     stride_b=strides[0], stride_t=strides[1], stride_h=strides[2],
+                     lambda_scale=lambda_scale, reserved=0, beta=beta, alpha=alpha)
 
 
 def forward_workspace_bytes(params):
@@ -135,10 +140,12 @@ def _ptr(t):
 
 
 def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=None, U_init=None,
-                return_state=False, return_fro=False, workspace=None, out=None, phase=GKA_PHASE_ALL):
+                return_state=False, return_fro=False, workspace=None, out=None, phase=GKA_PHASE_ALL,
+                beta=None, alpha=None, lambda_scale=0.0):
     """gka_forward on torch CUDA tensors: q, k, v [B,T,H,d] (float32 or bfloat16, contiguous),
-    gate, lam [B,T,H] float32. Enqueues on torch's current stream and returns o (and a dict of the
-    requested extras). Nothing here computes: it allocates outputs and passes pointers."""
+    gate, lam [B,T,H] float32 (lam None: lambda_t = lambda_scale * ||H_t||_F); beta, alpha: optional [B,T,H]
+    float32 write gate and alpha-connection. Enqueues on torch's current stream and returns o (and a dict of
+    the requested extras). Nothing here computes: it allocates outputs and passes pointers."""
     import torch
     if not (q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
         raise ValueError("q, k, v must be contiguous CUDA tensors")
@@ -146,7 +153,8 @@ def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=No
     io = _io_dtype(q)
     if compute is None:
         compute = GKA_COMPUTE_BF16 if io == GKA_BF16 else GKA_COMPUTE_F32
-    params = make_params(B, H, T, d, n_iter, io, compute, chunk=chunk, d_v=v.shape[-1], phase=phase)
+    params = make_params(B, H, T, d, n_iter, io, compute, chunk=chunk, d_v=v.shape[-1], phase=phase,
+                         lambda_scale=lambda_scale, beta=_ptr(beta), alpha=_ptr(alpha))
     nbytes = forward_workspace_bytes(params)
     if nbytes == 0:
         # let the library name the error
@@ -169,13 +177,15 @@ def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=No
     return (o, extras) if extras else o
 
 
-def gka_decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None):
+def gka_decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None, beta=None, alpha=None,
+                    lambda_scale=0.0):
     """gka_decode_step on torch CUDA tensors: states [B,H,d,d] float32 (updated in place), q, k, v [B,H,d],
-    gate, lam [B,H] float32."""
+    gate, lam [B,H] float32 (lam None: lambda_scale * ||H||_F); beta, alpha: optional [B,H] float32."""
     import torch
     B, H, d = q.shape
     io = _io_dtype(q)
-    params = make_params(B, H, 1, d, n_iter, io, GKA_COMPUTE_F32)
+    params = make_params(B, H, 1, d, n_iter, io, GKA_COMPUTE_F32, lambda_scale=lambda_scale, beta=_ptr(beta),
+                         alpha=_ptr(alpha))
     o = torch.empty_like(v) if out is None else out
     stream = torch.cuda.current_stream(q.device).cuda_stream
     _check(decode_step_raw(params, _ptr(H_state), _ptr(U_state), _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam),

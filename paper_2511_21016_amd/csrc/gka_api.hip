@@ -53,6 +53,7 @@ gka_status check_common(const gka_params *p, bool decode)
     if (p->io_dtype == GKA_F32 && p->compute == GKA_COMPUTE_BF16) return GKA_ERR_UNSUPPORTED;
     if (!decode && p->chunk != gka::kChunk) return GKA_ERR_UNSUPPORTED;
     if ((int64_t)p->B * p->H > (int64_t)1 << 24) return GKA_ERR_SHAPE;
+    if (!(p->lambda_scale >= 0.0f)) return GKA_ERR_SHAPE;
     return GKA_OK;
 }
 
@@ -155,7 +156,8 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     Plan pl;
     gka_status s = make_plan(p, &pl);
     if (s != GKA_OK) return s;
-    if (!q || !k || !v || !gate || !lambda || !o) return GKA_ERR_NULL;
+    if (!q || !k || !v || !gate || !o) return GKA_ERR_NULL;
+    if (!lambda && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;      // neither lambda_t nor the rule for it
     if ((H_init == nullptr) != (U_init == nullptr)) return GKA_ERR_NULL;
     if ((H_final == nullptr) != (U_final == nullptr)) return GKA_ERR_NULL;
     if (!workspace || workspace_bytes < pl.total || ((uintptr_t)workspace & 255)) return GKA_ERR_WORKSPACE;
@@ -163,7 +165,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     char *ws = (char *)workspace;
 
     gka::StatePassArgs sa;
-    sa.k = k; sa.v = v; sa.gate = gate;
+    sa.k = k; sa.v = v; sa.gate = gate; sa.beta = p->beta;
     sa.H_init = H_init; sa.U_init = U_init;
     sa.H_final = H_final; sa.U_final = U_final;
     sa.ws_H = ws + pl.off_H; sa.ws_U = ws + pl.off_U; sa.ws_hn = (float *)(ws + pl.off_hn);
@@ -174,6 +176,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     sa.init_mode = 0; sa.final_mode = 0; sa.write_frags = 1;
     gka::SolveArgs so;
     so.q = q; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
+    so.beta = p->beta; so.alpha = p->alpha; so.lambda_scale = p->lambda_scale;
     so.ws_H = sa.ws_H; so.ws_U = sa.ws_U; so.ws_hn = sa.ws_hn;
     so.stride_b = pl.stride_b; so.stride_t = pl.stride_t; so.stride_h = pl.stride_h;
     so.H = p->H; so.T = p->T; so.n_iter = p->n_iter;
@@ -259,10 +262,12 @@ gka_status gka_decode_step(const gka_params *p, float *H_state, float *U_state, 
 {
     gka_status s = check_common(p, true);
     if (s != GKA_OK) return s;
-    if (!H_state || !U_state || !q || !k || !v || !gate || !lambda || !o) return GKA_ERR_NULL;
+    if (!H_state || !U_state || !q || !k || !v || !gate || !o) return GKA_ERR_NULL;
+    if (!lambda && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;
     gka::DecodeArgs da;
     da.H_state = H_state; da.U_state = U_state;
     da.q = q; da.k = k; da.v = v; da.gate = gate; da.lambda = lambda; da.o = o;
+    da.beta = p->beta; da.alpha = p->alpha; da.lambda_scale = p->lambda_scale;
     da.n_iter = p->n_iter;
     if (gka::launch_decode_step(da, p->B * p->H, p->d_k, p->io_dtype == GKA_BF16, (hipStream_t)hip_stream) !=
         hipSuccess)
@@ -283,6 +288,6 @@ const char *gka_status_string(gka_status s)
     return "unknown status";
 }
 
-int gka_version(void) { return 100; }
+int gka_version(void) { return 200; }
 
 }  // extern "C"

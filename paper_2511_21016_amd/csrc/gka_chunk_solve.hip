@@ -243,7 +243,9 @@ __device__ __forceinline__ void publish_operand(typename MMA::frag *sX, const ty
 
 // The work of one wave. TW (token block) is a template parameter so that the causal structure (key blocks
 // jt <= TW) is resolved at compile time; fh (feature half) only enters through mt0.
-template <class MMA, class IO, int D, int TW>
+// GATED: the layer's variants (write gate, alpha-connection, lambda_t = a ||H_t||_F) are compiled in; the plain
+// kernel carries none of their loads, registers or branches.
+template <class MMA, class IO, int D, int TW, bool GATED>
 __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned char *smem, int w)
 {
     typedef SolveShape<MMA, D> SH;
@@ -291,6 +293,12 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     // every global read of the prologue is issued here, before the first wait; the gates first: loads return in
     // issue order, and the decay mask below needs nothing else, so it is built while the k rows are on their way
     const float gm = a.gate[gate_base + (int64_t)min(tok0 + lane, a.T - 1) * a.H];
+    // optional inputs: without them a valid array is read instead and the value replaced (no branch around a load)
+    float ball = 1.0f;                          // lane j: write gate beta_j of token j (Remark in Section 4.1)
+    if constexpr (GATED) {
+        const float bm_raw = (a.beta ? a.beta : a.gate)[gate_base + (int64_t)min(tok0 + lane, a.T - 1) * a.H];
+        ball = a.beta ? bm_raw : 1.0f;
+    }
     async_block_copy<H16>(sH, (const frag *)a.ws_H + chunk_id * (SH::H_FRAGS * 64), w, lane);   // H_[n] -> LDS
     RowStage<MMA, IO, D> krows;
     krows.load(a.k, base_bh, a.stride_t, tok0, a.T, tid);
@@ -299,12 +307,14 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4)
             qraw[i][q4] = IO::load_raw4(a.q, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g);
-    lam = a.lambda[gate_base + (int64_t)min(tok, a.T - 1) * a.H];
+    lam = ((!GATED || a.lambda) ? a.lambda : a.gate)[gate_base + (int64_t)min(tok, a.T - 1) * a.H];
     float hn[NB * NB];
 #pragma unroll
     for (int i = 0; i < NB * NB; ++i) hn[i] = a.ws_hn[chunk_id * (NB * NB) + i];
 
     // ---------------- decay mask (Section 4.2.1; log-space form of Appendix B.2, base 2) ----------------
+    // With the write gate, H_c = zeta_c H_[n] + sum_{j<=c} M[j,c] beta_j k_j k_j^T (the same for U): beta_j is folded
+    // into the mask, m[j,c] = M[j,c] beta_j, which every product below uses.
     // every wave scans the chunk's gates itself: no LDS round trip for the per-token decays
     Gall = wave_inclusive_scan((tok0 + lane < a.T) ? log2_gate(gm) : 0.0f, lane);
     const float Gc = __shfl(Gall, c_local, 64);
@@ -316,8 +326,12 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         for (int r = 0; r < 16; ++r) {
             const int j = 32 * jt + kidx(r, g);
             const float Gj = g ? lane_value(Gall, 32 * jt + kidx(r, 1)) : lane_value(Gall, 32 * jt + kidx(r, 0));
-            mreg[jt][r] = (j <= c_local) ? exp2f(Gc - Gj) : 0.0f;
+            float bj = 1.0f;
+            if constexpr (GATED)
+                bj = g ? lane_value(ball, 32 * jt + kidx(r, 1)) : lane_value(ball, 32 * jt + kidx(r, 0));
+            mreg[jt][r] = (j <= c_local) ? (GATED ? bj * exp2f(Gc - Gj) : exp2f(Gc - Gj)) : 0.0f;
         }
+    const float bc = GATED ? __shfl(ball, c_local, 64) : 1.0f;   // write gate of this lane's token
     __builtin_amdgcn_sched_barrier(0);         // the mask is not scheduled behind the wait for the k rows
     GKA_TSTAMP(1);
     krows.store(sRow, tok0, a.T, tid);
@@ -335,10 +349,11 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 
     GKA_TSTAMP(5);
     // ---------------- chunk-wise Frobenius norm ----------------
-    // ||H_c||^2 = zeta_c^2 ||H_[n]||^2 + sum_{j<=c} M[j,c]^2 w_j,
-    // w_j = 2 (zeta_j k_j^T H_[n] k_j + sum_{i<j} M[i,j] G_ij^2) + G_jj^2,  G = K K^T:
+    // ||H_c||^2 = zeta_c^2 ||H_[n]||^2 + sum_{j<=c} m[j,c]^2 w_j,
+    // w_j = 2 (zeta_j k_j^T H_[n] k_j + sum_{i<j} m[i,j] G_ij^2) / beta_j + G_jj^2,  G = K K^T:
     // the three-term expansion of Section 4.2.1 with its double sum over (i, j) folded by
-    // M[i,c] M[j,c] = M[j,c]^2 M[i,j] (i < j).
+    // M[i,c] M[j,c] = M[j,c]^2 M[i,j] (i < j), written with the gated mask m (a token with beta_j = 0 has m[j,.] = 0
+    // and contributes nothing: its w_j is set to 0).
     // Operand sets of the fused contractions: key blocks jt <= TW first, then this wave's row blocks of the state.
     const frag *Aset[NJ + NBH];
 #pragma unroll
@@ -381,8 +396,10 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         b_part += __shfl_xor(b_part, 32, 64);
         d_part += __shfl_xor(d_part, 32, 64);
         lds_barrier();
-        if (fh == 0 && g == 0)
-            sW[c_local] = 2.0f * (zeta * (sA[c_local] + sA[kChunk + c_local]) + b_part) + d_part;
+        if (fh == 0 && g == 0) {
+            const float cross = 2.0f * (zeta * (sA[c_local] + sA[kChunk + c_local]) + b_part);
+            sW[c_local] = GATED ? (bc > 0.0f ? cross / bc + d_part : 0.0f) : cross + d_part;
+        }
     }
     lds_barrier();
     float fro;
@@ -396,6 +413,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         fro = sqrtf(fmaxf(zeta * zeta * hn2 + f_part, 0.0f));
     }
     if (a.fro_out && valid && fh == 0 && g == 0) a.fro_out[gate_base + (int64_t)tok * a.H] = fro;
+    if (GATED && !a.lambda) lam = valid ? a.lambda_scale * fro : 1.0f;      // Section 4.1: lambda_t = a ||H_t||_F
 
     GKA_TSTAMP(6);
     // ---------------- Chebyshev iteration (Algorithm 1), residual form ----------------
@@ -462,7 +480,21 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     const frag *Uw = (const frag *)a.ws_U + chunk_id * (NSPL * SH::H_FRAGS * 64);
     RowStage<MMA, IO, D> vrows;
     vrows.load(a.v, base_bh, a.stride_t, tok0, a.T, tid);
-    // xhat as B operand: the rounded value and, on the bf16 path, the rounding remainder as a second operand
+    // alpha-connection (Section 4.3): the readout is applied to alpha xhat + (1 - alpha) q
+    if (GATED && a.alpha) {
+        const float al = valid ? a.alpha[gate_base + (int64_t)tok * a.H] : 1.0f;
+#pragma unroll
+        for (int i = 0; i < NBH; ++i)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 qv4 = IO::load4(a.q, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    xi[i][4 * q4 + e] = al * xi[i][4 * q4 + e] + (1.0f - al) * (valid ? qv4[e] : 0.0f);
+            }
+    }
+    // the operand of the readout as B operand: the rounded value and, on the bf16 path, the rounding remainder as a
+    // second operand
     frag ownlo[NBH][HS];
 #pragma unroll
     for (int i = 0; i < NBH; ++i)
@@ -534,49 +566,49 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     GKA_TSTAMP(11);
 }
 
-template <class MMA, class IO, int D>
+template <class MMA, class IO, int D, bool GATED>
 __device__ __forceinline__ void chunk_solve_body(const SolveArgs &a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // wave-uniform: token block and feature half of this wave
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (w & 1)
-        chunk_solve_wave<MMA, IO, D, 1>(a, smem, w);
+        chunk_solve_wave<MMA, IO, D, 1, GATED>(a, smem, w);
     else
-        chunk_solve_wave<MMA, IO, D, 0>(a, smem, w);
+        chunk_solve_wave<MMA, IO, D, 0, GATED>(a, smem, w);
 }
 
 // bf16 path: capped at 256 registers so that two workgroups (two waves per SIMD) share a CU.
-template <class IO, int D>
+template <class IO, int D, bool GATED>
 __global__ __launch_bounds__(kSolveThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void chunk_solve_kernel_bf16(
     SolveArgs a)
 {
-    chunk_solve_body<MmaBF16, IO, D>(a);
+    chunk_solve_body<MmaBF16, IO, D, GATED>(a);
 }
 
 // fp32 path: its fragments are twice as large, one workgroup per CU.
-template <class IO, int D>
+template <class IO, int D, bool GATED>
 __global__ __launch_bounds__(kSolveThreads) void chunk_solve_kernel_f32(SolveArgs a)
 {
-    chunk_solve_body<MmaF32, IO, D>(a);
+    chunk_solve_body<MmaF32, IO, D, GATED>(a);
 }
 
-template <class MMA, class IO, int D>
+template <class MMA, class IO, int D, bool GATED>
 struct SolveKernel;
-template <class IO, int D>
-struct SolveKernel<MmaBF16, IO, D> {
-    static constexpr auto fn = chunk_solve_kernel_bf16<IO, D>;
+template <class IO, int D, bool GATED>
+struct SolveKernel<MmaBF16, IO, D, GATED> {
+    static constexpr auto fn = chunk_solve_kernel_bf16<IO, D, GATED>;
 };
-template <class IO, int D>
-struct SolveKernel<MmaF32, IO, D> {
-    static constexpr auto fn = chunk_solve_kernel_f32<IO, D>;
+template <class IO, int D, bool GATED>
+struct SolveKernel<MmaF32, IO, D, GATED> {
+    static constexpr auto fn = chunk_solve_kernel_f32<IO, D, GATED>;
 };
 
-template <class MMA, class IO, int D>
-static hipError_t launch_chunk_solve_t(const SolveArgs &a, int n_pairs, hipStream_t stream)
+template <class MMA, class IO, int D, bool GATED>
+static hipError_t launch_chunk_solve_g(const SolveArgs &a, int n_pairs, hipStream_t stream)
 {
     typedef SolveShape<MMA, D> SH;
-    auto kern = SolveKernel<MMA, IO, D>::fn;
+    auto kern = SolveKernel<MMA, IO, D, GATED>::fn;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)SH::lds_bytes);
     if (e != hipSuccess) return e;
@@ -591,6 +623,13 @@ static hipError_t launch_chunk_solve_t(const SolveArgs &a, int n_pairs, hipStrea
 #endif
     hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
     return hipGetLastError();
+}
+
+template <class MMA, class IO, int D>
+static hipError_t launch_chunk_solve_t(const SolveArgs &a, int n_pairs, hipStream_t stream)
+{
+    if (a.beta || a.alpha || !a.lambda) return launch_chunk_solve_g<MMA, IO, D, true>(a, n_pairs, stream);
+    return launch_chunk_solve_g<MMA, IO, D, false>(a, n_pairs, stream);
 }
 
 hipError_t launch_chunk_solve(const SolveArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,

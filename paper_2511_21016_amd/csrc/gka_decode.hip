@@ -1,5 +1,5 @@
-// One recurrent step of Eq. (CH) per (sequence, head) pair: state update, ||H_t||_F, Algorithm 1 with the
-// matrix held in registers, readout. One workgroup of 256 threads per pair; all arithmetic fp32.
+// One recurrent step of Eq. (CH) per (sequence, head) pair: state update (with the optional write gate), ||H_t||_F,
+// Algorithm 1 with the matrix held in registers, readout (with the optional alpha-connection). One workgroup of 256 threads per pair; all arithmetic fp32.
 //
 // The d x d states are distributed as float4 pieces in flat row-major order, piece (it*256 + t) on thread
 // t, so that state reads and writes are fully coalesced: thread t holds, for each of its ITS pieces, row
@@ -34,7 +34,8 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
         s_v[t] = IO::load(a.v, (int64_t)pair * D + t);
     }
     const float gamma = a.gate[pair];
-    const float lam = a.lambda[pair];
+    const float beta = a.beta ? a.beta[pair] : 1.0f;        // write gate (Remark in Section 4.1)
+    const float alpha = a.alpha ? a.alpha[pair] : 1.0f;     // alpha-connection (Section 4.3)
     f32x4 hreg[ITS], ureg[ITS];
 #pragma unroll
     for (int it = 0; it < ITS; ++it) {
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
 #pragma unroll
     for (int it = 0; it < ITS; ++it) {
         const int row = it * RPI + rgrp;
-        const float kr = s_k[row], vr = s_v[row];
+        const float kr = beta * s_k[row], vr = beta * s_v[row];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             hreg[it][e] = gamma * hreg[it][e] + kr * kc[e];
@@ -65,6 +66,7 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
     if ((t & 63) == 0) s_red[t >> 6] = ss;
     __syncthreads();
     const float fro = sqrtf(s_red[0] + s_red[1] + s_red[2] + s_red[3]);
+    const float lam = a.lambda ? a.lambda[pair] : a.lambda_scale * fro;   // Section 4.1: lambda_t = a ||H_t||_F
 
     // ---- Algorithm 1 in residual form; thread j < D owns component j of xi, delta, r
     const float L = fro + lam, mu = lam;
@@ -103,8 +105,9 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
         __syncthreads();
     }
 
-    // ---- readout y = U xhat (rows of U are not symmetric: reduce each row over its C4 lanes)
-    if (t < D) s_x[t] = xi;
+    // ---- readout y = U (alpha xhat + (1 - alpha) q) (rows of U are not symmetric: reduce each row over its C4
+    // lanes)
+    if (t < D) s_x[t] = alpha * xi + (1.0f - alpha) * s_q[t];
     __syncthreads();
     float xc[4];
 #pragma unroll

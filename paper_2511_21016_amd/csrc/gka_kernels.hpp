@@ -10,6 +10,7 @@ constexpr int kChunk = 64;   // chunk size C of Section 4.2.1
 struct StatePassArgs {
     const void *k, *v;            // [B,T,H,d] tensors (element strides below)
     const float *gate;            // [B,T,H]
+    const float *beta;            // [B,T,H] write gate or nullptr (= 1)
     const float *H_init, *U_init; // [pairs,d,d] or nullptr
     float *H_final, *U_final;     // [pairs,d,d] or nullptr
     void *ws_H, *ws_U;            // chunk initial states, fragment order
@@ -32,7 +33,9 @@ struct StatePassArgs {
 
 struct SolveArgs {
     const void *q, *k, *v;
-    const float *gate, *lambda;
+    const float *gate, *lambda;   // lambda nullptr: lambda_t = lambda_scale ||H_t||_F
+    const float *beta, *alpha;    // [B,T,H] write gate / alpha-connection, each nullptr (= 1)
+    float lambda_scale;
     void *o;
     float *fro_out;               // [B,T,H] or nullptr
     const void *ws_H, *ws_U;
@@ -47,7 +50,9 @@ struct SolveArgs {
 struct DecodeArgs {
     float *H_state, *U_state;     // [pairs,d,d], in place
     const void *q, *k, *v;        // [pairs,d]
-    const float *gate, *lambda;   // [pairs]
+    const float *gate, *lambda;   // [pairs]; lambda nullptr: lambda = lambda_scale ||H||_F
+    const float *beta, *alpha;    // [pairs] or nullptr (= 1)
+    float lambda_scale;
     void *o;                      // [pairs,d]
     int n_iter;
 };

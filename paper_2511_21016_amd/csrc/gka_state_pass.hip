@@ -90,7 +90,7 @@ __device__ __forceinline__ void store_end_state(const StatePassArgs &a, const f3
 // DOH: this workgroup owns the H slab (else the U slab); WRITE: chunk states are written to the workspace. Both are
 // compile-time so that the chunk loop is straight-line code and the in-flight prefetches are never drained by a
 // conservative wait.
-template <class MMA, class IO, int D, bool DOH, bool WRITE>
+template <class MMA, class IO, int D, bool DOH, bool WRITE, bool GATED>
 __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, int group,
                                                 typename MMA::elem_t *s_k, typename MMA::elem_t *s_v)
 {
@@ -150,8 +150,10 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
     // divergent branch around a load would force a wait on it) and zeroed when they are stored to LDS.
     struct Fetch {
         typename IO::raw4 k[KP], v[VP];
-        float gate;
+        float gate, beta;
     };
+    // without a write gate the gates are read a second time and the value is replaced by 1: no branch around a load
+    const float *beta_src = a.beta ? a.beta : a.gate;
     auto fetch = [&](Fetch &f, int c) {
 #pragma unroll
         for (int i = 0; i < KP; ++i) {
@@ -171,18 +173,20 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
         }
         const int t = min(c * kChunk + lane, a.T - 1);
         f.gate = a.gate[gate_base + (int64_t)t * a.H];
+        if constexpr (GATED) f.beta = beta_src[gate_base + (int64_t)t * a.H];
     };
     float Gseg = 0.0f;
 
     auto process = [&](const Fetch &f, int c) {
         const bool stamp = (c == chunk_begin + 20);
         if (stamp) GKA_STSTAMP(1);
-        // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights 2^(G_C - G_j)
+        // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights beta_j 2^(G_C - G_j)
         const float lg = (c * kChunk + lane < a.T) ? log2_gate(f.gate) : 0.0f;
         const float G = wave_inclusive_scan(lg, lane);
         const float Gtot = lane_value(G, 63);
         Gseg += Gtot;
-        const float swd = exp2f(0.5f * (Gtot - G));   // lane j: sqrt(zeta_C / zeta_j)
+        float swd = exp2f(0.5f * (Gtot - G));          // lane j: sqrt(beta_j zeta_C / zeta_j)
+        if constexpr (GATED) swd *= sqrtf(a.beta ? f.beta : 1.0f);
         if (stamp) GKA_STSTAMP(2);
         lds_barrier();                          // previous chunk's LDS readers are done
         if (stamp) GKA_STSTAMP(3);
@@ -387,7 +391,7 @@ __device__ __forceinline__ uint32_t lds_address(const void *p)
 //     rows (H) or v rows (U) are prefetched into registers, scaled and stored to a small padded tile.
 // Vector-memory operations of one wave complete in issue order, so "the copy of chunk c has landed" is a counted
 // wait: every iteration issues, in this order, NA copies, NS state stores, [wait], NL prefetch loads.
-template <class IO, int D, bool DOH, bool WRITE>
+template <class IO, int D, bool DOH, bool WRITE, bool GATED>
 __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int rb, int group, uint16_t *s_k,
                                                      uint16_t *s_b)
 {
@@ -407,7 +411,7 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
     constexpr int VP = kChunk * 8 / NT;           // 4-element pieces of the B tile per thread
     constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
     constexpr int NS = WRITE ? (DOH ? HS + 1 : HS * NSPL) : 0;   // state stores per chunk
-    constexpr int NL = VP + 1;                    // prefetch loads per chunk
+    constexpr int NL = VP + (GATED ? 2 : 1);      // prefetch loads per chunk (B pieces, gate, write gate)
     typedef SwizzledRows<ROWB, 2> KRows;
 
     const int tid = threadIdx.x;
@@ -446,8 +450,11 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
     };
     struct Fetch {
         typename IO::raw4 b[VP];
-        float gate;
+        float gate, beta;
     };
+    // GATED without a write gate: the gates are read a second time and the value is replaced by 1, so that the
+    // number of loads per iteration is fixed
+    const float *beta_src = a.beta ? a.beta : a.gate;
     auto fetch = [&](Fetch &f, int c) {
 #pragma unroll
         for (int i = 0; i < VP; ++i) {
@@ -457,6 +464,7 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
         }
         const int t = min(c * kChunk + lane, a.T - 1);
         f.gate = a.gate[gate_base + (int64_t)t * a.H];
+        if constexpr (GATED) f.beta = beta_src[gate_base + (int64_t)t * a.H];
     };
     float Gseg = 0.0f;
     int kb = 0;                                   // buffer that holds the chunk being processed
@@ -474,13 +482,14 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
         __builtin_amdgcn_sched_barrier(0);
         const bool stamp = (c == chunk_begin + 20);
         if (stamp) GKA_STSTAMP(1);
-        // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights zeta_C / zeta_j = 2^(G_C - G_j)
+        // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights beta_j zeta_C / zeta_j = beta_j 2^(G_C - G_j)
         const bool valid = c * kChunk + lane < a.T;
         const float lg = valid ? log2_gate(f.gate) : 0.0f;
         const float G = wave_inclusive_scan(lg, lane);
         const float Gtot = lane_value(G, 63);
         Gseg += Gtot;
-        const float wj = valid ? exp2f(Gtot - G) : 0.0f;     // lane j: weight of token j
+        float wj = valid ? exp2f(Gtot - G) : 0.0f;     // lane j: weight of token j
+        if constexpr (GATED) wj *= a.beta ? f.beta : 1.0f;
         const float zetaC = exp2f(Gtot);
         if (stamp) GKA_STSTAMP(2);
         lds_barrier();                          // the previous chunk's operand reads are done
@@ -579,7 +588,7 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
     store_end_state<D, DOH>(a, acc, Gseg, pair, seg, rb, w, lane);
 }
 
-template <class MMA, class IO, int D>
+template <class MMA, class IO, int D, bool GATED>
 __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE_WAVES))) void state_pass_kernel(StatePassArgs a)
 {
     constexpr int NB = D / 32;
@@ -606,25 +615,25 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
     __shared__ __attribute__((aligned(16))) elem_t s_v[kChunk * (32 + MMA::kRowPad)];
     if constexpr (kDirect) {
         if (a.write_frags) {
-            if (sub & 1) state_pass_body_bf16<IO, D, false, true>(a, rb, group, s_k, s_v);
-            else state_pass_body_bf16<IO, D, true, true>(a, rb, group, s_k, s_v);
+            if (sub & 1) state_pass_body_bf16<IO, D, false, true, GATED>(a, rb, group, s_k, s_v);
+            else state_pass_body_bf16<IO, D, true, true, GATED>(a, rb, group, s_k, s_v);
         } else {
-            if (sub & 1) state_pass_body_bf16<IO, D, false, false>(a, rb, group, s_k, s_v);
-            else state_pass_body_bf16<IO, D, true, false>(a, rb, group, s_k, s_v);
+            if (sub & 1) state_pass_body_bf16<IO, D, false, false, GATED>(a, rb, group, s_k, s_v);
+            else state_pass_body_bf16<IO, D, true, false, GATED>(a, rb, group, s_k, s_v);
         }
     } else {
         if (a.write_frags) {
-            if (sub & 1) state_pass_body<MMA, IO, D, false, true>(a, rb, group, s_k, s_v);
-            else state_pass_body<MMA, IO, D, true, true>(a, rb, group, s_k, s_v);
+            if (sub & 1) state_pass_body<MMA, IO, D, false, true, GATED>(a, rb, group, s_k, s_v);
+            else state_pass_body<MMA, IO, D, true, true, GATED>(a, rb, group, s_k, s_v);
         } else {
-            if (sub & 1) state_pass_body<MMA, IO, D, false, false>(a, rb, group, s_k, s_v);
-            else state_pass_body<MMA, IO, D, true, false>(a, rb, group, s_k, s_v);
+            if (sub & 1) state_pass_body<MMA, IO, D, false, false, GATED>(a, rb, group, s_k, s_v);
+            else state_pass_body<MMA, IO, D, true, false, GATED>(a, rb, group, s_k, s_v);
         }
     }
 }
 
-template <class MMA, class IO, int D>
-static hipError_t launch_state_pass_t(const StatePassArgs &a0, int n_pairs, hipStream_t stream)
+template <class MMA, class IO, int D, bool GATED>
+static hipError_t launch_state_pass_g(const StatePassArgs &a0, int n_pairs, hipStream_t stream)
 {
     constexpr int NB = D / 32;
     dim3 block(D * 2);
@@ -638,7 +647,7 @@ static hipError_t launch_state_pass_t(const StatePassArgs &a0, int n_pairs, hipS
         a.init_mode = 0;
         a.final_mode = 2;
         a.write_frags = 0;
-        hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * 2 * NB * (a.n_segs - 1)), block, 0, stream, a);
+        hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D, GATED>), dim3(n_pairs * 2 * NB * (a.n_segs - 1)), block, 0, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -646,8 +655,16 @@ static hipError_t launch_state_pass_t(const StatePassArgs &a0, int n_pairs, hipS
     a.init_mode = 1;
     a.final_mode = 1;
     a.write_frags = 1;
-    hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D>), dim3(n_pairs * 2 * NB * a.n_segs), block, 0, stream, a);
+    hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D, GATED>), dim3(n_pairs * 2 * NB * a.n_segs), block, 0, stream, a);
     return hipGetLastError();
+}
+
+template <class MMA, class IO, int D>
+static hipError_t launch_state_pass_t(const StatePassArgs &a, int n_pairs, hipStream_t stream)
+{
+    // the write gate is the only variant of the layer that reaches this kernel
+    if (a.beta) return launch_state_pass_g<MMA, IO, D, true>(a, n_pairs, stream);
+    return launch_state_pass_g<MMA, IO, D, false>(a, n_pairs, stream);
 }
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,

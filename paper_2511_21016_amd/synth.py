@@ -119,6 +119,17 @@ def make_inputs(w):
     return draw_tokens(rng, w, w.B, w.T)
 
 
+def make_gates(w, T=None, seed_offset=5000):
+    """Optional per-token gates of the layer's variants, [B,T,H] float32 each, both in (0, 1) as sigmoid
+    outputs: beta (write gate of the beta-augmented recurrence) and alpha (alpha-connection)."""
+    rng = np.random.default_rng(w.seed + seed_offset)
+    T = w.T if T is None else T
+    sig = lambda z: 1.0 / (1.0 + np.exp(-z))
+    beta = sig(rng.normal(1.0, 1.0, (w.B, T, w.H))).astype(np.float32)
+    alpha = sig(rng.normal(1.0, 1.0, (w.B, T, w.H))).astype(np.float32)
+    return {"beta": beta, "alpha": alpha}
+
+
 def make_decode_tokens(w, n_steps, seed_offset=1000):
     """Single-token inputs for n_steps decode steps: arrays [n_steps, B, H, d] / [n_steps, B, H]."""
     rng = np.random.default_rng(w.seed + seed_offset)

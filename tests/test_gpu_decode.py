@@ -35,3 +35,29 @@ def test_decode_steps_from_oracle_prefill(d, dtype):
         assert err.max() <= tol, (s, err.max())
     np.testing.assert_allclose(to_host(Hd), Hs, rtol=0, atol=1e-5 * np.abs(Hs).max())
     np.testing.assert_allclose(to_host(Ud), Us, rtol=0, atol=1e-5 * np.abs(Us).max())
+
+
+@pytest.mark.parametrize("d,dtype", [(128, "f32"), (64, "bf16")])
+def test_decode_layer_variants(d, dtype):
+    """Write gate, alpha-connection and lambda = a ||H||_F together, stepping from zero states."""
+    import torch
+    base = synth.CFG5 if dtype == "bf16" else synth.CFG1
+    w = base.scaled(B=2, H=3, T=1, d=d, n_iter=7, seed=77 + d)
+    n_steps = 10
+    steps = synth.make_decode_tokens(w, n_steps)
+    gates = synth.make_gates(w, T=n_steps)                      # [B, n_steps, H]
+    Hs = np.zeros((w.B, w.H, d, d)); Us = np.zeros((w.B, w.H, d, d))
+    Hd, Ud = to_device(Hs.astype(np.float32), "f32"), to_device(Us.astype(np.float32), "f32")
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+    for s in range(n_steps):
+        q, k, v = (to_device(steps[n][s], dtype) for n in ("q", "k", "v"))
+        beta, alpha = np.ascontiguousarray(gates["beta"][:, s]), np.ascontiguousarray(gates["alpha"][:, s])
+        o = binding.gka_decode_step(Hd, Ud, q, k, v, to_device(steps["gate"][s], "f32"), None, w.n_iter,
+                                    beta=to_device(beta, "f32"), alpha=to_device(alpha, "f32"), lambda_scale=0.05)
+        torch.cuda.synchronize()
+        ref = oracle.decode_step(Hs, Us, steps["q"][s], steps["k"][s], steps["v"][s], steps["gate"][s], None,
+                                 w.n_iter, beta=beta, alpha=alpha, lambda_scale=0.05)
+        y = to_host(o)
+        err = np.abs(y - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
+        assert err.max() <= tol, (s, err.max())
+    np.testing.assert_allclose(to_host(Hd), Hs, rtol=0, atol=2e-5 * np.abs(Hs).max())

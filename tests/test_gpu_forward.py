@@ -135,3 +135,48 @@ def test_explicit_strides_head_major_layout(compute, d):
     ref = oracle_forward(w, x)
     y = np.transpose(to_host(o), (0, 2, 1, 3))
     assert pair_rel_err(y, ref) <= TOL_BF16
+
+
+VARIANTS = {
+    "beta": dict(beta=True),
+    "alpha": dict(alpha=True),
+    "lambda_rule": dict(rule=True),
+    "all": dict(beta=True, alpha=True, rule=True),
+}
+
+
+@pytest.mark.parametrize("which", sorted(VARIANTS))
+@pytest.mark.parametrize("dtype,compute,d", [("f32", "f32", 64), ("f32", "f32", 128), ("bf16", "bf16", 128),
+                                             ("bf16", "bf16", 64), ("bf16", "f32", 128)])
+def test_layer_variants(which, dtype, compute, d):
+    """Write gate beta_t, alpha-connection and the rule lambda_t = a ||H_t||_F (a = 0.02, the paper's default),
+    one at a time and together, on a ragged multi-chunk sequence."""
+    import torch
+    sel = VARIANTS[which]
+    base = synth.CFG1 if dtype == "f32" else synth.CFG2
+    w = base.scaled(B=2, H=2, T=300, d=d, n_iter=8, seed=50 + d)
+    x = synth.make_inputs(w)
+    gates = synth.make_gates(w)
+    beta = gates["beta"] if sel.get("beta") else None
+    alpha = gates["alpha"] if sel.get("alpha") else None
+    # a few tokens write nothing at all
+    if beta is not None:
+        beta = beta.copy()
+        beta[:, 5::37] = 0.0
+    a = 0.02 if sel.get("rule") else 0.0
+    dev = upload_inputs(x, w.dtype)
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    o, ex = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], None if a else dev["lam"], w.n_iter,
+                                compute=cm, beta=None if beta is None else to_device(beta, "f32"),
+                                alpha=None if alpha is None else to_device(alpha, "f32"), lambda_scale=a,
+                                return_fro=True, return_state=True)
+    torch.cuda.synchronize()
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], None if a else x["lam"], w.n_iter, beta=beta,
+                              alpha=alpha, lambda_scale=a, return_fro=True, return_state=True)
+    tol = TOL_F32 if compute == "f32" and dtype == "f32" else TOL_BF16
+    err = pair_rel_err(to_host(o), ref)
+    assert err <= tol, err
+    ftol = 1e-5 if dtype == "f32" else 5e-3
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= ftol * rex["fro"].max()
+    stol = 2e-5 if compute == "f32" else 5e-3
+    assert np.abs(to_host(ex["U_final"]) - rex["U_final"]).max() <= stol * np.abs(rex["U_final"]).max()

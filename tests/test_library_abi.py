@@ -75,6 +75,10 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(_p(strides=(1 << 40, 1 << 23, 128))) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(), q=None) == binding.GKA_ERR_NULL
     assert fwd(_p(), gate=None) == binding.GKA_ERR_NULL
+    # lambda may be NULL only together with the rule lambda_t = lambda_scale ||H_t||_F
+    assert binding.forward_raw(_p(), fake, fake, fake, fake, None, fake, workspace=0x100000,
+                               workspace_bytes=ok_ws) == binding.GKA_ERR_NULL
+    assert fwd(_p(lambda_scale=-1.0)) == binding.GKA_ERR_SHAPE
     assert fwd(_p(), H_init=fake) == binding.GKA_ERR_NULL                        # H_init without U_init
     assert fwd(_p(), ws=None) == binding.GKA_ERR_WORKSPACE
     assert fwd(_p(), ws_bytes=ok_ws - 1) == binding.GKA_ERR_WORKSPACE
