@@ -180,3 +180,30 @@ def test_layer_variants(which, dtype, compute, d):
     assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= ftol * rex["fro"].max()
     stol = 2e-5 if compute == "f32" else 5e-3
     assert np.abs(to_host(ex["U_final"]) - rex["U_final"]).max() <= stol * np.abs(rex["U_final"]).max()
+
+
+@pytest.mark.parametrize("dtype,compute,lam_min", [("f32", "f32", 1e-4), ("bf16", "f32", 1e-4), ("bf16", "bf16", 1e-2)])
+def test_degenerate_values(dtype, compute, lam_min):
+    """Zero keys (H_t stays 0 for a while), zero queries and values, gates of exactly 1 and gates so small that the
+    whole past is forgotten within a token, lambda over many decades, many passes: finite outputs and parity.
+    With bf16 operands lambda starts at 1e-2: below that the first tokens (rank-one H_t) have |xhat| a thousand times
+    |y|, which is the regime the fp32-operand mode exists for."""
+    base = synth.CFG1 if dtype == "f32" else synth.CFG2
+    w = base.scaled(B=1, H=4, T=200, d=64, n_iter=40, seed=91)
+    x = {n: a.copy() for n, a in synth.make_inputs(w).items()}
+    x["k"][:, :70, 0] = 0.0                    # head 0: nothing written for the first 70 tokens
+    x["q"][:, 100:110, 1] = 0.0
+    x["v"][:, 120:130, 1] = 0.0
+    x["gate"][:, :, 2] = 1.0                   # head 2: no forgetting
+    x["gate"][:, 50::17, 3] = 1e-30            # head 3: hard resets (log2 below the documented floor of exp(-100))
+    x["gate"][:, 90, 3] = 0.999
+    lam = np.geomspace(lam_min, 1e4, w.T).astype(np.float32)
+    x["lam"][:] = lam[None, :, None]
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    o, ex = run_forward(w, x, compute=cm, return_fro=True)
+    y = to_host(o)
+    assert np.isfinite(y).all()
+    ref, rex = oracle_forward(w, x, return_fro=True)
+    err = pair_rel_err(y, ref)
+    assert err <= (TOL_F32 if dtype == "f32" else TOL_BF16), err
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= (1e-5 if dtype == "f32" else 5e-3) * rex["fro"].max()
