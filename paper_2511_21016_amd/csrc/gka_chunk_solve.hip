@@ -70,12 +70,30 @@ struct SolveShape {
     static constexpr size_t lds_bytes = h_bytes + k_bytes + kt_bytes + x_bytes;
 };
 
+// Calls fill(std::integral_constant<int, s>) for the (unrolled, hence constant) step s of N.
+template <int N, class Fill, int S = 0>
+__device__ __forceinline__ void fill_step(Fill &fill, int s)
+{
+    if constexpr (S < N) {
+        if (s == S) fill(std::integral_constant<int, S>{});
+        else fill_step<N, Fill, S + 1>(fill, s);
+    }
+}
+
 // acc[a] += sum_s A[a][s] * B[s] over NSTEPS contraction steps; all operands are LDS fragment arrays
 // (fragment s of a set at [s * 64 + lane]). The fragments of step s + 1 are requested before the MFMAs of
-// step s are issued, so LDS latency is paid once per call, not once per MFMA.
-template <class MMA, int NSTEPS, int NA>
+// step s are issued, so LDS latency is paid once per call, not once per MFMA. `fill(step)` is called once per
+// step with the step as a compile-time constant: independent vector-ALU work of the caller that is issued between
+// the MFMAs, where the wave would otherwise wait for the matrix pipe.
+struct NoFill {
+    template <class S>
+    __device__ __forceinline__ void operator()(S) const {}
+};
+// N_FROM_ZERO: the first N_FROM_ZERO accumulators start from zero (their incoming values are ignored): the first MFMA of each
+// takes a constant zero as its C operand, which costs no instruction, instead of sixteen register moves.
+template <class MMA, int NSTEPS, int NA, class Fill = NoFill, int N_FROM_ZERO = 0>
 __device__ __forceinline__ void fused_gemm(const typename MMA::frag *const (&A)[NA], const typename MMA::frag *B,
-                                           f32x16 (&acc)[NA], int lane)
+                                           f32x16 (&acc)[NA], int lane, Fill fill = Fill())
 {
     typename MMA::frag abuf[2][NA], bbuf[2];
 #pragma unroll
@@ -91,7 +109,9 @@ __device__ __forceinline__ void fused_gemm(const typename MMA::frag *const (&A)[
         }
         __builtin_amdgcn_sched_barrier(0);     // keep the requests for step s + 1 ahead of the MFMAs of step s
 #pragma unroll
-        for (int x = 0; x < NA; ++x) acc[x] = MMA::mma(abuf[cur][x], bbuf[cur], acc[x]);
+        for (int x = 0; x < NA; ++x)
+            acc[x] = MMA::mma(abuf[cur][x], bbuf[cur], (s == 0 && x < N_FROM_ZERO) ? zero16() : acc[x]);
+        fill_step<NSTEPS>(fill, s);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -434,8 +454,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
             for (int e = 0; e < 4; ++e) {
                 const float qv = valid ? qv4[e] : 0.0f;
                 gI[i][4 * q4 + e] = -qv;
-                xi[i][4 * q4 + e] = s0 * qv;      // xi_0 = 2 q / (L + mu); delta_0 = xi_0 - xi_{-1} = xi_0
-                dl[i][4 * q4 + e] = s0 * qv;
+                dl[i][4 * q4 + e] = s0 * qv;      // delta_0 = xi_0 - xi_{-1} = xi_0 = 2 q / (L + mu)
             }
         }
 #pragma unroll
@@ -443,36 +462,66 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     }
     const frag *myX = sX + (TW * NSTEPS) * 64;         // this token block's operand in the exchange region
     float omega = 2.0f;
+    // xi lags one update behind: xi += delta is applied while the next pass's first sweep runs (and once after the
+    // last pass), so it starts from xi_{-1} = 0
+#pragma unroll
+    for (int i = 0; i < NBH; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xi[i][r] = 0.0f;
     lds_barrier();                           // sW, sA are dead: the region becomes the operand exchange
     for (int it = 0; it < a.n_iter; ++it) {
         // operands are re-read from LDS in every pass (they are not kept in registers across passes)
         asm volatile("" ::: "memory");
         publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
         lds_barrier();
-        // two sweeps over the D features of delta: P = K delta^T (key blocks jt <= TW), then the state product
+        // Two sweeps over the D features of delta: P = K delta^T (key blocks jt <= TW), then the state product.
+        // Vector-ALU work of the pass that does not depend on the sweep in flight is issued between its MFMAs:
+        // xi += delta during the first sweep, the masking of P during the second.
         f32x16 pacc[NJ];
+        auto add_delta = [&](auto step) {
+            constexpr int S = decltype(step)::value;
+            constexpr int TOTAL = NBH * 16, PER = (TOTAL + NSTEPS - 1) / NSTEPS;
 #pragma unroll
-        for (int jt = 0; jt < NJ; ++jt) pacc[jt] = zero16();
-        fused_gemm<MMA, NSTEPS, NJ>(Kset, myX, pacc, lane);
-        fused_gemm<MMA, NSTEPS, NBH>(Hset, myX, gS, lane);
-        lds_barrier();                       // the exchange region may be overwritten from here on
+            for (int e = 0; e < PER; ++e) {
+                const int idx = S * PER + e;
+                if (idx < TOTAL) xi[idx / 16][idx % 16] += dl[idx / 16][idx % 16];
+            }
+        };
+        fused_gemm<MMA, NSTEPS, NJ, decltype(add_delta), NJ>(Kset, myX, pacc, lane, add_delta);
         frag pm[NJ][HS];
-        mask_p<MMA, TW>(pacc, mreg, pm);
+        fused_gemm<MMA, NSTEPS, NBH>(Hset, myX, gS, lane, [&](auto step) {
+            constexpr int S = decltype(step)::value;
+            if constexpr (S < NJ * HS) {
+                constexpr int jt = S / HS, hh = S % HS;
+                float t[VEC];
+#pragma unroll
+                for (int p = 0; p < VEC; ++p) t[p] = pacc[jt][hh * VEC + p] * mreg[jt][hh * VEC + p];
+                pm[jt][hh] = MMA::pack(t);
+            }
+        });
+        lds_barrier();                       // the exchange region may be overwritten from here on
         gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, gI, lane);
         omega = 4.0f / (4.0f - rho2 * omega);                      // weight schedule
         const float cm = omega - 1.0f, ncs = -omega * s0;
+        // -r_{i-1} = zeta gS + gI + lam xi; delta_i = cm delta_{i-1} - omega s0 r... : everything but the gI term is
+        // formed while the MFMAs that finish gI are in flight
+        const float ncz = ncs * zeta, ncl = ncs * lam;
+#pragma unroll
+        for (int i = 0; i < NBH; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dl[i][r] = cm * dl[i][r] + ncz * gS[i][r] + ncl * xi[i][r];
 #pragma unroll
         for (int i = 0; i < NBH; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float nres = zeta * gS[i][r] + gI[i][r] + lam * xi[i][r];   // -r_{i-1}
-                dl[i][r] = cm * dl[i][r] + ncs * nres;                            // delta_i
-                xi[i][r] += dl[i][r];                                             // xi_i
-            }
+            for (int r = 0; r < 16; ++r) dl[i][r] += ncs * gI[i][r];                     // delta_i
 #pragma unroll
             for (int hh = 0; hh < HS; ++hh) own[i][hh] = MMA::pack(&dl[i][hh * VEC]);
         }
     }
+#pragma unroll
+    for (int i = 0; i < NBH; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xi[i][r] += dl[i][r];                               // xi_r
 
     GKA_TSTAMP(7);
     // ---------------- readout y_c = zeta_c U_[n] xhat_c + sum_{j<=c} M[j,c] v_j (k_j . xhat_c) ----------------
