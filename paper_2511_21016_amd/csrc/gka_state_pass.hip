@@ -37,6 +37,10 @@ extern "C" int gka_debug_read_state_timers(unsigned long long *host)
 #define GKA_STSTAMP(i) do {} while (0)
 #endif
 
+// k-row buffers of the bf16 body: the copy of a chunk's rows is issued GKA_STATE_KBUFS - 1 chunks ahead of its use
+#ifndef GKA_STATE_KBUFS
+#define GKA_STATE_KBUFS 3
+#endif
 #ifndef GKA_STATE_WAVES
 #define GKA_STATE_WAVES 2          // waves per SIMD the state-pass kernel is compiled for (register cap)
 #endif
@@ -405,6 +409,9 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
     constexpr int RSB = 32 + MMA::kRowPad;        // row stride of the B tile
     constexpr int ROWB = D * 2;                   // bytes per k row
     constexpr int KBUF = kChunk * D;              // elements per k buffer
+    constexpr int NKB = GKA_STATE_KBUFS;          // k buffers
+    constexpr int PD = NKB - 1;                   // chunks between the issue of a copy and its use
+    static_assert(NKB >= 2 && NKB <= 3, "two or three buffers");
     constexpr int NA = kChunk * ROWB / (NT * 16); // 16-byte copies per thread per chunk
     constexpr int LPR = ROWB / 16;                // lanes (16-byte pieces) per row
     constexpr int RPI = 64 / LPR;                 // rows per wave-wide copy instruction
@@ -494,8 +501,8 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
         if (stamp) GKA_STSTAMP(2);
         lds_barrier();                          // the previous chunk's operand reads are done
         if (stamp) GKA_STSTAMP(3);
-        const int kb2 = kb >= 1 ? kb - 1 : 2;   // (kb + 2) % 3: the previous chunk's buffer
-        issue_k(min(c + 2, c_last), kb2);
+        const int kb2 = kb >= 1 ? kb - 1 : NKB - 1;   // (kb + PD) % NKB: the previous chunk's buffer
+        issue_k(min(c + PD, c_last), kb2);
 #pragma unroll
         for (int i = 0; i < VP; ++i) {
             const int piece = i * NT + tid;
@@ -540,9 +547,9 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
             }
         }
         if (stamp) GKA_STSTAMP(5);
-        // This chunk's copy was issued two iterations ago; since then the wave has issued at least the copies and
-        // stores of this and the previous iteration and the prefetch loads of the previous one.
-        wait_vector_memory_upto<2 * NA + 2 * NS + NL>();
+        // This chunk's copy was issued PD iterations ago, right after a barrier. Since then the wave has issued at
+        // least PD - 1 whole iterations (copies, stores, prefetch loads) and this iteration's copies and stores.
+        wait_vector_memory_upto<(PD - 1) * (NA + NS + NL) + NA + NS>();
         lds_barrier();                          // k rows (all waves' copies) and the B tile are visible
         if (stamp) GKA_STSTAMP(6);
 
@@ -553,7 +560,7 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
         for (int r = 0; r < 16; ++r) acc[r] *= zetaC;
 #pragma unroll
         for (int s = 0; s < STEPS; ++s) acc = MMA::mma(fa[s], fb[s], acc);
-        kb = kb == 2 ? 0 : kb + 1;
+        kb = kb == NKB - 1 ? 0 : kb + 1;
         if (stamp) GKA_STSTAMP(7);
     };
 
@@ -562,7 +569,7 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
     GKA_STSTAMP(0);
     int c = chunk_begin;
     issue_k(c, 0);
-    issue_k(min(c + 1, c_last), 1);
+    if (PD > 1) issue_k(min(c + 1, c_last), 1);
     if ((chunk_end - chunk_begin) & 1) {
         Fetch fp;
         fetch(fp, c);
@@ -611,7 +618,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
     const int rb = sub >> 1;                       // slab index (row block of H0 / U0)
     typedef typename MMA::elem_t elem_t;
     constexpr bool kDirect = std::is_same<MMA, MmaBF16>::value;    // k rows copied straight into LDS
-    __shared__ __attribute__((aligned(1024))) elem_t s_k[kDirect ? 3 * kChunk * D : kChunk * (D + MMA::kRowPad)];
+    __shared__ __attribute__((aligned(1024))) elem_t s_k[kDirect ? GKA_STATE_KBUFS * kChunk * D : kChunk * (D + MMA::kRowPad)];
     __shared__ __attribute__((aligned(16))) elem_t s_v[kChunk * (32 + MMA::kRowPad)];
     if constexpr (kDirect) {
         if (a.write_frags) {
