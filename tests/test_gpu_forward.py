@@ -207,3 +207,19 @@ def test_degenerate_values(dtype, compute, lam_min):
     err = pair_rel_err(y, ref)
     assert err <= (TOL_F32 if dtype == "f32" else TOL_BF16), err
     assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= (1e-5 if dtype == "f32" else 5e-3) * rex["fro"].max()
+
+
+def test_more_pairs_than_one_batch():
+    """More (batch, head) pairs than the library processes per launch (1024): the pair-batch loop with non-zero
+    initial states and returned final states, ragged T."""
+    w = synth.CFG2.scaled(B=41, H=32, T=100, d=64, n_iter=6, seed=123)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(6)
+    A = rng.standard_normal((w.B, w.H, w.d, 4)).astype(np.float32)
+    Hi = np.einsum("bhik,bhjk->bhij", A, A).astype(np.float32) / 4
+    Ui = rng.standard_normal((w.B, w.H, w.d, w.d)).astype(np.float32) * 0.1
+    o, ex = run_forward(w, x, H_init=to_device(Hi, "f32"), U_init=to_device(Ui, "f32"), return_state=True)
+    ref, rex = oracle_forward(w, x, H_init=Hi, U_init=Ui, return_state=True)
+    assert pair_rel_err(to_host(o), ref) <= TOL_BF16
+    assert np.abs(to_host(ex["H_final"]) - rex["H_final"]).max() <= 5e-3 * np.abs(rex["H_final"]).max()
+    assert np.abs(to_host(ex["U_final"]) - rex["U_final"]).max() <= 5e-3 * np.abs(rex["U_final"]).max()
