@@ -18,8 +18,10 @@
  *     (a hipStream_t passed as void*; NULL is the default stream).
  *   - Every call returns a gka_status. Argument errors are detected on the host before any
  *     kernel is launched, and leave all buffers untouched.
- *   - Value preconditions are NOT checked: gamma in (0, 1], lambda > 0, finite inputs.
- *     Gates below exp(-100) are treated as exp(-100).
+ *   - Value preconditions are NOT checked: gamma in [0, 1], lambda > 0, finite inputs.
+ *     Gates below exp(-100), including 0, are treated as exp(-100) by gka_forward: such a gate wipes
+ *     the state (to within 4e-44 of its magnitude). This is how packed variable-length sequences are
+ *     run: concatenate them along T and give the first token of every sequence a gate of 0.
  *   - State layout: H[b][h][i][j] (d_k x d_k) and U[b][h][i_v][j_k] (d_v x d_k, U = sum v k^T),
  *     row-major float32.
  */

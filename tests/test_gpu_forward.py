@@ -223,3 +223,26 @@ def test_more_pairs_than_one_batch():
     assert pair_rel_err(to_host(o), ref) <= TOL_BF16
     assert np.abs(to_host(ex["H_final"]) - rex["H_final"]).max() <= 5e-3 * np.abs(rex["H_final"]).max()
     assert np.abs(to_host(ex["U_final"]) - rex["U_final"]).max() <= 5e-3 * np.abs(rex["U_final"]).max()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_packed_variable_length_sequences(dtype):
+    """Sequences of different lengths concatenated along T, the gate of every sequence's first token set to 0 (the
+    library treats it as exp(-100), which wipes the state): every sequence must come out as if it had been run alone
+    from zero states, whatever the chunk boundaries."""
+    base = synth.CFG1 if dtype == "f32" else synth.CFG2
+    lengths = [70, 1, 130, 63, 64, 56]
+    w = base.scaled(B=1, H=3, T=sum(lengths), d=64, n_iter=6, seed=19)
+    x = {n: a.copy() for n, a in synth.make_inputs(w).items()}
+    starts = np.cumsum([0] + lengths[:-1])
+    x["gate"][:, starts] = 0.0
+    o = run_forward(w, x)
+    y = to_host(o)
+    assert np.isfinite(y).all()
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16
+    for s0, n in zip(starts, lengths):
+        part = {name: np.ascontiguousarray(a[:, s0:s0 + n]) for name, a in x.items()}
+        part["gate"][:, 0] = 0.5                 # irrelevant: the sequence starts from zero states
+        ref = oracle.forward(part["q"], part["k"], part["v"], part["gate"], part["lam"], w.n_iter)
+        err = pair_rel_err(y[:, s0:s0 + n], ref)
+        assert err <= tol, (s0, n, err)

@@ -429,3 +429,19 @@ def test_initial_state_is_decayed_by_first_gate():
                            H_init=Hi, U_init=Ui, return_state=True)
     np.testing.assert_allclose(ex["H_final"], 0.25 * Hi)
     np.testing.assert_allclose(ex["U_final"], 0.25 * Ui)
+
+
+def test_zero_gate_resets_the_state():
+    """A gate of exactly 0 discards the past: two sequences concatenated with gamma = 0 at the seam give the outputs
+    of the two sequences run separately (packed variable-length batches rest on this)."""
+    rng = np.random.default_rng(41)
+    B, T, H, d = 1, 11, 2, 4
+    q, k, v, gate, lam = _rand_inputs(rng, B, T, H, d)
+    cut = 6
+    gate[:, cut] = 0.0
+    y = oracle.forward(q, k, v, gate, lam, 5)
+    ya = oracle.forward(q[:, :cut], k[:, :cut], v[:, :cut], gate[:, :cut], lam[:, :cut], 5)
+    gb = gate[:, cut:].copy(); gb[:, 0] = 0.7
+    yb = oracle.forward(q[:, cut:], k[:, cut:], v[:, cut:], gb, lam[:, cut:], 5)
+    np.testing.assert_allclose(y[:, :cut], ya, rtol=0, atol=0)
+    np.testing.assert_allclose(y[:, cut:], yb, rtol=1e-13, atol=1e-15)
