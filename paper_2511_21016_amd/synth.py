@@ -39,7 +39,7 @@ class Workload:
         return replace(self, **kw)
 
 
-# The five benchmark configurations (BASELINE: configs[0..4]).
+# The five benchmark configurations.
 CFG1 = Workload("cfg1_tiny_f32", B=1, H=1, T=256, d=64, chunk=64, n_iter=8, dtype="f32",
                 gate_mean=2.0, lambda_mult=1.0, lambda_add=1e-2, seed=0)
 CFG2 = Workload("cfg2_layer_bf16", B=4, H=16, T=4096, d=128, chunk=64, n_iter=10, dtype="bf16",
