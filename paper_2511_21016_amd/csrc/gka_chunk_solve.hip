@@ -558,6 +558,16 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
                 ownlo[i][hh] = MMA::pack(lo);
             }
         }
+    // The rounding remainder of U_[n] is used once, against the rounded xhat: its fragments go from global memory
+    // straight into registers (the passes' registers are free by now) and never pass through LDS.
+    frag ulo[NBH][NSTEPS];
+    if (NSPL == 2) {
+        const frag *Ulo = Uw + SH::H_FRAGS * 64;
+#pragma unroll
+        for (int i = 0; i < NBH; ++i)
+#pragma unroll
+            for (int st = 0; st < NSTEPS; ++st) ulo[i][st] = Ulo[((mt0 + i) * NSTEPS + st) * 64 + lane];
+    }
     lds_barrier();                           // every wave is done with H_[n], K^T and the exchange region
     GKA_TSTAMP(8);
     async_block_copy<H16>(sH, Uw, w, lane);    // U_[n] (rounded part) replaces H_[n]
@@ -574,21 +584,17 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     for (int x = 0; x < NJ + NBH; ++x) acc[x] = zero16();
     fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);          // K xhat^T and U xhat
     if (NSPL == 2) {
+        // remainder of U_[n] (registers) times the rounded xhat (still published)
+#pragma unroll
+        for (int st = 0; st < NSTEPS; ++st) {
+            const frag bx = myX[st * 64 + lane];
+#pragma unroll
+            for (int i = 0; i < NBH; ++i) acc[NJ + i] = MMA::mma(ulo[i][st], bx, acc[NJ + i]);
+        }
         lds_barrier();
         publish_operand<MMA, NB>(sX, ownlo, TW, mt0, lane);
         lds_barrier();
-        fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);      // the same on the remainder of xhat
-        lds_barrier();
-        async_block_copy<H16>(sH, Uw + SH::H_FRAGS * 64, w, lane);    // remainder of U_[n]
-        publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
-        wait_all_memory();
-        lds_barrier();
-        f32x16 accU[NBH];
-#pragma unroll
-        for (int i = 0; i < NBH; ++i) accU[i] = acc[NJ + i];
-        fused_gemm<MMA, NSTEPS, NBH>(Hset, myX, accU, lane);
-#pragma unroll
-        for (int i = 0; i < NBH; ++i) acc[NJ + i] = accU[i];
+        fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);      // K and rounded U on the remainder of xhat
     }
     frag pm[NJ][HS];
     f32x16 y[NBH];
