@@ -21,7 +21,10 @@
  * form of Algorithm 1 on an eigen-decomposed matrix; the single-token closed form; the
  * direct Cholesky solve of the ridge problem Eq. (rls) / its closed form in Section 4.1 and
  * convergence towards it; the ungated constant-lambda Kalman/RLS recursion Eq. (KF); the
- * chunk identities of Section 4.2.1; sequence-split and decode hand-off.
+ * chunk identities of Section 4.2.1; sequence-split and decode hand-off; the write gate beta
+ * (equivalence with sqrt(beta)-scaled k and v, single-token closed form); the alpha-connection
+ * (single-token closed form, interpolation against directly summed gated linear attention);
+ * a gate of 0 as a state reset.
  * Parity unpinned beyond those: the paper prints no output values of the layer.
  *
  * Layouts (row-major, all double):
