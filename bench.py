@@ -21,6 +21,8 @@ HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak
 # HBM bytes of one solve-kernel launch on this workload, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/chunk_solve_and_state_pass_cfg2_hbm_traffic.md (604 MiB read + 76 MiB written). Update with the kernel.
 SOLVE_TRAFFIC_BYTES = (604 + 76) * (1 << 20)
+# the same for one decode-step launch on the configuration-5 shape (1031 MiB read + 1026 MiB written)
+DECODE_TRAFFIC_BYTES = (1031 + 1026) * (1 << 20)
 N_INPUT_SETS = 3                   # rotated so that the 256 MiB of q,k,v,o do not sit in the last-level cache
 
 
@@ -171,7 +173,8 @@ def main():
                             "ms_per_step": ms_decode, "sequence_tokens_per_s": dB / (ms_decode * 1e-3),
                             "roofline": {"kernel": "decode_step_kernel<IOBF16,128>", "bound": "hbm",
                                          "achieved": state_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                                         "unit": "GB/s", "frac": state_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+                                         "unit": "GB/s", "frac": state_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                         "traffic": DECODE_TRAFFIC_BYTES}}
 
     if not args.no_cpu_baseline:
         import oracle
