@@ -43,6 +43,9 @@ def main():
     # a step is about half a millisecond; the clocks of an idle GPU take tens of milliseconds of work to settle
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--n-iter", type=int, default=None,
+                    help="profiling aid: another number of Chebyshev passes than the workload's 10 (the difference "
+                         "between two counts isolates the passes); the JSON line then describes that variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     args = ap.parse_args()
@@ -61,7 +64,7 @@ def main():
         sys.exit(1)
     binding.load_library()          # fails loudly when the HIP library has not been built
 
-    w = synth.CFG2
+    w = synth.CFG2 if args.n_iter is None else synth.CFG2.scaled(n_iter=args.n_iter)
     sets_host = [synth.make_inputs(w.scaled(seed=w.seed + 100 * i)) for i in range(N_INPUT_SETS)]
     sets = [upload_inputs(x, w.dtype) for x in sets_host]
     params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16)
