@@ -513,7 +513,12 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int i = 0; i < NBH; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) dl[i][r] += ncs * gI[i][r];                     // delta_i
+            for (int r = 0; r < 16; ++r) {                                               // delta_i
+                // three-address form: the result goes straight into the loop-carried register instead of a
+                // temporary that is copied there at the end of the pass
+                float t = dl[i][r];
+                asm("v_fma_f32 %0, %1, %2, %3" : "=v"(dl[i][r]) : "v"(ncs), "v"(gI[i][r]), "v"(t));
+            }
 #pragma unroll
             for (int hh = 0; hh < HS; ++hh) own[i][hh] = MMA::pack(&dl[i][hh * VEC]);
         }
