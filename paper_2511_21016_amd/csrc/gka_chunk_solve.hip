@@ -133,13 +133,15 @@ __device__ __forceinline__ void mask_p(const f32x16 (&pacc)[TW + 1], const f32x1
         }
 }
 
-// acc[i] += sum_{jt<=TW,h} AT[mt0 + i][jt][h] * pm[jt][h]     (AT = K^T or V^T fragments in LDS)
-template <class MMA, int NBH, int TW>
+// acc[i] += sum_{jt<=TW,h} AT[mt0 + i][jt][h] * pm[jt][h]     (AT = K^T or V^T fragments in LDS). With a filler the MFMAs
+// are issued in the order (jt, h, i), so that consecutive ones use different accumulators, and `fill(step)` is called
+// after each of the NBH * (TW + 1) * HS of them with its index as a compile-time constant (see fused_gemm).
+template <class MMA, int NBH, int TW, class Fill = NoFill>
 __device__ __forceinline__ void gemm_intra(const typename MMA::frag *sAT, int mt0,
                                            const typename MMA::frag (&pm)[TW + 1][MMA::HS], f32x16 (&acc)[NBH],
-                                           int lane)
+                                           int lane, Fill fill = Fill())
 {
-    constexpr int HS = MMA::HS;
+    constexpr int HS = MMA::HS, NM = NBH * (TW + 1) * HS;
     typename MMA::frag af[NBH][TW + 1][HS];
 #pragma unroll
     for (int i = 0; i < NBH; ++i)
@@ -147,12 +149,26 @@ __device__ __forceinline__ void gemm_intra(const typename MMA::frag *sAT, int mt
         for (int jt = 0; jt <= TW; ++jt)
 #pragma unroll
             for (int hh = 0; hh < HS; ++hh) af[i][jt][hh] = sAT[(((mt0 + i) * 2 + jt) * HS + hh) * 64 + lane];
+    if constexpr (std::is_same<Fill, NoFill>::value) {
 #pragma unroll
-    for (int i = 0; i < NBH; ++i)
+        for (int i = 0; i < NBH; ++i)
+#pragma unroll
+            for (int jt = 0; jt <= TW; ++jt)
+#pragma unroll
+                for (int hh = 0; hh < HS; ++hh) acc[i] = MMA::mma(af[i][jt][hh], pm[jt][hh], acc[i]);
+    } else {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int jt = 0; jt <= TW; ++jt)
 #pragma unroll
-            for (int hh = 0; hh < HS; ++hh) acc[i] = MMA::mma(af[i][jt][hh], pm[jt][hh], acc[i]);
+            for (int hh = 0; hh < HS; ++hh)
+#pragma unroll
+                for (int i = 0; i < NBH; ++i) {
+                    acc[i] = MMA::mma(af[i][jt][hh], pm[jt][hh], acc[i]);
+                    fill_step<NM>(fill, (jt * HS + hh) * NBH + i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+    }
 }
 
 // A block of N16 * kSolveThreads 16-byte units copied global -> LDS by the workgroup, asynchronously and without
@@ -500,16 +516,25 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
             }
         });
         lds_barrier();                       // the exchange region may be overwritten from here on
-        gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, gI, lane);
         omega = 4.0f / (4.0f - rho2 * omega);                      // weight schedule
         const float cm = omega - 1.0f, ncs = -omega * s0;
-        // -r_{i-1} = zeta gS + gI + lam xi; delta_i = cm delta_{i-1} - omega s0 r... : everything but the gI term is
-        // formed while the MFMAs that finish gI are in flight
-        const float ncz = ncs * zeta, ncl = ncs * lam;
+        // -r_{i-1} = zeta gS + gI + lam xi; delta_i = cm delta_{i-1} - omega s0 r_{i-1}: the gS term is formed while the
+        // MFMAs that finish gI are in flight
+        constexpr int TOTAL = NBH * 16, NM = NBH * (TW + 1) * HS, PERM = (TOTAL + NM - 1) / NM;
+        gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, gI, lane, [&](auto step) {
+            constexpr int S = decltype(step)::value;
+            const float ncz = ncs * zeta;
+#pragma unroll
+            for (int e = 0; e < PERM; ++e) {
+                const int idx = S * PERM + e;
+                if (idx < TOTAL) dl[idx / 16][idx % 16] = cm * dl[idx / 16][idx % 16] + ncz * gS[idx / 16][idx % 16];
+            }
+        });
+        const float ncl = ncs * lam;
 #pragma unroll
         for (int i = 0; i < NBH; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) dl[i][r] = cm * dl[i][r] + ncz * gS[i][r] + ncl * xi[i][r];
+            for (int r = 0; r < 16; ++r) dl[i][r] += ncl * xi[i][r];
 #pragma unroll
         for (int i = 0; i < NBH; ++i) {
 #pragma unroll
