@@ -178,6 +178,28 @@ def main():
                                          "achieved": state_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                                          "unit": "GB/s", "frac": state_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                          "traffic": DECODE_TRAFFIC_BYTES}}
+        # several tokens per call (gka_decode_tokens): the states still cross HBM once per call
+        multi = {}
+        for nt in (4, 8):
+            qm = torch.nn.functional.normalize(torch.randn((dB, nt, dH, dd), device="cuda", generator=gen),
+                                               dim=-1).bfloat16()
+            km = torch.nn.functional.normalize(torch.randn((dB, nt, dH, dd), device="cuda", generator=gen),
+                                               dim=-1).bfloat16()
+            vm = torch.randn((dB, nt, dH, dd), device="cuda", generator=gen).bfloat16()
+            gm = torch.sigmoid(torch.randn((dB, nt, dH), device="cuda", generator=gen) + 3.0)
+            lm = torch.nn.functional.softplus(torch.randn((dB, nt, dH), device="cuda", generator=gen)) + 1e-2
+            om = torch.empty_like(vm)
+            for _ in range(3):
+                binding.gka_decode_tokens(Hs, Us, qm, km, vm, gm, lm, 10, out=om)
+            torch.cuda.synchronize()
+            d0.record()
+            for _ in range(20):
+                binding.gka_decode_tokens(Hs, Us, qm, km, vm, gm, lm, 10, out=om)
+            d1.record()
+            torch.cuda.synchronize()
+            ms = d0.elapsed_time(d1) / 20
+            multi[f"tokens_per_call_{nt}"] = {"ms_per_call": ms, "sequence_tokens_per_s": dB * nt / (ms * 1e-3)}
+        result["decode"]["multi_token"] = multi
 
     if not args.no_cpu_baseline:
         import oracle

@@ -10,7 +10,7 @@
  * where CH is r passes of the Chebyshev Iteration (Algorithm 1) with eigenvalue bounds
  * L = ||H_t||_F + lambda_t and mu = lambda_t (Section 4.1, "Adaptive Regularization").
  * gka_forward processes whole sequences chunk-wise (Section 4.2.1); gka_decode_step advances
- * stored states by one token.
+ * stored states by one token, gka_decode_tokens by a few.
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers. The caller owns every buffer; the library never
@@ -147,6 +147,22 @@ gka_status gka_decode_step(const gka_params *p,
                            const void *q, const void *k, const void *v,
                            const float *gate, const float *lambda,
                            void *o, void *hip_stream);
+
+/* Several recurrent steps of Eq. (CH) on stored states in one call: the T = p->T next tokens of every sequence
+ * (short continuations: speculative or multi-token decoding, the tail of a prompt). The result equals T calls of
+ * gka_decode_step, but the states cross HBM once per call instead of once per token; each (sequence, head) pair
+ * is advanced by one workgroup, token after token, in float32. For long segments gka_forward (with H_init /
+ * H_final) is the faster path: its work runs on the matrix cores.
+ *   H_state [B,H,d_k,d_k], U_state [B,H,d_v,d_k] float32, updated IN PLACE to the state after the last token
+ *   q, k [B,T,H,d_k], v [B,T,H,d_v] io_dtype, packed (explicit strides: GKA_ERR_UNSUPPORTED);
+ *   gate, lambda (NULL as in gka_forward), p->beta, p->alpha [B,T,H] float32
+ *   o [B,T,H,d_v] io_dtype (written)
+ * T <= 0: GKA_ERR_SHAPE. */
+gka_status gka_decode_tokens(const gka_params *p,
+                             float *H_state, float *U_state,
+                             const void *q, const void *k, const void *v,
+                             const float *gate, const float *lambda,
+                             void *o, void *hip_stream);
 
 const char *gka_status_string(gka_status s);
 

@@ -20,6 +20,7 @@ EXPORTED_SYMBOLS = (
     "gka_forward",
     "gka_forward_profile",
     "gka_decode_step",
+    "gka_decode_tokens",
     "gka_status_string",
     "gka_version",
 )
@@ -70,6 +71,8 @@ def load_library():
         lib.gka_forward_profile.restype = ctypes.c_int
         lib.gka_decode_step.argtypes = [ctypes.POINTER(GkaParams), fp, fp, vp, vp, vp, fp, fp, vp, vp]
         lib.gka_decode_step.restype = ctypes.c_int
+        lib.gka_decode_tokens.argtypes = lib.gka_decode_step.argtypes
+        lib.gka_decode_tokens.restype = ctypes.c_int
         lib.gka_status_string.argtypes = [ctypes.c_int]
         lib.gka_status_string.restype = ctypes.c_char_p
         lib.gka_version.argtypes = []
@@ -119,6 +122,11 @@ def forward_profile_raw(params, q, k, v, gate, lam, o, workspace, workspace_byte
 def decode_step_raw(params, H_state, U_state, q, k, v, gate, lam, o, stream=None):
     pp = None if params is None else ctypes.byref(params)
     return int(load_library().gka_decode_step(pp, H_state, U_state, q, k, v, gate, lam, o, stream))
+
+
+def decode_tokens_raw(params, H_state, U_state, q, k, v, gate, lam, o, stream=None):
+    pp = None if params is None else ctypes.byref(params)
+    return int(load_library().gka_decode_tokens(pp, H_state, U_state, q, k, v, gate, lam, o, stream))
 
 
 def _check(status):
@@ -190,4 +198,23 @@ def gka_decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None, b
     stream = torch.cuda.current_stream(q.device).cuda_stream
     _check(decode_step_raw(params, _ptr(H_state), _ptr(U_state), _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam),
                            _ptr(o), stream))
+    return o
+
+
+def gka_decode_tokens(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None, beta=None, alpha=None,
+                      lambda_scale=0.0):
+    """gka_decode_tokens on torch CUDA tensors: states [B,H,d,d] float32 (updated in place), q, k, v [B,T,H,d]
+    contiguous, gate, lam [B,T,H] float32 (lam None: lambda_scale * ||H||_F); beta, alpha: optional [B,T,H]."""
+    import torch
+    B, T, H, d = q.shape
+    for x in (q, k, v):
+        if not x.is_contiguous():
+            raise ValueError("gka_decode_tokens takes packed [B,T,H,d] tensors")
+    io = _io_dtype(q)
+    params = make_params(B, H, T, d, n_iter, io, GKA_COMPUTE_F32, lambda_scale=lambda_scale, beta=_ptr(beta),
+                         alpha=_ptr(alpha))
+    o = torch.empty_like(v) if out is None else out
+    stream = torch.cuda.current_stream(q.device).cuda_stream
+    _check(decode_tokens_raw(params, _ptr(H_state), _ptr(U_state), _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam),
+                             _ptr(o), stream))
     return o

@@ -260,11 +260,13 @@ gka_status gka_forward_profile(const gka_params *p, const void *q, const void *k
     return GKA_OK;
 }
 
-gka_status gka_decode_step(const gka_params *p, float *H_state, float *U_state, const void *q, const void *k,
-                           const void *v, const float *gate, const float *lambda, void *o, void *hip_stream)
+namespace {
+gka_status decode_impl(const gka_params *p, int n_tokens, float *H_state, float *U_state, const void *q, const void *k,
+                       const void *v, const float *gate, const float *lambda, void *o, void *hip_stream)
 {
     gka_status s = check_common(p, true);
     if (s != GKA_OK) return s;
+    if (n_tokens <= 0) return GKA_ERR_SHAPE;
     if (!H_state || !U_state || !q || !k || !v || !gate || !o) return GKA_ERR_NULL;
     if (!lambda && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;
     gka::DecodeArgs da;
@@ -272,10 +274,26 @@ gka_status gka_decode_step(const gka_params *p, float *H_state, float *U_state, 
     da.q = q; da.k = k; da.v = v; da.gate = gate; da.lambda = lambda; da.o = o;
     da.beta = p->beta; da.alpha = p->alpha; da.lambda_scale = p->lambda_scale;
     da.n_iter = p->n_iter;
+    da.T = n_tokens; da.H = p->H;
     if (gka::launch_decode_step(da, p->B * p->H, p->d_k, p->io_dtype == GKA_BF16, (hipStream_t)hip_stream) !=
         hipSuccess)
         return GKA_ERR_LAUNCH;
     return GKA_OK;
+}
+}  // namespace
+
+gka_status gka_decode_step(const gka_params *p, float *H_state, float *U_state, const void *q, const void *k,
+                           const void *v, const float *gate, const float *lambda, void *o, void *hip_stream)
+{
+    return decode_impl(p, 1, H_state, U_state, q, k, v, gate, lambda, o, hip_stream);
+}
+
+gka_status gka_decode_tokens(const gka_params *p, float *H_state, float *U_state, const void *q, const void *k,
+                             const void *v, const float *gate, const float *lambda, void *o, void *hip_stream)
+{
+    if (!p) return GKA_ERR_NULL;
+    if (p->stride_b != 0 || p->stride_t != 0 || p->stride_h != 0) return GKA_ERR_UNSUPPORTED;
+    return decode_impl(p, p->T, H_state, U_state, q, k, v, gate, lambda, o, hip_stream);
 }
 
 const char *gka_status_string(gka_status s)
@@ -291,6 +309,6 @@ const char *gka_status_string(gka_status s)
     return "unknown status";
 }
 
-int gka_version(void) { return 200; }
+int gka_version(void) { return 300; }
 
 }  // extern "C"

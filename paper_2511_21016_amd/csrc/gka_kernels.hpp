@@ -48,13 +48,14 @@ struct SolveArgs {
 };
 
 struct DecodeArgs {
-    float *H_state, *U_state;     // [pairs,d,d], in place
-    const void *q, *k, *v;        // [pairs,d]
-    const float *gate, *lambda;   // [pairs]; lambda nullptr: lambda = lambda_scale ||H||_F
-    const float *beta, *alpha;    // [pairs] or nullptr (= 1)
+    float *H_state, *U_state;     // [B,H,d,d], in place
+    const void *q, *k, *v;        // [B,T,H,d]
+    const float *gate, *lambda;   // [B,T,H]; lambda nullptr: lambda = lambda_scale ||H||_F
+    const float *beta, *alpha;    // [B,T,H] or nullptr (= 1)
     float lambda_scale;
-    void *o;                      // [pairs,d]
+    void *o;                      // [B,T,H,d]
     int n_iter;
+    int T, H;                     // tokens per call (1 for a single step), heads
 };
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,

@@ -61,3 +61,58 @@ def test_decode_layer_variants(d, dtype):
         err = np.abs(y - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
         assert err.max() <= tol, (s, err.max())
     np.testing.assert_allclose(to_host(Hd), Hs, rtol=0, atol=2e-5 * np.abs(Hs).max())
+
+
+@pytest.mark.parametrize("d,dtype,variants", [(128, "bf16", False), (64, "f32", False), (128, "f32", True),
+                                              (64, "bf16", True)])
+def test_decode_tokens_in_segments(d, dtype, variants):
+    """gka_decode_tokens over a sequence cut into segments of 1, 5, 8 and 9 tokens, against the oracle's forward
+    over the whole sequence; the last state against the oracle's; and bit-identical to single steps."""
+    import torch
+    base = synth.CFG5 if dtype == "bf16" else synth.CFG1
+    segs = [1, 5, 8, 9]
+    T = sum(segs)
+    w = base.scaled(B=3, H=2, T=T, d=d, n_iter=6, seed=91 + d)
+    x = synth.make_inputs(w)
+    kw, gates = {}, None
+    if variants:
+        gates = synth.make_gates(w)
+        kw = dict(beta=gates["beta"], alpha=gates["alpha"], lambda_scale=0.03)
+    lam = None if variants else x["lam"]
+    ref, ex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], lam, w.n_iter, return_state=True, **kw)
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+
+    def dev(a, t0, t1, dt):
+        return to_device(np.ascontiguousarray(a[:, t0:t1]), dt)
+
+    Hd = torch.zeros((w.B, w.H, d, d), dtype=torch.float32, device="cuda")
+    Ud = torch.zeros_like(Hd)
+    H1, U1 = torch.zeros_like(Hd), torch.zeros_like(Hd)
+    t0 = 0
+    for n in segs:
+        t1 = t0 + n
+        q, k, v = (dev(x[name], t0, t1, dtype) for name in ("q", "k", "v"))
+        gate = dev(x["gate"], t0, t1, "f32")
+        lam_d = None if variants else dev(x["lam"], t0, t1, "f32")
+        gk = {}
+        if variants:
+            gk = dict(beta=dev(gates["beta"], t0, t1, "f32"), alpha=dev(gates["alpha"], t0, t1, "f32"),
+                      lambda_scale=0.03)
+        o = binding.gka_decode_tokens(Hd, Ud, q, k, v, gate, lam_d, w.n_iter, **gk)
+        torch.cuda.synchronize()
+        y = to_host(o)
+        r = ref[:, t0:t1]
+        err = np.abs(y - r).max(axis=-1) / np.abs(r).max(axis=-1)
+        assert err.max() <= tol, (t0, n, err.max())
+        # the same tokens one step at a time: the same kernel arithmetic, hence the same bits
+        for s in range(n):
+            sk = {name: val[:, s].contiguous() for name, val in gk.items() if name != "lambda_scale"}
+            o1 = binding.gka_decode_step(H1, U1, q[:, s].contiguous(), k[:, s].contiguous(), v[:, s].contiguous(),
+                                         gate[:, s].contiguous(), None if variants else lam_d[:, s].contiguous(),
+                                         w.n_iter, lambda_scale=0.03 if variants else 0.0, **sk)
+            assert torch.equal(o1, o[:, s])
+        assert torch.equal(H1, Hd) and torch.equal(U1, Ud)
+        t0 = t1
+    Hs, Us = ex["H_final"], ex["U_final"]
+    np.testing.assert_allclose(to_host(Hd), Hs, rtol=0, atol=2e-5 * np.abs(Hs).max())
+    np.testing.assert_allclose(to_host(Ud), Us, rtol=0, atol=2e-5 * np.abs(Us).max())

@@ -85,4 +85,9 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(_p(), ws=0x100010) == binding.GKA_ERR_WORKSPACE                   # misaligned
     assert binding.decode_step_raw(_p(), None, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
     assert binding.decode_step_raw(_p(d=32), fake, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_UNSUPPORTED
+    assert binding.decode_tokens_raw(_p(), None, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
+    assert binding.decode_tokens_raw(_p(T=0), fake, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_SHAPE
+    assert binding.decode_tokens_raw(_p(strides=(1 << 20, 2048, 128)), fake, fake, fake, fake, fake, fake, fake,
+                                     fake) == binding.GKA_ERR_UNSUPPORTED
+    assert binding.decode_tokens_raw(None, fake, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
     assert binding.forward_raw(None, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
