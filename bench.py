@@ -174,10 +174,29 @@ def main():
         state_bytes = dB * dH * 2 * dd * dd * 4 * 2          # H and U, read and written
         result["decode"] = {"workload": "cfg5_decode_bf16 (256 seq x 32 heads, d=128, n_iter=10)",
                             "ms_per_step": ms_decode, "sequence_tokens_per_s": dB / (ms_decode * 1e-3),
-                            "roofline": {"kernel": "decode_step_kernel<IOBF16,128>", "bound": "hbm",
+                            "roofline": {"kernel": "decode_step_kernel<IOBF16,128,false,false>", "bound": "hbm",
                                          "achieved": state_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                                          "unit": "GB/s", "frac": state_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                          "traffic": DECODE_TRAFFIC_BYTES}}
+        # the decode cache in the reduced layout of H (only the 32 x 32 blocks on and below the block diagonal are
+        # read and written: 10 of 16 blocks at d = 128)
+        for _ in range(5):
+            binding.gka_decode_step(Hs, Us, qd, kd, vd, gd, ld, 10, out=od,
+                                    state_layout=binding.GKA_STATE_H_LOWER_BLOCKS)
+        torch.cuda.synchronize()
+        d0.record()
+        for _ in range(d_steps):
+            binding.gka_decode_step(Hs, Us, qd, kd, vd, gd, ld, 10, out=od,
+                                    state_layout=binding.GKA_STATE_H_LOWER_BLOCKS)
+        d1.record()
+        torch.cuda.synchronize()
+        ms_lower = d0.elapsed_time(d1) / d_steps
+        lower_bytes = dB * dH * (dd * dd + 10 * 32 * 32) * 4 * 2
+        result["decode"]["h_lower_blocks"] = {
+            "ms_per_step": ms_lower, "sequence_tokens_per_s": dB / (ms_lower * 1e-3),
+            "roofline": {"kernel": "decode_step_kernel<IOBF16,128,false,true>", "bound": "hbm",
+                         "achieved": lower_bytes / (ms_lower * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": lower_bytes / (ms_lower * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None}}
         # several tokens per call (gka_decode_tokens): the states still cross HBM once per call
         multi = {}
         for nt in (4, 8):

@@ -62,6 +62,16 @@ typedef enum { GKA_COMPUTE_F32 = 0, GKA_COMPUTE_BF16 = 1 } gka_compute;
  * enough to be processed as one launch of each kernel (otherwise GKA_ERR_UNSUPPORTED). */
 typedef enum { GKA_PHASE_ALL = 0, GKA_PHASE_STATES = 1, GKA_PHASE_SOLVE = 2 } gka_phase;
 
+/* Which elements of a stored H state carry it. H_t is symmetric, so a decode cache needs only one triangle.
+ * GKA_STATE_FULL          : all d x d elements are read and written.
+ * GKA_STATE_H_LOWER_BLOCKS: only the 32 x 32 blocks on and below the block diagonal are: element [i][j] with
+ *                           j < 32 (i / 32 + 1). gka_decode_step and gka_decode_tokens neither read nor write the
+ *                           other elements of H_state (the buffer keeps its [d,d] shape; those elements keep
+ *                           whatever they held), which removes 3/8 (d = 128) or 1/4 (d = 64) of the traffic of H;
+ *                           gka_forward reads H_init the same way (its H_final is always written in full, which
+ *                           is valid under either layout). U states are not symmetric and are always full. */
+typedef enum { GKA_STATE_FULL = 0, GKA_STATE_H_LOWER_BLOCKS = 1 } gka_state_layout;
+
 typedef struct {
     int32_t B;            /* batch (gka_decode_step: number of sequences)                      */
     int32_t H;            /* heads                                                             */
@@ -82,7 +92,7 @@ typedef struct {
     /* Variants of the layer (Section 4.1 "Adaptive Regularization" and its Remark, Section 4.3). With
      * lambda_scale = 0 and both pointers NULL the call is Eq. (CH) as printed. */
     float   lambda_scale; /* a > 0 of lambda_t = a ||H_t||_F; used when the lambda argument is NULL     */
-    int32_t reserved;     /* 0                                                                          */
+    int32_t state_layout; /* gka_state_layout of H_state / H_init: 0 = every element is read and written   */
     const float *beta;    /* DEVICE pointer or NULL (= 1): write gate beta_t in [0,1] of the            */
                           /*   beta-augmented recurrence H_t = gamma_t H_{t-1} + beta_t k_t k_t^T,      */
                           /*   U_t = gamma_t U_{t-1} + beta_t v_t k_t^T; [B,T,H] ([B,H] for decode)     */

@@ -14,6 +14,7 @@ GKA_OK, GKA_ERR_NULL, GKA_ERR_SHAPE, GKA_ERR_UNSUPPORTED, GKA_ERR_WORKSPACE, GKA
 GKA_F32, GKA_BF16 = 0, 1
 GKA_COMPUTE_F32, GKA_COMPUTE_BF16 = 0, 1
 GKA_PHASE_ALL, GKA_PHASE_STATES, GKA_PHASE_SOLVE = 0, 1, 2
+GKA_STATE_FULL, GKA_STATE_H_LOWER_BLOCKS = 0, 1
 
 EXPORTED_SYMBOLS = (
     "gka_forward_workspace_bytes",
@@ -33,7 +34,7 @@ class GkaParams(ctypes.Structure):
         ("n_iter", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("compute", ctypes.c_int32),
         ("phase", ctypes.c_int32),
         ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
-        ("lambda_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+        ("lambda_scale", ctypes.c_float), ("state_layout", ctypes.c_int32),
         ("beta", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
     ]
 
@@ -90,12 +91,12 @@ def version():
 
 
 def make_params(B, H, T, d, n_iter, io_dtype, compute, chunk=64, d_v=None, strides=(0, 0, 0), phase=0,
-                lambda_scale=0.0, beta=None, alpha=None):
+                lambda_scale=0.0, beta=None, alpha=None, state_layout=0):
     """beta, alpha: device addresses (ints) of the optional per-token gates, or None."""
     return GkaParams(B=B, H=H, T=T, d_k=d, d_v=d if d_v is None else d_v, chunk=chunk, n_iter=n_iter,
                      io_dtype=io_dtype, compute=compute, phase=phase,
                      stride_b=strides[0], stride_t=strides[1], stride_h=strides[2],
-                     lambda_scale=lambda_scale, reserved=0, beta=beta, alpha=alpha)
+                     lambda_scale=lambda_scale, state_layout=state_layout, beta=beta, alpha=alpha)
 
 
 def forward_workspace_bytes(params):
@@ -149,7 +150,7 @@ def _ptr(t):
 
 def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=None, U_init=None,
                 return_state=False, return_fro=False, workspace=None, out=None, phase=GKA_PHASE_ALL,
-                beta=None, alpha=None, lambda_scale=0.0):
+                beta=None, alpha=None, lambda_scale=0.0, state_layout=GKA_STATE_FULL):
     """gka_forward on torch CUDA tensors: q, k, v [B,T,H,d] (float32 or bfloat16, contiguous),
     gate, lam [B,T,H] float32 (lam None: lambda_t = lambda_scale * ||H_t||_F); beta, alpha: optional [B,T,H]
     float32 write gate and alpha-connection. Enqueues on torch's current stream and returns o (and a dict of
@@ -162,7 +163,7 @@ def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=No
     if compute is None:
         compute = GKA_COMPUTE_BF16 if io == GKA_BF16 else GKA_COMPUTE_F32
     params = make_params(B, H, T, d, n_iter, io, compute, chunk=chunk, d_v=v.shape[-1], phase=phase,
-                         lambda_scale=lambda_scale, beta=_ptr(beta), alpha=_ptr(alpha))
+                         lambda_scale=lambda_scale, beta=_ptr(beta), alpha=_ptr(alpha), state_layout=state_layout)
     nbytes = forward_workspace_bytes(params)
     if nbytes == 0:
         # let the library name the error
@@ -186,14 +187,14 @@ def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=No
 
 
 def gka_decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None, beta=None, alpha=None,
-                    lambda_scale=0.0):
+                    lambda_scale=0.0, state_layout=GKA_STATE_FULL):
     """gka_decode_step on torch CUDA tensors: states [B,H,d,d] float32 (updated in place), q, k, v [B,H,d],
     gate, lam [B,H] float32 (lam None: lambda_scale * ||H||_F); beta, alpha: optional [B,H] float32."""
     import torch
     B, H, d = q.shape
     io = _io_dtype(q)
     params = make_params(B, H, 1, d, n_iter, io, GKA_COMPUTE_F32, lambda_scale=lambda_scale, beta=_ptr(beta),
-                         alpha=_ptr(alpha))
+                         alpha=_ptr(alpha), state_layout=state_layout)
     o = torch.empty_like(v) if out is None else out
     stream = torch.cuda.current_stream(q.device).cuda_stream
     _check(decode_step_raw(params, _ptr(H_state), _ptr(U_state), _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam),
@@ -202,7 +203,7 @@ def gka_decode_step(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None, b
 
 
 def gka_decode_tokens(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None, beta=None, alpha=None,
-                      lambda_scale=0.0):
+                      lambda_scale=0.0, state_layout=GKA_STATE_FULL):
     """gka_decode_tokens on torch CUDA tensors: states [B,H,d,d] float32 (updated in place), q, k, v [B,T,H,d]
     contiguous, gate, lam [B,T,H] float32 (lam None: lambda_scale * ||H||_F); beta, alpha: optional [B,T,H]."""
     import torch
@@ -212,7 +213,7 @@ def gka_decode_tokens(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None,
             raise ValueError("gka_decode_tokens takes packed [B,T,H,d] tensors")
     io = _io_dtype(q)
     params = make_params(B, H, T, d, n_iter, io, GKA_COMPUTE_F32, lambda_scale=lambda_scale, beta=_ptr(beta),
-                         alpha=_ptr(alpha))
+                         alpha=_ptr(alpha), state_layout=state_layout)
     o = torch.empty_like(v) if out is None else out
     stream = torch.cuda.current_stream(q.device).cuda_stream
     _check(decode_tokens_raw(params, _ptr(H_state), _ptr(U_state), _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam),

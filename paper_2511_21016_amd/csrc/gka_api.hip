@@ -57,6 +57,7 @@ gka_status check_common(const gka_params *p, bool decode)
     if (!decode && p->chunk != gka::kChunk) return GKA_ERR_UNSUPPORTED;
     if ((int64_t)p->B * p->H > (int64_t)1 << 24) return GKA_ERR_SHAPE;
     if (!(p->lambda_scale >= 0.0f)) return GKA_ERR_SHAPE;
+    if (p->state_layout != GKA_STATE_FULL && p->state_layout != GKA_STATE_H_LOWER_BLOCKS) return GKA_ERR_UNSUPPORTED;
     return GKA_OK;
 }
 
@@ -204,6 +205,8 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
             sa.H_init = first ? H_init : in;
             sa.U_init = first ? U_init : in + state_elems;
             sa.init_pair0 = first ? pair0 : 0;
+            // states carried between slabs are always complete
+            sa.h_init_lower_blocks = first && p->state_layout == GKA_STATE_H_LOWER_BLOCKS;
             sa.H_final = last ? H_final : out;
             sa.U_final = last ? U_final : out + state_elems;
             sa.final_pair0 = last ? pair0 : 0;
@@ -275,6 +278,7 @@ gka_status decode_impl(const gka_params *p, int n_tokens, float *H_state, float 
     da.beta = p->beta; da.alpha = p->alpha; da.lambda_scale = p->lambda_scale;
     da.n_iter = p->n_iter;
     da.T = n_tokens; da.H = p->H;
+    da.h_lower_blocks = p->state_layout == GKA_STATE_H_LOWER_BLOCKS;
     if (gka::launch_decode_step(da, p->B * p->H, p->d_k, p->io_dtype == GKA_BF16, (hipStream_t)hip_stream) !=
         hipSuccess)
         return GKA_ERR_LAUNCH;

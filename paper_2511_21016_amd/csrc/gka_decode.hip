@@ -14,7 +14,9 @@
 namespace gka {
 
 // MULTI = false: the single-step kernel, a.T == 1 known at compile time.
-template <class IO, int D, bool MULTI>
+// LOWER: of H_state only the 32 x 32 blocks on and below the block diagonal are read and written; the blocks above
+// are rebuilt in registers from their mirror images (through LDS, once per call), so the arithmetic is the same.
+template <class IO, int D, bool MULTI, bool LOWER>
 __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
 {
     const int T = MULTI ? a.T : 1;
@@ -34,10 +36,34 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
     float *Us = a.U_state + (int64_t)pair * D * D;
     const int b = pair / a.H, h = pair - b * a.H;
     f32x4 hreg[ITS], ureg[ITS];
+    // piece `it` of this thread lies in block row (it * RPI) / 32 (RPI divides 32) and block column bj
+    const int bj = col4 / 8;
+    auto held = [&](int it) { return !LOWER || bj <= (it * RPI) / 32; };
 #pragma unroll
     for (int it = 0; it < ITS; ++it) {
-        hreg[it] = *(const f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4);
+        if (held(it)) hreg[it] = *(const f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4);
         ureg[it] = *(const f32x4 *)(Us + (int64_t)(it * 256 + t) * 4);
+    }
+    if constexpr (LOWER) {
+        constexpr int NBLK = D / 32, NOFF = NBLK * (NBLK - 1) / 2;
+        __shared__ float s_tr[NOFF][32][33];         // the blocks below the diagonal, block (bi, bj) at bi (bi - 1) / 2 + bj
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int bi = (it * RPI) / 32, row = it * RPI + rgrp;
+            if (bj < bi) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s_tr[bi * (bi - 1) / 2 + bj][row % 32][(4 * col4) % 32 + e] = hreg[it][e];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < ITS; ++it) {
+            const int bi = (it * RPI) / 32, row = it * RPI + rgrp;
+            if (bj > bi) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) hreg[it][e] = s_tr[bj * (bj - 1) / 2 + bi][(4 * col4 + e) % 32][row % 32];
+            }
+        }
     }
     for (int tok = 0; tok < T; ++tok) {
         const int64_t bth = ((int64_t)b * T + tok) * a.H + h;      // [B,T,H] index of this token
@@ -59,15 +85,17 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
 #pragma unroll
         for (int it = 0; it < ITS; ++it) {
             const int row = it * RPI + rgrp;
-            const float kr = beta * s_k[row], vr = beta * s_v[row];
+            const float kr = s_k[row], vr = beta * s_v[row];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                hreg[it][e] = gamma * hreg[it][e] + kr * kc[e];
+                // beta (k_i k_j): the product of the two k components first, so that both mirror images of an
+                // element get the same bits
+                hreg[it][e] = gamma * hreg[it][e] + beta * (kr * kc[e]);
                 ureg[it][e] = gamma * ureg[it][e] + vr * kc[e];
                 ss += hreg[it][e] * hreg[it][e];
             }
             if (tok == T - 1) {              // the stores drain while the last token is solved
-                *(f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4) = hreg[it];
+                if (held(it)) *(f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4) = hreg[it];
                 *(f32x4 *)(Us + (int64_t)(it * 256 + t) * 4) = ureg[it];
             }
         }
@@ -133,23 +161,28 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
     }
 }
 
-template <bool MULTI>
+template <bool MULTI, bool LOWER>
 static void launch_decode(const DecodeArgs &a, int n_pairs, int d, bool io_bf16, hipStream_t stream)
 {
     dim3 grid((unsigned)n_pairs), block(256);
     if (io_bf16) {
-        if (d == 128) hipLaunchKernelGGL((decode_step_kernel<IOBF16, 128, MULTI>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((decode_step_kernel<IOBF16, 64, MULTI>), grid, block, 0, stream, a);
+        if (d == 128) hipLaunchKernelGGL((decode_step_kernel<IOBF16, 128, MULTI, LOWER>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((decode_step_kernel<IOBF16, 64, MULTI, LOWER>), grid, block, 0, stream, a);
     } else {
-        if (d == 128) hipLaunchKernelGGL((decode_step_kernel<IOF32, 128, MULTI>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((decode_step_kernel<IOF32, 64, MULTI>), grid, block, 0, stream, a);
+        if (d == 128) hipLaunchKernelGGL((decode_step_kernel<IOF32, 128, MULTI, LOWER>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((decode_step_kernel<IOF32, 64, MULTI, LOWER>), grid, block, 0, stream, a);
     }
 }
 
 hipError_t launch_decode_step(const DecodeArgs &a, int n_pairs, int d, bool io_bf16, hipStream_t stream)
 {
-    if (a.T == 1) launch_decode<false>(a, n_pairs, d, io_bf16, stream);
-    else launch_decode<true>(a, n_pairs, d, io_bf16, stream);
+    if (a.h_lower_blocks) {
+        if (a.T == 1) launch_decode<false, true>(a, n_pairs, d, io_bf16, stream);
+        else launch_decode<true, true>(a, n_pairs, d, io_bf16, stream);
+    } else {
+        if (a.T == 1) launch_decode<false, false>(a, n_pairs, d, io_bf16, stream);
+        else launch_decode<true, false>(a, n_pairs, d, io_bf16, stream);
+    }
     return hipGetLastError();
 }
 

@@ -21,6 +21,7 @@ struct StatePassArgs {
     int chunk0, n_chunks;         // this launch covers chunks chunk0 .. chunk0 + n_chunks - 1 of every pair;
                                   // the workspace is indexed from 0 in both pairs and chunks
     int init_pair0, final_pair0;  // pair index of element 0 of H_init/U_init and of H_final/U_final
+    bool h_init_lower_blocks;     // H_init: blocks above the block diagonal are taken from their mirror images
     int n_segs, seg_len;          // segments per pair and chunks per segment (n_segs <= 1: one pass)
     int n_pairs;                  // pairs of this launch (set by the launcher)
     float *seg_buf;               // [pairs, n_segs, 2, d*d] segment summaries / start states
@@ -56,6 +57,7 @@ struct DecodeArgs {
     void *o;                      // [B,T,H,d]
     int n_iter;
     int T, H;                     // tokens per call (1 for a single step), heads
+    bool h_lower_blocks;          // H_state: only the 32 x 32 blocks on and below the block diagonal are read / written
 };
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,

@@ -61,8 +61,13 @@ __device__ __forceinline__ void load_start_state(const StatePassArgs &a, f32x16 
     const int n = lane & 31, g = lane >> 5;
     if (a.H_init) {
         const float *Si = (DOH ? a.H_init : a.U_init) + (int64_t)(a.init_pair0 + pair) * D * D;
+        if (DOH && a.h_init_lower_blocks && w > rb) {      // H is symmetric: block (rb, w) = block (w, rb) transposed
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = Si[(int64_t)(32 * rb + n) * D + 32 * w + kidx(r, g)];
+            for (int r = 0; r < 16; ++r) acc[r] = Si[(int64_t)(32 * w + kidx(r, g)) * D + 32 * rb + n];
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = Si[(int64_t)(32 * rb + n) * D + 32 * w + kidx(r, g)];
+        }
     }
     for (int sg = 0; sg < seg; ++sg) {
         const float *t = segment_tile<D>(a, pair, sg, rb, w) + (DOH ? 0 : 1024);
@@ -135,20 +140,7 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
     // accumulators: element (row = 32*w + kidx(r,g), col n) = S0[32*rb + n][32*w + kidx(r,g)]
     f32x16 acc = zero16();                        // this workgroup's state: H (doH) or U
     const int tile_off = doH ? 0 : 1024;
-    if (a.init_mode != 0) {
-        if (a.H_init) {
-            const float *Si = (doH ? a.H_init : a.U_init) + (int64_t)(a.init_pair0 + pair) * D * D;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = Si[(int64_t)(32 * rb + n) * D + 32 * w + kidx(r, g)];
-        }
-        // start state of this segment: scan of the summaries (decay, Delta) of the segments before it
-        for (int sg = 0; sg < seg; ++sg) {
-            const float *t = seg_tile(sg);
-            const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = decay * acc[r] + t[tile_off + r * 64 + lane];
-        }
-    }
+    load_start_state<D, DOH>(a, acc, pair, seg, rb, w, lane);
 
     // Register prefetch, two chunks deep. Rows past the end of the sequence are read from the last valid row (a
     // divergent branch around a load would force a wait on it) and zeroed when they are stored to LDS.

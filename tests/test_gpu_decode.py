@@ -116,3 +116,64 @@ def test_decode_tokens_in_segments(d, dtype, variants):
     Hs, Us = ex["H_final"], ex["U_final"]
     np.testing.assert_allclose(to_host(Hd), Hs, rtol=0, atol=2e-5 * np.abs(Hs).max())
     np.testing.assert_allclose(to_host(Ud), Us, rtol=0, atol=2e-5 * np.abs(Us).max())
+
+
+def _lower_block_mask(d):
+    i, j = np.meshgrid(np.arange(d), np.arange(d), indexing="ij")
+    return j < 32 * (i // 32 + 1)
+
+
+@pytest.mark.parametrize("d,dtype", [(128, "bf16"), (64, "f32")])
+def test_lower_block_state_layout(d, dtype):
+    """GKA_STATE_H_LOWER_BLOCKS: the elements of H_state above the block diagonal hold NaN throughout; decode steps,
+    multi-token decode and a forward pass that starts from that state must neither read nor write them."""
+    import torch
+    base = synth.CFG5 if dtype == "bf16" else synth.CFG1
+    w = base.scaled(B=2, H=3, T=70, d=d, n_iter=6, seed=123 + d)
+    x = synth.make_inputs(w)
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+    mask = _lower_block_mask(d)
+    # prefill on the oracle, then the cache in the reduced layout
+    t_pre, t_step, t_multi = 40, 44, 50
+    _, ex = oracle.forward(x["q"][:, :t_pre], x["k"][:, :t_pre], x["v"][:, :t_pre], x["gate"][:, :t_pre],
+                           x["lam"][:, :t_pre], w.n_iter, return_state=True)
+    H0 = ex["H_final"].astype(np.float32)
+    U0 = ex["U_final"].astype(np.float32)
+    Hd = to_device(np.where(mask, H0, np.nan).astype(np.float32), "f32")
+    Ud = to_device(U0, "f32")
+    ref, exr = oracle.forward(x["q"][:, t_pre:], x["k"][:, t_pre:], x["v"][:, t_pre:], x["gate"][:, t_pre:],
+                              x["lam"][:, t_pre:], w.n_iter, H_init=H0, U_init=U0, return_state=True)
+
+    def dev(name, t0, t1, dt):
+        return to_device(np.ascontiguousarray(x[name][:, t0:t1]), dt)
+
+    def check(y, t0, t1):
+        r = ref[:, t0 - t_pre:t1 - t_pre]
+        err = np.abs(y - r).max(axis=-1) / np.abs(r).max(axis=-1)
+        assert np.isfinite(y).all() and err.max() <= tol, (t0, t1, err.max())
+
+    L = binding.GKA_STATE_H_LOWER_BLOCKS
+    for t in range(t_pre, t_step):                                   # single steps
+        o = binding.gka_decode_step(Hd, Ud, dev("q", t, t + 1, dtype)[:, 0].contiguous(),
+                                    dev("k", t, t + 1, dtype)[:, 0].contiguous(),
+                                    dev("v", t, t + 1, dtype)[:, 0].contiguous(),
+                                    dev("gate", t, t + 1, "f32")[:, 0].contiguous(),
+                                    dev("lam", t, t + 1, "f32")[:, 0].contiguous(), w.n_iter, state_layout=L)
+        check(to_host(o)[:, None], t, t + 1)
+    o = binding.gka_decode_tokens(Hd, Ud, dev("q", t_step, t_multi, dtype), dev("k", t_step, t_multi, dtype),
+                                  dev("v", t_step, t_multi, dtype), dev("gate", t_step, t_multi, "f32"),
+                                  dev("lam", t_step, t_multi, "f32"), w.n_iter, state_layout=L)
+    check(to_host(o), t_step, t_multi)
+    Hh = to_host(Hd)
+    assert np.isnan(Hh[..., ~mask]).all()                            # never written
+    # forward pass over the rest, starting from the reduced-layout state
+    o, extras = binding.gka_forward(dev("q", t_multi, w.T, dtype), dev("k", t_multi, w.T, dtype),
+                                    dev("v", t_multi, w.T, dtype), dev("gate", t_multi, w.T, "f32"),
+                                    dev("lam", t_multi, w.T, "f32"), w.n_iter, H_init=Hd, U_init=Ud,
+                                    return_state=True, state_layout=L)
+    torch.cuda.synchronize()
+    check(to_host(o), t_multi, w.T)
+    Hf, Uf = to_host(extras["H_final"]), to_host(extras["U_final"])
+    Hs, Us = exr["H_final"], exr["U_final"]
+    np.testing.assert_allclose(Hf, Hs, rtol=0, atol=(2e-5 if dtype == "f32" else 2e-2) * np.abs(Hs).max())
+    np.testing.assert_allclose(Uf, Us, rtol=0, atol=(2e-5 if dtype == "f32" else 2e-2) * np.abs(Us).max())

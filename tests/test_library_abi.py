@@ -79,6 +79,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert binding.forward_raw(_p(), fake, fake, fake, fake, None, fake, workspace=0x100000,
                                workspace_bytes=ok_ws) == binding.GKA_ERR_NULL
     assert fwd(_p(lambda_scale=-1.0)) == binding.GKA_ERR_SHAPE
+    assert fwd(_p(state_layout=2)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(state_layout=binding.GKA_STATE_H_LOWER_BLOCKS), ws=None) == binding.GKA_ERR_WORKSPACE   # valid layout
     assert fwd(_p(), H_init=fake) == binding.GKA_ERR_NULL                        # H_init without U_init
     assert fwd(_p(), ws=None) == binding.GKA_ERR_WORKSPACE
     assert fwd(_p(), ws_bytes=ok_ws - 1) == binding.GKA_ERR_WORKSPACE
