@@ -23,6 +23,8 @@ HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak
 SOLVE_TRAFFIC_BYTES = (604 + 76) * (1 << 20)
 # the same for one decode-step launch on the configuration-5 shape (1031 MiB read + 1026 MiB written)
 DECODE_TRAFFIC_BYTES = (1031 + 1026) * (1 << 20)
+# and with the reduced layout of H (839 MiB read + 834 MiB written)
+DECODE_LOWER_TRAFFIC_BYTES = (839 + 834) * (1 << 20)
 N_INPUT_SETS = 3                   # rotated so that the 256 MiB of q,k,v,o do not sit in the last-level cache
 
 
@@ -196,7 +198,8 @@ def main():
             "ms_per_step": ms_lower, "sequence_tokens_per_s": dB / (ms_lower * 1e-3),
             "roofline": {"kernel": "decode_step_kernel<IOBF16,128,false,true>", "bound": "hbm",
                          "achieved": lower_bytes / (ms_lower * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": lower_bytes / (ms_lower * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None}}
+                         "frac": lower_bytes / (ms_lower * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": DECODE_LOWER_TRAFFIC_BYTES}}
         # several tokens per call (gka_decode_tokens): the states still cross HBM once per call
         multi = {}
         for nt in (4, 8):
