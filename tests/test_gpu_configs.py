@@ -97,3 +97,63 @@ def test_cfg5_decode_subset():
     assert worst <= TOL_BF16
     np.testing.assert_allclose(to_host(Hd), Hs, rtol=0, atol=1e-4 * np.abs(Hs).max())
     np.testing.assert_allclose(to_host(Ud), Us, rtol=0, atol=1e-4 * np.abs(Us).max())
+
+
+def test_cfg5_decode_full_batch_sampled():
+    """The decode benchmark's launch configuration (256 sequences x 32 heads = 8192 pairs, d = 128): a one-chunk
+    prefill with gka_forward, then 8 tokens three ways (single steps on the full H state, single steps on the
+    block-lower layout, one gka_decode_tokens call). The oracle follows a seeded sample of 48 pairs from the
+    states the prefill left."""
+    import torch
+    w = synth.CFG5.scaled(T=64)
+    n_steps = 8
+    x = synth.make_inputs(w)
+    o, ex = _forward(w, x, binding.GKA_COMPUTE_F32, return_state=True)
+    rng = np.random.default_rng(55)
+    flat = rng.choice(w.B * w.H, size=48, replace=False)
+    sb, sh = flat // w.H, flat % w.H
+
+    def sample(a):                      # [B,T,H,...] -> [S,T,1,...]
+        return np.ascontiguousarray(a[sb, :, sh][:, :, None])
+
+    xs = {name: sample(a) for name, a in x.items()}
+    ref, rex = oracle.forward(xs["q"], xs["k"], xs["v"], xs["gate"], xs["lam"], w.n_iter, return_state=True)
+    assert pair_rel_err(sample(to_host(o)), ref) <= TOL_BF16
+    Hd, Ud = ex["H_final"], ex["U_final"]
+    Hs = np.ascontiguousarray(to_host(Hd)[sb, sh][:, None])          # the oracle continues from the GPU's fp32 states
+    Us = np.ascontiguousarray(to_host(Ud)[sb, sh][:, None])
+    steps = synth.make_decode_tokens(w, n_steps)                     # [n_steps, B, H, ...]
+    dev = {name: to_device(steps[name], w.dtype if name in ("q", "k", "v") else "f32") for name in steps}
+    H_full, U_full = Hd.clone(), Ud.clone()
+    H_low, U_low = Hd.clone(), Ud.clone()
+    H_multi, U_multi = Hd.clone(), Ud.clone()
+    out_full = torch.empty((n_steps, w.B, w.H, w.d), dtype=torch.bfloat16, device="cuda")
+    out_low = torch.empty_like(out_full)
+    for s in range(n_steps):
+        binding.gka_decode_step(H_full, U_full, dev["q"][s], dev["k"][s], dev["v"][s], dev["gate"][s], dev["lam"][s],
+                                w.n_iter, out=out_full[s])
+        binding.gka_decode_step(H_low, U_low, dev["q"][s], dev["k"][s], dev["v"][s], dev["gate"][s], dev["lam"][s],
+                                w.n_iter, out=out_low[s], state_layout=binding.GKA_STATE_H_LOWER_BLOCKS)
+    bt = {name: dev[name].transpose(0, 1).contiguous() for name in dev}          # [B, n_steps, H, ...]
+    out_multi = binding.gka_decode_tokens(H_multi, U_multi, bt["q"], bt["k"], bt["v"], bt["gate"], bt["lam"], w.n_iter)
+    torch.cuda.synchronize()
+    ys = {"full": to_host(out_full)[:, sb, sh], "lower": to_host(out_low)[:, sb, sh],
+          "multi": np.moveaxis(to_host(out_multi)[sb, :, sh], 0, 1)}            # [n_steps, S, d]
+    worst = dict.fromkeys(ys, 0.0)
+    for s in range(n_steps):
+        r = oracle.decode_step(Hs, Us, *(np.ascontiguousarray(steps[n][s][sb, sh][:, None])
+                                         for n in ("q", "k", "v", "gate", "lam")), w.n_iter)[:, 0]
+        for name, y in ys.items():
+            e = np.abs(y[s] - r).max(axis=-1) / np.abs(r).max(axis=-1)
+            worst[name] = max(worst[name], float(e.max()))
+    print("cfg5 full batch, sampled pairs, max rel err:", worst)
+    assert max(worst.values()) <= TOL_BF16
+    assert torch.equal(out_full, out_multi.transpose(0, 1))          # the same kernel arithmetic token by token
+    for Hx, Ux in ((H_full, U_full), (H_low, U_low), (H_multi, U_multi)):
+        hh = to_host(Hx)[sb, sh][:, None]
+        if Hx is H_low:                                              # only the block-lower part is maintained
+            i, j = np.meshgrid(np.arange(w.d), np.arange(w.d), indexing="ij")
+            keep = j < 32 * (i // 32 + 1)
+            hh = np.where(keep, hh, Hs)
+        np.testing.assert_allclose(hh, Hs, rtol=0, atol=1e-4 * np.abs(Hs).max())
+        np.testing.assert_allclose(to_host(Ux)[sb, sh][:, None], Us, rtol=0, atol=1e-4 * np.abs(Us).max())
