@@ -141,6 +141,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "T": w.T, "d": w.d, "chunk": w.chunk,
                    "n_iter": w.n_iter, "input_sets_rotated": N_INPUT_SETS},
+        "head_tokens_per_s": tokens * w.H / (ms_per_step * 1e-3),
         "tflops_algorithmic": tflops_total,
         "frac_bf16_mfma_peak": tflops_total / MFMA_BF16_PEAK_TFLOPS,
         "phase_ms": {"states": ms_states, "solve": ms_solve, "solve_launches_per_step": n_launches,
