@@ -116,6 +116,43 @@ __device__ __forceinline__ void fused_gemm(const typename MMA::frag *const (&A)[
     }
 }
 
+// The two products of a pass that share the B operand (the published delta), in one sweep over its NSTEPS fragments:
+// pacc[j] = sum_s K[j][s] * B[s] (from zero) and gS[i] += sum_s Hs[i][s] * B[s]. Every B fragment is read from LDS
+// once. The A fragments are staggered instead of double-buffered as a whole: those of the state product are
+// requested at the start of their own step and arrive while the key MFMAs run; the keys and B of the next step are
+// requested before the state MFMAs. `fill(step)` as in fused_gemm.
+template <class MMA, int NSTEPS, int NJ, int NBH, class Fill>
+__device__ __forceinline__ void fused_pass_sweep(const typename MMA::frag *const (&K)[NJ],
+                                                 const typename MMA::frag *const (&Hs)[NBH],
+                                                 const typename MMA::frag *B, f32x16 (&pacc)[NJ], f32x16 (&gS)[NBH],
+                                                 int lane, Fill fill)
+{
+    typename MMA::frag kb[2][NJ], bb[2], hb[NBH];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) kb[0][j] = K[j][lane];
+    bb[0] = B[lane];
+#pragma unroll
+    for (int s = 0; s < NSTEPS; ++s) {
+        const int cur = s & 1, nxt = cur ^ 1;
+#pragma unroll
+        for (int i = 0; i < NBH; ++i) hb[i] = Hs[i][s * 64 + lane];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) pacc[j] = MMA::mma(kb[cur][j], bb[cur], s == 0 ? zero16() : pacc[j]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (s + 1 < NSTEPS) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) kb[nxt][j] = K[j][(s + 1) * 64 + lane];
+            bb[nxt] = B[(s + 1) * 64 + lane];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NBH; ++i) gS[i] = MMA::mma(hb[i], bb[cur], gS[i]);
+        fill_step<NSTEPS>(fill, s);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // (P o M) as B-operand fragments, key blocks jt <= TW
 template <class MMA, int TW>
 __device__ __forceinline__ void mask_p(const f32x16 (&pacc)[TW + 1], const f32x16 (&mreg)[TW + 1],
@@ -490,9 +527,8 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         asm volatile("" ::: "memory");
         publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
         lds_barrier();
-        // Two sweeps over the D features of delta: P = K delta^T (key blocks jt <= TW), then the state product.
-        // Vector-ALU work of the pass that does not depend on the sweep in flight is issued between its MFMAs:
-        // xi += delta during the first sweep, the masking of P during the second.
+        // One sweep over the D features of delta for both products that take it as B operand: P = K delta^T (key
+        // blocks jt <= TW) and the state product. xi += delta is issued between its MFMAs.
         f32x16 pacc[NJ];
         auto add_delta = [&](auto step) {
             constexpr int S = decltype(step)::value;
@@ -503,18 +539,9 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
                 if (idx < TOTAL) xi[idx / 16][idx % 16] += dl[idx / 16][idx % 16];
             }
         };
-        fused_gemm<MMA, NSTEPS, NJ, decltype(add_delta), NJ>(Kset, myX, pacc, lane, add_delta);
+        fused_pass_sweep<MMA, NSTEPS, NJ, NBH>(Kset, Hset, myX, pacc, gS, lane, add_delta);
         frag pm[NJ][HS];
-        fused_gemm<MMA, NSTEPS, NBH>(Hset, myX, gS, lane, [&](auto step) {
-            constexpr int S = decltype(step)::value;
-            if constexpr (S < NJ * HS) {
-                constexpr int jt = S / HS, hh = S % HS;
-                float t[VEC];
-#pragma unroll
-                for (int p = 0; p < VEC; ++p) t[p] = pacc[jt][hh * VEC + p] * mreg[jt][hh * VEC + p];
-                pm[jt][hh] = MMA::pack(t);
-            }
-        });
+        mask_p<MMA, TW>(pacc, mreg, pm);
         lds_barrier();                       // the exchange region may be overwritten from here on
         omega = 4.0f / (4.0f - rho2 * omega);                      // weight schedule
         const float cm = omega - 1.0f, ncs = -omega * s0;
