@@ -402,7 +402,9 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
             float bj = 1.0f;
             if constexpr (GATED)
                 bj = g ? lane_value(ball, 32 * jt + kidx(r, 1)) : lane_value(ball, 32 * jt + kidx(r, 0));
-            mreg[jt][r] = (j <= c_local) ? (GATED ? bj * exp2f(Gc - Gj) : exp2f(Gc - Gj)) : 0.0f;
+            // hardware exp2: results below the normal range (decays under 2^-126) are flushed to zero
+            const float decay = __builtin_amdgcn_exp2f(Gc - Gj);
+            mreg[jt][r] = (j <= c_local) ? (GATED ? bj * decay : decay) : 0.0f;
         }
     const float bc = GATED ? __shfl(ball, c_local, 64) : 1.0f;   // write gate of this lane's token
     __builtin_amdgcn_sched_barrier(0);         // the mask is not scheduled behind the wait for the k rows
@@ -441,9 +443,8 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     const frag *myK = sK + (TW * NSTEPS) * 64;         // this token block's keys as a B operand
     {
         f32x16 acc[NJ + NBH];
-#pragma unroll
-        for (int x = 0; x < NJ + NBH; ++x) acc[x] = zero16();
-        fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myK, acc, lane);
+        fused_gemm<MMA, NSTEPS, NJ + NBH, NoFill, NJ + NBH>(Aset, myK, acc, lane);
+        GKA_TSTAMP(12);
         // k_c^T H_[n] k_c: this wave's rows of H_[n] k_c, then summed over the two feature halves
         float a_part = 0.0f;
 #pragma unroll
@@ -456,25 +457,29 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
             }
         a_part += __shfl_xor(a_part, 32, 64);
         if (g == 0) sA[fh * kChunk + c_local] = a_part;
+        // sum_{i<c} m[i,c] G_ic^2: the mask is zero above the diagonal, so the sum runs over the whole column and the
+        // diagonal term m[c,c] G_cc^2 (m[c,c] = beta_c) is taken out again; G_cc^2 sits in the diagonal key block
         float b_part = 0.0f, d_part = 0.0f;
 #pragma unroll
         for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int j = 32 * jt + kidx(r, g);
-                const float g2 = acc[jt][r] * acc[jt][r];
-                if (j < c_local) b_part += mreg[jt][r] * g2;
-                if (j == c_local) d_part += g2;
-            }
+            for (int r = 0; r < 16; ++r) b_part += mreg[jt][r] * (acc[jt][r] * acc[jt][r]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (32 * TW + kidx(r, g) == c_local) d_part = acc[TW][r] * acc[TW][r];
+        b_part -= bc * d_part;
         b_part += __shfl_xor(b_part, 32, 64);
         d_part += __shfl_xor(d_part, 32, 64);
+        GKA_TSTAMP(13);
         lds_barrier();
+        GKA_TSTAMP(14);
         if (fh == 0 && g == 0) {
             const float cross = 2.0f * (zeta * (sA[c_local] + sA[kChunk + c_local]) + b_part);
             sW[c_local] = GATED ? (bc > 0.0f ? cross / bc + d_part : 0.0f) : cross + d_part;
         }
     }
     lds_barrier();
+    GKA_TSTAMP(15);
     float fro;
     {
         float f_part = 0.0f;
@@ -637,9 +642,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     wait_all_memory();
     lds_barrier();
     f32x16 acc[NJ + NBH];
-#pragma unroll
-    for (int x = 0; x < NJ + NBH; ++x) acc[x] = zero16();
-    fused_gemm<MMA, NSTEPS, NJ + NBH>(Aset, myX, acc, lane);          // K xhat^T and U xhat
+    fused_gemm<MMA, NSTEPS, NJ + NBH, NoFill, NJ + NBH>(Aset, myX, acc, lane);   // K xhat^T and U xhat
     if (NSPL == 2) {
         // remainder of U_[n] (registers) times the rounded xhat (still published)
 #pragma unroll
