@@ -569,12 +569,18 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
             for (int r = 0; r < 16; ++r) dl[i][r] += ncl * xi[i][r];
 #pragma unroll
         for (int i = 0; i < NBH; ++i) {
+            // The last term is written as inline assembly (below). The compiler does not track the matrix pipe's
+            // result hazard for inline assembly: a vector instruction may read an MFMA result only 3 + (number of
+            // passes of the MFMA, at most 16) wait states after it was issued, and for its own instructions the
+            // compiler inserts the idle cycles. Here they are spelled out: the statement reads gI[i], so it follows the
+            // MFMAs that produce it, and volatile assembly statements keep their order, so it precedes the reads below.
+            asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : : "v"(gI[i][0]));
 #pragma unroll
             for (int r = 0; r < 16; ++r) {                                               // delta_i
                 // three-address form: the result goes straight into the loop-carried register instead of a
                 // temporary that is copied there at the end of the pass
                 float t = dl[i][r];
-                asm("v_fma_f32 %0, %1, %2, %3" : "=v"(dl[i][r]) : "v"(ncs), "v"(gI[i][r]), "v"(t));
+                asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(dl[i][r]) : "v"(ncs), "v"(gI[i][r]), "v"(t));
             }
 #pragma unroll
             for (int hh = 0; hh < HS; ++hh) own[i][hh] = MMA::pack(&dl[i][hh * VEC]);
