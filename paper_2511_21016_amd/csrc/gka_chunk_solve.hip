@@ -570,17 +570,19 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int i = 0; i < NBH; ++i) {
             // The last term is written as inline assembly (below). The compiler does not track the matrix pipe's
-            // result hazard for inline assembly: a vector instruction may read an MFMA result only 3 + (number of
-            // passes of the MFMA, at most 16) wait states after it was issued, and for its own instructions the
-            // compiler inserts the idle cycles. Here they are spelled out: the statement reads gI[i], so it follows the
-            // MFMAs that produce it, and volatile assembly statements keep their order, so it precedes the reads below.
-            asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : : "v"(gI[i][0]));
+            // result hazard for inline assembly: a vector instruction may read an MFMA result only some wait states
+            // after the MFMA was issued, and only for its own instructions does the compiler insert the idle cycles.
+            // So the first read of gI[i] is one of its own: the coefficient of the assembly statements is routed
+            // through an instruction that reads gI[i] (0 * gI + ncs), which orders them behind it and behind the wait.
+            // (The converse also holds: no MFMA may take a register that inline assembly has just written. The
+            // results below go to LDS and to vector instructions only.)
+            const float ncs_i = __builtin_fmaf(gI[i][0], 0.0f, ncs);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {                                               // delta_i
                 // three-address form: the result goes straight into the loop-carried register instead of a
                 // temporary that is copied there at the end of the pass
                 float t = dl[i][r];
-                asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(dl[i][r]) : "v"(ncs), "v"(gI[i][r]), "v"(t));
+                asm("v_fma_f32 %0, %1, %2, %3" : "=v"(dl[i][r]) : "v"(ncs_i), "v"(gI[i][r]), "v"(t));
             }
 #pragma unroll
             for (int hh = 0; hh < HS; ++hh) own[i][hh] = MMA::pack(&dl[i][hh * VEC]);
@@ -596,7 +598,13 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
     const frag *Uw = (const frag *)a.ws_U + chunk_id * (NSPL * SH::H_FRAGS * 64);
     RowStage<MMA, IO, D> vrows;
-    vrows.load(a.v, base_bh, a.stride_t, tok0, a.T, tid);
+    // The addresses of the readout's loads and staging stores are formed here, from a copy of the thread index that
+    // the compiler cannot trace back past this point: formed before the passes (where it would hoist them, or keep
+    // those of the k rows) they would occupy registers across the loop.
+    int tid_late = tid;
+    asm volatile("" : "+v"(tid_late));
+    const int lane_late = tid_late & 63;
+    vrows.load(a.v, base_bh, a.stride_t, tok0, a.T, tid_late);
     // alpha-connection (Section 4.3): the readout is applied to alpha xhat + (1 - alpha) q
     if (GATED && a.alpha) {
         const float al = valid ? a.alpha[gate_base + (int64_t)tok * a.H] : 1.0f;
@@ -634,14 +642,14 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int i = 0; i < NBH; ++i)
 #pragma unroll
-            for (int st = 0; st < NSTEPS; ++st) ulo[i][st] = Ulo[((mt0 + i) * NSTEPS + st) * 64 + lane];
+            for (int st = 0; st < NSTEPS; ++st) ulo[i][st] = Ulo[((mt0 + i) * NSTEPS + st) * 64 + lane_late];
     }
     lds_barrier();                           // every wave is done with H_[n], K^T and the exchange region
     GKA_TSTAMP(8);
-    async_block_copy<H16>(sH, Uw, w, lane);    // U_[n] (rounded part) replaces H_[n]
-    vrows.store(sRow, tok0, a.T, tid);
+    async_block_copy<H16>(sH, Uw, w, lane_late);    // U_[n] (rounded part) replaces H_[n]
+    vrows.store(sRow, tok0, a.T, tid_late);
     lds_barrier();
-    build_transposed_frags<MMA, D, true>(sKT, sRow, w, lane);      // V^T replaces K^T
+    build_transposed_frags<MMA, D, true>(sKT, sRow, w, lane_late);      // V^T replaces K^T
     lds_barrier();                           // the staging tile becomes the exchange region again
     GKA_TSTAMP(9);
     publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
