@@ -19,8 +19,8 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak
 # HBM bytes of one solve-kernel launch on this workload, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/chunk_solve_and_state_pass_cfg2_hbm_traffic.md (604 MiB read + 76 MiB written). Update with the kernel.
-SOLVE_TRAFFIC_BYTES = (604 + 76) * (1 << 20)
+# profiles/chunk_solve_and_state_pass_cfg2_hbm_traffic.md (593 MiB read + 64 MiB written). Update with the kernel.
+SOLVE_TRAFFIC_BYTES = (593 + 64) * (1 << 20)
 # the same for one decode-step launch on the configuration-5 shape (1031 MiB read + 1026 MiB written)
 DECODE_TRAFFIC_BYTES = (1031 + 1026) * (1 << 20)
 # and with the reduced layout of H (839 MiB read + 834 MiB written)
