@@ -246,3 +246,54 @@ def test_packed_variable_length_sequences(dtype):
         ref = oracle.forward(part["q"], part["k"], part["v"], part["gate"], part["lam"], w.n_iter)
         err = pair_rel_err(y[:, s0:s0 + n], ref)
         assert err <= tol, (s0, n, err)
+
+
+def _random_case(i):
+    """Seeded draw of one configuration: shape, dtypes, variants, initial state."""
+    rng = np.random.default_rng(9000 + i)
+    dtype, compute = [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32")][int(rng.integers(3))]
+    return dict(B=int(rng.integers(1, 4)), H=int(rng.integers(1, 5)), T=int(rng.integers(1, 300)),
+                d=int(rng.choice([64, 128])), n_iter=int(rng.integers(0, 13)), dtype=dtype, compute=compute,
+                beta=bool(rng.integers(2)), alpha=bool(rng.integers(2)), rule=bool(rng.integers(2)),
+                init=bool(rng.integers(2)), seed=9000 + i)
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_random_configurations(i):
+    """24 seeded random draws over shapes (ragged T included), dtypes, compute modes, layer variants and initial
+    states: output and final states against the oracle."""
+    import torch
+    c = _random_case(i)
+    base = synth.CFG2 if c["dtype"] == "bf16" else synth.CFG1
+    w = base.scaled(B=c["B"], H=c["H"], T=c["T"], d=c["d"], n_iter=c["n_iter"], seed=c["seed"])
+    x = synth.make_inputs(w)
+    gates = synth.make_gates(w)
+    kw, okw = {}, {}
+    if c["beta"]:
+        kw["beta"], okw["beta"] = to_device(gates["beta"], "f32"), gates["beta"]
+    if c["alpha"]:
+        kw["alpha"], okw["alpha"] = to_device(gates["alpha"], "f32"), gates["alpha"]
+    lam_h = x["lam"]
+    if c["rule"]:
+        kw["lambda_scale"] = okw["lambda_scale"] = 0.05
+        lam_h = None
+    if c["init"]:
+        rng = np.random.default_rng(c["seed"] + 1)
+        A = rng.standard_normal((w.B, w.H, w.d, w.d)).astype(np.float32) / np.sqrt(w.d)
+        H0 = np.ascontiguousarray(A @ np.transpose(A, (0, 1, 3, 2)))
+        H0 = (0.5 * (H0 + np.transpose(H0, (0, 1, 3, 2)))).astype(np.float32)      # exactly symmetric in fp32
+        U0 = rng.standard_normal((w.B, w.H, w.d, w.d)).astype(np.float32)
+        kw["H_init"], kw["U_init"] = to_device(H0, "f32"), to_device(U0, "f32")
+        okw["H_init"], okw["U_init"] = H0.astype(np.float64), U0.astype(np.float64)
+    dev = upload_inputs(x, w.dtype)
+    cm = binding.GKA_COMPUTE_BF16 if c["compute"] == "bf16" else binding.GKA_COMPUTE_F32
+    o, ex = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], None if c["rule"] else dev["lam"],
+                                w.n_iter, compute=cm, return_state=True, **kw)
+    torch.cuda.synchronize()
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], lam_h, w.n_iter, return_state=True, **okw)
+    tol = TOL_BF16 if c["compute"] == "bf16" else (TOL_F32 if c["dtype"] == "f32" else TOL_BF16)
+    assert pair_rel_err(to_host(o), ref) <= tol, c
+    st_tol = 2e-2 if c["compute"] == "bf16" else 2e-5
+    for name in ("H_final", "U_final"):
+        np.testing.assert_allclose(to_host(ex[name]), rex[name], rtol=0, atol=st_tol * np.abs(rex[name]).max(),
+                                   err_msg=str(c))
