@@ -106,7 +106,7 @@ gka_status make_plan(const gka_params *p, Plan *pl)
     // Segments of the chunk scan. A workgroup walks its chunks one after the other (a few microseconds each), and a
     // segmented pass reads k and v twice, so: one segment unless that leaves CUs idle or makes the walk longer than
     // about 64 chunks; never fewer than two chunks per segment.
-    const int wg_per_seg = pl->pairs_per_batch * 2 * (pl->d / 32);
+    const int wg_per_seg = gka::state_pass_workgroups_per_segment(pl->pairs_per_batch, pl->d, pl->compute_bf16);
     int n_segs = (kStateMinWorkgroups + wg_per_seg - 1) / wg_per_seg;
     if (n_segs < pl->slab_chunks / kStateMaxWalk) n_segs = pl->slab_chunks / kStateMaxWalk;
     if (n_segs > pl->slab_chunks / 2) n_segs = pl->slab_chunks / 2;

@@ -62,6 +62,8 @@ struct DecodeArgs {
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
                              hipStream_t stream);
+// Workgroups the state pass launches per segment of the chunk scan (the plan sizes the segments with it).
+int state_pass_workgroups_per_segment(int n_pairs, int d, bool compute_bf16);
 hipError_t launch_chunk_solve(const SolveArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
                               hipStream_t stream);
 hipError_t launch_decode_step(const DecodeArgs &a, int n_pairs, int d, bool io_bf16, hipStream_t stream);

@@ -587,6 +587,272 @@ __device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int
     store_end_state<D, DOH>(a, acc, Gseg, pair, seg, rb, w, lane);
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Whole-tile variant of the bf16 body: one workgroup owns all row blocks of one state (H or U) of a pair and walks
+// a segment of its chunks. Wave w keeps column block w of every row block (NB accumulators), so its A fragments (the
+// chunk's unscaled k columns of block w) are read once and used NB times, and the latency of a chunk step (barriers,
+// LDS round trips, the wait for the copies) is paid once for NB times the work of a slab step. The B tile holds all
+// D columns of the scaled k (H) or v (U) rows. Two k buffers (copy one chunk ahead).
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// Four transpose reads (one per MFMA step, STEP bytes apart) from one lane address; not waited for here.
+template <int STEP>
+__device__ __forceinline__ void issue_tr4(uint32_t addr, u32x2_t (&r)[4])
+{
+    asm volatile("ds_read_b64_tr_b16 %0, %4\n\t"
+                 "ds_read_b64_tr_b16 %1, %4 offset:%5\n\t"
+                 "ds_read_b64_tr_b16 %2, %4 offset:%6\n\t"
+                 "ds_read_b64_tr_b16 %3, %4 offset:%7"
+                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3])
+                 : "v"(addr), "n"(STEP), "n"(2 * STEP), "n"(3 * STEP)
+                 : "memory");
+}
+// At most N LDS operations issued after the reads into lo / hi are still outstanding: those reads have landed. The
+// registers pass through the statement so that their uses stay behind it.
+template <int N>
+__device__ __forceinline__ void await_tr8(u32x2_t (&lo)[4], u32x2_t (&hi)[4])
+{
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(lo[0]), "+v"(lo[1]), "+v"(lo[2]), "+v"(lo[3]), "+v"(hi[0]), "+v"(hi[1]), "+v"(hi[2]), "+v"(hi[3])
+                 : "n"(N)
+                 : "memory");
+}
+__device__ __forceinline__ bf16x8 join_runs(const u32x2_t &lo, const u32x2_t &hi)
+{
+    const u32x4_t u = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+template <class IO, int D, bool DOH, bool WRITE, bool GATED>
+__device__ __forceinline__ void state_pass_body_bf16_tile(const StatePassArgs &a, int group, uint16_t *s_k, uint16_t *s_b)
+{
+    typedef MmaBF16 MMA;
+    typedef typename MMA::frag frag;
+    constexpr int NB = D / 32;
+    constexpr int HS = MMA::HS;
+    constexpr int STEPS = kChunk / 16;            // MFMA steps over the chunk's tokens
+    constexpr int NT = D * 2;                     // threads
+    constexpr int NW = NT / 64;                   // waves = column blocks
+    constexpr int RSB = D + MMA::kRowPad;         // row stride of the B tile (elements)
+    constexpr int ROWB = D * 2;                   // bytes per k row
+    constexpr int KBUF = kChunk * D;              // elements per k buffer
+    constexpr int NA = kChunk * ROWB / (NT * 16); // 16-byte copies per thread per chunk
+    constexpr int LPR = ROWB / 16;                // lanes (16-byte pieces) per row
+    constexpr int RPI = 64 / LPR;                 // rows per wave-wide copy instruction
+    constexpr int PPR = D / 4;                    // 4-element pieces per row of the B tile
+    constexpr int VP = kChunk * PPR / NT;         // pieces of the B tile per thread
+    constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
+    constexpr int NS = WRITE ? NB * (DOH ? HS + 1 : HS * NSPL) : 0;   // state stores per chunk
+    static_assert(NW == NB && STEPS == 4, "one wave per column block, four MFMA steps per chunk");
+    static_assert(NA + NS < 64, "the counted wait below fits the counter");
+    typedef SwizzledRows<ROWB, 2> KRows;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // column block owned by this wave (uniform)
+    const int g = lane >> 5;
+    const int pair = group % a.n_pairs;
+    const int seg = group / a.n_pairs;
+    const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
+    const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    const int64_t gate_base = (int64_t)b * a.T * a.H + h;
+    const int chunk_begin = a.chunk0 + seg * a.seg_len;
+    const int chunk_end = min(chunk_begin + a.seg_len, a.chunk0 + a.n_chunks);
+    const int c_last = max(chunk_end - 1, chunk_begin);
+    const void *bsrc = DOH ? a.k : a.v;
+
+    f32x16 acc[NB];
+#pragma unroll
+    for (int rb = 0; rb < NB; ++rb) {
+        acc[rb] = zero16();
+        load_start_state<D, DOH>(a, acc[rb], pair, seg, rb, w, lane);
+    }
+
+    const int lrow = lane / LPR, lbyte = (lane % LPR) * 16;
+    const int row_bytes = (int)a.stride_t * 2;
+    auto issue_k = [&](int c, int buf) {
+        const uint16_t *base = (const uint16_t *)a.k + base_bh + (int64_t)c * kChunk * a.stride_t;
+        const buffer_rsrc rsrc = make_raw_buffer(base);
+        const int last_row = a.T - 1 - c * kChunk;
+#pragma unroll
+        for (int q = 0; q < NA; ++q) {
+            const int row = (q * NW + w) * RPI + lrow;
+            const int sbyte = lbyte ^ ((row & KRows::kMask) << 5);
+            async_copy16_to_lds(s_k + buf * KBUF + (q * NW + w) * 512, rsrc, min(row, last_row) * row_bytes + sbyte, 0);
+        }
+    };
+    struct Fetch {
+        typename IO::raw4 b[VP];
+        float gate, beta;
+    };
+    const float *beta_src = a.beta ? a.beta : a.gate;
+    auto fetch = [&](Fetch &f, int c) {
+#pragma unroll
+        for (int i = 0; i < VP; ++i) {
+            const int piece = i * NT + tid;
+            const int t = min(c * kChunk + piece / PPR, a.T - 1);
+            f.b[i] = IO::load_raw4(bsrc, base_bh + (int64_t)t * a.stride_t + 4 * (piece % PPR));
+        }
+        const int t = min(c * kChunk + lane, a.T - 1);
+        f.gate = a.gate[gate_base + (int64_t)t * a.H];
+        if constexpr (GATED) f.beta = beta_src[gate_base + (int64_t)t * a.H];
+    };
+    float Gseg = 0.0f;
+    int kb = 0;                                   // buffer that holds the chunk being processed
+    // transpose-read addresses of this lane, as in the slab body; the B tile's row blocks are 64 bytes apart
+    const int sub = 16 * ((lane >> 4) & 1);
+    const int li = lane & 15;
+    const uint32_t ka0 = lds_address(s_k + KRows{}(8 * g + (li >> 2), 32 * w + sub + 4 * (li & 3)));
+    const uint32_t ka1 = lds_address(s_k + KRows{}(8 * g + 4 + (li >> 2), 32 * w + sub + 4 * (li & 3)));
+    const uint32_t kb0 = lds_address(s_b + (8 * g + (li >> 2)) * RSB + sub + 4 * (li & 3));
+
+    auto process = [&](const Fetch &f, int c) {
+        __builtin_amdgcn_sched_barrier(0);
+        const bool valid = c * kChunk + lane < a.T;
+        const float lg = valid ? log2_gate(f.gate) : 0.0f;
+        const float G = wave_inclusive_scan(lg, lane);
+        const float Gtot = lane_value(G, 63);
+        Gseg += Gtot;
+        float wj = valid ? exp2f(Gtot - G) : 0.0f;     // lane j: weight of token j
+        if constexpr (GATED) wj *= a.beta ? f.beta : 1.0f;
+        const float zetaC = exp2f(Gtot);
+        lds_barrier();                          // the previous chunk's operand reads are done
+        issue_k(min(c + 1, c_last), kb ^ 1);
+#pragma unroll
+        for (int i = 0; i < VP; ++i) {
+            const int piece = i * NT + tid;
+            const int row = piece / PPR;
+            MMA::store4(s_b + row * RSB + 4 * (piece % PPR), IO::cvt4(f.b[i]) * __shfl(wj, row, 64));
+        }
+        // ---- write the state before the chunk, fragment order
+        if (WRITE) {
+            const int64_t chunk_id = (int64_t)(c - a.chunk0) * a.n_pairs + pair;   // chunk-major: pairs adjacent
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb) {
+                float vals[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) vals[r] = acc[rb][r];
+                if (DOH) {
+                    frag *Hw = (frag *)a.ws_H + chunk_id * (NB * NB * HS * 64);
+                    float ss = 0.0f;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) ss += vals[r] * vals[r];
+#pragma unroll
+                    for (int hh = 0; hh < HS; ++hh)
+                        Hw[((rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(vals + hh * MMA::VEC);
+                    ss = wave_inclusive_scan(ss, lane);           // lane 63: the wave's total
+                    if (lane == 63) a.ws_hn[chunk_id * (NB * NB) + rb * NB + w] = ss;
+                } else {
+                    frag *Uw = (frag *)a.ws_U + chunk_id * (NSPL * NB * NB * HS * 64);
+                    float lo[16];
+#pragma unroll
+                    for (int hh = 0; hh < HS; ++hh) {
+                        frag fr = MMA::pack(vals + hh * MMA::VEC);
+                        Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
+                        float back[MMA::VEC];
+                        MMA::unpack(fr, back);
+#pragma unroll
+                        for (int p = 0; p < MMA::VEC; ++p) lo[hh * MMA::VEC + p] = vals[hh * MMA::VEC + p] - back[p];
+                    }
+                    if (NSPL == 2) {
+#pragma unroll
+                        for (int hh = 0; hh < HS; ++hh)
+                            Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(lo + hh * MMA::VEC);
+                    }
+                }
+            }
+        }
+        // This chunk's copy was issued one iteration ago, right after a barrier, followed by that iteration's stores
+        // and prefetch loads; this iteration has added its copies and stores. (Letting the older stores stay in
+        // flight as well, by issuing the prefetch loads ahead of the stores, was measured and is slower.)
+        wait_vector_memory_upto<NA + NS>();
+        lds_barrier();                          // k rows (all waves' copies) and the B tile are visible
+
+        // ---- S <- zeta_C S + sum_j w_j a_j k_j^T. The LDS counter holds 15 operations, so the operand reads go in
+        // groups: A and the first row block's B, then each further row block's B while the products of the block
+        // before it run.
+        u32x2_t fa0[4], fa1[4], fb0[NB][4], fb1[NB][4];
+        issue_tr4<16 * ROWB>(ka0 + kb * (KBUF * 2), fa0);
+        issue_tr4<16 * ROWB>(ka1 + kb * (KBUF * 2), fa1);
+        issue_tr4<16 * RSB * 2>(kb0, fb0[0]);
+        issue_tr4<16 * RSB * 2>(kb0 + 4 * RSB * 2, fb1[0]);
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rb][r] *= zetaC;
+        await_tr8<0>(fa0, fa1);
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb) {
+            await_tr8<0>(fb0[rb], fb1[rb]);
+            if (rb + 1 < NB) {
+                issue_tr4<16 * RSB * 2>(kb0 + 64 * (rb + 1), fb0[rb + 1]);
+                issue_tr4<16 * RSB * 2>(kb0 + 64 * (rb + 1) + 4 * RSB * 2, fb1[rb + 1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < STEPS; ++s)
+                acc[rb] = MMA::mma(join_runs(fa0[s], fa1[s]), join_runs(fb0[rb][s], fb1[rb][s]), acc[rb]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        kb ^= 1;
+    };
+
+    int c = chunk_begin;
+    issue_k(c, 0);
+    if ((chunk_end - chunk_begin) & 1) {
+        Fetch fp;
+        fetch(fp, c);
+        drain_vector_memory();
+        process(fp, c);
+        ++c;
+    }
+    if (c < chunk_end) {
+        Fetch f0, f1;
+        fetch(f0, c);
+        fetch(f1, c + 1);
+        drain_vector_memory();
+        for (; c < chunk_end; c += 2) {
+            process(f0, c);
+            fetch(f0, min(c + 2, c_last));
+            process(f1, c + 1);
+            fetch(f1, min(c + 3, c_last));
+        }
+    }
+    // no copy into this workgroup's LDS may still be in flight when it ends
+    drain_vector_memory();
+#pragma unroll
+    for (int rb = 0; rb < NB; ++rb) store_end_state<D, DOH>(a, acc[rb], Gseg, pair, seg, rb, w, lane);
+}
+
+// One workgroup per (pair, segment, H or U). The two workgroups of a (pair, segment) read the same k rows: they get
+// block indices that are equal modulo 8, i.e. the same XCD and L2.
+template <class IO, int D, bool GATED>
+__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE_WAVES))) void state_pass_tile_kernel(StatePassArgs a)
+{
+    constexpr int PER = 2;
+    const int id = blockIdx.x;
+    const int full = (gridDim.x / (8 * PER)) * (8 * PER);
+    int sub, group;
+    if (id < full) {
+        const int within = id % (8 * PER);
+        sub = within / 8;
+        group = (id / (8 * PER)) * 8 + within % 8;
+    } else {
+        sub = (id - full) % PER;
+        group = full / PER + (id - full) / PER;
+    }
+    __shared__ __attribute__((aligned(1024))) uint16_t s_k[2 * kChunk * D];
+    __shared__ __attribute__((aligned(16))) uint16_t s_b[kChunk * (D + MmaBF16::kRowPad)];
+    if (a.write_frags) {
+        if (sub & 1) state_pass_body_bf16_tile<IO, D, false, true, GATED>(a, group, s_k, s_b);
+        else state_pass_body_bf16_tile<IO, D, true, true, GATED>(a, group, s_k, s_b);
+    } else {
+        if (sub & 1) state_pass_body_bf16_tile<IO, D, false, false, GATED>(a, group, s_k, s_b);
+        else state_pass_body_bf16_tile<IO, D, true, false, GATED>(a, group, s_k, s_b);
+    }
+}
+
 template <class MMA, class IO, int D, bool GATED>
 __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE_WAVES))) void state_pass_kernel(StatePassArgs a)
 {
@@ -631,11 +897,28 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
     }
 }
 
+// Workgroups per (pair, segment): bf16 operands use the whole-tile kernel (one workgroup for H, one for U), fp32
+// operands the slab kernel (one per 32-row slab and state).
+#ifndef GKA_STATE_SLABS
+#define GKA_STATE_SLABS 0          // 1: bf16 operands on the slab kernel as well
+#endif
+template <class MMA, int D>
+constexpr bool uses_tile_kernel() { return std::is_same<MMA, MmaBF16>::value && !GKA_STATE_SLABS; }
+
 template <class MMA, class IO, int D, bool GATED>
-static hipError_t launch_state_pass_g(const StatePassArgs &a0, int n_pairs, hipStream_t stream)
+static void launch_state_kernel(const StatePassArgs &a, int n_groups, hipStream_t stream)
 {
     constexpr int NB = D / 32;
     dim3 block(D * 2);
+    if constexpr (uses_tile_kernel<MMA, D>())
+        hipLaunchKernelGGL((state_pass_tile_kernel<IO, D, GATED>), dim3(n_groups * 2), block, 0, stream, a);
+    else
+        hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D, GATED>), dim3(n_groups * 2 * NB), block, 0, stream, a);
+}
+
+template <class MMA, class IO, int D, bool GATED>
+static hipError_t launch_state_pass_g(const StatePassArgs &a0, int n_pairs, hipStream_t stream)
+{
     StatePassArgs a = a0;
     a.n_pairs = n_pairs;
     if (a.n_segs <= 1) {
@@ -646,7 +929,7 @@ static hipError_t launch_state_pass_g(const StatePassArgs &a0, int n_pairs, hipS
         a.init_mode = 0;
         a.final_mode = 2;
         a.write_frags = 0;
-        hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D, GATED>), dim3(n_pairs * 2 * NB * (a.n_segs - 1)), block, 0, stream, a);
+        launch_state_kernel<MMA, IO, D, GATED>(a, n_pairs * (a.n_segs - 1), stream);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -654,7 +937,7 @@ static hipError_t launch_state_pass_g(const StatePassArgs &a0, int n_pairs, hipS
     a.init_mode = 1;
     a.final_mode = 1;
     a.write_frags = 1;
-    hipLaunchKernelGGL((state_pass_kernel<MMA, IO, D, GATED>), dim3(n_pairs * 2 * NB * a.n_segs), block, 0, stream, a);
+    launch_state_kernel<MMA, IO, D, GATED>(a, n_pairs * a.n_segs, stream);
     return hipGetLastError();
 }
 
@@ -664,6 +947,12 @@ static hipError_t launch_state_pass_t(const StatePassArgs &a, int n_pairs, hipSt
     // the write gate is the only variant of the layer that reaches this kernel
     if (a.beta) return launch_state_pass_g<MMA, IO, D, true>(a, n_pairs, stream);
     return launch_state_pass_g<MMA, IO, D, false>(a, n_pairs, stream);
+}
+
+int state_pass_workgroups_per_segment(int n_pairs, int d, bool compute_bf16)
+{
+    const bool tile = compute_bf16 && !GKA_STATE_SLABS;
+    return n_pairs * 2 * (tile ? 1 : d / 32);
 }
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
