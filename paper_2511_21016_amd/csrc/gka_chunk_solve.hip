@@ -544,7 +544,12 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
                 if (idx < TOTAL) xi[idx / 16][idx % 16] += dl[idx / 16][idx % 16];
             }
         };
-        fused_pass_sweep<MMA, NSTEPS, NJ, NBH>(Kset, Hset, myX, pacc, gS, lane, add_delta);
+        if constexpr (MMA::kFusedPassSweep) {
+            fused_pass_sweep<MMA, NSTEPS, NJ, NBH>(Kset, Hset, myX, pacc, gS, lane, add_delta);
+        } else {
+            fused_gemm<MMA, NSTEPS, NJ, decltype(add_delta), NJ>(Kset, myX, pacc, lane, add_delta);
+            fused_gemm<MMA, NSTEPS, NBH>(Hset, myX, gS, lane);
+        }
         frag pm[NJ][HS];
         mask_p<MMA, TW>(pacc, mreg, pm);
         lds_barrier();                       // the exchange region may be overwritten from here on
@@ -553,15 +558,26 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         // -r_{i-1} = zeta gS + gI + lam xi; delta_i = cm delta_{i-1} - omega s0 r_{i-1}: the gS term is formed while the
         // MFMAs that finish gI are in flight
         constexpr int TOTAL = NBH * 16, NM = NBH * (TW + 1) * HS, PERM = (TOTAL + NM - 1) / NM;
-        gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, gI, lane, [&](auto step) {
-            constexpr int S = decltype(step)::value;
+        if constexpr (MMA::kFusedPassSweep) {
+            gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, gI, lane, [&](auto step) {
+                constexpr int S = decltype(step)::value;
+                const float ncz = ncs * zeta;
+#pragma unroll
+                for (int e = 0; e < PERM; ++e) {
+                    const int idx = S * PERM + e;
+                    if (idx < TOTAL)
+                        dl[idx / 16][idx % 16] = cm * dl[idx / 16][idx % 16] + ncz * gS[idx / 16][idx % 16];
+                }
+            });
+        } else {
+            // many short MFMAs per product: the compiler's own schedule is better than a pinned interleaving
+            gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, gI, lane);
             const float ncz = ncs * zeta;
 #pragma unroll
-            for (int e = 0; e < PERM; ++e) {
-                const int idx = S * PERM + e;
-                if (idx < TOTAL) dl[idx / 16][idx % 16] = cm * dl[idx / 16][idx % 16] + ncz * gS[idx / 16][idx % 16];
-            }
-        });
+            for (int i = 0; i < NBH; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) dl[i][r] = cm * dl[i][r] + ncz * gS[i][r];
+        }
         const float ncl = ncs * lam;
 #pragma unroll
         for (int i = 0; i < NBH; ++i)

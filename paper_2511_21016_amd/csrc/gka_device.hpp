@@ -194,6 +194,9 @@ struct MmaBF16 {
     static constexpr int VEC = 8;
     static constexpr int HS = 2;
     static constexpr bool kSplitReadout = true;   // readout uses hi+lo operands
+    // P and the state product of a pass share one sweep over delta, and part of the update is pinned between the
+    // MFMAs of the intra-chunk product
+    static constexpr bool kFusedPassSweep = true;
     typedef bf16x8 frag;
     typedef uint16_t elem_t;                      // operand element as stored in LDS rows
     // Padding of a row-major LDS tile (elements): rows 32 bytes apart modulo 256, so that the four rows
@@ -248,6 +251,9 @@ struct MmaF32 {
     static constexpr int VEC = 1;
     static constexpr int HS = 16;
     static constexpr bool kSplitReadout = false;
+    // 64 contraction steps per sweep and 64 MFMAs per intra-chunk product: the fused sweep's staggered reads and a
+    // pinned interleaving cost more than they save
+    static constexpr bool kFusedPassSweep = false;
     typedef float frag;
     typedef float elem_t;
     static constexpr int kRowPad = 4;
