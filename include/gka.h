@@ -98,6 +98,11 @@ typedef struct {
                           /*   U_t = gamma_t U_{t-1} + beta_t v_t k_t^T; [B,T,H] ([B,H] for decode)     */
     const float *alpha;   /* DEVICE pointer or NULL (= 1): alpha-connection, the readout becomes        */
                           /*   y_t = U_t (alpha_t xhat_t + (1 - alpha_t) q_t); same shape as beta       */
+    float *xhat_out;      /* DEVICE pointer or NULL: gka_forward also writes the solve's result            */
+                          /*   xhat_t = CH(H_t + lambda_t I, q_t, r) here, packed [B,T,H,d_k] float32       */
+                          /*   (before the alpha-connection). With q := an incoming gradient this is the    */
+                          /*   solve of the backward pass, CH(H_t + lambda_t I, dxhat_t, r) (Section 4.2.2). */
+                          /*   Ignored by the decode entry points.                                          */
 } gka_params;
 
 /* Bytes of scratch gka_forward needs for these parameters (0 if they are invalid). The buffer must

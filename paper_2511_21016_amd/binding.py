@@ -35,7 +35,7 @@ class GkaParams(ctypes.Structure):
         ("phase", ctypes.c_int32),
         ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
         ("lambda_scale", ctypes.c_float), ("state_layout", ctypes.c_int32),
-        ("beta", ctypes.c_void_p), ("alpha", ctypes.c_void_p),
+        ("beta", ctypes.c_void_p), ("alpha", ctypes.c_void_p), ("xhat_out", ctypes.c_void_p),
     ]
 
 
@@ -91,12 +91,12 @@ def version():
 
 
 def make_params(B, H, T, d, n_iter, io_dtype, compute, chunk=64, d_v=None, strides=(0, 0, 0), phase=0,
-                lambda_scale=0.0, beta=None, alpha=None, state_layout=0):
-    """beta, alpha: device addresses (ints) of the optional per-token gates, or None."""
+                lambda_scale=0.0, beta=None, alpha=None, state_layout=0, xhat_out=None):
+    """beta, alpha, xhat_out: device addresses (ints) of the optional per-token gates / solve output, or None."""
     return GkaParams(B=B, H=H, T=T, d_k=d, d_v=d if d_v is None else d_v, chunk=chunk, n_iter=n_iter,
                      io_dtype=io_dtype, compute=compute, phase=phase,
                      stride_b=strides[0], stride_t=strides[1], stride_h=strides[2],
-                     lambda_scale=lambda_scale, state_layout=state_layout, beta=beta, alpha=alpha)
+                     lambda_scale=lambda_scale, state_layout=state_layout, beta=beta, alpha=alpha, xhat_out=xhat_out)
 
 
 def forward_workspace_bytes(params):
@@ -150,10 +150,10 @@ def _ptr(t):
 
 def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=None, U_init=None,
                 return_state=False, return_fro=False, workspace=None, out=None, phase=GKA_PHASE_ALL,
-                beta=None, alpha=None, lambda_scale=0.0, state_layout=GKA_STATE_FULL):
+                beta=None, alpha=None, lambda_scale=0.0, state_layout=GKA_STATE_FULL, return_xhat=False):
     """gka_forward on torch CUDA tensors: q, k, v [B,T,H,d] (float32 or bfloat16, contiguous),
     gate, lam [B,T,H] float32 (lam None: lambda_t = lambda_scale * ||H_t||_F); beta, alpha: optional [B,T,H]
-    float32 write gate and alpha-connection. Enqueues on torch's current stream and returns o (and a dict of
+    float32 write gate and alpha-connection; return_xhat: also the solve's result [B,T,H,d] float32. Enqueues on torch's current stream and returns o (and a dict of
     the requested extras). Nothing here computes: it allocates outputs and passes pointers."""
     import torch
     if not (q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()):
@@ -162,8 +162,10 @@ def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=No
     io = _io_dtype(q)
     if compute is None:
         compute = GKA_COMPUTE_BF16 if io == GKA_BF16 else GKA_COMPUTE_F32
+    xhat = torch.empty((B, T, H, d), dtype=torch.float32, device=q.device) if return_xhat else None
     params = make_params(B, H, T, d, n_iter, io, compute, chunk=chunk, d_v=v.shape[-1], phase=phase,
-                         lambda_scale=lambda_scale, beta=_ptr(beta), alpha=_ptr(alpha), state_layout=state_layout)
+                         lambda_scale=lambda_scale, beta=_ptr(beta), alpha=_ptr(alpha), state_layout=state_layout,
+                         xhat_out=_ptr(xhat))
     nbytes = forward_workspace_bytes(params)
     if nbytes == 0:
         # let the library name the error
@@ -180,6 +182,8 @@ def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=No
     if return_fro:
         fro = torch.empty((B, T, H), dtype=torch.float32, device=q.device)
         extras["fro"] = fro
+    if return_xhat:
+        extras["xhat"] = xhat
     stream = torch.cuda.current_stream(q.device).cuda_stream
     _check(forward_raw(params, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam), _ptr(o), _ptr(H_init),
                        _ptr(U_init), _ptr(Hf), _ptr(Uf), _ptr(fro), _ptr(workspace), workspace.numel(), stream))

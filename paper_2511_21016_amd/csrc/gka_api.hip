@@ -181,6 +181,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     gka::SolveArgs so;
     so.q = q; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
     so.beta = p->beta; so.alpha = p->alpha; so.lambda_scale = p->lambda_scale;
+    so.xhat_out = p->xhat_out;
     so.ws_H = sa.ws_H; so.ws_U = sa.ws_U; so.ws_hn = sa.ws_hn;
     so.stride_b = pl.stride_b; so.stride_t = pl.stride_t; so.stride_h = pl.stride_h;
     so.H = p->H; so.T = p->T; so.n_iter = p->n_iter;
@@ -313,6 +314,6 @@ const char *gka_status_string(gka_status s)
     return "unknown status";
 }
 
-int gka_version(void) { return 300; }
+int gka_version(void) { return 400; }
 
 }  // extern "C"

@@ -621,6 +621,16 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     asm volatile("" : "+v"(tid_late));
     const int lane_late = tid_late & 63;
     vrows.load(a.v, base_bh, a.stride_t, tok0, a.T, tid_late);
+    // optional output of the solve's result (the variants' kernel only, so that the plain kernel carries no trace of it)
+    if (GATED && a.xhat_out && valid) {
+        float *xo = a.xhat_out + (gate_base + (int64_t)tok * a.H) * D;
+#pragma unroll
+        for (int i = 0; i < NBH; ++i)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *(f32x4 *)(xo + 32 * (mt0 + i) + 8 * q4 + 4 * g) =
+                    f32x4{xi[i][4 * q4], xi[i][4 * q4 + 1], xi[i][4 * q4 + 2], xi[i][4 * q4 + 3]};
+    }
     // alpha-connection (Section 4.3): the readout is applied to alpha xhat + (1 - alpha) q
     if (GATED && a.alpha) {
         const float al = valid ? a.alpha[gate_base + (int64_t)tok * a.H] : 1.0f;
@@ -773,7 +783,7 @@ static hipError_t launch_chunk_solve_g(const SolveArgs &a, int n_pairs, hipStrea
 template <class MMA, class IO, int D>
 static hipError_t launch_chunk_solve_t(const SolveArgs &a, int n_pairs, hipStream_t stream)
 {
-    if (a.beta || a.alpha || !a.lambda) return launch_chunk_solve_g<MMA, IO, D, true>(a, n_pairs, stream);
+    if (a.beta || a.alpha || !a.lambda || a.xhat_out) return launch_chunk_solve_g<MMA, IO, D, true>(a, n_pairs, stream);
     return launch_chunk_solve_g<MMA, IO, D, false>(a, n_pairs, stream);
 }
 

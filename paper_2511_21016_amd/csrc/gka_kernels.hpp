@@ -39,6 +39,7 @@ struct SolveArgs {
     float lambda_scale;
     void *o;
     float *fro_out;               // [B,T,H] or nullptr
+    float *xhat_out;              // [B,T,H,d] packed float32 or nullptr: the solve's result
     const void *ws_H, *ws_U;
     const float *ws_hn;
     int64_t stride_b, stride_t, stride_h;

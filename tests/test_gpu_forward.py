@@ -297,3 +297,28 @@ def test_random_configurations(i):
     for name in ("H_final", "U_final"):
         np.testing.assert_allclose(to_host(ex[name]), rex[name], rtol=0, atol=st_tol * np.abs(rex[name]).max(),
                                    err_msg=str(c))
+
+
+@pytest.mark.parametrize("dtype,compute,d", [("f32", "f32", 64), ("f32", "f32", 128), ("bf16", "bf16", 128),
+                                             ("bf16", "bf16", 64), ("bf16", "f32", 128)])
+def test_solve_result_output(dtype, compute, d):
+    """xhat_out: the solve's result before the readout, against the oracle's; with the alpha-connection on, so that
+    the output is seen to be taken before the mix; and the output o is unchanged by asking for it."""
+    import torch
+    base = synth.CFG2 if dtype == "bf16" else synth.CFG1
+    w = base.scaled(B=2, H=2, T=150, d=d, n_iter=7, seed=606 + d)
+    x = synth.make_inputs(w)
+    gates = synth.make_gates(w)
+    dev = upload_inputs(x, w.dtype)
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    alpha = to_device(gates["alpha"], "f32")
+    o, ex = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=cm,
+                                alpha=alpha, return_xhat=True)
+    o2 = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=cm, alpha=alpha)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, alpha=gates["alpha"],
+                              return_xhat=True)
+    tol = TOL_BF16 if compute == "bf16" else 1e-4
+    assert pair_rel_err(to_host(ex["xhat"]), rex["xhat"]) <= tol
+    assert pair_rel_err(to_host(o), ref) <= (TOL_F32 if dtype == "f32" else TOL_BF16)
