@@ -50,6 +50,7 @@ def main():
                          "between two counts isolates the passes); the JSON line then describes that variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-backward", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); every (batch, head) pair is independent, "
@@ -223,6 +224,27 @@ def main():
             ms = d0.elapsed_time(d1) / 20
             multi[f"tokens_per_call_{nt}"] = {"ms_per_call": ms, "sequence_tokens_per_s": dB * nt / (ms * 1e-3)}
         result["decode"]["multi_token"] = multi
+
+    # ---- backward pass on the same workload (extra information, not the headline metric): a composition of forward
+    # kernels, see the header of gka_backward
+    if not args.no_backward:
+        xs = sets[0]
+        dyb = torch.randn_like(xs["v"])
+        bparams = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16)
+        bws = torch.empty(binding.backward_workspace_bytes(bparams), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            binding.gka_backward(xs["q"], xs["k"], xs["v"], xs["gate"], xs["lam"], dyb, w.n_iter, workspace=bws)
+        torch.cuda.synchronize()
+        b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        b0.record()
+        for _ in range(10):
+            binding.gka_backward(xs["q"], xs["k"], xs["v"], xs["gate"], xs["lam"], dyb, w.n_iter, workspace=bws)
+        b1.record()
+        torch.cuda.synchronize()
+        ms_bwd = b0.elapsed_time(b1) / 10
+        result["backward"] = {"ms_per_call": ms_bwd, "tokens_per_s": tokens / (ms_bwd * 1e-3),
+                              "times_forward": ms_bwd / ms_per_step, "workspace_bytes": bws.numel()}
+        del bws, dyb
 
     if not args.no_cpu_baseline:
         import oracle

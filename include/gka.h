@@ -179,6 +179,31 @@ gka_status gka_decode_tokens(const gka_params *p,
                              const float *gate, const float *lambda,
                              void *o, void *hip_stream);
 
+/* Backward pass of the layer by implicit differentiation (Section 4.2.2 "Backward Pass", Appendix B.2): given
+ * dy_t = dL/dy_t, the gradients at q, k, v, the gates and lambda (and at the write gate and the alpha-connection if
+ * they are in use). The forward solve's result is treated as the exact solution of its system and both solves run
+ * r passes of Algorithm 1 (dq_t = CH(H_t + lambda_t I, dxhat_t, r)), as in the paper. Everything runs on the forward
+ * kernels plus a few elementwise ones: two solves and six gated-linear-attention readouts (the reverse recurrences
+ * of Section 4.2.2 are readouts of time-reversed sequences), i.e. about six to seven times the cost of gka_forward;
+ * the paper's chunk-wise backward kernels are not reproduced.
+ *   Supported: explicit lambda (lambda NULL, i.e. the rule lambda_t = a ||H_t||_F with its w_t H_t terms:
+ *   GKA_ERR_UNSUPPORTED), zero initial states, packed tensors (explicit strides: GKA_ERR_UNSUPPORTED), p->beta and
+ *   p->alpha as in gka_forward. Gates must be > 0 (dgate divides by them).
+ *   q, k, v, dy  [B,T,H,d] io_dtype;  gate, lambda [B,T,H] float32
+ *   dq, dk, dv   [B,T,H,d] float32 (written);  dgate [B,T,H] float32 (written)
+ *   dlambda, dbeta, dalpha [B,T,H] float32, each written if not NULL
+ *   workspace: gka_backward_workspace_bytes(p) bytes, 256-byte aligned (about 21 tensors of the size of q in
+ *   io_dtype plus the forward workspace); contents unspecified afterwards. */
+size_t gka_backward_workspace_bytes(const gka_params *p);
+gka_status gka_backward(const gka_params *p,
+                        const void *q, const void *k, const void *v,
+                        const float *gate, const float *lambda,
+                        const void *dy,
+                        float *dq, float *dk, float *dv, float *dgate,
+                        float *dlambda, float *dbeta, float *dalpha,
+                        void *workspace, size_t workspace_bytes,
+                        void *hip_stream);
+
 const char *gka_status_string(gka_status s);
 
 /* Library version: major * 10000 + minor * 100 + patch. */

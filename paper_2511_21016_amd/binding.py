@@ -22,6 +22,8 @@ EXPORTED_SYMBOLS = (
     "gka_forward_profile",
     "gka_decode_step",
     "gka_decode_tokens",
+    "gka_backward_workspace_bytes",
+    "gka_backward",
     "gka_status_string",
     "gka_version",
 )
@@ -74,6 +76,11 @@ def load_library():
         lib.gka_decode_step.restype = ctypes.c_int
         lib.gka_decode_tokens.argtypes = lib.gka_decode_step.argtypes
         lib.gka_decode_tokens.restype = ctypes.c_int
+        lib.gka_backward_workspace_bytes.argtypes = [ctypes.POINTER(GkaParams)]
+        lib.gka_backward_workspace_bytes.restype = ctypes.c_size_t
+        lib.gka_backward.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp, fp, vp,
+                                     ctypes.c_size_t, vp]
+        lib.gka_backward.restype = ctypes.c_int
         lib.gka_status_string.argtypes = [ctypes.c_int]
         lib.gka_status_string.restype = ctypes.c_char_p
         lib.gka_version.argtypes = []
@@ -223,3 +230,44 @@ def gka_decode_tokens(H_state, U_state, q, k, v, gate, lam, n_iter, *, out=None,
     _check(decode_tokens_raw(params, _ptr(H_state), _ptr(U_state), _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam),
                              _ptr(o), stream))
     return o
+
+
+def backward_workspace_bytes(params):
+    return int(load_library().gka_backward_workspace_bytes(ctypes.byref(params)))
+
+
+def backward_raw(params, q, k, v, gate, lam, dy, dq, dk, dv, dgate, dlam=None, dbeta=None, dalpha=None,
+                 workspace=None, workspace_bytes=0, stream=None):
+    pp = None if params is None else ctypes.byref(params)
+    return int(load_library().gka_backward(pp, q, k, v, gate, lam, dy, dq, dk, dv, dgate, dlam, dbeta, dalpha,
+                                           workspace, workspace_bytes, stream))
+
+
+def gka_backward(q, k, v, gate, lam, dy, n_iter, *, compute=None, beta=None, alpha=None, workspace=None):
+    """gka_backward on torch CUDA tensors (packed [B,T,H,d] / [B,T,H]). Returns a dict of float32 gradients:
+    dq, dk, dv, dgate, dlam and, when given, dbeta, dalpha."""
+    import torch
+    B, T, H, d = q.shape
+    for x in (q, k, v, dy):
+        if not x.is_contiguous():
+            raise ValueError("gka_backward takes packed tensors")
+    io = _io_dtype(q)
+    if compute is None:
+        compute = GKA_COMPUTE_BF16 if io == GKA_BF16 else GKA_COMPUTE_F32
+    params = make_params(B, H, T, d, n_iter, io, compute, beta=_ptr(beta), alpha=_ptr(alpha))
+    nbytes = backward_workspace_bytes(params)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=q.device)
+    f32 = dict(dtype=torch.float32, device=q.device)
+    out = {"dq": torch.empty((B, T, H, d), **f32), "dk": torch.empty((B, T, H, d), **f32),
+           "dv": torch.empty((B, T, H, d), **f32), "dgate": torch.empty((B, T, H), **f32),
+           "dlam": torch.empty((B, T, H), **f32)}
+    if beta is not None:
+        out["dbeta"] = torch.empty((B, T, H), **f32)
+    if alpha is not None:
+        out["dalpha"] = torch.empty((B, T, H), **f32)
+    stream = torch.cuda.current_stream(q.device).cuda_stream
+    _check(backward_raw(params, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam), _ptr(dy), _ptr(out["dq"]),
+                        _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dgate"]), _ptr(out["dlam"]),
+                        _ptr(out.get("dbeta")), _ptr(out.get("dalpha")), _ptr(workspace), workspace.numel(), stream))
+    return out

@@ -301,6 +301,119 @@ gka_status gka_decode_tokens(const gka_params *p, float *H_state, float *U_state
     return decode_impl(p, p->T, H_state, U_state, q, k, v, gate, lambda, o, hip_stream);
 }
 
+namespace {
+struct BackwardPlan {
+    size_t n_elems, n_tokens, esz;
+    size_t off_f32[2];        // xhat, p
+    size_t off_io[17];
+    size_t off_m[3];          // gate_rev, zeros, s
+    size_t off_fwd, fwd_bytes, total;
+};
+enum { IO_Y, IO_DXT, IO_RHS, IO_HX, IO_X, IO_XT, IO_KR, IO_VR, IO_DYR, IO_XR, IO_PR, IO_XTR, IO_R1, IO_R2, IO_R3, IO_R4,
+       IO_SCRATCH };
+
+gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
+{
+    gka_status s = check_common(p, false);
+    if (s != GKA_OK) return s;
+    if (p->stride_b != 0 || p->stride_t != 0 || p->stride_h != 0) return GKA_ERR_UNSUPPORTED;
+    if (p->phase != GKA_PHASE_ALL) return GKA_ERR_UNSUPPORTED;
+    bp->n_tokens = (size_t)p->B * p->T * p->H;
+    bp->n_elems = bp->n_tokens * p->d_k;
+    bp->esz = p->io_dtype == GKA_BF16 ? 2 : 4;
+    size_t off = 0;
+    for (int i = 0; i < 2; ++i) { bp->off_f32[i] = off; off = align_up(off + bp->n_elems * 4, 256); }
+    for (int i = 0; i < 17; ++i) { bp->off_io[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
+    for (int i = 0; i < 3; ++i) { bp->off_m[i] = off; off = align_up(off + bp->n_tokens * 4, 256); }
+    bp->off_fwd = off;
+    gka_params pf = *p;
+    pf.xhat_out = nullptr;
+    bp->fwd_bytes = gka_forward_workspace_bytes(&pf);
+    if (bp->fwd_bytes == 0) return GKA_ERR_SHAPE;
+    bp->total = off + bp->fwd_bytes;
+    return GKA_OK;
+}
+}  // namespace
+
+size_t gka_backward_workspace_bytes(const gka_params *p)
+{
+    BackwardPlan bp;
+    if (make_backward_plan(p, &bp) != GKA_OK) return 0;
+    return bp.total;
+}
+
+gka_status gka_backward(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
+                        const float *lambda, const void *dy, float *dq, float *dk, float *dv, float *dgate,
+                        float *dlambda, float *dbeta, float *dalpha, void *workspace, size_t workspace_bytes,
+                        void *hip_stream)
+{
+    BackwardPlan bp;
+    gka_status st = make_backward_plan(p, &bp);
+    if (st != GKA_OK) return st;
+    if (!q || !k || !v || !gate || !dy || !dq || !dk || !dv || !dgate) return GKA_ERR_NULL;
+    if (!lambda) return GKA_ERR_UNSUPPORTED;      // the rule lambda_t = a ||H_t||_F adds the w_t H_t terms: not built
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < bp.total) return GKA_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    unsigned char *ws = (unsigned char *)workspace;
+    auto io = [&](int i) { return (void *)(ws + bp.off_io[i]); };
+    float *xf = (float *)(ws + bp.off_f32[0]), *pf32 = (float *)(ws + bp.off_f32[1]);
+    float *gate_rev = (float *)(ws + bp.off_m[0]), *zeros = (float *)(ws + bp.off_m[1]), *sbuf = (float *)(ws + bp.off_m[2]);
+    void *fws = ws + bp.off_fwd;
+    const bool io_bf16 = p->io_dtype == GKA_BF16;
+
+    gka::BackwardGlueArgs g = {};
+    g.n_elems = (int64_t)bp.n_elems; g.n_tokens = (int64_t)bp.n_tokens;
+    g.T = p->T; g.H = p->H; g.d = p->d_k;
+    g.q = q; g.k = k; g.v = v; g.dy = dy; g.gate = gate; g.alpha = p->alpha; g.beta = p->beta;
+    g.x_f32 = xf; g.p_f32 = pf32;
+    g.x_io = io(IO_X); g.xt_io = io(IO_XT); g.rhs_io = io(IO_RHS);
+    g.dxt_io = io(IO_DXT); g.y_io = io(IO_Y); g.hx_io = io(IO_HX);
+    g.k_rev = io(IO_KR); g.v_rev = io(IO_VR); g.dy_rev = io(IO_DYR); g.x_rev = io(IO_XR); g.p_rev = io(IO_PR);
+    g.xt_rev = io(IO_XTR);
+    g.gate_rev = gate_rev; g.zeros = zeros;
+    g.r1 = io(IO_R1); g.r2 = io(IO_R2); g.r3 = io(IO_R3); g.r4 = io(IO_R4);
+    g.dq = dq; g.dk = dk; g.dv = dv; g.dgate = dgate; g.dlambda = dlambda; g.dbeta = dbeta; g.dalpha = dalpha; g.s = sbuf;
+
+    // a forward pass with the roles given; alpha = zeros makes it the plain readout y_t = U_t q_t of the gated
+    // recurrence U_t = gate_t U_{t-1} + beta_t v_t k_t^T (the solve is reduced to its starting point and discarded)
+    auto fwd = [&](const void *qq, const void *kk, const void *vv, const float *gg, const float *beta,
+                   const float *alpha, int n_iter, void *out, float *xhat) {
+        gka_params pp = *p;
+        pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat; pp.lambda_scale = 0.0f;
+        pp.state_layout = GKA_STATE_FULL;
+        return gka_forward(&pp, qq, kk, vv, gg, lambda, out, nullptr, nullptr, nullptr, nullptr, nullptr, fws,
+                           bp.fwd_bytes, hip_stream);
+    };
+    auto glue = [&](int which) {
+        return gka::launch_backward_glue(g, which, io_bf16, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
+    };
+#define GKA_TRY(expr) do { gka_status e_ = (expr); if (e_ != GKA_OK) return e_; } while (0)
+    // the forward solve and output; xt, x in the tensors' dtype; zeros and the reversed gates are written by the
+    // reversal, which therefore runs before the first plain readout
+    GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf));
+    GKA_TRY(glue(0));
+    // p is not known yet: the reversal of k, v, dy, x, xt and of the gates is repeated below for p_rev; this first
+    // call provides zeros (p_rev of this call is overwritten)
+    GKA_TRY(glue(2));
+    // dxt_t = U_t^T dy_t: the recurrence with the roles of k and v exchanged, read out with dy
+    GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
+    GKA_TRY(glue(1));
+    // p_t = CH(H_t + lambda_t I, alpha_t dxt_t, r)
+    GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32));
+    // H_t x_t
+    GKA_TRY(fwd(io(IO_X), k, k, gate, p->beta, zeros, 0, io(IO_HX), nullptr));
+    // reverse recurrences: A_t k_t, A_t^T k_t, Ubar_t^T v_t, Ubar_t k_t (no write gate inside them)
+    GKA_TRY(glue(2));
+    GKA_TRY(fwd(io(IO_KR), io(IO_XR), io(IO_PR), gate_rev, nullptr, zeros, 0, io(IO_R1), nullptr));
+    GKA_TRY(fwd(io(IO_KR), io(IO_PR), io(IO_XR), gate_rev, nullptr, zeros, 0, io(IO_R2), nullptr));
+    GKA_TRY(fwd(io(IO_VR), io(IO_DYR), io(IO_XTR), gate_rev, nullptr, zeros, 0, io(IO_R3), nullptr));
+    GKA_TRY(fwd(io(IO_KR), io(IO_XTR), io(IO_DYR), gate_rev, nullptr, zeros, 0, io(IO_R4), nullptr));
+    GKA_TRY(glue(3));
+    GKA_TRY(glue(4));
+#undef GKA_TRY
+    return GKA_OK;
+}
+
 const char *gka_status_string(gka_status s)
 {
     switch (s) {
@@ -314,6 +427,6 @@ const char *gka_status_string(gka_status s)
     return "unknown status";
 }
 
-int gka_version(void) { return 400; }
+int gka_version(void) { return 500; }
 
 }  // extern "C"

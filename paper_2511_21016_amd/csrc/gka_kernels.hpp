@@ -61,6 +61,24 @@ struct DecodeArgs {
     bool h_lower_blocks;          // H_state: only the 32 x 32 blocks on and below the block diagonal are read / written
 };
 
+// Elementwise / per-token kernels of the backward pass. Packed tensors: vectors [B,T,H,d] in the tensors' dtype unless
+// named _f32, scalars [B,T,H] float32.
+struct BackwardGlueArgs {
+    int64_t n_elems, n_tokens;    // B*T*H*d, B*T*H
+    int T, H, d;
+    const void *q, *k, *v, *dy;   // inputs
+    const float *gate, *alpha, *beta;                      // alpha, beta may be nullptr (= 1)
+    const float *x_f32, *p_f32;   // results of the two solves
+    void *x_io, *xt_io, *rhs_io;  // x, alpha x + (1 - alpha) q, alpha dxt
+    const void *dxt_io, *y_io, *hx_io;                     // U_t^T dy_t, forward output, H_t x_t
+    void *k_rev, *v_rev, *dy_rev, *x_rev, *p_rev, *xt_rev; // time-reversed copies
+    float *gate_rev, *zeros;      // gates of the reverse recurrences; an all-zero alpha
+    const void *r1, *r2, *r3, *r4;                         // reversed passes: A k, A^T k, Ubar^T v, Ubar k
+    float *dq, *dk, *dv, *dgate, *dlambda, *dbeta, *dalpha, *s;
+};
+// which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan
+hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf16, hipStream_t stream);
+
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
                              hipStream_t stream);
 // Workgroups the state pass launches per segment of the chunk scan (the plan sizes the segments with it).

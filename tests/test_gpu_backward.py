@@ -1,0 +1,48 @@
+"""GPU parity: gka_backward (through the C ABI) against the backward oracle on identical seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import gka_backward_oracle as bwd
+from paper_2511_21016_amd import binding, synth
+from gka_testutil import to_device, to_host, upload_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _rel(got, ref):
+    """Per (batch, head) pair: max |got - ref| over the pair's entries / max |ref| over them; the worst pair."""
+    axes = (1, 3) if got.ndim == 4 else (1,)
+    return float((np.abs(got - ref).max(axis=axes) / np.abs(ref).max(axis=axes)).max())
+
+
+@pytest.mark.parametrize("dtype,compute,d,variants", [("f32", "f32", 64, False), ("f32", "f32", 128, True),
+                                                       ("bf16", "f32", 128, True), ("bf16", "bf16", 128, False),
+                                                       ("bf16", "bf16", 64, True)])
+def test_backward_against_oracle(dtype, compute, d, variants):
+    import torch
+    base = synth.CFG2 if dtype == "bf16" else synth.CFG1
+    w = base.scaled(B=2, H=2, T=150, d=d, n_iter=8, seed=808 + d)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 3)
+    dy = rng.standard_normal(x["v"].shape).astype(np.float32)
+    if dtype == "bf16":
+        dy = synth.round_to_bf16(dy)
+    kw, okw = {}, {}
+    if variants:
+        gates = synth.make_gates(w)
+        kw = dict(beta=to_device(gates["beta"], "f32"), alpha=to_device(gates["alpha"], "f32"))
+        okw = dict(beta=gates["beta"], alpha=gates["alpha"])
+    dev = upload_inputs(x, w.dtype)
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    out = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], to_device(dy, dtype), w.n_iter,
+                               compute=cm, **kw)
+    torch.cuda.synchronize()
+    ref = bwd.backward(x["q"], x["k"], x["v"], x["gate"], x["lam"], dy, w.n_iter, **okw)
+    # float32 tensors and operands: rounding only. bf16 tensors: the intermediate tensors of the composition (the
+    # right-hand side of the second solve among them, whose error the solve amplifies) are rounded to bf16 as well
+    tol = 2e-4 if dtype == "f32" else 6e-2
+    names = ["dq", "dk", "dv", "dgate", "dlam"] + (["dbeta", "dalpha"] if variants else [])
+    errs = {n: _rel(to_host(out[n]), ref[n]) for n in names}
+    print(dtype, compute, d, variants, errs)
+    assert max(errs.values()) <= tol, errs

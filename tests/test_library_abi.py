@@ -92,4 +92,16 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert binding.decode_tokens_raw(_p(strides=(1 << 20, 2048, 128)), fake, fake, fake, fake, fake, fake, fake,
                                      fake) == binding.GKA_ERR_UNSUPPORTED
     assert binding.decode_tokens_raw(None, fake, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
+    # backward: workspace query and argument checks
+    bws = binding.backward_workspace_bytes(_p())
+    assert bws > ok_ws and bws % 256 == 0
+    assert binding.backward_workspace_bytes(_p(strides=(1 << 20, 2048, 128))) == 0
+    bw = lambda p, **kw: binding.backward_raw(p, *[kw.get(n, fake) for n in ("q", "k", "v", "gate", "lam", "dy", "dq",
+                                                                            "dk", "dv", "dgate")],
+                                              workspace=kw.get("ws", 0x100000), workspace_bytes=kw.get("ws_bytes", bws))
+    assert bw(_p(), dy=None) == binding.GKA_ERR_NULL
+    assert bw(_p(), lam=None) == binding.GKA_ERR_UNSUPPORTED          # the rule lambda = a ||H||_F is not differentiated
+    assert bw(_p(strides=(1 << 20, 2048, 128))) == binding.GKA_ERR_UNSUPPORTED
+    assert bw(_p(), ws_bytes=bws - 1) == binding.GKA_ERR_WORKSPACE
+    assert bw(_p(d=96)) == binding.GKA_ERR_UNSUPPORTED
     assert binding.forward_raw(None, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
