@@ -388,13 +388,9 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
         return gka::launch_backward_glue(g, which, io_bf16, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
     };
 #define GKA_TRY(expr) do { gka_status e_ = (expr); if (e_ != GKA_OK) return e_; } while (0)
-    // the forward solve and output; xt, x in the tensors' dtype; zeros and the reversed gates are written by the
-    // reversal, which therefore runs before the first plain readout
+    // the forward solve and output; then x, xt in the tensors' dtype, the all-zero alpha and the reversed gates
     GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf));
     GKA_TRY(glue(0));
-    // p is not known yet: the reversal of k, v, dy, x, xt and of the gates is repeated below for p_rev; this first
-    // call provides zeros (p_rev of this call is overwritten)
-    GKA_TRY(glue(2));
     // dxt_t = U_t^T dy_t: the recurrence with the roles of k and v exchanged, read out with dy
     GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
     GKA_TRY(glue(1));

@@ -11,7 +11,8 @@
 
 namespace gka {
 
-// After the forward solve: x in the tensors' dtype and the readout operand xt = alpha x + (1 - alpha) q.
+// After the forward solve: x in the tensors' dtype, the readout operand xt = alpha x + (1 - alpha) q, and the
+// per-token constants of the later passes.
 template <class IO>
 __global__ __launch_bounds__(256) void bwd_mix_kernel(BackwardGlueArgs a)
 {
@@ -22,6 +23,14 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BackwardGlueArgs a)
     const float x = a.x_f32[i];
     IO::store1(a.x_io, i, x);
     IO::store1(a.xt_io, i, al * x + (1.0f - al) * IO::load(a.q, i));
+    // once per token: the all-zero alpha of the plain readouts and the gates of the reverse recurrences,
+    // gate'_tau = gate_{T - tau} for tau >= 1 (gate'_0 multiplies a zero state: 1)
+    if (i - tok * a.d == 0) {
+        const int64_t bt = tok / a.H, h = tok - bt * a.H;
+        const int64_t b = bt / a.T, tau = bt - b * a.T;
+        a.zeros[tok] = 0.0f;
+        a.gate_rev[tok] = tau == 0 ? 1.0f : a.gate[(b * a.T + (a.T - tau)) * a.H + h];
+    }
 }
 
 // Right-hand side of the backward solve: alpha_t dxt_t.
@@ -34,8 +43,7 @@ __global__ __launch_bounds__(256) void bwd_rhs_kernel(BackwardGlueArgs a)
     IO::store1(a.rhs_io, i, al * IO::load(a.dxt_io, i));
 }
 
-// Time reversal tau = T - 1 - t of k, v, dy, x, p, xt (p converted from float32 on the way) and the gates of the
-// reverse recurrences, gate'_tau = gate_{T - tau} for tau >= 1 (gate'_0 multiplies a zero state: 1).
+// Time reversal tau = T - 1 - t of k, v, dy, x, p, xt (p converted from float32 on the way).
 template <class IO>
 __global__ __launch_bounds__(256) void bwd_reverse_kernel(BackwardGlueArgs a)
 {
@@ -51,12 +59,6 @@ __global__ __launch_bounds__(256) void bwd_reverse_kernel(BackwardGlueArgs a)
     IO::store1(a.x_rev, i, IO::load(a.x_io, src));
     IO::store1(a.xt_rev, i, IO::load(a.xt_io, src));
     IO::store1(a.p_rev, i, a.p_f32[src]);
-    if (within % a.d == 0) {
-        const int64_t h = within / a.d;
-        const int64_t m = (b * a.T + tau) * a.H + h;
-        a.gate_rev[m] = tau == 0 ? 1.0f : a.gate[(b * a.T + (a.T - tau)) * a.H + h];
-        a.zeros[m] = 0.0f;
-    }
 }
 
 // One wave per token: the pieces are combined into the gradients (Section 4.2.2, Appendix B.2):
