@@ -155,7 +155,7 @@ struct PhaseEvents {
 gka_status forward_impl(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
                         const float *lambda, void *o, const float *H_init, const float *U_init, float *H_final,
                         float *U_final, float *fro_out, void *workspace, size_t workspace_bytes,
-                        void *hip_stream, PhaseEvents *prof)
+                        void *hip_stream, PhaseEvents *prof, bool readout_only = false)
 {
     Plan pl;
     gka_status s = make_plan(p, &pl);
@@ -182,6 +182,8 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     so.q = q; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
     so.beta = p->beta; so.alpha = p->alpha; so.lambda_scale = p->lambda_scale;
     so.xhat_out = p->xhat_out;
+    // plain readout y_t = U_t q_t (used by the backward pass): needs alpha = 0 from the caller; no H states, no solve
+    sa.only_u = readout_only; so.readout_only = readout_only;
     so.ws_H = sa.ws_H; so.ws_U = sa.ws_U; so.ws_hn = sa.ws_hn;
     so.stride_b = pl.stride_b; so.stride_t = pl.stride_t; so.stride_h = pl.stride_h;
     so.H = p->H; so.T = p->T; so.n_iter = p->n_iter;
@@ -381,8 +383,9 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
         gka_params pp = *p;
         pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat; pp.lambda_scale = 0.0f;
         pp.state_layout = GKA_STATE_FULL;
-        return gka_forward(&pp, qq, kk, vv, gg, lambda, out, nullptr, nullptr, nullptr, nullptr, nullptr, fws,
-                           bp.fwd_bytes, hip_stream);
+        const bool plain_readout = alpha == zeros;
+        return forward_impl(&pp, qq, kk, vv, gg, lambda, out, nullptr, nullptr, nullptr, nullptr, nullptr, fws,
+                            bp.fwd_bytes, hip_stream, nullptr, plain_readout);
     };
     auto glue = [&](int which) {
         return gka::launch_backward_glue(g, which, io_bf16, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;

@@ -372,7 +372,9 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         const float bm_raw = (a.beta ? a.beta : a.gate)[gate_base + (int64_t)min(tok0 + lane, a.T - 1) * a.H];
         ball = a.beta ? bm_raw : 1.0f;
     }
-    async_block_copy<H16>(sH, (const frag *)a.ws_H + chunk_id * (SH::H_FRAGS * 64), w, lane);   // H_[n] -> LDS
+    // plain readout (variants' kernel only): no solve, so neither H_[n] nor its norm is read
+    const bool solve = !(GATED && a.readout_only);
+    if (solve) async_block_copy<H16>(sH, (const frag *)a.ws_H + chunk_id * (SH::H_FRAGS * 64), w, lane);   // H_[n] -> LDS
     RowStage<MMA, IO, D> krows;
     krows.load(a.k, base_bh, a.stride_t, tok0, a.T, tid);
 #pragma unroll
@@ -383,7 +385,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     lam = ((!GATED || a.lambda) ? a.lambda : a.gate)[gate_base + (int64_t)min(tok, a.T - 1) * a.H];
     float hn[NB * NB];
 #pragma unroll
-    for (int i = 0; i < NB * NB; ++i) hn[i] = a.ws_hn[chunk_id * (NB * NB) + i];
+    for (int i = 0; i < NB * NB; ++i) hn[i] = solve ? a.ws_hn[chunk_id * (NB * NB) + i] : 0.0f;
 
     // ---------------- decay mask (Section 4.2.1; log-space form of Appendix B.2, base 2) ----------------
     // With the write gate, H_c = zeta_c H_[n] + sum_{j<=c} M[j,c] beta_j k_j k_j^T (the same for U): beta_j is folded
@@ -441,7 +443,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
     for (int i = 0; i < NBH; ++i) Hset[i] = Aset[NJ + i];
     const frag *myK = sK + (TW * NSTEPS) * 64;         // this token block's keys as a B operand
-    {
+    if (solve) {
         f32x16 acc[NJ + NBH];
         fused_gemm<MMA, NSTEPS, NJ + NBH, NoFill, NJ + NBH>(Aset, myK, acc, lane);
         GKA_TSTAMP(12);
@@ -488,7 +490,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
             for (int r = 0; r < 16; ++r) f_part += mreg[jt][r] * mreg[jt][r] * sW[32 * jt + kidx(r, g)];
         f_part += __shfl_xor(f_part, 32, 64);
-        fro = sqrtf(fmaxf(zeta * zeta * hn2 + f_part, 0.0f));
+        fro = solve ? sqrtf(fmaxf(zeta * zeta * hn2 + f_part, 0.0f)) : 0.0f;   // (no solve: sW was not written)
     }
     if (a.fro_out && valid && fh == 0 && g == 0) a.fro_out[gate_base + (int64_t)tok * a.H] = fro;
     if (GATED && !a.lambda) lam = valid ? a.lambda_scale * fro : 1.0f;      // Section 4.1: lambda_t = a ||H_t||_F

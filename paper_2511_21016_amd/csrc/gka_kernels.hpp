@@ -30,6 +30,7 @@ struct StatePassArgs {
     int init_mode;                // 0 zero state, 1 H_init/U_init (or zero) advanced over the earlier segments
     int final_mode;               // 1 last segment writes H_final/U_final, 2 segment summary to seg_buf
     int write_frags;              // store chunk states to ws_H / ws_U / ws_hn
+    bool only_u;                  // the H states are not needed (plain readout y_t = U_t q_t): their workgroups exit
 };
 
 struct SolveArgs {
@@ -47,6 +48,7 @@ struct SolveArgs {
     int chunk0, n_chunks;         // chunks of every pair covered by this launch (workspace indexed from 0)
     int n_pairs;                  // pairs of this launch (set by the launcher)
     int pair0;                    // first (batch, head) pair of this launch; workspace is indexed from 0
+    bool readout_only;            // variants' kernel: no solve (its result is discarded by alpha = 0): H_[n] is not read
 };
 
 struct DecodeArgs {
