@@ -232,18 +232,26 @@ def main():
         dyb = torch.randn_like(xs["v"])
         bparams = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16)
         bws = torch.empty(binding.backward_workspace_bytes(bparams), dtype=torch.uint8, device="cuda")
-        for _ in range(3):
-            binding.gka_backward(xs["q"], xs["k"], xs["v"], xs["gate"], xs["lam"], dyb, w.n_iter, workspace=bws)
-        torch.cuda.synchronize()
-        b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        b0.record()
-        for _ in range(10):
-            binding.gka_backward(xs["q"], xs["k"], xs["v"], xs["gate"], xs["lam"], dyb, w.n_iter, workspace=bws)
-        b1.record()
-        torch.cuda.synchronize()
-        ms_bwd = b0.elapsed_time(b1) / 10
+
+        def time_backward(lam, lambda_scale):
+            call = lambda: binding.gka_backward(xs["q"], xs["k"], xs["v"], xs["gate"], lam, dyb, w.n_iter,
+                                                lambda_scale=lambda_scale, workspace=bws)
+            for _ in range(3):
+                call()
+            torch.cuda.synchronize()
+            b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            b0.record()
+            for _ in range(10):
+                call()
+            b1.record()
+            torch.cuda.synchronize()
+            return b0.elapsed_time(b1) / 10
+
+        ms_bwd = time_backward(xs["lam"], 0.0)
+        ms_rule = time_backward(None, 0.02)                 # lambda_t = 0.02 ||H_t||_F (Section 4.1)
         result["backward"] = {"ms_per_call": ms_bwd, "tokens_per_s": tokens / (ms_bwd * 1e-3),
-                              "times_forward": ms_bwd / ms_per_step, "workspace_bytes": bws.numel()}
+                              "times_forward": ms_bwd / ms_per_step, "workspace_bytes": bws.numel(),
+                              "frobenius_rule_ms_per_call": ms_rule}
         del bws, dyb
 
     if not args.no_cpu_baseline:

@@ -186,13 +186,13 @@ gka_status gka_decode_tokens(const gka_params *p,
  * kernels plus a few elementwise ones: two solves and six gated-linear-attention readouts (the reverse recurrences
  * of Section 4.2.2 are readouts of time-reversed sequences), i.e. about six to seven times the cost of gka_forward;
  * the paper's chunk-wise backward kernels are not reproduced.
- *   Supported: explicit lambda (lambda NULL, i.e. the rule lambda_t = a ||H_t||_F with its w_t H_t terms:
- *   GKA_ERR_UNSUPPORTED), zero initial states, packed tensors (explicit strides: GKA_ERR_UNSUPPORTED), p->beta and
- *   p->alpha as in gka_forward. Gates must be > 0 (dgate divides by them).
+ *   Supported: lambda given or NULL with p->lambda_scale > 0 (the rule lambda_t = a ||H_t||_F, whose w_t H_t terms
+ *   of the Lemma in Section 4.2.2 cost two more readouts), zero initial states, packed tensors (explicit strides:
+ *   GKA_ERR_UNSUPPORTED), p->beta and p->alpha as in gka_forward. Gates must be > 0 (dgate divides by them).
  *   q, k, v, dy  [B,T,H,d] io_dtype;  gate, lambda [B,T,H] float32
  *   dq, dk, dv   [B,T,H,d] float32 (written);  dgate [B,T,H] float32 (written)
- *   dlambda, dbeta, dalpha [B,T,H] float32, each written if not NULL
- *   workspace: gka_backward_workspace_bytes(p) bytes, 256-byte aligned (about 21 tensors of the size of q in
+ *   dlambda, dbeta, dalpha [B,T,H] float32, each written if not NULL (dlambda only when lambda is given)
+ *   workspace: gka_backward_workspace_bytes(p) bytes, 256-byte aligned (about 24 tensors of the size of q in
  *   io_dtype plus the forward workspace); contents unspecified afterwards. */
 size_t gka_backward_workspace_bytes(const gka_params *p);
 gka_status gka_backward(const gka_params *p,

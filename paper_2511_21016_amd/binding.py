@@ -243,9 +243,11 @@ def backward_raw(params, q, k, v, gate, lam, dy, dq, dk, dv, dgate, dlam=None, d
                                            workspace, workspace_bytes, stream))
 
 
-def gka_backward(q, k, v, gate, lam, dy, n_iter, *, compute=None, beta=None, alpha=None, workspace=None):
-    """gka_backward on torch CUDA tensors (packed [B,T,H,d] / [B,T,H]). Returns a dict of float32 gradients:
-    dq, dk, dv, dgate, dlam and, when given, dbeta, dalpha."""
+def gka_backward(q, k, v, gate, lam, dy, n_iter, *, compute=None, beta=None, alpha=None, lambda_scale=0.0,
+                 workspace=None):
+    """gka_backward on torch CUDA tensors (packed [B,T,H,d] / [B,T,H]). lam None: the rule
+    lambda_t = lambda_scale ||H_t||_F. Returns a dict of float32 gradients: dq, dk, dv, dgate, dlam (when lam is
+    given) and, when given, dbeta, dalpha."""
     import torch
     B, T, H, d = q.shape
     for x in (q, k, v, dy):
@@ -254,20 +256,22 @@ def gka_backward(q, k, v, gate, lam, dy, n_iter, *, compute=None, beta=None, alp
     io = _io_dtype(q)
     if compute is None:
         compute = GKA_COMPUTE_BF16 if io == GKA_BF16 else GKA_COMPUTE_F32
-    params = make_params(B, H, T, d, n_iter, io, compute, beta=_ptr(beta), alpha=_ptr(alpha))
+    params = make_params(B, H, T, d, n_iter, io, compute, lambda_scale=lambda_scale, beta=_ptr(beta),
+                         alpha=_ptr(alpha))
     nbytes = backward_workspace_bytes(params)
     if workspace is None:
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=q.device)
     f32 = dict(dtype=torch.float32, device=q.device)
     out = {"dq": torch.empty((B, T, H, d), **f32), "dk": torch.empty((B, T, H, d), **f32),
-           "dv": torch.empty((B, T, H, d), **f32), "dgate": torch.empty((B, T, H), **f32),
-           "dlam": torch.empty((B, T, H), **f32)}
+           "dv": torch.empty((B, T, H, d), **f32), "dgate": torch.empty((B, T, H), **f32)}
+    if lam is not None:
+        out["dlam"] = torch.empty((B, T, H), **f32)
     if beta is not None:
         out["dbeta"] = torch.empty((B, T, H), **f32)
     if alpha is not None:
         out["dalpha"] = torch.empty((B, T, H), **f32)
     stream = torch.cuda.current_stream(q.device).cuda_stream
     _check(backward_raw(params, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam), _ptr(dy), _ptr(out["dq"]),
-                        _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dgate"]), _ptr(out["dlam"]),
+                        _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dgate"]), _ptr(out.get("dlam")),
                         _ptr(out.get("dbeta")), _ptr(out.get("dalpha")), _ptr(workspace), workspace.numel(), stream))
     return out

@@ -307,12 +307,12 @@ namespace {
 struct BackwardPlan {
     size_t n_elems, n_tokens, esz;
     size_t off_f32[2];        // xhat, p
-    size_t off_io[17];
-    size_t off_m[3];          // gate_rev, zeros, s
+    size_t off_io[20];
+    size_t off_m[6];          // gate_rev, zeros, s, fro, c, C
     size_t off_fwd, fwd_bytes, total;
 };
 enum { IO_Y, IO_DXT, IO_RHS, IO_HX, IO_X, IO_XT, IO_KR, IO_VR, IO_DYR, IO_XR, IO_PR, IO_XTR, IO_R1, IO_R2, IO_R3, IO_R4,
-       IO_SCRATCH };
+       IO_SCRATCH, IO_HK, IO_VPR, IO_R5 };
 
 gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
 {
@@ -325,8 +325,8 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     bp->esz = p->io_dtype == GKA_BF16 ? 2 : 4;
     size_t off = 0;
     for (int i = 0; i < 2; ++i) { bp->off_f32[i] = off; off = align_up(off + bp->n_elems * 4, 256); }
-    for (int i = 0; i < 17; ++i) { bp->off_io[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
-    for (int i = 0; i < 3; ++i) { bp->off_m[i] = off; off = align_up(off + bp->n_tokens * 4, 256); }
+    for (int i = 0; i < 20; ++i) { bp->off_io[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
+    for (int i = 0; i < 6; ++i) { bp->off_m[i] = off; off = align_up(off + bp->n_tokens * 4, 256); }
     bp->off_fwd = off;
     gka_params pf = *p;
     pf.xhat_out = nullptr;
@@ -353,13 +353,15 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     gka_status st = make_backward_plan(p, &bp);
     if (st != GKA_OK) return st;
     if (!q || !k || !v || !gate || !dy || !dq || !dk || !dv || !dgate) return GKA_ERR_NULL;
-    if (!lambda) return GKA_ERR_UNSUPPORTED;      // the rule lambda_t = a ||H_t||_F adds the w_t H_t terms: not built
+    const bool rule = lambda == nullptr;          // lambda_t = lambda_scale ||H_t||_F
+    if (rule && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < bp.total) return GKA_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
     unsigned char *ws = (unsigned char *)workspace;
     auto io = [&](int i) { return (void *)(ws + bp.off_io[i]); };
     float *xf = (float *)(ws + bp.off_f32[0]), *pf32 = (float *)(ws + bp.off_f32[1]);
     float *gate_rev = (float *)(ws + bp.off_m[0]), *zeros = (float *)(ws + bp.off_m[1]), *sbuf = (float *)(ws + bp.off_m[2]);
+    float *fro = (float *)(ws + bp.off_m[3]), *cbuf = (float *)(ws + bp.off_m[4]), *Cbuf = (float *)(ws + bp.off_m[5]);
     void *fws = ws + bp.off_fwd;
     const bool io_bf16 = p->io_dtype == GKA_BF16;
 
@@ -375,16 +377,18 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     g.gate_rev = gate_rev; g.zeros = zeros;
     g.r1 = io(IO_R1); g.r2 = io(IO_R2); g.r3 = io(IO_R3); g.r4 = io(IO_R4);
     g.dq = dq; g.dk = dk; g.dv = dv; g.dgate = dgate; g.dlambda = dlambda; g.dbeta = dbeta; g.dalpha = dalpha; g.s = sbuf;
+    g.rule_a = rule ? p->lambda_scale : 0.0f; g.fro = fro; g.c = cbuf; g.C = Cbuf;
+    g.vp_rev = io(IO_VPR); g.hk_io = io(IO_HK); g.r5 = io(IO_R5);
 
     // a forward pass with the roles given; alpha = zeros makes it the plain readout y_t = U_t q_t of the gated
     // recurrence U_t = gate_t U_{t-1} + beta_t v_t k_t^T (the solve is reduced to its starting point and discarded)
     auto fwd = [&](const void *qq, const void *kk, const void *vv, const float *gg, const float *beta,
-                   const float *alpha, int n_iter, void *out, float *xhat) {
-        gka_params pp = *p;
-        pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat; pp.lambda_scale = 0.0f;
+                   const float *alpha, int n_iter, void *out, float *xhat, float *fro_out = nullptr) {
+        gka_params pp = *p;                      // lambda (or its rule) as given: only the two solves use it
+        pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat;
         pp.state_layout = GKA_STATE_FULL;
         const bool plain_readout = alpha == zeros;
-        return forward_impl(&pp, qq, kk, vv, gg, lambda, out, nullptr, nullptr, nullptr, nullptr, nullptr, fws,
+        return forward_impl(&pp, qq, kk, vv, gg, lambda, out, nullptr, nullptr, nullptr, nullptr, fro_out, fws,
                             bp.fwd_bytes, hip_stream, nullptr, plain_readout);
     };
     auto glue = [&](int which) {
@@ -392,7 +396,7 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     };
 #define GKA_TRY(expr) do { gka_status e_ = (expr); if (e_ != GKA_OK) return e_; } while (0)
     // the forward solve and output; then x, xt in the tensors' dtype, the all-zero alpha and the reversed gates
-    GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf));
+    GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf, rule ? fro : nullptr));
     GKA_TRY(glue(0));
     // dxt_t = U_t^T dy_t: the recurrence with the roles of k and v exchanged, read out with dy
     GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
@@ -401,8 +405,15 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32));
     // H_t x_t
     GKA_TRY(fwd(io(IO_X), k, k, gate, p->beta, zeros, 0, io(IO_HX), nullptr));
+    // the rule's extra gradient -c_t H_t at every state: c_t, C_t = sum_{s>=t} M[t,s]^2 c_s, and H_t k_t
+    if (rule) {
+        GKA_TRY(glue(5));
+        GKA_TRY(glue(6));
+        GKA_TRY(fwd(k, k, k, gate, p->beta, zeros, 0, io(IO_HK), nullptr));
+    }
     // reverse recurrences: A_t k_t, A_t^T k_t, Ubar_t^T v_t, Ubar_t k_t (no write gate inside them)
     GKA_TRY(glue(2));
+    if (rule) GKA_TRY(fwd(io(IO_KR), io(IO_KR), io(IO_VPR), gate_rev, nullptr, zeros, 0, io(IO_R5), nullptr));
     GKA_TRY(fwd(io(IO_KR), io(IO_XR), io(IO_PR), gate_rev, nullptr, zeros, 0, io(IO_R1), nullptr));
     GKA_TRY(fwd(io(IO_KR), io(IO_PR), io(IO_XR), gate_rev, nullptr, zeros, 0, io(IO_R2), nullptr));
     GKA_TRY(fwd(io(IO_VR), io(IO_DYR), io(IO_XTR), gate_rev, nullptr, zeros, 0, io(IO_R3), nullptr));

@@ -494,6 +494,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     }
     if (a.fro_out && valid && fh == 0 && g == 0) a.fro_out[gate_base + (int64_t)tok * a.H] = fro;
     if (GATED && !a.lambda) lam = valid ? a.lambda_scale * fro : 1.0f;      // Section 4.1: lambda_t = a ||H_t||_F
+    if (!solve) lam = 1.0f;                    // plain readout: the discarded starting point stays finite
 
     GKA_TSTAMP(6);
     // ---------------- Chebyshev iteration (Algorithm 1), residual form ----------------

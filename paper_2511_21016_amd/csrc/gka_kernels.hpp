@@ -77,8 +77,14 @@ struct BackwardGlueArgs {
     float *gate_rev, *zeros;      // gates of the reverse recurrences; an all-zero alpha
     const void *r1, *r2, *r3, *r4;                         // reversed passes: A k, A^T k, Ubar^T v, Ubar k
     float *dq, *dk, *dv, *dgate, *dlambda, *dbeta, *dalpha, *s;
+    // the rule lambda_t = a ||H_t||_F (rule_a > 0): its extra gradient -c_t H_t at every state, c_t = a x_t.p_t / ||H_t||_F
+    float rule_a;
+    const float *fro;             // ||H_t||_F of the forward pass
+    float *c, *C;                 // c_t and C_t = sum_{s>=t} M[t,s]^2 c_s
+    void *vp_rev;                 // time-reversed beta_t C_t k_t
+    const void *hk_io, *r5;       // H_t k_t; reversed pass sum_{j>=t} M[t,j] beta_j C_j k_j (k_j . k_t)
 };
-// which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan
+// which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan, 5 rule scalars (c_t), 6 rule scan (C_t)
 hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf16, hipStream_t stream);
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,

@@ -46,3 +46,36 @@ def test_backward_against_oracle(dtype, compute, d, variants):
     errs = {n: _rel(to_host(out[n]), ref[n]) for n in names}
     print(dtype, compute, d, variants, errs)
     assert max(errs.values()) <= tol, errs
+
+
+@pytest.mark.parametrize("dtype,compute,d,variants", [("f32", "f32", 64, True), ("f32", "f32", 128, False),
+                                                       ("bf16", "bf16", 128, True), ("bf16", "f32", 64, False)])
+def test_backward_with_the_frobenius_rule(dtype, compute, d, variants):
+    """lambda_t = a ||H_t||_F (Section 4.1): the gradient at every H_t gains the -c_t H_t term of the Lemma of
+    Section 4.2.2; no dlam is returned."""
+    import torch
+    base = synth.CFG2 if dtype == "bf16" else synth.CFG1
+    w = base.scaled(B=2, H=2, T=150, d=d, n_iter=8, seed=919 + d)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 3)
+    dy = rng.standard_normal(x["v"].shape).astype(np.float32)
+    if dtype == "bf16":
+        dy = synth.round_to_bf16(dy)
+    a = 0.05
+    kw, okw = {}, {}
+    if variants:
+        gates = synth.make_gates(w)
+        kw = dict(beta=to_device(gates["beta"], "f32"), alpha=to_device(gates["alpha"], "f32"))
+        okw = dict(beta=gates["beta"], alpha=gates["alpha"])
+    dev = upload_inputs(x, w.dtype)
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    out = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], None, to_device(dy, dtype), w.n_iter,
+                               compute=cm, lambda_scale=a, **kw)
+    torch.cuda.synchronize()
+    assert "dlam" not in out
+    ref = bwd.backward(x["q"], x["k"], x["v"], x["gate"], None, dy, w.n_iter, lambda_scale=a, **okw)
+    tol = 2e-4 if dtype == "f32" else 6e-2
+    names = ["dq", "dk", "dv", "dgate"] + (["dbeta", "dalpha"] if variants else [])
+    errs = {n: _rel(to_host(out[n]), ref[n]) for n in names}
+    print("rule", dtype, compute, d, variants, errs)
+    assert max(errs.values()) <= tol, errs

@@ -100,7 +100,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
                                                                             "dk", "dv", "dgate")],
                                               workspace=kw.get("ws", 0x100000), workspace_bytes=kw.get("ws_bytes", bws))
     assert bw(_p(), dy=None) == binding.GKA_ERR_NULL
-    assert bw(_p(), lam=None) == binding.GKA_ERR_UNSUPPORTED          # the rule lambda = a ||H||_F is not differentiated
+    assert bw(_p(), lam=None) == binding.GKA_ERR_NULL                 # no lambda and no rule (lambda_scale = 0)
     assert bw(_p(strides=(1 << 20, 2048, 128))) == binding.GKA_ERR_UNSUPPORTED
     assert bw(_p(), ws_bytes=bws - 1) == binding.GKA_ERR_WORKSPACE
     assert bw(_p(d=96)) == binding.GKA_ERR_UNSUPPORTED
