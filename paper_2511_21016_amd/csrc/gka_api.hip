@@ -61,7 +61,7 @@ gka_status check_common(const gka_params *p, bool decode)
     return GKA_OK;
 }
 
-gka_status make_plan(const gka_params *p, Plan *pl)
+gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
 {
     gka_status s = check_common(p, false);
     if (s != GKA_OK) return s;
@@ -106,7 +106,9 @@ gka_status make_plan(const gka_params *p, Plan *pl)
     // Segments of the chunk scan. A workgroup walks its chunks one after the other (a few microseconds each), and a
     // segmented pass reads k and v twice, so: one segment unless that leaves CUs idle or makes the walk longer than
     // about 64 chunks; never fewer than two chunks per segment.
-    const int wg_per_seg = gka::state_pass_workgroups_per_segment(pl->pairs_per_batch, pl->d, pl->compute_bf16);
+    // (a plain readout walks U only: half the workgroups of a segment have nothing to do)
+    int wg_per_seg = gka::state_pass_workgroups_per_segment(pl->pairs_per_batch, pl->d, pl->compute_bf16);
+    if (readout_only && wg_per_seg > 1) wg_per_seg /= 2;
     int n_segs = (kStateMinWorkgroups + wg_per_seg - 1) / wg_per_seg;
     if (n_segs < pl->slab_chunks / kStateMaxWalk) n_segs = pl->slab_chunks / kStateMaxWalk;
     if (n_segs > pl->slab_chunks / 2) n_segs = pl->slab_chunks / 2;
@@ -158,7 +160,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
                         void *hip_stream, PhaseEvents *prof, bool readout_only = false)
 {
     Plan pl;
-    gka_status s = make_plan(p, &pl);
+    gka_status s = make_plan(p, &pl, readout_only);
     if (s != GKA_OK) return s;
     if (!q || !k || !v || !gate || !o) return GKA_ERR_NULL;
     if (!lambda && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;      // neither lambda_t nor the rule for it
@@ -330,8 +332,9 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     bp->off_fwd = off;
     gka_params pf = *p;
     pf.xhat_out = nullptr;
-    bp->fwd_bytes = gka_forward_workspace_bytes(&pf);
-    if (bp->fwd_bytes == 0) return GKA_ERR_SHAPE;
+    Plan full, plain;                              // the plain readouts cut the scan into more segments
+    if (make_plan(&pf, &full) != GKA_OK || make_plan(&pf, &plain, true) != GKA_OK) return GKA_ERR_SHAPE;
+    bp->fwd_bytes = full.total > plain.total ? full.total : plain.total;
     bp->total = off + bp->fwd_bytes;
     return GKA_OK;
 }

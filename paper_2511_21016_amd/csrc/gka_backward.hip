@@ -11,18 +11,24 @@
 
 namespace gka {
 
+// The elementwise kernels take four consecutive features per thread (16-byte accesses to float32 tensors, 8-byte ones
+// to bf16 tensors); d is a multiple of 4, so the four belong to one token.
+__device__ __forceinline__ f32x4 load_f32x4(const float *p, int64_t i) { return *(const f32x4 *)(p + i); }
+
 // After the forward solve: x in the tensors' dtype, the readout operand xt = alpha x + (1 - alpha) q, and the
 // per-token constants of the later passes.
 template <class IO>
 __global__ __launch_bounds__(256) void bwd_mix_kernel(BackwardGlueArgs a)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= a.n_elems) return;
     const int64_t tok = i / a.d;
     const float al = a.alpha ? a.alpha[tok] : 1.0f;
-    const float x = a.x_f32[i];
-    IO::store1(a.x_io, i, x);
-    IO::store1(a.xt_io, i, al * x + (1.0f - al) * IO::load(a.q, i));
+    const f32x4 x = load_f32x4(a.x_f32, i);
+    const f32x4 q = IO::load4(a.q, i);
+    IO::store4(a.x_io, i, x[0], x[1], x[2], x[3]);
+    IO::store4(a.xt_io, i, al * x[0] + (1.0f - al) * q[0], al * x[1] + (1.0f - al) * q[1],
+               al * x[2] + (1.0f - al) * q[2], al * x[3] + (1.0f - al) * q[3]);
     // once per token: the all-zero alpha of the plain readouts and the gates of the reverse recurrences,
     // gate'_tau = gate_{T - tau} for tau >= 1 (gate'_0 multiplies a zero state: 1)
     if (i - tok * a.d == 0) {
@@ -37,31 +43,39 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BackwardGlueArgs a)
 template <class IO>
 __global__ __launch_bounds__(256) void bwd_rhs_kernel(BackwardGlueArgs a)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= a.n_elems) return;
     const float al = a.alpha ? a.alpha[i / a.d] : 1.0f;
-    IO::store1(a.rhs_io, i, al * IO::load(a.dxt_io, i));
+    const f32x4 g = IO::load4(a.dxt_io, i);
+    IO::store4(a.rhs_io, i, al * g[0], al * g[1], al * g[2], al * g[3]);
 }
 
 // Time reversal tau = T - 1 - t of k, v, dy, x, p, xt (p converted from float32 on the way).
 template <class IO>
 __global__ __launch_bounds__(256) void bwd_reverse_kernel(BackwardGlueArgs a)
 {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= a.n_elems) return;
     const int64_t hd = (int64_t)a.H * a.d;
     const int64_t b = i / (hd * a.T), rem = i - b * hd * a.T;
     const int64_t tau = rem / hd, within = rem - tau * hd;
     const int64_t src = (b * a.T + (a.T - 1 - tau)) * hd + within;
-    IO::store1(a.k_rev, i, IO::load(a.k, src));
-    IO::store1(a.v_rev, i, IO::load(a.v, src));
-    IO::store1(a.dy_rev, i, IO::load(a.dy, src));
-    IO::store1(a.x_rev, i, IO::load(a.x_io, src));
-    IO::store1(a.xt_rev, i, IO::load(a.xt_io, src));
-    IO::store1(a.p_rev, i, a.p_f32[src]);
+    auto copy4 = [&](void *dst, const void *from) {
+        const f32x4 v = IO::load4(from, src);
+        IO::store4(dst, i, v[0], v[1], v[2], v[3]);
+    };
+    const f32x4 kv = IO::load4(a.k, src);
+    IO::store4(a.k_rev, i, kv[0], kv[1], kv[2], kv[3]);
+    copy4(a.v_rev, a.v);
+    copy4(a.dy_rev, a.dy);
+    copy4(a.x_rev, a.x_io);
+    copy4(a.xt_rev, a.xt_io);
+    const f32x4 pv = load_f32x4(a.p_f32, src);
+    IO::store4(a.p_rev, i, pv[0], pv[1], pv[2], pv[3]);
     if (a.rule_a > 0.0f) {
         const int64_t stok = src / a.d;
-        IO::store1(a.vp_rev, i, (a.beta ? a.beta[stok] : 1.0f) * a.C[stok] * IO::load(a.k, src));
+        const float bc = (a.beta ? a.beta[stok] : 1.0f) * a.C[stok];
+        IO::store4(a.vp_rev, i, bc * kv[0], bc * kv[1], bc * kv[2], bc * kv[3]);
     }
 }
 
@@ -87,25 +101,28 @@ __global__ __launch_bounds__(64) void bwd_rule_scan_kernel(BackwardGlueArgs a)
 {
     const int lane = threadIdx.x;
     const int64_t b = blockIdx.x / a.H, h = blockIdx.x - b * a.H;
+    auto index = [&](int64_t t) { return (b * a.T + (t >= 0 ? t : 0)) * a.H + h; };
+    auto next_gate = [&](int64_t t) { return (t >= 0 && t + 1 < a.T) ? a.gate[index(t + 1)] : 0.0f; };
     float carry = 0.0f;
+    float c_next = a.c[index(a.T - 1 - lane)], g_next = next_gate(a.T - 1 - lane);   // read one block ahead
     for (int64_t t0 = a.T - 1; t0 >= 0; t0 -= 64) {
         const int64_t t = t0 - lane;
-        const int64_t m = (b * a.T + (t >= 0 ? t : 0)) * a.H + h;
-        float c = t >= 0 ? a.c[m] : 0.0f;
-        const float gnext = (t >= 0 && t + 1 < a.T) ? a.gate[m + a.H] : 0.0f;
-        float w = gnext * gnext;
+        float c = t >= 0 ? c_next : 0.0f;
+        float w = g_next * g_next;
+        c_next = a.c[index(t - 64)];
+        g_next = next_gate(t - 64);
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const float cp = __shfl_up(c, off, 64), wp = __shfl_up(w, off, 64);
             if (lane >= off) { c = c + w * cp; w = w * wp; }
         }
         const float run = c + w * carry;
-        if (t >= 0) a.C[m] = run;
+        if (t >= 0) a.C[index(t)] = run;
         carry = lane_value(run, 63);
     }
 }
 
-// One wave per token: the pieces are combined into the gradients (Section 4.2.2, Appendix B.2):
+// d / 4 lanes per token: the pieces are combined into the gradients (Section 4.2.2, Appendix B.2):
 //   dq = p + (1 - alpha) dxt,  dk = beta (-A k - A^T k + Ubar^T v),  dv = beta Ubar k,
 //   dalpha = dxt . (x - q),  dlambda = -x . p,  dbeta = k^T Abar k + v . (Ubar k)  (Abar = -A without the rule),
 //   s = -p . (H x) + dy . y - beta dbeta      (the gate gradient is the reverse cumulative sum of s over gamma)
@@ -116,53 +133,62 @@ __global__ __launch_bounds__(64) void bwd_rule_scan_kernel(BackwardGlueArgs a)
 template <class IO, int D>
 __global__ __launch_bounds__(256) void bwd_combine_kernel(BackwardGlueArgs a)
 {
-    constexpr int E = D / 64;                    // elements per lane
+    constexpr int LPT = D / 4;                   // lanes per token, four features each
+    constexpr int TPW = 64 / LPT;                // tokens per wave
     const int lane = threadIdx.x & 63;
-    const int64_t tok = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);      // index into [B,T,H]
-    if (tok >= a.n_tokens) return;
+    const int sub = lane % LPT;
+    const int64_t tok_raw = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * TPW + lane / LPT;   // index into [B,T,H]
+    const bool live = tok_raw < a.n_tokens;      // a dead group computes on the last token and stores nothing
+    const int64_t tok = live ? tok_raw : a.n_tokens - 1;
     const int64_t bt = tok / a.H, h = tok - bt * a.H;
     const int64_t b = bt / a.T, t = bt - b * a.T;
     const int64_t rtok = (b * a.T + (a.T - 1 - t)) * a.H + h;              // the same token in the reversed tensors
+    const int64_t i = tok * D + sub * 4, ri = rtok * D + sub * 4;
+    auto group_sum = [](float x) {
+#pragma unroll
+        for (int off = LPT / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+        return x;
+    };
     const float al = a.alpha ? a.alpha[tok] : 1.0f;
     const float be = a.beta ? a.beta[tok] : 1.0f;
-    float s_dalpha = 0.0f, s_dlam = 0.0f, s_ka1 = 0.0f, s_vd4 = 0.0f, s_phx = 0.0f, s_dyy = 0.0f;
     const bool rule = a.rule_a > 0.0f;
     const float Ct = rule ? a.C[tok] : 0.0f;
+    const f32x4 x = load_f32x4(a.x_f32, i), p = load_f32x4(a.p_f32, i);
+    const f32x4 q = IO::load4(a.q, i), k = IO::load4(a.k, i), v = IO::load4(a.v, i), dy = IO::load4(a.dy, i);
+    const f32x4 dxt = IO::load4(a.dxt_io, i), y = IO::load4(a.y_io, i), hx = IO::load4(a.hx_io, i);
+    const f32x4 a1 = IO::load4(a.r1, ri), a2 = IO::load4(a.r2, ri), u1 = IO::load4(a.r3, ri), d4 = IO::load4(a.r4, ri);
+    f32x4 hk = {0.0f, 0.0f, 0.0f, 0.0f}, r5 = hk;
     float kk = 0.0f;                             // k_t . k_t (the rule's diagonal term)
     if (rule) {
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const float kv = IO::load(a.k, tok * D + lane * E + e);
-            kk += kv * kv;
-        }
-        kk = wave_sum(kk);
+        hk = IO::load4(a.hk_io, i);
+        r5 = IO::load4(a.r5, ri);
+        kk = group_sum(k[0] * k[0] + k[1] * k[1] + k[2] * k[2] + k[3] * k[3]);
     }
+    float s_dalpha = 0.0f, s_dlam = 0.0f, s_ka1 = 0.0f, s_vd4 = 0.0f, s_phx = 0.0f, s_dyy = 0.0f;
+    f32x4 o_dq, o_dk, o_dv;
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const int64_t i = tok * D + lane * E + e, ri = rtok * D + lane * E + e;
-        const float x = a.x_f32[i], p = a.p_f32[i];
-        const float q = IO::load(a.q, i), k = IO::load(a.k, i), v = IO::load(a.v, i), dy = IO::load(a.dy, i);
-        const float dxt = IO::load(a.dxt_io, i), y = IO::load(a.y_io, i), hx = IO::load(a.hx_io, i);
-        const float a1 = IO::load(a.r1, ri), a2 = IO::load(a.r2, ri), u1 = IO::load(a.r3, ri), d4 = IO::load(a.r4, ri);
+    for (int e = 0; e < 4; ++e) {
         // (Abar + Abar^T) k of the H state; with the rule, the -c_t H_t terms add -2 (C H k + sum_{j>t} ...)
-        float dkh = -a1 - a2;
-        if (rule) {
-            const float hk = IO::load(a.hk_io, i), e2 = IO::load(a.r5, ri) - be * Ct * k * kk;
-            dkh -= 2.0f * (Ct * hk + e2);
-        }
-        a.dq[i] = p + (1.0f - al) * dxt;
-        a.dk[i] = be * (u1 + dkh);
-        a.dv[i] = be * d4;
-        s_dalpha += dxt * (x - q);
-        s_dlam -= x * p;
-        s_ka1 -= 0.5f * k * dkh;
-        s_vd4 += v * d4;
-        s_phx += p * hx;
-        s_dyy += dy * y;
+        float dkh = -a1[e] - a2[e];
+        if (rule) dkh -= 2.0f * (Ct * hk[e] + (r5[e] - be * Ct * k[e] * kk));
+        o_dq[e] = p[e] + (1.0f - al) * dxt[e];
+        o_dk[e] = be * (u1[e] + dkh);
+        o_dv[e] = be * d4[e];
+        s_dalpha += dxt[e] * (x[e] - q[e]);
+        s_dlam -= x[e] * p[e];
+        s_ka1 -= 0.5f * k[e] * dkh;
+        s_vd4 += v[e] * d4[e];
+        s_phx += p[e] * hx[e];
+        s_dyy += dy[e] * y[e];
     }
-    s_dalpha = wave_sum(s_dalpha); s_dlam = wave_sum(s_dlam); s_ka1 = wave_sum(s_ka1);
-    s_vd4 = wave_sum(s_vd4); s_phx = wave_sum(s_phx); s_dyy = wave_sum(s_dyy);
-    if (lane == 0) {
+    if (live) {
+        *(f32x4 *)(a.dq + i) = o_dq;
+        *(f32x4 *)(a.dk + i) = o_dk;
+        *(f32x4 *)(a.dv + i) = o_dv;
+    }
+    s_dalpha = group_sum(s_dalpha); s_dlam = group_sum(s_dlam); s_ka1 = group_sum(s_ka1);
+    s_vd4 = group_sum(s_vd4); s_phx = group_sum(s_phx); s_dyy = group_sum(s_dyy);
+    if (live && sub == 0) {
         const float dbeta = s_vd4 - s_ka1;       // s_ka1 = -k . (Abar + Abar^T) k / 2 = -k^T Abar k
         if (a.dalpha) a.dalpha[tok] = s_dalpha;
         if (a.dlambda && !rule) a.dlambda[tok] = s_dlam;
@@ -179,13 +205,18 @@ __global__ __launch_bounds__(64) void bwd_gate_scan_kernel(BackwardGlueArgs a)
 {
     const int lane = threadIdx.x;
     const int64_t b = blockIdx.x / a.H, h = blockIdx.x - b * a.H;
+    auto index = [&](int64_t t) { return (b * a.T + (t >= 0 ? t : 0)) * a.H + h; };
     float carry = 0.0f;
+    // the next block's values are read before this block's scan, so that the walk does not pay a memory round trip
+    // per block
+    float sv_next = a.s[index(a.T - 1 - lane)], g_next = a.gate[index(a.T - 1 - lane)];
     for (int64_t t0 = a.T - 1; t0 >= 0; t0 -= 64) {
         const int64_t t = t0 - lane;                       // lane 0 takes the latest token of the block
-        const int64_t m = (b * a.T + (t >= 0 ? t : 0)) * a.H + h;
-        const float sv = t >= 0 ? a.s[m] : 0.0f;
+        const float sv = t >= 0 ? sv_next : 0.0f, gv = g_next;
+        sv_next = a.s[index(t - 64)];
+        g_next = a.gate[index(t - 64)];
         const float run = wave_inclusive_scan(sv, lane) + carry;
-        if (t >= 0) a.dgate[m] = run / a.gate[m];
+        if (t >= 0) a.dgate[index(t)] = run / gv;
         carry = lane_value(run, 63);
     }
 }
@@ -193,13 +224,14 @@ __global__ __launch_bounds__(64) void bwd_gate_scan_kernel(BackwardGlueArgs a)
 template <class IO>
 static void launch_glue_t(const BackwardGlueArgs &a, int which, hipStream_t stream)
 {
-    const unsigned blocks = (unsigned)((a.n_elems + 255) / 256);
+    const unsigned blocks = (unsigned)((a.n_elems / 4 + 255) / 256);
     switch (which) {
     case 0: hipLaunchKernelGGL((bwd_mix_kernel<IO>), dim3(blocks), dim3(256), 0, stream, a); break;
     case 1: hipLaunchKernelGGL((bwd_rhs_kernel<IO>), dim3(blocks), dim3(256), 0, stream, a); break;
     case 2: hipLaunchKernelGGL((bwd_reverse_kernel<IO>), dim3(blocks), dim3(256), 0, stream, a); break;
     case 3: {
-        const unsigned tb = (unsigned)((a.n_tokens + 3) / 4);
+        const int64_t per_block = 4 * (256 / a.d);         // 4 waves of 64 / (d / 4) tokens
+        const unsigned tb = (unsigned)((a.n_tokens + per_block - 1) / per_block);
         if (a.d == 128) hipLaunchKernelGGL((bwd_combine_kernel<IO, 128>), dim3(tb), dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((bwd_combine_kernel<IO, 64>), dim3(tb), dim3(256), 0, stream, a);
         break;
