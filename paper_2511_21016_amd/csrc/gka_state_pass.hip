@@ -22,6 +22,12 @@
 
 namespace gka {
 
+// Chunk states are written once and read once, by another kernel, after hundreds of megabytes of other states:
+// non-temporal stores (measured: the state phase of configuration 2 goes from 0.160 to 0.134 ms).
+template <class T>
+__device__ __forceinline__ void store_once(T *dst, T value) { __builtin_nontemporal_store(value, dst); }
+
+
 #ifdef GKA_DEBUG_TIMERS
 __device__ unsigned long long g_dbg_state_timers[64 * 16];
 #define GKA_STSTAMP(i)                                                                          \
@@ -224,7 +230,7 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
                 for (int r = 0; r < 16; ++r) ss += acc[r] * acc[r];
 #pragma unroll
                 for (int hh = 0; hh < HS; ++hh)
-                    Hw[((rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(vals + hh * VEC);
+                    store_once(&Hw[((rb * NB + w) * HS + hh) * 64 + lane], MMA::pack(vals + hh * VEC));
                 ss = wave_sum(ss);
                 if (lane == 0) a.ws_hn[chunk_id * (NB * NB) + rb * NB + w] = ss;
             } else {
@@ -234,7 +240,7 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
 #pragma unroll
                 for (int hh = 0; hh < HS; ++hh) {
                     frag fr = MMA::pack(vals + hh * VEC);
-                    Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
+                    store_once(&Uw[((rb * NB + w) * HS + hh) * 64 + lane], fr);
                     if (NSPL == 2) {
 #pragma unroll
                         for (int p = 0; p < VEC; ++p) lo[hh * VEC + p] = vals[hh * VEC + p] - MMA::elem(fr, p);
@@ -740,7 +746,7 @@ __device__ __forceinline__ void state_pass_body_bf16_tile(const StatePassArgs &a
                     for (int r = 0; r < 16; ++r) ss += vals[r] * vals[r];
 #pragma unroll
                     for (int hh = 0; hh < HS; ++hh)
-                        Hw[((rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(vals + hh * MMA::VEC);
+                        store_once(&Hw[((rb * NB + w) * HS + hh) * 64 + lane], MMA::pack(vals + hh * MMA::VEC));
                     ss = wave_inclusive_scan(ss, lane);           // lane 63: the wave's total
                     if (lane == 63) a.ws_hn[chunk_id * (NB * NB) + rb * NB + w] = ss;
                 } else {
@@ -749,7 +755,7 @@ __device__ __forceinline__ void state_pass_body_bf16_tile(const StatePassArgs &a
 #pragma unroll
                     for (int hh = 0; hh < HS; ++hh) {
                         frag fr = MMA::pack(vals + hh * MMA::VEC);
-                        Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
+                        store_once(&Uw[((rb * NB + w) * HS + hh) * 64 + lane], fr);
                         float back[MMA::VEC];
                         MMA::unpack(fr, back);
 #pragma unroll
@@ -758,7 +764,8 @@ __device__ __forceinline__ void state_pass_body_bf16_tile(const StatePassArgs &a
                     if (NSPL == 2) {
 #pragma unroll
                         for (int hh = 0; hh < HS; ++hh)
-                            Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(lo + hh * MMA::VEC);
+                            store_once(&Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane],
+                                       MMA::pack(lo + hh * MMA::VEC));
                     }
                 }
             }
