@@ -41,8 +41,8 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
     auto held = [&](int it) { return !LOWER || bj <= (it * RPI) / 32; };
 #pragma unroll
     for (int it = 0; it < ITS; ++it) {
-        if (held(it)) hreg[it] = *(const f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4);
-        ureg[it] = *(const f32x4 *)(Us + (int64_t)(it * 256 + t) * 4);
+        if (held(it)) hreg[it] = __builtin_nontemporal_load((const f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4));
+        ureg[it] = __builtin_nontemporal_load((const f32x4 *)(Us + (int64_t)(it * 256 + t) * 4));
     }
     if constexpr (LOWER) {
         constexpr int NBLK = D / 32, NOFF = NBLK * (NBLK - 1) / 2;
@@ -95,8 +95,8 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
                 ss += hreg[it][e] * hreg[it][e];
             }
             if (tok == T - 1) {              // the stores drain while the last token is solved
-                if (held(it)) *(f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4) = hreg[it];
-                *(f32x4 *)(Us + (int64_t)(it * 256 + t) * 4) = ureg[it];
+                if (held(it)) __builtin_nontemporal_store(hreg[it], (f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4));
+                __builtin_nontemporal_store(ureg[it], (f32x4 *)(Us + (int64_t)(it * 256 + t) * 4));
             }
         }
         ss = wave_sum(ss);
