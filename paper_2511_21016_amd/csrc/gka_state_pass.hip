@@ -98,7 +98,8 @@ __device__ __forceinline__ void store_end_state(const StatePassArgs &a, const f3
         float *t = segment_tile<D>(a, pair, seg, rb, w) + (DOH ? 0 : 1024);
 #pragma unroll
         for (int r = 0; r < 16; ++r) t[r * 64 + lane] = acc[r];
-        if (rb == 0 && DOH && threadIdx.x == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
+        // (the H workgroup's job; in a launch without H workgroups the U workgroup's)
+        if (rb == 0 && (DOH || a.only_u) && threadIdx.x == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
     }
 }
 
@@ -320,7 +321,7 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
         float *t = seg_tile(seg);
 #pragma unroll
         for (int r = 0; r < 16; ++r) t[tile_off + r * 64 + lane] = acc[r];
-        if (rb == 0 && doH && tid == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
+        if (rb == 0 && (doH || a.only_u) && tid == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
     }
 }
 

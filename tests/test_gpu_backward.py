@@ -81,13 +81,17 @@ def test_backward_with_the_frobenius_rule(dtype, compute, d, variants):
     assert max(errs.values()) <= tol, errs
 
 
-@pytest.mark.parametrize("dtype,d,rule", [("f32", 64, True), ("bf16", 128, False), ("bf16", 128, True)])
-def test_backward_over_several_segments(dtype, d, rule):
+@pytest.mark.parametrize("dtype,d,rule,gate_mean", [("f32", 64, True, 2.0), ("bf16", 128, False, 3.0),
+                                                     ("bf16", 128, True, 3.0), ("f32", 64, False, 7.0),
+                                                     ("f32", 128, True, 7.0), ("bf16", 128, False, 7.0)])
+def test_backward_over_several_segments(dtype, d, rule, gate_mean):
     """18 chunks per pair: the chunk scans of the composed passes run in several segments (more of them in the
-    plain readouts than in the solves), and the reversed sequences have a ragged first chunk."""
+    plain readouts than in the solves), and the reversed sequences have a ragged first chunk. With gate_mean = 7
+    (gates of about 0.999) the states carried from segment to segment, forwards and backwards in time, weigh in
+    every gradient."""
     import torch
     base = synth.CFG2 if dtype == "bf16" else synth.CFG1
-    w = base.scaled(B=1, H=2, T=1100, d=d, n_iter=6, seed=1234 + d)
+    w = base.scaled(B=1, H=2, T=1100, d=d, n_iter=6, gate_mean=gate_mean, seed=1234 + d)
     x = synth.make_inputs(w)
     rng = np.random.default_rng(w.seed + 3)
     dy = rng.standard_normal(x["v"].shape).astype(np.float32)

@@ -322,3 +322,23 @@ def test_solve_result_output(dtype, compute, d):
     tol = TOL_BF16 if compute == "bf16" else 1e-4
     assert pair_rel_err(to_host(ex["xhat"]), rex["xhat"]) <= tol
     assert pair_rel_err(to_host(o), ref) <= (TOL_F32 if dtype == "f32" else TOL_BF16)
+
+
+@pytest.mark.parametrize("dtype,compute,d", [("f32", "f32", 64), ("bf16", "f32", 128), ("bf16", "bf16", 128)])
+def test_slow_decay_over_many_segments(dtype, compute, d):
+    """Gates of about 0.999: after 1300 tokens the first token still weighs e^-2, so every state that the segmented
+    chunk scan carries from segment to segment (and the decays it carries them with) shows in the outputs and in
+    the final states. The other configurations forget within a chunk or two."""
+    base = synth.CFG2 if dtype == "bf16" else synth.CFG1
+    w = base.scaled(B=1, H=2, T=1300, d=d, n_iter=8, gate_mean=7.0, seed=4242 + d)
+    x = synth.make_inputs(w)
+    assert np.prod(x["gate"].astype(np.float64), axis=1).min() > 0.02
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    o, ex = run_forward(w, x, compute=cm, return_state=True)
+    ref, rex = oracle_forward(w, x, return_state=True)
+    err = pair_rel_err(to_host(o), ref)
+    print("slow decay", dtype, compute, d, err)
+    assert err <= (TOL_F32 if dtype == "f32" else TOL_BF16), err
+    tol_state = 5e-3 if compute == "bf16" else 2e-5
+    assert np.abs(to_host(ex["H_final"]) - rex["H_final"]).max() <= tol_state * np.abs(rex["H_final"]).max()
+    assert np.abs(to_host(ex["U_final"]) - rex["U_final"]).max() <= tol_state * np.abs(rex["U_final"]).max()
