@@ -306,6 +306,18 @@ gka_status gka_decode_tokens(const gka_params *p, float *H_state, float *U_state
 }
 
 namespace {
+// Segments of the fused readout's chunk scan: two workgroups per CU when the pairs alone do not give that many,
+// never fewer than two chunks per segment.
+constexpr int kReadoutMinWorkgroups = 512;
+void plan_readout_segments(int n_pairs, int n_chunks, int *n_segs, int *seg_len)
+{
+    int ns = (kReadoutMinWorkgroups + n_pairs - 1) / n_pairs;
+    if (ns > n_chunks / 2) ns = n_chunks / 2;
+    if (ns < 1) ns = 1;
+    *seg_len = (n_chunks + ns - 1) / ns;
+    *n_segs = (n_chunks + *seg_len - 1) / *seg_len;
+}
+
 struct BackwardPlan {
     size_t n_elems, n_tokens, esz;
     size_t off_f32[2];        // xhat, p
@@ -335,6 +347,10 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     Plan full, plain;                              // the plain readouts cut the scan into more segments
     if (make_plan(&pf, &full) != GKA_OK || make_plan(&pf, &plain, true) != GKA_OK) return GKA_ERR_SHAPE;
     bp->fwd_bytes = full.total > plain.total ? full.total : plain.total;
+    int rs_n, rs_len;
+    plan_readout_segments(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk, &rs_n, &rs_len);
+    const size_t rbytes = align_up(gka::gla_readout_workspace_bytes(p->B * p->H, rs_n, p->d_k), 256);
+    if (rbytes > bp->fwd_bytes) bp->fwd_bytes = rbytes;
     bp->total = off + bp->fwd_bytes;
     return GKA_OK;
 }
@@ -397,30 +413,56 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     auto glue = [&](int which) {
         return gka::launch_backward_glue(g, which, io_bf16, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
     };
+    // the plain readout y_t = U_t qq_t, U_t = gate_t U_{t-1} + beta_t vv_t kk_t^T, in one kernel with the state in
+    // registers (bf16 tensors and operands); `reverse`: the recurrence runs from the last token to the first
+    const bool fused = io_bf16 && p->compute == GKA_COMPUTE_BF16;
+    auto readout = [&](const void *qq, const void *kk, const void *vv, const float *beta, bool reverse, void *out) {
+        gka::ReadoutArgs r;
+        r.q = qq; r.k = kk; r.v = vv; r.o = out; r.gate = gate; r.beta = beta;
+        r.stride_h = p->d_k; r.stride_t = (int64_t)p->H * p->d_k; r.stride_b = (int64_t)p->T * p->H * p->d_k;
+        r.H = p->H; r.T = p->T; r.n_pairs = p->B * p->H;
+        plan_readout_segments(r.n_pairs, (p->T + gka::kChunk - 1) / gka::kChunk, &r.n_segs, &r.seg_len);
+        r.seg_buf = (float *)fws;
+        r.seg_logdecay = r.seg_buf + (size_t)r.n_pairs * r.n_segs * p->d_k * p->d_k;
+        r.reverse = reverse;
+        return gka::launch_gla_readout(r, p->d_k, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
+    };
+    g.natural_order = fused;
 #define GKA_TRY(expr) do { gka_status e_ = (expr); if (e_ != GKA_OK) return e_; } while (0)
     // the forward solve and output; then x, xt in the tensors' dtype, the all-zero alpha and the reversed gates
     GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf, rule ? fro : nullptr));
     GKA_TRY(glue(0));
     // dxt_t = U_t^T dy_t: the recurrence with the roles of k and v exchanged, read out with dy
-    GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
+    if (fused) GKA_TRY(readout(dy, v, k, p->beta, false, io(IO_DXT)));
+    else GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
     GKA_TRY(glue(1));
     // p_t = CH(H_t + lambda_t I, alpha_t dxt_t, r)
     GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32));
     // H_t x_t
-    GKA_TRY(fwd(io(IO_X), k, k, gate, p->beta, zeros, 0, io(IO_HX), nullptr));
+    if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, io(IO_HX)));
+    else GKA_TRY(fwd(io(IO_X), k, k, gate, p->beta, zeros, 0, io(IO_HX), nullptr));
     // the rule's extra gradient -c_t H_t at every state: c_t, C_t = sum_{s>=t} M[t,s]^2 c_s, and H_t k_t
     if (rule) {
         GKA_TRY(glue(5));
         GKA_TRY(glue(6));
-        GKA_TRY(fwd(k, k, k, gate, p->beta, zeros, 0, io(IO_HK), nullptr));
+        if (fused) GKA_TRY(readout(k, k, k, p->beta, false, io(IO_HK)));
+        else GKA_TRY(fwd(k, k, k, gate, p->beta, zeros, 0, io(IO_HK), nullptr));
     }
     // reverse recurrences: A_t k_t, A_t^T k_t, Ubar_t^T v_t, Ubar_t k_t (no write gate inside them)
     GKA_TRY(glue(2));
-    if (rule) GKA_TRY(fwd(io(IO_KR), io(IO_KR), io(IO_VPR), gate_rev, nullptr, zeros, 0, io(IO_R5), nullptr));
-    GKA_TRY(fwd(io(IO_KR), io(IO_XR), io(IO_PR), gate_rev, nullptr, zeros, 0, io(IO_R1), nullptr));
-    GKA_TRY(fwd(io(IO_KR), io(IO_PR), io(IO_XR), gate_rev, nullptr, zeros, 0, io(IO_R2), nullptr));
-    GKA_TRY(fwd(io(IO_VR), io(IO_DYR), io(IO_XTR), gate_rev, nullptr, zeros, 0, io(IO_R3), nullptr));
-    GKA_TRY(fwd(io(IO_KR), io(IO_XTR), io(IO_DYR), gate_rev, nullptr, zeros, 0, io(IO_R4), nullptr));
+    if (fused) {
+        if (rule) GKA_TRY(readout(k, k, io(IO_VPR), nullptr, true, io(IO_R5)));
+        GKA_TRY(readout(k, io(IO_X), io(IO_PR), nullptr, true, io(IO_R1)));
+        GKA_TRY(readout(k, io(IO_PR), io(IO_X), nullptr, true, io(IO_R2)));
+        GKA_TRY(readout(v, dy, io(IO_XT), nullptr, true, io(IO_R3)));
+        GKA_TRY(readout(k, io(IO_XT), dy, nullptr, true, io(IO_R4)));
+    } else {
+        if (rule) GKA_TRY(fwd(io(IO_KR), io(IO_KR), io(IO_VPR), gate_rev, nullptr, zeros, 0, io(IO_R5), nullptr));
+        GKA_TRY(fwd(io(IO_KR), io(IO_XR), io(IO_PR), gate_rev, nullptr, zeros, 0, io(IO_R1), nullptr));
+        GKA_TRY(fwd(io(IO_KR), io(IO_PR), io(IO_XR), gate_rev, nullptr, zeros, 0, io(IO_R2), nullptr));
+        GKA_TRY(fwd(io(IO_VR), io(IO_DYR), io(IO_XTR), gate_rev, nullptr, zeros, 0, io(IO_R3), nullptr));
+        GKA_TRY(fwd(io(IO_KR), io(IO_XTR), io(IO_DYR), gate_rev, nullptr, zeros, 0, io(IO_R4), nullptr));
+    }
     GKA_TRY(glue(3));
     GKA_TRY(glue(4));
 #undef GKA_TRY

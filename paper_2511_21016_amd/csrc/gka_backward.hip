@@ -56,6 +56,17 @@ __global__ __launch_bounds__(256) void bwd_reverse_kernel(BackwardGlueArgs a)
 {
     const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= a.n_elems) return;
+    if (a.natural_order) {                       // nothing to reverse: p in the tensors' dtype and beta C k
+        const f32x4 pv = load_f32x4(a.p_f32, i);
+        IO::store4(a.p_rev, i, pv[0], pv[1], pv[2], pv[3]);
+        if (a.rule_a > 0.0f) {
+            const int64_t tok = i / a.d;
+            const float bc = (a.beta ? a.beta[tok] : 1.0f) * a.C[tok];
+            const f32x4 kv = IO::load4(a.k, i);
+            IO::store4(a.vp_rev, i, bc * kv[0], bc * kv[1], bc * kv[2], bc * kv[3]);
+        }
+        return;
+    }
     const int64_t hd = (int64_t)a.H * a.d;
     const int64_t b = i / (hd * a.T), rem = i - b * hd * a.T;
     const int64_t tau = rem / hd, within = rem - tau * hd;
@@ -142,7 +153,8 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(BackwardGlueArgs a)
     const int64_t tok = live ? tok_raw : a.n_tokens - 1;
     const int64_t bt = tok / a.H, h = tok - bt * a.H;
     const int64_t b = bt / a.T, t = bt - b * a.T;
-    const int64_t rtok = (b * a.T + (a.T - 1 - t)) * a.H + h;              // the same token in the reversed tensors
+    // the same token in the results of the reversed passes
+    const int64_t rtok = a.natural_order ? tok : (b * a.T + (a.T - 1 - t)) * a.H + h;
     const int64_t i = tok * D + sub * 4, ri = rtok * D + sub * 4;
     auto group_sum = [](float x) {
 #pragma unroll

@@ -82,10 +82,30 @@ struct BackwardGlueArgs {
     const float *fro;             // ||H_t||_F of the forward pass
     float *c, *C;                 // c_t and C_t = sum_{s>=t} M[t,s]^2 c_s
     void *vp_rev;                 // time-reversed beta_t C_t k_t
+    bool natural_order;           // the reversed passes read and write the tensors in place (gla_readout `reverse`):
+                                  // nothing is reversed here, p_rev and vp_rev are plain conversions
     const void *hk_io, *r5;       // H_t k_t; reversed pass sum_{j>=t} M[t,j] beta_j C_j k_j (k_j . k_t)
 };
 // which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan, 5 rule scalars (c_t), 6 rule scan (C_t)
 hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf16, hipStream_t stream);
+
+// Gated-linear-attention readout y_t = U_t q_t, U_t = gate_t U_{t-1} + beta_t v_t k_t^T with the state in registers
+// (bf16 tensors, packed or strided like the forward pass's). reverse: the recurrence runs from the last token to
+// the first with gate'_tau = gate_{T-tau}; tensors are read and written at their own positions.
+struct ReadoutArgs {
+    const void *q, *k, *v;
+    void *o;
+    const float *gate, *beta;     // [B,T,H]; beta nullptr (= 1)
+    int64_t stride_b, stride_t, stride_h;
+    int H, T;
+    int n_pairs;                  // B * H
+    int n_segs, seg_len;          // segments of the chunk scan per pair, chunks per segment
+    float *seg_buf;               // [pairs, n_segs, d*d] segment summaries
+    float *seg_logdecay;          // [pairs, n_segs]
+    bool reverse;
+};
+hipError_t launch_gla_readout(const ReadoutArgs &a, int d, hipStream_t stream);
+size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int d);
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
                              hipStream_t stream);

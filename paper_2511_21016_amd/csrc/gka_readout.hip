@@ -1,0 +1,325 @@
+// Gated-linear-attention readout y_t = U_t q_t, U_t = gamma_t U_{t-1} + beta_t v_t k_t^T, with the state kept in
+// registers: the reverse recurrences of the backward pass (Section 4.2.2, Eq. (Ai) and its counterpart for U) and its
+// plain forward readouts (U_t^T dy_t, H_t xhat_t, H_t k_t) are all of this form. Unlike the forward pass of the layer
+// there is no solve between the state and its readout, so nothing forces the chunk states through memory: one
+// workgroup walks a segment of a pair's chunks, as the state pass does, and produces the chunk's outputs on the way,
+//   y_c = zeta_c U_[n] q_c + sum_{s<=c} M[s,c] beta_s v_s (k_s . q_c)          (chunk-wise form, Section 4.2.1),
+// then advances the state. Segment start states come from a first launch of the same kernel that only accumulates
+// (SUMMARY), exactly as in the state pass. bf16 tensors and operands, d = 128 or 64.
+//
+// Layout. Wave w owns the 32 v-features 32w .. 32w+31 of U for all k-features: accumulator tile jb holds
+// U[32w + n][32jb + kidx(r, g)] on lane (n, g), register r. In that layout a tile converts in place into the A operand
+// of (U q): no transposition, the contraction index is enumerated in kidx order on both operands. All products have
+// tokens on the output lanes (the layer's token-per-lane layout), so a token's decay is a per-lane scalar.
+// With `reverse` the kernel walks the sequence backwards: token tau of its walk is token T-1-tau of the tensors, and
+// gamma'_tau = gamma_{T-tau} (gamma'_0 multiplies a zero state), which is the recurrence of Eq. (Ai).
+#include "gka_device.hpp"
+#include "gka_kernels.hpp"
+
+namespace gka {
+
+namespace {
+
+typedef MmaBF16 MMA;
+typedef MMA::frag frag;
+
+template <int D>
+struct ReadoutShape {
+    static constexpr int NB = D / 32;              // 32-blocks of the features = waves
+    static constexpr int NT = NB * 64;             // threads
+    static constexpr int RSQ = D + 8;              // q rows: read along the row, two 8-byte runs per lane
+    static constexpr int RSK = D + 16;             // k and v rows: transpose reads (rows 32 bytes apart modulo 256)
+    static constexpr int PIECES = kChunk * D / 8 / NT;   // 16-byte pieces of a chunk's rows per thread and tensor
+    static constexpr size_t q_elems = (size_t)kChunk * RSQ;
+    static constexpr size_t k_elems = (size_t)kChunk * RSK;
+    static constexpr size_t p_frags = 3 * 2 * 64;  // masked P: three causal 32x32 tiles, two MFMA steps each
+    static constexpr size_t lds_bytes = (q_elems + 2 * k_elems) * 2 + p_frags * sizeof(frag);
+};
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+// Operand fragment whose 8 elements are two runs of 4 consecutive features of one row (cols j0.., j0+8..).
+__device__ __forceinline__ frag row_runs(const uint16_t *row, int j0)
+{
+    const u32x2_t a = *(const u32x2_t *)(row + j0), b = *(const u32x2_t *)(row + j0 + 8);
+    const u32x4_t u = {a[0], a[1], b[0], b[1]};
+    return __builtin_bit_cast(frag, u);
+}
+
+struct PaddedTile {
+    int rs;
+    __device__ __forceinline__ int operator()(int row, int col) const { return row * rs + col; }
+};
+
+template <int D>
+__device__ __forceinline__ float *summary_tile(const ReadoutArgs &a, int pair, int sg, int w, int jb)
+{
+    constexpr int NB = D / 32;
+    return a.seg_buf + (((int64_t)(pair * a.n_segs + sg) * NB + w) * NB + jb) * 1024;
+}
+
+}  // namespace
+
+template <int D, bool GATED, bool SUMMARY>
+__global__ __launch_bounds__(D * 2) void gla_readout_kernel(ReadoutArgs a)
+{
+    typedef ReadoutShape<D> SH;
+    constexpr int NB = SH::NB, NT = SH::NT, RSQ = SH::RSQ, RSK = SH::RSK, PIECES = SH::PIECES;
+    constexpr int PPR = D / 8;                     // 16-byte pieces per row
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    uint16_t *sQ = (uint16_t *)smem;
+    uint16_t *sK = sQ + SH::q_elems;
+    uint16_t *sV = sK + SH::k_elems;
+    frag *sP = (frag *)(sV + SH::k_elems);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31, g = lane >> 5;
+    const int pair = blockIdx.x % a.n_pairs;
+    const int seg = blockIdx.x / a.n_pairs;
+    const int b = pair / a.H, h = pair % a.H;
+    const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    const int64_t gate_base = (int64_t)b * a.T * a.H + h;
+    const int n_chunks = (a.T + kChunk - 1) / kChunk;
+    const int chunk_begin = seg * a.seg_len;
+    const int chunk_end = min(chunk_begin + a.seg_len, n_chunks);
+    if (chunk_begin >= chunk_end) return;          // (whole workgroup)
+
+    // token tau of the walk -> token of the tensors
+    auto tensor_token = [&](int tau) {
+        const int t = min(tau, a.T - 1);
+        return a.reverse ? a.T - 1 - t : t;
+    };
+
+    // ---- state: start of the segment
+    f32x16 acc[NB];
+#pragma unroll
+    for (int jb = 0; jb < NB; ++jb) {
+        acc[jb] = zero16();
+        if (!SUMMARY) {
+            for (int sg = 0; sg < seg; ++sg) {
+                const float *t = summary_tile<D>(a, pair, sg, w, jb);
+                const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[jb][r] = decay * acc[jb][r] + t[r * 64 + lane];
+            }
+        }
+    }
+
+    // ---- rows of a chunk: global -> registers (one chunk ahead) -> LDS
+    struct Rows {
+        u32x4_t q[PIECES], k[PIECES], v[PIECES];
+        float gate, beta;
+    };
+    auto fetch = [&](Rows &f, int c) {
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) {
+            const int piece = i * NT + tid;
+            const int64_t off = base_bh + (int64_t)tensor_token(c * kChunk + piece / PPR) * a.stride_t + 8 * (piece % PPR);
+            if (!SUMMARY) f.q[i] = *(const u32x4_t *)((const uint16_t *)a.q + off);
+            f.k[i] = *(const u32x4_t *)((const uint16_t *)a.k + off);
+            f.v[i] = *(const u32x4_t *)((const uint16_t *)a.v + off);
+        }
+        const int tau = min(c * kChunk + lane, a.T - 1);
+        if (a.reverse) f.gate = tau == 0 ? 1.0f : a.gate[gate_base + (int64_t)(a.T - tau) * a.H];
+        else f.gate = a.gate[gate_base + (int64_t)tau * a.H];
+        f.beta = 1.0f;
+        if (GATED) f.beta = a.beta[gate_base + (int64_t)tensor_token(tau) * a.H];
+    };
+    auto stage = [&](const Rows &f) {
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) {
+            const int piece = i * NT + tid;
+            const int row = piece / PPR, col = 8 * (piece % PPR);
+            if (!SUMMARY) *(u32x4_t *)(sQ + row * RSQ + col) = f.q[i];
+            *(u32x4_t *)(sK + row * RSK + col) = f.k[i];
+            *(u32x4_t *)(sV + row * RSK + col) = f.v[i];
+        }
+    };
+
+    const int sub16 = 16 * ((lane >> 4) & 1);      // this lane's half of a 32-block in transpose reads
+    float Gseg = 0.0f;
+    Rows rows;
+    fetch(rows, chunk_begin);
+    for (int c = chunk_begin; c < chunk_end; ++c) {
+        // ---- decays of the chunk (every wave for itself): lane j holds token j
+        const bool valid = c * kChunk + lane < a.T;
+        const float lg = valid ? log2_gate(rows.gate) : 0.0f;
+        const float G = wave_inclusive_scan(lg, lane);
+        const float Gtot = lane_value(G, 63);
+        Gseg += Gtot;
+        const float bj = GATED ? rows.beta : 1.0f;
+        const float wj = valid ? exp2f(Gtot - G) * bj : 0.0f;      // weight of token j in the state after the chunk
+        const float zetaC = exp2f(Gtot);
+        __syncthreads();                           // the previous chunk's tiles have been read
+        stage(rows);
+        if (c + 1 < chunk_end) fetch(rows, c + 1);
+        __syncthreads();
+
+        // V^T fragments, tokens of step (sb, h2) in kidx order: runs at 32 sb + 16 h2 + 4 g and 8 further
+        frag vt[2][2];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const int t0 = 32 * sb + 16 * h2 + 4 * g;
+                vt[sb][h2] = gather_transposed_bf16(sV, PaddedTile{RSK}, 32 * w + sub16, lane, t0, t0 + 8);
+            }
+
+        if (!SUMMARY) {
+            // ---- P = K Q^T on the causal tiles (key block sb, token block tb), one tile per wave, masked and rounded
+#pragma unroll
+            for (int tile = 0; tile < 3; ++tile) {
+                if (tile % NB != w) continue;      // (wave-uniform)
+                const int sb = tile == 2 ? 1 : 0, tb = tile == 0 ? 0 : 1;
+                f32x16 pacc = zero16();
+                const uint16_t *krow = sK + (32 * sb + n) * RSK, *qrow = sQ + (32 * tb + n) * RSQ;
+#pragma unroll
+                for (int st = 0; st < 2 * NB; ++st)
+                    pacc = MMA::mma(row_runs(krow, 16 * st + 4 * g), row_runs(qrow, 16 * st + 4 * g), pacc);
+                // M[s,t] beta_s = exp2(G_t - G_s) beta_s for s <= t (Appendix B.2, base 2)
+                const float Gt = __shfl(G, 32 * tb + n, 64);
+                float pm[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int s0 = 32 * sb + kidx(r, 0), s1 = 32 * sb + kidx(r, 1);
+                    const float Gs = g ? lane_value(G, s1) : lane_value(G, s0);
+                    const float bs = GATED ? (g ? lane_value(bj, s1) : lane_value(bj, s0)) : 1.0f;
+                    const int s = g ? s1 : s0;
+                    pm[r] = (s <= 32 * tb + n) ? pacc[r] * exp2f(Gt - Gs) * bs : 0.0f;
+                }
+                sP[(tile * 2 + 0) * 64 + lane] = MMA::pack(pm);
+                sP[(tile * 2 + 1) * 64 + lane] = MMA::pack(pm + 8);
+            }
+
+            // ---- zeta_t U_[n] q_t for both token blocks: the state's tiles are the A operand (value + remainder)
+            f32x16 y[2] = {zero16(), zero16()};
+#pragma unroll
+            for (int jb = 0; jb < NB; ++jb)
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh) {
+                    float hi_f[8], lo_f[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) hi_f[e] = acc[jb][8 * hh + e];
+                    const frag uhi = MMA::pack(hi_f);
+                    MMA::unpack(uhi, lo_f);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) lo_f[e] = hi_f[e] - lo_f[e];
+                    const frag ulo = MMA::pack(lo_f);
+#pragma unroll
+                    for (int tb = 0; tb < 2; ++tb) {
+                        const frag qf = row_runs(sQ + (32 * tb + n) * RSQ, 32 * jb + 16 * hh + 4 * g);
+                        y[tb] = MMA::mma(uhi, qf, y[tb]);
+                        y[tb] = MMA::mma(ulo, qf, y[tb]);
+                    }
+                }
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const float zt = exp2f(__shfl(G, 32 * tb + n, 64));
+#pragma unroll
+                for (int r = 0; r < 16; ++r) y[tb][r] *= zt;
+            }
+            __syncthreads();                       // P is visible
+            // ---- + sum_s V[s] P[s,t] over the causal tiles
+#pragma unroll
+            for (int tile = 0; tile < 3; ++tile) {
+                const int sb = tile == 2 ? 1 : 0, tb = tile == 0 ? 0 : 1;
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) y[tb] = MMA::mma(vt[sb][h2], sP[(tile * 2 + h2) * 64 + lane], y[tb]);
+            }
+            // ---- store: lane (n, g) holds features 32 w + kidx(r, g) of token 32 tb + n
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb) {
+                const int tau = c * kChunk + 32 * tb + n;
+                if (tau < a.T) {
+                    const int64_t off = base_bh + (int64_t)tensor_token(tau) * a.stride_t + 32 * w + 4 * g;
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4)
+                        IOBF16::store4(a.o, off + 8 * q4, y[tb][4 * q4], y[tb][4 * q4 + 1], y[tb][4 * q4 + 2],
+                                       y[tb][4 * q4 + 3]);
+                }
+            }
+        }
+
+        // ---- U <- zeta_C U + sum_s w_s v_s k_s^T: tile jb gets K^T (block jb) times the weighted V^T fragments
+        frag vw[2][2];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                float x[8];
+                MMA::unpack(vt[sb][h2], x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int s0 = 32 * sb + 16 * h2 + kidx(e, 0), s1 = 32 * sb + 16 * h2 + kidx(e, 1);
+                    x[e] *= g ? lane_value(wj, s1) : lane_value(wj, s0);
+                }
+                vw[sb][h2] = MMA::pack(x);
+            }
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[jb][r] *= zetaC;
+#pragma unroll
+            for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const int t0 = 32 * sb + 16 * h2 + 4 * g;
+                    const frag kt = gather_transposed_bf16(sK, PaddedTile{RSK}, 32 * jb + sub16, lane, t0, t0 + 8);
+                    acc[jb] = MMA::mma(kt, vw[sb][h2], acc[jb]);
+                }
+        }
+    }
+
+    if (SUMMARY) {
+#pragma unroll
+        for (int jb = 0; jb < NB; ++jb) {
+            float *t = summary_tile<D>(a, pair, seg, w, jb);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t[r * 64 + lane] = acc[jb][r];
+        }
+        if (tid == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
+    }
+}
+
+template <int D, bool GATED>
+static hipError_t launch_readout_d(const ReadoutArgs &a0, hipStream_t stream)
+{
+    typedef ReadoutShape<D> SH;
+    ReadoutArgs a = a0;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gla_readout_kernel<D, GATED, false>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::lds_bytes);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void *)gla_readout_kernel<D, GATED, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (a.n_segs > 1) {
+        // summaries of every segment but the last, each from a zero state
+        hipLaunchKernelGGL((gla_readout_kernel<D, GATED, true>), dim3(a.n_pairs * (a.n_segs - 1)), dim3(SH::NT),
+                           SH::lds_bytes, stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL((gla_readout_kernel<D, GATED, false>), dim3(a.n_pairs * a.n_segs), dim3(SH::NT), SH::lds_bytes,
+                       stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gla_readout(const ReadoutArgs &a, int d, hipStream_t stream)
+{
+    if (d == 128) return a.beta ? launch_readout_d<128, true>(a, stream) : launch_readout_d<128, false>(a, stream);
+    return a.beta ? launch_readout_d<64, true>(a, stream) : launch_readout_d<64, false>(a, stream);
+}
+
+size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int d)
+{
+    return (size_t)n_pairs * n_segs * d * d * sizeof(float) + (size_t)n_pairs * n_segs * sizeof(float);
+}
+
+}  // namespace gka
