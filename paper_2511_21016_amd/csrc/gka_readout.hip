@@ -62,7 +62,7 @@ __device__ __forceinline__ float *summary_tile(const ReadoutArgs &a, int pair, i
 }  // namespace
 
 template <int D, bool GATED, bool SUMMARY>
-__global__ __launch_bounds__(D * 2) void gla_readout_kernel(ReadoutArgs a)
+__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gla_readout_kernel(ReadoutArgs a)
 {
     typedef ReadoutShape<D> SH;
     constexpr int NB = SH::NB, NT = SH::NT, RSQ = SH::RSQ, RSK = SH::RSK, PIECES = SH::PIECES;
@@ -153,10 +153,10 @@ __global__ __launch_bounds__(D * 2) void gla_readout_kernel(ReadoutArgs a)
         const float bj = GATED ? rows.beta : 1.0f;
         const float wj = valid ? exp2f(Gtot - G) * bj : 0.0f;      // weight of token j in the state after the chunk
         const float zetaC = exp2f(Gtot);
-        __syncthreads();                           // the previous chunk's tiles have been read
+        lds_barrier();                             // the previous chunk's tiles have been read
         stage(rows);
         if (c + 1 < chunk_end) fetch(rows, c + 1);
-        __syncthreads();
+        lds_barrier();                             // (no wait for the rows in flight)
 
         // V^T fragments, tokens of step (sb, h2) in kidx order: runs at 32 sb + 16 h2 + 4 g and 8 further
         frag vt[2][2];
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(D * 2) void gla_readout_kernel(ReadoutArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) y[tb][r] *= zt;
             }
-            __syncthreads();                       // P is visible
+            lds_barrier();                         // P is visible
             // ---- + sum_s V[s] P[s,t] over the causal tiles
 #pragma unroll
             for (int tile = 0; tile < 3; ++tile) {
