@@ -188,7 +188,8 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
                     const float Gs = g ? lane_value(G, s1) : lane_value(G, s0);
                     const float bs = GATED ? (g ? lane_value(bj, s1) : lane_value(bj, s0)) : 1.0f;
                     const int s = g ? s1 : s0;
-                    pm[r] = (s <= 32 * tb + n) ? pacc[r] * exp2f(Gt - Gs) * bs : 0.0f;
+                    // hardware exp2: decays under 2^-126 are flushed to zero
+                    pm[r] = (s <= 32 * tb + n) ? pacc[r] * __builtin_amdgcn_exp2f(Gt - Gs) * bs : 0.0f;
                 }
                 sP[(tile * 2 + 0) * 64 + lane] = MMA::pack(pm);
                 sP[(tile * 2 + 1) * 64 + lane] = MMA::pack(pm + 8);
