@@ -182,15 +182,16 @@ gka_status gka_decode_tokens(const gka_params *p,
 /* Backward pass of the layer by implicit differentiation (Section 4.2.2 "Backward Pass", Appendix B.2): given
  * dy_t = dL/dy_t, the gradients at q, k, v, the gates and lambda (and at the write gate and the alpha-connection if
  * they are in use). The forward solve's result is treated as the exact solution of its system and both solves run
- * r passes of Algorithm 1 (dq_t = CH(H_t + lambda_t I, dxhat_t, r)), as in the paper. Everything runs on the forward
- * kernels plus a few elementwise ones: two solves and six gated-linear-attention readouts (the reverse recurrences
- * of Section 4.2.2 are readouts of time-reversed sequences), i.e. about six to seven times the cost of gka_forward;
- * the paper's chunk-wise backward kernels are not reproduced.
+ * r passes of Algorithm 1 (dq_t = CH(H_t + lambda_t I, dxhat_t, r)), as in the paper. The two solves run on the
+ * forward kernels; the reverse recurrences of Section 4.2.2 are six gated-linear-attention readouts, four of them
+ * walking the sequence backwards (one kernel with the state in registers for GKA_COMPUTE_BF16, the forward kernels
+ * on reversed copies for GKA_COMPUTE_F32), plus a few elementwise kernels: about five times the cost of gka_forward
+ * with bf16 operands; the paper's chunk-wise backward kernels are not reproduced.
  *   Supported: lambda given or NULL with p->lambda_scale > 0 (the rule lambda_t = a ||H_t||_F, whose w_t H_t terms
  *   of the Lemma in Section 4.2.2 cost two more readouts), zero initial states, packed tensors (explicit strides:
  *   GKA_ERR_UNSUPPORTED), p->beta and p->alpha as in gka_forward. Gates must be > 0 (dgate divides by them).
- *   q, k, v, dy  [B,T,H,d] io_dtype;  gate, lambda [B,T,H] float32
- *   dq, dk, dv   [B,T,H,d] float32 (written);  dgate [B,T,H] float32 (written)
+ *   q, k, v, dy  [B,T,H,d] io_dtype, 16-byte aligned;  gate, lambda [B,T,H] float32
+ *   dq, dk, dv   [B,T,H,d] float32, 16-byte aligned (written);  dgate [B,T,H] float32 (written)
  *   dlambda, dbeta, dalpha [B,T,H] float32, each written if not NULL (dlambda only when lambda is given)
  *   workspace: gka_backward_workspace_bytes(p) bytes, 256-byte aligned (about 24 tensors of the size of q in
  *   io_dtype plus the forward workspace); contents unspecified afterwards. */
