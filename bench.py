@@ -51,6 +51,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--no-sketch", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); every (batch, head) pair is independent, "
@@ -253,6 +254,31 @@ def main():
                               "times_forward": ms_bwd / ms_per_step, "workspace_bytes": bws.numel(),
                               "frobenius_rule_ms_per_call": ms_rule}
         del bws, dyb
+
+    # ---- latent sketching on the same workload (extra information): sketch dimension 32, one Gaussian sketch per head
+    if not args.no_sketch:
+        xs = sets[0]
+        d_s = 32
+        gen = torch.Generator(device="cuda").manual_seed(7)
+        S = torch.randn((w.H, d_s, w.d), generator=gen, device="cuda", dtype=torch.float32) / w.d ** 0.5
+        sparams = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16)
+        sws = torch.empty(binding.forward_sketched_workspace_bytes(sparams, d_s), dtype=torch.uint8, device="cuda")
+        so = torch.empty_like(xs["v"])
+        call = lambda: binding.gka_forward_sketched(xs["q"], xs["k"], xs["v"], xs["gate"], xs["lam"], S, w.n_iter,
+                                                    workspace=sws, out=so)
+        for _ in range(20):
+            call()
+        torch.cuda.synchronize()
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record()
+        for _ in range(50):
+            call()
+        s1.record()
+        torch.cuda.synchronize()
+        ms_sk = s0.elapsed_time(s1) / 50
+        result["latent_sketching"] = {"sketch_dim": d_s, "ms_per_step": ms_sk, "tokens_per_s": tokens / (ms_sk * 1e-3),
+                                      "times_forward": ms_sk / ms_per_step, "workspace_bytes": sws.numel()}
+        del sws, so, S
 
     if not args.no_cpu_baseline:
         import oracle

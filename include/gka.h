@@ -205,6 +205,30 @@ gka_status gka_backward(const gka_params *p,
                         void *workspace, size_t workspace_bytes,
                         void *hip_stream);
 
+/* Forward pass with latent sketching (appendix "Latent Sketching for Approximate Solutions"): the normal equations
+ * are projected into the subspace spanned by the rows of a sketch matrix S, solved there, and the solution is
+ * projected back:
+ *     z_t = CH(S H_t S^T + lambda_t I, S q_t, r),   xhat_t = S^T z_t,   y_t = U_t xhat_t,
+ * with S H_t S^T = sum_i eta_{t,i} (S k_i)(S k_i)^T and the bounds of Section 4.1 taken in the subspace
+ * (L = ||S H_t S^T||_F + lambda_t, mu = lambda_t; lambda NULL: lambda_t = p->lambda_scale ||S H_t S^T||_F). The paper
+ * gives no formulas for this variant; this is the reading the library and its test oracle share. U_t is the full
+ * state of Eq. (CH); sketched keys are not renormalised.
+ *   S        [d_s, d_k] float32 (one sketch for all heads) or, with sketch_per_head != 0, [H, d_s, d_k]; 1 <= d_s <= 64
+ *   q, k, v, o, gate, lambda, p->beta: as in gka_forward; p->alpha must be NULL
+ *   Supported: GKA_BF16 tensors with GKA_COMPUTE_BF16, packed layout, zero initial states (else GKA_ERR_UNSUPPORTED;
+ *   d_s out of range: GKA_ERR_SHAPE).
+ *   workspace: gka_forward_sketched_workspace_bytes(p, d_s) bytes, 256-byte aligned; contents unspecified afterwards.
+ * The solve runs on the forward kernels in 64 sketched dimensions (rows of zeros are appended to S, which changes
+ * nothing); the readout with U_t is a separate kernel that keeps the state in registers. */
+size_t gka_forward_sketched_workspace_bytes(const gka_params *p, int d_s);
+gka_status gka_forward_sketched(const gka_params *p,
+                                const void *q, const void *k, const void *v,
+                                const float *gate, const float *lambda,
+                                const float *S, int d_s, int sketch_per_head,
+                                void *o,
+                                void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
+
 const char *gka_status_string(gka_status s);
 
 /* Library version: major * 10000 + minor * 100 + patch. */

@@ -24,6 +24,8 @@ EXPORTED_SYMBOLS = (
     "gka_decode_tokens",
     "gka_backward_workspace_bytes",
     "gka_backward",
+    "gka_forward_sketched_workspace_bytes",
+    "gka_forward_sketched",
     "gka_status_string",
     "gka_version",
 )
@@ -81,6 +83,11 @@ def load_library():
         lib.gka_backward.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp, fp, vp,
                                      ctypes.c_size_t, vp]
         lib.gka_backward.restype = ctypes.c_int
+        lib.gka_forward_sketched_workspace_bytes.argtypes = [ctypes.POINTER(GkaParams), ctypes.c_int]
+        lib.gka_forward_sketched_workspace_bytes.restype = ctypes.c_size_t
+        lib.gka_forward_sketched.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, fp, ctypes.c_int,
+                                             ctypes.c_int, vp, vp, ctypes.c_size_t, vp]
+        lib.gka_forward_sketched.restype = ctypes.c_int
         lib.gka_status_string.argtypes = [ctypes.c_int]
         lib.gka_status_string.restype = ctypes.c_char_p
         lib.gka_version.argtypes = []
@@ -275,3 +282,35 @@ def gka_backward(q, k, v, gate, lam, dy, n_iter, *, compute=None, beta=None, alp
                         _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dgate"]), _ptr(out.get("dlam")),
                         _ptr(out.get("dbeta")), _ptr(out.get("dalpha")), _ptr(workspace), workspace.numel(), stream))
     return out
+
+
+def forward_sketched_workspace_bytes(params, d_s):
+    return int(load_library().gka_forward_sketched_workspace_bytes(ctypes.byref(params), d_s))
+
+
+def forward_sketched_raw(params, q, k, v, gate, lam, S, d_s, per_head, o, workspace=None, workspace_bytes=0,
+                         stream=None):
+    pp = None if params is None else ctypes.byref(params)
+    return int(load_library().gka_forward_sketched(pp, q, k, v, gate, lam, S, d_s, per_head, o, workspace,
+                                                   workspace_bytes, stream))
+
+
+def gka_forward_sketched(q, k, v, gate, lam, S, n_iter, *, beta=None, lambda_scale=0.0, workspace=None, out=None):
+    """gka_forward_sketched on torch CUDA tensors: bf16 q, k, v [B,T,H,d] (packed), S float32 [d_s,d] or [H,d_s,d]."""
+    import torch
+    B, T, H, d = q.shape
+    for x in (q, k, v, S):
+        if not x.is_contiguous():
+            raise ValueError("gka_forward_sketched takes packed tensors")
+    per_head = 1 if S.dim() == 3 else 0
+    d_s = S.shape[-2]
+    params = make_params(B, H, T, d, n_iter, _io_dtype(q), GKA_COMPUTE_BF16, lambda_scale=lambda_scale,
+                         beta=_ptr(beta))
+    nbytes = forward_sketched_workspace_bytes(params, d_s)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=q.device)
+    o = torch.empty_like(v) if out is None else out
+    stream = torch.cuda.current_stream(q.device).cuda_stream
+    _check(forward_sketched_raw(params, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam), _ptr(S), d_s, per_head,
+                                _ptr(o), _ptr(workspace), workspace.numel(), stream))
+    return o

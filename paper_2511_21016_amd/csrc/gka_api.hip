@@ -418,7 +418,7 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     const bool fused = io_bf16 && p->compute == GKA_COMPUTE_BF16;
     auto readout = [&](const void *qq, const void *kk, const void *vv, const float *beta, bool reverse, void *out) {
         gka::ReadoutArgs r;
-        r.q = qq; r.k = kk; r.v = vv; r.o = out; r.gate = gate; r.beta = beta;
+        r.q = qq; r.q_lo = nullptr; r.k = kk; r.v = vv; r.o = out; r.gate = gate; r.beta = beta;
         r.stride_h = p->d_k; r.stride_t = (int64_t)p->H * p->d_k; r.stride_b = (int64_t)p->T * p->H * p->d_k;
         r.H = p->H; r.T = p->T; r.n_pairs = p->B * p->H;
         plan_readout_segments(r.n_pairs, (p->T + gka::kChunk - 1) / gka::kChunk, &r.n_segs, &r.seg_len);
@@ -467,6 +467,94 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     GKA_TRY(glue(4));
 #undef GKA_TRY
     return GKA_OK;
+}
+
+// ---- latent sketching: down-projection, the solve in 64 (zero-padded) sketched dimensions on the forward kernels,
+// up-projection, plain readout with the full U_t
+namespace {
+struct SketchPlan {
+    size_t n_tokens;
+    size_t off_qs, off_ks, off_scratch, off_z, off_xhat, off_xhat_lo, off_fwd, fwd_bytes, total;
+    gka_params inner;             // the solve's problem: d = 64, packed
+    int rs_n, rs_len;
+};
+constexpr int kSketchDim = 64;
+gka_status make_sketch_plan(const gka_params *p, int d_s, SketchPlan *sp)
+{
+    gka_status s = check_common(p, false);
+    if (s != GKA_OK) return s;
+    if (p->io_dtype != GKA_BF16 || p->compute != GKA_COMPUTE_BF16) return GKA_ERR_UNSUPPORTED;
+    if (p->stride_b != 0 || p->stride_t != 0 || p->stride_h != 0) return GKA_ERR_UNSUPPORTED;
+    if (p->phase != GKA_PHASE_ALL || p->alpha) return GKA_ERR_UNSUPPORTED;
+    if (d_s < 1 || d_s > kSketchDim) return GKA_ERR_SHAPE;
+    sp->n_tokens = (size_t)p->B * p->T * p->H;
+    sp->inner = *p;
+    sp->inner.d_k = sp->inner.d_v = kSketchDim;
+    sp->inner.xhat_out = nullptr;
+    sp->inner.state_layout = GKA_STATE_FULL;
+    size_t off = 0;
+    sp->off_qs = off; off = align_up(off + sp->n_tokens * kSketchDim * 2, 256);
+    sp->off_ks = off; off = align_up(off + sp->n_tokens * kSketchDim * 2, 256);
+    sp->off_scratch = off; off = align_up(off + sp->n_tokens * kSketchDim * 2, 256);
+    sp->off_z = off; off = align_up(off + sp->n_tokens * kSketchDim * 4, 256);
+    sp->off_xhat = off; off = align_up(off + sp->n_tokens * p->d_k * 2, 256);
+    sp->off_xhat_lo = off; off = align_up(off + sp->n_tokens * p->d_k * 2, 256);
+    sp->off_fwd = off;
+    Plan pl;
+    if (make_plan(&sp->inner, &pl) != GKA_OK) return GKA_ERR_SHAPE;
+    sp->fwd_bytes = pl.total;
+    plan_readout_segments(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk, &sp->rs_n, &sp->rs_len);
+    const size_t rbytes = align_up(gka::gla_readout_workspace_bytes(p->B * p->H, sp->rs_n, p->d_k), 256);
+    if (rbytes > sp->fwd_bytes) sp->fwd_bytes = rbytes;
+    sp->total = off + sp->fwd_bytes;
+    return GKA_OK;
+}
+}  // namespace
+
+size_t gka_forward_sketched_workspace_bytes(const gka_params *p, int d_s)
+{
+    SketchPlan sp;
+    if (make_sketch_plan(p, d_s, &sp) != GKA_OK) return 0;
+    return sp.total;
+}
+
+gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
+                                const float *lambda, const float *S, int d_s, int sketch_per_head, void *o,
+                                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    SketchPlan sp;
+    gka_status st = make_sketch_plan(p, d_s, &sp);
+    if (st != GKA_OK) return st;
+    if (!q || !k || !v || !gate || !S || !o) return GKA_ERR_NULL;
+    if (!lambda && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < sp.total) return GKA_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    unsigned char *ws = (unsigned char *)workspace;
+    gka::SketchArgs sa = {};
+    sa.q = q; sa.k = k; sa.S = S; sa.d_s = d_s; sa.per_head = sketch_per_head != 0;
+    sa.qs = ws + sp.off_qs; sa.ks = ws + sp.off_ks; sa.z = (const float *)(ws + sp.off_z);
+    sa.xhat_hi = ws + sp.off_xhat; sa.xhat_lo = ws + sp.off_xhat_lo;
+    sa.T = p->T; sa.H = p->H;
+    const int n_pairs = p->B * p->H;
+    if (gka::launch_sketch(sa, n_pairs, p->d_k, false, stream) != hipSuccess) return GKA_ERR_LAUNCH;
+    // z_t = CH(S H_t S^T + lambda_t I, S q_t, r): the forward pass on the sketched keys and queries, its own readout
+    // discarded (the sketched keys stand in for its values)
+    gka_params inner = sp.inner;
+    inner.xhat_out = (float *)(ws + sp.off_z);
+    st = forward_impl(&inner, sa.qs, sa.ks, sa.ks, gate, lambda, ws + sp.off_scratch, nullptr, nullptr, nullptr, nullptr,
+                      nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr);
+    if (st != GKA_OK) return st;
+    if (gka::launch_sketch(sa, n_pairs, p->d_k, true, stream) != hipSuccess) return GKA_ERR_LAUNCH;
+    // y_t = U_t xhat_t with the full state of Eq. (CH)
+    gka::ReadoutArgs r;
+    r.q = sa.xhat_hi; r.q_lo = sa.xhat_lo; r.k = k; r.v = v; r.o = o; r.gate = gate; r.beta = p->beta;
+    r.stride_h = p->d_k; r.stride_t = (int64_t)p->H * p->d_k; r.stride_b = (int64_t)p->T * p->H * p->d_k;
+    r.H = p->H; r.T = p->T; r.n_pairs = n_pairs;
+    r.n_segs = sp.rs_n; r.seg_len = sp.rs_len;
+    r.seg_buf = (float *)(ws + sp.off_fwd);
+    r.seg_logdecay = r.seg_buf + (size_t)n_pairs * r.n_segs * p->d_k * p->d_k;
+    r.reverse = false;
+    return gka::launch_gla_readout(r, p->d_k, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
 }
 
 const char *gka_status_string(gka_status s)

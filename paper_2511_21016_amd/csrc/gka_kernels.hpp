@@ -94,6 +94,7 @@ hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf
 // the first with gate'_tau = gate_{T-tau}; tensors are read and written at their own positions.
 struct ReadoutArgs {
     const void *q, *k, *v;
+    const void *q_lo;             // optional bf16 remainder of q (y_t = U_t (q_t + q_lo_t)), or nullptr
     void *o;
     const float *gate, *beta;     // [B,T,H]; beta nullptr (= 1)
     int64_t stride_b, stride_t, stride_h;
@@ -106,6 +107,20 @@ struct ReadoutArgs {
 };
 hipError_t launch_gla_readout(const ReadoutArgs &a, int d, hipStream_t stream);
 size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int d);
+
+// Projections of latent sketching: down (qs = S q, ks = S k, 64 sketched features stored, zeros above d_s) and up
+// (xhat = S^T z as bf16 value and optional remainder). Packed bf16 tensors [B,T,H,d]; z float32 [B,T,H,64].
+struct SketchArgs {
+    const void *q, *k;
+    const float *S;               // [d_s, d] float32, or [H, d_s, d] with per_head
+    int d_s;
+    bool per_head;
+    void *qs, *ks;                // [B,T,H,64] bf16
+    const float *z;               // [B,T,H,64]
+    void *xhat_hi, *xhat_lo;      // [B,T,H,d] bf16; xhat_lo may be nullptr
+    int T, H;
+};
+hipError_t launch_sketch(const SketchArgs &a, int n_pairs, int d, bool up, hipStream_t stream);
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
                              hipStream_t stream);

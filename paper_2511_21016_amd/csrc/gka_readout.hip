@@ -5,7 +5,8 @@
 // workgroup walks a segment of a pair's chunks, as the state pass does, and produces the chunk's outputs on the way,
 //   y_c = zeta_c U_[n] q_c + sum_{s<=c} M[s,c] beta_s v_s (k_s . q_c)          (chunk-wise form, Section 4.2.1),
 // then advances the state. Segment start states come from a first launch of the same kernel that only accumulates
-// (SUMMARY), exactly as in the state pass. bf16 tensors and operands, d = 128 or 64.
+// (SUMMARY), exactly as in the state pass. bf16 tensors and operands, d = 128 or 64. QLO: q is given as a bf16 value
+// and a bf16 remainder (q + q_lo), for a q that was computed in float32 (latent sketching's projected solution).
 //
 // Layout. Wave w owns the 32 v-features 32w .. 32w+31 of U for all k-features: accumulator tile jb holds
 // U[32w + n][32jb + kidx(r, g)] on lane (n, g), register r. In that layout a tile converts in place into the A operand
@@ -34,6 +35,7 @@ struct ReadoutShape {
     static constexpr size_t k_elems = (size_t)kChunk * RSK;
     static constexpr size_t p_frags = 3 * 2 * 64;  // masked P: three causal 32x32 tiles, two MFMA steps each
     static constexpr size_t lds_bytes = (q_elems + 2 * k_elems) * 2 + p_frags * sizeof(frag);
+    static constexpr size_t lds_bytes_qlo = lds_bytes + q_elems * 2;   // with the remainder of q as a second tile
 };
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -61,7 +63,7 @@ __device__ __forceinline__ float *summary_tile(const ReadoutArgs &a, int pair, i
 
 }  // namespace
 
-template <int D, bool GATED, bool SUMMARY>
+template <int D, bool GATED, bool SUMMARY, bool QLO>
 __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gla_readout_kernel(ReadoutArgs a)
 {
     typedef ReadoutShape<D> SH;
@@ -72,6 +74,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     uint16_t *sK = sQ + SH::q_elems;
     uint16_t *sV = sK + SH::k_elems;
     frag *sP = (frag *)(sV + SH::k_elems);
+    uint16_t *sQ2 = (uint16_t *)(sP + SH::p_frags);   // (QLO only)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 
     // ---- rows of a chunk: global -> registers (one chunk ahead) -> LDS
     struct Rows {
-        u32x4_t q[PIECES], k[PIECES], v[PIECES];
+        u32x4_t q[PIECES], k[PIECES], v[PIECES], q2[QLO ? PIECES : 1];
         float gate, beta;
     };
     auto fetch = [&](Rows &f, int c) {
@@ -119,6 +122,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
             const int piece = i * NT + tid;
             const int64_t off = base_bh + (int64_t)tensor_token(c * kChunk + piece / PPR) * a.stride_t + 8 * (piece % PPR);
             if (!SUMMARY) f.q[i] = *(const u32x4_t *)((const uint16_t *)a.q + off);
+            if (QLO) f.q2[i] = *(const u32x4_t *)((const uint16_t *)a.q_lo + off);
             f.k[i] = *(const u32x4_t *)((const uint16_t *)a.k + off);
             f.v[i] = *(const u32x4_t *)((const uint16_t *)a.v + off);
         }
@@ -134,6 +138,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
             const int piece = i * NT + tid;
             const int row = piece / PPR, col = 8 * (piece % PPR);
             if (!SUMMARY) *(u32x4_t *)(sQ + row * RSQ + col) = f.q[i];
+            if (QLO) *(u32x4_t *)(sQ2 + row * RSQ + col) = f.q2[i];
             *(u32x4_t *)(sK + row * RSK + col) = f.k[i];
             *(u32x4_t *)(sV + row * RSK + col) = f.v[i];
         }
@@ -177,8 +182,11 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
                 f32x16 pacc = zero16();
                 const uint16_t *krow = sK + (32 * sb + n) * RSK, *qrow = sQ + (32 * tb + n) * RSQ;
 #pragma unroll
-                for (int st = 0; st < 2 * NB; ++st)
-                    pacc = MMA::mma(row_runs(krow, 16 * st + 4 * g), row_runs(qrow, 16 * st + 4 * g), pacc);
+                for (int st = 0; st < 2 * NB; ++st) {
+                    const frag kf = row_runs(krow, 16 * st + 4 * g);
+                    pacc = MMA::mma(kf, row_runs(qrow, 16 * st + 4 * g), pacc);
+                    if (QLO) pacc = MMA::mma(kf, row_runs(sQ2 + (32 * tb + n) * RSQ, 16 * st + 4 * g), pacc);
+                }
                 // M[s,t] beta_s = exp2(G_t - G_s) beta_s for s <= t (Appendix B.2, base 2)
                 const float Gt = __shfl(G, 32 * tb + n, 64);
                 float pm[16];
@@ -214,6 +222,8 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
                         const frag qf = row_runs(sQ + (32 * tb + n) * RSQ, 32 * jb + 16 * hh + 4 * g);
                         y[tb] = MMA::mma(uhi, qf, y[tb]);
                         y[tb] = MMA::mma(ulo, qf, y[tb]);
+                        if (QLO)
+                            y[tb] = MMA::mma(uhi, row_runs(sQ2 + (32 * tb + n) * RSQ, 32 * jb + 16 * hh + 4 * g), y[tb]);
                     }
                 }
 #pragma unroll
@@ -285,37 +295,44 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     }
 }
 
-template <int D, bool GATED>
+template <int D, bool GATED, bool QLO>
 static hipError_t launch_readout_d(const ReadoutArgs &a0, hipStream_t stream)
 {
     typedef ReadoutShape<D> SH;
     ReadoutArgs a = a0;
+    constexpr size_t lds_main = QLO ? SH::lds_bytes_qlo : SH::lds_bytes;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gla_readout_kernel<D, GATED, false>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::lds_bytes);
+        hipError_t e = hipFuncSetAttribute((const void *)gla_readout_kernel<D, GATED, false, QLO>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_main);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)gla_readout_kernel<D, GATED, true>,
+        e = hipFuncSetAttribute((const void *)gla_readout_kernel<D, GATED, true, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (a.n_segs > 1) {
         // summaries of every segment but the last, each from a zero state
-        hipLaunchKernelGGL((gla_readout_kernel<D, GATED, true>), dim3(a.n_pairs * (a.n_segs - 1)), dim3(SH::NT),
+        hipLaunchKernelGGL((gla_readout_kernel<D, GATED, true, false>), dim3(a.n_pairs * (a.n_segs - 1)), dim3(SH::NT),
                            SH::lds_bytes, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((gla_readout_kernel<D, GATED, false>), dim3(a.n_pairs * a.n_segs), dim3(SH::NT), SH::lds_bytes,
+    hipLaunchKernelGGL((gla_readout_kernel<D, GATED, false, QLO>), dim3(a.n_pairs * a.n_segs), dim3(SH::NT), lds_main,
                        stream, a);
     return hipGetLastError();
 }
 
+template <int D>
+static hipError_t launch_readout_q(const ReadoutArgs &a, hipStream_t stream)
+{
+    if (a.q_lo) return a.beta ? launch_readout_d<D, true, true>(a, stream) : launch_readout_d<D, false, true>(a, stream);
+    return a.beta ? launch_readout_d<D, true, false>(a, stream) : launch_readout_d<D, false, false>(a, stream);
+}
+
 hipError_t launch_gla_readout(const ReadoutArgs &a, int d, hipStream_t stream)
 {
-    if (d == 128) return a.beta ? launch_readout_d<128, true>(a, stream) : launch_readout_d<128, false>(a, stream);
-    return a.beta ? launch_readout_d<64, true>(a, stream) : launch_readout_d<64, false>(a, stream);
+    return d == 128 ? launch_readout_q<128>(a, stream) : launch_readout_q<64>(a, stream);
 }
 
 size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int d)

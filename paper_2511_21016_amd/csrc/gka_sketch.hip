@@ -1,0 +1,158 @@
+// Latent sketching (appendix "Latent Sketching for Approximate Solutions"): the two projections around the solve.
+//   down:  qs_t = S q_t, ks_t = S k_t     (d_s <= 64 sketched features, written as 64 with zeros above d_s)
+//   up:    xhat_t = S^T z_t               (z_t: the solve's result in the subspace, float32)
+// Both are skinny matrix products over all tokens, written for the matrix cores with tokens on the output lanes:
+// a wave takes 32 consecutive tokens of one head. The sketch S is float32 and is used as value + remainder (two bf16
+// operands), so the products carry no rounding of S; q and k are bf16 already; z is split the same way. Packed
+// [B,T,H,d] tensors.
+#include "gka_device.hpp"
+#include "gka_kernels.hpp"
+
+namespace gka {
+
+namespace {
+
+typedef MmaBF16 MMA;
+typedef MMA::frag frag;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+constexpr int kSketchPad = 64;                     // sketched features as stored (zeros above d_s)
+
+__device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
+{
+    hi = f32_to_bf16_bits(x);
+    lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
+}
+
+}  // namespace
+
+// One workgroup: 4 waves x 32 tokens of one (batch, head) pair. LDS: S as bf16 value and remainder,
+// row-major [64][D + 8].
+template <int D>
+__global__ __launch_bounds__(256) void sketch_down_kernel(SketchArgs a)
+{
+    constexpr int RS = D + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t s_hi[kSketchPad * RS];
+    __shared__ __attribute__((aligned(16))) uint16_t s_lo[kSketchPad * RS];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int n = lane & 31, g = lane >> 5;
+    const int pair = blockIdx.x, b = pair / a.H, h = pair % a.H;
+    const float *S = a.S + (a.per_head ? (int64_t)h * a.d_s * D : 0);
+    for (int e = tid; e < kSketchPad * D; e += 256) {
+        const int i = e / D, j = e % D;
+        uint16_t hi, lo;
+        split_bf16(i < a.d_s ? S[(int64_t)i * D + j] : 0.0f, hi, lo);
+        s_hi[i * RS + j] = hi;
+        s_lo[i * RS + j] = lo;
+    }
+    __syncthreads();
+    const int t = blockIdx.y * 128 + w * 32 + n;
+    const int tc = min(t, a.T - 1);
+    const int64_t row = (((int64_t)b * a.T + tc) * a.H + h) * D;
+    f32x16 aq[2] = {zero16(), zero16()}, ak[2] = {zero16(), zero16()};
+#pragma unroll
+    for (int st = 0; st < D / 16; ++st) {
+        const frag xq = __builtin_bit_cast(frag, *(const u32x4_t *)((const uint16_t *)a.q + row + 16 * st + 8 * g));
+        const frag xk = __builtin_bit_cast(frag, *(const u32x4_t *)((const uint16_t *)a.k + row + 16 * st + 8 * g));
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            const frag shi = *(const frag *)(s_hi + (32 * mt + n) * RS + 16 * st + 8 * g);
+            const frag slo = *(const frag *)(s_lo + (32 * mt + n) * RS + 16 * st + 8 * g);
+            aq[mt] = MMA::mma(shi, xq, aq[mt]);
+            aq[mt] = MMA::mma(slo, xq, aq[mt]);
+            ak[mt] = MMA::mma(shi, xk, ak[mt]);
+            ak[mt] = MMA::mma(slo, xk, ak[mt]);
+        }
+    }
+    if (t < a.T) {
+        const int64_t orow = (((int64_t)b * a.T + t) * a.H + h) * kSketchPad;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int64_t o = orow + 32 * mt + 8 * q4 + 4 * g;
+                IOBF16::store4(a.qs, o, aq[mt][4 * q4], aq[mt][4 * q4 + 1], aq[mt][4 * q4 + 2], aq[mt][4 * q4 + 3]);
+                IOBF16::store4(a.ks, o, ak[mt][4 * q4], ak[mt][4 * q4 + 1], ak[mt][4 * q4 + 2], ak[mt][4 * q4 + 3]);
+            }
+    }
+}
+
+// xhat_t = S^T z_t as bf16 value (xhat_hi) and remainder (xhat_lo, optional). LDS: S^T as bf16 value and remainder,
+// row-major [D][64 + 8].
+template <int D>
+__global__ __launch_bounds__(256) void sketch_up_kernel(SketchArgs a)
+{
+    constexpr int RS = kSketchPad + 8;
+    constexpr int NB = D / 32;
+    __shared__ __attribute__((aligned(16))) uint16_t s_hi[D * RS];
+    __shared__ __attribute__((aligned(16))) uint16_t s_lo[D * RS];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int n = lane & 31, g = lane >> 5;
+    const int pair = blockIdx.x, b = pair / a.H, h = pair % a.H;
+    const float *S = a.S + (a.per_head ? (int64_t)h * a.d_s * D : 0);
+    for (int e = tid; e < kSketchPad * D; e += 256) {
+        const int i = e / D, j = e % D;
+        uint16_t hi, lo;
+        split_bf16(i < a.d_s ? S[(int64_t)i * D + j] : 0.0f, hi, lo);
+        s_hi[j * RS + i] = hi;
+        s_lo[j * RS + i] = lo;
+    }
+    __syncthreads();
+    const int t = blockIdx.y * 128 + w * 32 + n;
+    const int tc = min(t, a.T - 1);
+    const float *zrow = a.z + (((int64_t)b * a.T + tc) * a.H + h) * kSketchPad;
+    f32x16 acc[NB];
+#pragma unroll
+    for (int mt = 0; mt < NB; ++mt) acc[mt] = zero16();
+#pragma unroll
+    for (int st = 0; st < kSketchPad / 16; ++st) {
+        float zf[8], back[8];
+        const f32x4 z0 = *(const f32x4 *)(zrow + 16 * st + 8 * g), z1 = *(const f32x4 *)(zrow + 16 * st + 8 * g + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { zf[e] = z0[e]; zf[4 + e] = z1[e]; }
+        const frag zhi = MMA::pack(zf);
+        MMA::unpack(zhi, back);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) back[e] = zf[e] - back[e];
+        const frag zlo = MMA::pack(back);
+#pragma unroll
+        for (int mt = 0; mt < NB; ++mt) {
+            const frag shi = *(const frag *)(s_hi + (32 * mt + n) * RS + 16 * st + 8 * g);
+            const frag slo = *(const frag *)(s_lo + (32 * mt + n) * RS + 16 * st + 8 * g);
+            acc[mt] = MMA::mma(shi, zhi, acc[mt]);
+            acc[mt] = MMA::mma(slo, zhi, acc[mt]);
+            acc[mt] = MMA::mma(shi, zlo, acc[mt]);
+        }
+    }
+    if (t < a.T) {
+        const int64_t orow = (((int64_t)b * a.T + t) * a.H + h) * D;
+#pragma unroll
+        for (int mt = 0; mt < NB; ++mt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int64_t o = orow + 32 * mt + 8 * q4 + 4 * g;
+                float x[4], lo[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    x[e] = acc[mt][4 * q4 + e];
+                    lo[e] = x[e] - bf16_bits_to_f32(f32_to_bf16_bits(x[e]));
+                }
+                IOBF16::store4(a.xhat_hi, o, x[0], x[1], x[2], x[3]);
+                if (a.xhat_lo) IOBF16::store4(a.xhat_lo, o, lo[0], lo[1], lo[2], lo[3]);
+            }
+    }
+}
+
+hipError_t launch_sketch(const SketchArgs &a, int n_pairs, int d, bool up, hipStream_t stream)
+{
+    const dim3 grid(n_pairs, (a.T + 127) / 128), block(256);
+    if (up) {
+        if (d == 128) hipLaunchKernelGGL(sketch_up_kernel<128>, grid, block, 0, stream, a);
+        else hipLaunchKernelGGL(sketch_up_kernel<64>, grid, block, 0, stream, a);
+    } else {
+        if (d == 128) hipLaunchKernelGGL(sketch_down_kernel<128>, grid, block, 0, stream, a);
+        else hipLaunchKernelGGL(sketch_down_kernel<64>, grid, block, 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace gka

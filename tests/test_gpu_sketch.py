@@ -1,0 +1,60 @@
+"""GPU parity: gka_forward_sketched (through the C ABI) against the latent-sketching oracle on identical seeded
+inputs."""
+import numpy as np
+import pytest
+
+from oracle import gka_sketch_oracle as sk
+from paper_2511_21016_amd import binding, synth
+from gka_testutil import pair_rel_err, to_device, to_host, upload_inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+
+
+def _sketch(rng, shape):
+    """Gaussian sketch with unit-norm rows in expectation (float32, not bf16-representable on purpose)."""
+    return (rng.standard_normal(shape) / np.sqrt(shape[-1])).astype(np.float32)
+
+
+@pytest.mark.parametrize("d,d_s,T,per_head,rule,with_beta", [(128, 32, 200, False, False, False),
+                                                             (128, 64, 333, True, True, True),
+                                                             (128, 17, 64, False, True, False),
+                                                             (64, 32, 150, True, False, True),
+                                                             (128, 32, 1100, False, False, True)])
+def test_sketched_forward_against_oracle(d, d_s, T, per_head, rule, with_beta):
+    import torch
+    w = synth.CFG2.scaled(B=2, H=2, T=T, d=d, n_iter=8, seed=3100 + d + d_s + T)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 9)
+    S = _sketch(rng, (w.H, d_s, d) if per_head else (d_s, d))
+    beta = synth.make_gates(w)["beta"] if with_beta else None
+    a = 0.05 if rule else 0.0
+    dev = upload_inputs(x, w.dtype)
+    out = binding.gka_forward_sketched(dev["q"], dev["k"], dev["v"], dev["gate"], None if rule else dev["lam"],
+                                       to_device(S, "f32"), w.n_iter, lambda_scale=a,
+                                       beta=None if beta is None else to_device(beta, "f32"))
+    torch.cuda.synchronize()
+    ref = sk.forward_sketched(x["q"], x["k"], x["v"], x["gate"], None if rule else x["lam"], S, w.n_iter, beta=beta,
+                              lambda_scale=a)
+    err = pair_rel_err(to_host(out), ref)
+    print("sketch", d, d_s, T, per_head, rule, with_beta, err)
+    # The sketched keys S k_t are an intermediate tensor of the bf16 path, stored in bf16: a relative perturbation of
+    # up to 2^-8 of S H_t S^T, which the solve amplifies by up to its condition number. With lambda_t given (1e-2 and
+    # more against ||H|| of order 1) that stays inside the forward tolerance; with the rule, kappa = (1 + a) / a = 21
+    # at a = 0.05, so up to 21 * 2^-8 = 8e-2 in the worst direction (measured: 1e-2 to 3e-2).
+    assert err <= (5e-2 if rule else TOL_BF16), err
+
+
+def test_identity_sketch_matches_the_unsketched_forward():
+    """d = 64 with S = I: the sketched path (projections, solve, separate readout) against gka_forward itself."""
+    import torch
+    w = synth.CFG2.scaled(B=1, H=2, T=300, d=64, n_iter=8, seed=77)
+    x = synth.make_inputs(w)
+    dev = upload_inputs(x, w.dtype)
+    S = np.eye(64, dtype=np.float32)
+    out = binding.gka_forward_sketched(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], to_device(S, "f32"),
+                                       w.n_iter)
+    plain = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter)
+    torch.cuda.synchronize()
+    assert pair_rel_err(to_host(out), to_host(plain).astype(np.float64)) <= TOL_BF16

@@ -104,4 +104,20 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert bw(_p(strides=(1 << 20, 2048, 128))) == binding.GKA_ERR_UNSUPPORTED
     assert bw(_p(), ws_bytes=bws - 1) == binding.GKA_ERR_WORKSPACE
     assert bw(_p(d=96)) == binding.GKA_ERR_UNSUPPORTED
+    # latent sketching: workspace query and argument checks
+    sws = binding.forward_sketched_workspace_bytes(_p(), 32)
+    assert sws > 0 and sws % 256 == 0
+    assert binding.forward_sketched_workspace_bytes(_p(), 65) == 0
+    assert binding.forward_sketched_workspace_bytes(_p(io_dtype=binding.GKA_F32, compute=binding.GKA_COMPUTE_F32), 32) == 0
+    sk = lambda p, d_s=32, **kw: binding.forward_sketched_raw(
+        p, *[kw.get(n, fake) for n in ("q", "k", "v", "gate", "lam", "S")], d_s, 0, kw.get("o", fake),
+        workspace=kw.get("ws", 0x100000), workspace_bytes=kw.get("ws_bytes", sws))
+    assert sk(_p(), S=None) == binding.GKA_ERR_NULL
+    assert sk(_p(), lam=None) == binding.GKA_ERR_NULL
+    assert sk(_p(), d_s=0) == binding.GKA_ERR_SHAPE
+    assert sk(_p(), d_s=65) == binding.GKA_ERR_SHAPE
+    assert sk(_p(alpha=fake)) == binding.GKA_ERR_UNSUPPORTED
+    assert sk(_p(compute=binding.GKA_COMPUTE_F32)) == binding.GKA_ERR_UNSUPPORTED
+    assert sk(_p(strides=(1 << 20, 2048, 128))) == binding.GKA_ERR_UNSUPPORTED
+    assert sk(_p(), ws_bytes=sws - 1) == binding.GKA_ERR_WORKSPACE
     assert binding.forward_raw(None, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
