@@ -16,6 +16,7 @@ typedef MmaBF16 MMA;
 typedef MMA::frag frag;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int kSketchPad = 64;                     // sketched features as stored (zeros above d_s)
+constexpr int kSketchReps = 1;                     // groups of 128 tokens per workgroup (S is staged once for them)
 
 __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
 {
@@ -25,7 +26,7 @@ __device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo)
 
 }  // namespace
 
-// One workgroup: 4 waves x 32 tokens of one (batch, head) pair. LDS: S as bf16 value and remainder,
+// One workgroup: kSketchReps groups of 4 waves x 32 tokens of one (batch, head) pair. LDS: S as bf16 value and remainder,
 // row-major [64][D + 8].
 template <int D>
 __global__ __launch_bounds__(256) void sketch_down_kernel(SketchArgs a)
@@ -45,7 +46,9 @@ __global__ __launch_bounds__(256) void sketch_down_kernel(SketchArgs a)
         s_lo[i * RS + j] = lo;
     }
     __syncthreads();
-    const int t = blockIdx.y * 128 + w * 32 + n;
+    for (int rep = 0; rep < kSketchReps; ++rep) {
+    const int t = (blockIdx.y * kSketchReps + rep) * 128 + w * 32 + n;
+    if (t - n >= a.T) break;                       // (wave-uniform)
     const int tc = min(t, a.T - 1);
     const int64_t row = (((int64_t)b * a.T + tc) * a.H + h) * D;
     f32x16 aq[2] = {zero16(), zero16()}, ak[2] = {zero16(), zero16()};
@@ -74,6 +77,7 @@ __global__ __launch_bounds__(256) void sketch_down_kernel(SketchArgs a)
                 IOBF16::store4(a.ks, o, ak[mt][4 * q4], ak[mt][4 * q4 + 1], ak[mt][4 * q4 + 2], ak[mt][4 * q4 + 3]);
             }
     }
+    }
 }
 
 // xhat_t = S^T z_t as bf16 value (xhat_hi) and remainder (xhat_lo, optional). LDS: S^T as bf16 value and remainder,
@@ -97,7 +101,9 @@ __global__ __launch_bounds__(256) void sketch_up_kernel(SketchArgs a)
         s_lo[j * RS + i] = lo;
     }
     __syncthreads();
-    const int t = blockIdx.y * 128 + w * 32 + n;
+    for (int rep = 0; rep < kSketchReps; ++rep) {
+    const int t = (blockIdx.y * kSketchReps + rep) * 128 + w * 32 + n;
+    if (t - n >= a.T) break;                       // (wave-uniform)
     const int tc = min(t, a.T - 1);
     const float *zrow = a.z + (((int64_t)b * a.T + tc) * a.H + h) * kSketchPad;
     f32x16 acc[NB];
@@ -140,11 +146,12 @@ __global__ __launch_bounds__(256) void sketch_up_kernel(SketchArgs a)
                 if (a.xhat_lo) IOBF16::store4(a.xhat_lo, o, lo[0], lo[1], lo[2], lo[3]);
             }
     }
+    }
 }
 
 hipError_t launch_sketch(const SketchArgs &a, int n_pairs, int d, bool up, hipStream_t stream)
 {
-    const dim3 grid(n_pairs, (a.T + 127) / 128), block(256);
+    const dim3 grid(n_pairs, (a.T + 128 * kSketchReps - 1) / (128 * kSketchReps)), block(256);
     if (up) {
         if (d == 128) hipLaunchKernelGGL(sketch_up_kernel<128>, grid, block, 0, stream, a);
         else hipLaunchKernelGGL(sketch_up_kernel<64>, grid, block, 0, stream, a);
