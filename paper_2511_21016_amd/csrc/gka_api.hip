@@ -570,6 +570,6 @@ const char *gka_status_string(gka_status s)
     return "unknown status";
 }
 
-int gka_version(void) { return 500; }
+int gka_version(void) { return 600; }
 
 }  // extern "C"
