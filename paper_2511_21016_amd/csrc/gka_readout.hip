@@ -34,7 +34,8 @@ struct ReadoutShape {
     static constexpr size_t q_elems = (size_t)kChunk * RSQ;
     static constexpr size_t k_elems = (size_t)kChunk * RSK;
     static constexpr size_t p_frags = 3 * 2 * 64;  // masked P: three causal 32x32 tiles, two MFMA steps each
-    static constexpr size_t lds_bytes = (q_elems + 2 * k_elems) * 2 + p_frags * sizeof(frag);
+    static constexpr size_t tab_bytes = 3 * kChunk * sizeof(float);   // per-token G, state weight, beta of the chunk
+    static constexpr size_t lds_bytes = (q_elems + 2 * k_elems) * 2 + p_frags * sizeof(frag) + tab_bytes;
     static constexpr size_t lds_bytes_qlo = lds_bytes + q_elems * 2;   // with the remainder of q as a second tile
 };
 
@@ -74,7 +75,8 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     uint16_t *sK = sQ + SH::q_elems;
     uint16_t *sV = sK + SH::k_elems;
     frag *sP = (frag *)(sV + SH::k_elems);
-    uint16_t *sQ2 = (uint16_t *)(sP + SH::p_frags);   // (QLO only)
+    float *sG = (float *)(sP + SH::p_frags), *sW = sG + kChunk, *sB = sW + kChunk;
+    uint16_t *sQ2 = (uint16_t *)(sB + kChunk);        // (QLO only)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -160,6 +162,11 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         const float zetaC = exp2f(Gtot);
         lds_barrier();                             // the previous chunk's tiles have been read
         stage(rows);
+        if (w == 0) {                              // per-token scalars of the chunk, read back in fragment order
+            sG[lane] = G;
+            sW[lane] = wj;
+            if (GATED) sB[lane] = bj;
+        }
         if (c + 1 < chunk_end) fetch(rows, c + 1);
         lds_barrier();                             // (no wait for the rows in flight)
 
@@ -191,13 +198,18 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
                 const float Gt = __shfl(G, 32 * tb + n, 64);
                 float pm[16];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int s0 = 32 * sb + kidx(r, 0), s1 = 32 * sb + kidx(r, 1);
-                    const float Gs = g ? lane_value(G, s1) : lane_value(G, s0);
-                    const float bs = GATED ? (g ? lane_value(bj, s1) : lane_value(bj, s0)) : 1.0f;
-                    const int s = g ? s1 : s0;
-                    // hardware exp2: decays under 2^-126 are flushed to zero
-                    pm[r] = (s <= 32 * tb + n) ? pacc[r] * __builtin_amdgcn_exp2f(Gt - Gs) * bs : 0.0f;
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    // registers 4 q4 .. 4 q4 + 3 hold keys 32 sb + 8 q4 + 4 g + (0..3)
+                    const int s0 = 32 * sb + 8 * q4 + 4 * g;
+                    const f32x4 Gs = *(const f32x4 *)(sG + s0);
+                    f32x4 bs = {1.0f, 1.0f, 1.0f, 1.0f};
+                    if (GATED) bs = *(const f32x4 *)(sB + s0);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        // hardware exp2: decays under 2^-126 are flushed to zero
+                        const float m = __builtin_amdgcn_exp2f(Gt - Gs[e]) * bs[e];
+                        pm[4 * q4 + e] = (s0 + e <= 32 * tb + n) ? pacc[4 * q4 + e] * m : 0.0f;
+                    }
                 }
                 sP[(tile * 2 + 0) * 64 + lane] = MMA::pack(pm);
                 sP[(tile * 2 + 1) * 64 + lane] = MMA::pack(pm + 8);
@@ -262,10 +274,12 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
             for (int h2 = 0; h2 < 2; ++h2) {
                 float x[8];
                 MMA::unpack(vt[sb][h2], x);
+                const int t0 = 32 * sb + 16 * h2 + 4 * g;
+                const f32x4 w0 = *(const f32x4 *)(sW + t0), w1 = *(const f32x4 *)(sW + t0 + 8);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int s0 = 32 * sb + 16 * h2 + kidx(e, 0), s1 = 32 * sb + 16 * h2 + kidx(e, 1);
-                    x[e] *= g ? lane_value(wj, s1) : lane_value(wj, s0);
+                for (int e = 0; e < 4; ++e) {
+                    x[e] *= w0[e];
+                    x[4 + e] *= w1[e];
                 }
                 vw[sb][h2] = MMA::pack(x);
             }
