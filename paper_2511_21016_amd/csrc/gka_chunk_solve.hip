@@ -400,10 +400,10 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int j = 32 * jt + kidx(r, g);
-            const float Gj = g ? lane_value(Gall, 32 * jt + kidx(r, 1)) : lane_value(Gall, 32 * jt + kidx(r, 0));
+            // (one LDS-crossbar shuffle per value; as pairs of lane reads and a select they took twice the instructions)
+            const float Gj = __shfl(Gall, j, 64);
             float bj = 1.0f;
-            if constexpr (GATED)
-                bj = g ? lane_value(ball, 32 * jt + kidx(r, 1)) : lane_value(ball, 32 * jt + kidx(r, 0));
+            if constexpr (GATED) bj = __shfl(ball, j, 64);
             // hardware exp2: results below the normal range (decays under 2^-126) are flushed to zero
             const float decay = __builtin_amdgcn_exp2f(Gc - Gj);
             mreg[jt][r] = (j <= c_local) ? (GATED ? bj * decay : decay) : 0.0f;
