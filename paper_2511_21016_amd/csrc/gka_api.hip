@@ -432,6 +432,8 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     // the forward solve and output; then x, xt in the tensors' dtype, the all-zero alpha and the reversed gates
     GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf, rule ? fro : nullptr));
     GKA_TRY(glue(0));
+    // y_t again, from the stored xt (see the combine kernel)
+    if (fused) GKA_TRY(readout(io(IO_XT), k, v, p->beta, false, io(IO_Y)));
     // dxt_t = U_t^T dy_t: the recurrence with the roles of k and v exchanged, read out with dy
     if (fused) GKA_TRY(readout(dy, v, k, p->beta, false, io(IO_DXT)));
     else GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));

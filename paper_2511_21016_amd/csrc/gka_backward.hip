@@ -136,7 +136,10 @@ __global__ __launch_bounds__(64) void bwd_rule_scan_kernel(BackwardGlueArgs a)
 // d / 4 lanes per token: the pieces are combined into the gradients (Section 4.2.2, Appendix B.2):
 //   dq = p + (1 - alpha) dxt,  dk = beta (-A k - A^T k + Ubar^T v),  dv = beta Ubar k,
 //   dalpha = dxt . (x - q),  dlambda = -x . p,  dbeta = k^T Abar k + v . (Ubar k)  (Abar = -A without the rule),
-//   s = -p . (H x) + dy . y - beta dbeta      (the gate gradient is the reverse cumulative sum of s over gamma)
+//   s = -p . (H x) + dy . y - beta dbeta      (the gate gradient is the reverse cumulative sum of s over gamma),
+//   with y = U_t xt_t read out from the stored (rounded) xt where the tensors are bf16: the sum telescopes against
+//   v . (Ubar k), which the reversed passes form from that same xt; with the forward pass's own y (formed from the
+//   unrounded xhat) the mismatch accumulates along the sequence
 // With the rule lambda_t = a ||H_t||_F the gradient at every H_t gets the term -c_t H_t (Appendix B.2,
 // Eq. (dH_t-implicit)); summed over the later states it is C_t H_t for the keys up to t (C_t = sum_{s>=t} M[t,s]^2 c_s)
 // plus a reverse recurrence over the later keys, both read from plain readouts.

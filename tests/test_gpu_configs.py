@@ -157,3 +157,39 @@ def test_cfg5_decode_full_batch_sampled():
             hh = np.where(keep, hh, Hs)
         np.testing.assert_allclose(hh, Hs, rtol=0, atol=1e-4 * np.abs(Hs).max())
         np.testing.assert_allclose(to_host(Ux)[sb, sh][:, None], Us, rtol=0, atol=1e-4 * np.abs(Us).max())
+
+
+def test_cfg2_backward_and_sketch_full_size_sampled():
+    """The backward pass and the sketched forward at the size and in the launch configuration that bench.py times
+    (64 pairs x 4096 tokens: 4 scan segments in the solves, 8 in the plain readouts), checked on three sampled
+    (batch, head) pairs that the numpy oracles can follow one by one."""
+    import torch
+    from oracle import gka_backward_oracle as bwd
+    from oracle import gka_sketch_oracle as sk
+    w = synth.CFG2
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(99)
+    dy = synth.round_to_bf16(rng.standard_normal(x["v"].shape).astype(np.float32))
+    dev = upload_inputs(x, w.dtype)
+    out = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], to_device(dy, "bf16"), w.n_iter)
+    S = (rng.standard_normal((w.H, 32, w.d)) / np.sqrt(w.d)).astype(np.float32)
+    ys = binding.gka_forward_sketched(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], to_device(S, "f32"),
+                                      w.n_iter)
+    torch.cuda.synchronize()
+    got = {n: to_host(out[n]) for n in ("dq", "dk", "dv", "dgate", "dlam")}
+    ys = to_host(ys)
+    for b, h in ((0, 0), (2, 7), (3, 15)):
+        sel = lambda a: a[b, :, h]
+        ref = bwd.backward_pair(sel(x["q"]), sel(x["k"]), sel(x["v"]), sel(x["gate"]), sel(x["lam"]), sel(dy),
+                                w.n_iter)
+        errs = {n: float(np.abs(sel(got[n]) - ref[n]).max() / np.abs(ref[n]).max()) for n in got}
+        print("cfg2 backward pair", b, h, errs)
+        # bf16 tensors (see tests/test_gpu_backward.py): the gate gradient's cumulative sum and dlam carry the largest
+        # rounding errors
+        assert max(errs[n] for n in ("dq", "dk", "dv")) <= 6e-2, errs
+        assert errs["dgate"] <= 1e-1 and errs["dlam"] <= 2e-1, errs
+        yref = sk.forward_sketched_pair(sel(x["q"]), sel(x["k"]), sel(x["v"]), sel(x["gate"]), sel(x["lam"]), S[h],
+                                        w.n_iter)
+        es = float(np.abs(sel(ys) - yref).max() / np.abs(yref).max())
+        print("cfg2 sketched pair", b, h, es)
+        assert es <= TOL_BF16, es
