@@ -183,7 +183,8 @@ gka_status gka_decode_tokens(const gka_params *p,
  * dy_t = dL/dy_t, the gradients at q, k, v, the gates and lambda (and at the write gate and the alpha-connection if
  * they are in use). The forward solve's result is treated as the exact solution of its system and both solves run
  * r passes of Algorithm 1 (dq_t = CH(H_t + lambda_t I, dxhat_t, r)), as in the paper. The two solves run on the
- * forward kernels; the reverse recurrences of Section 4.2.2 are six gated-linear-attention readouts, four of them
+ * forward kernels; the reverse recurrences of Section 4.2.2 are six gated-linear-attention readouts (seven on bf16
+ * tensors, where the output is read out again from the stored operand for the gate gradient), four of them
  * walking the sequence backwards (one kernel with the state in registers for GKA_COMPUTE_BF16, the forward kernels
  * on reversed copies for GKA_COMPUTE_F32), plus a few elementwise kernels: about five times the cost of gka_forward
  * with bf16 operands; the paper's chunk-wise backward kernels are not reproduced.
