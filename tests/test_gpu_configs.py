@@ -193,3 +193,32 @@ def test_cfg2_backward_and_sketch_full_size_sampled():
         es = float(np.abs(sel(ys) - yref).max() / np.abs(yref).max())
         print("cfg2 sketched pair", b, h, es)
         assert es <= TOL_BF16, es
+
+
+def test_cfg3_shape_backward_two_paths_agree():
+    """A long sequence (configuration 3's shape, 8 heads of it: T = 32768, 512 chunks per pair, 64 scan segments in
+    the readouts) is beyond what the numpy backward oracle follows in reasonable time; here the two GPU paths check
+    each other: bf16 operands (fused readouts, sequences walked backwards in place) against float32 operands
+    (composition of the forward kernels on reversed copies), same bf16 tensors. The float32-operand path is the one
+    whose parity with the oracle is at rounding level on small cases."""
+    import torch
+    w = synth.CFG3.scaled(H=8, seed=31)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(5)
+    dy = synth.round_to_bf16(rng.standard_normal(x["v"].shape).astype(np.float32))
+    dev = upload_inputs(x, w.dtype)
+    dyd = to_device(dy, "bf16")
+    a = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], dyd, w.n_iter,
+                             compute=binding.GKA_COMPUTE_BF16)
+    b = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], dyd, w.n_iter,
+                             compute=binding.GKA_COMPUTE_F32)
+    torch.cuda.synchronize()
+    errs = {}
+    for n in ("dq", "dk", "dv", "dgate", "dlam"):
+        ga, gb = to_host(a[n]).astype(np.float64), to_host(b[n]).astype(np.float64)
+        axes = (1, 3) if ga.ndim == 4 else (1,)
+        errs[n] = float((np.abs(ga - gb).max(axis=axes) / np.abs(gb).max(axis=axes)).max())
+        assert np.isfinite(ga).all() and np.isfinite(gb).all()
+    print("cfg3-shape backward, bf16 vs float32 operands:", errs)
+    assert max(errs[n] for n in ("dq", "dk", "dv")) <= 6e-2, errs
+    assert errs["dgate"] <= 1.5e-1 and errs["dlam"] <= 2e-1, errs
