@@ -157,7 +157,7 @@ struct PhaseEvents {
 gka_status forward_impl(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
                         const float *lambda, void *o, const float *H_init, const float *U_init, float *H_final,
                         float *U_final, float *fro_out, void *workspace, size_t workspace_bytes,
-                        void *hip_stream, PhaseEvents *prof, bool readout_only = false)
+                        void *hip_stream, PhaseEvents *prof, bool readout_only = false, bool solve_only = false)
 {
     Plan pl;
     gka_status s = make_plan(p, &pl, readout_only);
@@ -186,6 +186,8 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     so.xhat_out = p->xhat_out;
     // plain readout y_t = U_t q_t (used by the backward pass): needs alpha = 0 from the caller; no H states, no solve
     sa.only_u = readout_only; so.readout_only = readout_only;
+    // the solve alone (latent sketching): needs xhat_out; no U states, no readout, o is left untouched
+    sa.only_h = solve_only; so.solve_only = solve_only;
     so.ws_H = sa.ws_H; so.ws_U = sa.ws_U; so.ws_hn = sa.ws_hn;
     so.stride_b = pl.stride_b; so.stride_t = pl.stride_t; so.stride_h = pl.stride_h;
     so.H = p->H; so.T = p->T; so.n_iter = p->n_iter;
@@ -544,7 +546,7 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
     gka_params inner = sp.inner;
     inner.xhat_out = (float *)(ws + sp.off_z);
     st = forward_impl(&inner, sa.qs, sa.ks, sa.ks, gate, lambda, ws + sp.off_scratch, nullptr, nullptr, nullptr, nullptr,
-                      nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr);
+                      nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr, false, true);
     if (st != GKA_OK) return st;
     if (gka::launch_sketch(sa, n_pairs, p->d_k, true, stream) != hipSuccess) return GKA_ERR_LAUNCH;
     // y_t = U_t xhat_t with the full state of Eq. (CH)

@@ -623,7 +623,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     int tid_late = tid;
     asm volatile("" : "+v"(tid_late));
     const int lane_late = tid_late & 63;
-    vrows.load(a.v, base_bh, a.stride_t, tok0, a.T, tid_late);
+    if (!(GATED && a.solve_only)) vrows.load(a.v, base_bh, a.stride_t, tok0, a.T, tid_late);
     // optional output of the solve's result (the variants' kernel only, so that the plain kernel carries no trace of it)
     if (GATED && a.xhat_out && valid) {
         float *xo = a.xhat_out + (gate_base + (int64_t)tok * a.H) * D;
@@ -634,6 +634,7 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
                 *(f32x4 *)(xo + 32 * (mt0 + i) + 8 * q4 + 4 * g) =
                     f32x4{xi[i][4 * q4], xi[i][4 * q4 + 1], xi[i][4 * q4 + 2], xi[i][4 * q4 + 3]};
     }
+    if (GATED && a.solve_only) return;         // (whole workgroup) the caller wants xhat only: no U_[n], no readout
     // alpha-connection (Section 4.3): the readout is applied to alpha xhat + (1 - alpha) q
     if (GATED && a.alpha) {
         const float al = valid ? a.alpha[gate_base + (int64_t)tok * a.H] : 1.0f;

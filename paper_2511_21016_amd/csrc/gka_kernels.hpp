@@ -31,6 +31,7 @@ struct StatePassArgs {
     int final_mode;               // 1 last segment writes H_final/U_final, 2 segment summary to seg_buf
     int write_frags;              // store chunk states to ws_H / ws_U / ws_hn
     bool only_u;                  // the H states are not needed (plain readout y_t = U_t q_t): their workgroups exit
+    bool only_h;                  // the U states are not needed (solve without readout): their workgroups exit
 };
 
 struct SolveArgs {
@@ -49,6 +50,7 @@ struct SolveArgs {
     int n_pairs;                  // pairs of this launch (set by the launcher)
     int pair0;                    // first (batch, head) pair of this launch; workspace is indexed from 0
     bool readout_only;            // variants' kernel: no solve (its result is discarded by alpha = 0): H_[n] is not read
+    bool solve_only;              // variants' kernel: xhat_out is all the caller wants: U_[n] is not read, o not written
 };
 
 struct DecodeArgs {

@@ -851,6 +851,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
         group = full / PER + (id - full) / PER;
     }
     if (a.only_u && !(sub & 1)) return;            // nobody reads the H states of this launch
+    if (a.only_h && (sub & 1)) return;             // ... or its U states
     __shared__ __attribute__((aligned(1024))) uint16_t s_k[2 * kChunk * D];
     __shared__ __attribute__((aligned(16))) uint16_t s_b[kChunk * (D + MmaBF16::kRowPad)];
     if (a.write_frags) {
@@ -883,6 +884,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
         group = full / PER + (id - full) / PER;
     }
     if (a.only_u && !(sub & 1)) return;            // nobody reads the H states of this launch
+    if (a.only_h && (sub & 1)) return;             // ... or its U states
     const int rb = sub >> 1;                       // slab index (row block of H0 / U0)
     typedef typename MMA::elem_t elem_t;
     constexpr bool kDirect = std::is_same<MMA, MmaBF16>::value;    // k rows copied straight into LDS
