@@ -220,7 +220,8 @@ gka_status gka_backward(const gka_params *p,
  *   d_s out of range: GKA_ERR_SHAPE).
  *   workspace: gka_forward_sketched_workspace_bytes(p, d_s) bytes, 256-byte aligned; contents unspecified afterwards.
  * The solve runs on the forward kernels in 64 sketched dimensions (rows of zeros are appended to S, which changes
- * nothing); the readout with U_t is a separate kernel that keeps the state in registers. */
+ * nothing); the readout is a separate kernel that keeps its state in registers and, for d = 128, works in the
+ * sketched space: y_t = (U_t S^T) z_t with the d_v x 64 state built from the stored sketched keys. */
 size_t gka_forward_sketched_workspace_bytes(const gka_params *p, int d_s);
 gka_status gka_forward_sketched(const gka_params *p,
                                 const void *q, const void *k, const void *v,

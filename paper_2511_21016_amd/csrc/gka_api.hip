@@ -351,7 +351,7 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     bp->fwd_bytes = full.total > plain.total ? full.total : plain.total;
     int rs_n, rs_len;
     plan_readout_segments(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk, &rs_n, &rs_len);
-    const size_t rbytes = align_up(gka::gla_readout_workspace_bytes(p->B * p->H, rs_n, p->d_k), 256);
+    const size_t rbytes = align_up(gka::gla_readout_workspace_bytes(p->B * p->H, rs_n, p->d_k, p->d_v), 256);
     if (rbytes > bp->fwd_bytes) bp->fwd_bytes = rbytes;
     bp->total = off + bp->fwd_bytes;
     return GKA_OK;
@@ -420,14 +420,15 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     const bool fused = io_bf16 && p->compute == GKA_COMPUTE_BF16;
     auto readout = [&](const void *qq, const void *kk, const void *vv, const float *beta, bool reverse, void *out) {
         gka::ReadoutArgs r;
-        r.q = qq; r.q_lo = nullptr; r.k = kk; r.v = vv; r.o = out; r.gate = gate; r.beta = beta;
+        r.q = qq; r.q_lo = nullptr; r.q_is_f32 = false; r.k = kk; r.v = vv; r.o = out; r.gate = gate; r.beta = beta;
         r.stride_h = p->d_k; r.stride_t = (int64_t)p->H * p->d_k; r.stride_b = (int64_t)p->T * p->H * p->d_k;
+        r.qk_stride_h = r.stride_h; r.qk_stride_t = r.stride_t; r.qk_stride_b = r.stride_b;
         r.H = p->H; r.T = p->T; r.n_pairs = p->B * p->H;
         plan_readout_segments(r.n_pairs, (p->T + gka::kChunk - 1) / gka::kChunk, &r.n_segs, &r.seg_len);
         r.seg_buf = (float *)fws;
-        r.seg_logdecay = r.seg_buf + (size_t)r.n_pairs * r.n_segs * p->d_k * p->d_k;
+        r.seg_logdecay = r.seg_buf + (size_t)r.n_pairs * r.n_segs * p->d_k * p->d_v;
         r.reverse = reverse;
-        return gka::launch_gla_readout(r, p->d_k, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
+        return gka::launch_gla_readout(r, p->d_k, p->d_v, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
     };
     g.natural_order = fused;
 #define GKA_TRY(expr) do { gka_status e_ = (expr); if (e_ != GKA_OK) return e_; } while (0)
@@ -508,7 +509,7 @@ gka_status make_sketch_plan(const gka_params *p, int d_s, SketchPlan *sp)
     if (make_plan(&sp->inner, &pl) != GKA_OK) return GKA_ERR_SHAPE;
     sp->fwd_bytes = pl.total;
     plan_readout_segments(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk, &sp->rs_n, &sp->rs_len);
-    const size_t rbytes = align_up(gka::gla_readout_workspace_bytes(p->B * p->H, sp->rs_n, p->d_k), 256);
+    const size_t rbytes = align_up(gka::gla_readout_workspace_bytes(p->B * p->H, sp->rs_n, p->d_k, p->d_v), 256);
     if (rbytes > sp->fwd_bytes) sp->fwd_bytes = rbytes;
     sp->total = off + sp->fwd_bytes;
     return GKA_OK;
@@ -548,17 +549,29 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
     st = forward_impl(&inner, sa.qs, sa.ks, sa.ks, gate, lambda, ws + sp.off_scratch, nullptr, nullptr, nullptr, nullptr,
                       nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr, false, true);
     if (st != GKA_OK) return st;
-    if (gka::launch_sketch(sa, n_pairs, p->d_k, true, stream) != hipSuccess) return GKA_ERR_LAUNCH;
-    // y_t = U_t xhat_t with the full state of Eq. (CH)
     gka::ReadoutArgs r;
-    r.q = sa.xhat_hi; r.q_lo = sa.xhat_lo; r.k = k; r.v = v; r.o = o; r.gate = gate; r.beta = p->beta;
-    r.stride_h = p->d_k; r.stride_t = (int64_t)p->H * p->d_k; r.stride_b = (int64_t)p->T * p->H * p->d_k;
+    r.v = v; r.o = o; r.gate = gate; r.beta = p->beta;
+    r.stride_h = p->d_v; r.stride_t = (int64_t)p->H * p->d_v; r.stride_b = (int64_t)p->T * p->H * p->d_v;
     r.H = p->H; r.T = p->T; r.n_pairs = n_pairs;
     r.n_segs = sp.rs_n; r.seg_len = sp.rs_len;
     r.seg_buf = (float *)(ws + sp.off_fwd);
-    r.seg_logdecay = r.seg_buf + (size_t)n_pairs * r.n_segs * p->d_k * p->d_k;
     r.reverse = false;
-    return gka::launch_gla_readout(r, p->d_k, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
+    if (p->d_v == 128) {
+        // y_t = U_t S^T z_t = (sum_i eta_{t,i} beta_i v_i (S k_i)^T) z_t: the readout runs in the sketched space, on the
+        // stored sketched keys and the float32 z_t (split into value + remainder inside the kernel), with a d_v x 64
+        // state; the projected solution xhat_t is never formed
+        r.q = sa.z; r.q_lo = nullptr; r.q_is_f32 = true; r.k = sa.ks;
+        r.qk_stride_h = kSketchDim; r.qk_stride_t = (int64_t)p->H * kSketchDim;
+        r.qk_stride_b = (int64_t)p->T * p->H * kSketchDim;
+        r.seg_logdecay = r.seg_buf + (size_t)n_pairs * r.n_segs * kSketchDim * p->d_v;
+        return gka::launch_gla_readout(r, kSketchDim, p->d_v, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
+    }
+    // d = 64: xhat_t = S^T z_t as value + remainder, then y_t = U_t xhat_t with the state of Eq. (CH)
+    if (gka::launch_sketch(sa, n_pairs, p->d_k, true, stream) != hipSuccess) return GKA_ERR_LAUNCH;
+    r.q = sa.xhat_hi; r.q_lo = sa.xhat_lo; r.q_is_f32 = false; r.k = k;
+    r.qk_stride_h = r.stride_h; r.qk_stride_t = r.stride_t; r.qk_stride_b = r.stride_b;
+    r.seg_logdecay = r.seg_buf + (size_t)n_pairs * r.n_segs * p->d_k * p->d_v;
+    return gka::launch_gla_readout(r, p->d_k, p->d_v, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
 }
 
 const char *gka_status_string(gka_status s)

@@ -92,23 +92,25 @@ struct BackwardGlueArgs {
 hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf16, hipStream_t stream);
 
 // Gated-linear-attention readout y_t = U_t q_t, U_t = gate_t U_{t-1} + beta_t v_t k_t^T with the state in registers
-// (bf16 tensors, packed or strided like the forward pass's). reverse: the recurrence runs from the last token to
+// (bf16 tensors, packed or strided like the forward pass's; U is dv x dk). reverse: the recurrence runs from the last token to
 // the first with gate'_tau = gate_{T-tau}; tensors are read and written at their own positions.
 struct ReadoutArgs {
-    const void *q, *k, *v;
+    const void *q, *k, *v;        // q, k: [B,T,H,dk]; v: [B,T,H,dv]
     const void *q_lo;             // optional bf16 remainder of q (y_t = U_t (q_t + q_lo_t)), or nullptr
-    void *o;
+    bool q_is_f32;                // q is float32 (split into value + remainder inside); dk = 64, dv = 128 only
+    void *o;                      // [B,T,H,dv]
     const float *gate, *beta;     // [B,T,H]; beta nullptr (= 1)
-    int64_t stride_b, stride_t, stride_h;
+    int64_t stride_b, stride_t, stride_h;            // element strides of v and o
+    int64_t qk_stride_b, qk_stride_t, qk_stride_h;   // ... of q (q_lo) and k
     int H, T;
     int n_pairs;                  // B * H
     int n_segs, seg_len;          // segments of the chunk scan per pair, chunks per segment
-    float *seg_buf;               // [pairs, n_segs, d*d] segment summaries
+    float *seg_buf;               // [pairs, n_segs, dv*dk] segment summaries
     float *seg_logdecay;          // [pairs, n_segs]
     bool reverse;
 };
-hipError_t launch_gla_readout(const ReadoutArgs &a, int d, hipStream_t stream);
-size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int d);
+hipError_t launch_gla_readout(const ReadoutArgs &a, int dk, int dv, hipStream_t stream);
+size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int dk, int dv);
 
 // Projections of latent sketching: down (qs = S q, ks = S k, 64 sketched features stored, zeros above d_s) and up
 // (xhat = S^T z as bf16 value and optional remainder). Packed bf16 tensors [B,T,H,d]; z float32 [B,T,H,64].

@@ -24,18 +24,25 @@ namespace {
 typedef MmaBF16 MMA;
 typedef MMA::frag frag;
 
-template <int D>
+// DK: features of q and k; DV: features of v and of the output (U is DV x DK). DK = DV for the recurrences of the
+// backward pass; DK = 64, DV = 128 for the readout of latent sketching in the sketched space.
+template <int DK, int DV>
 struct ReadoutShape {
-    static constexpr int NB = D / 32;              // 32-blocks of the features = waves
+    static constexpr int NB = DV / 32;             // 32-blocks of the v-features = waves
+    static constexpr int NBK = DK / 32;            // 32-blocks of the k-features = state tiles per wave
     static constexpr int NT = NB * 64;             // threads
-    static constexpr int RSQ = D + 8;              // q rows: read along the row, two 8-byte runs per lane
-    static constexpr int RSK = D + 16;             // k and v rows: transpose reads (rows 32 bytes apart modulo 256)
-    static constexpr int PIECES = kChunk * D / 8 / NT;   // 16-byte pieces of a chunk's rows per thread and tensor
+    static constexpr int RSQ = DK + 8;             // q rows: read along the row, two 8-byte runs per lane
+    static constexpr int RSK = DK + 16;            // k and v rows: transpose reads (rows 32 bytes apart modulo 256)
+    static constexpr int RSV = DV + 16;
+    static constexpr int PK = kChunk * DK / 8 / NT;   // 16-byte pieces of a chunk's k (or bf16 q) rows per thread
+    static constexpr int PV = kChunk * DV / 8 / NT;   // ... of its v rows
+    static constexpr int PQ32 = kChunk * DK / 4 / NT; // ... of float32 q rows
     static constexpr size_t q_elems = (size_t)kChunk * RSQ;
     static constexpr size_t k_elems = (size_t)kChunk * RSK;
+    static constexpr size_t v_elems = (size_t)kChunk * RSV;
     static constexpr size_t p_frags = 3 * 2 * 64;  // masked P: three causal 32x32 tiles, two MFMA steps each
     static constexpr size_t tab_bytes = 3 * kChunk * sizeof(float);   // per-token G, state weight, beta of the chunk
-    static constexpr size_t lds_bytes = (q_elems + 2 * k_elems) * 2 + p_frags * sizeof(frag) + tab_bytes;
+    static constexpr size_t lds_bytes = (q_elems + k_elems + v_elems) * 2 + p_frags * sizeof(frag) + tab_bytes;
     static constexpr size_t lds_bytes_qlo = lds_bytes + q_elems * 2;   // with the remainder of q as a second tile
 };
 
@@ -55,26 +62,27 @@ struct PaddedTile {
     __device__ __forceinline__ int operator()(int row, int col) const { return row * rs + col; }
 };
 
-template <int D>
+template <int DK, int DV>
 __device__ __forceinline__ float *summary_tile(const ReadoutArgs &a, int pair, int sg, int w, int jb)
 {
-    constexpr int NB = D / 32;
-    return a.seg_buf + (((int64_t)(pair * a.n_segs + sg) * NB + w) * NB + jb) * 1024;
+    return a.seg_buf + (((int64_t)(pair * a.n_segs + sg) * (DV / 32) + w) * (DK / 32) + jb) * 1024;
 }
 
 }  // namespace
 
-template <int D, bool GATED, bool SUMMARY, bool QLO>
-__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gla_readout_kernel(ReadoutArgs a)
+// QMODE: 0 q in bf16; 1 q as bf16 value + bf16 remainder (q_lo); 2 q in float32, split into value + remainder here.
+template <int DK, int DV, bool GATED, bool SUMMARY, int QMODE>
+__global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gla_readout_kernel(ReadoutArgs a)
 {
-    typedef ReadoutShape<D> SH;
-    constexpr int NB = SH::NB, NT = SH::NT, RSQ = SH::RSQ, RSK = SH::RSK, PIECES = SH::PIECES;
-    constexpr int PPR = D / 8;                     // 16-byte pieces per row
+    typedef ReadoutShape<DK, DV> SH;
+    constexpr bool QLO = QMODE != 0, QF32 = QMODE == 2;
+    constexpr int NB = SH::NB, NBK = SH::NBK, NT = SH::NT, RSQ = SH::RSQ, RSK = SH::RSK, RSV = SH::RSV;
+    constexpr int PK = SH::PK, PV = SH::PV, PQ = QF32 ? SH::PQ32 : SH::PK;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint16_t *sQ = (uint16_t *)smem;
     uint16_t *sK = sQ + SH::q_elems;
     uint16_t *sV = sK + SH::k_elems;
-    frag *sP = (frag *)(sV + SH::k_elems);
+    frag *sP = (frag *)(sV + SH::v_elems);
     float *sG = (float *)(sP + SH::p_frags), *sW = sG + kChunk, *sB = sW + kChunk;
     uint16_t *sQ2 = (uint16_t *)(sB + kChunk);        // (QLO only)
 
@@ -85,7 +93,8 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     const int pair = blockIdx.x % a.n_pairs;
     const int seg = blockIdx.x / a.n_pairs;
     const int b = pair / a.H, h = pair % a.H;
-    const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    const int64_t base_v = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;            // v and the output
+    const int64_t base_qk = (int64_t)b * a.qk_stride_b + (int64_t)h * a.qk_stride_h;    // q and k
     const int64_t gate_base = (int64_t)b * a.T * a.H + h;
     const int n_chunks = (a.T + kChunk - 1) / kChunk;
     const int chunk_begin = seg * a.seg_len;
@@ -99,13 +108,13 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     };
 
     // ---- state: start of the segment
-    f32x16 acc[NB];
+    f32x16 acc[NBK];
 #pragma unroll
-    for (int jb = 0; jb < NB; ++jb) {
+    for (int jb = 0; jb < NBK; ++jb) {
         acc[jb] = zero16();
         if (!SUMMARY) {
             for (int sg = 0; sg < seg; ++sg) {
-                const float *t = summary_tile<D>(a, pair, sg, w, jb);
+                const float *t = summary_tile<DK, DV>(a, pair, sg, w, jb);
                 const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[jb][r] = decay * acc[jb][r] + t[r * 64 + lane];
@@ -115,17 +124,33 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 
     // ---- rows of a chunk: global -> registers (one chunk ahead) -> LDS
     struct Rows {
-        u32x4_t q[PIECES], k[PIECES], v[PIECES], q2[QLO ? PIECES : 1];
+        u32x4_t q[PQ], k[PK], v[PV], q2[QMODE == 1 ? PK : 1];
         float gate, beta;
     };
     auto fetch = [&](Rows &f, int c) {
 #pragma unroll
-        for (int i = 0; i < PIECES; ++i) {
+        for (int i = 0; i < PK; ++i) {
             const int piece = i * NT + tid;
-            const int64_t off = base_bh + (int64_t)tensor_token(c * kChunk + piece / PPR) * a.stride_t + 8 * (piece % PPR);
-            if (!SUMMARY) f.q[i] = *(const u32x4_t *)((const uint16_t *)a.q + off);
-            if (QLO) f.q2[i] = *(const u32x4_t *)((const uint16_t *)a.q_lo + off);
+            const int64_t off = base_qk + (int64_t)tensor_token(c * kChunk + piece / (DK / 8)) * a.qk_stride_t +
+                                8 * (piece % (DK / 8));
+            if (!SUMMARY && !QF32) f.q[i] = *(const u32x4_t *)((const uint16_t *)a.q + off);
+            if (QMODE == 1) f.q2[i] = *(const u32x4_t *)((const uint16_t *)a.q_lo + off);
             f.k[i] = *(const u32x4_t *)((const uint16_t *)a.k + off);
+        }
+        if (QF32) {
+#pragma unroll
+            for (int i = 0; i < PQ; ++i) {
+                const int piece = i * NT + tid;
+                const int64_t off = base_qk + (int64_t)tensor_token(c * kChunk + piece / (DK / 4)) * a.qk_stride_t +
+                                    4 * (piece % (DK / 4));
+                f.q[i] = *(const u32x4_t *)((const float *)a.q + off);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PV; ++i) {
+            const int piece = i * NT + tid;
+            const int64_t off = base_v + (int64_t)tensor_token(c * kChunk + piece / (DV / 8)) * a.stride_t +
+                                8 * (piece % (DV / 8));
             f.v[i] = *(const u32x4_t *)((const uint16_t *)a.v + off);
         }
         const int tau = min(c * kChunk + lane, a.T - 1);
@@ -136,13 +161,31 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     };
     auto stage = [&](const Rows &f) {
 #pragma unroll
-        for (int i = 0; i < PIECES; ++i) {
+        for (int i = 0; i < PK; ++i) {
             const int piece = i * NT + tid;
-            const int row = piece / PPR, col = 8 * (piece % PPR);
-            if (!SUMMARY) *(u32x4_t *)(sQ + row * RSQ + col) = f.q[i];
-            if (QLO) *(u32x4_t *)(sQ2 + row * RSQ + col) = f.q2[i];
+            const int row = piece / (DK / 8), col = 8 * (piece % (DK / 8));
+            if (!SUMMARY && !QF32) *(u32x4_t *)(sQ + row * RSQ + col) = f.q[i];
+            if (QMODE == 1) *(u32x4_t *)(sQ2 + row * RSQ + col) = f.q2[i];
             *(u32x4_t *)(sK + row * RSK + col) = f.k[i];
-            *(u32x4_t *)(sV + row * RSK + col) = f.v[i];
+        }
+        if (QF32) {
+#pragma unroll
+            for (int i = 0; i < PQ; ++i) {
+                const int piece = i * NT + tid;
+                const int row = piece / (DK / 4), col = 4 * (piece % (DK / 4));
+                const f32x4 x = __builtin_bit_cast(f32x4, f.q[i]);
+                float lo[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) lo[e] = x[e] - bf16_bits_to_f32(f32_to_bf16_bits(x[e]));
+                MMA::store4(sQ + row * RSQ + col, x);
+                MMA::store4(sQ2 + row * RSQ + col, f32x4{lo[0], lo[1], lo[2], lo[3]});
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PV; ++i) {
+            const int piece = i * NT + tid;
+            const int row = piece / (DV / 8), col = 8 * (piece % (DV / 8));
+            *(u32x4_t *)(sV + row * RSV + col) = f.v[i];
         }
     };
 
@@ -177,7 +220,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
                 const int t0 = 32 * sb + 16 * h2 + 4 * g;
-                vt[sb][h2] = gather_transposed_bf16(sV, PaddedTile{RSK}, 32 * w + sub16, lane, t0, t0 + 8);
+                vt[sb][h2] = gather_transposed_bf16(sV, PaddedTile{RSV}, 32 * w + sub16, lane, t0, t0 + 8);
             }
 
         if (!SUMMARY) {
@@ -189,7 +232,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
                 f32x16 pacc = zero16();
                 const uint16_t *krow = sK + (32 * sb + n) * RSK, *qrow = sQ + (32 * tb + n) * RSQ;
 #pragma unroll
-                for (int st = 0; st < 2 * NB; ++st) {
+                for (int st = 0; st < 2 * NBK; ++st) {
                     const frag kf = row_runs(krow, 16 * st + 4 * g);
                     pacc = MMA::mma(kf, row_runs(qrow, 16 * st + 4 * g), pacc);
                     if (QLO) pacc = MMA::mma(kf, row_runs(sQ2 + (32 * tb + n) * RSQ, 16 * st + 4 * g), pacc);
@@ -218,7 +261,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
             // ---- zeta_t U_[n] q_t for both token blocks: the state's tiles are the A operand (value + remainder)
             f32x16 y[2] = {zero16(), zero16()};
 #pragma unroll
-            for (int jb = 0; jb < NB; ++jb)
+            for (int jb = 0; jb < NBK; ++jb)
 #pragma unroll
                 for (int hh = 0; hh < 2; ++hh) {
                     float hi_f[8], lo_f[8];
@@ -257,7 +300,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
             for (int tb = 0; tb < 2; ++tb) {
                 const int tau = c * kChunk + 32 * tb + n;
                 if (tau < a.T) {
-                    const int64_t off = base_bh + (int64_t)tensor_token(tau) * a.stride_t + 32 * w + 4 * g;
+                    const int64_t off = base_v + (int64_t)tensor_token(tau) * a.stride_t + 32 * w + 4 * g;
 #pragma unroll
                     for (int q4 = 0; q4 < 4; ++q4)
                         IOBF16::store4(a.o, off + 8 * q4, y[tb][4 * q4], y[tb][4 * q4 + 1], y[tb][4 * q4 + 2],
@@ -284,7 +327,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
                 vw[sb][h2] = MMA::pack(x);
             }
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) {
+        for (int jb = 0; jb < NBK; ++jb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[jb][r] *= zetaC;
 #pragma unroll
@@ -300,8 +343,8 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 
     if (SUMMARY) {
 #pragma unroll
-        for (int jb = 0; jb < NB; ++jb) {
-            float *t = summary_tile<D>(a, pair, seg, w, jb);
+        for (int jb = 0; jb < NBK; ++jb) {
+            float *t = summary_tile<DK, DV>(a, pair, seg, w, jb);
 #pragma unroll
             for (int r = 0; r < 16; ++r) t[r * 64 + lane] = acc[jb][r];
         }
@@ -309,49 +352,55 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     }
 }
 
-template <int D, bool GATED, bool QLO>
+template <int DK, int DV, bool GATED, int QMODE>
 static hipError_t launch_readout_d(const ReadoutArgs &a0, hipStream_t stream)
 {
-    typedef ReadoutShape<D> SH;
+    typedef ReadoutShape<DK, DV> SH;
     ReadoutArgs a = a0;
-    constexpr size_t lds_main = QLO ? SH::lds_bytes_qlo : SH::lds_bytes;
+    constexpr size_t lds_main = QMODE != 0 ? SH::lds_bytes_qlo : SH::lds_bytes;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gla_readout_kernel<D, GATED, false, QLO>,
+        hipError_t e = hipFuncSetAttribute((const void *)gla_readout_kernel<DK, DV, GATED, false, QMODE>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_main);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)gla_readout_kernel<D, GATED, true, false>,
+        e = hipFuncSetAttribute((const void *)gla_readout_kernel<DK, DV, GATED, true, 0>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::lds_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (a.n_segs > 1) {
         // summaries of every segment but the last, each from a zero state
-        hipLaunchKernelGGL((gla_readout_kernel<D, GATED, true, false>), dim3(a.n_pairs * (a.n_segs - 1)), dim3(SH::NT),
+        hipLaunchKernelGGL((gla_readout_kernel<DK, DV, GATED, true, 0>), dim3(a.n_pairs * (a.n_segs - 1)), dim3(SH::NT),
                            SH::lds_bytes, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((gla_readout_kernel<D, GATED, false, QLO>), dim3(a.n_pairs * a.n_segs), dim3(SH::NT), lds_main,
-                       stream, a);
+    hipLaunchKernelGGL((gla_readout_kernel<DK, DV, GATED, false, QMODE>), dim3(a.n_pairs * a.n_segs), dim3(SH::NT),
+                       lds_main, stream, a);
     return hipGetLastError();
 }
 
 template <int D>
-static hipError_t launch_readout_q(const ReadoutArgs &a, hipStream_t stream)
+static hipError_t launch_readout_square(const ReadoutArgs &a, hipStream_t stream)
 {
-    if (a.q_lo) return a.beta ? launch_readout_d<D, true, true>(a, stream) : launch_readout_d<D, false, true>(a, stream);
-    return a.beta ? launch_readout_d<D, true, false>(a, stream) : launch_readout_d<D, false, false>(a, stream);
+    if (a.q_lo)
+        return a.beta ? launch_readout_d<D, D, true, 1>(a, stream) : launch_readout_d<D, D, false, 1>(a, stream);
+    return a.beta ? launch_readout_d<D, D, true, 0>(a, stream) : launch_readout_d<D, D, false, 0>(a, stream);
 }
 
-hipError_t launch_gla_readout(const ReadoutArgs &a, int d, hipStream_t stream)
+hipError_t launch_gla_readout(const ReadoutArgs &a, int dk, int dv, hipStream_t stream)
 {
-    return d == 128 ? launch_readout_q<128>(a, stream) : launch_readout_q<64>(a, stream);
+    if (a.q_is_f32) {                          // the sketched readout: float32 q, 64 sketched features, full v
+        if (dk != 64 || dv != 128 || a.q_lo) return hipErrorInvalidValue;
+        return a.beta ? launch_readout_d<64, 128, true, 2>(a, stream) : launch_readout_d<64, 128, false, 2>(a, stream);
+    }
+    if (dk != dv) return hipErrorInvalidValue;
+    return dk == 128 ? launch_readout_square<128>(a, stream) : launch_readout_square<64>(a, stream);
 }
 
-size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int d)
+size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int dk, int dv)
 {
-    return (size_t)n_pairs * n_segs * d * d * sizeof(float) + (size_t)n_pairs * n_segs * sizeof(float);
+    return (size_t)n_pairs * n_segs * dk * dv * sizeof(float) + (size_t)n_pairs * n_segs * sizeof(float);
 }
 
 }  // namespace gka

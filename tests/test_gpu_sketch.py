@@ -39,11 +39,10 @@ def test_sketched_forward_against_oracle(d, d_s, T, per_head, rule, with_beta):
                               lambda_scale=a)
     err = pair_rel_err(to_host(out), ref)
     print("sketch", d, d_s, T, per_head, rule, with_beta, err)
-    # The sketched keys S k_t are an intermediate tensor of the bf16 path, stored in bf16: a relative perturbation of
-    # up to 2^-8 of S H_t S^T, which the solve amplifies by up to its condition number. With lambda_t given (1e-2 and
-    # more against ||H|| of order 1) that stays inside the forward tolerance; with the rule, kappa = (1 + a) / a = 21
-    # at a = 0.05, so up to 21 * 2^-8 = 8e-2 in the worst direction (measured: 1e-2 to 3e-2).
-    assert err <= (5e-2 if rule else TOL_BF16), err
+    # The sketched keys S k_t are an intermediate tensor of the bf16 path, stored in bf16. Solve and readout both work
+    # on those stored keys (the readout runs in the sketched space), so the output is the exact layer of slightly
+    # perturbed keys and stays inside the forward tolerance, also with the rule's kappa = (1 + a) / a = 21.
+    assert err <= TOL_BF16, err
 
 
 def test_identity_sketch_matches_the_unsketched_forward():
