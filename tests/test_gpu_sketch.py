@@ -57,3 +57,33 @@ def test_identity_sketch_matches_the_unsketched_forward():
     plain = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter)
     torch.cuda.synchronize()
     assert pair_rel_err(to_host(out), to_host(plain).astype(np.float64)) <= TOL_BF16
+
+
+@pytest.mark.parametrize("i", range(8))
+def test_sketched_forward_random_shapes(i):
+    """Odd shapes: single tokens, partial chunks, one head, sketch dimensions from 1 to 64."""
+    import torch
+    rng = np.random.default_rng(5000 + i)
+    B, H = int(rng.integers(1, 4)), int(rng.integers(1, 6))
+    T = int(rng.choice([1, 2, 63, 64, 65, 129, 300, 700]))
+    d = int(rng.choice([64, 128]))
+    d_s = int(rng.choice([1, 5, 16, 31, 32, 33, 64]))
+    rule = bool(rng.integers(0, 2))
+    per_head = bool(rng.integers(0, 2))
+    with_beta = bool(rng.integers(0, 2))
+    w = synth.CFG2.scaled(B=B, H=H, T=T, d=d, n_iter=int(rng.integers(0, 12)), seed=5100 + i)
+    x = synth.make_inputs(w)
+    S = _sketch(rng, (H, d_s, d) if per_head else (d_s, d))
+    beta = synth.make_gates(w)["beta"] if with_beta else None
+    a = 0.05 if rule else 0.0
+    dev = upload_inputs(x, w.dtype)
+    out = binding.gka_forward_sketched(dev["q"], dev["k"], dev["v"], dev["gate"], None if rule else dev["lam"],
+                                       to_device(S, "f32"), w.n_iter, lambda_scale=a,
+                                       beta=None if beta is None else to_device(beta, "f32"))
+    torch.cuda.synchronize()
+    ref = sk.forward_sketched(x["q"], x["k"], x["v"], x["gate"], None if rule else x["lam"], S, w.n_iter, beta=beta,
+                              lambda_scale=a)
+    err = pair_rel_err(to_host(out), ref)
+    print("sketch random", i, dict(B=B, H=H, T=T, d=d, d_s=d_s, rule=rule, per_head=per_head, beta=with_beta,
+                                   n_iter=w.n_iter), err)
+    assert err <= TOL_BF16, err
