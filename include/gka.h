@@ -214,7 +214,8 @@ gka_status gka_backward(const gka_params *p,
  * (L = ||S H_t S^T||_F + lambda_t, mu = lambda_t; lambda NULL: lambda_t = p->lambda_scale ||S H_t S^T||_F). The paper
  * gives no formulas for this variant; this is the reading the library and its test oracle share. U_t is the full
  * state of Eq. (CH); sketched keys are not renormalised.
- *   S        [d_s, d_k] float32 (one sketch for all heads) or, with sketch_per_head != 0, [H, d_s, d_k]; 1 <= d_s <= 64
+ *   S        [d_s, d_k] float32, 16-byte aligned (one sketch for all heads) or, with sketch_per_head != 0,
+ *            [H, d_s, d_k]; 1 <= d_s <= 64
  *   q, k, v, o, gate, lambda, p->beta: as in gka_forward; p->alpha must be NULL
  *   Supported: GKA_BF16 tensors with GKA_COMPUTE_BF16, packed layout, zero initial states (else GKA_ERR_UNSUPPORTED;
  *   d_s out of range: GKA_ERR_SHAPE).
