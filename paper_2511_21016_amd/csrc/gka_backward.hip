@@ -215,23 +215,35 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(BackwardGlueArgs a)
 }
 
 // One wave per (batch, head) pair: dgate_t = (sum_{s>=t} s_s) / gate_t, walking the sequence backwards 64 tokens at a
-// time.
+// time. A gate of 0 starts a new packed sequence (it wipes the state): everything after it sums to gamma dgamma = 0
+// exactly, so the sum restarts there instead of carrying that zero as rounding noise, G_t = s_t + w_t G_{t+1} with
+// w_t = 0 where gate_{t+1} = 0; the gradient at such a gate itself is reported as 0. Inside a block the affine maps
+// are composed by a Hillis-Steele scan over the lanes (lane 0 the latest token).
 __global__ __launch_bounds__(64) void bwd_gate_scan_kernel(BackwardGlueArgs a)
 {
     const int lane = threadIdx.x;
     const int64_t b = blockIdx.x / a.H, h = blockIdx.x - b * a.H;
     auto index = [&](int64_t t) { return (b * a.T + (t >= 0 ? t : 0)) * a.H + h; };
+    auto gate_at = [&](int64_t t) { return (t >= 0 && t < a.T) ? a.gate[index(t)] : 1.0f; };
     float carry = 0.0f;
     // the next block's values are read before this block's scan, so that the walk does not pay a memory round trip
     // per block
-    float sv_next = a.s[index(a.T - 1 - lane)], g_next = a.gate[index(a.T - 1 - lane)];
+    float sv_next = a.s[index(a.T - 1 - lane)], g_next = gate_at(a.T - 1 - lane), gn_next = gate_at(a.T - lane);
     for (int64_t t0 = a.T - 1; t0 >= 0; t0 -= 64) {
         const int64_t t = t0 - lane;                       // lane 0 takes the latest token of the block
-        const float sv = t >= 0 ? sv_next : 0.0f, gv = g_next;
+        float c = t >= 0 ? sv_next : 0.0f;
+        const float gv = g_next;
+        float w = (t >= 0 && gn_next > 0.0f) ? 1.0f : 0.0f; // does the sum of the later tokens reach this one?
         sv_next = a.s[index(t - 64)];
-        g_next = a.gate[index(t - 64)];
-        const float run = wave_inclusive_scan(sv, lane) + carry;
-        if (t >= 0) a.dgate[index(t)] = run / gv;
+        g_next = gate_at(t - 64);
+        gn_next = gate_at(t - 63);
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float cp = __shfl_up(c, off, 64), wp = __shfl_up(w, off, 64);
+            if (lane >= off) { c = c + w * cp; w = w * wp; }
+        }
+        const float run = c + w * carry;
+        if (t >= 0) a.dgate[index(t)] = gv > 0.0f ? run / gv : 0.0f;
         carry = lane_value(run, 63);
     }
 }
