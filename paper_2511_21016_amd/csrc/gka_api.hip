@@ -404,13 +404,14 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     // a forward pass with the roles given; alpha = zeros makes it the plain readout y_t = U_t q_t of the gated
     // recurrence U_t = gate_t U_{t-1} + beta_t v_t k_t^T (the solve is reduced to its starting point and discarded)
     auto fwd = [&](const void *qq, const void *kk, const void *vv, const float *gg, const float *beta,
-                   const float *alpha, int n_iter, void *out, float *xhat, float *fro_out = nullptr) {
+                   const float *alpha, int n_iter, void *out, float *xhat, float *fro_out = nullptr,
+                   bool solve_only = false) {
         gka_params pp = *p;                      // lambda (or its rule) as given: only the two solves use it
         pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat;
         pp.state_layout = GKA_STATE_FULL;
         const bool plain_readout = alpha == zeros;
         return forward_impl(&pp, qq, kk, vv, gg, lambda, out, nullptr, nullptr, nullptr, nullptr, fro_out, fws,
-                            bp.fwd_bytes, hip_stream, nullptr, plain_readout);
+                            bp.fwd_bytes, hip_stream, nullptr, plain_readout, solve_only);
     };
     auto glue = [&](int which) {
         return gka::launch_backward_glue(g, which, io_bf16, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
@@ -433,7 +434,8 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     g.natural_order = fused;
 #define GKA_TRY(expr) do { gka_status e_ = (expr); if (e_ != GKA_OK) return e_; } while (0)
     // the forward solve and output; then x, xt in the tensors' dtype, the all-zero alpha and the reversed gates
-    GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf, rule ? fro : nullptr));
+    // (with the fused readouts y is read out again below, and the solves run without U states and readout)
+    GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf, rule ? fro : nullptr, fused));
     GKA_TRY(glue(0));
     // y_t again, from the stored xt (see the combine kernel)
     if (fused) GKA_TRY(readout(io(IO_XT), k, v, p->beta, false, io(IO_Y)));
@@ -442,7 +444,7 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     else GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
     GKA_TRY(glue(1));
     // p_t = CH(H_t + lambda_t I, alpha_t dxt_t, r)
-    GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32));
+    GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32, nullptr, fused));
     // H_t x_t
     if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, io(IO_HX)));
     else GKA_TRY(fwd(io(IO_X), k, k, gate, p->beta, zeros, 0, io(IO_HX), nullptr));
