@@ -322,7 +322,7 @@ void plan_readout_segments(int n_pairs, int n_chunks, int *n_segs, int *seg_len)
 
 struct BackwardPlan {
     size_t n_elems, n_tokens, esz;
-    size_t off_f32[2];        // xhat, p
+    size_t off_f32[7];        // xhat, p; with the fused readouts also y, H x, A k, A^T k, Ubar k in float32        // xhat, p
     size_t off_io[20];
     size_t off_m[6];          // gate_rev, zeros, s, fro, c, C
     size_t off_fwd, fwd_bytes, total;
@@ -340,7 +340,7 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     bp->n_elems = bp->n_tokens * p->d_k;
     bp->esz = p->io_dtype == GKA_BF16 ? 2 : 4;
     size_t off = 0;
-    for (int i = 0; i < 2; ++i) { bp->off_f32[i] = off; off = align_up(off + bp->n_elems * 4, 256); }
+    for (int i = 0; i < 7; ++i) { bp->off_f32[i] = off; off = align_up(off + bp->n_elems * 4, 256); }
     for (int i = 0; i < 20; ++i) { bp->off_io[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
     for (int i = 0; i < 6; ++i) { bp->off_m[i] = off; off = align_up(off + bp->n_tokens * 4, 256); }
     bp->off_fwd = off;
@@ -381,6 +381,7 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     unsigned char *ws = (unsigned char *)workspace;
     auto io = [&](int i) { return (void *)(ws + bp.off_io[i]); };
     float *xf = (float *)(ws + bp.off_f32[0]), *pf32 = (float *)(ws + bp.off_f32[1]);
+    auto f32buf = [&](int i) { return (float *)(ws + bp.off_f32[i]); };
     float *gate_rev = (float *)(ws + bp.off_m[0]), *zeros = (float *)(ws + bp.off_m[1]), *sbuf = (float *)(ws + bp.off_m[2]);
     float *fro = (float *)(ws + bp.off_m[3]), *cbuf = (float *)(ws + bp.off_m[4]), *Cbuf = (float *)(ws + bp.off_m[5]);
     void *fws = ws + bp.off_fwd;
@@ -419,50 +420,57 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     // the plain readout y_t = U_t qq_t, U_t = gate_t U_{t-1} + beta_t vv_t kk_t^T, in one kernel with the state in
     // registers (bf16 tensors and operands); `reverse`: the recurrence runs from the last token to the first
     const bool fused = io_bf16 && p->compute == GKA_COMPUTE_BF16;
-    auto readout = [&](const void *qq, const void *kk, const void *vv, const float *beta, bool reverse, void *out) {
+    // out_f32: the output in float32 (the pieces of the gate gradient's sum), else in the tensors' dtype
+    auto readout = [&](const void *qq, const void *kk, const void *vv, const float *beta, bool reverse, void *out,
+                       int seg_mode = 0, float *out_f32 = nullptr) {
         gka::ReadoutArgs r;
-        r.q = qq; r.q_lo = nullptr; r.q_is_f32 = false; r.k = kk; r.v = vv; r.o = out; r.gate = gate; r.beta = beta;
+        r.q = qq; r.q_lo = nullptr; r.q_is_f32 = false; r.k = kk; r.v = vv; r.o = out; r.o_f32 = out_f32;
+        r.gate = gate; r.beta = beta;
         r.stride_h = p->d_k; r.stride_t = (int64_t)p->H * p->d_k; r.stride_b = (int64_t)p->T * p->H * p->d_k;
         r.qk_stride_h = r.stride_h; r.qk_stride_t = r.stride_t; r.qk_stride_b = r.stride_b;
         r.H = p->H; r.T = p->T; r.n_pairs = p->B * p->H;
         plan_readout_segments(r.n_pairs, (p->T + gka::kChunk - 1) / gka::kChunk, &r.n_segs, &r.seg_len);
         r.seg_buf = (float *)fws;
         r.seg_logdecay = r.seg_buf + (size_t)r.n_pairs * r.n_segs * p->d_k * p->d_v;
-        r.reverse = reverse;
+        r.reverse = reverse; r.seg_mode = seg_mode;
         return gka::launch_gla_readout(r, p->d_k, p->d_v, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
     };
     g.natural_order = fused;
+    if (fused) {                                  // these five arrive in float32 (see the combine kernel)
+        g.y_io = f32buf(2); g.hx_io = f32buf(3); g.r1 = f32buf(4); g.r2 = f32buf(5); g.r4 = f32buf(6);
+    }
 #define GKA_TRY(expr) do { gka_status e_ = (expr); if (e_ != GKA_OK) return e_; } while (0)
     // the forward solve and output; then x, xt in the tensors' dtype, the all-zero alpha and the reversed gates
     // (with the fused readouts y is read out again below, and the solves run without U states and readout)
     GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf, rule ? fro : nullptr, fused));
     GKA_TRY(glue(0));
     // y_t again, from the stored xt (see the combine kernel)
-    if (fused) GKA_TRY(readout(io(IO_XT), k, v, p->beta, false, io(IO_Y)));
+    if (fused) GKA_TRY(readout(io(IO_XT), k, v, p->beta, false, nullptr, 0, f32buf(2)));
     // dxt_t = U_t^T dy_t: the recurrence with the roles of k and v exchanged, read out with dy
-    if (fused) GKA_TRY(readout(dy, v, k, p->beta, false, io(IO_DXT)));
+    // (its state is the transpose of the one just read out: the segment summaries are reused)
+    if (fused) GKA_TRY(readout(dy, v, k, p->beta, false, io(IO_DXT), 2));
     else GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
     GKA_TRY(glue(1));
     // p_t = CH(H_t + lambda_t I, alpha_t dxt_t, r)
     GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32, nullptr, fused));
     // H_t x_t
-    if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, io(IO_HX)));
+    if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, nullptr, 0, f32buf(3)));
     else GKA_TRY(fwd(io(IO_X), k, k, gate, p->beta, zeros, 0, io(IO_HX), nullptr));
     // the rule's extra gradient -c_t H_t at every state: c_t, C_t = sum_{s>=t} M[t,s]^2 c_s, and H_t k_t
     if (rule) {
         GKA_TRY(glue(5));
         GKA_TRY(glue(6));
-        if (fused) GKA_TRY(readout(k, k, k, p->beta, false, io(IO_HK)));
+        if (fused) GKA_TRY(readout(k, k, k, p->beta, false, io(IO_HK), 1));
         else GKA_TRY(fwd(k, k, k, gate, p->beta, zeros, 0, io(IO_HK), nullptr));
     }
     // reverse recurrences: A_t k_t, A_t^T k_t, Ubar_t^T v_t, Ubar_t k_t (no write gate inside them)
     GKA_TRY(glue(2));
     if (fused) {
         if (rule) GKA_TRY(readout(k, k, io(IO_VPR), nullptr, true, io(IO_R5)));
-        GKA_TRY(readout(k, io(IO_X), io(IO_PR), nullptr, true, io(IO_R1)));
-        GKA_TRY(readout(k, io(IO_PR), io(IO_X), nullptr, true, io(IO_R2)));
+        GKA_TRY(readout(k, io(IO_X), io(IO_PR), nullptr, true, nullptr, 0, f32buf(4)));
+        GKA_TRY(readout(k, io(IO_PR), io(IO_X), nullptr, true, nullptr, 2, f32buf(5)));
         GKA_TRY(readout(v, dy, io(IO_XT), nullptr, true, io(IO_R3)));
-        GKA_TRY(readout(k, io(IO_XT), dy, nullptr, true, io(IO_R4)));
+        GKA_TRY(readout(k, io(IO_XT), dy, nullptr, true, nullptr, 2, f32buf(6)));
     } else {
         if (rule) GKA_TRY(fwd(io(IO_KR), io(IO_KR), io(IO_VPR), gate_rev, nullptr, zeros, 0, io(IO_R5), nullptr));
         GKA_TRY(fwd(io(IO_KR), io(IO_XR), io(IO_PR), gate_rev, nullptr, zeros, 0, io(IO_R1), nullptr));
@@ -552,12 +560,12 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
                       nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr, false, true);
     if (st != GKA_OK) return st;
     gka::ReadoutArgs r;
-    r.v = v; r.o = o; r.gate = gate; r.beta = p->beta;
+    r.v = v; r.o = o; r.o_f32 = nullptr; r.gate = gate; r.beta = p->beta;
     r.stride_h = p->d_v; r.stride_t = (int64_t)p->H * p->d_v; r.stride_b = (int64_t)p->T * p->H * p->d_v;
     r.H = p->H; r.T = p->T; r.n_pairs = n_pairs;
     r.n_segs = sp.rs_n; r.seg_len = sp.rs_len;
     r.seg_buf = (float *)(ws + sp.off_fwd);
-    r.reverse = false;
+    r.reverse = false; r.seg_mode = 0;
     if (p->d_v == 128) {
         // y_t = U_t S^T z_t = (sum_i eta_{t,i} beta_i v_i (S k_i)^T) z_t: the readout runs in the sketched space, on the
         // stored sketched keys and the float32 z_t (split into value + remainder inside the kernel), with a d_v x 64

@@ -170,8 +170,12 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(BackwardGlueArgs a)
     const float Ct = rule ? a.C[tok] : 0.0f;
     const f32x4 x = load_f32x4(a.x_f32, i), p = load_f32x4(a.p_f32, i);
     const f32x4 q = IO::load4(a.q, i), k = IO::load4(a.k, i), v = IO::load4(a.v, i), dy = IO::load4(a.dy, i);
-    const f32x4 dxt = IO::load4(a.dxt_io, i), y = IO::load4(a.y_io, i), hx = IO::load4(a.hx_io, i);
-    const f32x4 a1 = IO::load4(a.r1, ri), a2 = IO::load4(a.r2, ri), u1 = IO::load4(a.r3, ri), d4 = IO::load4(a.r4, ri);
+    // with the fused readouts (natural_order) the pieces of the gate gradient's sum arrive in float32
+    auto piece = [&](const void *ptr, int64_t idx) {
+        return a.natural_order ? load_f32x4((const float *)ptr, idx) : IO::load4(ptr, idx);
+    };
+    const f32x4 dxt = IO::load4(a.dxt_io, i), y = piece(a.y_io, i), hx = piece(a.hx_io, i);
+    const f32x4 a1 = piece(a.r1, ri), a2 = piece(a.r2, ri), u1 = IO::load4(a.r3, ri), d4 = piece(a.r4, ri);
     f32x4 hk = {0.0f, 0.0f, 0.0f, 0.0f}, r5 = hk;
     float kk = 0.0f;                             // k_t . k_t (the rule's diagonal term)
     if (rule) {

@@ -85,7 +85,8 @@ struct BackwardGlueArgs {
     float *c, *C;                 // c_t and C_t = sum_{s>=t} M[t,s]^2 c_s
     void *vp_rev;                 // time-reversed beta_t C_t k_t
     bool natural_order;           // the reversed passes read and write the tensors in place (gla_readout `reverse`):
-                                  // nothing is reversed here, p_rev and vp_rev are plain conversions
+                                  // nothing is reversed here, p_rev and vp_rev are plain conversions, and y_io, hx_io,
+                                  // r1, r2, r4 are float32
     const void *hk_io, *r5;       // H_t k_t; reversed pass sum_{j>=t} M[t,j] beta_j C_j k_j (k_j . k_t)
 };
 // which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan, 5 rule scalars (c_t), 6 rule scan (C_t)
@@ -99,6 +100,7 @@ struct ReadoutArgs {
     const void *q_lo;             // optional bf16 remainder of q (y_t = U_t (q_t + q_lo_t)), or nullptr
     bool q_is_f32;                // q is float32 (split into value + remainder inside); dk = 64, dv = 128 only
     void *o;                      // [B,T,H,dv]
+    float *o_f32;                 // if not nullptr the output goes here in float32 instead (same strides)
     const float *gate, *beta;     // [B,T,H]; beta nullptr (= 1)
     int64_t stride_b, stride_t, stride_h;            // element strides of v and o
     int64_t qk_stride_b, qk_stride_t, qk_stride_h;   // ... of q (q_lo) and k
@@ -107,6 +109,9 @@ struct ReadoutArgs {
     int n_segs, seg_len;          // segments of the chunk scan per pair, chunks per segment
     float *seg_buf;               // [pairs, n_segs, dv*dk] segment summaries
     float *seg_logdecay;          // [pairs, n_segs]
+    int seg_mode;                 // 0: the summaries are computed by this call; 1: they are in seg_buf already (the call
+                                  // before had the same k, v, gate, beta, direction); 2: likewise, with k and v exchanged
+                                  // (the transposed state; dk = dv only)
     bool reverse;
 };
 hipError_t launch_gla_readout(const ReadoutArgs &a, int dk, int dv, hipStream_t stream);

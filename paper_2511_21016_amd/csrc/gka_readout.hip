@@ -40,7 +40,10 @@ struct ReadoutShape {
     static constexpr size_t q_elems = (size_t)kChunk * RSQ;
     static constexpr size_t k_elems = (size_t)kChunk * RSK;
     static constexpr size_t v_elems = (size_t)kChunk * RSV;
-    static constexpr size_t p_frags = 3 * 2 * 64;  // masked P: three causal 32x32 tiles, two MFMA steps each
+    // masked P: three causal 32x32 tiles, two MFMA steps each; square states (the backward pass's recurrences) keep
+    // the rounding remainder of P as a second set of fragments
+    static constexpr bool kPrecise = DK == DV;
+    static constexpr size_t p_frags = 3 * 2 * 64 * (kPrecise ? 2 : 1);
     static constexpr size_t tab_bytes = 3 * kChunk * sizeof(float);   // per-token G, state weight, beta of the chunk
     static constexpr size_t lds_bytes = (q_elems + k_elems + v_elems) * 2 + p_frags * sizeof(frag) + tab_bytes;
     static constexpr size_t lds_bytes_qlo = lds_bytes + q_elems * 2;   // with the remainder of q as a second tile
@@ -76,6 +79,10 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 {
     typedef ReadoutShape<DK, DV> SH;
     constexpr bool QLO = QMODE != 0, QF32 = QMODE == 2;
+    // PRECISE: P and the weighted v rows enter their products as value + remainder, so that the outputs carry the
+    // rounding of the tensors they are given and nothing else of that size: the gate gradient of the backward pass is
+    // a long cumulative sum of differences of such outputs, and only errors common to all of them cancel in it
+    constexpr bool PRECISE = SH::kPrecise;
     constexpr int NB = SH::NB, NBK = SH::NBK, NT = SH::NT, RSQ = SH::RSQ, RSK = SH::RSK, RSV = SH::RSV;
     constexpr int PK = SH::PK, PV = SH::PV, PQ = QF32 ? SH::PQ32 : SH::PK;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -114,10 +121,20 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         acc[jb] = zero16();
         if (!SUMMARY) {
             for (int sg = 0; sg < seg; ++sg) {
-                const float *t = summary_tile<DK, DV>(a, pair, sg, w, jb);
                 const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
+                if (DK == DV && a.seg_mode == 2) {
+                    // summaries of the transposed recurrence (k and v exchanged), left by the readout before this one:
+                    // U[32w + n][32jb + kidx(r, g)] is its element [32jb + kidx(r, g)][32w + n], i.e. tile (jb, w),
+                    // lane (kidx(r, g), g'), register r' with kidx(r', g') = n
+                    const float *t = summary_tile<DK, DV>(a, pair, sg, jb, w);
+                    const int gp = (n >> 2) & 1, rp = 4 * (n >> 3) + (n & 3);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[jb][r] = decay * acc[jb][r] + t[r * 64 + lane];
+                    for (int r = 0; r < 16; ++r) acc[jb][r] = decay * acc[jb][r] + t[rp * 64 + 32 * gp + kidx(r, g)];
+                } else {
+                    const float *t = summary_tile<DK, DV>(a, pair, sg, w, jb);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[jb][r] = decay * acc[jb][r] + t[r * 64 + lane];
+                }
             }
         }
     }
@@ -254,8 +271,18 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                         pm[4 * q4 + e] = (s0 + e <= 32 * tb + n) ? pacc[4 * q4 + e] * m : 0.0f;
                     }
                 }
-                sP[(tile * 2 + 0) * 64 + lane] = MMA::pack(pm);
-                sP[(tile * 2 + 1) * 64 + lane] = MMA::pack(pm + 8);
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    const frag hi = MMA::pack(pm + 8 * h2);
+                    sP[(tile * 2 + h2) * 64 + lane] = hi;
+                    if (PRECISE) {
+                        float back[8];
+                        MMA::unpack(hi, back);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) back[e] = pm[8 * h2 + e] - back[e];
+                        sP[(6 + tile * 2 + h2) * 64 + lane] = MMA::pack(back);
+                    }
+                }
             }
 
             // ---- zeta_t U_[n] q_t for both token blocks: the state's tiles are the A operand (value + remainder)
@@ -293,7 +320,10 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             for (int tile = 0; tile < 3; ++tile) {
                 const int sb = tile == 2 ? 1 : 0, tb = tile == 0 ? 0 : 1;
 #pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2) y[tb] = MMA::mma(vt[sb][h2], sP[(tile * 2 + h2) * 64 + lane], y[tb]);
+                for (int h2 = 0; h2 < 2; ++h2) {
+                    y[tb] = MMA::mma(vt[sb][h2], sP[(tile * 2 + h2) * 64 + lane], y[tb]);
+                    if (PRECISE) y[tb] = MMA::mma(vt[sb][h2], sP[(6 + tile * 2 + h2) * 64 + lane], y[tb]);
+                }
             }
             // ---- store: lane (n, g) holds features 32 w + kidx(r, g) of token 32 tb + n
 #pragma unroll
@@ -302,15 +332,20 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 if (tau < a.T) {
                     const int64_t off = base_v + (int64_t)tensor_token(tau) * a.stride_t + 32 * w + 4 * g;
 #pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4)
-                        IOBF16::store4(a.o, off + 8 * q4, y[tb][4 * q4], y[tb][4 * q4 + 1], y[tb][4 * q4 + 2],
-                                       y[tb][4 * q4 + 3]);
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        if (a.o_f32)
+                            *(f32x4 *)(a.o_f32 + off + 8 * q4) =
+                                f32x4{y[tb][4 * q4], y[tb][4 * q4 + 1], y[tb][4 * q4 + 2], y[tb][4 * q4 + 3]};
+                        else
+                            IOBF16::store4(a.o, off + 8 * q4, y[tb][4 * q4], y[tb][4 * q4 + 1], y[tb][4 * q4 + 2],
+                                           y[tb][4 * q4 + 3]);
+                    }
                 }
             }
         }
 
         // ---- U <- zeta_C U + sum_s w_s v_s k_s^T: tile jb gets K^T (block jb) times the weighted V^T fragments
-        frag vw[2][2];
+        frag vw[2][2], vwlo[2][2];
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -325,6 +360,13 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                     x[4 + e] *= w1[e];
                 }
                 vw[sb][h2] = MMA::pack(x);
+                if (PRECISE) {
+                    float back[8];
+                    MMA::unpack(vw[sb][h2], back);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) back[e] = x[e] - back[e];
+                    vwlo[sb][h2] = MMA::pack(back);
+                }
             }
 #pragma unroll
         for (int jb = 0; jb < NBK; ++jb) {
@@ -337,6 +379,7 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                     const int t0 = 32 * sb + 16 * h2 + 4 * g;
                     const frag kt = gather_transposed_bf16(sK, PaddedTile{RSK}, 32 * jb + sub16, lane, t0, t0 + 8);
                     acc[jb] = MMA::mma(kt, vw[sb][h2], acc[jb]);
+                    if (PRECISE) acc[jb] = MMA::mma(kt, vwlo[sb][h2], acc[jb]);
                 }
         }
     }
@@ -368,7 +411,7 @@ static hipError_t launch_readout_d(const ReadoutArgs &a0, hipStream_t stream)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    if (a.n_segs > 1) {
+    if (a.n_segs > 1 && a.seg_mode == 0) {
         // summaries of every segment but the last, each from a zero state
         hipLaunchKernelGGL((gla_readout_kernel<DK, DV, GATED, true, 0>), dim3(a.n_pairs * (a.n_segs - 1)), dim3(SH::NT),
                            SH::lds_bytes, stream, a);

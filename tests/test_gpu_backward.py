@@ -106,9 +106,9 @@ def test_backward_over_several_segments(dtype, d, rule, gate_mean):
     torch.cuda.synchronize()
     ref = bwd.backward(x["q"], x["k"], x["v"], x["gate"], None if rule else x["lam"], dy, w.n_iter, lambda_scale=a,
                        beta=gates["beta"], alpha=gates["alpha"])
-    # bf16 tensors: the gate gradient is a reverse cumulative sum of differences of bf16-rounded pieces, whose
-    # errors add up along the 1100 tokens (6 % here against 3-5 % at 150 tokens); float32 tensors show the logic
-    tol = 2e-4 if dtype == "f32" else 1e-1
+    # bf16 tensors: measured 1-3 % on dq, dk, dv, below 2 % on the gate gradient (a reverse cumulative sum over 1100
+    # tokens, whose pieces the readouts form with value + remainder operands); float32 tensors show the logic
+    tol = 2e-4 if dtype == "f32" else 6e-2
     names = ["dq", "dk", "dv", "dgate", "dbeta", "dalpha"] + ([] if rule else ["dlam"])
     errs = {n: _rel(to_host(out[n]), ref[n]) for n in names}
     print("segments", dtype, d, rule, errs)

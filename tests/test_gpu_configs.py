@@ -184,10 +184,11 @@ def test_cfg2_backward_and_sketch_full_size_sampled():
                                 w.n_iter)
         errs = {n: float(np.abs(sel(got[n]) - ref[n]).max() / np.abs(ref[n]).max()) for n in got}
         print("cfg2 backward pair", b, h, errs)
-        # bf16 tensors (see tests/test_gpu_backward.py): the gate gradient's cumulative sum and dlam carry the largest
-        # rounding errors
+        # bf16 tensors (see tests/test_gpu_backward.py): dlam = -xhat . p carries the largest rounding error; the gate
+        # gradient, a cumulative sum over the rest of the sequence, stays below 1 % here because its pieces are
+        # formed with value + remainder operands and handed over in float32
         assert max(errs[n] for n in ("dq", "dk", "dv")) <= 6e-2, errs
-        assert errs["dgate"] <= 1e-1 and errs["dlam"] <= 2e-1, errs
+        assert errs["dgate"] <= 3e-2 and errs["dlam"] <= 2e-1, errs
         yref = sk.forward_sketched_pair(sel(x["q"]), sel(x["k"]), sel(x["v"]), sel(x["gate"]), sel(x["lam"]), S[h],
                                         w.n_iter)
         es = float(np.abs(sel(ys) - yref).max() / np.abs(yref).max())
