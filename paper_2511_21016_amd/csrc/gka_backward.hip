@@ -241,12 +241,17 @@ __global__ __launch_bounds__(64) void bwd_gate_scan_kernel(BackwardGlueArgs a)
         sv_next = a.s[index(t - 64)];
         g_next = gate_at(t - 64);
         gn_next = gate_at(t - 63);
+        float run;
+        if (__ballot(t >= 0 && w == 0.0f) == 0) {          // (wave-uniform) no restart in this block: a plain prefix sum
+            run = wave_inclusive_scan(c, lane) + carry;
+        } else {
 #pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const float cp = __shfl_up(c, off, 64), wp = __shfl_up(w, off, 64);
-            if (lane >= off) { c = c + w * cp; w = w * wp; }
+            for (int off = 1; off < 64; off <<= 1) {
+                const float cp = __shfl_up(c, off, 64), wp = __shfl_up(w, off, 64);
+                if (lane >= off) { c = c + w * cp; w = w * wp; }
+            }
+            run = c + w * carry;
         }
-        const float run = c + w * carry;
         if (t >= 0) a.dgate[index(t)] = gv > 0.0f ? run / gv : 0.0f;
         carry = lane_value(run, 63);
     }
