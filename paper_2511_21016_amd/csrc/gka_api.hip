@@ -322,7 +322,7 @@ void plan_readout_segments(int n_pairs, int n_chunks, int *n_segs, int *seg_len)
 
 struct BackwardPlan {
     size_t n_elems, n_tokens, esz;
-    size_t off_f32[7];        // xhat, p; with the fused readouts also y, H x, A k, A^T k, Ubar k in float32        // xhat, p
+    size_t off_f32[7];        // xhat, p; with the fused readouts also y, H x, A k, A^T k, Ubar k in float32
     size_t off_io[20];
     size_t off_m[6];          // gate_rev, zeros, s, fro, c, C
     size_t off_fwd, fwd_bytes, total;
