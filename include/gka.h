@@ -185,9 +185,9 @@ gka_status gka_decode_tokens(const gka_params *p,
  * r passes of Algorithm 1 (dq_t = CH(H_t + lambda_t I, dxhat_t, r)), as in the paper. The two solves run on the
  * forward kernels; the reverse recurrences of Section 4.2.2 are six gated-linear-attention readouts (seven on bf16
  * tensors, where the output is read out again from the stored operand for the gate gradient), four of them
- * walking the sequence backwards (one kernel with the state in registers for GKA_COMPUTE_BF16, the forward kernels
- * on reversed copies for GKA_COMPUTE_F32), plus a few elementwise kernels: about five times the cost of gka_forward
- * with bf16 operands; the paper's chunk-wise backward kernels are not reproduced.
+ * walking the sequence backwards (one kernel with the state in registers for GKA_BF16 tensors, the forward kernels
+ * on reversed copies for GKA_F32 tensors), plus a few elementwise kernels: about five times the cost of gka_forward
+ * with bf16 tensors and operands; the paper's chunk-wise backward kernels are not reproduced.
  *   Supported: lambda given or NULL with p->lambda_scale > 0 (the rule lambda_t = a ||H_t||_F, whose w_t H_t terms
  *   of the Lemma in Section 4.2.2 cost two more readouts), zero initial states, packed tensors (explicit strides:
  *   GKA_ERR_UNSUPPORTED), p->beta and p->alpha as in gka_forward. Packed sequences (a gate of 0 at a sequence's first token) are handled:

@@ -418,8 +418,9 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
         return gka::launch_backward_glue(g, which, io_bf16, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
     };
     // the plain readout y_t = U_t qq_t, U_t = gate_t U_{t-1} + beta_t vv_t kk_t^T, in one kernel with the state in
-    // registers (bf16 tensors and operands); `reverse`: the recurrence runs from the last token to the first
-    const bool fused = io_bf16 && p->compute == GKA_COMPUTE_BF16;
+    // registers (bf16 tensors); `reverse`: the recurrence runs from the last token to the first
+    // (bf16 tensors: whatever operands the two solves use, the readouts take the stored bf16 tensors as they are)
+    const bool fused = io_bf16;
     // out_f32: the output in float32 (the pieces of the gate gradient's sum), else in the tensors' dtype
     auto readout = [&](const void *qq, const void *kk, const void *vv, const float *beta, bool reverse, void *out,
                        int seg_mode = 0, float *out_f32 = nullptr) {

@@ -2,8 +2,8 @@
 // parts of the backward pass run elsewhere: two solves on the forward kernels (the forward solve for xhat_t and the
 // solve of the incoming gradient, dq_t = CH(H_t + lambda_t I, dxhat_t, r)) and the gated-linear-attention readouts,
 // four of them walking the sequence backwards, which are the reverse recurrences of Section 4.2.2 (Eq. (Ai) and the
-// like for U): one kernel with the state in registers for bf16 operands, the forward kernels on time-reversed
-// copies for float32 operands. What remains is here: mixing, conversions, the time reversal (for the latter path),
+// like for U): one kernel with the state in registers for bf16 tensors, the forward kernels on time-reversed
+// copies for float32 tensors. What remains is here: mixing, conversions, the time reversal (for the latter path),
 // the per-token combination of the pieces and the reverse cumulative sum that gives the gradient of the gates.
 //
 // All tensors are packed: [B,T,H,d] for vectors, [B,T,H] for scalars.

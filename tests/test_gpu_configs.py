@@ -196,30 +196,27 @@ def test_cfg2_backward_and_sketch_full_size_sampled():
         assert es <= TOL_BF16, es
 
 
-def test_cfg3_shape_backward_two_paths_agree():
-    """A long sequence (configuration 3's shape, 8 heads of it: T = 32768, 512 chunks per pair, 64 scan segments in
-    the readouts) is beyond what the numpy backward oracle follows in reasonable time; here the two GPU paths check
-    each other: bf16 operands (fused readouts, sequences walked backwards in place) against float32 operands
-    (composition of the forward kernels on reversed copies), same bf16 tensors. The float32-operand path is the one
-    whose parity with the oracle is at rounding level on small cases."""
+@pytest.mark.parametrize("compute", ["bf16", "f32"])
+def test_cfg3_shape_backward_long_sequence(compute):
+    """A long sequence (configuration 3's shape with two heads: T = 32768, 512 chunks per pair, 256 scan segments in
+    the readouts) against the backward oracle on one pair (the oracle keeps every state of that pair: 8.6 GB, 10 s).
+    The gate gradient is a cumulative sum over up to 32768 tokens: it stays near 1 % because the pieces of the sum
+    are formed from the stored tensors with value + remainder operands and handed over in float32."""
     import torch
-    w = synth.CFG3.scaled(H=8, seed=31)
+    from oracle import gka_backward_oracle as bwd
+    w = synth.CFG3.scaled(H=2, seed=31)
     x = synth.make_inputs(w)
     rng = np.random.default_rng(5)
     dy = synth.round_to_bf16(rng.standard_normal(x["v"].shape).astype(np.float32))
     dev = upload_inputs(x, w.dtype)
-    dyd = to_device(dy, "bf16")
-    a = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], dyd, w.n_iter,
-                             compute=binding.GKA_COMPUTE_BF16)
-    b = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], dyd, w.n_iter,
-                             compute=binding.GKA_COMPUTE_F32)
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    out = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], to_device(dy, "bf16"), w.n_iter,
+                               compute=cm)
     torch.cuda.synchronize()
-    errs = {}
-    for n in ("dq", "dk", "dv", "dgate", "dlam"):
-        ga, gb = to_host(a[n]).astype(np.float64), to_host(b[n]).astype(np.float64)
-        axes = (1, 3) if ga.ndim == 4 else (1,)
-        errs[n] = float((np.abs(ga - gb).max(axis=axes) / np.abs(gb).max(axis=axes)).max())
-        assert np.isfinite(ga).all() and np.isfinite(gb).all()
-    print("cfg3-shape backward, bf16 vs float32 operands:", errs)
+    sel = lambda a: a[0, :, 1]
+    ref = bwd.backward_pair(sel(x["q"]), sel(x["k"]), sel(x["v"]), sel(x["gate"]), sel(x["lam"]), sel(dy), w.n_iter)
+    errs = {n: float(np.abs(sel(to_host(out[n])) - ref[n]).max() / np.abs(ref[n]).max())
+            for n in ("dq", "dk", "dv", "dgate", "dlam")}
+    print("cfg3-shape backward,", compute, "operands:", errs)
     assert max(errs[n] for n in ("dq", "dk", "dv")) <= 6e-2, errs
-    assert errs["dgate"] <= 1.5e-1 and errs["dlam"] <= 2e-1, errs
+    assert errs["dgate"] <= 3e-2 and errs["dlam"] <= 1e-1, errs
