@@ -170,7 +170,9 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(BackwardGlueArgs a)
     const bool rule = a.rule_a > 0.0f;
     const float Ct = rule ? a.C[tok] : 0.0f;
     const f32x4 x = load_f32x4(a.x_f32, i), p = load_f32x4(a.p_f32, i);
-    const f32x4 q = IO::load4(a.q, i), k = IO::load4(a.k, i), v = IO::load4(a.v, i), dy = IO::load4(a.dy, i);
+    f32x4 q = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (a.dalpha) q = IO::load4(a.q, i);         // q enters dalpha only
+    const f32x4 k = IO::load4(a.k, i), v = IO::load4(a.v, i), dy = IO::load4(a.dy, i);
     // with the fused readouts (natural_order) the pieces of the gate gradient's sum arrive in float32
     auto piece = [&](const void *ptr, int64_t idx) {
         return a.natural_order ? load_f32x4((const float *)ptr, idx) : IO::load4(ptr, idx);
