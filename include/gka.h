@@ -72,6 +72,15 @@ typedef enum { GKA_PHASE_ALL = 0, GKA_PHASE_STATES = 1, GKA_PHASE_SOLVE = 2 } gk
  *                           is valid under either layout). U states are not symmetric and are always full. */
 typedef enum { GKA_STATE_FULL = 0, GKA_STATE_H_LOWER_BLOCKS = 1 } gka_state_layout;
 
+/* Which kernels gka_forward runs.
+ * GKA_PATH_AUTO     : the library's choice (the fused kernel where it applies, else the two-phase kernels).
+ * GKA_PATH_TWO_PHASE: chunk initial states H_[n], U_[n] of Section 4.2.1 are computed and stored in the workspace
+ *                     first, then every chunk is solved independently (all dtypes, head dimensions and variants).
+ * GKA_PATH_FUSED    : one kernel walks the chunks of a pair in order with H and U in registers, so that no chunk state
+ *                     crosses HBM. Available for GKA_BF16 tensors with GKA_COMPUTE_BF16, d = 128, Eq. (CH) as printed
+ *                     (lambda given, no beta / alpha / xhat_out), GKA_PHASE_ALL; GKA_ERR_UNSUPPORTED otherwise. */
+typedef enum { GKA_PATH_AUTO = 0, GKA_PATH_TWO_PHASE = 1, GKA_PATH_FUSED = 2 } gka_path;
+
 typedef struct {
     int32_t B;            /* batch (gka_decode_step: number of sequences)                      */
     int32_t H;            /* heads                                                             */
@@ -103,6 +112,14 @@ typedef struct {
                           /*   (before the alpha-connection). With q := an incoming gradient this is the    */
                           /*   solve of the backward pass, CH(H_t + lambda_t I, dxhat_t, r) (Section 4.2.2). */
                           /*   Ignored by the decode entry points.                                          */
+    /* Launch plan of gka_forward (0 everywhere = the library's choices; results do not depend on these beyond
+     * rounding). They exist so that callers and tests can bound the workspace or force short walks. */
+    int64_t slab_state_bytes; /* two-phase kernels: bytes of chunk states one launch pair keeps in the workspace  */
+                              /*   (0 = 1 GiB); larger problems run as several launches, states carried in fp32   */
+    int32_t walk_chunks;      /* fused kernel: chunks one workgroup walks (rounded up to an even number); the     */
+                              /*   sequence is cut into such segments, whose start states come from a summary     */
+                              /*   launch. 0 = as few segments as fill the GPU                                    */
+    int32_t path;             /* gka_path                                                                         */
 } gka_params;
 
 /* Bytes of scratch gka_forward needs for these parameters (0 if they are invalid). The buffer must
@@ -110,8 +127,8 @@ typedef struct {
  * operand layout of the solve kernel, for one batch of (batch, head) pairs and one slab of consecutive
  * chunks at a time: large problems are processed as a sequence of such launches, the running states
  * carried from slab to slab in float32, so that the workspace stays bounded (about 1 GiB of chunk
- * states; the environment variable GKA_SLAB_STATE_BYTES, read by this query and by gka_forward,
- * overrides that budget). Its contents after a call are unspecified. */
+ * states; p->slab_state_bytes overrides that budget). The fused kernel (gka_path) needs only the segment summaries
+ * of its chunk walk; the query returns the larger of the two sizes. Its contents after a call are unspecified. */
 size_t gka_forward_workspace_bytes(const gka_params *p);
 
 /* Whole-sequence forward, Eq. (CH).

@@ -15,6 +15,7 @@ GKA_F32, GKA_BF16 = 0, 1
 GKA_COMPUTE_F32, GKA_COMPUTE_BF16 = 0, 1
 GKA_PHASE_ALL, GKA_PHASE_STATES, GKA_PHASE_SOLVE = 0, 1, 2
 GKA_STATE_FULL, GKA_STATE_H_LOWER_BLOCKS = 0, 1
+GKA_PATH_AUTO, GKA_PATH_TWO_PHASE, GKA_PATH_FUSED = 0, 1, 2
 
 EXPORTED_SYMBOLS = (
     "gka_forward_workspace_bytes",
@@ -40,6 +41,7 @@ class GkaParams(ctypes.Structure):
         ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
         ("lambda_scale", ctypes.c_float), ("state_layout", ctypes.c_int32),
         ("beta", ctypes.c_void_p), ("alpha", ctypes.c_void_p), ("xhat_out", ctypes.c_void_p),
+        ("slab_state_bytes", ctypes.c_int64), ("walk_chunks", ctypes.c_int32), ("path", ctypes.c_int32),
     ]
 
 
@@ -105,12 +107,14 @@ def version():
 
 
 def make_params(B, H, T, d, n_iter, io_dtype, compute, chunk=64, d_v=None, strides=(0, 0, 0), phase=0,
-                lambda_scale=0.0, beta=None, alpha=None, state_layout=0, xhat_out=None):
+                lambda_scale=0.0, beta=None, alpha=None, state_layout=0, xhat_out=None, slab_state_bytes=0,
+                walk_chunks=0, path=0):
     """beta, alpha, xhat_out: device addresses (ints) of the optional per-token gates / solve output, or None."""
     return GkaParams(B=B, H=H, T=T, d_k=d, d_v=d if d_v is None else d_v, chunk=chunk, n_iter=n_iter,
                      io_dtype=io_dtype, compute=compute, phase=phase,
                      stride_b=strides[0], stride_t=strides[1], stride_h=strides[2],
-                     lambda_scale=lambda_scale, state_layout=state_layout, beta=beta, alpha=alpha, xhat_out=xhat_out)
+                     lambda_scale=lambda_scale, state_layout=state_layout, beta=beta, alpha=alpha, xhat_out=xhat_out,
+                     slab_state_bytes=slab_state_bytes, walk_chunks=walk_chunks, path=path)
 
 
 def forward_workspace_bytes(params):
@@ -164,7 +168,8 @@ def _ptr(t):
 
 def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=None, U_init=None,
                 return_state=False, return_fro=False, workspace=None, out=None, phase=GKA_PHASE_ALL,
-                beta=None, alpha=None, lambda_scale=0.0, state_layout=GKA_STATE_FULL, return_xhat=False):
+                beta=None, alpha=None, lambda_scale=0.0, state_layout=GKA_STATE_FULL, return_xhat=False,
+                slab_state_bytes=0, walk_chunks=0, path=GKA_PATH_AUTO):
     """gka_forward on torch CUDA tensors: q, k, v [B,T,H,d] (float32 or bfloat16, contiguous),
     gate, lam [B,T,H] float32 (lam None: lambda_t = lambda_scale * ||H_t||_F); beta, alpha: optional [B,T,H]
     float32 write gate and alpha-connection; return_xhat: also the solve's result [B,T,H,d] float32. Enqueues on torch's current stream and returns o (and a dict of
@@ -179,7 +184,7 @@ def gka_forward(q, k, v, gate, lam, n_iter, *, compute=None, chunk=64, H_init=No
     xhat = torch.empty((B, T, H, d), dtype=torch.float32, device=q.device) if return_xhat else None
     params = make_params(B, H, T, d, n_iter, io, compute, chunk=chunk, d_v=v.shape[-1], phase=phase,
                          lambda_scale=lambda_scale, beta=_ptr(beta), alpha=_ptr(alpha), state_layout=state_layout,
-                         xhat_out=_ptr(xhat))
+                         xhat_out=_ptr(xhat), slab_state_bytes=slab_state_bytes, walk_chunks=walk_chunks, path=path)
     nbytes = forward_workspace_bytes(params)
     if nbytes == 0:
         # let the library name the error

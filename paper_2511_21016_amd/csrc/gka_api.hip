@@ -3,8 +3,6 @@
 #include "../../include/gka.h"
 #include "gka_kernels.hpp"
 
-#include <stdlib.h>
-
 #include <vector>
 
 namespace {
@@ -17,6 +15,8 @@ struct Plan {
     int n_segs, seg_len;
     int pairs_per_batch;          // (batch, head) pairs per launch
     int slab_chunks;              // chunks of every pair per launch
+    bool fused_shape;             // dtype, operands and head dimension of the fused kernel
+    int fused_n_segs, fused_seg_len;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -26,19 +26,11 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 #endif
 constexpr int kStateMinWorkgroups = GKA_STATE_MIN_WGS;   // two state-pass workgroups per CU
 constexpr int kStateMaxWalk = 64;          // chunks a state-pass workgroup walks before segments are added
-// Chunk states one launch pair keeps in the workspace. The environment variable GKA_SLAB_STATE_BYTES overrides the
-// default (tests use it to force several slabs on small problems).
+// Chunk states one launch pair keeps in the workspace unless gka_params::slab_state_bytes says otherwise (tests use
+// that to force several slabs on small problems).
 constexpr size_t kDefaultSlabStateBytes = (size_t)1 << 30;
-size_t slab_state_bytes()
-{
-    const char *e = getenv("GKA_SLAB_STATE_BYTES");
-    if (e && *e) {
-        char *end = nullptr;
-        const unsigned long long v = strtoull(e, &end, 10);
-        if (end != e && v > 0) return (size_t)v;
-    }
-    return kDefaultSlabStateBytes;
-}
+// Workgroups the fused kernel should at least have: one per compute unit.
+constexpr int kFusedMinWorkgroups = 256;
 constexpr size_t kMaxPairsPerBatch = 1024;
 constexpr size_t kMinSlabChunks = 4;
 
@@ -58,6 +50,8 @@ gka_status check_common(const gka_params *p, bool decode)
     if ((int64_t)p->B * p->H > (int64_t)1 << 24) return GKA_ERR_SHAPE;
     if (!(p->lambda_scale >= 0.0f)) return GKA_ERR_SHAPE;
     if (p->state_layout != GKA_STATE_FULL && p->state_layout != GKA_STATE_H_LOWER_BLOCKS) return GKA_ERR_UNSUPPORTED;
+    if (p->slab_state_bytes < 0 || p->walk_chunks < 0) return GKA_ERR_SHAPE;
+    if (p->path < GKA_PATH_AUTO || p->path > GKA_PATH_FUSED) return GKA_ERR_UNSUPPORTED;
     return GKA_OK;
 }
 
@@ -93,7 +87,8 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
     const size_t per_chunk = gka::ws_H_bytes_per_chunk(pl->d, pl->compute_bf16) +
                              gka::ws_U_bytes_per_chunk(pl->d, pl->compute_bf16);
     size_t ppb = pl->n_pairs < kMaxPairsPerBatch ? pl->n_pairs : kMaxPairsPerBatch;
-    size_t slab = slab_state_bytes() / (ppb * per_chunk);
+    const size_t budget = p->slab_state_bytes > 0 ? (size_t)p->slab_state_bytes : kDefaultSlabStateBytes;
+    size_t slab = budget / (ppb * per_chunk);
     if (slab < kMinSlabChunks) slab = kMinSlabChunks;
     if (slab > (size_t)pl->n_chunks) slab = pl->n_chunks;
     pl->pairs_per_batch = (int)ppb;
@@ -119,6 +114,27 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
     pl->off_carry = align_up(pl->off_segdecay + (size_t)pl->pairs_per_batch * pl->n_segs * sizeof(float), 256);
     // two ping-pong pairs of fp32 (H, U) carried from slab to slab
     pl->total = align_up(pl->off_carry + (size_t)4 * pl->pairs_per_batch * pl->d * pl->d * sizeof(float), 256);
+    // Fused kernel: one workgroup per (pair, segment of the chunk walk). As few segments as give every compute unit a
+    // workgroup (every segment but the last costs a second read of its k and v rows for the summary launch); an even
+    // number of chunks per segment, because a workgroup takes its chunks two at a time.
+    pl->fused_shape = pl->io_bf16 && pl->compute_bf16 && pl->d == 128 && !readout_only;
+    if (pl->fused_shape) {
+        int seg_len;
+        if (p->walk_chunks > 0) {
+            seg_len = p->walk_chunks;
+        } else {
+            int n_segs = (kFusedMinWorkgroups + pl->n_pairs - 1) / pl->n_pairs;
+            if (n_segs > pl->n_chunks / 2) n_segs = pl->n_chunks / 2;
+            if (n_segs < 1) n_segs = 1;
+            seg_len = (pl->n_chunks + n_segs - 1) / n_segs;
+        }
+        seg_len += seg_len & 1;
+        pl->fused_seg_len = seg_len;
+        pl->fused_n_segs = (pl->n_chunks + seg_len - 1) / seg_len;
+        if ((int64_t)pl->n_pairs * pl->fused_n_segs > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
+        const size_t fused = align_up(gka::fused_workspace_bytes(pl->n_pairs, pl->fused_n_segs), 256);
+        if (fused > pl->total) pl->total = fused;
+    }
     return GKA_OK;
 }
 
@@ -169,6 +185,26 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     if (!workspace || workspace_bytes < pl.total || ((uintptr_t)workspace & 255)) return GKA_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
+
+    const bool fused_ok = pl.fused_shape && !p->beta && !p->alpha && lambda && !p->xhat_out && !solve_only &&
+                          p->phase == GKA_PHASE_ALL;
+    if (p->path == GKA_PATH_FUSED && !fused_ok) return GKA_ERR_UNSUPPORTED;
+    if (fused_ok && p->path != GKA_PATH_TWO_PHASE) {
+        gka::FusedArgs fa;
+        fa.q = q; fa.k = k; fa.v = v; fa.gate = gate; fa.lambda = lambda; fa.o = o; fa.fro_out = fro_out;
+        fa.H_init = H_init; fa.U_init = U_init; fa.H_final = H_final; fa.U_final = U_final;
+        fa.h_init_lower_blocks = p->state_layout == GKA_STATE_H_LOWER_BLOCKS;
+        fa.stride_b = pl.stride_b; fa.stride_t = pl.stride_t; fa.stride_h = pl.stride_h;
+        fa.H = p->H; fa.T = p->T; fa.n_iter = p->n_iter;
+        fa.n_pairs = pl.n_pairs; fa.n_chunks = pl.n_chunks;
+        fa.n_segs = pl.fused_n_segs; fa.seg_len = pl.fused_seg_len;
+        fa.seg_buf = nullptr; fa.seg_logdecay = nullptr;
+        if (prof) prof->mark(stream);
+        if (prof) prof->mark(stream);
+        if (gka::launch_fused_forward(fa, ws, stream) != hipSuccess) return GKA_ERR_LAUNCH;
+        if (prof) prof->mark(stream);
+        return GKA_OK;
+    }
 
     gka::StatePassArgs sa;
     sa.k = k; sa.v = v; sa.gate = gate; sa.beta = p->beta;

@@ -1,0 +1,911 @@
+// Whole forward pass of Eq. (CH) in one kernel for bf16 tensors and operands at d = 128: a workgroup walks a run
+// of consecutive chunks of one (batch, head) pair with the states H and U in registers, so that no chunk state
+// crosses HBM (Section 4.2.1 computes the initial state of every chunk first and then treats the chunks
+// independently; here the state is advanced and used chunk by chunk instead).
+//
+// Tiles. Everything is built from the 16x16x32 bf16 MFMA. Lane l = 16 kg + n (n = 0..15, kg = 0..3) of a
+// 16 x 16 accumulator tile holds rows 4 kg + r (r = 0..3) of column n. An operand fragment holds, per lane (n, kg),
+// eight contraction values ("slots" p = 0..7) of row / column n. Two accumulator tiles (rows 16 a .., rows 16 b ..)
+// of the same columns convert in place into one B fragment whose slot p stands for row 16 (p < 4 ? a : b) + 4 kg +
+// p % 4; with a = 2 f, b = 2 f + 1 this is "fragment f" of a 128-vector: slot p <-> index 32 f + 16 (p / 4) + 4 kg +
+// p % 4. Every A operand enumerates its contraction index in the same slot order, so vectors go from accumulators
+// to operands without leaving their lanes.
+//
+// Roles. The workgroup has eight waves and handles two consecutive chunks (A, B) per iteration.
+//   * State role (all waves): wave w owns columns 16 w .. 16 w + 15 of H (as H[16 jt + row][16 w + n], eight tiles)
+//     and of U^T (U[16 w + n][16 jt + row]). It converts H to the bf16 A operand of the solve, advances H and U by a
+//     chunk (S <- zeta_C S + sum_j w_j k_j a_j^T, the weights on its own B fragments), and reads out
+//     zeta-free U_[n] xhat for all tokens of a chunk from its registers (rounded value + remainder of both operands).
+//   * Solver role: waves 0-3 take chunk A, waves 4-7 chunk B, each wave 16 tokens with all 128 features: chunk-wise
+//     Frobenius norm, all passes of Algorithm 1 and the intra-chunk part of the readout run without any
+//     barrier, the iterate never leaves the wave's registers.
+#include "gka_device.hpp"
+#include "gka_kernels.hpp"
+
+namespace gka {
+namespace {
+
+constexpr int kFusedThreads = 512;
+constexpr int kD = 128;
+
+// LDS map (bytes). Regions are reused along an iteration; see the phase list in fused_forward_kernel.
+constexpr int kOffH = 0;            // [2 chunks] 32 KiB: H_[n] as A fragments [ft 8][fb 4][64 lanes]
+                                    //   later: xhat as B fragments [ts 4][hi/lo 2][fb 4][64 lanes]
+constexpr int kOffK = 65536;        // [2] 16 KiB: key rows as A fragments [js 4][fb 4][64]
+                                    //   later (both halves): state part of the readout [ts 4][ft 8][64] float4
+constexpr int kOffKT = 98304;       // [2] 16 KiB: keys transposed as A fragments [ft 8][jb 2][64]
+constexpr int kOffR = 131072;       // [2] 16 KiB: row-major tile of k rows, later of v rows (64 x 256 B, swizzled)
+constexpr int kLdsBytes = 163840;
+// per-token scalars of the Frobenius phase and the partial norms of H_[n]: last KiB of the second row tile
+constexpr int kOffTab = kOffR + 2 * 16384 - 1024;
+
+typedef SwizzledRows<256, 2> Rows;
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+__device__ __forceinline__ f32x4 mma16(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 zero4() { return f32x4{0.0f, 0.0f, 0.0f, 0.0f}; }
+__device__ __forceinline__ bf16x8 pack8(f32x4 lo, f32x4 hi)
+{
+    bf16x8 f;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        f[p] = (__bf16)lo[p];
+        f[4 + p] = (__bf16)hi[p];
+    }
+    return f;
+}
+__device__ __forceinline__ void unpack8(bf16x8 f, f32x4 &lo, f32x4 &hi)
+{
+    float x[8];
+    MmaBF16::unpack(f, x);
+    lo = f32x4{x[0], x[1], x[2], x[3]};
+    hi = f32x4{x[4], x[5], x[6], x[7]};
+}
+// rounded value and what the rounding left over, both as fragments
+__device__ __forceinline__ void split8(f32x4 lo, f32x4 hi, bf16x8 &val, bf16x8 &rem)
+{
+    val = pack8(lo, hi);
+    f32x4 bl, bh;
+    unpack8(val, bl, bh);
+    rem = pack8(lo - bl, hi - bh);
+}
+__device__ __forceinline__ float sum_over_kg(float x)
+{
+    x += __shfl_xor(x, 16, 64);
+    x += __shfl_xor(x, 32, 64);
+    return x;
+}
+
+struct Ctx {
+    const FusedArgs &a;
+    unsigned char *smem;
+    int tid, lane, w, n, kg;
+    int64_t base_bh, gate_base;
+    int T_eff;                       // tokens at or beyond this index do not exist for this workgroup
+};
+
+__device__ __forceinline__ bf16x8 *lds_frags(const Ctx &c, int off) { return (bf16x8 *)(c.smem + off); }
+__device__ __forceinline__ uint16_t *lds_rows(const Ctx &c, int g) { return (uint16_t *)(c.smem + kOffR + g * 16384); }
+
+// Gates of one chunk: lane j holds G_j = sum_{i<=j} log2 gamma_i over the chunk (tokens that do not exist: gamma = 1).
+struct ChunkGates {
+    float G, Gtot;
+};
+__device__ __forceinline__ ChunkGates scan_gates(const Ctx &c, int tok0)
+{
+    const int t = tok0 + c.lane;
+    const float gm = c.a.gate[c.gate_base + (int64_t)min(t, c.a.T - 1) * c.a.H];
+    const float lg = (t < c.T_eff) ? log2_gate(gm) : 0.0f;
+    ChunkGates r;
+    r.G = wave_inclusive_scan(lg, c.lane);
+    r.Gtot = lane_value(r.G, 63);
+    return r;
+}
+
+// ---- state role ------------------------------------------------------------------------------------------------
+
+// This wave's B fragments of a chunk update: rows of the tile (k or v) transposed, columns 16 w .., each token
+// scaled by its weight (lane j of wj: weight of token j).
+__device__ __forceinline__ void own_weighted_frags(const Ctx &c, const uint16_t *rows, float wj, bf16x8 (&out)[2])
+{
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+        const int t0 = 32 * st + 4 * c.kg;
+        const bf16x8 raw = gather_transposed_bf16(rows, Rows(), 16 * c.w, c.lane, t0, t0 + 16);
+        f32x4 lo, hi;
+        unpack8(raw, lo, hi);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            lo[p] *= __shfl(wj, t0 + p, 64);
+            hi[p] *= __shfl(wj, t0 + 16 + p, 64);
+        }
+        out[st] = pack8(lo, hi);
+    }
+}
+
+// S <- zeta_C S + sum_j w_j k_j a_j^T for this wave's eight tiles (A: transposed keys of chunk g from LDS)
+__device__ __forceinline__ void advance_state(const Ctx &c, f32x4 (&acc)[8], int g, float zetaC, const bf16x8 (&wB)[2])
+{
+    const bf16x8 *sKT = lds_frags(c, kOffKT + g * 16384) + c.lane;
+    bf16x8 a[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a[i] = sKT[i * 64];
+#pragma unroll
+    for (int jt = 0; jt < 8; ++jt) {
+        acc[jt] *= zetaC;
+        acc[jt] = mma16(a[2 * jt], wB[0], acc[jt]);
+        acc[jt] = mma16(a[2 * jt + 1], wB[1], acc[jt]);
+    }
+}
+
+// H_[n] as the A operand of the solve (by symmetry the accumulators are rows 16 w .. of H in slot order) and this
+// wave's share of ||H_[n]||_F^2.
+__device__ __forceinline__ float publish_H(const Ctx &c, const f32x4 (&accH)[8], int g)
+{
+    bf16x8 *sH = lds_frags(c, kOffH + g * 32768) + (c.w * 4) * 64 + c.lane;
+    float ss = 0.0f;
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) {
+        sH[fb * 64] = pack8(accH[2 * fb], accH[2 * fb + 1]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ss += accH[2 * fb][r] * accH[2 * fb][r] + accH[2 * fb + 1][r] * accH[2 * fb + 1][r];
+    }
+    return wave_sum(ss);
+}
+
+// State part of the readout for all 64 tokens of chunk g: rows 16 w .. of U_[n] xhat, with U and xhat as rounded
+// value + remainder (three products), to the exchange region as [ts][w][lane] float4.
+__device__ __forceinline__ void readout_state(const Ctx &c, const f32x4 (&accU)[8], int g)
+{
+    bf16x8 Uv[4], Ur[4];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) split8(accU[2 * fb], accU[2 * fb + 1], Uv[fb], Ur[fb]);
+    const bf16x8 *sX = lds_frags(c, kOffH + g * 32768) + c.lane;
+    f32x4 *sY = (f32x4 *)(c.smem + kOffK);
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+        bf16x8 xv[4], xr[4];
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) {
+            xv[fb] = sX[((ts * 2 + 0) * 4 + fb) * 64];
+            xr[fb] = sX[((ts * 2 + 1) * 4 + fb) * 64];
+        }
+        f32x4 y0 = zero4(), y1 = zero4(), y2 = zero4();
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) {
+            y0 = mma16(Uv[fb], xv[fb], y0);
+            y1 = mma16(Ur[fb], xv[fb], y1);
+            y2 = mma16(Uv[fb], xr[fb], y2);
+        }
+        sY[(ts * 8 + c.w) * 64 + c.lane] = y0 + (y1 + y2);
+    }
+}
+
+// ---- solver role -----------------------------------------------------------------------------------------------
+
+struct Solver {
+    f32x4 mreg[4];                   // decay mask M[j][c], key block js: rows j = 16 js + 4 kg + r
+    f32x4 yi[8];                     // intra-chunk part of the readout
+    float zeta, fro;
+    int tok;                         // this lane's token (global index)
+    bool valid;
+};
+
+// LDS reads of the pass loop are assembly statements with their own counted waits: the compiler would order every
+// LDS read it knows of behind the copies of the v rows into LDS that are in flight during the passes (a full wait for
+// them), whichever part of LDS they fill. A register loaded this way must be awaited before it is used or reused.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <int BYTE_OFFSET>
+__device__ __forceinline__ void lds_read16_untracked(u32x4 &dst, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(BYTE_OFFSET) : "memory");
+}
+// at most N LDS operations issued after the read into x are still outstanding: x has landed
+template <int N>
+__device__ __forceinline__ void lds_await(u32x4 &x)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+template <int NJ>
+struct PassPlan {
+    // steps of the loop body: the tile phase (8 tiles x (4 state + NJB intra products)), then the key products of the
+    // next pass
+    static constexpr int NJB = (NJ + 1) / 2, NP = 4 * NJ, PER_TILE = 4 + NJB, NT = 8 * PER_TILE, NS = NT + NP;
+    static constexpr int base(int i) { return i >= NT ? 1 : (i % PER_TILE < 4 ? 0 : 2); }
+    static constexpr int off(int i)
+    {
+        if (i >= NT) return (((i - NT) % NJ) * 4 + (i - NT) / NJ) * 64;       // keys [js][fb], fb-major order
+        const int t = i / PER_TILE, u = i % PER_TILE;
+        return u < 4 ? (t * 4 + u) * 64 : (t * 2 + (u - 4)) * 64;
+    }
+};
+
+// (P o M) of key blocks 2 jb, 2 jb + 1 as a B fragment (a block beyond the causal range contributes zeros)
+template <int NJ>
+__device__ __forceinline__ bf16x8 masked_frag(const f32x4 (&P)[NJ], const f32x4 (&mreg)[4], int jb)
+{
+    const f32x4 lo = P[2 * jb] * mreg[2 * jb];
+    const f32x4 hi = (2 * jb + 1 < NJ) ? P[(2 * jb + 1 < NJ) ? 2 * jb + 1 : 0] * mreg[(2 * jb + 1 < NJ) ? 2 * jb + 1 : 0]
+                                       : zero4();
+    return pack8(lo, hi);
+}
+
+// Algorithm 1 in residual form for the 16 tokens of this wave:
+//   delta_i = (omega_i - 1) delta_{i-1} - (2 omega_i / (L + mu)) (g_{i-1} + lambda xi_{i-1}),  xi_i = xi_{i-1} + delta_i,
+// with g_i = H_c xi_i - q accumulated over the passes (H_c delta = zeta_c H_[n] delta + K^T (M o (K delta)), Section
+// 4.2.1), so that the rounded operand of every product is the shrinking update, not the iterate.
+// On entry: xi = xi_{-1} = 0, dl = delta_0 = xi_0, gn = -q. On exit xi + dl is the result.
+// The loop body is one straight line of MFMA steps, each with its A fragment requested kDepth steps ahead and a slice
+// of the vector work behind it.
+template <int NJ>
+__device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, const bf16x8 *sKT, f32x4 (&xi)[8],
+                                            f32x4 (&dl)[8], f32x4 (&gn)[8], const f32x4 (&mreg)[4], float zeta,
+                                            float lam, float s0, float rho2, int n_iter, int lane)
+{
+    typedef PassPlan<NJ> PL;
+    constexpr int NJB = PL::NJB, NP = PL::NP, PER_TILE = PL::PER_TILE, NT = PL::NT, NS = PL::NS;
+    // A fragments in flight. The request of step i + kDepth goes into the register that step i has just freed, also
+    // across the end of the loop body, so the depth divides the number of steps (44, 48, 60, 64).
+    constexpr int kDepth = NJ == 1 ? 4 : (NJ == 4 ? 8 : 6);
+    static_assert(NS % kDepth == 0 && kDepth <= 15, "queue registers rotate with the loop; the LDS counter holds 15 operations");
+    const uint32_t bases[3] = {lds_address(sH + lane), lds_address(sK + lane), lds_address(sKT + lane)};
+    u32x4 q[kDepth];
+    bf16x8 dB[4];
+    f32x4 P[NJ];
+    if (n_iter <= 0) return;
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) dB[fb] = pack8(dl[2 * fb], dl[2 * fb + 1]);
+    // key products of the first pass
+    static_for<0, NP>([&](auto step) {
+        constexpr int i0 = decltype(step)::value;
+        // (in groups of kDepth)
+        if constexpr (i0 % kDepth == 0) {
+            static_for<0, kDepth>([&](auto sub) {
+                constexpr int i = i0 + decltype(sub)::value;
+                if constexpr (i < NP) lds_read16_untracked<PL::off(NT + i) * 16>(q[i % kDepth], bases[1]);
+            });
+            static_for<0, kDepth>([&](auto sub) {
+                constexpr int i = i0 + decltype(sub)::value;
+                if constexpr (i < NP) {
+                    constexpr int left = (i0 + kDepth < NP ? i0 + kDepth : NP) - 1 - i;
+                    lds_await<left>(q[i % kDepth]);
+                    constexpr int fb = i / NJ, js = i % NJ;
+                    P[js] = mma16(__builtin_bit_cast(bf16x8, q[i % kDepth]), dB[fb], fb == 0 ? zero4() : P[js]);
+                }
+            });
+        }
+    });
+    static_for<0, kDepth>([&](auto step) {
+        constexpr int i = decltype(step)::value;
+        lds_read16_untracked<PL::off(i) * 16>(q[i], bases[PL::base(i)]);
+    });
+    float omega = 2.0f;
+    for (int it = 0; it < n_iter; ++it) {
+        asm volatile("" ::: "memory");
+        omega = 4.0f * __builtin_amdgcn_rcpf(4.0f - rho2 * omega);           // weight schedule
+        const float cm = omega - 1.0f, ncs = -omega * s0, ncl = ncs * lam;
+        bf16x8 pm[NJB];
+        f32x4 s = zero4(), sprev = zero4();
+        f32x4 tcm;
+        // update of one element, split into what needs no product of this pass (a) and the rest (b)
+        auto upd_a = [&](auto ftc, auto rc) {
+            constexpr int ft = decltype(ftc)::value, r = decltype(rc)::value;
+            xi[ft][r] += dl[ft][r];
+            tcm[r] = cm * dl[ft][r];
+        };
+        auto upd_b = [&](auto ftc, auto rc, const f32x4 &sv) {
+            constexpr int ft = decltype(ftc)::value, r = decltype(rc)::value;
+            const float g = __builtin_fmaf(zeta, sv[r], gn[ft][r]);
+            gn[ft][r] = g;
+            dl[ft][r] = __builtin_fmaf(ncl, xi[ft][r], __builtin_fmaf(ncs, g, tcm[r]));
+        };
+        typedef std::integral_constant<int, 0> R0;
+        typedef std::integral_constant<int, 1> R1;
+        typedef std::integral_constant<int, 2> R2;
+        typedef std::integral_constant<int, 3> R3;
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, NS>([&](auto step) {
+            constexpr int i = decltype(step)::value;
+            lds_await<kDepth - 1>(q[i % kDepth]);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, q[i % kDepth]);
+            if constexpr (i < NT) {
+                constexpr int t = i / PER_TILE, u = i % PER_TILE;
+                if constexpr (u < 4) s = mma16(a, dB[u], u == 0 ? zero4() : s);
+                else gn[t] = mma16(a, pm[u - 4], gn[t]);
+            } else {
+                constexpr int fb = (i - NT) / NJ, js = (i - NT) % NJ;
+                P[js] = mma16(a, dB[fb], fb == 0 ? zero4() : P[js]);
+            }
+            {
+                constexpr int nx = (i + kDepth) % NS;
+                lds_read16_untracked<PL::off(nx) * 16>(q[i % kDepth], bases[PL::base(nx)]);
+            }
+            if constexpr (i < NT) {
+                constexpr int t = i / PER_TILE, u = i % PER_TILE;
+                if constexpr (t == 0 && u == 2) pm[0] = masked_frag<NJ>(P, mreg, 0);
+                if constexpr (t == 0 && u == 3 && NJB == 2) pm[NJB - 1] = masked_frag<NJ>(P, mreg, NJB - 1);
+                if constexpr (u == PER_TILE - 1) sprev = s;
+                if constexpr (t >= 1) {
+                    typedef std::integral_constant<int, t - 1> FT;
+                    if constexpr (u == 0) { upd_a(FT{}, R0{}); upd_a(FT{}, R1{}); }
+                    if constexpr (u == 1) { upd_a(FT{}, R2{}); upd_a(FT{}, R3{}); }
+                    if constexpr (u == 2) { upd_b(FT{}, R0{}, sprev); upd_b(FT{}, R1{}, sprev); }
+                    if constexpr (u == 3) { upd_b(FT{}, R2{}, sprev); upd_b(FT{}, R3{}, sprev); }
+                }
+            } else {
+                // key products of the next pass: the last tile's update and the new operands meanwhile
+                constexpr int k = i - NT;
+                typedef std::integral_constant<int, 7> FT;
+                if constexpr (k == 0) {
+                    upd_a(FT{}, R0{}); upd_a(FT{}, R1{}); upd_a(FT{}, R2{}); upd_a(FT{}, R3{});
+                    dB[1] = pack8(dl[2], dl[3]);
+                }
+                if constexpr (k == NJ) {
+                    upd_b(FT{}, R0{}, s); upd_b(FT{}, R1{}, s); upd_b(FT{}, R2{}, s); upd_b(FT{}, R3{}, s);
+                    dB[2] = pack8(dl[4], dl[5]);
+                }
+                if constexpr (k == 2 * NJ) dB[3] = pack8(dl[6], dl[7]);
+            }
+            if constexpr (i == NT - 1) dB[0] = pack8(dl[0], dl[1]);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    }
+    // the reads issued for a pass that does not follow must have landed before their registers are used again
+    static_for<0, kDepth>([&](auto step) { lds_await<0>(q[decltype(step)::value]); });
+}
+
+// Decay mask of Section 4.2.1 in the log-space form of Appendix B.2 (base 2): M[j][c] = 2^(G_c - G_j) for j <= c.
+template <int NJ>
+__device__ __forceinline__ void build_mask(const Ctx &c, Solver &s, const ChunkGates &cg, int ts)
+{
+    const int c_local = 16 * ts + c.n;
+    const float Gc = __shfl(cg.G, c_local, 64);
+    s.zeta = exp2f(Gc);
+#pragma unroll
+    for (int js = 0; js < 4; ++js)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (js < NJ) {
+                const int j = 16 * js + 4 * c.kg + r;
+                const float Gj = __shfl(cg.G, j, 64);
+                s.mreg[js][r] = (j <= c_local) ? __builtin_amdgcn_exp2f(Gc - Gj) : 0.0f;
+            } else {
+                s.mreg[js][r] = 0.0f;
+            }
+        }
+}
+
+// Chunk-wise Frobenius norm, first half: w_j of this wave's tokens to the table.
+//   ||H_c||^2 = zeta_c^2 ||H_[n]||^2 + sum_{j<=c} M[j,c]^2 w_j,  w_j = 2 (zeta_j k_j^T H_[n] k_j + sum_{i<j} M[i,j] G_ij^2) + G_jj^2
+// (G = K K^T): the three-term expansion of Section 4.2.1 with its double sum folded by M[i,c] M[j,c] = M[j,c]^2 M[i,j].
+template <int NJ>
+__device__ __forceinline__ void frobenius_terms(const Ctx &c, const Solver &s, int g, int ts)
+{
+    const bf16x8 *sH = lds_frags(c, kOffH + g * 32768) + c.lane;
+    const bf16x8 *sK = lds_frags(c, kOffK + g * 16384) + c.lane;
+    bf16x8 kB[4];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) kB[fb] = sK[(ts * 4 + fb) * 64];
+    // k_c^T H_[n] k_c
+    float a_part = 0.0f;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        bf16x8 a[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a[i] = sH[(half * 16 + i) * 64];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int ft = 4 * half + t;
+            f32x4 acc = zero4();
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb) acc = mma16(a[t * 4 + fb], kB[fb], acc);
+            f32x4 lo, hi;
+            unpack8(kB[ft >> 1], lo, hi);
+            const f32x4 kc = (ft & 1) ? hi : lo;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) a_part += acc[r] * kc[r];
+        }
+    }
+    // Gram columns of this wave's tokens against the key blocks js <= ts
+    float b_part = 0.0f, d_part = 0.0f;
+#pragma unroll
+    for (int js = 0; js < NJ; ++js) {
+        f32x4 G = zero4();
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) G = mma16(sK[(js * 4 + fb) * 64], kB[fb], G);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            b_part += s.mreg[js][r] * (G[r] * G[r]);
+            if (js == NJ - 1 && 4 * c.kg + r == c.n) d_part = G[r] * G[r];
+        }
+    }
+    b_part -= d_part;                 // the sum runs over i < c: the diagonal term (M[c][c] = 1) is taken out again
+    a_part = sum_over_kg(a_part);
+    b_part = sum_over_kg(b_part);
+    d_part = sum_over_kg(d_part);
+    float *sW = (float *)(c.smem + kOffTab) + g * 64;
+    if (c.kg == 0) sW[16 * ts + c.n] = 2.0f * (s.zeta * a_part + b_part) + d_part;
+}
+
+// second half: ||H_c||_F of this lane's token
+template <int NJ>
+__device__ __forceinline__ float frobenius_norm(const Ctx &c, const Solver &s, int g)
+{
+    const float *sW = (const float *)(c.smem + kOffTab) + g * 64;
+    const float *sN = (const float *)(c.smem + kOffTab) + 128 + g * 8;
+    float hn2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) hn2 += sN[i];
+    float f = 0.0f;
+#pragma unroll
+    for (int js = 0; js < NJ; ++js) {
+        const f32x4 wv = *(const f32x4 *)(sW + 16 * js + 4 * c.kg);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) f += s.mreg[js][r] * s.mreg[js][r] * wv[r];
+    }
+    f = sum_over_kg(f);
+    return sqrtf(fmaxf(s.zeta * s.zeta * hn2 + f, 0.0f));
+}
+
+// Everything between the Frobenius table and the published result: the passes, then (after the workgroup has
+// passed `barrier`) xhat to LDS and the intra-chunk part of the readout.
+template <int NJ>
+__device__ __forceinline__ void solve_tokens(const Ctx &c, Solver &s, int g, int ts, const typename IOBF16::raw4 (&qraw)[8],
+                                             float lam)
+{
+    const bf16x8 *sH = lds_frags(c, kOffH + g * 32768);
+    const bf16x8 *sK = lds_frags(c, kOffK + g * 16384);
+    const bf16x8 *sKT = lds_frags(c, kOffKT + g * 16384);
+    // Section 4.1: L = ||H_t||_F + lambda_t, mu = lambda_t
+    const float L = s.fro + lam, mu = lam;
+    const float s0 = 2.0f / (L + mu);
+    const float rho = (L - mu) / (L + mu);
+    f32x4 xi[8], dl[8], gn[8];
+#pragma unroll
+    for (int ft = 0; ft < 8; ++ft) {
+        const f32x4 qv = IOBF16::cvt4(qraw[ft]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float qe = s.valid ? qv[r] : 0.0f;
+            xi[ft][r] = 0.0f;
+            dl[ft][r] = s0 * qe;
+            gn[ft][r] = -qe;
+        }
+    }
+    cheb_passes<NJ>(sH, sK, sKT, xi, dl, gn, s.mreg, s.zeta, lam, s0, rho * rho, c.a.n_iter, c.lane);
+#pragma unroll
+    for (int ft = 0; ft < 8; ++ft) xi[ft] += dl[ft];
+
+    // ---- readout, intra-chunk part: sum_{j<=c} M[j,c] v_j (k_j . xhat_c), xhat as value + remainder
+    bf16x8 xv[4], xr[4];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) split8(xi[2 * fb], xi[2 * fb + 1], xv[fb], xr[fb]);
+    f32x4 P[NJ];
+#pragma unroll
+    for (int js = 0; js < NJ; ++js) {
+        P[js] = zero4();
+#pragma unroll
+        for (int fb = 0; fb < 4; ++fb) {
+            const bf16x8 a = sK[(js * 4 + fb) * 64 + c.lane];
+            P[js] = mma16(a, xv[fb], P[js]);
+            P[js] = mma16(a, xr[fb], P[js]);
+        }
+    }
+    constexpr int NJB = (NJ + 1) / 2;
+    bf16x8 pm[NJB];
+#pragma unroll
+    for (int jb = 0; jb < NJB; ++jb) pm[jb] = masked_frag<NJ>(P, s.mreg, jb);
+
+    wait_all_memory();               // this wave's copies of v rows have landed
+    lds_barrier();                   // all of them have; every wave is through its passes: H_[n] is dead
+    bf16x8 *sX = lds_frags(c, kOffH + g * 32768) + c.lane;
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) {
+        sX[((ts * 2 + 0) * 4 + fb) * 64] = xv[fb];
+        sX[((ts * 2 + 1) * 4 + fb) * 64] = xr[fb];
+    }
+    const uint16_t *rowsV = lds_rows(c, g);
+#pragma unroll
+    for (int ft = 0; ft < 8; ++ft) {
+        s.yi[ft] = zero4();
+#pragma unroll
+        for (int jb = 0; jb < NJB; ++jb) {
+            const int t0 = 32 * jb + 4 * c.kg;
+            const bf16x8 vt = gather_transposed_bf16(rowsV, Rows(), 16 * ft, c.lane, t0, t0 + 16);
+            s.yi[ft] = mma16(vt, pm[jb], s.yi[ft]);
+        }
+    }
+}
+
+// y_c = zeta_c U_[n] xhat_c + intra part, stored
+__device__ __forceinline__ void store_output(const Ctx &c, const Solver &s, int ts)
+{
+    const f32x4 *sY = (const f32x4 *)(c.smem + kOffK);
+    if (!s.valid) return;
+    const int64_t off = c.base_bh + (int64_t)s.tok * c.a.stride_t;
+#pragma unroll
+    for (int ft = 0; ft < 8; ++ft) {
+        const f32x4 ys = sY[(ts * 8 + ft) * 64 + c.lane];
+        const f32x4 y = s.zeta * ys + s.yi[ft];
+        IOBF16::store4(c.a.o, off + 16 * ft + 4 * c.kg, y[0], y[1], y[2], y[3]);
+    }
+}
+
+// ---- data movement ---------------------------------------------------------------------------------------------
+
+// k rows of the two chunks starting at chunk c0: global -> registers (four 16-byte pieces per thread)
+struct KRowRegs {
+    uint4 r[4];
+};
+__device__ __forceinline__ void load_k_rows(const Ctx &c, KRowRegs &kr, int c0)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int p = i * kFusedThreads + c.tid;
+        const int g = p >> 10, row = (p & 1023) >> 4, piece = p & 15;
+        const int tok = min((c0 + g) * kChunk + row, c.a.T - 1);
+        kr.r[i] = *(const uint4 *)((const uint16_t *)c.a.k + c.base_bh + (int64_t)tok * c.a.stride_t + 8 * piece);
+    }
+}
+__device__ __forceinline__ void store_k_rows(const Ctx &c, const KRowRegs &kr)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int p = i * kFusedThreads + c.tid;
+        const int g = p >> 10, row = (p & 1023) >> 4, piece = p & 15;
+        *(uint4 *)(lds_rows(c, g) + Rows()(row, 8 * piece)) = kr.r[i];
+    }
+}
+// v rows of chunk `chunk` into row tile g: direct copies global -> LDS, 1 KiB (four rows) per wave instruction; the
+// lane picks the 16 source bytes that belong at its place of the swizzled row. Rows past the end of the sequence
+// repeat the last row (finite values that only ever meet zero weights).
+__device__ __forceinline__ void copy_v_rows(const Ctx &c, int g, int chunk)
+{
+    const int tok_base = min(chunk * kChunk, c.a.T - 1);
+    const uint16_t *base = (const uint16_t *)c.a.v + c.base_bh + (int64_t)tok_base * c.a.stride_t;
+    const buffer_rsrc rsrc = make_raw_buffer(base);
+    const int last_row = c.a.T - 1 - tok_base;
+    const int row_bytes = (int)c.a.stride_t * 2;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int i = c.w + 8 * h;
+        const int row = 4 * i + (c.lane >> 4);
+        const int sbyte = ((c.lane & 15) * 16) ^ ((row & 7) << 5);
+        async_copy16_to_lds((char *)lds_rows(c, g) + i * 1024, rsrc, min(row, last_row) * row_bytes + sbyte, 0);
+    }
+}
+
+// A fragments of the keys of both chunks from their row tiles: rows (K[js][fb]) and transposed (KT[ft][jb]); each
+// wave builds four of the 32 fragments of either kind.
+__device__ __forceinline__ void build_key_frags(const Ctx &c)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int idx = c.w * 4 + q;
+        const int g = idx >> 4, f = idx & 15;
+        const uint16_t *rows = lds_rows(c, g);
+        {
+            const int js = f >> 2, fb = f & 3;
+            const u16x4 lo = *(const u16x4 *)(rows + Rows()(16 * js + c.n, 32 * fb + 4 * c.kg));
+            const u16x4 hi = *(const u16x4 *)(rows + Rows()(16 * js + c.n, 32 * fb + 16 + 4 * c.kg));
+            const u16x8 u = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            lds_frags(c, kOffK + g * 16384)[f * 64 + c.lane] = __builtin_bit_cast(bf16x8, u);
+        }
+        {
+            const int ft = f >> 1, jb = f & 1;
+            const int t0 = 32 * jb + 4 * c.kg;
+            lds_frags(c, kOffKT + g * 16384)[f * 64 + c.lane] =
+                gather_transposed_bf16(rows, Rows(), 16 * ft, c.lane, t0, t0 + 16);
+        }
+    }
+}
+
+// Start state of this wave's tiles: the caller's initial state advanced over the segments before this one.
+__device__ __forceinline__ void load_start_state(const Ctx &c, f32x4 (&accH)[8], f32x4 (&accU)[8], int pair, int seg)
+{
+    const FusedArgs &a = c.a;
+#pragma unroll
+    for (int jt = 0; jt < 8; ++jt) {
+        accH[jt] = zero4();
+        accU[jt] = zero4();
+    }
+    if (a.H_init) {
+        const float *Hi = a.H_init + (int64_t)pair * kD * kD;
+        const float *Ui = a.U_init + (int64_t)pair * kD * kD;
+#pragma unroll
+        for (int jt = 0; jt < 8; ++jt) {
+            // tile element (row 4 kg + r, column n) = H[16 jt + 4 kg + r][16 w + n] = H[16 w + n][16 jt + 4 kg + r]
+            if (a.h_init_lower_blocks && (jt >> 1) > (c.w >> 1)) {
+                // the 32 x 32 block above the block diagonal is not stored: take the mirror image
+#pragma unroll
+                for (int r = 0; r < 4; ++r) accH[jt][r] = Hi[(int64_t)(16 * jt + 4 * c.kg + r) * kD + 16 * c.w + c.n];
+            } else {
+                accH[jt] = *(const f32x4 *)(Hi + (int64_t)(16 * c.w + c.n) * kD + 16 * jt + 4 * c.kg);
+            }
+            accU[jt] = *(const f32x4 *)(Ui + (int64_t)(16 * c.w + c.n) * kD + 16 * jt + 4 * c.kg);
+        }
+    }
+    for (int sg = 0; sg < seg; ++sg) {
+        const f32x4 *t = (const f32x4 *)a.seg_buf + ((int64_t)(pair * a.n_segs + sg) * 2) * 4096 + (c.w * 8) * 64 + c.lane;
+        const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
+#pragma unroll
+        for (int jt = 0; jt < 8; ++jt) {
+            accH[jt] = decay * accH[jt] + t[jt * 64];
+            accU[jt] = decay * accU[jt] + t[4096 + jt * 64];
+        }
+    }
+}
+
+}  // namespace
+
+// One workgroup per (pair, segment of chunks). Per iteration (chunks A = c0, B = c0 + 1), with the barriers between
+// the phases:
+//   1. k rows (registers, fetched during the previous iteration) -> row tiles; H_[n] of A -> LDS
+//   2. key fragments of both chunks; this wave's weighted k fragments
+//   3. H advanced over A; H_[n] of B -> LDS; H advanced over B; partial norms -> table (in the dead k row tile)
+//   4. solver: Frobenius terms -> table
+//   5. solver: norms; copies of the v rows into the row tiles start; passes, intra-chunk readout products;
+//      xhat -> LDS (over H_[n]); fetch of the next k rows
+//   6. state part of the readout for A (over the key fragments), U advanced over A;  7. solver A stores
+//   8. the same for B;  9. solver B stores
+__global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    Ctx c{a, smem};
+    c.tid = threadIdx.x;
+    c.lane = c.tid & 63;
+    c.w = __builtin_amdgcn_readfirstlane(c.tid >> 6);
+    c.n = c.lane & 15;
+    c.kg = c.lane >> 4;
+    const int pair = blockIdx.x % a.n_pairs, seg = blockIdx.x / a.n_pairs;
+    const int b = pair / a.H, h = pair % a.H;
+    c.base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    c.gate_base = (int64_t)b * a.T * a.H + h;
+    const int chunk_begin = seg * a.seg_len;
+    const int chunk_end = min(chunk_begin + a.seg_len, a.n_chunks);
+    if (chunk_begin >= chunk_end) return;
+    c.T_eff = min(a.T, chunk_end * kChunk);
+    const int grp = c.w >> 2;                               // solver role: chunk of the pair
+    const int ts = grp ? 3 - (c.w & 3) : (c.w & 3);         // ... and token block (a light and a heavy one per SIMD)
+
+    f32x4 accH[8], accU[8];
+    load_start_state(c, accH, accU, pair, seg);
+    KRowRegs kr;
+    load_k_rows(c, kr, chunk_begin);
+    float *sTab = (float *)(smem + kOffTab);
+
+    for (int c0 = chunk_begin; c0 < chunk_end; c0 += 2) {
+        // ---- 1
+        store_k_rows(c, kr);
+        const float hnA = publish_H(c, accH, 0);
+        const ChunkGates cgA = scan_gates(c, c0 * kChunk), cgB = scan_gates(c, (c0 + 1) * kChunk);
+        const float wjA = (c0 * kChunk + c.lane < c.T_eff) ? exp2f(cgA.Gtot - cgA.G) : 0.0f;
+        const float wjB = ((c0 + 1) * kChunk + c.lane < c.T_eff) ? exp2f(cgB.Gtot - cgB.G) : 0.0f;
+        const float zetaA = exp2f(cgA.Gtot), zetaB = exp2f(cgB.Gtot);
+        lds_barrier();
+        // ---- 2
+        build_key_frags(c);
+        bf16x8 wBA[2], wBB[2];
+        own_weighted_frags(c, lds_rows(c, 0), wjA, wBA);
+        own_weighted_frags(c, lds_rows(c, 1), wjB, wBB);
+        lds_barrier();
+        // ---- 3
+        advance_state(c, accH, 0, zetaA, wBA);
+        const float hnB = publish_H(c, accH, 1);
+        advance_state(c, accH, 1, zetaB, wBB);
+        if (c.lane == 0) {
+            sTab[128 + c.w] = hnA;
+            sTab[128 + 8 + c.w] = hnB;
+        }
+        // solver inputs of this lane's token
+        Solver s;
+        s.tok = (c0 + grp) * kChunk + 16 * ts + c.n;
+        s.valid = s.tok < c.T_eff;
+        const int64_t tok_off = c.base_bh + (int64_t)min(s.tok, a.T - 1) * a.stride_t;
+        IOBF16::raw4 qraw[8];
+#pragma unroll
+        for (int ft = 0; ft < 8; ++ft) qraw[ft] = IOBF16::load_raw4(a.q, tok_off + 16 * ft + 4 * c.kg);
+        float lam = a.lambda[c.gate_base + (int64_t)min(s.tok, a.T - 1) * a.H];
+        if (!s.valid) lam = 1.0f;
+        const ChunkGates &cg = grp ? cgB : cgA;
+        switch (ts) {
+        case 0: build_mask<1>(c, s, cg, ts); break;
+        case 1: build_mask<2>(c, s, cg, ts); break;
+        case 2: build_mask<3>(c, s, cg, ts); break;
+        default: build_mask<4>(c, s, cg, ts); break;
+        }
+        lds_barrier();
+        // ---- 4
+        switch (ts) {
+        case 0: frobenius_terms<1>(c, s, grp, ts); break;
+        case 1: frobenius_terms<2>(c, s, grp, ts); break;
+        case 2: frobenius_terms<3>(c, s, grp, ts); break;
+        default: frobenius_terms<4>(c, s, grp, ts); break;
+        }
+        lds_barrier();
+        // ---- 5
+        switch (ts) {
+        case 0: s.fro = frobenius_norm<1>(c, s, grp); break;
+        case 1: s.fro = frobenius_norm<2>(c, s, grp); break;
+        case 2: s.fro = frobenius_norm<3>(c, s, grp); break;
+        default: s.fro = frobenius_norm<4>(c, s, grp); break;
+        }
+        if (a.fro_out && s.valid && c.kg == 0) a.fro_out[c.gate_base + (int64_t)s.tok * a.H] = s.fro;
+        lds_barrier();                   // the table is dead
+        // v rows replace the k rows; they land during the passes
+        copy_v_rows(c, 0, c0);
+        copy_v_rows(c, 1, c0 + 1);
+        switch (ts) {
+        case 0: solve_tokens<1>(c, s, grp, ts, qraw, lam); break;
+        case 1: solve_tokens<2>(c, s, grp, ts, qraw, lam); break;
+        case 2: solve_tokens<3>(c, s, grp, ts, qraw, lam); break;
+        default: solve_tokens<4>(c, s, grp, ts, qraw, lam); break;
+        }
+        if (c0 + 2 < chunk_end) load_k_rows(c, kr, c0 + 2);
+        // this wave's weighted v fragments of both chunks (the v rows stay until the end of the iteration)
+        bf16x8 wVA[2], wVB[2];
+        own_weighted_frags(c, lds_rows(c, 0), wjA, wVA);
+        own_weighted_frags(c, lds_rows(c, 1), wjB, wVB);
+        lds_barrier();                   // xhat of both chunks is visible; the key-row fragments are dead
+        // ---- 6
+        readout_state(c, accU, 0);
+        advance_state(c, accU, 0, zetaA, wVA);
+        lds_barrier();
+        // ---- 7
+        if (grp == 0) store_output(c, s, ts);
+        lds_barrier();
+        // ---- 8
+        readout_state(c, accU, 1);
+        advance_state(c, accU, 1, zetaB, wVB);
+        lds_barrier();
+        // ---- 9
+        if (grp == 1) store_output(c, s, ts);
+    }
+
+    if (a.H_final && seg == a.n_segs - 1) {
+        float *Hf = a.H_final + (int64_t)pair * kD * kD;
+        float *Uf = a.U_final + (int64_t)pair * kD * kD;
+#pragma unroll
+        for (int jt = 0; jt < 8; ++jt) {
+            *(f32x4 *)(Hf + (int64_t)(16 * c.w + c.n) * kD + 16 * jt + 4 * c.kg) = accH[jt];
+            *(f32x4 *)(Uf + (int64_t)(16 * c.w + c.n) * kD + 16 * jt + 4 * c.kg) = accU[jt];
+        }
+    }
+}
+
+// Summary (prod gamma, Delta H, Delta U from a zero state) of every segment but the last: the start states of the
+// fused kernel's workgroups follow from these by a short scan.
+__global__ __launch_bounds__(kFusedThreads) void fused_summary_kernel(FusedArgs a)
+{
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[3 * 16384];     // k rows, v rows, transposed keys
+    Ctx c{a, smem};
+    c.tid = threadIdx.x;
+    c.lane = c.tid & 63;
+    c.w = __builtin_amdgcn_readfirstlane(c.tid >> 6);
+    c.n = c.lane & 15;
+    c.kg = c.lane >> 4;
+    const int pair = blockIdx.x % a.n_pairs, seg = blockIdx.x / a.n_pairs;
+    const int b = pair / a.H, h = pair % a.H;
+    c.base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
+    c.gate_base = (int64_t)b * a.T * a.H + h;
+    const int chunk_begin = seg * a.seg_len;
+    const int chunk_end = min(chunk_begin + a.seg_len, a.n_chunks);
+    c.T_eff = min(a.T, chunk_end * kChunk);
+    uint16_t *rowsK = (uint16_t *)smem, *rowsV = (uint16_t *)(smem + 16384);
+    bf16x8 *sKT = (bf16x8 *)(smem + 32768);
+
+    f32x4 accH[8], accU[8];
+#pragma unroll
+    for (int jt = 0; jt < 8; ++jt) {
+        accH[jt] = zero4();
+        accU[jt] = zero4();
+    }
+    // rows of one chunk: two 16-byte pieces of k and two of v per thread, fetched one chunk ahead
+    uint4 kr[2], vr[2];
+    auto fetch = [&](int chunk) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int p = i * kFusedThreads + c.tid;
+            const int row = p >> 4, piece = p & 15;
+            const int tok = min(chunk * kChunk + row, a.T - 1);
+            const int64_t off = c.base_bh + (int64_t)tok * a.stride_t + 8 * piece;
+            kr[i] = *(const uint4 *)((const uint16_t *)a.k + off);
+            vr[i] = *(const uint4 *)((const uint16_t *)a.v + off);
+        }
+    };
+    float Gseg = 0.0f;
+    fetch(chunk_begin);
+    for (int ch = chunk_begin; ch < chunk_end; ++ch) {
+        lds_barrier();                   // the previous chunk's operand reads are done
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int p = i * kFusedThreads + c.tid;
+            const int row = p >> 4, piece = p & 15;
+            *(uint4 *)(rowsK + Rows()(row, 8 * piece)) = kr[i];
+            *(uint4 *)(rowsV + Rows()(row, 8 * piece)) = vr[i];
+        }
+        if (ch + 1 < chunk_end) fetch(ch + 1);
+        const ChunkGates cg = scan_gates(c, ch * kChunk);
+        Gseg += cg.Gtot;
+        const float wj = (ch * kChunk + c.lane < c.T_eff) ? exp2f(cg.Gtot - cg.G) : 0.0f;
+        const float zetaC = exp2f(cg.Gtot);
+        lds_barrier();
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int f = c.w * 2 + q;
+            const int ft = f >> 1, jb = f & 1;
+            const int t0 = 32 * jb + 4 * c.kg;
+            sKT[f * 64 + c.lane] = gather_transposed_bf16(rowsK, Rows(), 16 * ft, c.lane, t0, t0 + 16);
+        }
+        bf16x8 wK[2], wV[2];
+        own_weighted_frags(c, rowsK, wj, wK);
+        own_weighted_frags(c, rowsV, wj, wV);
+        lds_barrier();
+        bf16x8 af[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) af[i] = sKT[i * 64 + c.lane];
+#pragma unroll
+        for (int jt = 0; jt < 8; ++jt) {
+            accH[jt] *= zetaC;
+            accU[jt] *= zetaC;
+            accH[jt] = mma16(af[2 * jt], wK[0], accH[jt]);
+            accU[jt] = mma16(af[2 * jt], wV[0], accU[jt]);
+            accH[jt] = mma16(af[2 * jt + 1], wK[1], accH[jt]);
+            accU[jt] = mma16(af[2 * jt + 1], wV[1], accU[jt]);
+        }
+    }
+    f32x4 *t = (f32x4 *)a.seg_buf + ((int64_t)(pair * a.n_segs + seg) * 2) * 4096 + (c.w * 8) * 64 + c.lane;
+#pragma unroll
+    for (int jt = 0; jt < 8; ++jt) {
+        t[jt * 64] = accH[jt];
+        t[4096 + jt * 64] = accU[jt];
+    }
+    if (c.tid == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
+}
+
+size_t fused_workspace_bytes(int n_pairs, int n_segs)
+{
+    // per (pair, segment): Delta H, Delta U in the kernels' tile order, and the segment's log2 decay
+    return (size_t)n_pairs * n_segs * (2 * kD * kD * sizeof(float)) + (((size_t)n_pairs * n_segs * sizeof(float) + 255) / 256) * 256;
+}
+
+hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_t stream)
+{
+    FusedArgs a = a0;
+    a.seg_buf = (float *)workspace;
+    a.seg_logdecay = (float *)((char *)workspace + (size_t)a.n_pairs * a.n_segs * (2 * kD * kD * sizeof(float)));
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)fused_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (a.n_segs > 1) {
+        hipLaunchKernelGGL(fused_summary_kernel, dim3((unsigned)(a.n_pairs * (a.n_segs - 1))), dim3(kFusedThreads), 0,
+                           stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(fused_forward_kernel, dim3((unsigned)(a.n_pairs * a.n_segs)), dim3(kFusedThreads), kLdsBytes,
+                       stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace gka

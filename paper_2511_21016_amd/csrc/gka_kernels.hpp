@@ -139,6 +139,24 @@ hipError_t launch_chunk_solve(const SolveArgs &a, int n_pairs, int d, bool io_bf
                               hipStream_t stream);
 hipError_t launch_decode_step(const DecodeArgs &a, int n_pairs, int d, bool io_bf16, hipStream_t stream);
 
+// Forward pass in one kernel with the states in registers (bf16 tensors and operands, d = 128, Eq. (CH) as printed).
+struct FusedArgs {
+    const void *q, *k, *v;
+    const float *gate, *lambda;   // [B,T,H]
+    void *o;
+    float *fro_out;               // [B,T,H] or nullptr
+    const float *H_init, *U_init; // [pairs,d,d] or nullptr
+    float *H_final, *U_final;     // [pairs,d,d] or nullptr
+    bool h_init_lower_blocks;
+    int64_t stride_b, stride_t, stride_h;
+    int H, T, n_iter;
+    int n_pairs, n_chunks;
+    int n_segs, seg_len;          // segments of the chunk walk per pair (one workgroup each), chunks per segment
+    float *seg_buf, *seg_logdecay; // set by the launcher (carved from the workspace)
+};
+size_t fused_workspace_bytes(int n_pairs, int n_segs);
+hipError_t launch_fused_forward(const FusedArgs &a, void *workspace, hipStream_t stream);
+
 // Workspace sizes in bytes per (pair, chunk).
 size_t ws_H_bytes_per_chunk(int d, bool compute_bf16);
 size_t ws_U_bytes_per_chunk(int d, bool compute_bf16);

@@ -87,7 +87,7 @@ def test_initial_and_final_state_handoff():
 
 
 @pytest.mark.parametrize("compute", ["bf16", "f32"])
-def test_multi_slab_with_state_carry(compute, monkeypatch):
+def test_multi_slab_with_state_carry(compute):
     """The sequence is processed as several chunk slabs (states carried between launches), with a ragged tail
     and non-zero initial states; final states are checked too."""
     w = synth.CFG2.scaled(B=8, H=16, T=1000, seed=77)
@@ -95,8 +95,9 @@ def test_multi_slab_with_state_carry(compute, monkeypatch):
     cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
     params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, cm)
     one_slab = binding.forward_workspace_bytes(params)
-    # a workspace budget small enough that this problem is cut into slabs of four chunks
-    monkeypatch.setenv("GKA_SLAB_STATE_BYTES", str(48 << 20))
+    # a workspace budget small enough that this problem is cut into slabs of four chunks (two-phase kernels)
+    slab = dict(slab_state_bytes=48 << 20, path=binding.GKA_PATH_TWO_PHASE)
+    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, cm, slab_state_bytes=48 << 20)
     assert binding.forward_workspace_bytes(params) < one_slab // 2
     rng = np.random.default_rng(5)
     A = rng.standard_normal((w.B, w.H, w.d, 8)).astype(np.float32)
@@ -104,7 +105,7 @@ def test_multi_slab_with_state_carry(compute, monkeypatch):
     Ui = rng.standard_normal((w.B, w.H, w.d, w.d)).astype(np.float32) * 0.1
     cmode = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
     o, ex = run_forward(w, x, compute=cmode, H_init=to_device(Hi, "f32"), U_init=to_device(Ui, "f32"),
-                        return_state=True)
+                        return_state=True, **slab)
     ref, rex = oracle_forward(w, x, H_init=Hi, U_init=Ui, return_state=True)
     err = pair_rel_err(to_host(o), ref)
     assert err <= TOL_BF16, err
