@@ -23,6 +23,20 @@
 #include "gka_kernels.hpp"
 
 namespace gka {
+#ifdef GKA_FUSED_TIMERS
+__device__ unsigned long long g_fused_timers[8 * 32];
+#define GKA_FT(i)                                                                                  \
+    do {                                                                                           \
+        if (c.lane == 0 && blockIdx.x == 100 && c0 == chunk_begin + 4)                             \
+            g_fused_timers[c.w * 32 + (i)] = __builtin_readcyclecounter();                         \
+    } while (0)
+extern "C" int gka_debug_read_fused_timers(unsigned long long *host)
+{
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_fused_timers), sizeof(g_fused_timers));
+}
+#else
+#define GKA_FT(i) do {} while (0)
+#endif
 namespace {
 
 constexpr int kFusedThreads = 512;
@@ -87,13 +101,44 @@ __device__ __forceinline__ float sum_over_kg(float x)
     return x;
 }
 
+// U is needed only for the state part of the readout and its own update, once per iteration; in between it is
+// parked in a scratch block of this workgroup in global memory (1 KiB per wave and tile, written and read by the same
+// lanes), so that the passes have its registers.
+__device__ __forceinline__ void park_store(f32x4 *slot, const f32x4 (&acc)[8])
+{
+#pragma unroll
+    for (int jt = 0; jt < 8; ++jt) slot[jt * 64] = acc[jt];
+}
+__device__ __forceinline__ void park_load(const f32x4 *slot, f32x4 (&acc)[8])
+{
+#pragma unroll
+    for (int jt = 0; jt < 8; ++jt) acc[jt] = slot[jt * 64];
+}
+
 struct Ctx {
     const FusedArgs &a;
     unsigned char *smem;
     int tid, lane, w, n, kg;
     int64_t base_bh, gate_base;
     int T_eff;                       // tokens at or beyond this index do not exist for this workgroup
+    f32x4 *park;                     // this lane's place in the workgroup's scratch block
+#ifdef GKA_FUSED_TIMERS
+    bool stamp;
+#endif
 };
+
+// Lane-derived fields from a copy of the lane index that the compiler cannot trace back: addresses formed from it
+// are formed anew instead of being kept in registers (or spilled) across the code in between.
+__device__ __forceinline__ void refresh_lane(Ctx &c)
+{
+    int lane_now = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane_now));
+    c.lane = lane_now;
+    c.tid = c.w * 64 + lane_now;
+    c.n = lane_now & 15;
+    c.kg = lane_now >> 4;
+    c.park = (f32x4 *)c.a.park + ((int64_t)blockIdx.x * 8 + c.w) * (8 * 64) + lane_now;
+}
 
 __device__ __forceinline__ bf16x8 *lds_frags(const Ctx &c, int off) { return (bf16x8 *)(c.smem + off); }
 __device__ __forceinline__ uint16_t *lds_rows(const Ctx &c, int g) { return (uint16_t *)(c.smem + kOffR + g * 16384); }
@@ -114,6 +159,8 @@ __device__ __forceinline__ ChunkGates scan_gates(const Ctx &c, int tok0)
 }
 
 // ---- state role ------------------------------------------------------------------------------------------------
+// (Loops that run once per chunk are kept rolled where that costs little: the loop body of the kernel is executed
+// once per iteration, straight through, so its size is paid in instruction fetches.)
 
 // This wave's B fragments of a chunk update: rows of the tile (k or v) transposed, columns 16 w .., each token
 // scaled by its weight (lane j of wj: weight of token j).
@@ -138,14 +185,18 @@ __device__ __forceinline__ void own_weighted_frags(const Ctx &c, const uint16_t 
 __device__ __forceinline__ void advance_state(const Ctx &c, f32x4 (&acc)[8], int g, float zetaC, const bf16x8 (&wB)[2])
 {
     const bf16x8 *sKT = lds_frags(c, kOffKT + g * 16384) + c.lane;
-    bf16x8 a[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) a[i] = sKT[i * 64];
+    for (int half = 0; half < 2; ++half) {
+        bf16x8 a[8];
 #pragma unroll
-    for (int jt = 0; jt < 8; ++jt) {
-        acc[jt] *= zetaC;
-        acc[jt] = mma16(a[2 * jt], wB[0], acc[jt]);
-        acc[jt] = mma16(a[2 * jt + 1], wB[1], acc[jt]);
+        for (int i = 0; i < 8; ++i) a[i] = sKT[(half * 8 + i) * 64];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int jt = 4 * half + t;
+            acc[jt] *= zetaC;
+            acc[jt] = mma16(a[2 * t], wB[0], acc[jt]);
+            acc[jt] = mma16(a[2 * t + 1], wB[1], acc[jt]);
+        }
     }
 }
 
@@ -172,8 +223,8 @@ __device__ __forceinline__ void readout_state(const Ctx &c, const f32x4 (&accU)[
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) split8(accU[2 * fb], accU[2 * fb + 1], Uv[fb], Ur[fb]);
     const bf16x8 *sX = lds_frags(c, kOffH + g * 32768) + c.lane;
-    f32x4 *sY = (f32x4 *)(c.smem + kOffK);
-#pragma unroll
+    f32x4 *sY = (f32x4 *)(c.smem + kOffK) + c.w * 64 + c.lane;
+#pragma unroll 1
     for (int ts = 0; ts < 4; ++ts) {
         bf16x8 xv[4], xr[4];
 #pragma unroll
@@ -188,11 +239,14 @@ __device__ __forceinline__ void readout_state(const Ctx &c, const f32x4 (&accU)[
             y1 = mma16(Ur[fb], xv[fb], y1);
             y2 = mma16(Uv[fb], xr[fb], y2);
         }
-        sY[(ts * 8 + c.w) * 64 + c.lane] = y0 + (y1 + y2);
+        sY[ts * 8 * 64] = y0 + (y1 + y2);
     }
 }
 
 // ---- solver role -----------------------------------------------------------------------------------------------
+// A wave's tokens see the key blocks js <= ts of their chunk (16 keys each). Two instantiations cover the four token
+// blocks: NJ = 2 key blocks for ts = 0, 1 and NJ = 4 for ts = 2, 3; a block beyond ts is all future keys, its mask is
+// zero and it costs a few products (four instantiations would cost more in instruction fetches than they save).
 
 struct Solver {
     f32x4 mreg[4];                   // decay mask M[j][c], key block js: rows j = 16 js + 4 kg + r
@@ -226,7 +280,7 @@ template <int NJ>
 struct PassPlan {
     // steps of the loop body: the tile phase (8 tiles x (4 state + NJB intra products)), then the key products of the
     // next pass
-    static constexpr int NJB = (NJ + 1) / 2, NP = 4 * NJ, PER_TILE = 4 + NJB, NT = 8 * PER_TILE, NS = NT + NP;
+    static constexpr int NJB = NJ / 2, NP = 4 * NJ, PER_TILE = 4 + NJB, NT = 8 * PER_TILE, NS = NT + NP;
     static constexpr int base(int i) { return i >= NT ? 1 : (i % PER_TILE < 4 ? 0 : 2); }
     static constexpr int off(int i)
     {
@@ -236,14 +290,31 @@ struct PassPlan {
     }
 };
 
-// (P o M) of key blocks 2 jb, 2 jb + 1 as a B fragment (a block beyond the causal range contributes zeros)
-template <int NJ>
-__device__ __forceinline__ bf16x8 masked_frag(const f32x4 (&P)[NJ], const f32x4 (&mreg)[4], int jb)
+// (P o M) of key blocks 2 jb, 2 jb + 1 as a B fragment
+__device__ __forceinline__ bf16x8 masked_frag(const f32x4 &P0, const f32x4 &P1, const f32x4 (&mreg)[4], int jb)
 {
-    const f32x4 lo = P[2 * jb] * mreg[2 * jb];
-    const f32x4 hi = (2 * jb + 1 < NJ) ? P[(2 * jb + 1 < NJ) ? 2 * jb + 1 : 0] * mreg[(2 * jb + 1 < NJ) ? 2 * jb + 1 : 0]
-                                       : zero4();
-    return pack8(lo, hi);
+    return pack8(P0 * mreg[2 * jb], P1 * mreg[2 * jb + 1]);
+}
+
+// P[js] = K[js] x for the key blocks js < NJ, x given as B fragments; a rolled loop (used once per chunk)
+template <int NJ, int NX>
+__device__ __forceinline__ void key_products(const bf16x8 *sK, const bf16x8 (&x)[NX][4], f32x4 (&P)[NJ], int lane)
+{
+#pragma unroll
+    for (int js = 0; js < NJ; ++js) P[js] = zero4();
+#pragma unroll 1
+    for (int fb = 0; fb < 4; ++fb) {
+        bf16x8 a[NJ];
+#pragma unroll
+        for (int js = 0; js < NJ; ++js) a[js] = sK[(js * 4 + fb) * 64 + lane];
+        bf16x8 b[NX];
+#pragma unroll
+        for (int v = 0; v < NX; ++v) b[v] = fb == 0 ? x[v][0] : (fb == 1 ? x[v][1] : (fb == 2 ? x[v][2] : x[v][3]));
+#pragma unroll
+        for (int js = 0; js < NJ; ++js)
+#pragma unroll
+            for (int v = 0; v < NX; ++v) P[js] = mma16(a[js], b[v], P[js]);
+    }
 }
 
 // Algorithm 1 in residual form for the 16 tokens of this wave:
@@ -253,49 +324,43 @@ __device__ __forceinline__ bf16x8 masked_frag(const f32x4 (&P)[NJ], const f32x4 
 // On entry: xi = xi_{-1} = 0, dl = delta_0 = xi_0, gn = -q. On exit xi + dl is the result.
 // The loop body is one straight line of MFMA steps, each with its A fragment requested kDepth steps ahead and a slice
 // of the vector work behind it.
-template <int NJ>
+// `start_copies` is called once, after the last LDS read that the compiler knows of: it issues the copies into LDS
+// that overlap the passes.
+template <int NJ, class StartCopies>
 __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, const bf16x8 *sKT, f32x4 (&xi)[8],
                                             f32x4 (&dl)[8], f32x4 (&gn)[8], const f32x4 (&mreg)[4], float zeta,
-                                            float lam, float s0, float rho2, int n_iter, int lane)
+                                            float lam, float s0, float rho2, int n_iter, int lane,
+                                            StartCopies start_copies)
 {
     typedef PassPlan<NJ> PL;
-    constexpr int NJB = PL::NJB, NP = PL::NP, PER_TILE = PL::PER_TILE, NT = PL::NT, NS = PL::NS;
+    constexpr int NJB = PL::NJB, PER_TILE = PL::PER_TILE, NT = PL::NT, NS = PL::NS;
     // A fragments in flight. The request of step i + kDepth goes into the register that step i has just freed, also
-    // across the end of the loop body, so the depth divides the number of steps (44, 48, 60, 64).
-    constexpr int kDepth = NJ == 1 ? 4 : (NJ == 4 ? 8 : 6);
+    // across the end of the loop body, so the depth divides the number of steps (48, 64).
+    constexpr int kDepth = 4;
     static_assert(NS % kDepth == 0 && kDepth <= 15, "queue registers rotate with the loop; the LDS counter holds 15 operations");
+    if (n_iter <= 0) {
+        start_copies();
+        return;
+    }
     const uint32_t bases[3] = {lds_address(sH + lane), lds_address(sK + lane), lds_address(sKT + lane)};
     u32x4 q[kDepth];
     bf16x8 dB[4];
     f32x4 P[NJ];
-    if (n_iter <= 0) return;
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) dB[fb] = pack8(dl[2 * fb], dl[2 * fb + 1]);
-    // key products of the first pass
-    static_for<0, NP>([&](auto step) {
-        constexpr int i0 = decltype(step)::value;
-        // (in groups of kDepth)
-        if constexpr (i0 % kDepth == 0) {
-            static_for<0, kDepth>([&](auto sub) {
-                constexpr int i = i0 + decltype(sub)::value;
-                if constexpr (i < NP) lds_read16_untracked<PL::off(NT + i) * 16>(q[i % kDepth], bases[1]);
-            });
-            static_for<0, kDepth>([&](auto sub) {
-                constexpr int i = i0 + decltype(sub)::value;
-                if constexpr (i < NP) {
-                    constexpr int left = (i0 + kDepth < NP ? i0 + kDepth : NP) - 1 - i;
-                    lds_await<left>(q[i % kDepth]);
-                    constexpr int fb = i / NJ, js = i % NJ;
-                    P[js] = mma16(__builtin_bit_cast(bf16x8, q[i % kDepth]), dB[fb], fb == 0 ? zero4() : P[js]);
-                }
-            });
-        }
-    });
+    {
+        // key products of the first pass
+        bf16x8 x[1][4] = {{dB[0], dB[1], dB[2], dB[3]}};
+        key_products<NJ, 1>(sK, x, P, lane);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    start_copies();
     static_for<0, kDepth>([&](auto step) {
         constexpr int i = decltype(step)::value;
         lds_read16_untracked<PL::off(i) * 16>(q[i], bases[PL::base(i)]);
     });
     float omega = 2.0f;
+#pragma unroll 1
     for (int it = 0; it < n_iter; ++it) {
         asm volatile("" ::: "memory");
         omega = 4.0f * __builtin_amdgcn_rcpf(4.0f - rho2 * omega);           // weight schedule
@@ -338,8 +403,8 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
             }
             if constexpr (i < NT) {
                 constexpr int t = i / PER_TILE, u = i % PER_TILE;
-                if constexpr (t == 0 && u == 2) pm[0] = masked_frag<NJ>(P, mreg, 0);
-                if constexpr (t == 0 && u == 3 && NJB == 2) pm[NJB - 1] = masked_frag<NJ>(P, mreg, NJB - 1);
+                if constexpr (t == 0 && u == 2) pm[0] = masked_frag(P[0], P[1], mreg, 0);
+                if constexpr (t == 0 && u == 3 && NJB == 2) pm[NJB - 1] = masked_frag(P[NJ - 2], P[NJ - 1], mreg, NJB - 1);
                 if constexpr (u == PER_TILE - 1) sprev = s;
                 if constexpr (t >= 1) {
                     typedef std::integral_constant<int, t - 1> FT;
@@ -371,23 +436,19 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
 }
 
 // Decay mask of Section 4.2.1 in the log-space form of Appendix B.2 (base 2): M[j][c] = 2^(G_c - G_j) for j <= c.
-template <int NJ>
-__device__ __forceinline__ void build_mask(const Ctx &c, Solver &s, const ChunkGates &cg, int ts)
+__device__ __forceinline__ void build_mask(const Ctx &c, Solver &s, float G, int ts)
 {
     const int c_local = 16 * ts + c.n;
-    const float Gc = __shfl(cg.G, c_local, 64);
+    const float Gc = __shfl(G, c_local, 64);
     s.zeta = exp2f(Gc);
 #pragma unroll
     for (int js = 0; js < 4; ++js)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            if (js < NJ) {
-                const int j = 16 * js + 4 * c.kg + r;
-                const float Gj = __shfl(cg.G, j, 64);
-                s.mreg[js][r] = (j <= c_local) ? __builtin_amdgcn_exp2f(Gc - Gj) : 0.0f;
-            } else {
-                s.mreg[js][r] = 0.0f;
-            }
+            const int j = 16 * js + 4 * c.kg + r;
+            const float Gj = __shfl(G, j, 64);
+            // hardware exp2: results below the normal range (decays under 2^-126) are flushed to zero
+            s.mreg[js][r] = (j <= c_local) ? __builtin_amdgcn_exp2f(Gc - Gj) : 0.0f;
         }
 }
 
@@ -398,43 +459,38 @@ template <int NJ>
 __device__ __forceinline__ void frobenius_terms(const Ctx &c, const Solver &s, int g, int ts)
 {
     const bf16x8 *sH = lds_frags(c, kOffH + g * 32768) + c.lane;
-    const bf16x8 *sK = lds_frags(c, kOffK + g * 16384) + c.lane;
-    bf16x8 kB[4];
+    const bf16x8 *sK = lds_frags(c, kOffK + g * 16384);
+    bf16x8 kB[1][4];
 #pragma unroll
-    for (int fb = 0; fb < 4; ++fb) kB[fb] = sK[(ts * 4 + fb) * 64];
+    for (int fb = 0; fb < 4; ++fb) kB[0][fb] = sK[(ts * 4 + fb) * 64 + c.lane];
+    // this lane's elements of k_c as floats: tile ft, row r <-> slot 4 (ft & 1) + r of fragment ft / 2
+    f32x4 kc[8];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) unpack8(kB[0][fb], kc[2 * fb], kc[2 * fb + 1]);
     // k_c^T H_[n] k_c
-    float a_part = 0.0f;
+    f32x4 dot = zero4();
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-        bf16x8 a[16];
+    for (int ft = 0; ft < 8; ++ft) {
+        bf16x8 a[4];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) a[i] = sH[(half * 16 + i) * 64];
+        for (int fb = 0; fb < 4; ++fb) a[fb] = sH[(ft * 4 + fb) * 64];
+        f32x4 acc = zero4();
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int ft = 4 * half + t;
-            f32x4 acc = zero4();
-#pragma unroll
-            for (int fb = 0; fb < 4; ++fb) acc = mma16(a[t * 4 + fb], kB[fb], acc);
-            f32x4 lo, hi;
-            unpack8(kB[ft >> 1], lo, hi);
-            const f32x4 kc = (ft & 1) ? hi : lo;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) a_part += acc[r] * kc[r];
-        }
+        for (int fb = 0; fb < 4; ++fb) acc = mma16(a[fb], kB[0][fb], acc);
+        dot += acc * kc[ft];
     }
+    float a_part = dot[0] + dot[1] + dot[2] + dot[3];
     // Gram columns of this wave's tokens against the key blocks js <= ts
+    f32x4 G[NJ];
+    key_products<NJ, 1>(sK, kB, G, c.lane);
     float b_part = 0.0f, d_part = 0.0f;
 #pragma unroll
-    for (int js = 0; js < NJ; ++js) {
-        f32x4 G = zero4();
-#pragma unroll
-        for (int fb = 0; fb < 4; ++fb) G = mma16(sK[(js * 4 + fb) * 64], kB[fb], G);
+    for (int js = 0; js < NJ; ++js)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            b_part += s.mreg[js][r] * (G[r] * G[r]);
-            if (js == NJ - 1 && 4 * c.kg + r == c.n) d_part = G[r] * G[r];
+            b_part += s.mreg[js][r] * (G[js][r] * G[js][r]);
+            if (js == ts && 4 * c.kg + r == c.n) d_part = G[js][r] * G[js][r];
         }
-    }
     b_part -= d_part;                 // the sum runs over i < c: the diagonal term (M[c][c] = 1) is taken out again
     a_part = sum_over_kg(a_part);
     b_part = sum_over_kg(b_part);
@@ -463,19 +519,22 @@ __device__ __forceinline__ float frobenius_norm(const Ctx &c, const Solver &s, i
     return sqrtf(fmaxf(s.zeta * s.zeta * hn2 + f, 0.0f));
 }
 
+__device__ __forceinline__ void copy_v_rows(const Ctx &c, int g, int chunk);
+
 // Everything between the Frobenius table and the published result: the passes, then (after the workgroup has
-// passed `barrier`) xhat to LDS and the intra-chunk part of the readout.
+// passed the barrier inside) xhat to LDS and the intra-chunk part of the readout.
 template <int NJ>
-__device__ __forceinline__ void solve_tokens(const Ctx &c, Solver &s, int g, int ts, const typename IOBF16::raw4 (&qraw)[8],
-                                             float lam)
+__device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, const typename IOBF16::raw4 (&qraw)[8],
+                                             float lam, f32x4 (&accU)[8], int c0)
 {
     const bf16x8 *sH = lds_frags(c, kOffH + g * 32768);
     const bf16x8 *sK = lds_frags(c, kOffK + g * 16384);
     const bf16x8 *sKT = lds_frags(c, kOffKT + g * 16384);
     // Section 4.1: L = ||H_t||_F + lambda_t, mu = lambda_t
     const float L = s.fro + lam, mu = lam;
-    const float s0 = 2.0f / (L + mu);
-    const float rho = (L - mu) / (L + mu);
+    const float rcp = __builtin_amdgcn_rcpf(L + mu);
+    const float s0 = 2.0f * rcp;
+    const float rho = (L - mu) * rcp;
     f32x4 xi[8], dl[8], gn[8];
 #pragma unroll
     for (int ft = 0; ft < 8; ++ft) {
@@ -488,38 +547,43 @@ __device__ __forceinline__ void solve_tokens(const Ctx &c, Solver &s, int g, int
             gn[ft][r] = -qe;
         }
     }
-    cheb_passes<NJ>(sH, sK, sKT, xi, dl, gn, s.mreg, s.zeta, lam, s0, rho * rho, c.a.n_iter, c.lane);
+    cheb_passes<NJ>(sH, sK, sKT, xi, dl, gn, s.mreg, s.zeta, lam, s0, rho * rho, c.a.n_iter, c.lane, [&]() {
+        // v rows of both chunks replace the k rows; they land during the passes
+        copy_v_rows(c, 0, c0);
+        copy_v_rows(c, 1, c0 + 1);
+    });
+    refresh_lane(c);
+#ifdef GKA_FUSED_TIMERS
+    if (c.stamp && c.lane == 0) g_fused_timers[c.w * 32 + 11] = __builtin_readcyclecounter();
+#endif
 #pragma unroll
     for (int ft = 0; ft < 8; ++ft) xi[ft] += dl[ft];
 
     // ---- readout, intra-chunk part: sum_{j<=c} M[j,c] v_j (k_j . xhat_c), xhat as value + remainder
-    bf16x8 xv[4], xr[4];
+    bf16x8 x[2][4];
 #pragma unroll
-    for (int fb = 0; fb < 4; ++fb) split8(xi[2 * fb], xi[2 * fb + 1], xv[fb], xr[fb]);
+    for (int fb = 0; fb < 4; ++fb) split8(xi[2 * fb], xi[2 * fb + 1], x[0][fb], x[1][fb]);
     f32x4 P[NJ];
-#pragma unroll
-    for (int js = 0; js < NJ; ++js) {
-        P[js] = zero4();
-#pragma unroll
-        for (int fb = 0; fb < 4; ++fb) {
-            const bf16x8 a = sK[(js * 4 + fb) * 64 + c.lane];
-            P[js] = mma16(a, xv[fb], P[js]);
-            P[js] = mma16(a, xr[fb], P[js]);
-        }
-    }
-    constexpr int NJB = (NJ + 1) / 2;
+    key_products<NJ, 2>(sK, x, P, c.lane);
+    constexpr int NJB = NJ / 2;
     bf16x8 pm[NJB];
 #pragma unroll
-    for (int jb = 0; jb < NJB; ++jb) pm[jb] = masked_frag<NJ>(P, s.mreg, jb);
-
+    for (int jb = 0; jb < NJB; ++jb) pm[jb] = masked_frag(P[2 * jb], P[2 * jb + 1], s.mreg, jb);
+#ifdef GKA_FUSED_TIMERS
+    if (c.stamp && c.lane == 0) g_fused_timers[c.w * 32 + 12] = __builtin_readcyclecounter();
+#endif
     wait_all_memory();               // this wave's copies of v rows have landed
     lds_barrier();                   // all of them have; every wave is through its passes: H_[n] is dead
+#ifdef GKA_FUSED_TIMERS
+    if (c.stamp && c.lane == 0) g_fused_timers[c.w * 32 + 23] = __builtin_readcyclecounter();
+#endif
     bf16x8 *sX = lds_frags(c, kOffH + g * 32768) + c.lane;
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) {
-        sX[((ts * 2 + 0) * 4 + fb) * 64] = xv[fb];
-        sX[((ts * 2 + 1) * 4 + fb) * 64] = xr[fb];
+        sX[((ts * 2 + 0) * 4 + fb) * 64] = x[0][fb];
+        sX[((ts * 2 + 1) * 4 + fb) * 64] = x[1][fb];
     }
+    park_load(c.park, accU);         // U comes back while the last products of this phase run
     const uint16_t *rowsV = lds_rows(c, g);
 #pragma unroll
     for (int ft = 0; ft < 8; ++ft) {
@@ -595,7 +659,7 @@ __device__ __forceinline__ void copy_v_rows(const Ctx &c, int g, int chunk)
 // wave builds four of the 32 fragments of either kind.
 __device__ __forceinline__ void build_key_frags(const Ctx &c)
 {
-#pragma unroll
+#pragma unroll 1
     for (int q = 0; q < 4; ++q) {
         const int idx = c.w * 4 + q;
         const int g = idx >> 4, f = idx & 15;
@@ -684,36 +748,58 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
     const int grp = c.w >> 2;                               // solver role: chunk of the pair
     const int ts = grp ? 3 - (c.w & 3) : (c.w & 3);         // ... and token block (a light and a heavy one per SIMD)
 
-    f32x4 accH[8], accU[8];
-    load_start_state(c, accH, accU, pair, seg);
-    KRowRegs kr;
-    load_k_rows(c, kr, chunk_begin);
+    c.park = (f32x4 *)a.park + ((int64_t)blockIdx.x * 8 + c.w) * (8 * 64) + c.lane;
+    f32x4 accH[8];
+    {
+        f32x4 accU[8];
+        load_start_state(c, accH, accU, pair, seg);
+        park_store(c.park, accU);
+    }
+    {
+        KRowRegs kr;
+        load_k_rows(c, kr, chunk_begin);
+        store_k_rows(c, kr);
+    }
     float *sTab = (float *)(smem + kOffTab);
 
+    const bool wide = ts >= 2;                              // which instantiation of the solver code this wave runs
+    float gmA = a.gate[c.gate_base + (int64_t)min(chunk_begin * kChunk + c.lane, a.T - 1) * a.H];
+    float gmB = a.gate[c.gate_base + (int64_t)min((chunk_begin + 1) * kChunk + c.lane, a.T - 1) * a.H];
+#pragma unroll 1
     for (int c0 = chunk_begin; c0 < chunk_end; c0 += 2) {
+        // Addresses are formed anew in every iteration from a copy of the lane index that the compiler cannot trace
+        // back: hoisted out of the loop they would occupy registers across the passes (or be spilled and reloaded).
+        refresh_lane(c);
+#ifdef GKA_FUSED_TIMERS
+        c.stamp = blockIdx.x == 100 && c0 == chunk_begin + 4;
+#endif
         // ---- 1
-        store_k_rows(c, kr);
+        GKA_FT(0);
         const float hnA = publish_H(c, accH, 0);
-        const ChunkGates cgA = scan_gates(c, c0 * kChunk), cgB = scan_gates(c, (c0 + 1) * kChunk);
-        const float wjA = (c0 * kChunk + c.lane < c.T_eff) ? exp2f(cgA.Gtot - cgA.G) : 0.0f;
-        const float wjB = ((c0 + 1) * kChunk + c.lane < c.T_eff) ? exp2f(cgB.Gtot - cgB.G) : 0.0f;
-        const float zetaA = exp2f(cgA.Gtot), zetaB = exp2f(cgB.Gtot);
+        // gates of both chunks (fetched during the previous iteration): lane j holds G_j, the weight of token j in the
+        // chunk's update 2^(G_C - G_j), and the chunk's decay
+        float GA, GB, wjA, wjB, zetaA, zetaB;
+        auto gate_scans = [&]() {
+            const bool vA = c0 * kChunk + c.lane < c.T_eff, vB = (c0 + 1) * kChunk + c.lane < c.T_eff;
+            GA = wave_inclusive_scan(vA ? log2_gate(gmA) : 0.0f, c.lane);
+            GB = wave_inclusive_scan(vB ? log2_gate(gmB) : 0.0f, c.lane);
+            const float GtA = lane_value(GA, 63), GtB = lane_value(GB, 63);
+            wjA = vA ? exp2f(GtA - GA) : 0.0f;
+            wjB = vB ? exp2f(GtB - GB) : 0.0f;
+            zetaA = exp2f(GtA);
+            zetaB = exp2f(GtB);
+        };
+        gate_scans();
+        GKA_FT(1);
         lds_barrier();
         // ---- 2
+        GKA_FT(2);
         build_key_frags(c);
         bf16x8 wBA[2], wBB[2];
         own_weighted_frags(c, lds_rows(c, 0), wjA, wBA);
         own_weighted_frags(c, lds_rows(c, 1), wjB, wBB);
-        lds_barrier();
-        // ---- 3
-        advance_state(c, accH, 0, zetaA, wBA);
-        const float hnB = publish_H(c, accH, 1);
-        advance_state(c, accH, 1, zetaB, wBB);
-        if (c.lane == 0) {
-            sTab[128 + c.w] = hnA;
-            sTab[128 + 8 + c.w] = hnB;
-        }
         // solver inputs of this lane's token
+        f32x4 accU[8];
         Solver s;
         s.tok = (c0 + grp) * kChunk + 16 * ts + c.n;
         s.valid = s.tok < c.T_eff;
@@ -722,65 +808,86 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
         for (int ft = 0; ft < 8; ++ft) qraw[ft] = IOBF16::load_raw4(a.q, tok_off + 16 * ft + 4 * c.kg);
         float lam = a.lambda[c.gate_base + (int64_t)min(s.tok, a.T - 1) * a.H];
-        if (!s.valid) lam = 1.0f;
-        const ChunkGates &cg = grp ? cgB : cgA;
-        switch (ts) {
-        case 0: build_mask<1>(c, s, cg, ts); break;
-        case 1: build_mask<2>(c, s, cg, ts); break;
-        case 2: build_mask<3>(c, s, cg, ts); break;
-        default: build_mask<4>(c, s, cg, ts); break;
+        GKA_FT(3);
+        lds_barrier();
+        // ---- 3
+        GKA_FT(4);
+        advance_state(c, accH, 0, zetaA, wBA);
+        const float hnB = publish_H(c, accH, 1);
+        advance_state(c, accH, 1, zetaB, wBB);
+        if (c.lane == 0) {
+            sTab[128 + c.w] = hnA;
+            sTab[128 + 8 + c.w] = hnB;
         }
+        build_mask(c, s, grp ? GB : GA, ts);
+        GKA_FT(5);
         lds_barrier();
         // ---- 4
-        switch (ts) {
-        case 0: frobenius_terms<1>(c, s, grp, ts); break;
-        case 1: frobenius_terms<2>(c, s, grp, ts); break;
-        case 2: frobenius_terms<3>(c, s, grp, ts); break;
-        default: frobenius_terms<4>(c, s, grp, ts); break;
-        }
+        GKA_FT(6);
+        if (wide) frobenius_terms<4>(c, s, grp, ts);
+        else frobenius_terms<2>(c, s, grp, ts);
+        GKA_FT(7);
         lds_barrier();
         // ---- 5
-        switch (ts) {
-        case 0: s.fro = frobenius_norm<1>(c, s, grp); break;
-        case 1: s.fro = frobenius_norm<2>(c, s, grp); break;
-        case 2: s.fro = frobenius_norm<3>(c, s, grp); break;
-        default: s.fro = frobenius_norm<4>(c, s, grp); break;
-        }
+        GKA_FT(8);
+        s.fro = wide ? frobenius_norm<4>(c, s, grp) : frobenius_norm<2>(c, s, grp);
         if (a.fro_out && s.valid && c.kg == 0) a.fro_out[c.gate_base + (int64_t)s.tok * a.H] = s.fro;
-        lds_barrier();                   // the table is dead
-        // v rows replace the k rows; they land during the passes
-        copy_v_rows(c, 0, c0);
-        copy_v_rows(c, 1, c0 + 1);
-        switch (ts) {
-        case 0: solve_tokens<1>(c, s, grp, ts, qraw, lam); break;
-        case 1: solve_tokens<2>(c, s, grp, ts, qraw, lam); break;
-        case 2: solve_tokens<3>(c, s, grp, ts, qraw, lam); break;
-        default: solve_tokens<4>(c, s, grp, ts, qraw, lam); break;
-        }
-        if (c0 + 2 < chunk_end) load_k_rows(c, kr, c0 + 2);
-        // this wave's weighted v fragments of both chunks (the v rows stay until the end of the iteration)
+        if (!s.valid) lam = 1.0f;
+        GKA_FT(9);
+        lds_barrier();                   // the table is dead: the row tiles may be overwritten
+        GKA_FT(10);
+        if (wide) solve_tokens<4>(c, s, grp, ts, qraw, lam, accU, c0);
+        else solve_tokens<2>(c, s, grp, ts, qraw, lam, accU, c0);
+        GKA_FT(13);
+        // (the gates are scanned again rather than kept across the passes: two registers instead of six; an opaque
+        // copy keeps the compiler from merging the two scans)
+        asm volatile("" : "+v"(gmA), "+v"(gmB));
+        gate_scans();
+        // this wave's weighted v fragments of both chunks
         bf16x8 wVA[2], wVB[2];
         own_weighted_frags(c, lds_rows(c, 0), wjA, wVA);
         own_weighted_frags(c, lds_rows(c, 1), wjB, wVB);
+        GKA_FT(14);
         lds_barrier();                   // xhat of both chunks is visible; the key-row fragments are dead
         // ---- 6
+        GKA_FT(15);
+        // k rows and gates of the next two chunks
+        KRowRegs kr;
+        if (c0 + 2 < chunk_end) {
+            load_k_rows(c, kr, c0 + 2);
+            gmA = a.gate[c.gate_base + (int64_t)min((c0 + 2) * kChunk + c.lane, a.T - 1) * a.H];
+            gmB = a.gate[c.gate_base + (int64_t)min((c0 + 3) * kChunk + c.lane, a.T - 1) * a.H];
+        }
         readout_state(c, accU, 0);
         advance_state(c, accU, 0, zetaA, wVA);
+        GKA_FT(16);
         lds_barrier();
         // ---- 7
+        GKA_FT(17);
         if (grp == 0) store_output(c, s, ts);
+        GKA_FT(18);
         lds_barrier();
         // ---- 8
+        GKA_FT(19);
         readout_state(c, accU, 1);
         advance_state(c, accU, 1, zetaB, wVB);
+        park_store(c.park, accU);
+        // k rows of the next two chunks (fetched since the passes ended) go to the row tiles, which are free since
+        // the barrier before the readout
+        if (c0 + 2 < chunk_end) store_k_rows(c, kr);
+        GKA_FT(20);
         lds_barrier();
         // ---- 9
+        GKA_FT(21);
         if (grp == 1) store_output(c, s, ts);
+        GKA_FT(22);
     }
 
     if (a.H_final && seg == a.n_segs - 1) {
         float *Hf = a.H_final + (int64_t)pair * kD * kD;
         float *Uf = a.U_final + (int64_t)pair * kD * kD;
+        f32x4 accU[8];
+        park_load(c.park, accU);
 #pragma unroll
         for (int jt = 0; jt < 8; ++jt) {
             *(f32x4 *)(Hf + (int64_t)(16 * c.w + c.n) * kD + 16 * jt + 4 * c.kg) = accH[jt];
@@ -881,15 +988,19 @@ __global__ __launch_bounds__(kFusedThreads) void fused_summary_kernel(FusedArgs 
 
 size_t fused_workspace_bytes(int n_pairs, int n_segs)
 {
-    // per (pair, segment): Delta H, Delta U in the kernels' tile order, and the segment's log2 decay
-    return (size_t)n_pairs * n_segs * (2 * kD * kD * sizeof(float)) + (((size_t)n_pairs * n_segs * sizeof(float) + 255) / 256) * 256;
+    // per (pair, segment): Delta H, Delta U in the kernels' tile order, the segment's log2 decay, and the scratch
+    // block that holds U between its uses
+    const size_t n = (size_t)n_pairs * n_segs;
+    return n * (2 * kD * kD * sizeof(float)) + ((n * sizeof(float) + 255) / 256) * 256 + n * (kD * kD * sizeof(float));
 }
 
 hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_t stream)
 {
     FusedArgs a = a0;
     a.seg_buf = (float *)workspace;
-    a.seg_logdecay = (float *)((char *)workspace + (size_t)a.n_pairs * a.n_segs * (2 * kD * kD * sizeof(float)));
+    const size_t n = (size_t)a.n_pairs * a.n_segs;
+    a.seg_logdecay = (float *)((char *)workspace + n * (2 * kD * kD * sizeof(float)));
+    a.park = (float *)((char *)a.seg_logdecay + ((n * sizeof(float) + 255) / 256) * 256);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)fused_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,

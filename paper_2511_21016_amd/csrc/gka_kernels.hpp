@@ -152,7 +152,7 @@ struct FusedArgs {
     int H, T, n_iter;
     int n_pairs, n_chunks;
     int n_segs, seg_len;          // segments of the chunk walk per pair (one workgroup each), chunks per segment
-    float *seg_buf, *seg_logdecay; // set by the launcher (carved from the workspace)
+    float *seg_buf, *seg_logdecay, *park; // set by the launcher (carved from the workspace)
 };
 size_t fused_workspace_bytes(int n_pairs, int n_segs);
 hipError_t launch_fused_forward(const FusedArgs &a, void *workspace, hipStream_t stream);
