@@ -519,7 +519,7 @@ __device__ __forceinline__ float frobenius_norm(const Ctx &c, const Solver &s, i
     return sqrtf(fmaxf(s.zeta * s.zeta * hn2 + f, 0.0f));
 }
 
-__device__ __forceinline__ void copy_v_rows(const Ctx &c, int g, int chunk);
+__device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, int chunk);
 
 // Everything between the Frobenius table and the published result: the passes, then (after the workgroup has
 // passed the barrier inside) xhat to LDS and the intra-chunk part of the readout.
@@ -549,8 +549,8 @@ __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, c
     }
     cheb_passes<NJ>(sH, sK, sKT, xi, dl, gn, s.mreg, s.zeta, lam, s0, rho * rho, c.a.n_iter, c.lane, [&]() {
         // v rows of both chunks replace the k rows; they land during the passes
-        copy_v_rows(c, 0, c0);
-        copy_v_rows(c, 1, c0 + 1);
+        copy_rows(c, c.a.v, 0, c0);
+        copy_rows(c, c.a.v, 1, c0 + 1);
     });
     refresh_lane(c);
 #ifdef GKA_FUSED_TIMERS
@@ -613,36 +613,14 @@ __device__ __forceinline__ void store_output(const Ctx &c, const Solver &s, int 
 
 // ---- data movement ---------------------------------------------------------------------------------------------
 
-// k rows of the two chunks starting at chunk c0: global -> registers (four 16-byte pieces per thread)
-struct KRowRegs {
-    uint4 r[4];
-};
-__device__ __forceinline__ void load_k_rows(const Ctx &c, KRowRegs &kr, int c0)
-{
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int p = i * kFusedThreads + c.tid;
-        const int g = p >> 10, row = (p & 1023) >> 4, piece = p & 15;
-        const int tok = min((c0 + g) * kChunk + row, c.a.T - 1);
-        kr.r[i] = *(const uint4 *)((const uint16_t *)c.a.k + c.base_bh + (int64_t)tok * c.a.stride_t + 8 * piece);
-    }
-}
-__device__ __forceinline__ void store_k_rows(const Ctx &c, const KRowRegs &kr)
-{
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int p = i * kFusedThreads + c.tid;
-        const int g = p >> 10, row = (p & 1023) >> 4, piece = p & 15;
-        *(uint4 *)(lds_rows(c, g) + Rows()(row, 8 * piece)) = kr.r[i];
-    }
-}
-// v rows of chunk `chunk` into row tile g: direct copies global -> LDS, 1 KiB (four rows) per wave instruction; the
-// lane picks the 16 source bytes that belong at its place of the swizzled row. Rows past the end of the sequence
-// repeat the last row (finite values that only ever meet zero weights).
-__device__ __forceinline__ void copy_v_rows(const Ctx &c, int g, int chunk)
+// Rows of chunk `chunk` of x (k or v) into row tile g: direct copies global -> LDS without staging registers, 1 KiB
+// (four rows) per wave instruction; the lane picks the 16 source bytes that belong at its place of the swizzled row.
+// Rows past the end of the sequence repeat the last row (finite values that only ever meet zero weights or masked
+// products). The copies complete in the background; the compiler waits for them before the next LDS read it knows of.
+__device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, int chunk)
 {
     const int tok_base = min(chunk * kChunk, c.a.T - 1);
-    const uint16_t *base = (const uint16_t *)c.a.v + c.base_bh + (int64_t)tok_base * c.a.stride_t;
+    const uint16_t *base = (const uint16_t *)x + c.base_bh + (int64_t)tok_base * c.a.stride_t;
     const buffer_rsrc rsrc = make_raw_buffer(base);
     const int last_row = c.a.T - 1 - tok_base;
     const int row_bytes = (int)c.a.stride_t * 2;
@@ -720,14 +698,14 @@ __device__ __forceinline__ void load_start_state(const Ctx &c, f32x4 (&accH)[8],
 
 // One workgroup per (pair, segment of chunks). Per iteration (chunks A = c0, B = c0 + 1), with the barriers between
 // the phases:
-//   1. k rows (registers, fetched during the previous iteration) -> row tiles; H_[n] of A -> LDS
+//   1. H_[n] of A -> LDS, gate scans (the k rows, copied global -> LDS since the end of the previous iteration, land)
 //   2. key fragments of both chunks; this wave's weighted k fragments
 //   3. H advanced over A; H_[n] of B -> LDS; H advanced over B; partial norms -> table (in the dead k row tile)
 //   4. solver: Frobenius terms -> table
 //   5. solver: norms; copies of the v rows into the row tiles start; passes, intra-chunk readout products;
-//      xhat -> LDS (over H_[n]); fetch of the next k rows
+//      xhat -> LDS (over H_[n])
 //   6. state part of the readout for A (over the key fragments), U advanced over A;  7. solver A stores
-//   8. the same for B;  9. solver B stores
+//   8. the same for B;  9. solver B stores; copies of the next k rows into the row tiles start
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -755,11 +733,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         load_start_state(c, accH, accU, pair, seg);
         park_store(c.park, accU);
     }
-    {
-        KRowRegs kr;
-        load_k_rows(c, kr, chunk_begin);
-        store_k_rows(c, kr);
-    }
+    copy_rows(c, a.k, 0, chunk_begin);
+    copy_rows(c, a.k, 1, chunk_begin + 1);
     float *sTab = (float *)(smem + kOffTab);
 
     const bool wide = ts >= 2;                              // which instantiation of the solver code this wave runs
@@ -791,7 +766,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         };
         gate_scans();
         GKA_FT(1);
-        lds_barrier();
+        wait_all_memory();               // this wave's copies of k rows have landed
+        lds_barrier();                   // ... and everybody else's
         // ---- 2
         GKA_FT(2);
         build_key_frags(c);
@@ -851,14 +827,12 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         lds_barrier();                   // xhat of both chunks is visible; the key-row fragments are dead
         // ---- 6
         GKA_FT(15);
-        // k rows and gates of the next two chunks
-        KRowRegs kr;
-        if (c0 + 2 < chunk_end) {
-            load_k_rows(c, kr, c0 + 2);
-            gmA = a.gate[c.gate_base + (int64_t)min((c0 + 2) * kChunk + c.lane, a.T - 1) * a.H];
-            gmB = a.gate[c.gate_base + (int64_t)min((c0 + 3) * kChunk + c.lane, a.T - 1) * a.H];
-        }
+        // gates of the next two chunks
+        gmA = a.gate[c.gate_base + (int64_t)min((c0 + 2) * kChunk + c.lane, a.T - 1) * a.H];
+        gmB = a.gate[c.gate_base + (int64_t)min((c0 + 3) * kChunk + c.lane, a.T - 1) * a.H];
+        GKA_FT(24);
         readout_state(c, accU, 0);
+        GKA_FT(25);
         advance_state(c, accU, 0, zetaA, wVA);
         GKA_FT(16);
         lds_barrier();
@@ -870,18 +844,23 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         // ---- 8
         GKA_FT(19);
         readout_state(c, accU, 1);
+        GKA_FT(26);
         advance_state(c, accU, 1, zetaB, wVB);
+        GKA_FT(27);
         park_store(c.park, accU);
-        // k rows of the next two chunks (fetched since the passes ended) go to the row tiles, which are free since
-        // the barrier before the readout
-        if (c0 + 2 < chunk_end) store_k_rows(c, kr);
+        GKA_FT(28);
         GKA_FT(20);
         lds_barrier();
         // ---- 9
         GKA_FT(21);
         if (grp == 1) store_output(c, s, ts);
+        // k rows of the next two chunks: the row tiles are free since the barrier before the readout; the copies land
+        // while the next iteration publishes H and scans its gates
+        copy_rows(c, a.k, 0, c0 + 2);
+        copy_rows(c, a.k, 1, c0 + 3);
         GKA_FT(22);
     }
+    wait_all_memory();               // no copy into this workgroup's LDS may be in flight when it ends
 
     if (a.H_final && seg == a.n_segs - 1) {
         float *Hf = a.H_final + (int64_t)pair * kD * kD;
@@ -897,16 +876,16 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 }
 
 // Summary (prod gamma, Delta H, Delta U from a zero state) of every segment but the last: the start states of the
-// fused kernel's workgroups follow from these by a short scan.
-__global__ __launch_bounds__(kFusedThreads) void fused_summary_kernel(FusedArgs a)
+// fused kernel's workgroups follow from these by a short scan. Two chunks per iteration; their k and v rows are fetched
+// one iteration ahead into registers and stored into the other half of a double buffer, so an iteration is one barrier
+// followed by wave-local work: every wave reads the transposed operands of its tiles straight from the row tiles.
+constexpr int kSummaryLds = 2 * 2 * 2 * 16384;             // [buffer][chunk of the pair][k, v] row tiles
+__global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_summary_kernel(FusedArgs a)
 {
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[3 * 16384];     // k rows, v rows, transposed keys
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     Ctx c{a, smem};
-    c.tid = threadIdx.x;
-    c.lane = c.tid & 63;
-    c.w = __builtin_amdgcn_readfirstlane(c.tid >> 6);
-    c.n = c.lane & 15;
-    c.kg = c.lane >> 4;
+    c.w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    refresh_lane(c);
     const int pair = blockIdx.x % a.n_pairs, seg = blockIdx.x / a.n_pairs;
     const int b = pair / a.H, h = pair % a.H;
     c.base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
@@ -914,8 +893,6 @@ __global__ __launch_bounds__(kFusedThreads) void fused_summary_kernel(FusedArgs 
     const int chunk_begin = seg * a.seg_len;
     const int chunk_end = min(chunk_begin + a.seg_len, a.n_chunks);
     c.T_eff = min(a.T, chunk_end * kChunk);
-    uint16_t *rowsK = (uint16_t *)smem, *rowsV = (uint16_t *)(smem + 16384);
-    bf16x8 *sKT = (bf16x8 *)(smem + 32768);
 
     f32x4 accH[8], accU[8];
 #pragma unroll
@@ -923,58 +900,61 @@ __global__ __launch_bounds__(kFusedThreads) void fused_summary_kernel(FusedArgs 
         accH[jt] = zero4();
         accU[jt] = zero4();
     }
-    // rows of one chunk: two 16-byte pieces of k and two of v per thread, fetched one chunk ahead
-    uint4 kr[2], vr[2];
-    auto fetch = [&](int chunk) {
+    // piece i of a thread: tile (g = i / 4, which = (i / 2) % 2), 16 bytes of row (i % 2) * 32 + tid / 16
+    u32x4 regs[8];                       // (a native vector type: arrays of HIP's uint4 struct stay in memory)
+    float gm[2];
+    auto fetch = [&](int c0) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int p = i * kFusedThreads + c.tid;
-            const int row = p >> 4, piece = p & 15;
-            const int tok = min(chunk * kChunk + row, a.T - 1);
-            const int64_t off = c.base_bh + (int64_t)tok * a.stride_t + 8 * piece;
-            kr[i] = *(const uint4 *)((const uint16_t *)a.k + off);
-            vr[i] = *(const uint4 *)((const uint16_t *)a.v + off);
+        for (int i = 0; i < 8; ++i) {
+            const int g = i >> 2, which = (i >> 1) & 1;
+            const int row = (i & 1) * 32 + (c.tid >> 4), piece = c.tid & 15;
+            const int tok = min((c0 + g) * kChunk + row, a.T - 1);
+            const uint16_t *x = (const uint16_t *)(which ? a.v : a.k);
+            regs[i] = *(const u32x4 *)(x + c.base_bh + (int64_t)tok * a.stride_t + 8 * piece);
         }
+#pragma unroll
+        for (int g = 0; g < 2; ++g) gm[g] = a.gate[c.gate_base + (int64_t)min((c0 + g) * kChunk + c.lane, a.T - 1) * a.H];
     };
     float Gseg = 0.0f;
     fetch(chunk_begin);
-    for (int ch = chunk_begin; ch < chunk_end; ++ch) {
-        lds_barrier();                   // the previous chunk's operand reads are done
+    int buf = 0;
+#pragma unroll 1
+    for (int c0 = chunk_begin; c0 < chunk_end; c0 += 2, buf ^= 1) {
+        refresh_lane(c);
+        unsigned char *tiles = smem + buf * (4 * 16384);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int p = i * kFusedThreads + c.tid;
-            const int row = p >> 4, piece = p & 15;
-            *(uint4 *)(rowsK + Rows()(row, 8 * piece)) = kr[i];
-            *(uint4 *)(rowsV + Rows()(row, 8 * piece)) = vr[i];
+        for (int i = 0; i < 8; ++i) {
+            const int row = (i & 1) * 32 + (c.tid >> 4), piece = c.tid & 15;
+            *(u32x4 *)((uint16_t *)(tiles + (i >> 1) * 16384) + Rows()(row, 8 * piece)) = regs[i];
         }
-        if (ch + 1 < chunk_end) fetch(ch + 1);
-        const ChunkGates cg = scan_gates(c, ch * kChunk);
-        Gseg += cg.Gtot;
-        const float wj = (ch * kChunk + c.lane < c.T_eff) ? exp2f(cg.Gtot - cg.G) : 0.0f;
-        const float zetaC = exp2f(cg.Gtot);
-        lds_barrier();
+        const float gm0 = gm[0], gm1 = gm[1];
+        lds_barrier();                   // the tiles are complete; the other buffer's readers are done
+        fetch(c0 + 2);                   // (past the end of the segment: harmless reads of rows that exist)
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int f = c.w * 2 + q;
-            const int ft = f >> 1, jb = f & 1;
-            const int t0 = 32 * jb + 4 * c.kg;
-            sKT[f * 64 + c.lane] = gather_transposed_bf16(rowsK, Rows(), 16 * ft, c.lane, t0, t0 + 16);
-        }
-        bf16x8 wK[2], wV[2];
-        own_weighted_frags(c, rowsK, wj, wK);
-        own_weighted_frags(c, rowsV, wj, wV);
-        lds_barrier();
-        bf16x8 af[16];
+        for (int g = 0; g < 2; ++g) {
+            const bool valid = (c0 + g) * kChunk + c.lane < c.T_eff;
+            const float G = wave_inclusive_scan(valid ? log2_gate(g ? gm1 : gm0) : 0.0f, c.lane);
+            const float Gtot = lane_value(G, 63);
+            Gseg += Gtot;
+            const float wj = valid ? exp2f(Gtot - G) : 0.0f;
+            const float zetaC = exp2f(Gtot);
+            const uint16_t *rowsK = (const uint16_t *)(tiles + (2 * g + 0) * 16384);
+            const uint16_t *rowsV = (const uint16_t *)(tiles + (2 * g + 1) * 16384);
+            bf16x8 wK[2], wV[2];
+            own_weighted_frags(c, rowsK, wj, wK);
+            own_weighted_frags(c, rowsV, wj, wV);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) af[i] = sKT[i * 64 + c.lane];
+            for (int jt = 0; jt < 8; ++jt) {
+                accH[jt] *= zetaC;
+                accU[jt] *= zetaC;
 #pragma unroll
-        for (int jt = 0; jt < 8; ++jt) {
-            accH[jt] *= zetaC;
-            accU[jt] *= zetaC;
-            accH[jt] = mma16(af[2 * jt], wK[0], accH[jt]);
-            accU[jt] = mma16(af[2 * jt], wV[0], accU[jt]);
-            accH[jt] = mma16(af[2 * jt + 1], wK[1], accH[jt]);
-            accU[jt] = mma16(af[2 * jt + 1], wV[1], accU[jt]);
+                for (int st = 0; st < 2; ++st) {
+                    const int t0 = 32 * st + 4 * c.kg;
+                    const bf16x8 kt = gather_transposed_bf16(rowsK, Rows(), 16 * jt, c.lane, t0, t0 + 16);
+                    accH[jt] = mma16(kt, wK[st], accH[jt]);
+                    accU[jt] = mma16(kt, wV[st], accU[jt]);
+                }
+            }
         }
     }
     f32x4 *t = (f32x4 *)a.seg_buf + ((int64_t)(pair * a.n_segs + seg) * 2) * 4096 + (c.w * 8) * 64 + c.lane;
@@ -1006,11 +986,13 @@ hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_
         hipError_t e = hipFuncSetAttribute((const void *)fused_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            kLdsBytes);
         if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void *)fused_summary_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kSummaryLds);
+        if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (a.n_segs > 1) {
-        hipLaunchKernelGGL(fused_summary_kernel, dim3((unsigned)(a.n_pairs * (a.n_segs - 1))), dim3(kFusedThreads), 0,
-                           stream, a);
+        hipLaunchKernelGGL(fused_summary_kernel, dim3((unsigned)(a.n_pairs * (a.n_segs - 1))), dim3(kFusedThreads),
+                           kSummaryLds, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
