@@ -360,9 +360,17 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
         lds_read16_untracked<PL::off(i) * 16>(q[i], bases[PL::base(i)]);
     });
     float omega = 2.0f;
+    // A SIMD runs one wave of each instantiation. The one with more products per pass gets the higher priority for
+    // the first seven tenths of the passes, so that the two finish together (measured: with equal priorities the
+    // lighter wave finishes a third earlier, with the priority held throughout it finishes a fifth later; alone on
+    // its SIMD a wave runs at half the rate of the two together).
+    constexpr bool kBoost = false;
+    if (kBoost && NJ == 4) __builtin_amdgcn_s_setprio(1);
+    const int prio_passes = (7 * n_iter) / 10;
 #pragma unroll 1
     for (int it = 0; it < n_iter; ++it) {
         asm volatile("" ::: "memory");
+        if (kBoost && NJ == 4 && it == prio_passes) __builtin_amdgcn_s_setprio(0);
         omega = 4.0f * __builtin_amdgcn_rcpf(4.0f - rho2 * omega);           // weight schedule
         const float cm = omega - 1.0f, ncs = -omega * s0, ncl = ncs * lam;
         bf16x8 pm[NJB];
@@ -431,6 +439,7 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
             __builtin_amdgcn_sched_barrier(0);
         });
     }
+    if (kBoost && NJ == 4) __builtin_amdgcn_s_setprio(0);
     // the reads issued for a pass that does not follow must have landed before their registers are used again
     static_for<0, kDepth>([&](auto step) { lds_await<0>(q[decltype(step)::value]); });
 }
@@ -723,8 +732,10 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
     const int chunk_end = min(chunk_begin + a.seg_len, a.n_chunks);
     if (chunk_begin >= chunk_end) return;
     c.T_eff = min(a.T, chunk_end * kChunk);
-    const int grp = c.w >> 2;                               // solver role: chunk of the pair
-    const int ts = grp ? 3 - (c.w & 3) : (c.w & 3);         // ... and token block (a light and a heavy one per SIMD)
+    // Solver role: chunk of the pair and token block. Waves w and w + 4 share a SIMD, whose arbiter prefers the older
+    // one: waves 0-3 take the token blocks with more key blocks (ts = 2, 3), waves 4-7 the others.
+    const int grp = (c.w >> 1) & 1;
+    const int ts = (c.w < 4 ? 2 : 0) + (c.w & 1);
 
     c.park = (f32x4 *)a.park + ((int64_t)blockIdx.x * 8 + c.w) * (8 * 64) + c.lane;
     f32x4 accH[8];
