@@ -364,13 +364,13 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
     // the first seven tenths of the passes, so that the two finish together (measured: with equal priorities the
     // lighter wave finishes a third earlier, with the priority held throughout it finishes a fifth later; alone on
     // its SIMD a wave runs at half the rate of the two together).
-    constexpr bool kBoost = false;
-    if (kBoost && NJ == 4) __builtin_amdgcn_s_setprio(1);
-    const int prio_passes = (7 * n_iter) / 10;
+    constexpr bool kBoost = NJ == 2;
+    if (kBoost) __builtin_amdgcn_s_setprio(1);
+    const int prio_passes = n_iter / 2;
 #pragma unroll 1
     for (int it = 0; it < n_iter; ++it) {
         asm volatile("" ::: "memory");
-        if (kBoost && NJ == 4 && it == prio_passes) __builtin_amdgcn_s_setprio(0);
+        if (kBoost && it == prio_passes) __builtin_amdgcn_s_setprio(0);
         omega = 4.0f * __builtin_amdgcn_rcpf(4.0f - rho2 * omega);           // weight schedule
         const float cm = omega - 1.0f, ncs = -omega * s0, ncl = ncs * lam;
         bf16x8 pm[NJB];
@@ -439,7 +439,7 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
             __builtin_amdgcn_sched_barrier(0);
         });
     }
-    if (kBoost && NJ == 4) __builtin_amdgcn_s_setprio(0);
+    if (kBoost) __builtin_amdgcn_s_setprio(0);
     // the reads issued for a pass that does not follow must have landed before their registers are used again
     static_for<0, kDepth>([&](auto step) { lds_await<0>(q[decltype(step)::value]); });
 }
