@@ -212,32 +212,35 @@ __device__ __forceinline__ float publish_H(const Ctx &c, const f32x4 (&accH)[8],
 #pragma unroll
         for (int r = 0; r < 4; ++r) ss += accH[2 * fb][r] * accH[2 * fb][r] + accH[2 * fb + 1][r] * accH[2 * fb + 1][r];
     }
-    return wave_sum(ss);
+    return lane_value(wave_inclusive_scan(ss, c.lane), 63);      // (DPP moves: no LDS round trips)
 }
 
 // State part of the readout for all 64 tokens of chunk g: rows 16 w .. of U_[n] xhat, with U and xhat as rounded
-// value + remainder (three products), to the exchange region as [ts][w][lane] float4.
-__device__ __forceinline__ void readout_state(const Ctx &c, const f32x4 (&accU)[8], int g)
+// value + remainder (three products), to the exchange region at byte offset y_off as [ts][w][lane] float4. The
+// fragments of the next token block are requested before the products of the current one.
+__device__ __forceinline__ void readout_state(const Ctx &c, const f32x4 (&accU)[8], int g, int y_off)
 {
     bf16x8 Uv[4], Ur[4];
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) split8(accU[2 * fb], accU[2 * fb + 1], Uv[fb], Ur[fb]);
     const bf16x8 *sX = lds_frags(c, kOffH + g * 32768) + c.lane;
-    f32x4 *sY = (f32x4 *)(c.smem + kOffK) + c.w * 64 + c.lane;
-#pragma unroll 1
-    for (int ts = 0; ts < 4; ++ts) {
-        bf16x8 xv[4], xr[4];
+    f32x4 *sY = (f32x4 *)(c.smem + y_off) + c.w * 64 + c.lane;
+    bf16x8 x[2][8];
 #pragma unroll
-        for (int fb = 0; fb < 4; ++fb) {
-            xv[fb] = sX[((ts * 2 + 0) * 4 + fb) * 64];
-            xr[fb] = sX[((ts * 2 + 1) * 4 + fb) * 64];
+    for (int i = 0; i < 8; ++i) x[0][i] = sX[i * 64];
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+        const int cur = ts & 1;
+        if (ts + 1 < 4) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[cur ^ 1][i] = sX[((ts + 1) * 8 + i) * 64];
         }
         f32x4 y0 = zero4(), y1 = zero4(), y2 = zero4();
 #pragma unroll
         for (int fb = 0; fb < 4; ++fb) {
-            y0 = mma16(Uv[fb], xv[fb], y0);
-            y1 = mma16(Ur[fb], xv[fb], y1);
-            y2 = mma16(Uv[fb], xr[fb], y2);
+            y0 = mma16(Uv[fb], x[cur][fb], y0);
+            y1 = mma16(Ur[fb], x[cur][fb], y1);
+            y2 = mma16(Uv[fb], x[cur][4 + fb], y2);
         }
         sY[ts * 8 * 64] = y0 + (y1 + y2);
     }
@@ -607,9 +610,9 @@ __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, c
 }
 
 // y_c = zeta_c U_[n] xhat_c + intra part, stored
-__device__ __forceinline__ void store_output(const Ctx &c, const Solver &s, int ts)
+__device__ __forceinline__ void store_output(const Ctx &c, const Solver &s, int ts, int y_off)
 {
-    const f32x4 *sY = (const f32x4 *)(c.smem + kOffK);
+    const f32x4 *sY = (const f32x4 *)(c.smem + y_off);
     if (!s.valid) return;
     const int64_t off = c.base_bh + (int64_t)s.tok * c.a.stride_t;
 #pragma unroll
@@ -646,7 +649,7 @@ __device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, in
 // wave builds four of the 32 fragments of either kind.
 __device__ __forceinline__ void build_key_frags(const Ctx &c)
 {
-#pragma unroll 1
+#pragma unroll
     for (int q = 0; q < 4; ++q) {
         const int idx = c.w * 4 + q;
         const int g = idx >> 4, f = idx & 15;
@@ -707,14 +710,16 @@ __device__ __forceinline__ void load_start_state(const Ctx &c, f32x4 (&accH)[8],
 
 // One workgroup per (pair, segment of chunks). Per iteration (chunks A = c0, B = c0 + 1), with the barriers between
 // the phases:
-//   1. H_[n] of A -> LDS, gate scans (the k rows, copied global -> LDS since the end of the previous iteration, land)
-//   2. key fragments of both chunks; this wave's weighted k fragments
+//   1. gate scans (the k rows, copied global -> LDS since the end of the previous iteration, land; solver B of the
+//      previous iteration may still be storing)
+//   2. H_[n] of A -> LDS; key fragments of both chunks; this wave's weighted k fragments
 //   3. H advanced over A; H_[n] of B -> LDS; H advanced over B; partial norms -> table (in the dead k row tile)
 //   4. solver: Frobenius terms -> table
 //   5. solver: norms; copies of the v rows into the row tiles start; passes, intra-chunk readout products;
 //      xhat -> LDS (over H_[n])
-//   6. state part of the readout for A (over the key fragments), U advanced over A;  7. solver A stores
-//   8. the same for B;  9. solver B stores; copies of the next k rows into the row tiles start
+//   6. state part of the readout for A (over the key-row fragments), U advanced over A
+//   7. solver A stores; state part of the readout for B (over A's xhat), U advanced over B and parked
+//   8. solver B stores; copies of the next k rows into the row tiles start
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -761,7 +766,6 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 #endif
         // ---- 1
         GKA_FT(0);
-        const float hnA = publish_H(c, accH, 0);
         // gates of both chunks (fetched during the previous iteration): lane j holds G_j, the weight of token j in the
         // chunk's update 2^(G_C - G_j), and the chunk's decay
         float GA, GB, wjA, wjB, zetaA, zetaB;
@@ -781,6 +785,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         lds_barrier();                   // ... and everybody else's
         // ---- 2
         GKA_FT(2);
+        const float hnA = publish_H(c, accH, 0);
         build_key_frags(c);
         bf16x8 wBA[2], wBB[2];
         own_weighted_frags(c, lds_rows(c, 0), wjA, wBA);
@@ -842,29 +847,25 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         gmA = a.gate[c.gate_base + (int64_t)min((c0 + 2) * kChunk + c.lane, a.T - 1) * a.H];
         gmB = a.gate[c.gate_base + (int64_t)min((c0 + 3) * kChunk + c.lane, a.T - 1) * a.H];
         GKA_FT(24);
-        readout_state(c, accU, 0);
+        readout_state(c, accU, 0, kOffK);
         GKA_FT(25);
         advance_state(c, accU, 0, zetaA, wVA);
         GKA_FT(16);
         lds_barrier();
-        // ---- 7
+        // ---- 7: solver A stores while the state part of B is read out into the place of A's xhat
         GKA_FT(17);
-        if (grp == 0) store_output(c, s, ts);
+        if (grp == 0) store_output(c, s, ts, kOffK);
         GKA_FT(18);
-        lds_barrier();
-        // ---- 8
-        GKA_FT(19);
-        readout_state(c, accU, 1);
+        readout_state(c, accU, 1, kOffH);
         GKA_FT(26);
         advance_state(c, accU, 1, zetaB, wVB);
         GKA_FT(27);
         park_store(c.park, accU);
         GKA_FT(28);
-        GKA_FT(20);
         lds_barrier();
-        // ---- 9
+        // ---- 8
         GKA_FT(21);
-        if (grp == 1) store_output(c, s, ts);
+        if (grp == 1) store_output(c, s, ts, kOffH);
         // k rows of the next two chunks: the row tiles are free since the barrier before the readout; the copies land
         // while the next iteration publishes H and scans its gates
         copy_rows(c, a.k, 0, c0 + 2);

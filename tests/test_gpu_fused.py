@@ -1,0 +1,230 @@
+"""GPU parity of the fused forward kernel (GKA_PATH_FUSED: the chunks of a pair are walked in order with H and U in
+registers) against the fp64 oracle, through the C ABI: shapes around the chunk and chunk-pair boundaries, forced
+short walks (many segments whose start states come from the summary launch), initial / final states in both
+layouts, strides, packed sequences, and the robustness checks (poisoned workspace, guard bands, bit-identical
+reruns)."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_21016_amd import binding, synth
+from gka_testutil import pair_rel_err, to_device, to_host, upload_inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+FUSED = binding.GKA_PATH_FUSED
+
+
+def run(w, x, **kw):
+    import torch
+    dev = upload_inputs(x, w.dtype)
+    out = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+def spd_state(w, seed, rank=8):
+    rng = np.random.default_rng(seed)
+    A = rng.standard_normal((w.B, w.H, w.d, rank)).astype(np.float32)
+    Hi = np.einsum("bhik,bhjk->bhij", A, A).astype(np.float32) / rank
+    Hi = (0.5 * (Hi + np.transpose(Hi, (0, 1, 3, 2)))).astype(np.float32)
+    Ui = rng.standard_normal((w.B, w.H, w.d, w.d)).astype(np.float32) * 0.1
+    return Hi, Ui
+
+
+@pytest.mark.parametrize("T", [1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 200, 448])
+@pytest.mark.parametrize("n_iter", [0, 1, 10])
+def test_fused_shapes_around_chunk_boundaries(T, n_iter):
+    """Every ragged position of the last chunk and of the last chunk pair; output, ||H_t||_F and final states."""
+    w = synth.CFG2.scaled(B=2, H=2, T=T, n_iter=n_iter, seed=300 + T)
+    x = synth.make_inputs(w)
+    o, ex = run(w, x, path=FUSED, return_fro=True, return_state=True)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], n_iter, return_fro=True, return_state=True)
+    y = to_host(o)
+    assert np.isfinite(y).all()
+    assert pair_rel_err(y, ref) <= TOL_BF16
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+    for name in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
+
+
+@pytest.mark.parametrize("walk", [2, 4, 6, 10])
+@pytest.mark.parametrize("layout", ["full", "lower_blocks"])
+def test_fused_segments_with_initial_state(walk, layout):
+    """Short walks: 21 chunks cut into segments of `walk` chunks (the last one ragged, an odd chunk count), every
+    segment but the first starting from the summaries of the segments before it, on top of a caller's initial
+    state in either layout of H."""
+    w = synth.CFG2.scaled(B=1, H=3, T=1300, n_iter=8, gate_mean=5.0, seed=4100 + walk)
+    x = synth.make_inputs(w)
+    Hi, Ui = spd_state(w, 7)
+    Hdev = Hi.copy()
+    kw = {}
+    if layout == "lower_blocks":
+        # poison what the layout says is not stored
+        blk = np.arange(w.d) // 32
+        Hdev[:, :, blk[:, None] < blk[None, :]] = np.nan
+        kw["state_layout"] = binding.GKA_STATE_H_LOWER_BLOCKS
+    o, ex = run(w, x, path=FUSED, walk_chunks=walk, H_init=to_device(Hdev, "f32"), U_init=to_device(Ui, "f32"),
+                return_state=True, return_fro=True, **kw)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, H_init=Hi, U_init=Ui,
+                              return_state=True, return_fro=True)
+    assert pair_rel_err(to_host(o), ref) <= TOL_BF16
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+    for name in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
+
+
+def test_fused_matches_two_phase_kernels():
+    """The two paths compute the same layer: their outputs differ by rounding only (and both meet the oracle)."""
+    w = synth.CFG2.scaled(B=2, H=4, T=700, seed=31)
+    x = synth.make_inputs(w)
+    o_f = to_host(run(w, x, path=FUSED))
+    o_t = to_host(run(w, x, path=binding.GKA_PATH_TWO_PHASE))
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    assert pair_rel_err(o_f, ref) <= TOL_BF16 and pair_rel_err(o_t, ref) <= TOL_BF16
+    assert pair_rel_err(o_f, o_t) <= TOL_BF16
+
+
+def test_fused_path_is_refused_where_it_does_not_apply():
+    import torch
+    w = synth.CFG2.scaled(B=1, H=1, T=64, d=64)
+    x = synth.make_inputs(w)
+    dev = upload_inputs(x, w.dtype)
+    with pytest.raises(binding.GkaError) as e:
+        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, path=FUSED)
+    assert e.value.status == binding.GKA_ERR_UNSUPPORTED
+    w = synth.CFG2.scaled(B=1, H=1, T=64)
+    x = synth.make_inputs(w)
+    dev = upload_inputs(x, w.dtype)
+    beta = torch.ones((1, 64, 1), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.GkaError) as e:
+        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, path=FUSED, beta=beta)
+    assert e.value.status == binding.GKA_ERR_UNSUPPORTED
+    with pytest.raises(binding.GkaError) as e:
+        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, path=FUSED,
+                            compute=binding.GKA_COMPUTE_F32)
+    assert e.value.status == binding.GKA_ERR_UNSUPPORTED
+
+
+def test_fused_explicit_strides_head_major_layout():
+    import torch
+    w = synth.CFG2.scaled(B=2, H=3, T=333, seed=12)
+    x = synth.make_inputs(w)
+    dev = {n: to_device(np.ascontiguousarray(np.transpose(x[n], (0, 2, 1, 3))), "bf16") for n in ("q", "k", "v")}
+    gate, lam = to_device(x["gate"], "f32"), to_device(x["lam"], "f32")
+    o = torch.zeros_like(dev["v"])
+    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16,
+                                 strides=(w.H * w.T * w.d, w.d, w.T * w.d), path=FUSED, walk_chunks=2)
+    ws = torch.empty(binding.forward_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    st = binding.forward_raw(params, dev["q"].data_ptr(), dev["k"].data_ptr(), dev["v"].data_ptr(), gate.data_ptr(),
+                             lam.data_ptr(), o.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws.numel(),
+                             stream=torch.cuda.current_stream().cuda_stream)
+    assert st == binding.GKA_OK
+    torch.cuda.synchronize()
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    assert pair_rel_err(np.transpose(to_host(o), (0, 2, 1, 3)), ref) <= TOL_BF16
+
+
+def test_fused_packed_variable_length_sequences():
+    """Gates of 0 at the first token of every packed sequence (treated as exp(-100)): each sequence as if run alone,
+    wherever the chunk, chunk-pair and segment boundaries fall."""
+    lengths = [70, 1, 130, 63, 64, 56, 200, 17]
+    w = synth.CFG2.scaled(B=1, H=2, T=sum(lengths), n_iter=6, seed=19)
+    x = {n: a.copy() for n, a in synth.make_inputs(w).items()}
+    starts = np.cumsum([0] + lengths[:-1])
+    x["gate"][:, starts] = 0.0
+    y = to_host(run(w, x, path=FUSED, walk_chunks=4))
+    assert np.isfinite(y).all()
+    for s0, n in zip(starts, lengths):
+        part = {name: np.ascontiguousarray(a[:, s0:s0 + n]) for name, a in x.items()}
+        part["gate"][:, 0] = 0.5
+        ref = oracle.forward(part["q"], part["k"], part["v"], part["gate"], part["lam"], w.n_iter)
+        assert pair_rel_err(y[:, s0:s0 + n], ref) <= TOL_BF16, (s0, n)
+
+
+def test_fused_degenerate_values():
+    """Zero keys, zero queries and values, gates of exactly 1, hard resets, lambda over many decades, 40 passes."""
+    w = synth.CFG2.scaled(B=1, H=4, T=200, n_iter=40, seed=91)
+    x = {n: a.copy() for n, a in synth.make_inputs(w).items()}
+    x["k"][:, :70, 0] = 0.0
+    x["q"][:, 100:110, 1] = 0.0
+    x["v"][:, 120:130, 1] = 0.0
+    x["gate"][:, :, 2] = 1.0
+    x["gate"][:, 50::17, 3] = 1e-30
+    x["gate"][:, 90, 3] = 0.999
+    lam = np.geomspace(1e-2, 1e4, w.T).astype(np.float32)
+    x["lam"][:] = lam[None, :, None]
+    o, ex = run(w, x, path=FUSED, return_fro=True)
+    y = to_host(o)
+    assert np.isfinite(y).all()
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, return_fro=True)
+    assert pair_rel_err(y, ref) <= TOL_BF16
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+
+
+def test_fused_poisoned_workspace_guard_bands_and_rerun():
+    """The workspace is filled with NaN before the call, every output sits between guard bands, and the call is
+    repeated: the result must not depend on what the workspace held, nothing outside the outputs may be written, and
+    the rerun must be bit-identical (no atomics, no races between the waves of a workgroup)."""
+    import torch
+    w = synth.CFG2.scaled(B=2, H=8, T=1100, seed=55)
+    x = synth.make_inputs(w)
+    dev = upload_inputs(x, w.dtype)
+    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16, path=FUSED)
+    nbytes = binding.forward_workspace_bytes(params)
+    guard = 4096
+
+    def guarded(n_elems, dtype):
+        esz = torch.empty((), dtype=dtype).element_size()
+        buf = torch.full((n_elems + 2 * guard // esz,), 7.0, dtype=dtype, device="cuda")
+        return buf, buf[guard // esz: guard // esz + n_elems]
+
+    results = []
+    for fill in (float("nan"), 1e30):
+        ws = torch.full((nbytes // 4 + 2 * guard // 4,), fill, dtype=torch.float32, device="cuda")
+        ws[:guard // 4] = 7.0
+        ws[-(guard // 4):] = 7.0
+        o_buf, o = guarded(w.B * w.T * w.H * w.d, torch.bfloat16)
+        H_buf, Hf = guarded(w.B * w.H * w.d * w.d, torch.float32)
+        U_buf, Uf = guarded(w.B * w.H * w.d * w.d, torch.float32)
+        f_buf, fro = guarded(w.B * w.T * w.H, torch.float32)
+        st = binding.forward_raw(params, dev["q"].data_ptr(), dev["k"].data_ptr(), dev["v"].data_ptr(),
+                                 dev["gate"].data_ptr(), dev["lam"].data_ptr(), o.data_ptr(), None, None,
+                                 Hf.data_ptr(), Uf.data_ptr(), fro.data_ptr(), ws.data_ptr() + guard, nbytes,
+                                 torch.cuda.current_stream().cuda_stream)
+        assert st == binding.GKA_OK
+        torch.cuda.synchronize()
+        g = guard // 4
+        assert torch.all(ws[:g] == 7.0) and torch.all(ws[-g:] == 7.0)
+        for buf, view in ((o_buf, o), (H_buf, Hf), (U_buf, Uf), (f_buf, fro)):
+            n_guard = (buf.numel() - view.numel()) // 2
+            assert torch.all(buf[:n_guard] == 7.0) and torch.all(buf[-n_guard:] == 7.0)
+        results.append((o.clone(), Hf.clone(), Uf.clone(), fro.clone()))
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    assert pair_rel_err(to_host(results[0][0].view(w.B, w.T, w.H, w.d)), ref) <= TOL_BF16
+
+
+def test_two_phase_forward_rerun_is_bit_identical():
+    """gka_forward twice on configuration-2 shaped inputs (two-phase kernels): torch.equal."""
+    import torch
+    w = synth.CFG2.scaled(B=1, H=4, T=2048, seed=56)
+    x = synth.make_inputs(w)
+    a = run(w, x, path=binding.GKA_PATH_TWO_PHASE)
+    b = run(w, x, path=binding.GKA_PATH_TWO_PHASE)
+    assert torch.equal(a, b)
+
+
+def test_fused_many_pairs():
+    """More workgroups than compute units: 1312 pairs, one segment each, initial states given."""
+    w = synth.CFG2.scaled(B=41, H=32, T=130, n_iter=4, seed=123)
+    x = synth.make_inputs(w)
+    Hi, Ui = spd_state(w, 6, rank=4)
+    o, ex = run(w, x, path=FUSED, H_init=to_device(Hi, "f32"), U_init=to_device(Ui, "f32"), return_state=True)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, H_init=Hi, U_init=Ui,
+                              return_state=True)
+    assert pair_rel_err(to_host(o), ref) <= TOL_BF16
+    for name in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
