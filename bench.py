@@ -2,8 +2,8 @@
 
 One step = one gka_forward over the single-layer bf16 workload (B=4, H=16, T=4096, d=128, chunk 64,
 n_iter=10), inputs resident in HBM. Prints one JSON line: layer tokens/s, the roofline of the dominant
-kernel (the per-chunk solve kernel, bf16 MFMA bound) from per-phase HIP-event timings, and the fp64 CPU
-oracle timed on this machine's host cores on the same workload.
+kernel (the fused chunk-walk kernel, bf16 MFMA bound) from HIP-event timings taken on the launch stream,
+and the fp64 CPU oracle timed on this machine's host cores on the same workload.
 """
 import argparse
 import json
@@ -18,14 +18,28 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak
-# HBM bytes of one solve-kernel launch on this workload, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/chunk_solve_and_state_pass_cfg2_hbm_traffic.md (593 MiB read + 64 MiB written). Update with the kernel.
-SOLVE_TRAFFIC_BYTES = (593 + 64) * (1 << 20)
-# the same for one decode-step launch on the configuration-5 shape (1031 MiB read + 1026 MiB written)
-DECODE_TRAFFIC_BYTES = (1031 + 1026) * (1 << 20)
-# and with the reduced layout of H (839 MiB read + 834 MiB written)
-DECODE_LOWER_TRAFFIC_BYTES = (839 + 834) * (1 << 20)
 N_INPUT_SETS = 3                   # rotated so that the 256 MiB of q,k,v,o do not sit in the last-level cache
+# An idle GPU needs tens of milliseconds of work before its clocks settle; a step is a third of a millisecond. These
+# untimed forward passes run before the W warm-up steps whatever W is (reported as "clock_ramp_steps").
+CLOCK_RAMP_STEPS = 300
+FUSED_KERNEL = "gka::fused_forward_kernel(gka::FusedArgs)"
+
+
+def committed_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summaries (profiles/*.md, lines of the
+    form `traffic_bytes_per_launch <kernel>: <bytes>`), or None: counters are collected in runs of their own, not here."""
+    pdir = os.path.join(ROOT, "profiles")
+    try:
+        for name in sorted(os.listdir(pdir)):
+            if not name.endswith(".md"):
+                continue
+            with open(os.path.join(pdir, name)) as f:
+                for line in f:
+                    if line.startswith("traffic_bytes_per_launch ") and kernel in line:
+                        return int(line.rsplit(":", 1)[1].strip())
+    except OSError:
+        pass
+    return None
 
 
 def algorithmic_flops_per_chunk(d, C, r):
@@ -52,6 +66,7 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--no-sketch", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); every (batch, head) pair is independent, "
@@ -94,6 +109,8 @@ def main():
     calib_dst.copy_(calib_src)
     del calib_src, calib_dst
 
+    for i in range(CLOCK_RAMP_STEPS):
+        step(i)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -123,10 +140,11 @@ def main():
     n_chunks = w.B * w.H * (w.T // w.chunk)
     f_s2, f_s4, f_s5, f_s6 = algorithmic_flops_per_chunk(w.d, w.chunk, w.n_iter)
     flops_total = n_chunks * (f_s2 + f_s4 + f_s5 + f_s6)
-    flops_solve = n_chunks * (f_s4 + f_s5 + f_s6)
     tokens = w.B * w.T
     tflops_total = flops_total / (ms_per_step * 1e-3) / 1e12
-    tflops_solve = flops_solve / (ms_solve * 1e-3) / 1e12
+    # the fused kernel does all of S1-S6 for every chunk (the summary launch before it repeats part of S2 and is
+    # not counted as algorithmic work)
+    tflops_solve = flops_total / (ms_solve_launch * 1e-3) / 1e12
 
     result = {
         "metric": "GKA layer forward tokens/sec + % bf16 MFMA peak (H=16,d=128,T=4096)",
@@ -142,47 +160,93 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "T": w.T, "d": w.d, "chunk": w.chunk,
-                   "n_iter": w.n_iter, "input_sets_rotated": N_INPUT_SETS},
+                   "n_iter": w.n_iter, "input_sets_rotated": N_INPUT_SETS, "clock_ramp_steps": CLOCK_RAMP_STEPS},
         "head_tokens_per_s": tokens * w.H / (ms_per_step * 1e-3),
         "tflops_algorithmic": tflops_total,
         "frac_bf16_mfma_peak": tflops_total / MFMA_BF16_PEAK_TFLOPS,
-        "phase_ms": {"states": ms_states, "solve": ms_solve, "solve_launches_per_step": n_launches,
-                     "solve_ms_per_launch": ms_solve_launch},
-        "roofline": {"kernel": "chunk_solve_kernel<MmaBF16,IOBF16,128>", "bound": "mfma",
+        "phase_ms": {"segment_summaries": ms_states, "chunk_walk": ms_solve, "chunk_walk_launches_per_step": n_launches,
+                     "chunk_walk_ms_per_launch": ms_solve_launch},
+        "roofline": {"kernel": FUSED_KERNEL, "bound": "mfma",
                      "achieved": tflops_solve, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops_solve / MFMA_BF16_PEAK_TFLOPS, "traffic": SOLVE_TRAFFIC_BYTES},
+                     "frac": tflops_solve / MFMA_BF16_PEAK_TFLOPS, "traffic": committed_traffic(FUSED_KERNEL)},
     }
 
-    # ---- recurrent decode (configuration 5 shape: 256 sequences x 32 heads, d = 128, n_iter = 10), HBM bound:
-    # 256 KiB of fp32 state read + written per (sequence, head) per step. Extra information, not the headline metric.
+    # ---- the other forward configurations (extra information): long context and the ill-conditioned stress
+    if not args.no_other_configs:
+        other = {}
+        for wo, compute, label in ((synth.CFG3, binding.GKA_COMPUTE_BF16, "bf16 operands"),
+                                   (synth.CFG4, binding.GKA_COMPUTE_BF16, "bf16 operands"),
+                                   (synth.CFG4, binding.GKA_COMPUTE_F32, "fp32 operands")):
+            xo = upload_inputs(synth.make_inputs(wo), wo.dtype)
+            po = binding.make_params(wo.B, wo.H, wo.T, wo.d, wo.n_iter, binding.GKA_BF16, compute)
+            wso = torch.empty(binding.forward_workspace_bytes(po), dtype=torch.uint8, device="cuda")
+            oo = torch.empty_like(xo["v"])
+            call = lambda: binding.gka_forward(xo["q"], xo["k"], xo["v"], xo["gate"], xo["lam"], wo.n_iter,
+                                               compute=compute, workspace=wso, out=oo)
+            for _ in range(10):
+                call()
+            torch.cuda.synchronize()
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record()
+            for _ in range(20):
+                call()
+            c1.record()
+            torch.cuda.synchronize()
+            ms = c0.elapsed_time(c1) / 20
+            other[f"{wo.name} ({label})"] = {"ms_per_step": ms, "tokens_per_s": wo.B * wo.T / (ms * 1e-3)}
+            del xo, wso, oo
+        result["other_configs"] = other
+
+    # ---- recurrent decode, configuration 5: 256 sequences x 32 heads, d = 128, states prefilled from 2048 tokens by
+    # gka_forward, then 1024 single-token steps timed end to end (no host synchronisation inside). HBM bound: 256 KiB
+    # of fp32 state read + written per (sequence, head) per step. Extra information, not the headline metric. The
+    # tokens are drawn on the device (same distributions as configuration 2; the parity tests use the host generator).
     if not args.no_decode:
-        dB, dH, dd, d_steps = 256, 32, 128, 50
+        w5 = synth.CFG5
+        dB, dH, dd, d_steps = w5.B, w5.H, w5.d, synth.CFG5_DECODE_STEPS
         gen = torch.Generator(device="cuda").manual_seed(5)
-        Hs = torch.zeros((dB, dH, dd, dd), dtype=torch.float32, device="cuda")
-        Us = torch.randn((dB, dH, dd, dd), dtype=torch.float32, device="cuda", generator=gen)
-        qd = torch.nn.functional.normalize(torch.randn((dB, dH, dd), device="cuda", generator=gen), dim=-1).bfloat16()
-        kd = torch.nn.functional.normalize(torch.randn((dB, dH, dd), device="cuda", generator=gen), dim=-1).bfloat16()
-        vd = torch.randn((dB, dH, dd), device="cuda", generator=gen).bfloat16()
-        gd = torch.sigmoid(torch.randn((dB, dH), device="cuda", generator=gen) + 3.0)
-        ld = torch.nn.functional.softplus(torch.randn((dB, dH), device="cuda", generator=gen)) + 1e-2
-        od = torch.empty_like(vd)
-        for _ in range(5):
-            binding.gka_decode_step(Hs, Us, qd, kd, vd, gd, ld, 10, out=od)
+
+        def draw(*lead):
+            qq = torch.nn.functional.normalize(torch.randn((*lead, dH, dd), device="cuda", generator=gen), dim=-1).bfloat16()
+            kk = torch.nn.functional.normalize(torch.randn((*lead, dH, dd), device="cuda", generator=gen), dim=-1).bfloat16()
+            vv = torch.randn((*lead, dH, dd), device="cuda", generator=gen).bfloat16()
+            gg = torch.sigmoid(torch.randn((*lead, dH), device="cuda", generator=gen) + w5.gate_mean)
+            ll = torch.nn.functional.softplus(torch.randn((*lead, dH), device="cuda", generator=gen)) + w5.lambda_add
+            return qq, kk, vv, gg, ll
+
+        qp, kp, vp, gp, lp = draw(dB, w5.T)
+        op, exs = binding.gka_forward(qp, kp, vp, gp, lp, w5.n_iter, return_state=True)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        binding.gka_forward(qp, kp, vp, gp, lp, w5.n_iter, out=op)
+        torch.cuda.synchronize()
+        ms_prefill = (time.time() - t0) * 1e3
+        Hs, Us = exs["H_final"], exs["U_final"]
+        del qp, kp, vp, gp, lp, op
+        qs, ks, vs, gs, ls = draw(d_steps, dB)
+        od = torch.empty((dB, dH, dd), dtype=torch.bfloat16, device="cuda")
+        qd, kd, vd, gd, ld = qs[0], ks[0], vs[0], gs[0], ls[0]
+        for i in range(5):
+            binding.gka_decode_step(Hs, Us, qs[i], ks[i], vs[i], gs[i], ls[i], w5.n_iter, out=od)
         torch.cuda.synchronize()
         d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         d0.record()
-        for _ in range(d_steps):
-            binding.gka_decode_step(Hs, Us, qd, kd, vd, gd, ld, 10, out=od)
+        for i in range(d_steps):
+            binding.gka_decode_step(Hs, Us, qs[i], ks[i], vs[i], gs[i], ls[i], w5.n_iter, out=od)
         d1.record()
         torch.cuda.synchronize()
         ms_decode = d0.elapsed_time(d1) / d_steps
         state_bytes = dB * dH * 2 * dd * dd * 4 * 2          # H and U, read and written
-        result["decode"] = {"workload": "cfg5_decode_bf16 (256 seq x 32 heads, d=128, n_iter=10)",
+        dk = "decode_step_kernel<IOBF16,128,false,false>"
+        result["decode"] = {"workload": f"{w5.name}: {dB} seq x {dH} heads, d={dd}, n_iter={w5.n_iter}, states prefilled "
+                                        f"from {w5.T} tokens by gka_forward ({ms_prefill:.1f} ms), {d_steps} steps",
                             "ms_per_step": ms_decode, "sequence_tokens_per_s": dB / (ms_decode * 1e-3),
-                            "roofline": {"kernel": "decode_step_kernel<IOBF16,128,false,false>", "bound": "hbm",
+                            "prefill_ms": ms_prefill, "prefill_tokens_per_s": dB * w5.T / (ms_prefill * 1e-3),
+                            "roofline": {"kernel": dk, "bound": "hbm",
                                          "achieved": state_bytes / (ms_decode * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                                          "unit": "GB/s", "frac": state_bytes / (ms_decode * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                         "traffic": DECODE_TRAFFIC_BYTES}}
+                                         "traffic": committed_traffic(dk)}}
+        d_steps = 50
         # the decode cache in the reduced layout of H (only the 32 x 32 blocks on and below the block diagonal are
         # read and written: 10 of 16 blocks at d = 128)
         for _ in range(5):
@@ -202,7 +266,7 @@ def main():
             "roofline": {"kernel": "decode_step_kernel<IOBF16,128,false,true>", "bound": "hbm",
                          "achieved": lower_bytes / (ms_lower * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": lower_bytes / (ms_lower * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": DECODE_LOWER_TRAFFIC_BYTES}}
+                         "traffic": committed_traffic("decode_step_kernel<IOBF16,128,false,true>")}}
         # several tokens per call (gka_decode_tokens): the states still cross HBM once per call
         multi = {}
         for nt in (4, 8):

@@ -986,7 +986,7 @@ size_t fused_workspace_bytes(int n_pairs, int n_segs)
     return n * (2 * kD * kD * sizeof(float)) + ((n * sizeof(float) + 255) / 256) * 256 + n * (kD * kD * sizeof(float));
 }
 
-hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_t stream)
+hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_t stream, int which)
 {
     FusedArgs a = a0;
     a.seg_buf = (float *)workspace;
@@ -1002,14 +1002,15 @@ hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    if (a.n_segs > 1) {
+    if (a.n_segs > 1 && (which & 1)) {
         hipLaunchKernelGGL(fused_summary_kernel, dim3((unsigned)(a.n_pairs * (a.n_segs - 1))), dim3(kFusedThreads),
                            kSummaryLds, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(fused_forward_kernel, dim3((unsigned)(a.n_pairs * a.n_segs)), dim3(kFusedThreads), kLdsBytes,
-                       stream, a);
+    if (which & 2)
+        hipLaunchKernelGGL(fused_forward_kernel, dim3((unsigned)(a.n_pairs * a.n_segs)), dim3(kFusedThreads), kLdsBytes,
+                           stream, a);
     return hipGetLastError();
 }
 

@@ -155,7 +155,8 @@ struct FusedArgs {
     float *seg_buf, *seg_logdecay, *park; // set by the launcher (carved from the workspace)
 };
 size_t fused_workspace_bytes(int n_pairs, int n_segs);
-hipError_t launch_fused_forward(const FusedArgs &a, void *workspace, hipStream_t stream);
+// which: bit 0 the summary launch (segment summaries for the start states), bit 1 the chunk walk itself
+hipError_t launch_fused_forward(const FusedArgs &a, void *workspace, hipStream_t stream, int which = 3);
 
 // Workspace sizes in bytes per (pair, chunk).
 size_t ws_H_bytes_per_chunk(int d, bool compute_bf16);
