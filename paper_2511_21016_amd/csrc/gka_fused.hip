@@ -164,12 +164,14 @@ __device__ __forceinline__ ChunkGates scan_gates(const Ctx &c, int tok0)
 
 // This wave's B fragments of a chunk update: rows of the tile (k or v) transposed, columns 16 w .., each token
 // scaled by its weight (lane j of wj: weight of token j).
-__device__ __forceinline__ void own_weighted_frags(const Ctx &c, const uint16_t *rows, float wj, bf16x8 (&out)[2])
+template <class Layout = Rows>
+__device__ __forceinline__ void own_weighted_frags(const Ctx &c, const uint16_t *rows, float wj, bf16x8 (&out)[2],
+                                                   Layout at = Layout())
 {
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
         const int t0 = 32 * st + 4 * c.kg;
-        const bf16x8 raw = gather_transposed_bf16(rows, Rows(), 16 * c.w, c.lane, t0, t0 + 16);
+        const bf16x8 raw = gather_transposed_bf16(rows, at, 16 * c.w, c.lane, t0, t0 + 16);
         f32x4 lo, hi;
         unpack8(raw, lo, hi);
 #pragma unroll
@@ -891,7 +893,10 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 // fused kernel's workgroups follow from these by a short scan. Two chunks per iteration; their k and v rows are fetched
 // one iteration ahead into registers and stored into the other half of a double buffer, so an iteration is one barrier
 // followed by wave-local work: every wave reads the transposed operands of its tiles straight from the row tiles.
-constexpr int kSummaryLds = 2 * 2 * 2 * 16384;             // [buffer][chunk of the pair][k, v] row tiles
+// The tiles are padded, not swizzled: the reads of a wave's eight tiles then differ by constant offsets.
+constexpr int kSummaryRowElems = kD + MmaBF16::kRowPad;    // rows 32 bytes apart modulo 256
+constexpr int kSummaryTile = kChunk * kSummaryRowElems * 2; // bytes
+constexpr int kSummaryLds = 2 * 2 * 2 * kSummaryTile;      // [buffer][chunk of the pair][k, v] row tiles
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_summary_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -933,15 +938,18 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll 1
     for (int c0 = chunk_begin; c0 < chunk_end; c0 += 2, buf ^= 1) {
         refresh_lane(c);
-        unsigned char *tiles = smem + buf * (4 * 16384);
+        unsigned char *tiles = smem + buf * (4 * kSummaryTile);
+        const PaddedRows at{kSummaryRowElems};
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int row = (i & 1) * 32 + (c.tid >> 4), piece = c.tid & 15;
-            *(u32x4 *)((uint16_t *)(tiles + (i >> 1) * 16384) + Rows()(row, 8 * piece)) = regs[i];
+            *(u32x4 *)((uint16_t *)(tiles + (i >> 1) * kSummaryTile) + at(row, 8 * piece)) = regs[i];
         }
         const float gm0 = gm[0], gm1 = gm[1];
         lds_barrier();                   // the tiles are complete; the other buffer's readers are done
         fetch(c0 + 2);                   // (past the end of the segment: harmless reads of rows that exist)
+        // (the scheduler must not sink these loads to where their data is stored, one iteration later)
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
             const bool valid = (c0 + g) * kChunk + c.lane < c.T_eff;
@@ -950,23 +958,26 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             Gseg += Gtot;
             const float wj = valid ? exp2f(Gtot - G) : 0.0f;
             const float zetaC = exp2f(Gtot);
-            const uint16_t *rowsK = (const uint16_t *)(tiles + (2 * g + 0) * 16384);
-            const uint16_t *rowsV = (const uint16_t *)(tiles + (2 * g + 1) * 16384);
+            const uint16_t *rowsK = (const uint16_t *)(tiles + (2 * g + 0) * kSummaryTile);
+            const uint16_t *rowsV = (const uint16_t *)(tiles + (2 * g + 1) * kSummaryTile);
             bf16x8 wK[2], wV[2];
-            own_weighted_frags(c, rowsK, wj, wK);
-            own_weighted_frags(c, rowsV, wj, wV);
+            own_weighted_frags(c, rowsK, wj, wK, at);
+            own_weighted_frags(c, rowsV, wj, wV, at);
 #pragma unroll
             for (int jt = 0; jt < 8; ++jt) {
+                // (operand reads of four tiles at a time in flight: more would take the registers of the prefetch)
+                if (jt == 4) __builtin_amdgcn_sched_barrier(0);
                 accH[jt] *= zetaC;
                 accU[jt] *= zetaC;
 #pragma unroll
                 for (int st = 0; st < 2; ++st) {
                     const int t0 = 32 * st + 4 * c.kg;
-                    const bf16x8 kt = gather_transposed_bf16(rowsK, Rows(), 16 * jt, c.lane, t0, t0 + 16);
+                    const bf16x8 kt = gather_transposed_bf16(rowsK, at, 16 * jt, c.lane, t0, t0 + 16);
                     accH[jt] = mma16(kt, wK[st], accH[jt]);
                     accU[jt] = mma16(kt, wV[st], accU[jt]);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     f32x4 *t = (f32x4 *)a.seg_buf + ((int64_t)(pair * a.n_segs + seg) * 2) * 4096 + (c.w * 8) * 64 + c.lane;
