@@ -41,7 +41,8 @@ typedef enum {
     GKA_ERR_SHAPE = 2,        /* non-positive or inconsistent size / stride                   */
     GKA_ERR_UNSUPPORTED = 3,  /* head dimension, chunk, dtype or compute mode not supported   */
     GKA_ERR_WORKSPACE = 4,    /* workspace NULL, misaligned or smaller than the query says    */
-    GKA_ERR_LAUNCH = 5        /* a HIP call or kernel launch reported an error                */
+    GKA_ERR_LAUNCH = 5,       /* a HIP call or kernel launch reported an error                */
+    GKA_ERR_STATIC_SCRATCH = 6 /* gka_forward_static: the problem needs more than GKA_STATIC_SCRATCH_BYTES */
 } gka_status;
 
 typedef enum { GKA_F32 = 0, GKA_BF16 = 1 } gka_dtype;
@@ -151,6 +152,31 @@ gka_status gka_forward(const gka_params *p,
                        float *fro_out,
                        void *workspace, size_t workspace_bytes,
                        void *hip_stream);
+
+/* gka_forward for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. The same arguments as gka_forward without the
+ * workspace, the same kernels and the same results; the scratch that the kernels need (segment summaries of the chunk
+ * walk and the parked states, 196,612 bytes per workgroup) lives in an array of GKA_STATIC_SCRATCH_BYTES
+ * that the library's code object reserves on every GPU it is loaded on, until the process ends. The call allocates
+ * and frees nothing, on the device or through any library.
+ *   Supported: what the fused kernels cover (see gka_path: GKA_BF16 tensors, GKA_COMPUTE_BF16, d = 128, lambda given,
+ *   no beta / alpha / xhat_out, GKA_PHASE_ALL, path not GKA_PATH_TWO_PHASE), else GKA_ERR_UNSUPPORTED.
+ *   Size limit: (number of (batch, head) pairs) x (segments of the chunk walk) x 196,612 bytes (+ padding) must not
+ *   exceed GKA_STATIC_SCRATCH_BYTES: at most 341 workgroups. The library cuts the walk into ceil(256 / (B H))
+ *   segments (fewer for short sequences); p->walk_chunks >= ceil(T / 64) asks for a single segment, with which any
+ *   B H <= 341 fits. Larger: GKA_ERR_STATIC_SCRATCH, nothing is launched.
+ *   Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race and
+ *   give wrong results; calls on one stream, or ordered by events, are safe. Nothing in the array needs clearing
+ *   between calls: every word a call reads it has written before. */
+#define GKA_STATIC_SCRATCH_BYTES (64u << 20)
+gka_status gka_forward_static(const gka_params *p,
+                              const void *q, const void *k, const void *v,
+                              const float *gate, const float *lambda,
+                              void *o,
+                              const float *H_init, const float *U_init,
+                              float *H_final, float *U_final,
+                              float *fro_out,
+                              void *hip_stream);
 
 /* gka_forward for profiling: the same work with the same arguments, bracketed per phase by HIP events on the
  * given stream. Unlike every other entry point this one creates and destroys events and BLOCKS until the work

@@ -10,7 +10,9 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgka.so")
 
-GKA_OK, GKA_ERR_NULL, GKA_ERR_SHAPE, GKA_ERR_UNSUPPORTED, GKA_ERR_WORKSPACE, GKA_ERR_LAUNCH = range(6)
+(GKA_OK, GKA_ERR_NULL, GKA_ERR_SHAPE, GKA_ERR_UNSUPPORTED, GKA_ERR_WORKSPACE, GKA_ERR_LAUNCH,
+ GKA_ERR_STATIC_SCRATCH) = range(7)
+GKA_STATIC_SCRATCH_BYTES = 64 << 20
 GKA_F32, GKA_BF16 = 0, 1
 GKA_COMPUTE_F32, GKA_COMPUTE_BF16 = 0, 1
 GKA_PHASE_ALL, GKA_PHASE_STATES, GKA_PHASE_SOLVE = 0, 1, 2
@@ -20,6 +22,7 @@ GKA_PATH_AUTO, GKA_PATH_TWO_PHASE, GKA_PATH_FUSED = 0, 1, 2
 EXPORTED_SYMBOLS = (
     "gka_forward_workspace_bytes",
     "gka_forward",
+    "gka_forward_static",
     "gka_forward_profile",
     "gka_decode_step",
     "gka_decode_tokens",
@@ -72,6 +75,8 @@ def load_library():
         lib.gka_forward.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, vp,
                                     ctypes.c_size_t, vp]
         lib.gka_forward.restype = ctypes.c_int
+        lib.gka_forward_static.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, vp]
+        lib.gka_forward_static.restype = ctypes.c_int
         lib.gka_forward_profile.argtypes = lib.gka_forward.argtypes + [ctypes.POINTER(ctypes.c_float),
                                                                        ctypes.POINTER(ctypes.c_float),
                                                                        ctypes.POINTER(ctypes.c_int32)]
@@ -127,6 +132,14 @@ def forward_raw(params, q, k, v, gate, lam, o, H_init=None, U_init=None, H_final
     pp = None if params is None else ctypes.byref(params)
     return int(load_library().gka_forward(pp, q, k, v, gate, lam, o, H_init, U_init, H_final,
                                           U_final, fro_out, workspace, workspace_bytes, stream))
+
+
+def forward_static_raw(params, q, k, v, gate, lam, o, H_init=None, U_init=None, H_final=None, U_final=None,
+                       fro_out=None, stream=None):
+    """gka_forward_static on raw device addresses (ints or None). Returns the gka_status."""
+    pp = None if params is None else ctypes.byref(params)
+    return int(load_library().gka_forward_static(pp, q, k, v, gate, lam, o, H_init, U_init, H_final, U_final,
+                                                 fro_out, stream))
 
 
 def forward_profile_raw(params, q, k, v, gate, lam, o, workspace, workspace_bytes, stream=None):

@@ -1,8 +1,10 @@
 // Host side of the C ABI declared in include/gka.h: argument validation, workspace carving and kernel
-// launches on the caller's stream. No allocation, no synchronisation, no global state.
+// launches on the caller's stream. No device allocation and no synchronisation (gka_forward_profile aside); the only
+// state kept between calls is the address of gka_forward_static's scratch array on each device.
 #include "../../include/gka.h"
 #include "gka_kernels.hpp"
 
+#include <mutex>
 #include <vector>
 
 namespace {
@@ -17,6 +19,7 @@ struct Plan {
     int slab_chunks;              // chunks of every pair per launch
     bool fused_shape;             // dtype, operands and head dimension of the fused kernel
     int fused_n_segs, fused_seg_len;
+    size_t fused_bytes;           // workspace of the fused kernels alone
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -118,6 +121,7 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
     // workgroup (every segment but the last costs a second read of its k and v rows for the summary launch); an even
     // number of chunks per segment, because a workgroup takes its chunks two at a time.
     pl->fused_shape = pl->io_bf16 && pl->compute_bf16 && pl->d == 128 && !readout_only;
+    pl->fused_bytes = 0;
     if (pl->fused_shape) {
         int seg_len;
         if (p->walk_chunks > 0) {
@@ -132,8 +136,9 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
         pl->fused_seg_len = seg_len;
         pl->fused_n_segs = (pl->n_chunks + seg_len - 1) / seg_len;
         if ((int64_t)pl->n_pairs * pl->fused_n_segs > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
-        const size_t fused = align_up(gka::fused_workspace_bytes(pl->n_pairs, pl->fused_n_segs), 256);
-        if (fused > pl->total) pl->total = fused;
+        pl->fused_bytes = align_up(gka::fused_workspace_bytes(pl->n_pairs, pl->fused_n_segs), 256);
+        // (a caller that insists on the fused kernels needs no room for the two-phase kernels' chunk states)
+        if (p->path == GKA_PATH_FUSED || pl->fused_bytes > pl->total) pl->total = pl->fused_bytes;
     }
     return GKA_OK;
 }
@@ -306,6 +311,49 @@ gka_status gka_forward_profile(const gka_params *p, const void *q, const void *k
     *ms_solve = t_solve;
     *n_solve_launches = (int32_t)(prof.ev.size() / 3);
     return GKA_OK;
+}
+
+// ---- gka_forward_static: the fused kernels with their scratch in a fixed device array --------------------------
+namespace {
+// Segment summaries and parked states of the fused kernels. Every GPU the library runs on holds its own copy until
+// the process ends. In host code the array's name is only a handle: its device address comes from
+// hipGetSymbolAddress, once per device, and is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[GKA_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+gka_status static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GKA_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GKA_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return GKA_OK;
+}
+}  // namespace
+
+gka_status gka_forward_static(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
+                              const float *lambda, void *o, const float *H_init, const float *U_init, float *H_final,
+                              float *U_final, float *fro_out, void *hip_stream)
+{
+    Plan pl;
+    gka_status s = make_plan(p, &pl);
+    if (s != GKA_OK) return s;
+    if (!pl.fused_shape || p->path == GKA_PATH_TWO_PHASE) return GKA_ERR_UNSUPPORTED;
+    if (pl.fused_bytes > (size_t)GKA_STATIC_SCRATCH_BYTES) return GKA_ERR_STATIC_SCRATCH;
+    void *ws = nullptr;
+    s = static_scratch(&ws);
+    if (s != GKA_OK) return s;
+    gka_params pf = *p;
+    pf.path = GKA_PATH_FUSED;            // (anything the fused kernels do not cover: GKA_ERR_UNSUPPORTED)
+    return forward_impl(&pf, q, k, v, gate, lambda, o, H_init, U_init, H_final, U_final, fro_out, ws,
+                        GKA_STATIC_SCRATCH_BYTES, hip_stream, nullptr);
 }
 
 namespace {
@@ -632,6 +680,7 @@ const char *gka_status_string(gka_status s)
     case GKA_ERR_UNSUPPORTED: return "unsupported head dimension, chunk, dtype or compute mode";
     case GKA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case GKA_ERR_LAUNCH: return "HIP launch failed";
+    case GKA_ERR_STATIC_SCRATCH: return "problem needs more scratch than gka_forward_static's fixed array holds";
     }
     return "unknown status";
 }

@@ -1004,7 +1004,13 @@ hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_
     const size_t n = (size_t)a.n_pairs * a.n_segs;
     a.seg_logdecay = (float *)((char *)workspace + n * (2 * kD * kD * sizeof(float)));
     a.park = (float *)((char *)a.seg_logdecay + ((n * sizeof(float) + 255) / 256) * 256);
-    static bool attr_set = false;
+    // (the attribute is kept per device)
+    static bool attr_set_on[64] = {};
+    int dev = 0;
+    hipError_t ed = hipGetDevice(&dev);
+    if (ed != hipSuccess) return ed;
+    bool unused = false;
+    bool &attr_set = (dev >= 0 && dev < 64) ? attr_set_on[dev] : unused;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)fused_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            kLdsBytes);
