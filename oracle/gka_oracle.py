@@ -11,7 +11,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gka_oracle.c")
-_LIB = os.path.join(_HERE, "libgka_oracle.so")
+_SANITIZED = bool(os.environ.get("GKA_ORACLE_SANITIZED"))      # the CPU tests' sanitizer run sets this
+_LIB = os.path.join(_HERE, "libgka_oracle_san.so" if _SANITIZED else "libgka_oracle.so")
 
 SOLVER_CHEBYSHEV = 0
 SOLVER_CHOLESKY = 1
@@ -23,6 +24,10 @@ def build(force=False):
     """Compile the oracle with gcc (no BLAS; -O2; OpenMP)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        if _SANITIZED:
+            # AddressSanitizer + UndefinedBehaviorSanitizer build; the process must preload gcc's libasan.so
+            cmd[1:2] = ["-O1", "-g", "-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=all",
+                        "-fno-omit-frame-pointer"]
         subprocess.run(cmd, check=True)
     return _LIB
 

@@ -8,7 +8,9 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgka.so")
+# GKA_LIBRARY: another build of the same library (the CPU tests use it to load the copy whose host code was compiled
+# with sanitizers).
+LIB_PATH = os.environ.get("GKA_LIBRARY") or os.path.join(_HERE, "libgka.so")
 
 (GKA_OK, GKA_ERR_NULL, GKA_ERR_SHAPE, GKA_ERR_UNSUPPORTED, GKA_ERR_WORKSPACE, GKA_ERR_LAUNCH,
  GKA_ERR_STATIC_SCRATCH) = range(7)

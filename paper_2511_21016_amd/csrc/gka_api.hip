@@ -24,10 +24,7 @@ struct Plan {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-#ifndef GKA_STATE_MIN_WGS
-#define GKA_STATE_MIN_WGS 512
-#endif
-constexpr int kStateMinWorkgroups = GKA_STATE_MIN_WGS;   // two state-pass workgroups per CU
+constexpr int kStateMinWorkgroups = 512;   // two state-pass workgroups per CU
 constexpr int kStateMaxWalk = 64;          // chunks a state-pass workgroup walks before segments are added
 // Chunk states one launch pair keeps in the workspace unless gka_params::slab_state_bytes says otherwise (tests use
 // that to force several slabs on small problems).

@@ -31,22 +31,6 @@ namespace gka {
 
 constexpr int kSolveThreads = 256;
 
-// Optional phase timestamps of a few mid-grid workgroups (debug builds only).
-#ifdef GKA_DEBUG_TIMERS
-__device__ unsigned long long g_dbg_timers[64 * 16];
-#define GKA_TSTAMP(i)                                                                            \
-    do {                                                                                         \
-        if (threadIdx.x == 0 && blockIdx.x >= 2048 && blockIdx.x < 2112)                         \
-            g_dbg_timers[(blockIdx.x - 2048) * 16 + (i)] = __builtin_amdgcn_s_memtime();         \
-    } while (0)
-extern "C" int gka_debug_read_timers(unsigned long long *host)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_timers), sizeof(g_dbg_timers));
-}
-#else
-#define GKA_TSTAMP(i) do {} while (0)
-#endif
-
 template <class MMA, int D>
 struct SolveShape {
     typedef typename MMA::frag frag;
@@ -356,7 +340,6 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     const int tok = tok0 + c_local;
     const bool valid = tok < a.T;
 
-    GKA_TSTAMP(0);
     // ---------------- staging ----------------
     constexpr int H16 = (int)(SH::h_bytes / 16 / kSolveThreads);   // 16-byte units of a state block per thread
     const int64_t tok_off = base_bh + (int64_t)min(tok, a.T - 1) * a.stride_t;
@@ -410,21 +393,16 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         }
     const float bc = GATED ? __shfl(ball, c_local, 64) : 1.0f;   // write gate of this lane's token
     __builtin_amdgcn_sched_barrier(0);         // the mask is not scheduled behind the wait for the k rows
-    GKA_TSTAMP(1);
     krows.store(sRow, tok0, a.T, tid);
     lds_barrier();
-    GKA_TSTAMP(2);
     build_row_frags<MMA, D>(sK, sRow, w, lane);
     build_transposed_frags<MMA, D>(sKT, sRow, w, lane);
     if (!valid) lam = 1.0f;
 #pragma unroll
     for (int i = 0; i < NB * NB; ++i) hn2 += hn[i];
-    GKA_TSTAMP(3);
     wait_all_memory();                         // H_[n] has landed in LDS
     lds_barrier();                           // fragments and H_[n] visible; the staging tile is free
-    GKA_TSTAMP(4);
 
-    GKA_TSTAMP(5);
     // ---------------- chunk-wise Frobenius norm ----------------
     // ||H_c||^2 = zeta_c^2 ||H_[n]||^2 + sum_{j<=c} m[j,c]^2 w_j,
     // w_j = 2 (zeta_j k_j^T H_[n] k_j + sum_{i<j} m[i,j] G_ij^2) / beta_j + G_jj^2,  G = K K^T:
@@ -446,7 +424,6 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     if (solve) {
         f32x16 acc[NJ + NBH];
         fused_gemm<MMA, NSTEPS, NJ + NBH, NoFill, NJ + NBH>(Aset, myK, acc, lane);
-        GKA_TSTAMP(12);
         // k_c^T H_[n] k_c: this wave's rows of H_[n] k_c, then summed over the two feature halves
         float a_part = 0.0f;
 #pragma unroll
@@ -472,16 +449,13 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         b_part -= bc * d_part;
         b_part += __shfl_xor(b_part, 32, 64);
         d_part += __shfl_xor(d_part, 32, 64);
-        GKA_TSTAMP(13);
         lds_barrier();
-        GKA_TSTAMP(14);
         if (fh == 0 && g == 0) {
             const float cross = 2.0f * (zeta * (sA[c_local] + sA[kChunk + c_local]) + b_part);
             sW[c_local] = GATED ? (bc > 0.0f ? cross / bc + d_part : 0.0f) : cross + d_part;
         }
     }
     lds_barrier();
-    GKA_TSTAMP(15);
     float fro;
     {
         float f_part = 0.0f;
@@ -496,7 +470,6 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
     if (GATED && !a.lambda) lam = valid ? a.lambda_scale * fro : 1.0f;      // Section 4.1: lambda_t = a ||H_t||_F
     if (!solve) lam = 1.0f;                    // plain readout: the discarded starting point stays finite
 
-    GKA_TSTAMP(6);
     // ---------------- Chebyshev iteration (Algorithm 1), residual form ----------------
     const float L = fro + lam, mu = lam;       // Section 4.1: L = ||H_t||_F + lambda_t, mu = lambda_t
     const float s0 = 2.0f / (L + mu);
@@ -612,7 +585,6 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int r = 0; r < 16; ++r) xi[i][r] += dl[i][r];                               // xi_r
 
-    GKA_TSTAMP(7);
     // ---------------- readout y_c = zeta_c U_[n] xhat_c + sum_{j<=c} M[j,c] v_j (k_j . xhat_c) ----------------
     constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
     const frag *Uw = (const frag *)a.ws_U + chunk_id * (NSPL * SH::H_FRAGS * 64);
@@ -675,13 +647,11 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
             for (int st = 0; st < NSTEPS; ++st) ulo[i][st] = Ulo[((mt0 + i) * NSTEPS + st) * 64 + lane_late];
     }
     lds_barrier();                           // every wave is done with H_[n], K^T and the exchange region
-    GKA_TSTAMP(8);
     async_block_copy<H16>(sH, Uw, w, lane_late);    // U_[n] (rounded part) replaces H_[n]
     vrows.store(sRow, tok0, a.T, tid_late);
     lds_barrier();
     build_transposed_frags<MMA, D, true>(sKT, sRow, w, lane_late);      // V^T replaces K^T
     lds_barrier();                           // the staging tile becomes the exchange region again
-    GKA_TSTAMP(9);
     publish_operand<MMA, NB>(sX, own, TW, mt0, lane);
     wait_all_memory();
     lds_barrier();
@@ -713,7 +683,6 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int r = 0; r < 16; ++r) y[i][r] = acc[NJ + i][r] * zeta;
     gemm_intra<MMA, NBH, TW>(sKT, mt0, pm, y, lane);
-    GKA_TSTAMP(10);
     if (valid) {
 #pragma unroll
         for (int i = 0; i < NBH; ++i)
@@ -722,7 +691,6 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
                 IO::store4(a.o, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g, y[i][4 * q4], y[i][4 * q4 + 1],
                            y[i][4 * q4 + 2], y[i][4 * q4 + 3]);
     }
-    GKA_TSTAMP(11);
 }
 
 template <class MMA, class IO, int D, bool GATED>
@@ -768,18 +736,20 @@ static hipError_t launch_chunk_solve_g(const SolveArgs &a, int n_pairs, hipStrea
 {
     typedef SolveShape<MMA, D> SH;
     auto kern = SolveKernel<MMA, IO, D, GATED>::fn;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)SH::lds_bytes);
+    // (set once per kernel instantiation and device, not per launch)
+    static bool attr_set_on[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64 || !attr_set_on[dev]) {
+        e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::lds_bytes);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) attr_set_on[dev] = true;
+    }
     SolveArgs args = a;
     args.n_pairs = n_pairs;
     dim3 grid((unsigned)(n_pairs * a.n_chunks)), block(kSolveThreads);
-#ifdef GKA_DEBUG_LDS_PAD
-    const size_t lds = SH::lds_bytes + GKA_DEBUG_LDS_PAD;
-    (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-#else
     const size_t lds = SH::lds_bytes;
-#endif
     hipLaunchKernelGGL(kern, grid, block, lds, stream, args);
     return hipGetLastError();
 }

@@ -28,28 +28,7 @@ template <class T>
 __device__ __forceinline__ void store_once(T *dst, T value) { __builtin_nontemporal_store(value, dst); }
 
 
-#ifdef GKA_DEBUG_TIMERS
-__device__ unsigned long long g_dbg_state_timers[64 * 16];
-#define GKA_STSTAMP(i)                                                                          \
-    do {                                                                                        \
-        if (threadIdx.x == 0 && blockIdx.x >= 128 && blockIdx.x < 192)                         \
-            g_dbg_state_timers[(blockIdx.x - 128) * 16 + (i)] = __builtin_amdgcn_s_memtime();  \
-    } while (0)
-extern "C" int gka_debug_read_state_timers(unsigned long long *host)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_dbg_state_timers), sizeof(g_dbg_state_timers));
-}
-#else
-#define GKA_STSTAMP(i) do {} while (0)
-#endif
-
-// k-row buffers of the bf16 body: the copy of a chunk's rows is issued GKA_STATE_KBUFS - 1 chunks ahead of its use
-#ifndef GKA_STATE_KBUFS
-#define GKA_STATE_KBUFS 3
-#endif
-#ifndef GKA_STATE_WAVES
-#define GKA_STATE_WAVES 2          // waves per SIMD the state-pass kernel is compiled for (register cap)
-#endif
+constexpr int kStateWavesPerSimd = 2;      // waves per SIMD the state-pass kernels are compiled for (register cap)
 
 // Start state of a workgroup's slab: the caller's initial state scanned with the summaries (decay, Delta) of the
 // segments before this one. Accumulator element (r, lane (n, g)) = S0[32*rb + n][32*w + kidx(r, g)].
@@ -181,8 +160,6 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
     float Gseg = 0.0f;
 
     auto process = [&](const Fetch &f, int c) {
-        const bool stamp = (c == chunk_begin + 20);
-        if (stamp) GKA_STSTAMP(1);
         // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights beta_j 2^(G_C - G_j)
         const float lg = (c * kChunk + lane < a.T) ? log2_gate(f.gate) : 0.0f;
         const float G = wave_inclusive_scan(lg, lane);
@@ -190,9 +167,7 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
         Gseg += Gtot;
         float swd = exp2f(0.5f * (Gtot - G));          // lane j: sqrt(beta_j zeta_C / zeta_j)
         if constexpr (GATED) swd *= sqrtf(a.beta ? f.beta : 1.0f);
-        if (stamp) GKA_STSTAMP(2);
         lds_barrier();                          // previous chunk's LDS readers are done
-        if (stamp) GKA_STSTAMP(3);
 #pragma unroll
         for (int i = 0; i < KP; ++i) {
             const int piece = i * NT + tid;
@@ -216,7 +191,6 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
             }
         }
         const float zetaC = exp2f(Gtot);
-        if (stamp) GKA_STSTAMP(4);
 
         // ---- write the state before the chunk, fragment order
         if (WRITE) {
@@ -254,9 +228,7 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
                 }
             }
         }
-        if (stamp) GKA_STSTAMP(5);
         lds_barrier();                          // s_k, s_v visible
-        if (stamp) GKA_STSTAMP(6);
 
         // ---- S <- zeta_C S + sum_j w_j a_j k_j^T
 #pragma unroll
@@ -281,7 +253,6 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
             }
             acc = MMA::mma(fa, fb, acc);
         }
-        if (stamp) GKA_STSTAMP(7);
     };
 
     // two fetch buffers in flight: while chunk c is processed, chunks c + 1 and c + 2 are on their way
@@ -289,7 +260,6 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
     // around memory operations)
     // An odd chunk count is evened out in front of the loop, with a fetch of its own, so that the loop body is the
     // only user of the two prefetch buffers.
-    GKA_STSTAMP(0);
     const int c_last = max(chunk_end - 1, chunk_begin);
     int c = chunk_begin;
     if ((chunk_end - chunk_begin) & 1) {
@@ -310,7 +280,6 @@ __device__ __forceinline__ void state_pass_body(const StatePassArgs &a, int rb, 
         }
     }
 
-    GKA_STSTAMP(8);
     if (a.final_mode == 1) {
         if (a.H_final && seg == a.n_segs - 1) {
             float *Sf = (doH ? a.H_final : a.U_final) + (int64_t)(a.final_pair0 + pair) * D * D;
@@ -342,256 +311,9 @@ __device__ __forceinline__ void drain_vector_memory()
     asm volatile("" ::: "memory");
 }
 
-// The eight operand fragments of one chunk update (4 MFMA steps x A, B) as sixteen transpose reads in one block
-// that ends with the wait for them. Written as assembly so that the compiler does not tie these reads to the
-// copies into LDS that are in flight for later chunks (it would wait for those as well). ka0 / ka1: byte
-// addresses in the k tile of this lane's place for token runs j and j + 4 of step 0 (later steps are 16 rows
-// further: a constant offset, the swizzle repeats every 8 rows); kb0: the same in the B tile, whose padded rows
-// make both the run and the step a constant offset.
-#define GKA_TR_READ(dst, addr, off) "ds_read_b64_tr_b16 %" #dst ", %" #addr " offset:" #off "\n\t"
-#define GKA_GATHER_CHUNK(A1, A2, A3)                                                                         \
-    asm volatile(GKA_TR_READ(0, 16, 0) GKA_TR_READ(1, 17, 0) GKA_TR_READ(2, 18, 0) GKA_TR_READ(3, 18, 384)   \
-                 GKA_TR_READ(4, 16, A1) GKA_TR_READ(5, 17, A1) GKA_TR_READ(6, 18, 1536) GKA_TR_READ(7, 18, 1920) \
-                 GKA_TR_READ(8, 16, A2) GKA_TR_READ(9, 17, A2) GKA_TR_READ(10, 18, 3072) GKA_TR_READ(11, 18, 3456) \
-                 GKA_TR_READ(12, 16, A3) GKA_TR_READ(13, 17, A3) GKA_TR_READ(14, 18, 4608) GKA_TR_READ(15, 18, 4992) \
-                 "s_waitcnt lgkmcnt(0)"                                                                       \
-                 : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]),   \
-                   "=&v"(r[7]), "=&v"(r[8]), "=&v"(r[9]), "=&v"(r[10]), "=&v"(r[11]), "=&v"(r[12]), "=&v"(r[13]), \
-                   "=&v"(r[14]), "=&v"(r[15])                                                                  \
-                 : "v"(ka0), "v"(ka1), "v"(kb0)                                                               \
-                 : "memory")
-template <int D>
-__device__ __forceinline__ void gather_chunk_operands(uint32_t ka0, uint32_t ka1, uint32_t kb0, bf16x8 (&fa)[4],
-                                                      bf16x8 (&fb)[4])
-{
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    static_assert(D == 128 || D == 64, "row bytes 256 or 128");
-    static_assert(MmaBF16::kRowPad == 16, "B tile rows are 96 bytes");
-    u32x2 r[16];
-    if constexpr (D == 128) GKA_GATHER_CHUNK(4096, 8192, 12288);
-    else GKA_GATHER_CHUNK(2048, 4096, 6144);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const u32x4 ua = {r[4 * s][0], r[4 * s][1], r[4 * s + 1][0], r[4 * s + 1][1]};
-        const u32x4 ub = {r[4 * s + 2][0], r[4 * s + 2][1], r[4 * s + 3][0], r[4 * s + 3][1]};
-        fa[s] = __builtin_bit_cast(bf16x8, ua);
-        fb[s] = __builtin_bit_cast(bf16x8, ub);
-    }
-}
-#undef GKA_GATHER_CHUNK
-#undef GKA_TR_READ
-
 __device__ __forceinline__ uint32_t lds_address(const void *p)
 {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
-}
-
-// bf16 tensors with bf16 operands: the same walk with less work per chunk on the critical path.
-//   - The chunk's k rows go from global memory straight into LDS (no registers, no conversion), into one of three
-//     swizzled buffers, two chunks ahead of their use. They are the A operand, unscaled.
-//   - The decay weight w_j = zeta_C / zeta_j is carried by the B operand alone: the slab's 32 columns of the k
-//     rows (H) or v rows (U) are prefetched into registers, scaled and stored to a small padded tile.
-// Vector-memory operations of one wave complete in issue order, so "the copy of chunk c has landed" is a counted
-// wait: every iteration issues, in this order, NA copies, NS state stores, [wait], NL prefetch loads.
-template <class IO, int D, bool DOH, bool WRITE, bool GATED>
-__device__ __forceinline__ void state_pass_body_bf16(const StatePassArgs &a, int rb, int group, uint16_t *s_k,
-                                                     uint16_t *s_b)
-{
-    typedef MmaBF16 MMA;
-    typedef typename MMA::frag frag;
-    constexpr int NB = D / 32;
-    constexpr int HS = MMA::HS;
-    constexpr int STEPS = kChunk / 16;            // MFMA steps over the chunk's tokens
-    constexpr int NT = D * 2;                     // threads
-    constexpr int NW = NT / 64;                   // waves
-    constexpr int RSB = 32 + MMA::kRowPad;        // row stride of the B tile
-    constexpr int ROWB = D * 2;                   // bytes per k row
-    constexpr int KBUF = kChunk * D;              // elements per k buffer
-    constexpr int NKB = GKA_STATE_KBUFS;          // k buffers
-    constexpr int PD = NKB - 1;                   // chunks between the issue of a copy and its use
-    static_assert(NKB >= 2 && NKB <= 3, "two or three buffers");
-    constexpr int NA = kChunk * ROWB / (NT * 16); // 16-byte copies per thread per chunk
-    constexpr int LPR = ROWB / 16;                // lanes (16-byte pieces) per row
-    constexpr int RPI = 64 / LPR;                 // rows per wave-wide copy instruction
-    constexpr int VP = kChunk * 8 / NT;           // 4-element pieces of the B tile per thread
-    constexpr int NSPL = MMA::kSplitReadout ? 2 : 1;
-    constexpr int NS = WRITE ? (DOH ? HS + 1 : HS * NSPL) : 0;   // state stores per chunk
-    constexpr int NL = VP + (GATED ? 2 : 1);      // prefetch loads per chunk (B pieces, gate, write gate)
-    typedef SwizzledRows<ROWB, 2> KRows;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // column block of the slab owned by this wave (uniform)
-    const int n = lane & 31, g = lane >> 5;
-    const int pair = group % a.n_pairs;
-    const int seg = group / a.n_pairs;
-    const int b = (a.pair0 + pair) / a.H, h = (a.pair0 + pair) % a.H;
-    const int64_t base_bh = (int64_t)b * a.stride_b + (int64_t)h * a.stride_h;
-    const int64_t gate_base = (int64_t)b * a.T * a.H + h;
-    const int chunk_begin = a.chunk0 + seg * a.seg_len;
-    const int chunk_end = min(chunk_begin + a.seg_len, a.chunk0 + a.n_chunks);
-    const int c_last = max(chunk_end - 1, chunk_begin);
-    const void *bsrc = DOH ? a.k : a.v;
-
-    f32x16 acc = zero16();
-    load_start_state<D, DOH>(a, acc, pair, seg, rb, w, lane);
-
-    // copy of chunk c's k rows into buffer `buf`: copy q of wave w fills rows (q NW + w) RPI .. + RPI of the tile
-    // (1 KiB); the lane picks the 16 source bytes that belong at its place of the swizzled row. Rows past the end
-    // of the sequence repeat the last row (finite values; their B rows are zero). The copies are buffer loads (a
-    // descriptor based at the chunk's first row, 32-bit byte offsets per lane).
-    const int lrow = lane / LPR, lbyte = (lane % LPR) * 16;
-    const int row_bytes = (int)a.stride_t * 2;
-    auto issue_k = [&](int c, int buf) {
-        const uint16_t *base = (const uint16_t *)a.k + base_bh + (int64_t)c * kChunk * a.stride_t;
-        const buffer_rsrc rsrc = make_raw_buffer(base);
-        const int last_row = a.T - 1 - c * kChunk;
-#pragma unroll
-        for (int q = 0; q < NA; ++q) {
-            const int row = (q * NW + w) * RPI + lrow;
-            const int sbyte = lbyte ^ ((row & KRows::kMask) << 5);
-            async_copy16_to_lds(s_k + buf * KBUF + (q * NW + w) * 512, rsrc, min(row, last_row) * row_bytes + sbyte, 0);
-        }
-    };
-    struct Fetch {
-        typename IO::raw4 b[VP];
-        float gate, beta;
-    };
-    // GATED without a write gate: the gates are read a second time and the value is replaced by 1, so that the
-    // number of loads per iteration is fixed
-    const float *beta_src = a.beta ? a.beta : a.gate;
-    auto fetch = [&](Fetch &f, int c) {
-#pragma unroll
-        for (int i = 0; i < VP; ++i) {
-            const int piece = i * NT + tid;
-            const int t = min(c * kChunk + piece / 8, a.T - 1);
-            f.b[i] = IO::load_raw4(bsrc, base_bh + (int64_t)t * a.stride_t + 32 * rb + 4 * (piece % 8));
-        }
-        const int t = min(c * kChunk + lane, a.T - 1);
-        f.gate = a.gate[gate_base + (int64_t)t * a.H];
-        if constexpr (GATED) f.beta = beta_src[gate_base + (int64_t)t * a.H];
-    };
-    float Gseg = 0.0f;
-    int kb = 0;                                   // buffer that holds the chunk being processed
-    // Transpose-read addresses of this lane (see gather_transposed_bf16): lane (n, g) gets tokens 16 s + 8 g + p of
-    // step s; within its block of 16 lanes, lane i addresses token run[i / 4] at the 4-column group i % 4.
-    static_assert(STEPS == 4, "one gather block per chunk");
-    const int sub = 16 * ((lane >> 4) & 1);       // this 16-lane block's columns within the 32
-    const int li = lane & 15;
-    const uint32_t ka0 = lds_address(s_k + KRows{}(8 * g + (li >> 2), 32 * w + sub + 4 * (li & 3)));
-    const uint32_t ka1 = lds_address(s_k + KRows{}(8 * g + 4 + (li >> 2), 32 * w + sub + 4 * (li & 3)));
-    const uint32_t kb0 = lds_address(s_b + (8 * g + (li >> 2)) * RSB + sub + 4 * (li & 3));
-
-    auto process = [&](const Fetch &f, int c) {
-        // nothing of this chunk is scheduled into the previous one (its prefetched values arrive last)
-        __builtin_amdgcn_sched_barrier(0);
-        const bool stamp = (c == chunk_begin + 20);
-        if (stamp) GKA_STSTAMP(1);
-        // ---- gates of the chunk: G_j = sum_{i<=j} log2 gamma_i, weights beta_j zeta_C / zeta_j = beta_j 2^(G_C - G_j)
-        const bool valid = c * kChunk + lane < a.T;
-        const float lg = valid ? log2_gate(f.gate) : 0.0f;
-        const float G = wave_inclusive_scan(lg, lane);
-        const float Gtot = lane_value(G, 63);
-        Gseg += Gtot;
-        float wj = valid ? exp2f(Gtot - G) : 0.0f;     // lane j: weight of token j
-        if constexpr (GATED) wj *= a.beta ? f.beta : 1.0f;
-        const float zetaC = exp2f(Gtot);
-        if (stamp) GKA_STSTAMP(2);
-        lds_barrier();                          // the previous chunk's operand reads are done
-        if (stamp) GKA_STSTAMP(3);
-        const int kb2 = kb >= 1 ? kb - 1 : NKB - 1;   // (kb + PD) % NKB: the previous chunk's buffer
-        issue_k(min(c + PD, c_last), kb2);
-#pragma unroll
-        for (int i = 0; i < VP; ++i) {
-            const int piece = i * NT + tid;
-            const int row = piece / 8;
-            MMA::store4(s_b + row * RSB + 4 * (piece % 8), IO::cvt4(f.b[i]) * __shfl(wj, row, 64));
-        }
-        if (stamp) GKA_STSTAMP(4);
-
-        // ---- write the state before the chunk, fragment order
-        if (WRITE) {
-            const int64_t chunk_id = (int64_t)(c - a.chunk0) * a.n_pairs + pair;   // chunk-major: pairs adjacent
-            float vals[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) vals[r] = acc[r];
-            if (DOH) {
-                frag *Hw = (frag *)a.ws_H + chunk_id * (NB * NB * HS * 64);
-                float ss = 0.0f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) ss += acc[r] * acc[r];
-#pragma unroll
-                for (int hh = 0; hh < HS; ++hh)
-                    Hw[((rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(vals + hh * MMA::VEC);
-                ss = wave_inclusive_scan(ss, lane);           // lane 63: the wave's total
-                if (lane == 63) a.ws_hn[chunk_id * (NB * NB) + rb * NB + w] = ss;
-            } else {
-                frag *Uw = (frag *)a.ws_U + chunk_id * (NSPL * NB * NB * HS * 64);
-                float lo[16];
-#pragma unroll
-                for (int hh = 0; hh < HS; ++hh) {
-                    frag fr = MMA::pack(vals + hh * MMA::VEC);
-                    Uw[((rb * NB + w) * HS + hh) * 64 + lane] = fr;
-                    float back[MMA::VEC];
-                    MMA::unpack(fr, back);
-#pragma unroll
-                    for (int p = 0; p < MMA::VEC; ++p) lo[hh * MMA::VEC + p] = vals[hh * MMA::VEC + p] - back[p];
-                }
-                if (NSPL == 2) {
-#pragma unroll
-                    for (int hh = 0; hh < HS; ++hh)
-                        Uw[(NB * NB * HS + (rb * NB + w) * HS + hh) * 64 + lane] = MMA::pack(lo + hh * MMA::VEC);
-                }
-            }
-        }
-        if (stamp) GKA_STSTAMP(5);
-        // This chunk's copy was issued PD iterations ago, right after a barrier. Since then the wave has issued at
-        // least PD - 1 whole iterations (copies, stores, prefetch loads) and this iteration's copies and stores.
-        wait_vector_memory_upto<(PD - 1) * (NA + NS + NL) + NA + NS>();
-        lds_barrier();                          // k rows (all waves' copies) and the B tile are visible
-        if (stamp) GKA_STSTAMP(6);
-
-        // ---- S <- zeta_C S + sum_j w_j a_j k_j^T
-        frag fa[STEPS], fb[STEPS];
-        gather_chunk_operands<D>(ka0 + kb * (KBUF * 2), ka1 + kb * (KBUF * 2), kb0, fa, fb);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] *= zetaC;
-#pragma unroll
-        for (int s = 0; s < STEPS; ++s) acc = MMA::mma(fa[s], fb[s], acc);
-        kb = kb == NKB - 1 ? 0 : kb + 1;
-        if (stamp) GKA_STSTAMP(7);
-    };
-
-    // Before the loop: copies of the first two chunks and their prefetches, all waited for once. An odd chunk
-    // count is evened out in front of the loop so that the loop body is the only user of its two prefetch buffers.
-    GKA_STSTAMP(0);
-    int c = chunk_begin;
-    issue_k(c, 0);
-    if (PD > 1) issue_k(min(c + 1, c_last), 1);
-    if ((chunk_end - chunk_begin) & 1) {
-        Fetch fp;
-        fetch(fp, c);
-        drain_vector_memory();
-        process(fp, c);
-        ++c;
-    }
-    if (c < chunk_end) {
-        Fetch f0, f1;
-        fetch(f0, c);
-        fetch(f1, c + 1);
-        drain_vector_memory();
-        for (; c < chunk_end; c += 2) {
-            process(f0, c);
-            fetch(f0, min(c + 2, c_last));
-            process(f1, c + 1);
-            fetch(f1, min(c + 3, c_last));
-        }
-    }
-    // no copy into this workgroup's LDS may still be in flight when it ends
-    drain_vector_memory();
-    GKA_STSTAMP(8);
-    store_end_state<D, DOH>(a, acc, Gseg, pair, seg, rb, w, lane);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -836,7 +558,7 @@ __device__ __forceinline__ void state_pass_body_bf16_tile(const StatePassArgs &a
 // One workgroup per (pair, segment, H or U). The two workgroups of a (pair, segment) read the same k rows: they get
 // block indices that are equal modulo 8, i.e. the same XCD and L2.
 template <class IO, int D, bool GATED>
-__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE_WAVES))) void state_pass_tile_kernel(StatePassArgs a)
+__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(kStateWavesPerSimd))) void state_pass_tile_kernel(StatePassArgs a)
 {
     constexpr int PER = 2;
     const int id = blockIdx.x;
@@ -864,7 +586,7 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
 }
 
 template <class MMA, class IO, int D, bool GATED>
-__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE_WAVES))) void state_pass_kernel(StatePassArgs a)
+__global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(kStateWavesPerSimd))) void state_pass_kernel(StatePassArgs a)
 {
     constexpr int NB = D / 32;
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2. The 2 NB workgroups of one
@@ -887,35 +609,21 @@ __global__ __launch_bounds__(D * 2) __attribute__((amdgpu_waves_per_eu(GKA_STATE
     if (a.only_h && (sub & 1)) return;             // ... or its U states
     const int rb = sub >> 1;                       // slab index (row block of H0 / U0)
     typedef typename MMA::elem_t elem_t;
-    constexpr bool kDirect = std::is_same<MMA, MmaBF16>::value;    // k rows copied straight into LDS
-    __shared__ __attribute__((aligned(1024))) elem_t s_k[kDirect ? GKA_STATE_KBUFS * kChunk * D : kChunk * (D + MMA::kRowPad)];
+    __shared__ __attribute__((aligned(1024))) elem_t s_k[kChunk * (D + MMA::kRowPad)];
     __shared__ __attribute__((aligned(16))) elem_t s_v[kChunk * (32 + MMA::kRowPad)];
-    if constexpr (kDirect) {
-        if (a.write_frags) {
-            if (sub & 1) state_pass_body_bf16<IO, D, false, true, GATED>(a, rb, group, s_k, s_v);
-            else state_pass_body_bf16<IO, D, true, true, GATED>(a, rb, group, s_k, s_v);
-        } else {
-            if (sub & 1) state_pass_body_bf16<IO, D, false, false, GATED>(a, rb, group, s_k, s_v);
-            else state_pass_body_bf16<IO, D, true, false, GATED>(a, rb, group, s_k, s_v);
-        }
+    if (a.write_frags) {
+        if (sub & 1) state_pass_body<MMA, IO, D, false, true, GATED>(a, rb, group, s_k, s_v);
+        else state_pass_body<MMA, IO, D, true, true, GATED>(a, rb, group, s_k, s_v);
     } else {
-        if (a.write_frags) {
-            if (sub & 1) state_pass_body<MMA, IO, D, false, true, GATED>(a, rb, group, s_k, s_v);
-            else state_pass_body<MMA, IO, D, true, true, GATED>(a, rb, group, s_k, s_v);
-        } else {
-            if (sub & 1) state_pass_body<MMA, IO, D, false, false, GATED>(a, rb, group, s_k, s_v);
-            else state_pass_body<MMA, IO, D, true, false, GATED>(a, rb, group, s_k, s_v);
-        }
+        if (sub & 1) state_pass_body<MMA, IO, D, false, false, GATED>(a, rb, group, s_k, s_v);
+        else state_pass_body<MMA, IO, D, true, false, GATED>(a, rb, group, s_k, s_v);
     }
 }
 
 // Workgroups per (pair, segment): bf16 operands use the whole-tile kernel (one workgroup for H, one for U), fp32
 // operands the slab kernel (one per 32-row slab and state).
-#ifndef GKA_STATE_SLABS
-#define GKA_STATE_SLABS 0          // 1: bf16 operands on the slab kernel as well
-#endif
 template <class MMA, int D>
-constexpr bool uses_tile_kernel() { return std::is_same<MMA, MmaBF16>::value && !GKA_STATE_SLABS; }
+constexpr bool uses_tile_kernel() { return std::is_same<MMA, MmaBF16>::value; }
 
 template <class MMA, class IO, int D, bool GATED>
 static void launch_state_kernel(const StatePassArgs &a, int n_groups, hipStream_t stream)
@@ -963,7 +671,7 @@ static hipError_t launch_state_pass_t(const StatePassArgs &a, int n_pairs, hipSt
 
 int state_pass_workgroups_per_segment(int n_pairs, int d, bool compute_bf16)
 {
-    const bool tile = compute_bf16 && !GKA_STATE_SLABS;
+    const bool tile = compute_bf16;
     return n_pairs * 2 * (tile ? 1 : d / 32);
 }
 

@@ -29,7 +29,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_version_and_status_strings(lib):
     assert binding.version() >= 100
-    for s in range(6):
+    for s in range(7):
         assert binding.status_string(s)
     assert binding.status_string(binding.GKA_OK) == "ok"
 
