@@ -51,33 +51,43 @@ void gka_oracle_omega_schedule(double L, double mu, int r, double *omega_out)
     }
 }
 
-/* Algorithm 1 (Chebyshev Iteration) for A xi = q, A a D x D symmetric positive definite
- * matrix (already regularised) with spectrum inside [mu, L].  r loop passes; r = 0 returns
- * xi_0 = 2 q / (L + mu).  The two assignments of the loop body (gradient-descent step, then
- * momentum step) are applied in the paper's order.  work holds 3*D doubles. */
+/* Chebyshev Iteration (Algorithm 1) for A xi = q, A a D x D symmetric positive definite matrix (already
+ * regularised) with spectrum inside [mu, L], written as the three-term semi-iterative method it is: with the
+ * damped Richardson map
+ *     R(x) = x + tau (q - A x),   tau = 2 / (L + mu),
+ * the iterates are xi_0 = R(0) and xi_i = xi_{i-2} + omega_i (R(xi_{i-1}) - xi_{i-2}), omega_i from
+ * gka_oracle_omega_schedule. (Substituting the first assignment of the algorithm's loop body into the second gives
+ * exactly this.) r >= 0 passes; work holds 3*D doubles. */
+static void richardson_map(int D, const double *A, const double *q, double tau, const double *x, double *out)
+{
+    for (int a = 0; a < D; ++a) {
+        double Ax = 0.0;
+        for (int b = 0; b < D; ++b) Ax += A[(size_t)a * D + b] * x[b];
+        out[a] = x[a] + tau * (q[a] - Ax);
+    }
+}
+
 void gka_oracle_chebyshev(int D, const double *A, const double *q, double L, double mu,
                           int r, double *xi_out, double *work)
 {
-    double *xi_prev = work;          /* xi_{i-2} */
-    double *xi_cur = work + D;       /* xi_{i-1} */
-    double *xi_new = work + 2 * D;   /* xi_i     */
-    double rho = (L - mu) / (L + mu);
+    double *older = work;            /* xi_{i-2} */
+    double *newer = work + D;        /* xi_{i-1} */
+    double *mapped = work + 2 * D;   /* R(xi_{i-1}), then xi_i */
+    const double tau = 2.0 / (L + mu);
+    const double rho = (L - mu) / (L + mu);
     double omega = 2.0;
-    for (int a = 0; a < D; ++a) {
-        xi_prev[a] = 0.0;
-        xi_cur[a] = 2.0 * q[a] / (L + mu);
-    }
+    memset(older, 0, (size_t)D * sizeof(double));
+    richardson_map(D, A, q, tau, older, newer);
     for (int i = 1; i <= r; ++i) {
-        omega = 4.0 / (4.0 - rho * rho * omega);                       /* weight schedule */
-        for (int a = 0; a < D; ++a) {
-            double Axi = 0.0;
-            for (int b = 0; b < D; ++b) Axi += A[(size_t)a * D + b] * xi_cur[b];
-            double t = xi_cur[a] - (2.0 * omega / (L + mu)) * (Axi - q[a]);   /* grad descent */
-            xi_new[a] = t + (omega - 1.0) * (xi_cur[a] - xi_prev[a]);          /* momentum */
-        }
-        double *tmp = xi_prev; xi_prev = xi_cur; xi_cur = xi_new; xi_new = tmp;
+        omega = 4.0 / (4.0 - rho * rho * omega);
+        richardson_map(D, A, q, tau, newer, mapped);
+        for (int a = 0; a < D; ++a) mapped[a] = older[a] + omega * (mapped[a] - older[a]);
+        double *recycled = older;
+        older = newer;
+        newer = mapped;
+        mapped = recycled;
     }
-    for (int a = 0; a < D; ++a) xi_out[a] = xi_cur[a];
+    memcpy(xi_out, newer, (size_t)D * sizeof(double));
 }
 
 /* Exact solve of A x = q by Cholesky factorisation A = R^T R (A is overwritten).
