@@ -175,7 +175,8 @@ struct PhaseEvents {
 gka_status forward_impl(const gka_params *p, const void *q, const void *k, const void *v, const float *gate,
                         const float *lambda, void *o, const float *H_init, const float *U_init, float *H_final,
                         float *U_final, float *fro_out, void *workspace, size_t workspace_bytes,
-                        void *hip_stream, PhaseEvents *prof, bool readout_only = false, bool solve_only = false)
+                        void *hip_stream, PhaseEvents *prof, bool readout_only = false, bool solve_only = false,
+                        const void *q_lo = nullptr)
 {
     Plan pl;
     gka_status s = make_plan(p, &pl, readout_only);
@@ -189,7 +190,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     char *ws = (char *)workspace;
 
     const bool fused_ok = pl.fused_shape && !p->beta && !p->alpha && lambda && !p->xhat_out && !solve_only &&
-                          p->phase == GKA_PHASE_ALL;
+                          !q_lo && p->phase == GKA_PHASE_ALL;
     if (p->path == GKA_PATH_FUSED && !fused_ok) return GKA_ERR_UNSUPPORTED;
     if (fused_ok && p->path != GKA_PATH_TWO_PHASE) {
         gka::FusedArgs fa;
@@ -221,7 +222,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     sa.seg_buf = (float *)(ws + pl.off_seg); sa.seg_logdecay = (float *)(ws + pl.off_segdecay);
     sa.init_mode = 0; sa.final_mode = 0; sa.write_frags = 1;
     gka::SolveArgs so;
-    so.q = q; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
+    so.q = q; so.q_lo = q_lo; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
     so.beta = p->beta; so.alpha = p->alpha; so.lambda_scale = p->lambda_scale;
     so.xhat_out = p->xhat_out;
     // plain readout y_t = U_t q_t (used by the backward pass): needs alpha = 0 from the caller; no H states, no solve
@@ -405,13 +406,13 @@ void plan_readout_segments(int n_pairs, int n_chunks, int *n_segs, int *seg_len)
 
 struct BackwardPlan {
     size_t n_elems, n_tokens, esz;
-    size_t off_f32[7];        // xhat, p; with the fused readouts also y, H x, A k, A^T k, Ubar k in float32
-    size_t off_io[20];
+    size_t off_f32[9];        // xhat, p; with the fused readouts also y, H x, A k, A^T k, Ubar k, U^T dy, Ubar^T v
+    size_t off_io[23];
     size_t off_m[6];          // gate_rev, zeros, s, fro, c, C
     size_t off_fwd, fwd_bytes, total;
 };
 enum { IO_Y, IO_DXT, IO_RHS, IO_HX, IO_X, IO_XT, IO_KR, IO_VR, IO_DYR, IO_XR, IO_PR, IO_XTR, IO_R1, IO_R2, IO_R3, IO_R4,
-       IO_SCRATCH, IO_HK, IO_VPR, IO_R5 };
+       IO_SCRATCH, IO_HK, IO_VPR, IO_R5, IO_RHS_LO, IO_X_LO, IO_XT_LO };
 
 gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
 {
@@ -423,8 +424,8 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     bp->n_elems = bp->n_tokens * p->d_k;
     bp->esz = p->io_dtype == GKA_BF16 ? 2 : 4;
     size_t off = 0;
-    for (int i = 0; i < 7; ++i) { bp->off_f32[i] = off; off = align_up(off + bp->n_elems * 4, 256); }
-    for (int i = 0; i < 20; ++i) { bp->off_io[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
+    for (int i = 0; i < 9; ++i) { bp->off_f32[i] = off; off = align_up(off + bp->n_elems * 4, 256); }
+    for (int i = 0; i < 23; ++i) { bp->off_io[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
     for (int i = 0; i < 6; ++i) { bp->off_m[i] = off; off = align_up(off + bp->n_tokens * 4, 256); }
     bp->off_fwd = off;
     gka_params pf = *p;
@@ -489,13 +490,13 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     // recurrence U_t = gate_t U_{t-1} + beta_t v_t k_t^T (the solve is reduced to its starting point and discarded)
     auto fwd = [&](const void *qq, const void *kk, const void *vv, const float *gg, const float *beta,
                    const float *alpha, int n_iter, void *out, float *xhat, float *fro_out = nullptr,
-                   bool solve_only = false) {
+                   bool solve_only = false, const void *q_lo = nullptr) {
         gka_params pp = *p;                      // lambda (or its rule) as given: only the two solves use it
         pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat;
         pp.state_layout = GKA_STATE_FULL;
         const bool plain_readout = alpha == zeros;
         return forward_impl(&pp, qq, kk, vv, gg, lambda, out, nullptr, nullptr, nullptr, nullptr, fro_out, fws,
-                            bp.fwd_bytes, hip_stream, nullptr, plain_readout, solve_only);
+                            bp.fwd_bytes, hip_stream, nullptr, plain_readout, solve_only, q_lo);
     };
     auto glue = [&](int which) {
         return gka::launch_backward_glue(g, which, io_bf16, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
@@ -505,10 +506,13 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     // (bf16 tensors: whatever operands the two solves use, the readouts take the stored bf16 tensors as they are)
     const bool fused = io_bf16;
     // out_f32: the output in float32 (the pieces of the gate gradient's sum), else in the tensors' dtype
+    // q_lo, k_lo, v_lo: the bf16 remainder of an operand that was computed in float32 (x, xt), or nullptr
     auto readout = [&](const void *qq, const void *kk, const void *vv, const float *beta, bool reverse, void *out,
-                       int seg_mode = 0, float *out_f32 = nullptr) {
+                       int seg_mode = 0, float *out_f32 = nullptr, const void *q_lo = nullptr,
+                       const void *k_lo = nullptr, const void *v_lo = nullptr) {
         gka::ReadoutArgs r;
-        r.q = qq; r.q_lo = nullptr; r.q_is_f32 = false; r.k = kk; r.v = vv; r.o = out; r.o_f32 = out_f32;
+        r.q = qq; r.q_lo = q_lo; r.k_lo = k_lo; r.v_lo = v_lo; r.q_is_f32 = false; r.k = kk; r.v = vv; r.o = out;
+        r.o_f32 = out_f32;
         r.gate = gate; r.beta = beta;
         r.stride_h = p->d_k; r.stride_t = (int64_t)p->H * p->d_k; r.stride_b = (int64_t)p->T * p->H * p->d_k;
         r.qk_stride_h = r.stride_h; r.qk_stride_t = r.stride_t; r.qk_stride_b = r.stride_b;
@@ -520,8 +524,11 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
         return gka::launch_gla_readout(r, p->d_k, p->d_v, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
     };
     g.natural_order = fused;
-    if (fused) {                                  // these five arrive in float32 (see the combine kernel)
+    if (fused) {                                  // these seven arrive in float32 (see the combine kernel)
         g.y_io = f32buf(2); g.hx_io = f32buf(3); g.r1 = f32buf(4); g.r2 = f32buf(5); g.r4 = f32buf(6);
+        g.dxt_io = f32buf(7); g.r3 = f32buf(8);
+        // bf16 tensors: the second solve takes alpha dxt, and the readouts take x and xt, as value + remainder
+        g.rhs_lo_io = io(IO_RHS_LO); g.x_lo_io = io(IO_X_LO); g.xt_lo_io = io(IO_XT_LO);
     }
 #define GKA_TRY(expr) do { gka_status e_ = (expr); if (e_ != GKA_OK) return e_; } while (0)
     // the forward solve and output; then x, xt in the tensors' dtype, the all-zero alpha and the reversed gates
@@ -529,16 +536,17 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf, rule ? fro : nullptr, fused));
     GKA_TRY(glue(0));
     // y_t again, from the stored xt (see the combine kernel)
-    if (fused) GKA_TRY(readout(io(IO_XT), k, v, p->beta, false, nullptr, 0, f32buf(2)));
+    if (fused) GKA_TRY(readout(io(IO_XT), k, v, p->beta, false, nullptr, 0, f32buf(2), io(IO_XT_LO)));
     // dxt_t = U_t^T dy_t: the recurrence with the roles of k and v exchanged, read out with dy
     // (its state is the transpose of the one just read out: the segment summaries are reused)
-    if (fused) GKA_TRY(readout(dy, v, k, p->beta, false, io(IO_DXT), 2));
+    if (fused) GKA_TRY(readout(dy, v, k, p->beta, false, nullptr, 2, f32buf(7)));
     else GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
     GKA_TRY(glue(1));
     // p_t = CH(H_t + lambda_t I, alpha_t dxt_t, r)
-    GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32, nullptr, fused));
+    GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32, nullptr, fused,
+                fused ? io(IO_RHS_LO) : nullptr));
     // H_t x_t
-    if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, nullptr, 0, f32buf(3)));
+    if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, nullptr, 0, f32buf(3), io(IO_X_LO)));
     else GKA_TRY(fwd(io(IO_X), k, k, gate, p->beta, zeros, 0, io(IO_HX), nullptr));
     // the rule's extra gradient -c_t H_t at every state: c_t, C_t = sum_{s>=t} M[t,s]^2 c_s, and H_t k_t
     if (rule) {
@@ -551,10 +559,10 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     GKA_TRY(glue(2));
     if (fused) {
         if (rule) GKA_TRY(readout(k, k, io(IO_VPR), nullptr, true, io(IO_R5)));
-        GKA_TRY(readout(k, io(IO_X), io(IO_PR), nullptr, true, nullptr, 0, f32buf(4)));
-        GKA_TRY(readout(k, io(IO_PR), io(IO_X), nullptr, true, nullptr, 2, f32buf(5)));
-        GKA_TRY(readout(v, dy, io(IO_XT), nullptr, true, io(IO_R3)));
-        GKA_TRY(readout(k, io(IO_XT), dy, nullptr, true, nullptr, 2, f32buf(6)));
+        GKA_TRY(readout(k, io(IO_X), io(IO_PR), nullptr, true, nullptr, 0, f32buf(4), nullptr, io(IO_X_LO), nullptr));
+        GKA_TRY(readout(k, io(IO_PR), io(IO_X), nullptr, true, nullptr, 2, f32buf(5), nullptr, nullptr, io(IO_X_LO)));
+        GKA_TRY(readout(v, dy, io(IO_XT), nullptr, true, nullptr, 0, f32buf(8), nullptr, nullptr, io(IO_XT_LO)));
+        GKA_TRY(readout(k, io(IO_XT), dy, nullptr, true, nullptr, 2, f32buf(6), nullptr, io(IO_XT_LO), nullptr));
     } else {
         if (rule) GKA_TRY(fwd(io(IO_KR), io(IO_KR), io(IO_VPR), gate_rev, nullptr, zeros, 0, io(IO_R5), nullptr));
         GKA_TRY(fwd(io(IO_KR), io(IO_XR), io(IO_PR), gate_rev, nullptr, zeros, 0, io(IO_R1), nullptr));
@@ -644,6 +652,7 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
                       nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr, false, true);
     if (st != GKA_OK) return st;
     gka::ReadoutArgs r;
+    r.k_lo = nullptr; r.v_lo = nullptr;
     r.v = v; r.o = o; r.o_f32 = nullptr; r.gate = gate; r.beta = p->beta;
     r.stride_h = p->d_v; r.stride_t = (int64_t)p->H * p->d_v; r.stride_b = (int64_t)p->T * p->H * p->d_v;
     r.H = p->H; r.T = p->T; r.n_pairs = n_pairs;

@@ -27,9 +27,17 @@ __global__ __launch_bounds__(256) void bwd_mix_kernel(BackwardGlueArgs a)
     const float al = a.alpha ? a.alpha[tok] : 1.0f;
     const f32x4 x = load_f32x4(a.x_f32, i);
     const f32x4 q = IO::load4(a.q, i);
+    const f32x4 xt = {al * x[0] + (1.0f - al) * q[0], al * x[1] + (1.0f - al) * q[1],
+                      al * x[2] + (1.0f - al) * q[2], al * x[3] + (1.0f - al) * q[3]};
     IO::store4(a.x_io, i, x[0], x[1], x[2], x[3]);
-    IO::store4(a.xt_io, i, al * x[0] + (1.0f - al) * q[0], al * x[1] + (1.0f - al) * q[1],
-               al * x[2] + (1.0f - al) * q[2], al * x[3] + (1.0f - al) * q[3]);
+    IO::store4(a.xt_io, i, xt[0], xt[1], xt[2], xt[3]);
+    if (a.x_lo_io) {
+        // bf16 tensors: the gradients at k and at the gates are small differences of sums over these operands, so
+        // what their rounding leaves over goes along as a second operand
+        const f32x4 xh = IO::load4(a.x_io, i), xth = IO::load4(a.xt_io, i);
+        IO::store4(a.x_lo_io, i, x[0] - xh[0], x[1] - xh[1], x[2] - xh[2], x[3] - xh[3]);
+        IO::store4(a.xt_lo_io, i, xt[0] - xth[0], xt[1] - xth[1], xt[2] - xth[2], xt[3] - xth[3]);
+    }
     // once per token: the all-zero alpha of the plain readouts and the gates of the reverse recurrences,
     // gate'_tau = gate_{T - tau} for tau >= 1 (gate'_0 multiplies a zero state: 1)
     if (i - tok * a.d == 0) {
@@ -47,8 +55,14 @@ __global__ __launch_bounds__(256) void bwd_rhs_kernel(BackwardGlueArgs a)
     const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= a.n_elems) return;
     const float al = a.alpha ? a.alpha[i / a.d] : 1.0f;
-    const f32x4 g = IO::load4(a.dxt_io, i);
-    IO::store4(a.rhs_io, i, al * g[0], al * g[1], al * g[2], al * g[3]);
+    const f32x4 g = a.natural_order ? load_f32x4((const float *)a.dxt_io, i) : IO::load4(a.dxt_io, i);
+    const f32x4 rhs = {al * g[0], al * g[1], al * g[2], al * g[3]};
+    IO::store4(a.rhs_io, i, rhs[0], rhs[1], rhs[2], rhs[3]);
+    if (a.rhs_lo_io) {
+        // the solve amplifies a perturbation of its right-hand side: the rounding remainder goes along
+        const f32x4 hi = IO::load4(a.rhs_io, i);
+        IO::store4(a.rhs_lo_io, i, rhs[0] - hi[0], rhs[1] - hi[1], rhs[2] - hi[2], rhs[3] - hi[3]);
+    }
 }
 
 // Time reversal tau = T - 1 - t of k, v, dy, x, p, xt (p converted from float32 on the way).
@@ -177,8 +191,8 @@ __global__ __launch_bounds__(256) void bwd_combine_kernel(BackwardGlueArgs a)
     auto piece = [&](const void *ptr, int64_t idx) {
         return a.natural_order ? load_f32x4((const float *)ptr, idx) : IO::load4(ptr, idx);
     };
-    const f32x4 dxt = IO::load4(a.dxt_io, i), y = piece(a.y_io, i), hx = piece(a.hx_io, i);
-    const f32x4 a1 = piece(a.r1, ri), a2 = piece(a.r2, ri), u1 = IO::load4(a.r3, ri), d4 = piece(a.r4, ri);
+    const f32x4 dxt = piece(a.dxt_io, i), y = piece(a.y_io, i), hx = piece(a.hx_io, i);
+    const f32x4 a1 = piece(a.r1, ri), a2 = piece(a.r2, ri), u1 = piece(a.r3, ri), d4 = piece(a.r4, ri);
     f32x4 hk = {0.0f, 0.0f, 0.0f, 0.0f}, r5 = hk;
     float kk = 0.0f;                             // k_t . k_t (the rule's diagonal term)
     if (rule) {

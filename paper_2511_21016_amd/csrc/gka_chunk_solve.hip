@@ -365,6 +365,18 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4)
             qraw[i][q4] = IO::load_raw4(a.q, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g);
+    typename IO::raw4 qlo[GATED ? NBH : 1][4];   // remainder of the right-hand side (variants' kernel), if given
+    bool has_qlo = false;
+    if constexpr (GATED) {
+        has_qlo = a.q_lo != nullptr;
+        if (has_qlo) {
+#pragma unroll
+            for (int i = 0; i < NBH; ++i)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    qlo[i][q4] = IO::load_raw4(a.q_lo, tok_off + 32 * (mt0 + i) + 8 * q4 + 4 * g);
+        }
+    }
     lam = ((!GATED || a.lambda) ? a.lambda : a.gate)[gate_base + (int64_t)min(tok, a.T - 1) * a.H];
     float hn[NB * NB];
 #pragma unroll
@@ -483,7 +495,10 @@ __device__ __forceinline__ void chunk_solve_wave(const SolveArgs &a, unsigned ch
         gS[i] = zero16();
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-            const f32x4 qv4 = IO::cvt4(qraw[i][q4]);
+            f32x4 qv4 = IO::cvt4(qraw[i][q4]);
+            if constexpr (GATED) {
+                if (has_qlo) qv4 += IO::cvt4(qlo[i][q4]);
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float qv = valid ? qv4[e] : 0.0f;

@@ -36,6 +36,8 @@ struct StatePassArgs {
 
 struct SolveArgs {
     const void *q, *k, *v;
+    const void *q_lo;             // variants' kernel: optional remainder of q in the tensors' dtype (the right-hand side
+                                  // of the solve is q + q_lo), or nullptr
     const float *gate, *lambda;   // lambda nullptr: lambda_t = lambda_scale ||H_t||_F
     const float *beta, *alpha;    // [B,T,H] write gate / alpha-connection, each nullptr (= 1)
     float lambda_scale;
@@ -74,6 +76,8 @@ struct BackwardGlueArgs {
     const float *gate, *alpha, *beta;                      // alpha, beta may be nullptr (= 1)
     const float *x_f32, *p_f32;   // results of the two solves
     void *x_io, *xt_io, *rhs_io;  // x, alpha x + (1 - alpha) q, alpha dxt
+    void *rhs_lo_io;              // bf16 tensors: what rounding alpha dxt to rhs_io left over (nullptr: not kept)
+    void *x_lo_io, *xt_lo_io;     // likewise for x_io and xt_io
     const void *dxt_io, *y_io, *hx_io;                     // U_t^T dy_t, forward output, H_t x_t
     void *k_rev, *v_rev, *dy_rev, *x_rev, *p_rev, *xt_rev; // time-reversed copies
     float *gate_rev, *zeros;      // gates of the reverse recurrences; an all-zero alpha
@@ -85,8 +89,8 @@ struct BackwardGlueArgs {
     float *c, *C;                 // c_t and C_t = sum_{s>=t} M[t,s]^2 c_s
     void *vp_rev;                 // time-reversed beta_t C_t k_t
     bool natural_order;           // the reversed passes read and write the tensors in place (gla_readout `reverse`):
-                                  // nothing is reversed here, p_rev and vp_rev are plain conversions, and y_io, hx_io,
-                                  // r1, r2, r4 are float32
+                                  // nothing is reversed here, p_rev and vp_rev are plain conversions, and dxt_io, y_io,
+                                  // hx_io, r1, r2, r3, r4 are float32
     const void *hk_io, *r5;       // H_t k_t; reversed pass sum_{j>=t} M[t,j] beta_j C_j k_j (k_j . k_t)
 };
 // which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan, 5 rule scalars (c_t), 6 rule scan (C_t)
@@ -98,6 +102,9 @@ hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf
 struct ReadoutArgs {
     const void *q, *k, *v;        // q, k: [B,T,H,dk]; v: [B,T,H,dv]
     const void *q_lo;             // optional bf16 remainder of q (y_t = U_t (q_t + q_lo_t)), or nullptr
+    const void *k_lo, *v_lo;      // optional bf16 remainder of k or of v (at most one of the two; dk = dv only), laid out
+                                  // like k / v: the recurrence is that of k + k_lo (v + v_lo). For operands that were
+                                  // computed in float32 (the solves' results in the backward pass)
     bool q_is_f32;                // q is float32 (split into value + remainder inside); dk = 64, dv = 128 only
     void *o;                      // [B,T,H,dv]
     float *o_f32;                 // if not nullptr the output goes here in float32 instead (same strides)

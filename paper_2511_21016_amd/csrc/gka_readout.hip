@@ -47,6 +47,7 @@ struct ReadoutShape {
     static constexpr size_t tab_bytes = 3 * kChunk * sizeof(float);   // per-token G, state weight, beta of the chunk
     static constexpr size_t lds_bytes = (q_elems + k_elems + v_elems) * 2 + p_frags * sizeof(frag) + tab_bytes;
     static constexpr size_t lds_bytes_qlo = lds_bytes + q_elems * 2;   // with the remainder of q as a second tile
+    static constexpr size_t lds_bytes_kvlo = lds_bytes + k_elems * 2;  // ... of k or v (square states: same size)
 };
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -74,11 +75,14 @@ __device__ __forceinline__ float *summary_tile(const ReadoutArgs &a, int pair, i
 }  // namespace
 
 // QMODE: 0 q in bf16; 1 q as bf16 value + bf16 remainder (q_lo); 2 q in float32, split into value + remainder here.
-template <int DK, int DV, bool GATED, bool SUMMARY, int QMODE>
+// KVLO: 0 k and v as they are; 1 k comes with a remainder tensor (k_lo); 2 v does (v_lo). Not combined with QMODE != 0.
+template <int DK, int DV, bool GATED, bool SUMMARY, int QMODE, int KVLO = 0>
 __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gla_readout_kernel(ReadoutArgs a)
 {
     typedef ReadoutShape<DK, DV> SH;
     constexpr bool QLO = QMODE != 0, QF32 = QMODE == 2;
+    constexpr bool KLO = KVLO == 1, VLO = KVLO == 2;
+    static_assert(KVLO == 0 || (QMODE == 0 && DK == DV), "remainders of k / v: square states, plain q");
     // PRECISE: P and the weighted v rows enter their products as value + remainder, so that the outputs carry the
     // rounding of the tensors they are given and nothing else of that size: the gate gradient of the backward pass is
     // a long cumulative sum of differences of such outputs, and only errors common to all of them cancel in it
@@ -92,6 +96,7 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     frag *sP = (frag *)(sV + SH::v_elems);
     float *sG = (float *)(sP + SH::p_frags), *sW = sG + kChunk, *sB = sW + kChunk;
     uint16_t *sQ2 = (uint16_t *)(sB + kChunk);        // (QLO only)
+    uint16_t *sKV2 = sQ2;                             // (KVLO only: the remainder rows of k or v, laid out like them)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
 
     // ---- rows of a chunk: global -> registers (one chunk ahead) -> LDS
     struct Rows {
-        u32x4_t q[PQ], k[PK], v[PV], q2[QMODE == 1 ? PK : 1];
+        u32x4_t q[PQ], k[PK], v[PV], q2[QMODE == 1 ? PK : 1], kv2[KVLO != 0 ? PK : 1];
         float gate, beta;
     };
     auto fetch = [&](Rows &f, int c) {
@@ -153,6 +158,7 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             if (!SUMMARY && !QF32) f.q[i] = *(const u32x4_t *)((const uint16_t *)a.q + off);
             if (QMODE == 1) f.q2[i] = *(const u32x4_t *)((const uint16_t *)a.q_lo + off);
             f.k[i] = *(const u32x4_t *)((const uint16_t *)a.k + off);
+            if (KLO) f.kv2[i] = *(const u32x4_t *)((const uint16_t *)a.k_lo + off);
         }
         if (QF32) {
 #pragma unroll
@@ -169,6 +175,7 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             const int64_t off = base_v + (int64_t)tensor_token(c * kChunk + piece / (DV / 8)) * a.stride_t +
                                 8 * (piece % (DV / 8));
             f.v[i] = *(const u32x4_t *)((const uint16_t *)a.v + off);
+            if (VLO) f.kv2[i] = *(const u32x4_t *)((const uint16_t *)a.v_lo + off);
         }
         const int tau = min(c * kChunk + lane, a.T - 1);
         if (a.reverse) f.gate = tau == 0 ? 1.0f : a.gate[gate_base + (int64_t)(a.T - tau) * a.H];
@@ -184,6 +191,7 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             if (!SUMMARY && !QF32) *(u32x4_t *)(sQ + row * RSQ + col) = f.q[i];
             if (QMODE == 1) *(u32x4_t *)(sQ2 + row * RSQ + col) = f.q2[i];
             *(u32x4_t *)(sK + row * RSK + col) = f.k[i];
+            if (KLO) *(u32x4_t *)(sKV2 + row * RSK + col) = f.kv2[i];
         }
         if (QF32) {
 #pragma unroll
@@ -203,6 +211,7 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             const int piece = i * NT + tid;
             const int row = piece / (DV / 8), col = 8 * (piece % (DV / 8));
             *(u32x4_t *)(sV + row * RSV + col) = f.v[i];
+            if (VLO) *(u32x4_t *)(sKV2 + row * RSV + col) = f.kv2[i];
         }
     };
 
@@ -231,13 +240,14 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
         lds_barrier();                             // (no wait for the rows in flight)
 
         // V^T fragments, tokens of step (sb, h2) in kidx order: runs at 32 sb + 16 h2 + 4 g and 8 further
-        frag vt[2][2];
+        frag vt[2][2], vt2[2][2];                  // (vt2: the remainder rows, VLO only)
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
             for (int h2 = 0; h2 < 2; ++h2) {
                 const int t0 = 32 * sb + 16 * h2 + 4 * g;
                 vt[sb][h2] = gather_transposed_bf16(sV, PaddedTile{RSV}, 32 * w + sub16, lane, t0, t0 + 8);
+                if (VLO) vt2[sb][h2] = gather_transposed_bf16(sKV2, PaddedTile{RSV}, 32 * w + sub16, lane, t0, t0 + 8);
             }
 
         if (!SUMMARY) {
@@ -252,6 +262,9 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 for (int st = 0; st < 2 * NBK; ++st) {
                     const frag kf = row_runs(krow, 16 * st + 4 * g);
                     pacc = MMA::mma(kf, row_runs(qrow, 16 * st + 4 * g), pacc);
+                    if (KLO)
+                        pacc = MMA::mma(row_runs(sKV2 + (32 * sb + n) * RSK, 16 * st + 4 * g),
+                                        row_runs(qrow, 16 * st + 4 * g), pacc);
                     if (QLO) pacc = MMA::mma(kf, row_runs(sQ2 + (32 * tb + n) * RSQ, 16 * st + 4 * g), pacc);
                 }
                 // M[s,t] beta_s = exp2(G_t - G_s) beta_s for s <= t (Appendix B.2, base 2)
@@ -323,6 +336,7 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                 for (int h2 = 0; h2 < 2; ++h2) {
                     y[tb] = MMA::mma(vt[sb][h2], sP[(tile * 2 + h2) * 64 + lane], y[tb]);
                     if (PRECISE) y[tb] = MMA::mma(vt[sb][h2], sP[(6 + tile * 2 + h2) * 64 + lane], y[tb]);
+                    if (VLO) y[tb] = MMA::mma(vt2[sb][h2], sP[(tile * 2 + h2) * 64 + lane], y[tb]);
                 }
             }
             // ---- store: lane (n, g) holds features 32 w + kidx(r, g) of token 32 tb + n
@@ -352,6 +366,12 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
             for (int h2 = 0; h2 < 2; ++h2) {
                 float x[8];
                 MMA::unpack(vt[sb][h2], x);
+                if (VLO) {
+                    float x2[8];
+                    MMA::unpack(vt2[sb][h2], x2);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[e] += x2[e];
+                }
                 const int t0 = 32 * sb + 16 * h2 + 4 * g;
                 const f32x4 w0 = *(const f32x4 *)(sW + t0), w1 = *(const f32x4 *)(sW + t0 + 8);
 #pragma unroll
@@ -380,6 +400,9 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
                     const frag kt = gather_transposed_bf16(sK, PaddedTile{RSK}, 32 * jb + sub16, lane, t0, t0 + 8);
                     acc[jb] = MMA::mma(kt, vw[sb][h2], acc[jb]);
                     if (PRECISE) acc[jb] = MMA::mma(kt, vwlo[sb][h2], acc[jb]);
+                    if (KLO)
+                        acc[jb] = MMA::mma(gather_transposed_bf16(sKV2, PaddedTile{RSK}, 32 * jb + sub16, lane, t0, t0 + 8),
+                                           vw[sb][h2], acc[jb]);
                 }
         }
     }
@@ -395,30 +418,31 @@ __global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) 
     }
 }
 
-template <int DK, int DV, bool GATED, int QMODE>
+template <int DK, int DV, bool GATED, int QMODE, int KVLO = 0>
 static hipError_t launch_readout_d(const ReadoutArgs &a0, hipStream_t stream)
 {
     typedef ReadoutShape<DK, DV> SH;
     ReadoutArgs a = a0;
-    constexpr size_t lds_main = QMODE != 0 ? SH::lds_bytes_qlo : SH::lds_bytes;
+    constexpr size_t lds_sum = KVLO != 0 ? SH::lds_bytes_kvlo : SH::lds_bytes;
+    constexpr size_t lds_main = QMODE != 0 ? SH::lds_bytes_qlo : lds_sum;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gla_readout_kernel<DK, DV, GATED, false, QMODE>,
+        hipError_t e = hipFuncSetAttribute((const void *)gla_readout_kernel<DK, DV, GATED, false, QMODE, KVLO>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_main);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)gla_readout_kernel<DK, DV, GATED, true, 0>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)SH::lds_bytes);
+        e = hipFuncSetAttribute((const void *)gla_readout_kernel<DK, DV, GATED, true, 0, KVLO>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_sum);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (a.n_segs > 1 && a.seg_mode == 0) {
         // summaries of every segment but the last, each from a zero state
-        hipLaunchKernelGGL((gla_readout_kernel<DK, DV, GATED, true, 0>), dim3(a.n_pairs * (a.n_segs - 1)), dim3(SH::NT),
-                           SH::lds_bytes, stream, a);
+        hipLaunchKernelGGL((gla_readout_kernel<DK, DV, GATED, true, 0, KVLO>), dim3(a.n_pairs * (a.n_segs - 1)),
+                           dim3(SH::NT), lds_sum, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL((gla_readout_kernel<DK, DV, GATED, false, QMODE>), dim3(a.n_pairs * a.n_segs), dim3(SH::NT),
+    hipLaunchKernelGGL((gla_readout_kernel<DK, DV, GATED, false, QMODE, KVLO>), dim3(a.n_pairs * a.n_segs), dim3(SH::NT),
                        lds_main, stream, a);
     return hipGetLastError();
 }
@@ -426,6 +450,11 @@ static hipError_t launch_readout_d(const ReadoutArgs &a0, hipStream_t stream)
 template <int D>
 static hipError_t launch_readout_square(const ReadoutArgs &a, hipStream_t stream)
 {
+    if (a.k_lo || a.v_lo) {
+        // (the reverse recurrences of the backward pass: no write gate inside them)
+        if (a.q_lo || a.beta || (a.k_lo && a.v_lo)) return hipErrorInvalidValue;
+        return a.k_lo ? launch_readout_d<D, D, false, 0, 1>(a, stream) : launch_readout_d<D, D, false, 0, 2>(a, stream);
+    }
     if (a.q_lo)
         return a.beta ? launch_readout_d<D, D, true, 1>(a, stream) : launch_readout_d<D, D, false, 1>(a, stream);
     return a.beta ? launch_readout_d<D, D, true, 0>(a, stream) : launch_readout_d<D, D, false, 0>(a, stream);
@@ -434,7 +463,7 @@ static hipError_t launch_readout_square(const ReadoutArgs &a, hipStream_t stream
 hipError_t launch_gla_readout(const ReadoutArgs &a, int dk, int dv, hipStream_t stream)
 {
     if (a.q_is_f32) {                          // the sketched readout: float32 q, 64 sketched features, full v
-        if (dk != 64 || dv != 128 || a.q_lo) return hipErrorInvalidValue;
+        if (dk != 64 || dv != 128 || a.q_lo || a.k_lo || a.v_lo) return hipErrorInvalidValue;
         return a.beta ? launch_readout_d<64, 128, true, 2>(a, stream) : launch_readout_d<64, 128, false, 2>(a, stream);
     }
     if (dk != dv) return hipErrorInvalidValue;

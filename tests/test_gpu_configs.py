@@ -184,11 +184,9 @@ def test_cfg2_backward_and_sketch_full_size_sampled():
                                 w.n_iter)
         errs = {n: float(np.abs(sel(got[n]) - ref[n]).max() / np.abs(ref[n]).max()) for n in got}
         print("cfg2 backward pair", b, h, errs)
-        # bf16 tensors (see tests/test_gpu_backward.py): dlam = -xhat . p carries the largest rounding error; the gate
-        # gradient, a cumulative sum over the rest of the sequence, stays below 1 % here because its pieces are
-        # formed with value + remainder operands and handed over in float32
-        assert max(errs[n] for n in ("dq", "dk", "dv")) <= 6e-2, errs
-        assert errs["dgate"] <= 3e-2 and errs["dlam"] <= 2e-1, errs
+        # bf16 tensors, the stated tolerance for every gradient (measured: dk 1.3-1.5 %, the gate gradient, a
+        # cumulative sum over the rest of the sequence, 0.2-1.1 %, the rest below 0.7 %)
+        assert max(errs.values()) <= TOL_BF16, errs
         yref = sk.forward_sketched_pair(sel(x["q"]), sel(x["k"]), sel(x["v"]), sel(x["gate"]), sel(x["lam"]), S[h],
                                         w.n_iter)
         es = float(np.abs(sel(ys) - yref).max() / np.abs(yref).max())
@@ -218,5 +216,7 @@ def test_cfg3_shape_backward_long_sequence(compute):
     errs = {n: float(np.abs(sel(to_host(out[n])) - ref[n]).max() / np.abs(ref[n]).max())
             for n in ("dq", "dk", "dv", "dgate", "dlam")}
     print("cfg3-shape backward,", compute, "operands:", errs)
-    assert max(errs[n] for n in ("dq", "dk", "dv")) <= 6e-2, errs
-    assert errs["dgate"] <= 3e-2 and errs["dlam"] <= 1e-1, errs
+    # the stated bf16 tolerance, but for the gate gradient: a cumulative sum over up to 32768 tokens of differences
+    # of readouts; measured 2.1 % (bf16 operands) and 1.9 % (float32 operands), the rest below 1.3 %
+    assert max(errs[n] for n in ("dq", "dk", "dv", "dlam")) <= TOL_BF16, errs
+    assert errs["dgate"] <= 3e-2, errs
