@@ -22,7 +22,7 @@ N_INPUT_SETS = 3                   # rotated so that the 256 MiB of q,k,v,o do n
 # An idle GPU needs tens of milliseconds of work before its clocks settle; a step is a third of a millisecond. These
 # untimed forward passes run before the W warm-up steps whatever W is (reported as "clock_ramp_steps").
 CLOCK_RAMP_STEPS = 300
-FUSED_KERNEL = "gka::fused_forward_kernel(gka::FusedArgs)"
+FUSED_KERNEL = "gka::fused_forward_kernel<false>(gka::FusedArgs)"
 
 
 def committed_traffic(kernel):
@@ -174,8 +174,9 @@ def main():
     # ---- the other forward configurations (extra information): long context and the ill-conditioned stress
     if not args.no_other_configs:
         other = {}
+        # (configuration 4 needs more than single bf16 operands: see tests/test_gpu_configs.py)
         for wo, compute, label in ((synth.CFG3, binding.GKA_COMPUTE_BF16, "bf16 operands"),
-                                   (synth.CFG4, binding.GKA_COMPUTE_BF16, "bf16 operands"),
+                                   (synth.CFG4, binding.GKA_COMPUTE_BF16_SPLIT, "bf16 value + remainder operands"),
                                    (synth.CFG4, binding.GKA_COMPUTE_F32, "fp32 operands")):
             xo = upload_inputs(synth.make_inputs(wo), wo.dtype)
             po = binding.make_params(wo.B, wo.H, wo.T, wo.d, wo.n_iter, binding.GKA_BF16, compute)

@@ -48,11 +48,16 @@ typedef enum {
 typedef enum { GKA_F32 = 0, GKA_BF16 = 1 } gka_dtype;
 
 /* Arithmetic of the matrix products.
- * GKA_COMPUTE_F32 : float32 operands on the float32 MFMA path (required for GKA_F32 tensors; also
- *                   the mode for ill-conditioned problems with bf16 tensors).
+ * GKA_COMPUTE_F32 : float32 operands on the float32 MFMA path (required for GKA_F32 tensors).
  * GKA_COMPUTE_BF16: bf16 operands with float32 accumulation on the bf16 MFMA path; the Chebyshev
- *                   iterate, the residual and all per-token scalars stay float32. */
-typedef enum { GKA_COMPUTE_F32 = 0, GKA_COMPUTE_BF16 = 1 } gka_compute;
+ *                   iterate, the residual and all per-token scalars stay float32.
+ * GKA_COMPUTE_BF16_SPLIT: the bf16 MFMA path for ill-conditioned systems (lambda_t orders of magnitude below
+ *                   ||H_t||_F, where the iteration amplifies the rounding of its operands): the chunk's initial state
+ *                   H_[n], the update of the iterate and the masked intra-chunk products enter their products as
+ *                   bf16 value + bf16 remainder, about 2.6 times the products of GKA_COMPUTE_BF16 and a fraction of the cost of GKA_COMPUTE_F32. (Appendix
+ *                   B.1 leaves the precision of the matrix products to the implementation.) gka_forward only, and only
+ *                   what the fused kernel covers (see gka_path); GKA_ERR_UNSUPPORTED otherwise. */
+typedef enum { GKA_COMPUTE_F32 = 0, GKA_COMPUTE_BF16 = 1, GKA_COMPUTE_BF16_SPLIT = 2 } gka_compute;
 
 /* Which part of gka_forward to enqueue. The forward pass has two phases (Section 4.2.1): first the
  * chunk initial states H_[n], U_[n] are computed and stored in the workspace (this phase also writes
@@ -78,7 +83,7 @@ typedef enum { GKA_STATE_FULL = 0, GKA_STATE_H_LOWER_BLOCKS = 1 } gka_state_layo
  * GKA_PATH_TWO_PHASE: chunk initial states H_[n], U_[n] of Section 4.2.1 are computed and stored in the workspace
  *                     first, then every chunk is solved independently (all dtypes, head dimensions and variants).
  * GKA_PATH_FUSED    : one kernel walks the chunks of a pair in order with H and U in registers, so that no chunk state
- *                     crosses HBM. Available for GKA_BF16 tensors with GKA_COMPUTE_BF16, d = 128, Eq. (CH) as printed
+ *                     crosses HBM. Available for GKA_BF16 tensors with GKA_COMPUTE_BF16 (or _SPLIT), d = 128, Eq. (CH) as printed
  *                     (lambda given, no beta / alpha / xhat_out), GKA_PHASE_ALL; GKA_ERR_UNSUPPORTED otherwise. */
 typedef enum { GKA_PATH_AUTO = 0, GKA_PATH_TWO_PHASE = 1, GKA_PATH_FUSED = 2 } gka_path;
 

@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("GKA_LIBRARY") or os.path.join(_HERE, "libgka.so")
  GKA_ERR_STATIC_SCRATCH) = range(7)
 GKA_STATIC_SCRATCH_BYTES = 64 << 20
 GKA_F32, GKA_BF16 = 0, 1
-GKA_COMPUTE_F32, GKA_COMPUTE_BF16 = 0, 1
+GKA_COMPUTE_F32, GKA_COMPUTE_BF16, GKA_COMPUTE_BF16_SPLIT = 0, 1, 2
 GKA_PHASE_ALL, GKA_PHASE_STATES, GKA_PHASE_SOLVE = 0, 1, 2
 GKA_STATE_FULL, GKA_STATE_H_LOWER_BLOCKS = 0, 1
 GKA_PATH_AUTO, GKA_PATH_TWO_PHASE, GKA_PATH_FUSED = 0, 1, 2

@@ -17,6 +17,7 @@ struct Plan {
     int n_segs, seg_len;
     int pairs_per_batch;          // (batch, head) pairs per launch
     int slab_chunks;              // chunks of every pair per launch
+    bool split;                   // GKA_COMPUTE_BF16_SPLIT (fused kernel only)
     bool fused_shape;             // dtype, operands and head dimension of the fused kernel
     int fused_n_segs, fused_seg_len;
     size_t fused_bytes;           // workspace of the fused kernels alone
@@ -44,8 +45,8 @@ gka_status check_common(const gka_params *p, bool decode)
     if (p->d_k != p->d_v) return GKA_ERR_UNSUPPORTED;
     if (p->d_k != 64 && p->d_k != 128) return GKA_ERR_UNSUPPORTED;
     if (p->io_dtype != GKA_F32 && p->io_dtype != GKA_BF16) return GKA_ERR_UNSUPPORTED;
-    if (p->compute != GKA_COMPUTE_F32 && p->compute != GKA_COMPUTE_BF16) return GKA_ERR_UNSUPPORTED;
-    if (p->io_dtype == GKA_F32 && p->compute == GKA_COMPUTE_BF16) return GKA_ERR_UNSUPPORTED;
+    if (p->compute < GKA_COMPUTE_F32 || p->compute > GKA_COMPUTE_BF16_SPLIT) return GKA_ERR_UNSUPPORTED;
+    if (p->io_dtype == GKA_F32 && p->compute != GKA_COMPUTE_F32) return GKA_ERR_UNSUPPORTED;
     if (!decode && p->chunk != gka::kChunk) return GKA_ERR_UNSUPPORTED;
     if ((int64_t)p->B * p->H > (int64_t)1 << 24) return GKA_ERR_SHAPE;
     if (!(p->lambda_scale >= 0.0f)) return GKA_ERR_SHAPE;
@@ -63,7 +64,8 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
     pl->n_pairs = p->B * p->H;
     pl->n_chunks = (p->T + gka::kChunk - 1) / gka::kChunk;
     pl->io_bf16 = p->io_dtype == GKA_BF16;
-    pl->compute_bf16 = p->compute == GKA_COMPUTE_BF16;
+    pl->compute_bf16 = p->compute != GKA_COMPUTE_F32;
+    pl->split = p->compute == GKA_COMPUTE_BF16_SPLIT;
     if ((int64_t)pl->n_pairs * pl->n_chunks > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
     if (p->stride_b == 0 && p->stride_t == 0 && p->stride_h == 0) {
         pl->stride_h = p->d_k;
@@ -125,17 +127,18 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
             seg_len = p->walk_chunks;
         } else {
             int n_segs = (kFusedMinWorkgroups + pl->n_pairs - 1) / pl->n_pairs;
-            if (n_segs > pl->n_chunks / 2) n_segs = pl->n_chunks / 2;
+            const int min_walk = pl->split ? 1 : 2;
+            if (n_segs > pl->n_chunks / min_walk) n_segs = pl->n_chunks / min_walk;
             if (n_segs < 1) n_segs = 1;
             seg_len = (pl->n_chunks + n_segs - 1) / n_segs;
         }
-        seg_len += seg_len & 1;
+        if (!pl->split) seg_len += seg_len & 1;
         pl->fused_seg_len = seg_len;
         pl->fused_n_segs = (pl->n_chunks + seg_len - 1) / seg_len;
         if ((int64_t)pl->n_pairs * pl->fused_n_segs > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
         pl->fused_bytes = align_up(gka::fused_workspace_bytes(pl->n_pairs, pl->fused_n_segs), 256);
         // (a caller that insists on the fused kernels needs no room for the two-phase kernels' chunk states)
-        if (p->path == GKA_PATH_FUSED || pl->fused_bytes > pl->total) pl->total = pl->fused_bytes;
+        if (p->path == GKA_PATH_FUSED || pl->split || pl->fused_bytes > pl->total) pl->total = pl->fused_bytes;
     }
     return GKA_OK;
 }
@@ -191,7 +194,8 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
 
     const bool fused_ok = pl.fused_shape && !p->beta && !p->alpha && lambda && !p->xhat_out && !solve_only &&
                           !q_lo && p->phase == GKA_PHASE_ALL;
-    if (p->path == GKA_PATH_FUSED && !fused_ok) return GKA_ERR_UNSUPPORTED;
+    if ((p->path == GKA_PATH_FUSED || pl.split) && !fused_ok) return GKA_ERR_UNSUPPORTED;
+    if (pl.split && p->path == GKA_PATH_TWO_PHASE) return GKA_ERR_UNSUPPORTED;     // only the fused kernel splits
     if (fused_ok && p->path != GKA_PATH_TWO_PHASE) {
         gka::FusedArgs fa;
         fa.q = q; fa.k = k; fa.v = v; fa.gate = gate; fa.lambda = lambda; fa.o = o; fa.fro_out = fro_out;
@@ -204,9 +208,9 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
         fa.seg_buf = nullptr; fa.seg_logdecay = nullptr;
         // (profiling: the summary launch is reported as the state phase, the chunk walk as the solve phase)
         if (prof) prof->mark(stream);
-        if (gka::launch_fused_forward(fa, ws, stream, 1) != hipSuccess) return GKA_ERR_LAUNCH;
+        if (gka::launch_fused_forward(fa, ws, stream, 1, pl.split) != hipSuccess) return GKA_ERR_LAUNCH;
         if (prof) prof->mark(stream);
-        if (gka::launch_fused_forward(fa, ws, stream, 2) != hipSuccess) return GKA_ERR_LAUNCH;
+        if (gka::launch_fused_forward(fa, ws, stream, 2, pl.split) != hipSuccess) return GKA_ERR_LAUNCH;
         if (prof) prof->mark(stream);
         return GKA_OK;
     }
@@ -419,7 +423,7 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     gka_status s = check_common(p, false);
     if (s != GKA_OK) return s;
     if (p->stride_b != 0 || p->stride_t != 0 || p->stride_h != 0) return GKA_ERR_UNSUPPORTED;
-    if (p->phase != GKA_PHASE_ALL) return GKA_ERR_UNSUPPORTED;
+    if (p->phase != GKA_PHASE_ALL || p->compute == GKA_COMPUTE_BF16_SPLIT) return GKA_ERR_UNSUPPORTED;
     bp->n_tokens = (size_t)p->B * p->T * p->H;
     bp->n_elems = bp->n_tokens * p->d_k;
     bp->esz = p->io_dtype == GKA_BF16 ? 2 : 4;

@@ -16,27 +16,20 @@
 //     and of U^T (U[16 w + n][16 jt + row]). It converts H to the bf16 A operand of the solve, advances H and U by a
 //     chunk (S <- zeta_C S + sum_j w_j k_j a_j^T, the weights on its own B fragments), and reads out
 //     zeta-free U_[n] xhat for all tokens of a chunk from its registers (rounded value + remainder of both operands).
-//   * Solver role: waves 0-3 take chunk A, waves 4-7 chunk B, each wave 16 tokens with all 128 features: chunk-wise
-//     Frobenius norm, all passes of Algorithm 1 and the intra-chunk part of the readout run without any
-//     barrier, the iterate never leaves the wave's registers.
+//   * Solver role: four waves per chunk, each wave 16 tokens with all 128 features: chunk-wise Frobenius norm, all
+//     passes of Algorithm 1 and the intra-chunk part of the readout run without any barrier, the iterate never
+//     leaves the wave's registers.
+//
+// SPLIT variant (GKA_COMPUTE_BF16_SPLIT), for ill-conditioned systems: the two operands whose rounding the
+// iteration amplifies, H_[n] and the update delta, enter their products as bf16 value + bf16 remainder
+// (H delta ~ Hv dv + Hv dr + Hr dv, K delta = K dv + K dr), and so do the masked intra-chunk products P o M (with
+// H_[n] = 0 and a handful of tokens they are all of H_c); everything else is as above. The remainder of H_[n] takes
+// the place of the second chunk's H_[n] in LDS, so an iteration handles one chunk, solved by waves 0-3 (one per
+// SIMD) while waves 4-7 only play their state role.
 #include "gka_device.hpp"
 #include "gka_kernels.hpp"
 
 namespace gka {
-#ifdef GKA_FUSED_TIMERS
-__device__ unsigned long long g_fused_timers[8 * 32];
-#define GKA_FT(i)                                                                                  \
-    do {                                                                                           \
-        if (c.lane == 0 && blockIdx.x == 100 && c0 == chunk_begin + 4)                             \
-            g_fused_timers[c.w * 32 + (i)] = __builtin_readcyclecounter();                         \
-    } while (0)
-extern "C" int gka_debug_read_fused_timers(unsigned long long *host)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_fused_timers), sizeof(g_fused_timers));
-}
-#else
-#define GKA_FT(i) do {} while (0)
-#endif
 namespace {
 
 constexpr int kFusedThreads = 512;
@@ -122,9 +115,6 @@ struct Ctx {
     int64_t base_bh, gate_base;
     int T_eff;                       // tokens at or beyond this index do not exist for this workgroup
     f32x4 *park;                     // this lane's place in the workgroup's scratch block
-#ifdef GKA_FUSED_TIMERS
-    bool stamp;
-#endif
 };
 
 // Lane-derived fields from a copy of the lane index that the compiler cannot trace back: addresses formed from it
@@ -204,13 +194,22 @@ __device__ __forceinline__ void advance_state(const Ctx &c, f32x4 (&acc)[8], int
 
 // H_[n] as the A operand of the solve (by symmetry the accumulators are rows 16 w .. of H in slot order) and this
 // wave's share of ||H_[n]||_F^2.
+// SPLIT: the rounding remainder goes to the second chunk's place (32 KiB further).
+template <bool SPLIT>
 __device__ __forceinline__ float publish_H(const Ctx &c, const f32x4 (&accH)[8], int g)
 {
     bf16x8 *sH = lds_frags(c, kOffH + g * 32768) + (c.w * 4) * 64 + c.lane;
     float ss = 0.0f;
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) {
-        sH[fb * 64] = pack8(accH[2 * fb], accH[2 * fb + 1]);
+        if constexpr (SPLIT) {
+            bf16x8 val, rem;
+            split8(accH[2 * fb], accH[2 * fb + 1], val, rem);
+            sH[fb * 64] = val;
+            sH[2048 + fb * 64] = rem;
+        } else {
+            sH[fb * 64] = pack8(accH[2 * fb], accH[2 * fb + 1]);
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r) ss += accH[2 * fb][r] * accH[2 * fb][r] + accH[2 * fb + 1][r] * accH[2 * fb + 1][r];
     }
@@ -281,17 +280,22 @@ __device__ __forceinline__ uint32_t lds_address(const void *p)
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
 }
 
-template <int NJ>
+template <int NJ, bool SPLIT>
 struct PassPlan {
-    // steps of the loop body: the tile phase (8 tiles x (4 state + NJB intra products)), then the key products of the
-    // next pass
-    static constexpr int NJB = NJ / 2, NP = 4 * NJ, PER_TILE = 4 + NJB, NT = 8 * PER_TILE, NS = NT + NP;
-    static constexpr int base(int i) { return i >= NT ? 1 : (i % PER_TILE < 4 ? 0 : 2); }
+    // steps of the loop body, one A fragment each: the tile phase (8 tiles x (HP state + NJB intra fragments)), then
+    // the key fragments of the next pass. SPLIT: the state fragments of a tile are the four of the value (each
+    // multiplied with the value and with the remainder of delta) and the four of the remainder of H_[n]; a key fragment
+    // is multiplied with both parts of delta.
+    static constexpr int NJB = NJ / 2, NP = 4 * NJ, HP = SPLIT ? 8 : 4, PER_TILE = HP + NJB, NT = 8 * PER_TILE,
+                         NS = NT + NP;
+    static constexpr int base(int i) { return i >= NT ? 1 : (i % PER_TILE < HP ? 0 : 2); }
     static constexpr int off(int i)
     {
         if (i >= NT) return (((i - NT) % NJ) * 4 + (i - NT) / NJ) * 64;       // keys [js][fb], fb-major order
         const int t = i / PER_TILE, u = i % PER_TILE;
-        return u < 4 ? (t * 4 + u) * 64 : (t * 2 + (u - 4)) * 64;
+        if (u < 4) return (t * 4 + u) * 64;
+        if (u < HP) return 2048 + (t * 4 + (u - 4)) * 64;                     // remainder of H_[n]: 32 KiB further
+        return (t * 2 + (u - HP)) * 64;
     }
 };
 
@@ -299,6 +303,12 @@ struct PassPlan {
 __device__ __forceinline__ bf16x8 masked_frag(const f32x4 &P0, const f32x4 &P1, const f32x4 (&mreg)[4], int jb)
 {
     return pack8(P0 * mreg[2 * jb], P1 * mreg[2 * jb + 1]);
+}
+// the same as rounded value + remainder
+__device__ __forceinline__ void masked_frag_split(const f32x4 &P0, const f32x4 &P1, const f32x4 (&mreg)[4], int jb,
+                                                  bf16x8 &val, bf16x8 &rem)
+{
+    split8(P0 * mreg[2 * jb], P1 * mreg[2 * jb + 1], val, rem);
 }
 
 // P[js] = K[js] x for the key blocks js < NJ, x given as B fragments; a rolled loop (used once per chunk)
@@ -331,14 +341,15 @@ __device__ __forceinline__ void key_products(const bf16x8 *sK, const bf16x8 (&x)
 // of the vector work behind it.
 // `start_copies` is called once, after the last LDS read that the compiler knows of: it issues the copies into LDS
 // that overlap the passes.
-template <int NJ, class StartCopies>
+template <int NJ, bool SPLIT, class StartCopies>
 __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, const bf16x8 *sKT, f32x4 (&xi)[8],
                                             f32x4 (&dl)[8], f32x4 (&gn)[8], const f32x4 (&mreg)[4], float zeta,
                                             float lam, float s0, float rho2, int n_iter, int lane,
                                             StartCopies start_copies)
 {
-    typedef PassPlan<NJ> PL;
-    constexpr int NJB = PL::NJB, PER_TILE = PL::PER_TILE, NT = PL::NT, NS = PL::NS;
+    typedef PassPlan<NJ, SPLIT> PL;
+    constexpr int NJB = PL::NJB, PER_TILE = PL::PER_TILE, NT = PL::NT, NS = PL::NS, HP = PL::HP;
+    static_assert((2048 + 31 * 64 + 63) * 16 < 65536, "the offset field of an LDS read holds 16 bits");
     // A fragments in flight. The request of step i + kDepth goes into the register that step i has just freed, also
     // across the end of the loop body, so the depth divides the number of steps (48, 64).
     constexpr int kDepth = 4;
@@ -349,12 +360,19 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
     }
     const uint32_t bases[3] = {lds_address(sH + lane), lds_address(sK + lane), lds_address(sKT + lane)};
     u32x4 q[kDepth];
-    bf16x8 dB[4];
+    bf16x8 dB[4], dR[SPLIT ? 4 : 1];         // delta as B fragments: rounded value and (SPLIT) remainder
     f32x4 P[NJ];
-#pragma unroll
-    for (int fb = 0; fb < 4; ++fb) dB[fb] = pack8(dl[2 * fb], dl[2 * fb + 1]);
-    {
+    auto pack_delta = [&](auto fbc) {
+        constexpr int fb = decltype(fbc)::value;
+        if constexpr (SPLIT) split8(dl[2 * fb], dl[2 * fb + 1], dB[fb], dR[fb]);
+        else dB[fb] = pack8(dl[2 * fb], dl[2 * fb + 1]);
+    };
+    static_for<0, 4>(pack_delta);
+    if constexpr (SPLIT) {
         // key products of the first pass
+        bf16x8 x[2][4] = {{dB[0], dB[1], dB[2], dB[3]}, {dR[0], dR[1], dR[2], dR[3]}};
+        key_products<NJ, 2>(sK, x, P, lane);
+    } else {
         bf16x8 x[1][4] = {{dB[0], dB[1], dB[2], dB[3]}};
         key_products<NJ, 1>(sK, x, P, lane);
     }
@@ -369,7 +387,7 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
     // the first seven tenths of the passes, so that the two finish together (measured: with equal priorities the
     // lighter wave finishes a third earlier, with the priority held throughout it finishes a fifth later; alone on
     // its SIMD a wave runs at half the rate of the two together).
-    constexpr bool kBoost = NJ == 2;
+    constexpr bool kBoost = NJ == 2 && !SPLIT;           // (SPLIT: one solver wave per SIMD)
     if (kBoost) __builtin_amdgcn_s_setprio(1);
     const int prio_passes = n_iter / 2;
 #pragma unroll 1
@@ -378,9 +396,14 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
         if (kBoost && it == prio_passes) __builtin_amdgcn_s_setprio(0);
         omega = 4.0f * __builtin_amdgcn_rcpf(4.0f - rho2 * omega);           // weight schedule
         const float cm = omega - 1.0f, ncs = -omega * s0, ncl = ncs * lam;
-        bf16x8 pm[NJB];
+        bf16x8 pm[NJB], pmR[SPLIT ? NJB : 1];
         f32x4 s = zero4(), sprev = zero4();
         f32x4 tcm;
+        auto mask_products = [&](auto jbc) {
+            constexpr int jb = decltype(jbc)::value;
+            if constexpr (SPLIT) masked_frag_split(P[2 * jb], P[2 * jb + 1], mreg, jb, pm[jb], pmR[jb]);
+            else pm[jb] = masked_frag(P[2 * jb], P[2 * jb + 1], mreg, jb);
+        };
         // update of one element, split into what needs no product of this pass (a) and the rest (b)
         auto upd_a = [&](auto ftc, auto rc) {
             constexpr int ft = decltype(ftc)::value, r = decltype(rc)::value;
@@ -404,11 +427,19 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
             const bf16x8 a = __builtin_bit_cast(bf16x8, q[i % kDepth]);
             if constexpr (i < NT) {
                 constexpr int t = i / PER_TILE, u = i % PER_TILE;
-                if constexpr (u < 4) s = mma16(a, dB[u], u == 0 ? zero4() : s);
-                else gn[t] = mma16(a, pm[u - 4], gn[t]);
+                if constexpr (u < 4) {
+                    s = mma16(a, dB[u], u == 0 ? zero4() : s);
+                    if constexpr (SPLIT) s = mma16(a, dR[u], s);
+                } else if constexpr (u < HP) {
+                    s = mma16(a, dB[u - 4], s);
+                } else {
+                    gn[t] = mma16(a, pm[u - HP], gn[t]);
+                    if constexpr (SPLIT) gn[t] = mma16(a, pmR[u - HP], gn[t]);
+                }
             } else {
                 constexpr int fb = (i - NT) / NJ, js = (i - NT) % NJ;
                 P[js] = mma16(a, dB[fb], fb == 0 ? zero4() : P[js]);
+                if constexpr (SPLIT) P[js] = mma16(a, dR[fb], P[js]);
             }
             {
                 constexpr int nx = (i + kDepth) % NS;
@@ -416,8 +447,8 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
             }
             if constexpr (i < NT) {
                 constexpr int t = i / PER_TILE, u = i % PER_TILE;
-                if constexpr (t == 0 && u == 2) pm[0] = masked_frag(P[0], P[1], mreg, 0);
-                if constexpr (t == 0 && u == 3 && NJB == 2) pm[NJB - 1] = masked_frag(P[NJ - 2], P[NJ - 1], mreg, NJB - 1);
+                if constexpr (t == 0 && u == 2) mask_products(std::integral_constant<int, 0>{});
+                if constexpr (t == 0 && u == 3 && NJB == 2) mask_products(std::integral_constant<int, NJB - 1>{});
                 if constexpr (u == PER_TILE - 1) sprev = s;
                 if constexpr (t >= 1) {
                     typedef std::integral_constant<int, t - 1> FT;
@@ -432,15 +463,15 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
                 typedef std::integral_constant<int, 7> FT;
                 if constexpr (k == 0) {
                     upd_a(FT{}, R0{}); upd_a(FT{}, R1{}); upd_a(FT{}, R2{}); upd_a(FT{}, R3{});
-                    dB[1] = pack8(dl[2], dl[3]);
+                    pack_delta(std::integral_constant<int, 1>{});
                 }
                 if constexpr (k == NJ) {
                     upd_b(FT{}, R0{}, s); upd_b(FT{}, R1{}, s); upd_b(FT{}, R2{}, s); upd_b(FT{}, R3{}, s);
-                    dB[2] = pack8(dl[4], dl[5]);
+                    pack_delta(std::integral_constant<int, 2>{});
                 }
-                if constexpr (k == 2 * NJ) dB[3] = pack8(dl[6], dl[7]);
+                if constexpr (k == 2 * NJ) pack_delta(std::integral_constant<int, 3>{});
             }
-            if constexpr (i == NT - 1) dB[0] = pack8(dl[0], dl[1]);
+            if constexpr (i == NT - 1) pack_delta(std::integral_constant<int, 0>{});
             __builtin_amdgcn_sched_barrier(0);
         });
     }
@@ -537,7 +568,7 @@ __device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, in
 
 // Everything between the Frobenius table and the published result: the passes, then (after the workgroup has
 // passed the barrier inside) xhat to LDS and the intra-chunk part of the readout.
-template <int NJ>
+template <int NJ, bool SPLIT>
 __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, const typename IOBF16::raw4 (&qraw)[8],
                                              float lam, f32x4 (&accU)[8], int c0)
 {
@@ -561,15 +592,12 @@ __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, c
             gn[ft][r] = -qe;
         }
     }
-    cheb_passes<NJ>(sH, sK, sKT, xi, dl, gn, s.mreg, s.zeta, lam, s0, rho * rho, c.a.n_iter, c.lane, [&]() {
-        // v rows of both chunks replace the k rows; they land during the passes
+    cheb_passes<NJ, SPLIT>(sH, sK, sKT, xi, dl, gn, s.mreg, s.zeta, lam, s0, rho * rho, c.a.n_iter, c.lane, [&]() {
+        // v rows of the iteration's chunks replace the k rows; they land during the passes
         copy_rows(c, c.a.v, 0, c0);
-        copy_rows(c, c.a.v, 1, c0 + 1);
+        if constexpr (!SPLIT) copy_rows(c, c.a.v, 1, c0 + 1);
     });
     refresh_lane(c);
-#ifdef GKA_FUSED_TIMERS
-    if (c.stamp && c.lane == 0) g_fused_timers[c.w * 32 + 11] = __builtin_readcyclecounter();
-#endif
 #pragma unroll
     for (int ft = 0; ft < 8; ++ft) xi[ft] += dl[ft];
 
@@ -583,14 +611,8 @@ __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, c
     bf16x8 pm[NJB];
 #pragma unroll
     for (int jb = 0; jb < NJB; ++jb) pm[jb] = masked_frag(P[2 * jb], P[2 * jb + 1], s.mreg, jb);
-#ifdef GKA_FUSED_TIMERS
-    if (c.stamp && c.lane == 0) g_fused_timers[c.w * 32 + 12] = __builtin_readcyclecounter();
-#endif
     wait_all_memory();               // this wave's copies of v rows have landed
     lds_barrier();                   // all of them have; every wave is through its passes: H_[n] is dead
-#ifdef GKA_FUSED_TIMERS
-    if (c.stamp && c.lane == 0) g_fused_timers[c.w * 32 + 23] = __builtin_readcyclecounter();
-#endif
     bf16x8 *sX = lds_frags(c, kOffH + g * 32768) + c.lane;
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) {
@@ -649,11 +671,14 @@ __device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, in
 
 // A fragments of the keys of both chunks from their row tiles: rows (K[js][fb]) and transposed (KT[ft][jb]); each
 // wave builds four of the 32 fragments of either kind.
+// (SPLIT: one chunk, two of its 16 fragments of either kind per wave.)
+template <bool SPLIT>
 __device__ __forceinline__ void build_key_frags(const Ctx &c)
 {
+    constexpr int PER_WAVE = SPLIT ? 2 : 4;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int idx = c.w * 4 + q;
+    for (int q = 0; q < PER_WAVE; ++q) {
+        const int idx = c.w * PER_WAVE + q;
         const int g = idx >> 4, f = idx & 15;
         const uint16_t *rows = lds_rows(c, g);
         {
@@ -722,6 +747,8 @@ __device__ __forceinline__ void load_start_state(const Ctx &c, f32x4 (&accH)[8],
 //   6. state part of the readout for A (over the key-row fragments), U advanced over A
 //   7. solver A stores; state part of the readout for B (over A's xhat), U advanced over B and parked
 //   8. solver B stores; copies of the next k rows into the row tiles start
+// SPLIT: the same with chunk A alone (everything that concerns B drops out, phase 8 joins phase 7).
+template <bool SPLIT>
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -739,10 +766,13 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
     const int chunk_end = min(chunk_begin + a.seg_len, a.n_chunks);
     if (chunk_begin >= chunk_end) return;
     c.T_eff = min(a.T, chunk_end * kChunk);
+    constexpr int kChunksPerIter = SPLIT ? 1 : 2;
     // Solver role: chunk of the pair and token block. Waves w and w + 4 share a SIMD, whose arbiter prefers the older
-    // one: waves 0-3 take the token blocks with more key blocks (ts = 2, 3), waves 4-7 the others.
-    const int grp = (c.w >> 1) & 1;
-    const int ts = (c.w < 4 ? 2 : 0) + (c.w & 1);
+    // one: waves 0-3 take the token blocks with more key blocks (ts = 2, 3), waves 4-7 the others. SPLIT: waves 0-3
+    // take the four token blocks of the one chunk, waves 4-7 none.
+    const int grp = SPLIT ? 0 : (c.w >> 1) & 1;
+    const int ts = SPLIT ? (c.w & 3) : (c.w < 4 ? 2 : 0) + (c.w & 1);
+    const bool solver = !SPLIT || c.w < 4;
 
     c.park = (f32x4 *)a.park + ((int64_t)blockIdx.x * 8 + c.w) * (8 * 64) + c.lane;
     f32x4 accH[8];
@@ -752,127 +782,128 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         park_store(c.park, accU);
     }
     copy_rows(c, a.k, 0, chunk_begin);
-    copy_rows(c, a.k, 1, chunk_begin + 1);
+    if constexpr (!SPLIT) copy_rows(c, a.k, 1, chunk_begin + 1);
     float *sTab = (float *)(smem + kOffTab);
 
     const bool wide = ts >= 2;                              // which instantiation of the solver code this wave runs
     float gmA = a.gate[c.gate_base + (int64_t)min(chunk_begin * kChunk + c.lane, a.T - 1) * a.H];
-    float gmB = a.gate[c.gate_base + (int64_t)min((chunk_begin + 1) * kChunk + c.lane, a.T - 1) * a.H];
+    float gmB = 1.0f;
+    if constexpr (!SPLIT) gmB = a.gate[c.gate_base + (int64_t)min((chunk_begin + 1) * kChunk + c.lane, a.T - 1) * a.H];
 #pragma unroll 1
-    for (int c0 = chunk_begin; c0 < chunk_end; c0 += 2) {
+    for (int c0 = chunk_begin; c0 < chunk_end; c0 += kChunksPerIter) {
         // Addresses are formed anew in every iteration from a copy of the lane index that the compiler cannot trace
         // back: hoisted out of the loop they would occupy registers across the passes (or be spilled and reloaded).
         refresh_lane(c);
-#ifdef GKA_FUSED_TIMERS
-        c.stamp = blockIdx.x == 100 && c0 == chunk_begin + 4;
-#endif
         // ---- 1
-        GKA_FT(0);
-        // gates of both chunks (fetched during the previous iteration): lane j holds G_j, the weight of token j in the
+        // gates of the chunks (fetched during the previous iteration): lane j holds G_j, the weight of token j in the
         // chunk's update 2^(G_C - G_j), and the chunk's decay
-        float GA, GB, wjA, wjB, zetaA, zetaB;
+        float GA, GB = 0.0f, wjA, wjB = 0.0f, zetaA, zetaB = 1.0f;
         auto gate_scans = [&]() {
-            const bool vA = c0 * kChunk + c.lane < c.T_eff, vB = (c0 + 1) * kChunk + c.lane < c.T_eff;
+            const bool vA = c0 * kChunk + c.lane < c.T_eff;
             GA = wave_inclusive_scan(vA ? log2_gate(gmA) : 0.0f, c.lane);
-            GB = wave_inclusive_scan(vB ? log2_gate(gmB) : 0.0f, c.lane);
-            const float GtA = lane_value(GA, 63), GtB = lane_value(GB, 63);
+            const float GtA = lane_value(GA, 63);
             wjA = vA ? exp2f(GtA - GA) : 0.0f;
-            wjB = vB ? exp2f(GtB - GB) : 0.0f;
             zetaA = exp2f(GtA);
-            zetaB = exp2f(GtB);
+            if constexpr (!SPLIT) {
+                const bool vB = (c0 + 1) * kChunk + c.lane < c.T_eff;
+                GB = wave_inclusive_scan(vB ? log2_gate(gmB) : 0.0f, c.lane);
+                const float GtB = lane_value(GB, 63);
+                wjB = vB ? exp2f(GtB - GB) : 0.0f;
+                zetaB = exp2f(GtB);
+            }
         };
         gate_scans();
-        GKA_FT(1);
         wait_all_memory();               // this wave's copies of k rows have landed
         lds_barrier();                   // ... and everybody else's
         // ---- 2
-        GKA_FT(2);
-        const float hnA = publish_H(c, accH, 0);
-        build_key_frags(c);
+        const float hnA = publish_H<SPLIT>(c, accH, 0);
+        build_key_frags<SPLIT>(c);
         bf16x8 wBA[2], wBB[2];
         own_weighted_frags(c, lds_rows(c, 0), wjA, wBA);
-        own_weighted_frags(c, lds_rows(c, 1), wjB, wBB);
+        if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), wjB, wBB);
         // solver inputs of this lane's token
         f32x4 accU[8];
         Solver s;
         s.tok = (c0 + grp) * kChunk + 16 * ts + c.n;
-        s.valid = s.tok < c.T_eff;
+        s.valid = solver && s.tok < c.T_eff;
         const int64_t tok_off = c.base_bh + (int64_t)min(s.tok, a.T - 1) * a.stride_t;
         IOBF16::raw4 qraw[8];
+        float lam = 1.0f;
+        if (solver) {                    // (wave-uniform)
 #pragma unroll
-        for (int ft = 0; ft < 8; ++ft) qraw[ft] = IOBF16::load_raw4(a.q, tok_off + 16 * ft + 4 * c.kg);
-        float lam = a.lambda[c.gate_base + (int64_t)min(s.tok, a.T - 1) * a.H];
-        GKA_FT(3);
+            for (int ft = 0; ft < 8; ++ft) qraw[ft] = IOBF16::load_raw4(a.q, tok_off + 16 * ft + 4 * c.kg);
+            lam = a.lambda[c.gate_base + (int64_t)min(s.tok, a.T - 1) * a.H];
+        }
         lds_barrier();
         // ---- 3
-        GKA_FT(4);
         advance_state(c, accH, 0, zetaA, wBA);
-        const float hnB = publish_H(c, accH, 1);
-        advance_state(c, accH, 1, zetaB, wBB);
+        float hnB = 0.0f;
+        if constexpr (!SPLIT) {
+            hnB = publish_H<false>(c, accH, 1);
+            advance_state(c, accH, 1, zetaB, wBB);
+        }
         if (c.lane == 0) {
             sTab[128 + c.w] = hnA;
-            sTab[128 + 8 + c.w] = hnB;
+            if constexpr (!SPLIT) sTab[128 + 8 + c.w] = hnB;
         }
-        build_mask(c, s, grp ? GB : GA, ts);
-        GKA_FT(5);
+        if (solver) build_mask(c, s, grp ? GB : GA, ts);
         lds_barrier();
         // ---- 4
-        GKA_FT(6);
-        if (wide) frobenius_terms<4>(c, s, grp, ts);
-        else frobenius_terms<2>(c, s, grp, ts);
-        GKA_FT(7);
+        if (solver) {
+            if (wide) frobenius_terms<4>(c, s, grp, ts);
+            else frobenius_terms<2>(c, s, grp, ts);
+        }
         lds_barrier();
         // ---- 5
-        GKA_FT(8);
-        s.fro = wide ? frobenius_norm<4>(c, s, grp) : frobenius_norm<2>(c, s, grp);
-        if (a.fro_out && s.valid && c.kg == 0) a.fro_out[c.gate_base + (int64_t)s.tok * a.H] = s.fro;
-        if (!s.valid) lam = 1.0f;
-        GKA_FT(9);
+        if (solver) {
+            s.fro = wide ? frobenius_norm<4>(c, s, grp) : frobenius_norm<2>(c, s, grp);
+            if (a.fro_out && s.valid && c.kg == 0) a.fro_out[c.gate_base + (int64_t)s.tok * a.H] = s.fro;
+            if (!s.valid) lam = 1.0f;
+        }
         lds_barrier();                   // the table is dead: the row tiles may be overwritten
-        GKA_FT(10);
-        if (wide) solve_tokens<4>(c, s, grp, ts, qraw, lam, accU, c0);
-        else solve_tokens<2>(c, s, grp, ts, qraw, lam, accU, c0);
-        GKA_FT(13);
+        if (solver) {
+            if (wide) solve_tokens<4, SPLIT>(c, s, grp, ts, qraw, lam, accU, c0);
+            else solve_tokens<2, SPLIT>(c, s, grp, ts, qraw, lam, accU, c0);
+        } else {
+            // (SPLIT, waves 4-7) this wave's share of the copies of the v rows, the barrier that the solver waves pass
+            // after their passes, and U back from its parking place
+            copy_rows(c, a.v, 0, c0);
+            wait_all_memory();
+            lds_barrier();
+            park_load(c.park, accU);
+        }
         // (the gates are scanned again rather than kept across the passes: two registers instead of six; an opaque
         // copy keeps the compiler from merging the two scans)
         asm volatile("" : "+v"(gmA), "+v"(gmB));
         gate_scans();
-        // this wave's weighted v fragments of both chunks
+        // this wave's weighted v fragments of the chunks
         bf16x8 wVA[2], wVB[2];
         own_weighted_frags(c, lds_rows(c, 0), wjA, wVA);
-        own_weighted_frags(c, lds_rows(c, 1), wjB, wVB);
-        GKA_FT(14);
-        lds_barrier();                   // xhat of both chunks is visible; the key-row fragments are dead
+        if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), wjB, wVB);
+        lds_barrier();                   // xhat of the chunks is visible; the key-row fragments are dead
         // ---- 6
-        GKA_FT(15);
-        // gates of the next two chunks
-        gmA = a.gate[c.gate_base + (int64_t)min((c0 + 2) * kChunk + c.lane, a.T - 1) * a.H];
-        gmB = a.gate[c.gate_base + (int64_t)min((c0 + 3) * kChunk + c.lane, a.T - 1) * a.H];
-        GKA_FT(24);
+        // gates of the next chunks
+        gmA = a.gate[c.gate_base + (int64_t)min((c0 + kChunksPerIter) * kChunk + c.lane, a.T - 1) * a.H];
+        if constexpr (!SPLIT) gmB = a.gate[c.gate_base + (int64_t)min((c0 + 3) * kChunk + c.lane, a.T - 1) * a.H];
         readout_state(c, accU, 0, kOffK);
-        GKA_FT(25);
         advance_state(c, accU, 0, zetaA, wVA);
-        GKA_FT(16);
         lds_barrier();
         // ---- 7: solver A stores while the state part of B is read out into the place of A's xhat
-        GKA_FT(17);
-        if (grp == 0) store_output(c, s, ts, kOffK);
-        GKA_FT(18);
-        readout_state(c, accU, 1, kOffH);
-        GKA_FT(26);
-        advance_state(c, accU, 1, zetaB, wVB);
-        GKA_FT(27);
+        if (solver && grp == 0) store_output(c, s, ts, kOffK);
+        if constexpr (!SPLIT) {
+            readout_state(c, accU, 1, kOffH);
+            advance_state(c, accU, 1, zetaB, wVB);
+        }
         park_store(c.park, accU);
-        GKA_FT(28);
-        lds_barrier();
-        // ---- 8
-        GKA_FT(21);
-        if (grp == 1) store_output(c, s, ts, kOffH);
-        // k rows of the next two chunks: the row tiles are free since the barrier before the readout; the copies land
+        if constexpr (!SPLIT) {
+            lds_barrier();
+            // ---- 8
+            if (grp == 1) store_output(c, s, ts, kOffH);
+        }
+        // k rows of the next chunks: the row tiles are free since the barrier before the readout; the copies land
         // while the next iteration publishes H and scans its gates
-        copy_rows(c, a.k, 0, c0 + 2);
-        copy_rows(c, a.k, 1, c0 + 3);
-        GKA_FT(22);
+        copy_rows(c, a.k, 0, c0 + kChunksPerIter);
+        if constexpr (!SPLIT) copy_rows(c, a.k, 1, c0 + 3);
     }
     wait_all_memory();               // no copy into this workgroup's LDS may be in flight when it ends
 
@@ -997,7 +1028,7 @@ size_t fused_workspace_bytes(int n_pairs, int n_segs)
     return n * (2 * kD * kD * sizeof(float)) + ((n * sizeof(float) + 255) / 256) * 256 + n * (kD * kD * sizeof(float));
 }
 
-hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_t stream, int which)
+hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_t stream, int which, bool split)
 {
     FusedArgs a = a0;
     a.seg_buf = (float *)workspace;
@@ -1012,8 +1043,11 @@ hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_
     bool unused = false;
     bool &attr_set = (dev >= 0 && dev < 64) ? attr_set_on[dev] : unused;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)fused_forward_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           kLdsBytes);
+        hipError_t e = hipFuncSetAttribute((const void *)fused_forward_kernel<false>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void *)fused_forward_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kLdsBytes);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute((const void *)fused_summary_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kSummaryLds);
         if (e != hipSuccess) return e;
@@ -1025,9 +1059,11 @@ hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (which & 2)
-        hipLaunchKernelGGL(fused_forward_kernel, dim3((unsigned)(a.n_pairs * a.n_segs)), dim3(kFusedThreads), kLdsBytes,
-                           stream, a);
+    if (which & 2) {
+        const dim3 grid((unsigned)(a.n_pairs * a.n_segs));
+        if (split) hipLaunchKernelGGL(fused_forward_kernel<true>, grid, dim3(kFusedThreads), kLdsBytes, stream, a);
+        else hipLaunchKernelGGL(fused_forward_kernel<false>, grid, dim3(kFusedThreads), kLdsBytes, stream, a);
+    }
     return hipGetLastError();
 }
 

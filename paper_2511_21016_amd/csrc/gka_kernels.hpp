@@ -163,7 +163,8 @@ struct FusedArgs {
 };
 size_t fused_workspace_bytes(int n_pairs, int n_segs);
 // which: bit 0 the summary launch (segment summaries for the start states), bit 1 the chunk walk itself
-hipError_t launch_fused_forward(const FusedArgs &a, void *workspace, hipStream_t stream, int which = 3);
+// which: bit 0 the summary launch, bit 1 the chunk walk; split: H_[n] and delta as bf16 value + remainder
+hipError_t launch_fused_forward(const FusedArgs &a, void *workspace, hipStream_t stream, int which, bool split);
 
 // Workspace sizes in bytes per (pair, chunk).
 size_t ws_H_bytes_per_chunk(int d, bool compute_bf16);

@@ -52,14 +52,16 @@ def test_cfg3_long_bf16_full():
     assert err <= TOL_BF16
 
 
-def test_cfg4_illconditioned_full():
-    """bf16 tensors, ill-conditioned H_t: run with float32 matrix products (the documented mode for such inputs)."""
+@pytest.mark.parametrize("compute", ["bf16_split", "f32"])
+def test_cfg4_illconditioned_full(compute):
+    """bf16 tensors, ill-conditioned H_t, at full size: on the bf16 matrix cores with H_[n] and the update as value +
+    remainder (GKA_COMPUTE_BF16_SPLIT, the mode for such inputs), and with float32 matrix products."""
     w = synth.CFG4
     x = synth.make_inputs(w)
-    o = _forward(w, x, binding.GKA_COMPUTE_F32)
+    o = _forward(w, x, binding.GKA_COMPUTE_BF16_SPLIT if compute == "bf16_split" else binding.GKA_COMPUTE_F32)
     ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
     err = pair_rel_err(to_host(o), ref)
-    print("cfg4 max rel err", err)
+    print("cfg4", compute, "max rel err", err)
     assert err <= TOL_BF16
 
 

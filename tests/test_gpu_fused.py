@@ -14,6 +14,7 @@ pytestmark = pytest.mark.gpu
 
 TOL_BF16 = 2e-2
 FUSED = binding.GKA_PATH_FUSED
+SPLIT = binding.GKA_COMPUTE_BF16_SPLIT
 
 
 def run(w, x, **kw):
@@ -228,3 +229,114 @@ def test_fused_many_pairs():
     assert pair_rel_err(to_host(o), ref) <= TOL_BF16
     for name in ("H_final", "U_final"):
         assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
+
+
+# ---- GKA_COMPUTE_BF16_SPLIT: H_[n] and the update as bf16 value + remainder, one chunk per iteration of the walk
+
+@pytest.mark.parametrize("T", [1, 17, 63, 64, 65, 128, 130, 321])
+@pytest.mark.parametrize("n_iter", [0, 1, 10])
+def test_split_shapes_around_chunk_boundaries(T, n_iter):
+    w = synth.CFG2.scaled(B=2, H=2, T=T, n_iter=n_iter, seed=700 + T)
+    x = synth.make_inputs(w)
+    o, ex = run(w, x, compute=SPLIT, return_fro=True, return_state=True)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], n_iter, return_fro=True, return_state=True)
+    y = to_host(o)
+    assert np.isfinite(y).all()
+    assert pair_rel_err(y, ref) <= TOL_BF16
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+    for name in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
+
+
+@pytest.mark.parametrize("walk", [1, 3, 4])
+@pytest.mark.parametrize("layout", ["full", "lower_blocks"])
+def test_split_segments_with_initial_state(walk, layout):
+    """Walks of one, three and four chunks (an odd walk is possible here: one chunk per iteration), on top of a
+    caller's initial state."""
+    w = synth.CFG2.scaled(B=1, H=3, T=1300, n_iter=8, gate_mean=5.0, seed=4200 + walk)
+    x = synth.make_inputs(w)
+    Hi, Ui = spd_state(w, 9)
+    Hdev = Hi.copy()
+    kw = {}
+    if layout == "lower_blocks":
+        blk = np.arange(w.d) // 32
+        Hdev[:, :, blk[:, None] < blk[None, :]] = np.nan
+        kw["state_layout"] = binding.GKA_STATE_H_LOWER_BLOCKS
+    o, ex = run(w, x, compute=SPLIT, walk_chunks=walk, H_init=to_device(Hdev, "f32"), U_init=to_device(Ui, "f32"),
+                return_state=True, return_fro=True, **kw)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, H_init=Hi, U_init=Ui,
+                              return_state=True, return_fro=True)
+    assert pair_rel_err(to_host(o), ref) <= TOL_BF16
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+    for name in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
+
+
+def test_split_ill_conditioned_against_the_plain_bf16_operands():
+    """Configuration 4's recipe (keys of rank 16, lambda_t = 1e-3 ||H_t||_F, 16 passes) at a size the oracle follows
+    in full: the split operands meet the bf16 tolerance where single bf16 operands are off by several percent, and
+    match the float32 products to a fraction of the tolerance."""
+    w = synth.CFG4.scaled(B=1, H=4, T=2048)
+    x = synth.make_inputs(w)
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    e_split = pair_rel_err(to_host(run(w, x, compute=SPLIT)), ref)
+    e_plain = pair_rel_err(to_host(run(w, x, path=FUSED)), ref)
+    e_f32 = pair_rel_err(to_host(run(w, x, compute=binding.GKA_COMPUTE_F32)), ref)
+    print("ill-conditioned: split", e_split, "single bf16 operands", e_plain, "float32 products", e_f32)
+    assert e_split <= TOL_BF16 and e_f32 <= TOL_BF16
+    assert e_plain > TOL_BF16            # (measured 13 %: what the split mode is for)
+
+
+def test_split_packed_sequences_strides_and_rerun():
+    import torch
+    lengths = [70, 1, 130, 63, 64, 56, 200, 17]
+    w = synth.CFG2.scaled(B=1, H=2, T=sum(lengths), n_iter=6, seed=23)
+    x = {n: a.copy() for n, a in synth.make_inputs(w).items()}
+    starts = np.cumsum([0] + lengths[:-1])
+    x["gate"][:, starts] = 0.0
+    y = to_host(run(w, x, compute=SPLIT, walk_chunks=3))
+    assert np.isfinite(y).all()
+    for s0, n in zip(starts, lengths):
+        part = {name: np.ascontiguousarray(a[:, s0:s0 + n]) for name, a in x.items()}
+        part["gate"][:, 0] = 0.5
+        ref = oracle.forward(part["q"], part["k"], part["v"], part["gate"], part["lam"], w.n_iter)
+        assert pair_rel_err(y[:, s0:s0 + n], ref) <= TOL_BF16, (s0, n)
+    # head-major tensors, a poisoned workspace, and the same call twice
+    w = synth.CFG2.scaled(B=2, H=3, T=333, seed=13)
+    x = synth.make_inputs(w)
+    dev = {n: to_device(np.ascontiguousarray(np.transpose(x[n], (0, 2, 1, 3))), "bf16") for n in ("q", "k", "v")}
+    gate, lam = to_device(x["gate"], "f32"), to_device(x["lam"], "f32")
+    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, SPLIT,
+                                 strides=(w.H * w.T * w.d, w.d, w.T * w.d), walk_chunks=1)
+    outs = []
+    for fill in (float("nan"), 1e30):
+        ws = torch.full((binding.forward_workspace_bytes(params) // 4,), fill, dtype=torch.float32, device="cuda")
+        o = torch.zeros_like(dev["v"])
+        st = binding.forward_raw(params, dev["q"].data_ptr(), dev["k"].data_ptr(), dev["v"].data_ptr(),
+                                 gate.data_ptr(), lam.data_ptr(), o.data_ptr(), workspace=ws.data_ptr(),
+                                 workspace_bytes=ws.numel() * 4, stream=torch.cuda.current_stream().cuda_stream)
+        assert st == binding.GKA_OK
+        torch.cuda.synchronize()
+        outs.append(o)
+    assert torch.equal(outs[0], outs[1])
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    assert pair_rel_err(np.transpose(to_host(outs[0]), (0, 2, 1, 3)), ref) <= TOL_BF16
+
+
+def test_split_is_refused_where_the_fused_kernel_does_not_apply():
+    w = synth.CFG2.scaled(B=1, H=1, T=64, d=64)
+    x = synth.make_inputs(w)
+    dev = upload_inputs(x, w.dtype)
+    with pytest.raises(binding.GkaError) as e:
+        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=SPLIT)
+    assert e.value.status == binding.GKA_ERR_UNSUPPORTED
+    w = synth.CFG2.scaled(B=1, H=1, T=64)
+    x = synth.make_inputs(w)
+    dev = upload_inputs(x, w.dtype)
+    with pytest.raises(binding.GkaError) as e:
+        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=SPLIT,
+                            path=binding.GKA_PATH_TWO_PHASE)
+    assert e.value.status == binding.GKA_ERR_UNSUPPORTED
+    with pytest.raises(binding.GkaError) as e:
+        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], None, w.n_iter, compute=SPLIT, lambda_scale=0.1)
+    assert e.value.status == binding.GKA_ERR_UNSUPPORTED
