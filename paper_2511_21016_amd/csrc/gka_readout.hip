@@ -74,10 +74,20 @@ __device__ __forceinline__ float *summary_tile(const ReadoutArgs &a, int pair, i
 
 }  // namespace
 
+// Waves per SIMD a variant is compiled for: two (256 registers each), but one (512 registers, half of them
+// accumulation registers that the compiler uses as a second file) for the d = 128 variants with a second operand
+// tensor, whose prefetch registers do not fit beside the state otherwise (they spilled 20-37 registers to memory).
+constexpr int readout_waves_per_simd(int dk, bool summary, int qmode, int kvlo)
+{
+    return (dk == 128 && !summary && (qmode == 1 || kvlo != 0)) ? 1 : 2;
+}
+
 // QMODE: 0 q in bf16; 1 q as bf16 value + bf16 remainder (q_lo); 2 q in float32, split into value + remainder here.
 // KVLO: 0 k and v as they are; 1 k comes with a remainder tensor (k_lo); 2 v does (v_lo). Not combined with QMODE != 0.
 template <int DK, int DV, bool GATED, bool SUMMARY, int QMODE, int KVLO = 0>
-__global__ __launch_bounds__(DV * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void gla_readout_kernel(ReadoutArgs a)
+__global__ __launch_bounds__(DV * 2)
+    __attribute__((amdgpu_waves_per_eu(readout_waves_per_simd(DK, SUMMARY, QMODE, KVLO), readout_waves_per_simd(DK, SUMMARY, QMODE, KVLO))))
+    void gla_readout_kernel(ReadoutArgs a)
 {
     typedef ReadoutShape<DK, DV> SH;
     constexpr bool QLO = QMODE != 0, QF32 = QMODE == 2;
