@@ -133,19 +133,12 @@ __device__ __forceinline__ void refresh_lane(Ctx &c)
 __device__ __forceinline__ bf16x8 *lds_frags(const Ctx &c, int off) { return (bf16x8 *)(c.smem + off); }
 __device__ __forceinline__ uint16_t *lds_rows(const Ctx &c, int g) { return (uint16_t *)(c.smem + kOffR + g * 16384); }
 
-// Gates of one chunk: lane j holds G_j = sum_{i<=j} log2 gamma_i over the chunk (tokens that do not exist: gamma = 1).
-struct ChunkGates {
-    float G, Gtot;
-};
-__device__ __forceinline__ ChunkGates scan_gates(const Ctx &c, int tok0)
+// Per-token scalars of a chunk travel from "lane j holds the value of token j" to fragment order through a small
+// table in LDS that every wave keeps for itself (written and read back by the same wave: no barrier; as lane
+// broadcasts the same reads cost an LDS round trip each, 8 per fragment). Slots of 64 floats.
+__device__ __forceinline__ float *wave_table(const Ctx &c, int byte_off, int slot)
 {
-    const int t = tok0 + c.lane;
-    const float gm = c.a.gate[c.gate_base + (int64_t)min(t, c.a.T - 1) * c.a.H];
-    const float lg = (t < c.T_eff) ? log2_gate(gm) : 0.0f;
-    ChunkGates r;
-    r.G = wave_inclusive_scan(lg, c.lane);
-    r.Gtot = lane_value(r.G, 63);
-    return r;
+    return (float *)(c.smem + byte_off) + (c.w * 4 + slot) * 64;
 }
 
 // ---- state role ------------------------------------------------------------------------------------------------
@@ -153,23 +146,19 @@ __device__ __forceinline__ ChunkGates scan_gates(const Ctx &c, int tok0)
 // once per iteration, straight through, so its size is paid in instruction fetches.)
 
 // This wave's B fragments of a chunk update: rows of the tile (k or v) transposed, columns 16 w .., each token
-// scaled by its weight (lane j of wj: weight of token j).
+// scaled by its weight (wtab: the weights of the chunk's 64 tokens, a slot of this wave's table).
 template <class Layout = Rows>
-__device__ __forceinline__ void own_weighted_frags(const Ctx &c, const uint16_t *rows, float wj, bf16x8 (&out)[2],
-                                                   Layout at = Layout())
+__device__ __forceinline__ void own_weighted_frags(const Ctx &c, const uint16_t *rows, const float *wtab,
+                                                   bf16x8 (&out)[2], Layout at = Layout())
 {
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
         const int t0 = 32 * st + 4 * c.kg;
         const bf16x8 raw = gather_transposed_bf16(rows, at, 16 * c.w, c.lane, t0, t0 + 16);
+        const f32x4 w0 = *(const f32x4 *)(wtab + t0), w1 = *(const f32x4 *)(wtab + t0 + 16);
         f32x4 lo, hi;
         unpack8(raw, lo, hi);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            lo[p] *= __shfl(wj, t0 + p, 64);
-            hi[p] *= __shfl(wj, t0 + 16 + p, 64);
-        }
-        out[st] = pack8(lo, hi);
+        out[st] = pack8(lo * w0, hi * w1);
     }
 }
 
@@ -481,20 +470,22 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
 }
 
 // Decay mask of Section 4.2.1 in the log-space form of Appendix B.2 (base 2): M[j][c] = 2^(G_c - G_j) for j <= c.
-__device__ __forceinline__ void build_mask(const Ctx &c, Solver &s, float G, int ts)
+// (Gtab: G_j of the chunk's 64 tokens, a slot of this wave's table.)
+__device__ __forceinline__ void build_mask(const Ctx &c, Solver &s, const float *Gtab, int ts)
 {
     const int c_local = 16 * ts + c.n;
-    const float Gc = __shfl(G, c_local, 64);
+    const float Gc = Gtab[c_local];
     s.zeta = exp2f(Gc);
 #pragma unroll
-    for (int js = 0; js < 4; ++js)
+    for (int js = 0; js < 4; ++js) {
+        const f32x4 Gj = *(const f32x4 *)(Gtab + 16 * js + 4 * c.kg);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int j = 16 * js + 4 * c.kg + r;
-            const float Gj = __shfl(G, j, 64);
             // hardware exp2: results below the normal range (decays under 2^-126) are flushed to zero
-            s.mreg[js][r] = (j <= c_local) ? __builtin_amdgcn_exp2f(Gc - Gj) : 0.0f;
+            s.mreg[js][r] = (j <= c_local) ? __builtin_amdgcn_exp2f(Gc - Gj[r]) : 0.0f;
         }
+    }
 }
 
 // Chunk-wise Frobenius norm, first half: w_j of this wave's tokens to the table.
@@ -676,6 +667,8 @@ template <bool SPLIT>
 __device__ __forceinline__ void build_key_frags(const Ctx &c)
 {
     constexpr int PER_WAVE = SPLIT ? 2 : 4;
+    // all reads first, then all writes: read-then-write per fragment would be one LDS round trip after the other
+    bf16x8 rowf[PER_WAVE], trf[PER_WAVE];
 #pragma unroll
     for (int q = 0; q < PER_WAVE; ++q) {
         const int idx = c.w * PER_WAVE + q;
@@ -686,14 +679,21 @@ __device__ __forceinline__ void build_key_frags(const Ctx &c)
             const u16x4 lo = *(const u16x4 *)(rows + Rows()(16 * js + c.n, 32 * fb + 4 * c.kg));
             const u16x4 hi = *(const u16x4 *)(rows + Rows()(16 * js + c.n, 32 * fb + 16 + 4 * c.kg));
             const u16x8 u = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            lds_frags(c, kOffK + g * 16384)[f * 64 + c.lane] = __builtin_bit_cast(bf16x8, u);
+            rowf[q] = __builtin_bit_cast(bf16x8, u);
         }
         {
             const int ft = f >> 1, jb = f & 1;
             const int t0 = 32 * jb + 4 * c.kg;
-            lds_frags(c, kOffKT + g * 16384)[f * 64 + c.lane] =
-                gather_transposed_bf16(rows, Rows(), 16 * ft, c.lane, t0, t0 + 16);
+            trf[q] = gather_transposed_bf16(rows, Rows(), 16 * ft, c.lane, t0, t0 + 16);
         }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < PER_WAVE; ++q) {
+        const int idx = c.w * PER_WAVE + q;
+        const int g = idx >> 4, f = idx & 15;
+        lds_frags(c, kOffK + g * 16384)[f * 64 + c.lane] = rowf[q];
+        lds_frags(c, kOffKT + g * 16384)[f * 64 + c.lane] = trf[q];
     }
 }
 
@@ -816,11 +816,18 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         wait_all_memory();               // this wave's copies of k rows have landed
         lds_barrier();                   // ... and everybody else's
         // ---- 2
+        // this wave's table of the chunks' per-token scalars: in a part of LDS that is free until the next barrier
+        // (the second chunk's H_[n]; SPLIT: the second chunk's key fragments, which do not exist)
+        constexpr int kTabBefore = SPLIT ? kOffK + 16384 : kOffH + 32768;
+        constexpr int kTabAfter = kOffK + 16384;             // after the passes: the key-row fragments are dead
+        wave_table(c, kTabBefore, 0)[c.lane] = wjA;
+        wave_table(c, kTabBefore, 2)[c.lane] = grp ? GB : GA;
+        if constexpr (!SPLIT) wave_table(c, kTabBefore, 1)[c.lane] = wjB;
         const float hnA = publish_H<SPLIT>(c, accH, 0);
         build_key_frags<SPLIT>(c);
         bf16x8 wBA[2], wBB[2];
-        own_weighted_frags(c, lds_rows(c, 0), wjA, wBA);
-        if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), wjB, wBB);
+        own_weighted_frags(c, lds_rows(c, 0), wave_table(c, kTabBefore, 0), wBA);
+        if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), wave_table(c, kTabBefore, 1), wBB);
         // solver inputs of this lane's token
         f32x4 accU[8];
         Solver s;
@@ -833,6 +840,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
             for (int ft = 0; ft < 8; ++ft) qraw[ft] = IOBF16::load_raw4(a.q, tok_off + 16 * ft + 4 * c.kg);
             lam = a.lambda[c.gate_base + (int64_t)min(s.tok, a.T - 1) * a.H];
+            build_mask(c, s, wave_table(c, kTabBefore, 2), ts);
         }
         lds_barrier();
         // ---- 3
@@ -846,7 +854,6 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             sTab[128 + c.w] = hnA;
             if constexpr (!SPLIT) sTab[128 + 8 + c.w] = hnB;
         }
-        if (solver) build_mask(c, s, grp ? GB : GA, ts);
         lds_barrier();
         // ---- 4
         if (solver) {
@@ -878,8 +885,10 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         gate_scans();
         // this wave's weighted v fragments of the chunks
         bf16x8 wVA[2], wVB[2];
-        own_weighted_frags(c, lds_rows(c, 0), wjA, wVA);
-        if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), wjB, wVB);
+        wave_table(c, kTabAfter, 0)[c.lane] = wjA;
+        if constexpr (!SPLIT) wave_table(c, kTabAfter, 1)[c.lane] = wjB;
+        own_weighted_frags(c, lds_rows(c, 0), wave_table(c, kTabAfter, 0), wVA);
+        if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), wave_table(c, kTabAfter, 1), wVB);
         lds_barrier();                   // xhat of the chunks is visible; the key-row fragments are dead
         // ---- 6
         // gates of the next chunks
@@ -927,7 +936,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 // The tiles are padded, not swizzled: the reads of a wave's eight tiles then differ by constant offsets.
 constexpr int kSummaryRowElems = kD + MmaBF16::kRowPad;    // rows 32 bytes apart modulo 256
 constexpr int kSummaryTile = kChunk * kSummaryRowElems * 2; // bytes
-constexpr int kSummaryLds = 2 * 2 * 2 * kSummaryTile;      // [buffer][chunk of the pair][k, v] row tiles
+constexpr int kSummaryTables = 2 * 2 * 2 * kSummaryTile;   // offset of the waves' tables of per-token weights
+constexpr int kSummaryLds = kSummaryTables + 8 * 4 * 64 * 4;   // [buffer][chunk of the pair][k, v] row tiles + tables
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_summary_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -992,8 +1002,10 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             const uint16_t *rowsK = (const uint16_t *)(tiles + (2 * g + 0) * kSummaryTile);
             const uint16_t *rowsV = (const uint16_t *)(tiles + (2 * g + 1) * kSummaryTile);
             bf16x8 wK[2], wV[2];
-            own_weighted_frags(c, rowsK, wj, wK, at);
-            own_weighted_frags(c, rowsV, wj, wV, at);
+            float *wtab = wave_table(c, kSummaryTables, g);
+            wtab[c.lane] = wj;
+            own_weighted_frags(c, rowsK, wtab, wK, at);
+            own_weighted_frags(c, rowsV, wtab, wV, at);
 #pragma unroll
             for (int jt = 0; jt < 8; ++jt) {
                 // (operand reads of four tiles at a time in flight: more would take the registers of the prefetch)
