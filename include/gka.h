@@ -237,7 +237,8 @@ gka_status gka_decode_tokens(const gka_params *p,
  * on reversed copies for GKA_F32 tensors), plus a few elementwise kernels: about five times the cost of gka_forward
  * with bf16 tensors and operands; the paper's chunk-wise backward kernels are not reproduced.
  *   Supported: lambda given or NULL with p->lambda_scale > 0 (the rule lambda_t = a ||H_t||_F, whose w_t H_t terms
- *   of the Lemma in Section 4.2.2 cost two more readouts), zero initial states, packed tensors (explicit strides:
+ *   of the Lemma in Section 4.2.2 cost two more readouts), zero initial states (gka_backward_from_state takes
+ *   others), packed tensors (explicit strides:
  *   GKA_ERR_UNSUPPORTED), p->beta and p->alpha as in gka_forward. Packed sequences (a gate of 0 at a sequence's first token) are handled:
  *   dgate at such a gate is written as 0 (the formula divides by the gate), and the cumulative sum behind dgate
  *   restarts there.
@@ -255,6 +256,28 @@ gka_status gka_backward(const gka_params *p,
                         float *dlambda, float *dbeta, float *dalpha,
                         void *workspace, size_t workspace_bytes,
                         void *hip_stream);
+
+/* gka_backward for a sequence that continues from given states (chunked training over a long sequence, a prefix
+ * cached elsewhere): the forward pass starts from H_init, U_init as gka_forward does (the first gate multiplies them),
+ * and the gradients at the two states are returned as well,
+ *     dH_init = gamma_0 sum_t M[0,t] dL/dH_t (partial),   dU_init = gamma_0 sum_t M[0,t] dy_t xt_t^T
+ * (Section 4.2.2: the accumulated gradients of the reverse recurrences at the first token, times its gate; with the rule
+ * lambda_t = a ||H_t||_F the -c_t H_t terms of the Lemma are included). dH_init is the partial derivative with respect
+ * to every element of H_init taken as independent, like the paper's dL/dH_t: it is not symmetrised.
+ *   H_init [B,H,d,d], U_init [B,H,d,d] float32, both or neither (NULL: zero states, as gka_backward)
+ *   dH_init, dU_init [B,H,d,d] float32, each written if not NULL
+ *   Supported: GKA_BF16 tensors, GKA_STATE_FULL (else GKA_ERR_UNSUPPORTED); everything else as gka_backward, whose
+ *   workspace query also serves this call. */
+gka_status gka_backward_from_state(const gka_params *p,
+                                   const void *q, const void *k, const void *v,
+                                   const float *gate, const float *lambda,
+                                   const void *dy,
+                                   const float *H_init, const float *U_init,
+                                   float *dq, float *dk, float *dv, float *dgate,
+                                   float *dlambda, float *dbeta, float *dalpha,
+                                   float *dH_init, float *dU_init,
+                                   void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
 
 /* Forward pass with latent sketching (appendix "Latent Sketching for Approximate Solutions"): the normal equations
  * are projected into the subspace spanned by the rows of a sketch matrix S, solved there, and the solution is

@@ -30,6 +30,7 @@ EXPORTED_SYMBOLS = (
     "gka_decode_tokens",
     "gka_backward_workspace_bytes",
     "gka_backward",
+    "gka_backward_from_state",
     "gka_forward_sketched_workspace_bytes",
     "gka_forward_sketched",
     "gka_status_string",
@@ -92,6 +93,9 @@ def load_library():
         lib.gka_backward.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp, fp, fp, vp,
                                      ctypes.c_size_t, vp]
         lib.gka_backward.restype = ctypes.c_int
+        lib.gka_backward_from_state.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, vp, fp, fp, fp, fp, fp,
+                                                fp, fp, fp, fp, fp, fp, vp, ctypes.c_size_t, vp]
+        lib.gka_backward_from_state.restype = ctypes.c_int
         lib.gka_forward_sketched_workspace_bytes.argtypes = [ctypes.POINTER(GkaParams), ctypes.c_int]
         lib.gka_forward_sketched_workspace_bytes.restype = ctypes.c_size_t
         lib.gka_forward_sketched.argtypes = [ctypes.POINTER(GkaParams), vp, vp, vp, fp, fp, fp, ctypes.c_int,
@@ -270,11 +274,20 @@ def backward_raw(params, q, k, v, gate, lam, dy, dq, dk, dv, dgate, dlam=None, d
                                            workspace, workspace_bytes, stream))
 
 
+def backward_from_state_raw(params, q, k, v, gate, lam, dy, H_init, U_init, dq, dk, dv, dgate, dlam=None, dbeta=None,
+                            dalpha=None, dH_init=None, dU_init=None, workspace=None, workspace_bytes=0, stream=None):
+    pp = None if params is None else ctypes.byref(params)
+    return int(load_library().gka_backward_from_state(pp, q, k, v, gate, lam, dy, H_init, U_init, dq, dk, dv, dgate,
+                                                      dlam, dbeta, dalpha, dH_init, dU_init, workspace,
+                                                      workspace_bytes, stream))
+
+
 def gka_backward(q, k, v, gate, lam, dy, n_iter, *, compute=None, beta=None, alpha=None, lambda_scale=0.0,
-                 workspace=None):
+                 workspace=None, H_init=None, U_init=None, return_state_grads=False):
     """gka_backward on torch CUDA tensors (packed [B,T,H,d] / [B,T,H]). lam None: the rule
     lambda_t = lambda_scale ||H_t||_F. Returns a dict of float32 gradients: dq, dk, dv, dgate, dlam (when lam is
-    given) and, when given, dbeta, dalpha."""
+    given) and, when given, dbeta, dalpha. H_init, U_init [B,H,d,d] float32: the sequence continues from these states
+    (gka_backward_from_state); return_state_grads: also dH_init, dU_init."""
     import torch
     B, T, H, d = q.shape
     for x in (q, k, v, dy):
@@ -298,6 +311,16 @@ def gka_backward(q, k, v, gate, lam, dy, n_iter, *, compute=None, beta=None, alp
     if alpha is not None:
         out["dalpha"] = torch.empty((B, T, H), **f32)
     stream = torch.cuda.current_stream(q.device).cuda_stream
+    if H_init is not None or return_state_grads:
+        if return_state_grads:
+            out["dH_init"] = torch.empty((B, H, d, d), **f32)
+            out["dU_init"] = torch.empty((B, H, d, d), **f32)
+        _check(backward_from_state_raw(params, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam), _ptr(dy),
+                                       _ptr(H_init), _ptr(U_init), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
+                                       _ptr(out["dgate"]), _ptr(out.get("dlam")), _ptr(out.get("dbeta")),
+                                       _ptr(out.get("dalpha")), _ptr(out.get("dH_init")), _ptr(out.get("dU_init")),
+                                       _ptr(workspace), workspace.numel(), stream))
+        return out
     _check(backward_raw(params, _ptr(q), _ptr(k), _ptr(v), _ptr(gate), _ptr(lam), _ptr(dy), _ptr(out["dq"]),
                         _ptr(out["dk"]), _ptr(out["dv"]), _ptr(out["dgate"]), _ptr(out.get("dlam")),
                         _ptr(out.get("dbeta")), _ptr(out.get("dalpha")), _ptr(workspace), workspace.numel(), stream))

@@ -413,6 +413,7 @@ struct BackwardPlan {
     size_t off_f32[9];        // xhat, p; with the fused readouts also y, H x, A k, A^T k, Ubar k, U^T dy, Ubar^T v
     size_t off_io[23];
     size_t off_m[6];          // gate_rev, zeros, s, fro, c, C
+    size_t off_fin[3];        // final states of three reverse readouts (gradients at the initial states)
     size_t off_fwd, fwd_bytes, total;
 };
 enum { IO_Y, IO_DXT, IO_RHS, IO_HX, IO_X, IO_XT, IO_KR, IO_VR, IO_DYR, IO_XR, IO_PR, IO_XTR, IO_R1, IO_R2, IO_R3, IO_R4,
@@ -431,6 +432,10 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     for (int i = 0; i < 9; ++i) { bp->off_f32[i] = off; off = align_up(off + bp->n_elems * 4, 256); }
     for (int i = 0; i < 23; ++i) { bp->off_io[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
     for (int i = 0; i < 6; ++i) { bp->off_m[i] = off; off = align_up(off + bp->n_tokens * 4, 256); }
+    for (int i = 0; i < 3; ++i) {
+        bp->off_fin[i] = off;
+        off = align_up(off + (size_t)p->B * p->H * p->d_k * p->d_k * 4, 256);
+    }
     bp->off_fwd = off;
     gka_params pf = *p;
     pf.xhat_out = nullptr;
@@ -458,10 +463,24 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
                         float *dlambda, float *dbeta, float *dalpha, void *workspace, size_t workspace_bytes,
                         void *hip_stream)
 {
+    return gka_backward_from_state(p, q, k, v, gate, lambda, dy, nullptr, nullptr, dq, dk, dv, dgate, dlambda, dbeta,
+                                   dalpha, nullptr, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+gka_status gka_backward_from_state(const gka_params *p, const void *q, const void *k, const void *v,
+                                   const float *gate, const float *lambda, const void *dy, const float *H_init,
+                                   const float *U_init, float *dq, float *dk, float *dv, float *dgate,
+                                   float *dlambda, float *dbeta, float *dalpha, float *dH_init, float *dU_init,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream)
+{
     BackwardPlan bp;
     gka_status st = make_backward_plan(p, &bp);
     if (st != GKA_OK) return st;
     if (!q || !k || !v || !gate || !dy || !dq || !dk || !dv || !dgate) return GKA_ERR_NULL;
+    if ((H_init == nullptr) != (U_init == nullptr)) return GKA_ERR_NULL;
+    const bool with_state = H_init != nullptr || dH_init != nullptr || dU_init != nullptr;
+    // initial states: bf16 tensors (the readouts that keep their state in registers), complete H_init
+    if (with_state && (p->io_dtype != GKA_BF16 || p->state_layout != GKA_STATE_FULL)) return GKA_ERR_UNSUPPORTED;
     const bool rule = lambda == nullptr;          // lambda_t = lambda_scale ||H_t||_F
     if (rule && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < bp.total) return GKA_ERR_WORKSPACE;
@@ -499,8 +518,11 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
         pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat;
         pp.state_layout = GKA_STATE_FULL;
         const bool plain_readout = alpha == zeros;
-        return forward_impl(&pp, qq, kk, vv, gg, lambda, out, nullptr, nullptr, nullptr, nullptr, fro_out, fws,
-                            bp.fwd_bytes, hip_stream, nullptr, plain_readout, solve_only, q_lo);
+        // (initial states reach the two solves; the composition of plain readouts for float32 tensors has none)
+        const bool is_solve = xhat != nullptr;
+        return forward_impl(&pp, qq, kk, vv, gg, lambda, out, is_solve ? H_init : nullptr, is_solve ? U_init : nullptr,
+                            nullptr, nullptr, fro_out, fws, bp.fwd_bytes, hip_stream, nullptr, plain_readout, solve_only,
+                            q_lo);
     };
     auto glue = [&](int which) {
         return gka::launch_backward_glue(g, which, io_bf16, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
@@ -511,10 +533,14 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     const bool fused = io_bf16;
     // out_f32: the output in float32 (the pieces of the gate gradient's sum), else in the tensors' dtype
     // q_lo, k_lo, v_lo: the bf16 remainder of an operand that was computed in float32 (x, xt), or nullptr
+    // init / init_transposed: the state before the first token (forward readouts); fin: where the state after the last
+    // token of the walk goes (reverse readouts: the accumulated gradient at the initial state)
     auto readout = [&](const void *qq, const void *kk, const void *vv, const float *beta, bool reverse, void *out,
                        int seg_mode = 0, float *out_f32 = nullptr, const void *q_lo = nullptr,
-                       const void *k_lo = nullptr, const void *v_lo = nullptr) {
+                       const void *k_lo = nullptr, const void *v_lo = nullptr, const float *init = nullptr,
+                       bool init_transposed = false, float *fin = nullptr) {
         gka::ReadoutArgs r;
+        r.init_state = init; r.init_transposed = init_transposed; r.final_state = fin;
         r.q = qq; r.q_lo = q_lo; r.k_lo = k_lo; r.v_lo = v_lo; r.q_is_f32 = false; r.k = kk; r.v = vv; r.o = out;
         r.o_f32 = out_f32;
         r.gate = gate; r.beta = beta;
@@ -540,32 +566,41 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     GKA_TRY(fwd(q, k, v, gate, p->beta, p->alpha, p->n_iter, io(IO_Y), xf, rule ? fro : nullptr, fused));
     GKA_TRY(glue(0));
     // y_t again, from the stored xt (see the combine kernel)
-    if (fused) GKA_TRY(readout(io(IO_XT), k, v, p->beta, false, nullptr, 0, f32buf(2), io(IO_XT_LO)));
+    if (fused) GKA_TRY(readout(io(IO_XT), k, v, p->beta, false, nullptr, 0, f32buf(2), io(IO_XT_LO), nullptr, nullptr,
+                               U_init));
     // dxt_t = U_t^T dy_t: the recurrence with the roles of k and v exchanged, read out with dy
     // (its state is the transpose of the one just read out: the segment summaries are reused)
-    if (fused) GKA_TRY(readout(dy, v, k, p->beta, false, nullptr, 2, f32buf(7)));
+    if (fused) GKA_TRY(readout(dy, v, k, p->beta, false, nullptr, 2, f32buf(7), nullptr, nullptr, nullptr, U_init, true));
     else GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
     GKA_TRY(glue(1));
     // p_t = CH(H_t + lambda_t I, alpha_t dxt_t, r)
     GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32, nullptr, fused,
                 fused ? io(IO_RHS_LO) : nullptr));
     // H_t x_t
-    if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, nullptr, 0, f32buf(3), io(IO_X_LO)));
+    if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, nullptr, 0, f32buf(3), io(IO_X_LO), nullptr, nullptr,
+                               H_init));
     else GKA_TRY(fwd(io(IO_X), k, k, gate, p->beta, zeros, 0, io(IO_HX), nullptr));
     // the rule's extra gradient -c_t H_t at every state: c_t, C_t = sum_{s>=t} M[t,s]^2 c_s, and H_t k_t
     if (rule) {
         GKA_TRY(glue(5));
         GKA_TRY(glue(6));
-        if (fused) GKA_TRY(readout(k, k, k, p->beta, false, io(IO_HK), 1));
+        if (fused) GKA_TRY(readout(k, k, k, p->beta, false, io(IO_HK), 1, nullptr, nullptr, nullptr, nullptr, H_init));
         else GKA_TRY(fwd(k, k, k, gate, p->beta, zeros, 0, io(IO_HK), nullptr));
     }
     // reverse recurrences: A_t k_t, A_t^T k_t, Ubar_t^T v_t, Ubar_t k_t (no write gate inside them)
     GKA_TRY(glue(2));
     if (fused) {
-        if (rule) GKA_TRY(readout(k, k, io(IO_VPR), nullptr, true, io(IO_R5)));
-        GKA_TRY(readout(k, io(IO_X), io(IO_PR), nullptr, true, nullptr, 0, f32buf(4), nullptr, io(IO_X_LO), nullptr));
+        float *fin_px = with_state ? (float *)(ws + bp.off_fin[0]) : nullptr;
+        float *fin_xtdy = with_state ? (float *)(ws + bp.off_fin[1]) : nullptr;
+        float *fin_ck = with_state && rule ? (float *)(ws + bp.off_fin[2]) : nullptr;
+        if (rule) GKA_TRY(readout(k, k, io(IO_VPR), nullptr, true, io(IO_R5), 0, nullptr, nullptr, nullptr, nullptr,
+                                  nullptr, false, fin_ck));
+        GKA_TRY(readout(k, io(IO_X), io(IO_PR), nullptr, true, nullptr, 0, f32buf(4), nullptr, io(IO_X_LO), nullptr,
+                        nullptr, false, fin_px));
         GKA_TRY(readout(k, io(IO_PR), io(IO_X), nullptr, true, nullptr, 2, f32buf(5), nullptr, nullptr, io(IO_X_LO)));
-        GKA_TRY(readout(v, dy, io(IO_XT), nullptr, true, nullptr, 0, f32buf(8), nullptr, nullptr, io(IO_XT_LO)));
+        GKA_TRY(readout(v, dy, io(IO_XT), nullptr, true, nullptr, 0, f32buf(8), nullptr, nullptr, io(IO_XT_LO),
+                        nullptr, false, fin_xtdy));
+        g.fin_px = fin_px; g.fin_xtdy = fin_xtdy; g.fin_ck = fin_ck;
         GKA_TRY(readout(k, io(IO_XT), dy, nullptr, true, nullptr, 2, f32buf(6), nullptr, io(IO_XT_LO), nullptr));
     } else {
         if (rule) GKA_TRY(fwd(io(IO_KR), io(IO_KR), io(IO_VPR), gate_rev, nullptr, zeros, 0, io(IO_R5), nullptr));
@@ -576,6 +611,10 @@ gka_status gka_backward(const gka_params *p, const void *q, const void *k, const
     }
     GKA_TRY(glue(3));
     GKA_TRY(glue(4));
+    if (dH_init || dU_init) {
+        g.H_init = H_init; g.dH_init = dH_init; g.dU_init = dU_init; g.n_pairs = p->B * p->H;
+        GKA_TRY(glue(7));
+    }
 #undef GKA_TRY
     return GKA_OK;
 }
@@ -695,6 +734,6 @@ const char *gka_status_string(gka_status s)
     return "unknown status";
 }
 
-int gka_version(void) { return 600; }
+int gka_version(void) { return 700; }
 
 }  // extern "C"

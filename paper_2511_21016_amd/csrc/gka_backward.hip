@@ -274,6 +274,28 @@ __global__ __launch_bounds__(64) void bwd_gate_scan_kernel(BackwardGlueArgs a)
     }
 }
 
+// Gradients at the initial states (Section 4.2.2: the accumulated gradients at H_0 and U_0, times the first gate):
+//   dH_init = gamma_0 Abar_0,  Abar_0 = -sum_t M[0,t] p_t xhat_t^T  [- gamma_0 C_0 H_init - sum_j M[0,j] beta_j C_j k_j k_j^T
+//   with the rule lambda_t = a ||H_t||_F],   dU_init = gamma_0 sum_t M[0,t] dy_t xt_t^T,
+// from the states that the reverse readouts hold after their last token (token 0).
+__global__ __launch_bounds__(256) void bwd_init_grads_kernel(BackwardGlueArgs a)
+{
+    const int64_t dd = (int64_t)a.d * a.d;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= (int64_t)a.n_pairs * dd) return;
+    const int64_t pair = e / dd, ij = e - pair * dd;
+    const int i = (int)(ij / a.d), j = (int)(ij - (int64_t)i * a.d);
+    const int64_t b = pair / a.H, h = pair - b * a.H;
+    const int64_t tok0 = (b * a.T) * a.H + h;            // the pair's first token
+    const float g0 = a.gate[tok0];
+    if (a.dH_init) {
+        float acc = -a.fin_px[e];
+        if (a.rule_a > 0.0f) acc -= g0 * a.C[tok0] * (a.H_init ? a.H_init[e] : 0.0f) + a.fin_ck[e];
+        a.dH_init[e] = g0 * acc;
+    }
+    if (a.dU_init) a.dU_init[e] = g0 * a.fin_xtdy[pair * dd + (int64_t)j * a.d + i];
+}
+
 template <class IO>
 static void launch_glue_t(const BackwardGlueArgs &a, int which, hipStream_t stream)
 {
@@ -298,8 +320,13 @@ static void launch_glue_t(const BackwardGlueArgs &a, int which, hipStream_t stre
         else hipLaunchKernelGGL((bwd_rule_scalar_kernel<64>), dim3(tb), dim3(256), 0, stream, a);
         break;
     }
-    default:
+    case 6:
         hipLaunchKernelGGL(bwd_rule_scan_kernel, dim3((unsigned)(a.n_tokens / a.T)), dim3(64), 0, stream, a);
+        break;
+    default: {
+        const int64_t n = (int64_t)a.n_pairs * a.d * a.d;
+        hipLaunchKernelGGL(bwd_init_grads_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, a);
+    }
     }
 }
 

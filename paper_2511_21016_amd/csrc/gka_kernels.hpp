@@ -92,8 +92,14 @@ struct BackwardGlueArgs {
                                   // nothing is reversed here, p_rev and vp_rev are plain conversions, and dxt_io, y_io,
                                   // hx_io, r1, r2, r3, r4 are float32
     const void *hk_io, *r5;       // H_t k_t; reversed pass sum_{j>=t} M[t,j] beta_j C_j k_j (k_j . k_t)
+    // gradients at the initial states (which = 7): the final states of three reverse readouts, each [pairs, d, d]
+    const float *H_init;          // the caller's initial H (the rule's term needs it)
+    const float *fin_px, *fin_xtdy, *fin_ck;   // sum p xhat^T, sum xt dy^T, sum (beta C k) k^T at token 0
+    float *dH_init, *dU_init;     // [pairs, d, d], each written if not nullptr
+    int n_pairs;
 };
-// which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan, 5 rule scalars (c_t), 6 rule scan (C_t)
+// which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan, 5 rule scalars (c_t), 6 rule scan (C_t),
+// 7 gradients at the initial states
 hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf16, hipStream_t stream);
 
 // Gated-linear-attention readout y_t = U_t q_t, U_t = gate_t U_{t-1} + beta_t v_t k_t^T with the state in registers
@@ -120,6 +126,9 @@ struct ReadoutArgs {
                                   // before had the same k, v, gate, beta, direction); 2: likewise, with k and v exchanged
                                   // (the transposed state; dk = dv only)
     bool reverse;
+    const float *init_state;      // [pairs, dv, dk] float32 or nullptr (zero): the state before the first token of the walk
+    bool init_transposed;         // init_state holds the transposed state, [pairs, dk, dv] (dk = dv only)
+    float *final_state;           // [pairs, dv, dk] float32 or nullptr: the state after the last token of the walk
 };
 hipError_t launch_gla_readout(const ReadoutArgs &a, int dk, int dv, hipStream_t stream);
 size_t gla_readout_workspace_bytes(int n_pairs, int n_segs, int dk, int dv);

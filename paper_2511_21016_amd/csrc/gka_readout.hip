@@ -135,6 +135,16 @@ __global__ __launch_bounds__(DV * 2)
     for (int jb = 0; jb < NBK; ++jb) {
         acc[jb] = zero16();
         if (!SUMMARY) {
+            if (a.init_state) {
+                // the caller's state before the first token of the walk (its first gate multiplies it), advanced over
+                // the earlier segments below like a zero state
+                const float *S0 = a.init_state + (int64_t)pair * DV * DK;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int row = 32 * w + n, col = 32 * jb + kidx(r, g);
+                    acc[jb][r] = a.init_transposed ? S0[(int64_t)col * DV + row] : S0[(int64_t)row * DK + col];
+                }
+            }
             for (int sg = 0; sg < seg; ++sg) {
                 const float decay = exp2f(a.seg_logdecay[pair * a.n_segs + sg]);
                 if (DK == DV && a.seg_mode == 2) {
@@ -417,6 +427,16 @@ __global__ __launch_bounds__(DV * 2)
         }
     }
 
+    if (!SUMMARY && a.final_state && seg == a.n_segs - 1) {
+        // the state after the last token of the walk, row-major [DV][DK]
+        float *S1 = a.final_state + (int64_t)pair * DV * DK;
+#pragma unroll
+        for (int jb = 0; jb < NBK; ++jb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *(f32x4 *)(S1 + (int64_t)(32 * w + n) * DK + 32 * jb + 8 * q4 + 4 * g) =
+                    f32x4{acc[jb][4 * q4], acc[jb][4 * q4 + 1], acc[jb][4 * q4 + 2], acc[jb][4 * q4 + 3]};
+    }
     if (SUMMARY) {
 #pragma unroll
         for (int jb = 0; jb < NBK; ++jb) {

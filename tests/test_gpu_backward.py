@@ -202,3 +202,62 @@ def test_backward_packed_sequences(dtype):
                          x["lam"][:, lo:hi], dy[:, lo:hi], w.n_iter)
     assert _rel(got["dk"][:, lo:hi], alone["dk"]) <= tol
     assert _rel(got["dgate"][:, lo + 1:hi], alone["dgate"][:, 1:]) <= tol
+
+
+@pytest.mark.parametrize("compute,rule,variants", [("f32", False, False), ("bf16", False, True), ("bf16", True, False),
+                                                   ("f32", True, True)])
+def test_backward_from_initial_states(compute, rule, variants):
+    """gka_backward_from_state: a sequence that continues from given H and U (bf16 tensors). Every gradient, the ones
+    at the two initial states included, against the backward oracle started from the same states; several segments
+    (gate_mean 6: the initial states weigh in hundreds of tokens). With float32 products in the solves (compute f32)
+    what is left is the readouts' arithmetic, which shows the logic more sharply than the bf16 tolerance."""
+    import torch
+    w = synth.CFG2.scaled(B=1, H=3, T=700, d=128, n_iter=6, gate_mean=6.0, seed=4321)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(77)
+    dy = synth.round_to_bf16(rng.standard_normal(x["v"].shape).astype(np.float32))
+    A = rng.standard_normal((w.B, w.H, w.d, 24)).astype(np.float32)
+    Hi = (np.einsum("bhik,bhjk->bhij", A, A) / 24).astype(np.float32)
+    Hi = (0.5 * (Hi + np.transpose(Hi, (0, 1, 3, 2)))).astype(np.float32)
+    Ui = (rng.standard_normal((w.B, w.H, w.d, w.d)) * 0.2).astype(np.float32)
+    kw, okw = {}, {}
+    if variants:
+        gates = synth.make_gates(w)
+        kw = dict(beta=to_device(gates["beta"], "f32"), alpha=to_device(gates["alpha"], "f32"))
+        okw = dict(beta=gates["beta"], alpha=gates["alpha"])
+    a = 0.05 if rule else 0.0
+    dev = upload_inputs(x, w.dtype)
+    cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
+    out = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], None if rule else dev["lam"],
+                               to_device(dy, "bf16"), w.n_iter, compute=cm, lambda_scale=a,
+                               H_init=to_device(Hi, "f32"), U_init=to_device(Ui, "f32"), return_state_grads=True, **kw)
+    torch.cuda.synchronize()
+    ref = bwd.backward(x["q"], x["k"], x["v"], x["gate"], None if rule else x["lam"], dy, w.n_iter, lambda_scale=a,
+                       H_init=Hi, U_init=Ui, **okw)
+    names = ["dq", "dk", "dv", "dgate"] + ([] if rule else ["dlam"]) + (["dbeta", "dalpha"] if variants else [])
+    errs = {n: _rel(to_host(out[n]), ref[n]) for n in names}
+    for n in ("dH_init", "dU_init"):
+        got, want = to_host(out[n]), ref[n]
+        errs[n] = float((np.abs(got - want).max(axis=(2, 3)) / np.abs(want).max(axis=(2, 3))).max())
+    print("from state", compute, rule, variants, errs)
+    assert max(errs.values()) <= TOL_BF16, errs
+    if compute == "f32":
+        assert max(errs[n] for n in ("dq", "dv", "dU_init")) <= 2e-3, errs
+
+
+def test_backward_from_state_argument_checks():
+    import torch
+    w = synth.CFG1.scaled(B=1, H=1, T=64, d=64)
+    x = synth.make_inputs(w)
+    dev = upload_inputs(x, w.dtype)
+    st = torch.zeros((1, 1, 64, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(binding.GkaError) as e:       # float32 tensors: not supported with states
+        binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], dev["v"], w.n_iter, H_init=st,
+                             U_init=st)
+    assert e.value.status == binding.GKA_ERR_UNSUPPORTED
+    w = synth.CFG2.scaled(B=1, H=1, T=64, d=64)
+    x = synth.make_inputs(w)
+    dev = upload_inputs(x, w.dtype)
+    with pytest.raises(binding.GkaError) as e:       # H_init without U_init
+        binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], dev["v"], w.n_iter, H_init=st)
+    assert e.value.status == binding.GKA_ERR_NULL
