@@ -8,10 +8,10 @@
 //      and, for bf16, what the rounding left over as a second operand),
 //   2. applies the chunk: S <- zeta_C S + sum_j (zeta_C / zeta_j) a_j k_j^T  (a = k for H, a = v for U),
 //      the decay weights built in log space (Appendix B.2), as one MFMA contraction over the chunk's tokens.
-// Two bodies implement the walk. The generic one (fp32 operands) stages the k rows and the slab's columns of a,
-// each scaled by the square root of the weight, through registers into padded LDS tiles. The bf16 one copies the k
-// rows from global memory straight into LDS two chunks ahead and puts the whole weight on the small a tile; see
-// state_pass_body_bf16.
+// Two bodies implement the walk. The generic one (fp32 operands, one workgroup per slab as above) stages the k rows
+// and the slab's columns of a, each scaled by the square root of the weight, through registers into padded LDS tiles.
+// The bf16 one owns all row blocks of a state in one workgroup, copies the k rows from global memory straight into
+// LDS one chunk ahead and puts the whole weight on the a tile; see state_pass_body_bf16_tile.
 //
 // The recurrence over chunks is an affine scan, S_[n+1] = zeta^(n) S_[n] + Delta_n. Long sequences are cut
 // into segments: a first launch reduces every segment to (prod zeta, Delta) from a zero state; a second launch
