@@ -136,7 +136,7 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
         pl->fused_seg_len = seg_len;
         pl->fused_n_segs = (pl->n_chunks + seg_len - 1) / seg_len;
         if ((int64_t)pl->n_pairs * pl->fused_n_segs > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
-        pl->fused_bytes = align_up(gka::fused_workspace_bytes(pl->n_pairs, pl->fused_n_segs), 256);
+        pl->fused_bytes = align_up(gka::fused_workspace_bytes(pl->n_pairs, pl->fused_n_segs, pl->split), 256);
         // (a caller that insists on the fused kernels needs no room for the two-phase kernels' chunk states)
         if (p->path == GKA_PATH_FUSED || pl->split || pl->fused_bytes > pl->total) pl->total = pl->fused_bytes;
     }
@@ -197,7 +197,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     if ((p->path == GKA_PATH_FUSED || pl.split) && !fused_ok) return GKA_ERR_UNSUPPORTED;
     if (pl.split && p->path == GKA_PATH_TWO_PHASE) return GKA_ERR_UNSUPPORTED;     // only the fused kernel splits
     if (fused_ok && p->path != GKA_PATH_TWO_PHASE) {
-        gka::FusedArgs fa;
+        gka::FusedArgs fa = {};
         fa.q = q; fa.k = k; fa.v = v; fa.gate = gate; fa.lambda = lambda; fa.o = o; fa.fro_out = fro_out;
         fa.H_init = H_init; fa.U_init = U_init; fa.H_final = H_final; fa.U_final = U_final;
         fa.h_init_lower_blocks = p->state_layout == GKA_STATE_H_LOWER_BLOCKS;
@@ -215,7 +215,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
         return GKA_OK;
     }
 
-    gka::StatePassArgs sa;
+    gka::StatePassArgs sa = {};
     sa.k = k; sa.v = v; sa.gate = gate; sa.beta = p->beta;
     sa.H_init = H_init; sa.U_init = U_init;
     sa.H_final = H_final; sa.U_final = U_final;
@@ -225,7 +225,7 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     sa.n_segs = pl.n_segs; sa.seg_len = pl.seg_len;
     sa.seg_buf = (float *)(ws + pl.off_seg); sa.seg_logdecay = (float *)(ws + pl.off_segdecay);
     sa.init_mode = 0; sa.final_mode = 0; sa.write_frags = 1;
-    gka::SolveArgs so;
+    gka::SolveArgs so = {};
     so.q = q; so.q_lo = q_lo; so.k = k; so.v = v; so.gate = gate; so.lambda = lambda; so.o = o; so.fro_out = fro_out;
     so.beta = p->beta; so.alpha = p->alpha; so.lambda_scale = p->lambda_scale;
     so.xhat_out = p->xhat_out;
@@ -367,7 +367,7 @@ gka_status decode_impl(const gka_params *p, int n_tokens, float *H_state, float 
     if (n_tokens <= 0) return GKA_ERR_SHAPE;
     if (!H_state || !U_state || !q || !k || !v || !gate || !o) return GKA_ERR_NULL;
     if (!lambda && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;
-    gka::DecodeArgs da;
+    gka::DecodeArgs da = {};
     da.H_state = H_state; da.U_state = U_state;
     da.q = q; da.k = k; da.v = v; da.gate = gate; da.lambda = lambda; da.o = o;
     da.beta = p->beta; da.alpha = p->alpha; da.lambda_scale = p->lambda_scale;
@@ -539,7 +539,7 @@ gka_status gka_backward_from_state(const gka_params *p, const void *q, const voi
                        int seg_mode = 0, float *out_f32 = nullptr, const void *q_lo = nullptr,
                        const void *k_lo = nullptr, const void *v_lo = nullptr, const float *init = nullptr,
                        bool init_transposed = false, float *fin = nullptr) {
-        gka::ReadoutArgs r;
+        gka::ReadoutArgs r = {};                     // (optional pointers default to nullptr)
         r.init_state = init; r.init_transposed = init_transposed; r.final_state = fin;
         r.q = qq; r.q_lo = q_lo; r.k_lo = k_lo; r.v_lo = v_lo; r.q_is_f32 = false; r.k = kk; r.v = vv; r.o = out;
         r.o_f32 = out_f32;
@@ -694,7 +694,7 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
     st = forward_impl(&inner, sa.qs, sa.ks, sa.ks, gate, lambda, ws + sp.off_scratch, nullptr, nullptr, nullptr, nullptr,
                       nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr, false, true);
     if (st != GKA_OK) return st;
-    gka::ReadoutArgs r;
+    gka::ReadoutArgs r = {};                     // (optional pointers default to nullptr)
     r.k_lo = nullptr; r.v_lo = nullptr;
     r.v = v; r.o = o; r.o_f32 = nullptr; r.gate = gate; r.beta = p->beta;
     r.stride_h = p->d_v; r.stride_t = (int64_t)p->H * p->d_v; r.stride_b = (int64_t)p->T * p->H * p->d_v;
