@@ -161,14 +161,13 @@ gka_status gka_forward(const gka_params *p,
 /* gka_forward for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc. The same arguments as gka_forward without the
  * workspace, the same kernels and the same results; the scratch that the kernels need (segment summaries of the chunk
- * walk and the parked states, 196,612 bytes per workgroup; 262,148 with GKA_COMPUTE_BF16_SPLIT) lives in an array of
- * GKA_STATIC_SCRATCH_BYTES
+ * walk and the parked states, 196,612 bytes per workgroup) lives in an array of GKA_STATIC_SCRATCH_BYTES
  * that the library's code object reserves on every GPU it is loaded on, until the process ends. The call allocates
  * and frees nothing, on the device or through any library.
  *   Supported: what the fused kernels cover (see gka_path: GKA_BF16 tensors, GKA_COMPUTE_BF16, d = 128, lambda given,
  *   no beta / alpha / xhat_out, GKA_PHASE_ALL, path not GKA_PATH_TWO_PHASE), else GKA_ERR_UNSUPPORTED.
  *   Size limit: (number of (batch, head) pairs) x (segments of the chunk walk) x 196,612 bytes (+ padding) must not
- *   exceed GKA_STATIC_SCRATCH_BYTES: at most 341 workgroups (255 with GKA_COMPUTE_BF16_SPLIT). The library cuts the walk into ceil(256 / (B H))
+ *   exceed GKA_STATIC_SCRATCH_BYTES: at most 341 workgroups. The library cuts the walk into ceil(256 / (B H))
  *   segments (fewer for short sequences); p->walk_chunks >= ceil(T / 64) asks for a single segment, with which any
  *   B H <= 341 fits. Larger: GKA_ERR_STATIC_SCRATCH, nothing is launched.
  *   Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race and

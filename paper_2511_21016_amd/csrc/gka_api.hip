@@ -136,7 +136,7 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
         pl->fused_seg_len = seg_len;
         pl->fused_n_segs = (pl->n_chunks + seg_len - 1) / seg_len;
         if ((int64_t)pl->n_pairs * pl->fused_n_segs > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
-        pl->fused_bytes = align_up(gka::fused_workspace_bytes(pl->n_pairs, pl->fused_n_segs, pl->split), 256);
+        pl->fused_bytes = align_up(gka::fused_workspace_bytes(pl->n_pairs, pl->fused_n_segs), 256);
         // (a caller that insists on the fused kernels needs no room for the two-phase kernels' chunk states)
         if (p->path == GKA_PATH_FUSED || pl->split || pl->fused_bytes > pl->total) pl->total = pl->fused_bytes;
     }

@@ -129,8 +129,6 @@ __device__ __forceinline__ void refresh_lane(Ctx &c)
     c.kg = lane_now >> 4;
     c.park = (f32x4 *)c.a.park + ((int64_t)blockIdx.x * 8 + c.w) * (8 * 64) + lane_now;
 }
-// (SPLIT variant) the same for H, in a second array of blocks behind the first
-__device__ __forceinline__ f32x4 *park_of_H(const Ctx &c) { return c.park + (int64_t)gridDim.x * 8 * (8 * 64); }
 
 __device__ __forceinline__ bf16x8 *lds_frags(const Ctx &c, int off) { return (bf16x8 *)(c.smem + off); }
 __device__ __forceinline__ uint16_t *lds_rows(const Ctx &c, int g) { return (uint16_t *)(c.smem + kOffR + g * 16384); }
@@ -389,9 +387,6 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
         const float cm = omega - 1.0f, ncs = -omega * s0, ncl = ncs * lam;
         bf16x8 pm[NJB], pmR[SPLIT ? NJB : 1];
         f32x4 s = zero4(), sprev = zero4();
-        // SPLIT: one solver wave per SIMD, so consecutive products alternate between two accumulators (a product that
-        // continues the accumulator of the one before it waits for its result)
-        f32x4 s2 = zero4(), g2 = zero4();
         f32x4 tcm;
         auto mask_products = [&](auto jbc) {
             constexpr int jb = decltype(jbc)::value;
@@ -423,13 +418,12 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
                 constexpr int t = i / PER_TILE, u = i % PER_TILE;
                 if constexpr (u < 4) {
                     s = mma16(a, dB[u], u == 0 ? zero4() : s);
-                    if constexpr (SPLIT) s2 = mma16(a, dR[u], u == 0 ? zero4() : s2);
+                    if constexpr (SPLIT) s = mma16(a, dR[u], s);
                 } else if constexpr (u < HP) {
-                    if constexpr (u % 2 == 0) s = mma16(a, dB[u - 4], s);
-                    else s2 = mma16(a, dB[u - 4], s2);
+                    s = mma16(a, dB[u - 4], s);
                 } else {
                     gn[t] = mma16(a, pm[u - HP], gn[t]);
-                    if constexpr (SPLIT) g2 = mma16(a, pmR[u - HP], u == HP ? zero4() : g2);
+                    if constexpr (SPLIT) gn[t] = mma16(a, pmR[u - HP], gn[t]);
                 }
             } else {
                 constexpr int fb = (i - NT) / NJ, js = (i - NT) % NJ;
@@ -444,17 +438,11 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
                 constexpr int t = i / PER_TILE, u = i % PER_TILE;
                 if constexpr (t == 0 && u == 2) mask_products(std::integral_constant<int, 0>{});
                 if constexpr (t == 0 && u == 3 && NJB == 2) mask_products(std::integral_constant<int, NJB - 1>{});
-                if constexpr (u == PER_TILE - 1) {
-                    if constexpr (SPLIT) sprev = s + s2;
-                    else sprev = s;
-                }
+                if constexpr (u == PER_TILE - 1) sprev = s;
                 if constexpr (t >= 1) {
                     typedef std::integral_constant<int, t - 1> FT;
                     if constexpr (u == 0) { upd_a(FT{}, R0{}); upd_a(FT{}, R1{}); }
-                    if constexpr (u == 1) {
-                        upd_a(FT{}, R2{}); upd_a(FT{}, R3{});
-                        if constexpr (SPLIT) gn[t - 1] += g2;      // (the previous tile's second intra accumulator)
-                    }
+                    if constexpr (u == 1) { upd_a(FT{}, R2{}); upd_a(FT{}, R3{}); }
                     if constexpr (u == 2) { upd_b(FT{}, R0{}, sprev); upd_b(FT{}, R1{}, sprev); }
                     if constexpr (u == 3) { upd_b(FT{}, R2{}, sprev); upd_b(FT{}, R3{}, sprev); }
                 }
@@ -463,12 +451,11 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
                 constexpr int k = i - NT;
                 typedef std::integral_constant<int, 7> FT;
                 if constexpr (k == 0) {
-                    if constexpr (SPLIT) gn[7] += g2;
                     upd_a(FT{}, R0{}); upd_a(FT{}, R1{}); upd_a(FT{}, R2{}); upd_a(FT{}, R3{});
                     pack_delta(std::integral_constant<int, 1>{});
                 }
                 if constexpr (k == NJ) {
-                    upd_b(FT{}, R0{}, sprev); upd_b(FT{}, R1{}, sprev); upd_b(FT{}, R2{}, sprev); upd_b(FT{}, R3{}, sprev);
+                    upd_b(FT{}, R0{}, s); upd_b(FT{}, R1{}, s); upd_b(FT{}, R2{}, s); upd_b(FT{}, R3{}, s);
                     pack_delta(std::integral_constant<int, 2>{});
                 }
                 if constexpr (k == 2 * NJ) pack_delta(std::integral_constant<int, 3>{});
@@ -794,8 +781,6 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         load_start_state(c, accH, accU, pair, seg);
         park_store(c.park, accU);
     }
-    // SPLIT: the passes need the registers of H as well; it is parked from its update to the next chunk's start
-    if constexpr (SPLIT) park_store(park_of_H(c), accH);
     copy_rows(c, a.k, 0, chunk_begin);
     if constexpr (!SPLIT) copy_rows(c, a.k, 1, chunk_begin + 1);
     float *sTab = (float *)(smem + kOffTab);
@@ -809,7 +794,6 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         // Addresses are formed anew in every iteration from a copy of the lane index that the compiler cannot trace
         // back: hoisted out of the loop they would occupy registers across the passes (or be spilled and reloaded).
         refresh_lane(c);
-        if constexpr (SPLIT) park_load(park_of_H(c), accH);
         // ---- 1
         // gates of the chunks (fetched during the previous iteration): lane j holds G_j, the weight of token j in the
         // chunk's update 2^(G_C - G_j), and the chunk's decay
@@ -861,7 +845,6 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         lds_barrier();
         // ---- 3
         advance_state(c, accH, 0, zetaA, wBA);
-        if constexpr (SPLIT) park_store(park_of_H(c), accH);
         float hnB = 0.0f;
         if constexpr (!SPLIT) {
             hnB = publish_H<false>(c, accH, 1);
@@ -938,7 +921,6 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         float *Uf = a.U_final + (int64_t)pair * kD * kD;
         f32x4 accU[8];
         park_load(c.park, accU);
-        if constexpr (SPLIT) park_load(park_of_H(c), accH);
 #pragma unroll
         for (int jt = 0; jt < 8; ++jt) {
             *(f32x4 *)(Hf + (int64_t)(16 * c.w + c.n) * kD + 16 * jt + 4 * c.kg) = accH[jt];
@@ -1050,13 +1032,12 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
     if (c.tid == 0) a.seg_logdecay[pair * a.n_segs + seg] = Gseg;
 }
 
-size_t fused_workspace_bytes(int n_pairs, int n_segs, bool split)
+size_t fused_workspace_bytes(int n_pairs, int n_segs)
 {
     // per (pair, segment): Delta H, Delta U in the kernels' tile order, the segment's log2 decay, and the scratch
-    // block that holds U between its uses (split: a second one for H)
+    // block that holds U between its uses
     const size_t n = (size_t)n_pairs * n_segs;
-    return n * (2 * kD * kD * sizeof(float)) + ((n * sizeof(float) + 255) / 256) * 256 +
-           n * (kD * kD * sizeof(float)) * (split ? 2 : 1);
+    return n * (2 * kD * kD * sizeof(float)) + ((n * sizeof(float) + 255) / 256) * 256 + n * (kD * kD * sizeof(float));
 }
 
 hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_t stream, int which, bool split)

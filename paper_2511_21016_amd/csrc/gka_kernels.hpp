@@ -170,7 +170,7 @@ struct FusedArgs {
     int n_segs, seg_len;          // segments of the chunk walk per pair (one workgroup each), chunks per segment
     float *seg_buf, *seg_logdecay, *park; // set by the launcher (carved from the workspace)
 };
-size_t fused_workspace_bytes(int n_pairs, int n_segs, bool split);
+size_t fused_workspace_bytes(int n_pairs, int n_segs);
 // which: bit 0 the summary launch (segment summaries for the start states), bit 1 the chunk walk itself
 // which: bit 0 the summary launch, bit 1 the chunk walk; split: H_[n] and delta as bf16 value + remainder
 hipError_t launch_fused_forward(const FusedArgs &a, void *workspace, hipStream_t stream, int which, bool split);
