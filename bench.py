@@ -22,7 +22,7 @@ N_INPUT_SETS = 3                   # rotated so that the 256 MiB of q,k,v,o do n
 # An idle GPU needs tens of milliseconds of work before its clocks settle; a step is a third of a millisecond. These
 # untimed forward passes run before the W warm-up steps whatever W is (reported as "clock_ramp_steps").
 CLOCK_RAMP_STEPS = 300
-FUSED_KERNEL = "gka::fused_forward_kernel<false>(gka::FusedArgs)"
+FUSED_KERNEL = "gka::fused_forward_kernel<false, false>(gka::FusedArgs)"
 
 
 def committed_traffic(kernel):

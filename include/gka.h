@@ -83,8 +83,9 @@ typedef enum { GKA_STATE_FULL = 0, GKA_STATE_H_LOWER_BLOCKS = 1 } gka_state_layo
  * GKA_PATH_TWO_PHASE: chunk initial states H_[n], U_[n] of Section 4.2.1 are computed and stored in the workspace
  *                     first, then every chunk is solved independently (all dtypes, head dimensions and variants).
  * GKA_PATH_FUSED    : one kernel walks the chunks of a pair in order with H and U in registers, so that no chunk state
- *                     crosses HBM. Available for GKA_BF16 tensors with GKA_COMPUTE_BF16 (or _SPLIT), d = 128, Eq. (CH) as printed
- *                     (lambda given, no beta / alpha / xhat_out), GKA_PHASE_ALL; GKA_ERR_UNSUPPORTED otherwise. */
+ *                     crosses HBM. Available for GKA_BF16 tensors with GKA_COMPUTE_BF16 (or _SPLIT), d = 128, with or without
+ *                     the layer's variants (beta, alpha, the rule for lambda) but without xhat_out, GKA_PHASE_ALL;
+ *                     GKA_ERR_UNSUPPORTED otherwise. */
 typedef enum { GKA_PATH_AUTO = 0, GKA_PATH_TWO_PHASE = 1, GKA_PATH_FUSED = 2 } gka_path;
 
 typedef struct {
@@ -164,8 +165,8 @@ gka_status gka_forward(const gka_params *p,
  * walk and the parked states, 196,612 bytes per workgroup) lives in an array of GKA_STATIC_SCRATCH_BYTES
  * that the library's code object reserves on every GPU it is loaded on, until the process ends. The call allocates
  * and frees nothing, on the device or through any library.
- *   Supported: what the fused kernels cover (see gka_path: GKA_BF16 tensors, GKA_COMPUTE_BF16, d = 128, lambda given,
- *   no beta / alpha / xhat_out, GKA_PHASE_ALL, path not GKA_PATH_TWO_PHASE), else GKA_ERR_UNSUPPORTED.
+ *   Supported: what the fused kernels cover (see gka_path: GKA_BF16 tensors, GKA_COMPUTE_BF16 or _SPLIT, d = 128, no
+ *   xhat_out, GKA_PHASE_ALL, path not GKA_PATH_TWO_PHASE), else GKA_ERR_UNSUPPORTED.
  *   Size limit: (number of (batch, head) pairs) x (segments of the chunk walk) x 196,612 bytes (+ padding) must not
  *   exceed GKA_STATIC_SCRATCH_BYTES: at most 341 workgroups. The library cuts the walk into ceil(256 / (B H))
  *   segments (fewer for short sequences); p->walk_chunks >= ceil(T / 64) asks for a single segment, with which any

@@ -192,13 +192,13 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     hipStream_t stream = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
 
-    const bool fused_ok = pl.fused_shape && !p->beta && !p->alpha && lambda && !p->xhat_out && !solve_only &&
-                          !q_lo && p->phase == GKA_PHASE_ALL;
+    const bool fused_ok = pl.fused_shape && !p->xhat_out && !solve_only && !q_lo && p->phase == GKA_PHASE_ALL;
     if ((p->path == GKA_PATH_FUSED || pl.split) && !fused_ok) return GKA_ERR_UNSUPPORTED;
     if (pl.split && p->path == GKA_PATH_TWO_PHASE) return GKA_ERR_UNSUPPORTED;     // only the fused kernel splits
     if (fused_ok && p->path != GKA_PATH_TWO_PHASE) {
         gka::FusedArgs fa = {};
         fa.q = q; fa.k = k; fa.v = v; fa.gate = gate; fa.lambda = lambda; fa.o = o; fa.fro_out = fro_out;
+        fa.beta = p->beta; fa.alpha = p->alpha; fa.lambda_scale = p->lambda_scale;
         fa.H_init = H_init; fa.U_init = U_init; fa.H_final = H_final; fa.U_final = U_final;
         fa.h_init_lower_blocks = p->state_layout == GKA_STATE_H_LOWER_BLOCKS;
         fa.stride_b = pl.stride_b; fa.stride_t = pl.stride_t; fa.stride_h = pl.stride_h;

@@ -245,6 +245,7 @@ struct Solver {
     f32x4 mreg[4];                   // decay mask M[j][c], key block js: rows j = 16 js + 4 kg + r
     f32x4 yi[8];                     // intra-chunk part of the readout
     float zeta, fro;
+    float beta;                      // write gate of this lane's token (1 without the variant)
     int tok;                         // this lane's token (global index)
     bool valid;
 };
@@ -470,20 +471,26 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
 }
 
 // Decay mask of Section 4.2.1 in the log-space form of Appendix B.2 (base 2): M[j][c] = 2^(G_c - G_j) for j <= c.
-// (Gtab: G_j of the chunk's 64 tokens, a slot of this wave's table.)
-__device__ __forceinline__ void build_mask(const Ctx &c, Solver &s, const float *Gtab, int ts)
+// (Gtab: G_j of the chunk's 64 tokens, a slot of this wave's table.) With the write gate of the Remark in Section 4.1,
+// H_c = zeta_c H_[n] + sum_{j<=c} M[j,c] beta_j k_j k_j^T (the same for U): beta_j is folded into the mask,
+// m[j,c] = M[j,c] beta_j, which every product uses (Btab: beta_j of the chunk's tokens).
+template <bool GATED>
+__device__ __forceinline__ void build_mask(const Ctx &c, Solver &s, const float *Gtab, const float *Btab, int ts)
 {
     const int c_local = 16 * ts + c.n;
     const float Gc = Gtab[c_local];
     s.zeta = exp2f(Gc);
+    s.beta = GATED ? Btab[c_local] : 1.0f;
 #pragma unroll
     for (int js = 0; js < 4; ++js) {
         const f32x4 Gj = *(const f32x4 *)(Gtab + 16 * js + 4 * c.kg);
+        f32x4 bj = {1.0f, 1.0f, 1.0f, 1.0f};
+        if constexpr (GATED) bj = *(const f32x4 *)(Btab + 16 * js + 4 * c.kg);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int j = 16 * js + 4 * c.kg + r;
             // hardware exp2: results below the normal range (decays under 2^-126) are flushed to zero
-            s.mreg[js][r] = (j <= c_local) ? __builtin_amdgcn_exp2f(Gc - Gj[r]) : 0.0f;
+            s.mreg[js][r] = (j <= c_local) ? __builtin_amdgcn_exp2f(Gc - Gj[r]) * bj[r] : 0.0f;
         }
     }
 }
@@ -491,7 +498,9 @@ __device__ __forceinline__ void build_mask(const Ctx &c, Solver &s, const float 
 // Chunk-wise Frobenius norm, first half: w_j of this wave's tokens to the table.
 //   ||H_c||^2 = zeta_c^2 ||H_[n]||^2 + sum_{j<=c} M[j,c]^2 w_j,  w_j = 2 (zeta_j k_j^T H_[n] k_j + sum_{i<j} M[i,j] G_ij^2) + G_jj^2
 // (G = K K^T): the three-term expansion of Section 4.2.1 with its double sum folded by M[i,c] M[j,c] = M[j,c]^2 M[i,j].
-template <int NJ>
+// With the write gate (mask m = M beta): w_j = 2 (zeta_j k_j^T H_[n] k_j + sum_{i<j} m[i,j] G_ij^2) / beta_j + G_jj^2,
+// and w_j = 0 for beta_j = 0 (its column of m vanishes).
+template <int NJ, bool GATED>
 __device__ __forceinline__ void frobenius_terms(const Ctx &c, const Solver &s, int g, int ts)
 {
     const bf16x8 *sH = lds_frags(c, kOffH + g * 32768) + c.lane;
@@ -527,12 +536,20 @@ __device__ __forceinline__ void frobenius_terms(const Ctx &c, const Solver &s, i
             b_part += s.mreg[js][r] * (G[js][r] * G[js][r]);
             if (js == ts && 4 * c.kg + r == c.n) d_part = G[js][r] * G[js][r];
         }
-    b_part -= d_part;                 // the sum runs over i < c: the diagonal term (M[c][c] = 1) is taken out again
     a_part = sum_over_kg(a_part);
     b_part = sum_over_kg(b_part);
     d_part = sum_over_kg(d_part);
+    // the sum runs over i < c: the diagonal term (m[c][c] = beta_c) is taken out again
+    float w;
+    if constexpr (GATED) {
+        b_part -= s.beta * d_part;
+        w = s.beta > 0.0f ? 2.0f * (s.zeta * a_part + b_part) / s.beta + d_part : 0.0f;
+    } else {
+        b_part -= d_part;
+        w = 2.0f * (s.zeta * a_part + b_part) + d_part;
+    }
     float *sW = (float *)(c.smem + kOffTab) + g * 64;
-    if (c.kg == 0) sW[16 * ts + c.n] = 2.0f * (s.zeta * a_part + b_part) + d_part;
+    if (c.kg == 0) sW[16 * ts + c.n] = w;
 }
 
 // second half: ||H_c||_F of this lane's token
@@ -559,7 +576,7 @@ __device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, in
 
 // Everything between the Frobenius table and the published result: the passes, then (after the workgroup has
 // passed the barrier inside) xhat to LDS and the intra-chunk part of the readout.
-template <int NJ, bool SPLIT>
+template <int NJ, bool SPLIT, bool GATED>
 __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, const typename IOBF16::raw4 (&qraw)[8],
                                              float lam, f32x4 (&accU)[8], int c0)
 {
@@ -591,6 +608,21 @@ __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, c
     refresh_lane(c);
 #pragma unroll
     for (int ft = 0; ft < 8; ++ft) xi[ft] += dl[ft];
+    if constexpr (GATED) {
+        // alpha-connection (Section 4.3): the readout is applied to alpha xhat + (1 - alpha) q; q is read again (it
+        // was not kept through the passes)
+        if (c.a.alpha) {
+            const int tokc = min(s.tok, c.a.T - 1);
+            const float al = s.valid ? c.a.alpha[c.gate_base + (int64_t)tokc * c.a.H] : 1.0f;
+            const int64_t tok_off = c.base_bh + (int64_t)tokc * c.a.stride_t;
+#pragma unroll
+            for (int ft = 0; ft < 8; ++ft) {
+                const f32x4 qv = IOBF16::load4(c.a.q, tok_off + 16 * ft + 4 * c.kg);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) xi[ft][r] = al * xi[ft][r] + (1.0f - al) * (s.valid ? qv[r] : 0.0f);
+            }
+        }
+    }
 
     // ---- readout, intra-chunk part: sum_{j<=c} M[j,c] v_j (k_j . xhat_c), xhat as value + remainder
     bf16x8 x[2][4];
@@ -748,7 +780,9 @@ __device__ __forceinline__ void load_start_state(const Ctx &c, f32x4 (&accH)[8],
 //   7. solver A stores; state part of the readout for B (over A's xhat), U advanced over B and parked
 //   8. solver B stores; copies of the next k rows into the row tiles start
 // SPLIT: the same with chunk A alone (everything that concerns B drops out, phase 8 joins phase 7).
-template <bool SPLIT>
+// GATED: the layer's variants (write gate beta, alpha-connection, the rule lambda_t = a ||H_t||_F), a compile-time
+// flag so that the plain kernel carries none of their loads, registers or branches.
+template <bool SPLIT, bool GATED>
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_forward_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -789,6 +823,17 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
     float gmA = a.gate[c.gate_base + (int64_t)min(chunk_begin * kChunk + c.lane, a.T - 1) * a.H];
     float gmB = 1.0f;
     if constexpr (!SPLIT) gmB = a.gate[c.gate_base + (int64_t)min((chunk_begin + 1) * kChunk + c.lane, a.T - 1) * a.H];
+    // write gates of the chunks' tokens (lane j: token j), fetched with the gates
+    float bmA = 1.0f, bmB = 1.0f;
+    auto fetch_beta = [&](int chunk0) {
+        if constexpr (GATED) {
+            if (a.beta) {
+                bmA = a.beta[c.gate_base + (int64_t)min(chunk0 * kChunk + c.lane, a.T - 1) * a.H];
+                if constexpr (!SPLIT) bmB = a.beta[c.gate_base + (int64_t)min((chunk0 + 1) * kChunk + c.lane, a.T - 1) * a.H];
+            }
+        }
+    };
+    fetch_beta(chunk_begin);
 #pragma unroll 1
     for (int c0 = chunk_begin; c0 < chunk_end; c0 += kChunksPerIter) {
         // Addresses are formed anew in every iteration from a copy of the lane index that the compiler cannot trace
@@ -802,13 +847,13 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             const bool vA = c0 * kChunk + c.lane < c.T_eff;
             GA = wave_inclusive_scan(vA ? log2_gate(gmA) : 0.0f, c.lane);
             const float GtA = lane_value(GA, 63);
-            wjA = vA ? exp2f(GtA - GA) : 0.0f;
+            wjA = vA ? exp2f(GtA - GA) * bmA : 0.0f;
             zetaA = exp2f(GtA);
             if constexpr (!SPLIT) {
                 const bool vB = (c0 + 1) * kChunk + c.lane < c.T_eff;
                 GB = wave_inclusive_scan(vB ? log2_gate(gmB) : 0.0f, c.lane);
                 const float GtB = lane_value(GB, 63);
-                wjB = vB ? exp2f(GtB - GB) : 0.0f;
+                wjB = vB ? exp2f(GtB - GB) * bmB : 0.0f;
                 zetaB = exp2f(GtB);
             }
         };
@@ -823,6 +868,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         wave_table(c, kTabBefore, 0)[c.lane] = wjA;
         wave_table(c, kTabBefore, 2)[c.lane] = grp ? GB : GA;
         if constexpr (!SPLIT) wave_table(c, kTabBefore, 1)[c.lane] = wjB;
+        if constexpr (GATED) wave_table(c, kTabBefore, 3)[c.lane] = grp ? bmB : bmA;
         const float hnA = publish_H<SPLIT>(c, accH, 0);
         build_key_frags<SPLIT>(c);
         bf16x8 wBA[2], wBB[2];
@@ -839,8 +885,8 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         if (solver) {                    // (wave-uniform)
 #pragma unroll
             for (int ft = 0; ft < 8; ++ft) qraw[ft] = IOBF16::load_raw4(a.q, tok_off + 16 * ft + 4 * c.kg);
-            lam = a.lambda[c.gate_base + (int64_t)min(s.tok, a.T - 1) * a.H];
-            build_mask(c, s, wave_table(c, kTabBefore, 2), ts);
+            if (!GATED || a.lambda) lam = a.lambda[c.gate_base + (int64_t)min(s.tok, a.T - 1) * a.H];
+            build_mask<GATED>(c, s, wave_table(c, kTabBefore, 2), wave_table(c, kTabBefore, 3), ts);
         }
         lds_barrier();
         // ---- 3
@@ -857,20 +903,23 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         lds_barrier();
         // ---- 4
         if (solver) {
-            if (wide) frobenius_terms<4>(c, s, grp, ts);
-            else frobenius_terms<2>(c, s, grp, ts);
+            if (wide) frobenius_terms<4, GATED>(c, s, grp, ts);
+            else frobenius_terms<2, GATED>(c, s, grp, ts);
         }
         lds_barrier();
         // ---- 5
         if (solver) {
             s.fro = wide ? frobenius_norm<4>(c, s, grp) : frobenius_norm<2>(c, s, grp);
             if (a.fro_out && s.valid && c.kg == 0) a.fro_out[c.gate_base + (int64_t)s.tok * a.H] = s.fro;
+            if constexpr (GATED) {
+                if (!a.lambda) lam = a.lambda_scale * s.fro;       // the rule of Section 4.1
+            }
             if (!s.valid) lam = 1.0f;
         }
         lds_barrier();                   // the table is dead: the row tiles may be overwritten
         if (solver) {
-            if (wide) solve_tokens<4, SPLIT>(c, s, grp, ts, qraw, lam, accU, c0);
-            else solve_tokens<2, SPLIT>(c, s, grp, ts, qraw, lam, accU, c0);
+            if (wide) solve_tokens<4, SPLIT, GATED>(c, s, grp, ts, qraw, lam, accU, c0);
+            else solve_tokens<2, SPLIT, GATED>(c, s, grp, ts, qraw, lam, accU, c0);
         } else {
             // (SPLIT, waves 4-7) this wave's share of the copies of the v rows, the barrier that the solver waves pass
             // after their passes, and U back from its parking place
@@ -894,6 +943,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         // gates of the next chunks
         gmA = a.gate[c.gate_base + (int64_t)min((c0 + kChunksPerIter) * kChunk + c.lane, a.T - 1) * a.H];
         if constexpr (!SPLIT) gmB = a.gate[c.gate_base + (int64_t)min((c0 + 3) * kChunk + c.lane, a.T - 1) * a.H];
+        fetch_beta(c0 + kChunksPerIter);
         readout_state(c, accU, 0, kOffK);
         advance_state(c, accU, 0, zetaA, wVA);
         lds_barrier();
@@ -960,7 +1010,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
     }
     // piece i of a thread: tile (g = i / 4, which = (i / 2) % 2), 16 bytes of row (i % 2) * 32 + tid / 16
     u32x4 regs[8];                       // (a native vector type: arrays of HIP's uint4 struct stay in memory)
-    float gm[2];
+    float gm[2], bm[2];                  // gates and write gates (1 if none) of the two chunks, lane j: token j
     auto fetch = [&](int c0) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -971,7 +1021,11 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             regs[i] = *(const u32x4 *)(x + c.base_bh + (int64_t)tok * a.stride_t + 8 * piece);
         }
 #pragma unroll
-        for (int g = 0; g < 2; ++g) gm[g] = a.gate[c.gate_base + (int64_t)min((c0 + g) * kChunk + c.lane, a.T - 1) * a.H];
+        for (int g = 0; g < 2; ++g) {
+            const int64_t at = c.gate_base + (int64_t)min((c0 + g) * kChunk + c.lane, a.T - 1) * a.H;
+            gm[g] = a.gate[at];
+            bm[g] = a.beta ? a.beta[at] : 1.0f;      // (uniform branch)
+        }
     };
     float Gseg = 0.0f;
     fetch(chunk_begin);
@@ -986,7 +1040,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             const int row = (i & 1) * 32 + (c.tid >> 4), piece = c.tid & 15;
             *(u32x4 *)((uint16_t *)(tiles + (i >> 1) * kSummaryTile) + at(row, 8 * piece)) = regs[i];
         }
-        const float gm0 = gm[0], gm1 = gm[1];
+        const float gm0 = gm[0], gm1 = gm[1], bm0 = bm[0], bm1 = bm[1];
         lds_barrier();                   // the tiles are complete; the other buffer's readers are done
         fetch(c0 + 2);                   // (past the end of the segment: harmless reads of rows that exist)
         // (the scheduler must not sink these loads to where their data is stored, one iteration later)
@@ -997,7 +1051,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             const float G = wave_inclusive_scan(valid ? log2_gate(g ? gm1 : gm0) : 0.0f, c.lane);
             const float Gtot = lane_value(G, 63);
             Gseg += Gtot;
-            const float wj = valid ? exp2f(Gtot - G) : 0.0f;
+            const float wj = valid ? exp2f(Gtot - G) * (g ? bm1 : bm0) : 0.0f;
             const float zetaC = exp2f(Gtot);
             const uint16_t *rowsK = (const uint16_t *)(tiles + (2 * g + 0) * kSummaryTile);
             const uint16_t *rowsV = (const uint16_t *)(tiles + (2 * g + 1) * kSummaryTile);
@@ -1055,12 +1109,15 @@ hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_
     bool unused = false;
     bool &attr_set = (dev >= 0 && dev < 64) ? attr_set_on[dev] : unused;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)fused_forward_kernel<false>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void *)fused_forward_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kLdsBytes);
-        if (e != hipSuccess) return e;
+        const void *walks[4] = {(const void *)fused_forward_kernel<false, false>,
+                                (const void *)fused_forward_kernel<false, true>,
+                                (const void *)fused_forward_kernel<true, false>,
+                                (const void *)fused_forward_kernel<true, true>};
+        hipError_t e = hipSuccess;
+        for (const void *f : walks) {
+            e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+            if (e != hipSuccess) return e;
+        }
         e = hipFuncSetAttribute((const void *)fused_summary_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kSummaryLds);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -1073,8 +1130,12 @@ hipError_t launch_fused_forward(const FusedArgs &a0, void *workspace, hipStream_
     }
     if (which & 2) {
         const dim3 grid((unsigned)(a.n_pairs * a.n_segs));
-        if (split) hipLaunchKernelGGL(fused_forward_kernel<true>, grid, dim3(kFusedThreads), kLdsBytes, stream, a);
-        else hipLaunchKernelGGL(fused_forward_kernel<false>, grid, dim3(kFusedThreads), kLdsBytes, stream, a);
+        const bool gated = a.beta || a.alpha || !a.lambda;
+        const dim3 block(kFusedThreads);
+        if (split && gated) hipLaunchKernelGGL((fused_forward_kernel<true, true>), grid, block, kLdsBytes, stream, a);
+        else if (split) hipLaunchKernelGGL((fused_forward_kernel<true, false>), grid, block, kLdsBytes, stream, a);
+        else if (gated) hipLaunchKernelGGL((fused_forward_kernel<false, true>), grid, block, kLdsBytes, stream, a);
+        else hipLaunchKernelGGL((fused_forward_kernel<false, false>), grid, block, kLdsBytes, stream, a);
     }
     return hipGetLastError();
 }

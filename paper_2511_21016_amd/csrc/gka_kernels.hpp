@@ -158,7 +158,9 @@ hipError_t launch_decode_step(const DecodeArgs &a, int n_pairs, int d, bool io_b
 // Forward pass in one kernel with the states in registers (bf16 tensors and operands, d = 128, Eq. (CH) as printed).
 struct FusedArgs {
     const void *q, *k, *v;
-    const float *gate, *lambda;   // [B,T,H]
+    const float *gate, *lambda;   // [B,T,H]; lambda nullptr: lambda_t = lambda_scale ||H_t||_F
+    const float *beta, *alpha;    // [B,T,H] write gate / alpha-connection, each nullptr (= 1)
+    float lambda_scale;
     void *o;
     float *fro_out;               // [B,T,H] or nullptr
     const float *H_init, *U_init; // [pairs,d,d] or nullptr
@@ -171,8 +173,9 @@ struct FusedArgs {
     float *seg_buf, *seg_logdecay, *park; // set by the launcher (carved from the workspace)
 };
 size_t fused_workspace_bytes(int n_pairs, int n_segs);
-// which: bit 0 the summary launch (segment summaries for the start states), bit 1 the chunk walk itself
-// which: bit 0 the summary launch, bit 1 the chunk walk; split: H_[n] and delta as bf16 value + remainder
+// which: bit 0 the summary launch (segment summaries for the start states), bit 1 the chunk walk; split: H_[n], delta
+// and the masked products as bf16 value + remainder. (beta, alpha or a missing lambda select the kernels' variant with
+// the write gate, the alpha-connection and the rule for lambda.)
 hipError_t launch_fused_forward(const FusedArgs &a, void *workspace, hipStream_t stream, int which, bool split);
 
 // Workspace sizes in bytes per (pair, chunk).

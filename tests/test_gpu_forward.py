@@ -313,9 +313,11 @@ def test_solve_result_output(dtype, compute, d):
     dev = upload_inputs(x, w.dtype)
     cm = binding.GKA_COMPUTE_BF16 if compute == "bf16" else binding.GKA_COMPUTE_F32
     alpha = to_device(gates["alpha"], "f32")
+    # (the two-phase kernels in both calls: they are the ones that write xhat)
     o, ex = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=cm,
                                 alpha=alpha, return_xhat=True)
-    o2 = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=cm, alpha=alpha)
+    o2 = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=cm, alpha=alpha,
+                             path=binding.GKA_PATH_TWO_PHASE)
     torch.cuda.synchronize()
     assert torch.equal(o, o2)
     ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, alpha=gates["alpha"],

@@ -98,9 +98,9 @@ def test_fused_path_is_refused_where_it_does_not_apply():
     w = synth.CFG2.scaled(B=1, H=1, T=64)
     x = synth.make_inputs(w)
     dev = upload_inputs(x, w.dtype)
-    beta = torch.ones((1, 64, 1), dtype=torch.float32, device="cuda")
-    with pytest.raises(binding.GkaError) as e:
-        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, path=FUSED, beta=beta)
+    with pytest.raises(binding.GkaError) as e:       # the solve's result as an output: two-phase kernels only
+        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, path=FUSED,
+                            return_xhat=True)
     assert e.value.status == binding.GKA_ERR_UNSUPPORTED
     with pytest.raises(binding.GkaError) as e:
         binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, path=FUSED,
@@ -338,5 +338,42 @@ def test_split_is_refused_where_the_fused_kernel_does_not_apply():
                             path=binding.GKA_PATH_TWO_PHASE)
     assert e.value.status == binding.GKA_ERR_UNSUPPORTED
     with pytest.raises(binding.GkaError) as e:
-        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], None, w.n_iter, compute=SPLIT, lambda_scale=0.1)
+        binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], dev["lam"], w.n_iter, compute=SPLIT,
+                            return_xhat=True)
     assert e.value.status == binding.GKA_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("compute", ["bf16", "split"])
+@pytest.mark.parametrize("which", ["beta", "alpha", "rule", "all"])
+def test_fused_layer_variants_over_segments(which, compute):
+    """Write gate (some tokens write nothing at all), alpha-connection and the rule lambda_t = a ||H_t||_F inside the
+    fused kernels, on short walks (the summaries carry the write gate too) and on top of an initial state."""
+    w = synth.CFG2.scaled(B=1, H=3, T=900, n_iter=8, gate_mean=4.0, seed=5200)
+    x = synth.make_inputs(w)
+    gates = synth.make_gates(w)
+    Hi, Ui = spd_state(w, 11)
+    kw, okw = {}, {}
+    if which in ("beta", "all"):
+        beta = gates["beta"].copy()
+        beta[:, 5::37] = 0.0
+        kw["beta"], okw["beta"] = to_device(beta, "f32"), beta
+    if which in ("alpha", "all"):
+        kw["alpha"], okw["alpha"] = to_device(gates["alpha"], "f32"), gates["alpha"]
+    lam = x["lam"]
+    if which in ("rule", "all"):
+        kw["lambda_scale"] = okw["lambda_scale"] = 0.05
+        lam = None
+    import torch
+    dev = upload_inputs(x, w.dtype)
+    cm = SPLIT if compute == "split" else binding.GKA_COMPUTE_BF16
+    o, ex = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], None if lam is None else dev["lam"],
+                                w.n_iter, compute=cm, path=FUSED, walk_chunks=3 if compute == "split" else 4,
+                                H_init=to_device(Hi, "f32"), U_init=to_device(Ui, "f32"), return_fro=True,
+                                return_state=True, **kw)
+    torch.cuda.synchronize()
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], lam, w.n_iter, H_init=Hi, U_init=Ui,
+                              return_fro=True, return_state=True, **okw)
+    assert pair_rel_err(to_host(o), ref) <= TOL_BF16
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+    for name in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name

@@ -67,6 +67,7 @@ def test_static_scratch_refusals():
     two = binding.make_params(1, 1, 64, 128, 10, binding.GKA_BF16, binding.GKA_COMPUTE_BF16,
                               path=binding.GKA_PATH_TWO_PHASE)
     assert binding.forward_static_raw(two, p, p, p, p, p, p) == binding.GKA_ERR_UNSUPPORTED
-    rule = binding.make_params(1, 1, 64, 128, 10, binding.GKA_BF16, binding.GKA_COMPUTE_BF16, lambda_scale=0.1)
-    assert binding.forward_static_raw(rule, p, p, p, p, None, p) == binding.GKA_ERR_UNSUPPORTED
+    # the solve's result as an output is not something the fused kernels write
+    xh = binding.make_params(1, 1, 64, 128, 10, binding.GKA_BF16, binding.GKA_COMPUTE_BF16, xhat_out=p)
+    assert binding.forward_static_raw(xh, p, p, p, p, p, p) == binding.GKA_ERR_UNSUPPORTED
     assert binding.forward_static_raw(None, p, p, p, p, p, p) == binding.GKA_ERR_NULL
