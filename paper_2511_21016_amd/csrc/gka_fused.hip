@@ -301,20 +301,20 @@ __device__ __forceinline__ void masked_frag_split(const f32x4 &P0, const f32x4 &
     split8(P0 * mreg[2 * jb], P1 * mreg[2 * jb + 1], val, rem);
 }
 
-// P[js] = K[js] x for the key blocks js < NJ, x given as B fragments; a rolled loop (used once per chunk)
+// P[js] = K[js] x for the key blocks js < NJ, x given as B fragments
 template <int NJ, int NX>
 __device__ __forceinline__ void key_products(const bf16x8 *sK, const bf16x8 (&x)[NX][4], f32x4 (&P)[NJ], int lane)
 {
 #pragma unroll
     for (int js = 0; js < NJ; ++js) P[js] = zero4();
-#pragma unroll 1
+#pragma unroll
     for (int fb = 0; fb < 4; ++fb) {
         bf16x8 a[NJ];
 #pragma unroll
         for (int js = 0; js < NJ; ++js) a[js] = sK[(js * 4 + fb) * 64 + lane];
         bf16x8 b[NX];
 #pragma unroll
-        for (int v = 0; v < NX; ++v) b[v] = fb == 0 ? x[v][0] : (fb == 1 ? x[v][1] : (fb == 2 ? x[v][2] : x[v][3]));
+        for (int v = 0; v < NX; ++v) b[v] = x[v][fb];
 #pragma unroll
         for (int js = 0; js < NJ; ++js)
 #pragma unroll
