@@ -66,6 +66,7 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--no-sketch", action="store_true")
+    ap.add_argument("--no-head-dims", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -344,6 +345,33 @@ def main():
         result["latent_sketching"] = {"sketch_dim": d_s, "ms_per_step": ms_sk, "tokens_per_s": tokens / (ms_sk * 1e-3),
                                       "times_forward": ms_sk / ms_per_step, "workspace_bytes": sws.numel()}
         del sws, so, S
+
+    # ---- other head dimensions (extra information): the token-by-token path of gka_forward, synthetic inputs of the
+    # workload's distributions. d = 16 on the shape of a vision model (Appendix L: 197 tokens, many short sequences);
+    # d = 256 at the model width of the headline workload.
+    if not args.no_head_dims:
+        result["other_head_dims"] = {}
+        for name, shape in (("d16_197_tokens", dict(B=256, H=24, T=197, d=16)), ("d256", dict(B=4, H=8, T=1024, d=256))):
+            wd = w.scaled(seed=w.seed + 50, **shape)
+            xd = upload_inputs(synth.make_inputs(wd), "bf16")
+            od = torch.empty_like(xd["v"])
+            pd = binding.make_params(wd.B, wd.H, wd.T, wd.d, wd.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16)
+            wsd = torch.empty(binding.forward_workspace_bytes(pd), dtype=torch.uint8, device="cuda")
+            call = lambda: binding.gka_forward(xd["q"], xd["k"], xd["v"], xd["gate"], xd["lam"], wd.n_iter,
+                                               workspace=wsd, out=od)
+            call()
+            torch.cuda.synchronize()
+            d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            d0.record()
+            for _ in range(3):
+                call()
+            d1.record()
+            torch.cuda.synchronize()
+            ms_d = d0.elapsed_time(d1) / 3
+            result["other_head_dims"][name] = {"B": wd.B, "H": wd.H, "T": wd.T, "d": wd.d, "ms_per_step": ms_d,
+                                               "tokens_per_s": wd.B * wd.H * wd.T / (ms_d * 1e-3),
+                                               "kernel": "decode_step_kernel (path recurrent)"}
+            del xd, od, wsd
 
     if not args.no_cpu_baseline:
         import oracle

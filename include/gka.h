@@ -85,14 +85,23 @@ typedef enum { GKA_STATE_FULL = 0, GKA_STATE_H_LOWER_BLOCKS = 1 } gka_state_layo
  * GKA_PATH_FUSED    : one kernel walks the chunks of a pair in order with H and U in registers, so that no chunk state
  *                     crosses HBM. Available for GKA_BF16 tensors with GKA_COMPUTE_BF16 (or _SPLIT), d = 128, with or without
  *                     the layer's variants (beta, alpha, the rule for lambda) but without xhat_out, GKA_PHASE_ALL;
- *                     GKA_ERR_UNSUPPORTED otherwise. */
-typedef enum { GKA_PATH_AUTO = 0, GKA_PATH_TWO_PHASE = 1, GKA_PATH_FUSED = 2 } gka_path;
+ *                     GKA_ERR_UNSUPPORTED otherwise.
+ * GKA_PATH_RECURRENT: Eq. (CH) token by token, one workgroup per (batch, head) pair with the states in registers (the
+ *                     kernel of gka_decode_tokens), float32 arithmetic whatever p->compute says. Every head dimension,
+ *                     dtype, stride and variant, with xhat_out and fro_out; GKA_PHASE_ALL only. It is the only path
+ *                     for d = 16, 32 and 256 (what GKA_PATH_AUTO selects there; the two chunk-wise paths return
+ *                     GKA_ERR_UNSUPPORTED) and its parallelism is the number of pairs: meant for short sequences over
+ *                     many heads (head dimension 16 of the vision models, Appendix L) and as a float32 cross-check
+ *                     of the chunk-wise kernels, not for long sequences over few pairs. Gates are used as given
+ *                     (no floor at exp(-100)). */
+typedef enum { GKA_PATH_AUTO = 0, GKA_PATH_TWO_PHASE = 1, GKA_PATH_FUSED = 2, GKA_PATH_RECURRENT = 3 } gka_path;
 
 typedef struct {
     int32_t B;            /* batch (gka_decode_step: number of sequences)                      */
     int32_t H;            /* heads                                                             */
     int32_t T;            /* tokens per sequence (ignored by gka_decode_step); any T >= 1      */
-    int32_t d_k;          /* head dimension of q, k: 64 or 128                                 */
+    int32_t d_k;          /* head dimension of q, k: 16, 32, 64, 128 or 256 (chunk-wise kernels, */
+                          /*   gka_backward and gka_forward_sketched: 64 or 128; see gka_path)    */
     int32_t d_v;          /* head dimension of v, o: must equal d_k                            */
     int32_t chunk;        /* chunk size C of Section 4.2.1: 64 (T need not be a multiple)      */
     int32_t n_iter;       /* r of Algorithm 1 = number of loop passes; 0 returns U_t xi_0      */
@@ -205,7 +214,8 @@ gka_status gka_forward_profile(const gka_params *p,
  *   H_state [B,H,d_k,d_k], U_state [B,H,d_v,d_k] float32, updated IN PLACE
  *   q, k [B,H,d_k], v [B,H,d_v] io_dtype (packed); gate, lambda [B,H] float32 (lambda NULL as in gka_forward)
  *   o [B,H,d_v] io_dtype (written)
- * The arithmetic is float32 for either compute mode. */
+ * The arithmetic is float32 for either compute mode. Every head dimension of gka_params; the block-lower layout of H
+ * up to d = 128 (d = 16 and 32 are a single block: the layout is the full one). */
 gka_status gka_decode_step(const gka_params *p,
                            float *H_state, float *U_state,
                            const void *q, const void *k, const void *v,

@@ -19,7 +19,7 @@ GKA_F32, GKA_BF16 = 0, 1
 GKA_COMPUTE_F32, GKA_COMPUTE_BF16, GKA_COMPUTE_BF16_SPLIT = 0, 1, 2
 GKA_PHASE_ALL, GKA_PHASE_STATES, GKA_PHASE_SOLVE = 0, 1, 2
 GKA_STATE_FULL, GKA_STATE_H_LOWER_BLOCKS = 0, 1
-GKA_PATH_AUTO, GKA_PATH_TWO_PHASE, GKA_PATH_FUSED = 0, 1, 2
+GKA_PATH_AUTO, GKA_PATH_TWO_PHASE, GKA_PATH_FUSED, GKA_PATH_RECURRENT = 0, 1, 2, 3
 
 EXPORTED_SYMBOLS = (
     "gka_forward_workspace_bytes",

@@ -17,6 +17,7 @@ struct Plan {
     int n_segs, seg_len;
     int pairs_per_batch;          // (batch, head) pairs per launch
     int slab_chunks;              // chunks of every pair per launch
+    bool recurrent;               // token-by-token kernel: no chunks, no launch plan
     bool split;                   // GKA_COMPUTE_BF16_SPLIT (fused kernel only)
     bool fused_shape;             // dtype, operands and head dimension of the fused kernel
     int fused_n_segs, fused_seg_len;
@@ -43,7 +44,7 @@ gka_status check_common(const gka_params *p, bool decode)
     if (p->d_k <= 0 || p->d_v <= 0) return GKA_ERR_SHAPE;
     if (p->phase < GKA_PHASE_ALL || p->phase > GKA_PHASE_SOLVE) return GKA_ERR_UNSUPPORTED;
     if (p->d_k != p->d_v) return GKA_ERR_UNSUPPORTED;
-    if (p->d_k != 64 && p->d_k != 128) return GKA_ERR_UNSUPPORTED;
+    if (p->d_k != 16 && p->d_k != 32 && p->d_k != 64 && p->d_k != 128 && p->d_k != 256) return GKA_ERR_UNSUPPORTED;
     if (p->io_dtype != GKA_F32 && p->io_dtype != GKA_BF16) return GKA_ERR_UNSUPPORTED;
     if (p->compute < GKA_COMPUTE_F32 || p->compute > GKA_COMPUTE_BF16_SPLIT) return GKA_ERR_UNSUPPORTED;
     if (p->io_dtype == GKA_F32 && p->compute != GKA_COMPUTE_F32) return GKA_ERR_UNSUPPORTED;
@@ -52,9 +53,13 @@ gka_status check_common(const gka_params *p, bool decode)
     if (!(p->lambda_scale >= 0.0f)) return GKA_ERR_SHAPE;
     if (p->state_layout != GKA_STATE_FULL && p->state_layout != GKA_STATE_H_LOWER_BLOCKS) return GKA_ERR_UNSUPPORTED;
     if (p->slab_state_bytes < 0 || p->walk_chunks < 0) return GKA_ERR_SHAPE;
-    if (p->path < GKA_PATH_AUTO || p->path > GKA_PATH_FUSED) return GKA_ERR_UNSUPPORTED;
+    if (p->state_layout == GKA_STATE_H_LOWER_BLOCKS && p->d_k == 256) return GKA_ERR_UNSUPPORTED;
+    if (p->path < GKA_PATH_AUTO || p->path > GKA_PATH_RECURRENT) return GKA_ERR_UNSUPPORTED;
     return GKA_OK;
 }
+
+// head dimensions of the chunk-wise kernels (the others run token by token)
+bool chunked_dim(int d) { return d == 64 || d == 128; }
 
 gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
 {
@@ -66,6 +71,9 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
     pl->io_bf16 = p->io_dtype == GKA_BF16;
     pl->compute_bf16 = p->compute != GKA_COMPUTE_F32;
     pl->split = p->compute == GKA_COMPUTE_BF16_SPLIT;
+    pl->recurrent = p->path == GKA_PATH_RECURRENT || !chunked_dim(pl->d);
+    if (pl->recurrent && (p->path == GKA_PATH_TWO_PHASE || p->path == GKA_PATH_FUSED || readout_only))
+        return GKA_ERR_UNSUPPORTED;
     if ((int64_t)pl->n_pairs * pl->n_chunks > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
     if (p->stride_b == 0 && p->stride_t == 0 && p->stride_h == 0) {
         pl->stride_h = p->d_k;
@@ -81,6 +89,14 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
         pl->stride_b = p->stride_b;
         pl->stride_t = p->stride_t;
         pl->stride_h = p->stride_h;
+    }
+    if (pl->recurrent) {
+        // states stay in registers; only d = 256 streams U through memory and needs room for it when the caller does
+        // not ask for U_final
+        pl->fused_shape = false;
+        pl->fused_bytes = 0;
+        pl->total = 256 + (pl->d == 256 ? align_up((size_t)pl->n_pairs * pl->d * pl->d * sizeof(float), 256) : 0);
+        return GKA_OK;
     }
     // The work is cut into launches of (a batch of pairs) x (a slab of consecutive chunks), slabs in sequence order,
     // so that the chunk states one launch pair writes and reads (state pass, then solve) fit a bounded workspace,
@@ -192,6 +208,25 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     hipStream_t stream = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
 
+    if (pl.recurrent) {
+        if (p->phase != GKA_PHASE_ALL || pl.split || solve_only || q_lo) return GKA_ERR_UNSUPPORTED;
+        gka::DecodeArgs da = {};
+        da.H_in = H_init; da.U_in = U_init;
+        da.H_state = H_final;
+        da.U_state = U_final ? U_final : (pl.d == 256 ? (float *)(ws + 256) : nullptr);
+        da.h_out_full = true;
+        da.h_lower_blocks = p->state_layout == GKA_STATE_H_LOWER_BLOCKS && chunked_dim(pl.d);
+        da.q = q; da.k = k; da.v = v; da.gate = gate; da.lambda = lambda; da.o = o;
+        da.stride_b = pl.stride_b; da.stride_t = pl.stride_t; da.stride_h = pl.stride_h;
+        da.beta = p->beta; da.alpha = p->alpha; da.lambda_scale = p->lambda_scale;
+        da.fro_out = fro_out; da.xhat_out = p->xhat_out;
+        da.n_iter = p->n_iter; da.T = p->T; da.H = p->H;
+        // (profiling: all of it is reported as the solve phase)
+        if (prof) { prof->mark(stream); prof->mark(stream); }
+        if (gka::launch_decode_step(da, pl.n_pairs, pl.d, pl.io_bf16, stream) != hipSuccess) return GKA_ERR_LAUNCH;
+        if (prof) prof->mark(stream);
+        return GKA_OK;
+    }
     const bool fused_ok = pl.fused_shape && !p->xhat_out && !solve_only && !q_lo && p->phase == GKA_PHASE_ALL;
     if ((p->path == GKA_PATH_FUSED || pl.split) && !fused_ok) return GKA_ERR_UNSUPPORTED;
     if (pl.split && p->path == GKA_PATH_TWO_PHASE) return GKA_ERR_UNSUPPORTED;     // only the fused kernel splits
@@ -368,12 +403,14 @@ gka_status decode_impl(const gka_params *p, int n_tokens, float *H_state, float 
     if (!H_state || !U_state || !q || !k || !v || !gate || !o) return GKA_ERR_NULL;
     if (!lambda && !(p->lambda_scale > 0.0f)) return GKA_ERR_NULL;
     gka::DecodeArgs da = {};
+    da.H_in = H_state; da.U_in = U_state;
     da.H_state = H_state; da.U_state = U_state;
     da.q = q; da.k = k; da.v = v; da.gate = gate; da.lambda = lambda; da.o = o;
+    da.stride_h = p->d_k; da.stride_t = (int64_t)p->H * p->d_k; da.stride_b = (int64_t)n_tokens * p->H * p->d_k;
     da.beta = p->beta; da.alpha = p->alpha; da.lambda_scale = p->lambda_scale;
     da.n_iter = p->n_iter;
     da.T = n_tokens; da.H = p->H;
-    da.h_lower_blocks = p->state_layout == GKA_STATE_H_LOWER_BLOCKS;
+    da.h_lower_blocks = p->state_layout == GKA_STATE_H_LOWER_BLOCKS && chunked_dim(p->d_k);
     if (gka::launch_decode_step(da, p->B * p->H, p->d_k, p->io_dtype == GKA_BF16, (hipStream_t)hip_stream) !=
         hipSuccess)
         return GKA_ERR_LAUNCH;
@@ -423,6 +460,7 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
 {
     gka_status s = check_common(p, false);
     if (s != GKA_OK) return s;
+    if (!chunked_dim(p->d_k) || p->path == GKA_PATH_RECURRENT) return GKA_ERR_UNSUPPORTED;
     if (p->stride_b != 0 || p->stride_t != 0 || p->stride_h != 0) return GKA_ERR_UNSUPPORTED;
     if (p->phase != GKA_PHASE_ALL || p->compute == GKA_COMPUTE_BF16_SPLIT) return GKA_ERR_UNSUPPORTED;
     bp->n_tokens = (size_t)p->B * p->T * p->H;
@@ -634,6 +672,7 @@ gka_status make_sketch_plan(const gka_params *p, int d_s, SketchPlan *sp)
     gka_status s = check_common(p, false);
     if (s != GKA_OK) return s;
     if (p->io_dtype != GKA_BF16 || p->compute != GKA_COMPUTE_BF16) return GKA_ERR_UNSUPPORTED;
+    if (!chunked_dim(p->d_k) || p->path == GKA_PATH_RECURRENT) return GKA_ERR_UNSUPPORTED;
     if (p->stride_b != 0 || p->stride_t != 0 || p->stride_h != 0) return GKA_ERR_UNSUPPORTED;
     if (p->phase != GKA_PHASE_ALL || p->alpha) return GKA_ERR_UNSUPPORTED;
     if (d_s < 1 || d_s > kSketchDim) return GKA_ERR_SHAPE;
@@ -734,6 +773,6 @@ const char *gka_status_string(gka_status s)
     return "unknown status";
 }
 
-int gka_version(void) { return 700; }
+int gka_version(void) { return 800; }
 
 }  // extern "C"

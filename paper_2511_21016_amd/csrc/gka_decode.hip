@@ -1,28 +1,41 @@
 // Recurrent steps of Eq. (CH) per (sequence, head) pair: state update (with the optional write gate), ||H_t||_F,
-// Algorithm 1 with the matrix held in registers, readout (with the optional alpha-connection). One workgroup of 256
-// threads per pair; all arithmetic fp32. The states are read once, advanced by a.T tokens in registers and written
-// once, so the state traffic of a call does not grow with the number of tokens.
+// Algorithm 1 with the matrix held in registers, readout (with the optional alpha-connection). One workgroup per pair;
+// all arithmetic fp32. The states are read once, advanced by a.T tokens in registers and written once, so the state
+// traffic of a call does not grow with the number of tokens. The same kernel is gka_forward's recurrent path (any
+// number of tokens, separate initial and final states, ||H_t||_F and the solve's result as optional outputs), the
+// only one for the head dimensions 16, 32 and 256.
 //
-// The d x d states are distributed as float4 pieces in flat row-major order, piece (it*256 + t) on thread
+// The d x d states are distributed as float4 pieces in flat row-major order, piece (it*NTHR + t) on thread
 // t, so that state reads and writes are fully coalesced: thread t holds, for each of its ITS pieces, row
-// i = it*RPI + t / C4 and columns 4*(t % C4) .. +3 (C4 = d/4 pieces per row, RPI = 256/C4 rows per sweep).
+// i = it*RPI + t / C4 and columns 4*(t % C4) .. +3 (C4 = d/4 pieces per row, RPI = NTHR/C4 rows per sweep).
 // H is symmetric, so H x is evaluated column-wise, (H x)_j = sum_i H[i][j] x_i: every thread accumulates
-// its rows into its four columns, and the 256/C4 partial sums per column are combined through LDS.
+// its rows into its four columns, and the NTHR/C4 partial sums per column are combined through LDS.
+// NTHR = 256 threads; 64 for d = 16 (64 pieces); 1024 for d = 256, where a thread holds 16 pieces of H and U does
+// not fit beside them: U is then streamed, each piece read, advanced, used for the readout and written back
+// once per token (STREAM_U).
 #include "gka_device.hpp"
 #include "gka_kernels.hpp"
 
 namespace gka {
 
+template <int D>
+struct DecodeShape {
+    static constexpr int NTHR = D == 16 ? 64 : (D == 256 ? 1024 : 256);
+    static constexpr int C4 = D / 4, RPI = NTHR / C4, ITS = D / RPI, NW = NTHR / 64;
+    static constexpr bool STREAM_U = D == 256;
+    static_assert(ITS * NTHR * 4 == D * D && ITS >= 1 && RPI * C4 == NTHR, "every thread holds ITS pieces of a state");
+};
+
 // MULTI = false: the single-step kernel, a.T == 1 known at compile time.
-// LOWER: of H_state only the 32 x 32 blocks on and below the block diagonal are read and written; the blocks above
-// are rebuilt in registers from their mirror images (through LDS, once per call), so the arithmetic is the same.
+// LOWER: of H_in / H_state only the 32 x 32 blocks on and below the block diagonal are read and written; the blocks
+// above are rebuilt in registers from their mirror images (through LDS, once per call), so the arithmetic is the same.
 template <class IO, int D, bool MULTI, bool LOWER>
-__global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
+__global__ __launch_bounds__(DecodeShape<D>::NTHR) void decode_step_kernel(DecodeArgs a)
 {
+    typedef DecodeShape<D> SH;
     const int T = MULTI ? a.T : 1;
-    constexpr int C4 = D / 4;
-    constexpr int RPI = 256 / C4;
-    constexpr int ITS = D / RPI;
+    constexpr int NTHR = SH::NTHR, C4 = SH::C4, RPI = SH::RPI, ITS = SH::ITS, NW = SH::NW;
+    constexpr bool STREAM_U = SH::STREAM_U;
     const int t = threadIdx.x;
     const int pair = blockIdx.x;
     const int col4 = t % C4, rgrp = t / C4;
@@ -30,19 +43,26 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
     __shared__ float s_q[D], s_k[D], s_v[D];
     __shared__ float s_x[D];                 // operand of the current product (delta_i or xhat)
     __shared__ float s_part[RPI][D];         // per row-group partial column sums
-    __shared__ float s_red[4];
+    __shared__ float s_red[NW];
 
-    float *Hs = a.H_state + (int64_t)pair * D * D;
-    float *Us = a.U_state + (int64_t)pair * D * D;
+    const int64_t state_off = (int64_t)pair * D * D;
+    const float *Hin = a.H_in ? a.H_in + state_off : nullptr;      // nullptr: zero initial states
+    const float *Uin = a.U_in ? a.U_in + state_off : nullptr;
+    float *Hs = a.H_state ? a.H_state + state_off : nullptr;       // nullptr: the final states are not wanted
+    float *Us = a.U_state ? a.U_state + state_off : nullptr;
     const int b = pair / a.H, h = pair - b * a.H;
-    f32x4 hreg[ITS], ureg[ITS];
+    f32x4 hreg[ITS], ureg[STREAM_U ? 1 : ITS];
     // piece `it` of this thread lies in block row (it * RPI) / 32 (RPI divides 32) and block column bj
     const int bj = col4 / 8;
     auto held = [&](int it) { return !LOWER || bj <= (it * RPI) / 32; };
 #pragma unroll
     for (int it = 0; it < ITS; ++it) {
-        if (held(it)) hreg[it] = __builtin_nontemporal_load((const f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4));
-        ureg[it] = __builtin_nontemporal_load((const f32x4 *)(Us + (int64_t)(it * 256 + t) * 4));
+        hreg[it] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (Hin && held(it)) hreg[it] = __builtin_nontemporal_load((const f32x4 *)(Hin + (int64_t)(it * NTHR + t) * 4));
+        if constexpr (!STREAM_U) {
+            ureg[it] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (Uin) ureg[it] = __builtin_nontemporal_load((const f32x4 *)(Uin + (int64_t)(it * NTHR + t) * 4));
+        }
     }
     if constexpr (LOWER) {
         constexpr int NBLK = D / 32, NOFF = NBLK * (NBLK - 1) / 2;
@@ -65,12 +85,19 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
             }
         }
     }
+    // H is written in full where the caller of the forward pass wants the final state (valid under either layout)
+    auto stored = [&](int it) { return held(it) || a.h_out_full; };
     for (int tok = 0; tok < T; ++tok) {
         const int64_t bth = ((int64_t)b * T + tok) * a.H + h;      // [B,T,H] index of this token
+        // d = 256: addresses of the state pieces are recomputed per token (hoisted out of the loop they would take
+        // registers that H needs)
+        int tv = t;
+        if constexpr (STREAM_U) asm volatile("" : "+v"(tv));
+        const int64_t row0 = b * a.stride_b + tok * a.stride_t + h * a.stride_h;   // its row of q, k, v, o
         if (t < D) {
-            s_q[t] = IO::load(a.q, bth * D + t);
-            s_k[t] = IO::load(a.k, bth * D + t);
-            s_v[t] = IO::load(a.v, bth * D + t);
+            s_q[t] = IO::load(a.q, row0 + t);
+            s_k[t] = IO::load(a.k, row0 + t);
+            s_v[t] = IO::load(a.v, row0 + t);
         }
         const float gamma = a.gate[bth];
         const float beta = a.beta ? a.beta[bth] : 1.0f;        // write gate (Remark in Section 4.1)
@@ -91,19 +118,25 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
                 // beta (k_i k_j): the product of the two k components first, so that both mirror images of an
                 // element get the same bits
                 hreg[it][e] = gamma * hreg[it][e] + beta * (kr * kc[e]);
-                ureg[it][e] = gamma * ureg[it][e] + vr * kc[e];
+                if constexpr (!STREAM_U) ureg[it][e] = gamma * ureg[it][e] + vr * kc[e];
                 ss += hreg[it][e] * hreg[it][e];
             }
             if (tok == T - 1) {              // the stores drain while the last token is solved
-                if (held(it)) __builtin_nontemporal_store(hreg[it], (f32x4 *)(Hs + (int64_t)(it * 256 + t) * 4));
-                __builtin_nontemporal_store(ureg[it], (f32x4 *)(Us + (int64_t)(it * 256 + t) * 4));
+                if (Hs && stored(it)) __builtin_nontemporal_store(hreg[it], (f32x4 *)(Hs + (int64_t)(it * NTHR + tv) * 4));
+                if constexpr (!STREAM_U) {
+                    if (Us) __builtin_nontemporal_store(ureg[it], (f32x4 *)(Us + (int64_t)(it * NTHR + t) * 4));
+                }
             }
         }
         ss = wave_sum(ss);
         if ((t & 63) == 0) s_red[t >> 6] = ss;
         __syncthreads();
-        const float fro = sqrtf(s_red[0] + s_red[1] + s_red[2] + s_red[3]);
+        float fro2 = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) fro2 += s_red[w];
+        const float fro = sqrtf(fro2);
         const float lam = a.lambda ? a.lambda[bth] : a.lambda_scale * fro;   // Section 4.1: lambda_t = a ||H_t||_F
+        if (a.fro_out && t == 0) a.fro_out[bth] = fro;
 
         // ---- Algorithm 1 in residual form; thread j < D owns component j of xi, delta, r
         const float L = fro + lam, mu = lam;
@@ -144,44 +177,79 @@ __global__ __launch_bounds__(256) void decode_step_kernel(DecodeArgs a)
 
         // ---- readout y = U (alpha xhat + (1 - alpha) q) (rows of U are not symmetric: reduce each row over its
         // C4 lanes)
-        if (t < D) s_x[t] = alpha * xi + (1.0f - alpha) * s_q[t];
+        if (t < D) {
+            s_x[t] = alpha * xi + (1.0f - alpha) * s_q[t];
+            if (a.xhat_out) a.xhat_out[bth * D + t] = xi;
+        }
         __syncthreads();
         float xc[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) xc[e] = s_x[4 * col4 + e];
-#pragma unroll
+        // (streamed U: four pieces in flight; all sixteen would not fit beside H)
+#pragma unroll(STREAM_U ? 4 : ITS)
         for (int it = 0; it < ITS; ++it) {
-            float y = ureg[it][0] * xc[0] + ureg[it][1] * xc[1] + ureg[it][2] * xc[2] + ureg[it][3] * xc[3];
+            f32x4 u;
+            if constexpr (STREAM_U) {
+                // this thread's piece of U: from the caller's initial state at the first token, afterwards what this
+                // same thread stored at the previous token
+                const int64_t at = (int64_t)(it * NTHR + tv) * 4;
+                u = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (tok > 0) u = *(const f32x4 *)(Us + at);
+                else if (Uin) u = *(const f32x4 *)(Uin + at);
+                const float vr = beta * s_v[it * RPI + rgrp];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) u[e] = gamma * u[e] + vr * kc[e];
+                *(f32x4 *)(Us + at) = u;
+            } else {
+                u = ureg[it];
+            }
+            float y = u[0] * xc[0] + u[1] * xc[1] + u[2] * xc[2] + u[3] * xc[3];
 #pragma unroll
             for (int off = C4 / 2; off > 0; off >>= 1) y += __shfl_xor(y, off, 64);
-            if (col4 == 0) IO::store1(a.o, bth * D + it * RPI + rgrp, y);
+            if (col4 == 0) IO::store1(a.o, row0 + it * RPI + rgrp, y);
         }
         // the next token overwrites s_q, s_k, s_v and (two barriers later) s_x: every thread must be done with xc
         __syncthreads();
     }
 }
 
-template <bool MULTI, bool LOWER>
-static void launch_decode(const DecodeArgs &a, int n_pairs, int d, bool io_bf16, hipStream_t stream)
+template <class IO, int D, bool MULTI, bool LOWER>
+static void launch_one(const DecodeArgs &a, int n_pairs, hipStream_t stream)
 {
-    dim3 grid((unsigned)n_pairs), block(256);
-    if (io_bf16) {
-        if (d == 128) hipLaunchKernelGGL((decode_step_kernel<IOBF16, 128, MULTI, LOWER>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((decode_step_kernel<IOBF16, 64, MULTI, LOWER>), grid, block, 0, stream, a);
-    } else {
-        if (d == 128) hipLaunchKernelGGL((decode_step_kernel<IOF32, 128, MULTI, LOWER>), grid, block, 0, stream, a);
-        else hipLaunchKernelGGL((decode_step_kernel<IOF32, 64, MULTI, LOWER>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((decode_step_kernel<IO, D, MULTI, LOWER>), dim3((unsigned)n_pairs), dim3(DecodeShape<D>::NTHR), 0,
+                       stream, a);
+}
+
+template <class IO, bool MULTI>
+static void launch_decode(const DecodeArgs &a, int n_pairs, int d, hipStream_t stream)
+{
+    // (up to d = 32 the state is a single 32 x 32 block: both layouts are the full one)
+    if (a.h_lower_blocks && d >= 64) {
+        if (d == 128) launch_one<IO, 128, MULTI, true>(a, n_pairs, stream);
+        else launch_one<IO, 64, MULTI, true>(a, n_pairs, stream);
+        return;
+    }
+    switch (d) {
+    case 16: launch_one<IO, 16, MULTI, false>(a, n_pairs, stream); break;
+    case 32: launch_one<IO, 32, MULTI, false>(a, n_pairs, stream); break;
+    case 64: launch_one<IO, 64, MULTI, false>(a, n_pairs, stream); break;
+    case 128: launch_one<IO, 128, MULTI, false>(a, n_pairs, stream); break;
+    default: launch_one<IO, 256, MULTI, false>(a, n_pairs, stream); break;
     }
 }
 
+// d in {16, 32, 64, 128, 256}; the block-lower layout of H only up to d = 128; d = 256 needs U_state (checked by the
+// callers).
 hipError_t launch_decode_step(const DecodeArgs &a, int n_pairs, int d, bool io_bf16, hipStream_t stream)
 {
-    if (a.h_lower_blocks) {
-        if (a.T == 1) launch_decode<false, true>(a, n_pairs, d, io_bf16, stream);
-        else launch_decode<true, true>(a, n_pairs, d, io_bf16, stream);
+    if (d != 16 && d != 32 && d != 64 && d != 128 && d != 256) return hipErrorInvalidValue;
+    if ((a.h_lower_blocks && d == 256) || (d == 256 && !a.U_state)) return hipErrorInvalidValue;
+    if (io_bf16) {
+        if (a.T == 1) launch_decode<IOBF16, false>(a, n_pairs, d, stream);
+        else launch_decode<IOBF16, true>(a, n_pairs, d, stream);
     } else {
-        if (a.T == 1) launch_decode<false, false>(a, n_pairs, d, io_bf16, stream);
-        else launch_decode<true, false>(a, n_pairs, d, io_bf16, stream);
+        if (a.T == 1) launch_decode<IOF32, false>(a, n_pairs, d, stream);
+        else launch_decode<IOF32, true>(a, n_pairs, d, stream);
     }
     return hipGetLastError();
 }

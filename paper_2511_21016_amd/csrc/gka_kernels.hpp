@@ -56,8 +56,13 @@ struct SolveArgs {
 };
 
 struct DecodeArgs {
-    float *H_state, *U_state;     // [B,H,d,d], in place
-    const void *q, *k, *v;        // [B,T,H,d]
+    const float *H_in, *U_in;     // [B,H,d,d] states before the first token (decode: the same buffers as H_state,
+                                  //   U_state); nullptr: zero
+    float *H_state, *U_state;     // [B,H,d,d] states after the last token; nullptr: not written (d = 256 needs U_state)
+    bool h_out_full;              // H_state is written in full whatever h_lower_blocks says
+    const void *q, *k, *v;        // [B,T,H,d] with the element strides below
+    int64_t stride_b, stride_t, stride_h;
+    float *fro_out, *xhat_out;    // ||H_t||_F [B,T,H] and the solve's result [B,T,H,d], each nullptr or written
     const float *gate, *lambda;   // [B,T,H]; lambda nullptr: lambda = lambda_scale ||H||_F
     const float *beta, *alpha;    // [B,T,H] or nullptr (= 1)
     float lambda_scale;

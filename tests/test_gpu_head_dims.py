@@ -1,0 +1,171 @@
+"""GPU parity: the head dimensions beyond the chunk-wise kernels (16 of the vision models in Appendix L, 32, 256) and
+the token-by-token path of gka_forward (GKA_PATH_RECURRENT) that serves them, against the fp64 oracle; the same path
+at d = 64 / 128 against the oracle and against the chunk-wise kernels; the decode entry points at those dimensions."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_21016_amd import binding, synth
+from gka_testutil import pair_rel_err, to_device, to_host, upload_inputs
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _workload(d, dtype, **kw):
+    base = synth.CFG2 if dtype == "bf16" else synth.CFG1
+    return base.scaled(d=d, **kw)
+
+
+def _forward(w, x, **kw):
+    import torch
+    dev = upload_inputs(x, w.dtype)
+    lam = None if kw.get("lambda_scale", 0.0) > 0.0 else dev["lam"]
+    out = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], lam, w.n_iter, **kw)
+    torch.cuda.synchronize()
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,T", [(16, 197), (32, 150), (256, 70)])
+def test_forward_small_and_large_head_dims(d, T, dtype):
+    w = _workload(d, dtype, B=2, H=3, T=T, n_iter=8, seed=900 + d)
+    x = synth.make_inputs(w)
+    o, ex = _forward(w, x, return_fro=True, return_state=True)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, return_fro=True,
+                              return_state=True)
+    assert pair_rel_err(to_host(o), ref) <= TOL[dtype]
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 1e-5 * rex["fro"].max()
+    for n in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[n]) - rex[n]).max() <= 1e-5 * np.abs(rex[n]).max(), n
+
+
+@pytest.mark.parametrize("d,dtype", [(16, "bf16"), (32, "f32"), (256, "f32"), (256, "bf16")])
+def test_forward_variants_states_and_solve_result(d, dtype):
+    """Write gate, alpha-connection and the rule for lambda together, from given initial states, in two segments whose
+    second starts from the first one's final states; the solve's result as an output."""
+    T, t_cut = (60, 23) if d == 256 else (130, 61)
+    w = _workload(d, dtype, B=2, H=2, T=T, n_iter=7, seed=950 + d)
+    x = synth.make_inputs(w)
+    g = synth.make_gates(w)
+    rng = np.random.default_rng(5 + d)
+    A = rng.standard_normal((w.B, w.H, d, d)) / np.sqrt(d)
+    H0 = (A @ np.transpose(A, (0, 1, 3, 2))).astype(np.float32)
+    U0 = (rng.standard_normal((w.B, w.H, d, d)) / np.sqrt(d)).astype(np.float32)
+    kw = dict(beta=g["beta"], alpha=g["alpha"], lambda_scale=0.05)
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], None, w.n_iter, H_init=H0, U_init=U0,
+                              return_state=True, return_xhat=True, **kw)
+    import torch
+    Hd, Ud = to_device(H0, "f32"), to_device(U0, "f32")
+    ys, xs = [], []
+    for t0, t1 in ((0, t_cut), (t_cut, T)):
+        sl = lambda a: np.ascontiguousarray(a[:, t0:t1])
+        q, k, v = (to_device(sl(x[n]), dtype) for n in ("q", "k", "v"))
+        o, ex = binding.gka_forward(q, k, v, to_device(sl(x["gate"]), "f32"), None, w.n_iter, H_init=Hd, U_init=Ud,
+                                    beta=to_device(sl(g["beta"]), "f32"), alpha=to_device(sl(g["alpha"]), "f32"),
+                                    lambda_scale=0.05, return_state=True, return_xhat=True)
+        torch.cuda.synchronize()
+        Hd, Ud = ex["H_final"], ex["U_final"]
+        ys.append(to_host(o))
+        xs.append(to_host(ex["xhat"]))
+    assert pair_rel_err(np.concatenate(ys, axis=1), ref) <= TOL[dtype]
+    assert pair_rel_err(np.concatenate(xs, axis=1), rex["xhat"]) <= 1e-4          # the solve itself is float32
+    assert np.abs(to_host(Hd) - rex["H_final"]).max() <= 1e-5 * np.abs(rex["H_final"]).max()
+    assert np.abs(to_host(Ud) - rex["U_final"]).max() <= 1e-5 * np.abs(rex["U_final"]).max()
+
+
+def test_forward_head_dim_16_strided_head_major_layout():
+    """q, k, v, o stored [B,H,T,d] and passed through the stride arguments."""
+    import torch
+    d = 16
+    w = _workload(d, "bf16", B=2, H=5, T=197, n_iter=6, seed=977)
+    x = synth.make_inputs(w)
+    dev = {n: to_device(np.ascontiguousarray(np.transpose(x[n], (0, 2, 1, 3))), "bf16") for n in ("q", "k", "v")}
+    gate, lam = to_device(x["gate"], "f32"), to_device(x["lam"], "f32")
+    o = torch.zeros_like(dev["v"])
+    params = binding.make_params(w.B, w.H, w.T, d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16,
+                                 strides=(w.H * w.T * d, d, w.T * d))
+    ws = torch.empty(binding.forward_workspace_bytes(params), dtype=torch.uint8, device="cuda")
+    st = binding.forward_raw(params, dev["q"].data_ptr(), dev["k"].data_ptr(), dev["v"].data_ptr(), gate.data_ptr(),
+                             lam.data_ptr(), o.data_ptr(), workspace=ws.data_ptr(), workspace_bytes=ws.numel(),
+                             stream=torch.cuda.current_stream().cuda_stream)
+    assert st == binding.GKA_OK
+    torch.cuda.synchronize()
+    ref = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter)
+    assert pair_rel_err(np.transpose(to_host(o), (0, 2, 1, 3)), ref) <= TOL["bf16"]
+
+
+def test_head_dim_256_without_final_states_uses_the_workspace():
+    """d = 256 streams U through memory: with no U_final to hold it, it lives in the workspace. Same output."""
+    import torch
+    w = _workload(256, "f32", B=1, H=3, T=40, n_iter=5, seed=981)
+    x = synth.make_inputs(w)
+    o1 = _forward(w, x)
+    o2, _ = _forward(w, x, return_state=True)
+    assert torch.equal(o1, o2)
+
+
+@pytest.mark.parametrize("d,dtype", [(64, "f32"), (128, "f32"), (128, "bf16"), (64, "bf16")])
+def test_recurrent_path_against_oracle_and_chunkwise_kernels(d, dtype):
+    """The token-by-token path at the head dimensions of the chunk-wise kernels: the oracle's tolerance, and the two
+    device paths agree with each other (float32: both round at 1e-7; bf16 tensors: the chunk-wise path rounds its
+    operands to bf16, the recurrent one only its inputs and outputs)."""
+    w = _workload(d, dtype, B=2, H=3, T=333, n_iter=8, seed=990 + d)
+    x = synth.make_inputs(w)
+    g = synth.make_gates(w)
+    kw = dict(beta=g["beta"], alpha=g["alpha"])
+    dkw = dict(beta=to_device(g["beta"], "f32"), alpha=to_device(g["alpha"], "f32"))
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], w.n_iter, return_fro=True, **kw)
+    o_r, ex_r = _forward(w, x, path=binding.GKA_PATH_RECURRENT, return_fro=True, return_state=True, **dkw)
+    o_c, ex_c = _forward(w, x, return_fro=True, return_state=True, **dkw)
+    assert pair_rel_err(to_host(o_r), ref) <= TOL[dtype]
+    assert np.abs(to_host(ex_r["fro"]) - rex["fro"]).max() <= 1e-5 * rex["fro"].max()
+    between = 2e-4 if dtype == "f32" else 2e-2
+    assert pair_rel_err(to_host(o_c), to_host(o_r)) <= between
+    tol_state = 2e-5 if dtype == "f32" else 5e-3
+    for n in ("H_final", "U_final"):
+        a, b = to_host(ex_c[n]), to_host(ex_r[n])
+        assert np.abs(a - b).max() <= tol_state * np.abs(b).max(), n
+
+
+@pytest.mark.parametrize("d,dtype,variants", [(16, "bf16", True), (16, "f32", False), (32, "f32", True),
+                                              (256, "f32", True), (256, "bf16", False)])
+def test_decode_at_other_head_dims(d, dtype, variants):
+    """gka_decode_tokens over a sequence cut into segments of 1, 4 and 7 tokens against the oracle's forward over the
+    whole sequence, the last state against the oracle's, and bit-identical to single steps."""
+    import torch
+    segs = [1, 4, 7]
+    T = sum(segs)
+    w = _workload(d, dtype, B=3, H=2, T=T, n_iter=6, seed=1200 + d)
+    x = synth.make_inputs(w)
+    kw, g = {}, None
+    if variants:
+        g = synth.make_gates(w)
+        kw = dict(beta=g["beta"], alpha=g["alpha"], lambda_scale=0.03)
+    lam_ref = None if variants else x["lam"]
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], lam_ref, w.n_iter, return_state=True, **kw)
+    zeros = lambda: torch.zeros((w.B, w.H, d, d), dtype=torch.float32, device="cuda")
+    Hd, Ud, Hs, Us = zeros(), zeros(), zeros(), zeros()
+    t0 = 0
+    for n in segs:
+        sl = lambda a, dt: to_device(np.ascontiguousarray(a[:, t0:t0 + n]), dt)
+        q, k, v, gate = sl(x["q"], dtype), sl(x["k"], dtype), sl(x["v"], dtype), sl(x["gate"], "f32")
+        lam = None if variants else sl(x["lam"], "f32")
+        dkw = dict(beta=sl(g["beta"], "f32"), alpha=sl(g["alpha"], "f32"), lambda_scale=0.03) if variants else {}
+        o = binding.gka_decode_tokens(Hd, Ud, q, k, v, gate, lam, w.n_iter, **dkw)
+        steps = []
+        for i in range(n):
+            one = lambda a: a[:, i].contiguous()
+            skw = dict(beta=one(dkw["beta"]), alpha=one(dkw["alpha"]), lambda_scale=0.03) if variants else {}
+            steps.append(binding.gka_decode_step(Hs, Us, one(q), one(k), one(v), one(gate),
+                                                 None if variants else one(lam), w.n_iter, **skw))
+        torch.cuda.synchronize()
+        assert torch.equal(o, torch.stack(steps, dim=1))
+        r = ref[:, t0:t0 + n]
+        err = np.abs(to_host(o) - r).max(axis=-1) / np.abs(r).max(axis=-1)
+        assert err.max() <= TOL[dtype], (t0, err.max())
+        t0 += n
+    assert torch.equal(Hd, Hs) and torch.equal(Ud, Us)
+    assert np.abs(to_host(Hd) - rex["H_final"]).max() <= 1e-5 * np.abs(rex["H_final"]).max()
+    assert np.abs(to_host(Ud) - rex["U_final"]).max() <= 1e-5 * np.abs(rex["U_final"]).max()

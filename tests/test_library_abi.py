@@ -46,6 +46,10 @@ def test_workspace_query(lib):
     # two chunks of a longer sequence need more scratch
     assert binding.forward_workspace_bytes(_p(T=1000)) > binding.forward_workspace_bytes(_p(T=100))
     assert binding.forward_workspace_bytes(_p(d=96)) == 0
+    # the token-by-token path keeps the states in registers; only d = 256 streams U through memory
+    assert binding.forward_workspace_bytes(_p(d=16)) == 256
+    assert binding.forward_workspace_bytes(_p(path=binding.GKA_PATH_RECURRENT)) == 256
+    assert binding.forward_workspace_bytes(_p(d=256)) == 256 + 4 * 256 * 256 * 4
     assert binding.forward_workspace_bytes(_p(T=0)) == 0
 
 
@@ -82,11 +86,22 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(_p(state_layout=2)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(state_layout=binding.GKA_STATE_H_LOWER_BLOCKS), ws=None) == binding.GKA_ERR_WORKSPACE   # valid layout
     assert fwd(_p(), H_init=fake) == binding.GKA_ERR_NULL                        # H_init without U_init
+    # head dimensions 16, 32 and 256 run token by token only; that path has no phases and no split operands
+    assert fwd(_p(d=16, path=binding.GKA_PATH_TWO_PHASE)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(d=256, path=binding.GKA_PATH_FUSED)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(d=256, state_layout=binding.GKA_STATE_H_LOWER_BLOCKS)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(d=32, phase=binding.GKA_PHASE_STATES)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(path=binding.GKA_PATH_RECURRENT, phase=binding.GKA_PHASE_SOLVE)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(path=binding.GKA_PATH_RECURRENT, compute=binding.GKA_COMPUTE_BF16_SPLIT)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(path=4)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(d=16), ws=None) == binding.GKA_ERR_WORKSPACE                   # a valid shape
     assert fwd(_p(), ws=None) == binding.GKA_ERR_WORKSPACE
     assert fwd(_p(), ws_bytes=ok_ws - 1) == binding.GKA_ERR_WORKSPACE
     assert fwd(_p(), ws=0x100010) == binding.GKA_ERR_WORKSPACE                   # misaligned
     assert binding.decode_step_raw(_p(), None, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
-    assert binding.decode_step_raw(_p(d=32), fake, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_UNSUPPORTED
+    assert binding.decode_step_raw(_p(d=48), fake, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_UNSUPPORTED
+    assert binding.decode_step_raw(_p(d=256, state_layout=binding.GKA_STATE_H_LOWER_BLOCKS), fake, fake, fake, fake,
+                                   fake, fake, fake, fake) == binding.GKA_ERR_UNSUPPORTED
     assert binding.decode_tokens_raw(_p(), None, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
     assert binding.decode_tokens_raw(_p(T=0), fake, fake, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_SHAPE
     assert binding.decode_tokens_raw(_p(strides=(1 << 20, 2048, 128)), fake, fake, fake, fake, fake, fake, fake,
@@ -104,6 +119,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert bw(_p(strides=(1 << 20, 2048, 128))) == binding.GKA_ERR_UNSUPPORTED
     assert bw(_p(), ws_bytes=bws - 1) == binding.GKA_ERR_WORKSPACE
     assert bw(_p(d=96)) == binding.GKA_ERR_UNSUPPORTED
+    assert bw(_p(d=16)) == binding.GKA_ERR_UNSUPPORTED                # the backward pass runs on the chunk-wise kernels
+    assert bw(_p(path=binding.GKA_PATH_RECURRENT)) == binding.GKA_ERR_UNSUPPORTED
     # latent sketching: workspace query and argument checks
     sws = binding.forward_sketched_workspace_bytes(_p(), 32)
     assert sws > 0 and sws % 256 == 0
@@ -120,4 +137,5 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert sk(_p(compute=binding.GKA_COMPUTE_F32)) == binding.GKA_ERR_UNSUPPORTED
     assert sk(_p(strides=(1 << 20, 2048, 128))) == binding.GKA_ERR_UNSUPPORTED
     assert sk(_p(), ws_bytes=sws - 1) == binding.GKA_ERR_WORKSPACE
+    assert sk(_p(d=256)) == binding.GKA_ERR_UNSUPPORTED
     assert binding.forward_raw(None, fake, fake, fake, fake, fake, fake) == binding.GKA_ERR_NULL
