@@ -23,6 +23,7 @@ N_INPUT_SETS = 3                   # rotated so that the 256 MiB of q,k,v,o do n
 # untimed forward passes run before the W warm-up steps whatever W is (reported as "clock_ramp_steps").
 CLOCK_RAMP_STEPS = 300
 FUSED_KERNEL = "gka::fused_forward_kernel<false, false>(gka::FusedArgs)"
+TWO_PHASE_SOLVE_KERNEL = "gka::chunk_solve_kernel_bf16<gka::IOBF16, 128, false>(gka::SolveArgs)"
 
 
 def committed_traffic(kernel):
@@ -62,6 +63,9 @@ def main():
     ap.add_argument("--n-iter", type=int, default=None,
                     help="profiling aid: another number of Chebyshev passes than the workload's 10 (the difference "
                          "between two counts isolates the passes); the JSON line then describes that variant")
+    ap.add_argument("--path", choices=["auto", "two-phase"], default="auto",
+                    help="profiling aid: time the two-phase kernels (chunk states through the workspace) instead of "
+                         "the library's choice, the fused kernels; the JSON line then describes that variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
@@ -87,7 +91,9 @@ def main():
     w = synth.CFG2 if args.n_iter is None else synth.CFG2.scaled(n_iter=args.n_iter)
     sets_host = [synth.make_inputs(w.scaled(seed=w.seed + 100 * i)) for i in range(N_INPUT_SETS)]
     sets = [upload_inputs(x, w.dtype) for x in sets_host]
-    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16)
+    two_phase = args.path == "two-phase"
+    params = binding.make_params(w.B, w.H, w.T, w.d, w.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16,
+                                 path=binding.GKA_PATH_TWO_PHASE if two_phase else binding.GKA_PATH_AUTO)
     ws = torch.empty(binding.forward_workspace_bytes(params), dtype=torch.uint8, device="cuda")
     outs = [torch.empty_like(s["v"]) for s in sets]
 
@@ -146,6 +152,13 @@ def main():
     # the fused kernel does all of S1-S6 for every chunk (the summary launch before it repeats part of S2 and is
     # not counted as algorithmic work)
     tflops_solve = flops_total / (ms_solve_launch * 1e-3) / 1e12
+    phase_names = ("segment_summaries", "chunk_walk")
+    kernel = FUSED_KERNEL
+    if two_phase:
+        # the solve kernel does S4-S6 and the in-chunk part of S1; the state pass before it does S2 and S3
+        tflops_solve = n_chunks * (f_s4 + f_s5 + f_s6) / (ms_solve_launch * 1e-3) / 1e12
+        phase_names = ("chunk_states", "chunk_solve")
+        kernel = TWO_PHASE_SOLVE_KERNEL
 
     result = {
         "metric": "GKA layer forward tokens/sec + % bf16 MFMA peak (H=16,d=128,T=4096)",
@@ -165,12 +178,15 @@ def main():
         "head_tokens_per_s": tokens * w.H / (ms_per_step * 1e-3),
         "tflops_algorithmic": tflops_total,
         "frac_bf16_mfma_peak": tflops_total / MFMA_BF16_PEAK_TFLOPS,
-        "phase_ms": {"segment_summaries": ms_states, "chunk_walk": ms_solve, "chunk_walk_launches_per_step": n_launches,
-                     "chunk_walk_ms_per_launch": ms_solve_launch},
-        "roofline": {"kernel": FUSED_KERNEL, "bound": "mfma",
+        "phase_ms": {phase_names[0]: ms_states, phase_names[1]: ms_solve,
+                     phase_names[1] + "_launches_per_step": n_launches,
+                     phase_names[1] + "_ms_per_launch": ms_solve_launch},
+        "roofline": {"kernel": kernel, "bound": "mfma",
                      "achieved": tflops_solve, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tflops_solve / MFMA_BF16_PEAK_TFLOPS, "traffic": committed_traffic(FUSED_KERNEL)},
+                     "frac": tflops_solve / MFMA_BF16_PEAK_TFLOPS, "traffic": committed_traffic(kernel)},
     }
+    if two_phase:
+        result["config"]["path"] = "two-phase kernels (profiling aid; not the library's choice for this workload)"
 
     # ---- the other forward configurations (extra information): long context and the ill-conditioned stress
     if not args.no_other_configs:

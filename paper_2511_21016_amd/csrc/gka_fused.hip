@@ -241,9 +241,12 @@ __device__ __forceinline__ void readout_state(const Ctx &c, const f32x4 (&accU)[
 // blocks: NJ = 2 key blocks for ts = 0, 1 and NJ = 4 for ts = 2, 3; a block beyond ts is all future keys, its mask is
 // zero and it costs a few products (four instantiations would cost more in instruction fetches than they save).
 
+// Smallest zeta_c by which a token's system is divided (see solve_tokens).
+constexpr float kMinSolveZeta = 0x1p-60f;
+
 struct Solver {
-    f32x4 mreg[4];                   // decay mask M[j][c], key block js: rows j = 16 js + 4 kg + r
-    f32x4 yi[8];                     // intra-chunk part of the readout
+    f32x4 mreg[4];                   // decay mask M[j][c], key block js: rows j = 16 js + 4 kg + r (from the passes on: / zeta)
+    f32x4 yi[8];                     // intra-chunk part of the readout (/ zeta)
     float zeta, fro;
     float beta;                      // write gate of this lane's token (1 without the variant)
     int tok;                         // this lane's token (global index)
@@ -326,15 +329,19 @@ __device__ __forceinline__ void key_products(const bf16x8 *sK, const bf16x8 (&x)
 //   delta_i = (omega_i - 1) delta_{i-1} - (2 omega_i / (L + mu)) (g_{i-1} + lambda xi_{i-1}),  xi_i = xi_{i-1} + delta_i,
 // with g_i = H_c xi_i - q accumulated over the passes (H_c delta = zeta_c H_[n] delta + K^T (M o (K delta)), Section
 // 4.2.1), so that the rounded operand of every product is the shrinking update, not the iterate.
-// On entry: xi = xi_{-1} = 0, dl = delta_0 = xi_0, gn = -q. On exit xi + dl is the result.
+// The system of a token is taken divided by its zeta_c: g / zeta_c = H_[n] xi + K^T ((M / zeta_c) o (K xi)) - q / zeta_c
+// is one chain of matrix products per feature tile, with no vector instruction between the state part and the
+// intra-chunk part (the caller passes the mask divided by zeta_c; the iterate itself is not scaled).
+// On entry: xi = xi_{-1} = 0, dl = delta_0 = xi_0, gn = -q / zeta_c; s0z = 2 zeta_c / (L + mu), s0lam = 2 lambda /
+// (L + mu). On exit xi + dl is the result.
 // The loop body is one straight line of MFMA steps, each with its A fragment requested kDepth steps ahead and a slice
 // of the vector work behind it.
 // `start_copies` is called once, after the last LDS read that the compiler knows of: it issues the copies into LDS
 // that overlap the passes.
 template <int NJ, bool SPLIT, class StartCopies>
 __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, const bf16x8 *sKT, f32x4 (&xi)[8],
-                                            f32x4 (&dl)[8], f32x4 (&gn)[8], const f32x4 (&mreg)[4], float zeta,
-                                            float lam, float s0, float rho2, int n_iter, int lane,
+                                            f32x4 (&dl)[8], f32x4 (&gn)[8], const f32x4 (&mreg)[4], float s0z,
+                                            float s0lam, float rho2, int n_iter, int lane,
                                             StartCopies start_copies)
 {
     typedef PassPlan<NJ, SPLIT> PL;
@@ -385,31 +392,27 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
         asm volatile("" ::: "memory");
         if (kBoost && it == prio_passes) __builtin_amdgcn_s_setprio(0);
         omega = 4.0f * __builtin_amdgcn_rcpf(4.0f - rho2 * omega);           // weight schedule
-        const float cm = omega - 1.0f, ncs = -omega * s0, ncl = ncs * lam;
+        const float cm = omega - 1.0f, ncs = -omega * s0z, ncl = -omega * s0lam;
         bf16x8 pm[NJB], pmR[SPLIT ? NJB : 1];
-        f32x4 s = zero4(), sprev = zero4();
         f32x4 tcm;
         auto mask_products = [&](auto jbc) {
             constexpr int jb = decltype(jbc)::value;
             if constexpr (SPLIT) masked_frag_split(P[2 * jb], P[2 * jb + 1], mreg, jb, pm[jb], pmR[jb]);
             else pm[jb] = masked_frag(P[2 * jb], P[2 * jb + 1], mreg, jb);
         };
-        // update of one element, split into what needs no product of this pass (a) and the rest (b)
-        auto upd_a = [&](auto ftc, auto rc) {
-            constexpr int ft = decltype(ftc)::value, r = decltype(rc)::value;
-            xi[ft][r] += dl[ft][r];
-            tcm[r] = cm * dl[ft][r];
+        // Update of a tile's four elements as sixteen single instructions, op = 2 r + {0, 1}: xi += delta and
+        // (omega - 1) delta, which need no product of this pass; then op = 8 + 2 r + {0, 1}: the two multiply-adds
+        // of the new delta. They are dealt out evenly over the steps of the next tile.
+        auto upd_op = [&](auto ftc, auto opc) {
+            constexpr int ft = decltype(ftc)::value, op = decltype(opc)::value, r = (op & 7) >> 1;
+            if constexpr (op < 8 && (op & 1) == 0) xi[ft][r] += dl[ft][r];
+            if constexpr (op < 8 && (op & 1) == 1) tcm[r] = cm * dl[ft][r];
+            if constexpr (op >= 8 && (op & 1) == 0) tcm[r] = __builtin_fmaf(ncs, gn[ft][r], tcm[r]);
+            if constexpr (op >= 8 && (op & 1) == 1) dl[ft][r] = __builtin_fmaf(ncl, xi[ft][r], tcm[r]);
         };
-        auto upd_b = [&](auto ftc, auto rc, const f32x4 &sv) {
-            constexpr int ft = decltype(ftc)::value, r = decltype(rc)::value;
-            const float g = __builtin_fmaf(zeta, sv[r], gn[ft][r]);
-            gn[ft][r] = g;
-            dl[ft][r] = __builtin_fmaf(ncl, xi[ft][r], __builtin_fmaf(ncs, g, tcm[r]));
+        auto upd_ops = [&](auto ftc, auto fromc, auto toc) {
+            static_for<decltype(fromc)::value, decltype(toc)::value>([&](auto opc) { upd_op(ftc, opc); });
         };
-        typedef std::integral_constant<int, 0> R0;
-        typedef std::integral_constant<int, 1> R1;
-        typedef std::integral_constant<int, 2> R2;
-        typedef std::integral_constant<int, 3> R3;
         __builtin_amdgcn_sched_barrier(0);
         static_for<0, NS>([&](auto step) {
             constexpr int i = decltype(step)::value;
@@ -418,10 +421,10 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
             if constexpr (i < NT) {
                 constexpr int t = i / PER_TILE, u = i % PER_TILE;
                 if constexpr (u < 4) {
-                    s = mma16(a, dB[u], u == 0 ? zero4() : s);
-                    if constexpr (SPLIT) s = mma16(a, dR[u], s);
+                    gn[t] = mma16(a, dB[u], gn[t]);
+                    if constexpr (SPLIT) gn[t] = mma16(a, dR[u], gn[t]);
                 } else if constexpr (u < HP) {
-                    s = mma16(a, dB[u - 4], s);
+                    gn[t] = mma16(a, dB[u - 4], gn[t]);
                 } else {
                     gn[t] = mma16(a, pm[u - HP], gn[t]);
                     if constexpr (SPLIT) gn[t] = mma16(a, pmR[u - HP], gn[t]);
@@ -439,24 +442,21 @@ __device__ __forceinline__ void cheb_passes(const bf16x8 *sH, const bf16x8 *sK, 
                 constexpr int t = i / PER_TILE, u = i % PER_TILE;
                 if constexpr (t == 0 && u == 2) mask_products(std::integral_constant<int, 0>{});
                 if constexpr (t == 0 && u == 3 && NJB == 2) mask_products(std::integral_constant<int, NJB - 1>{});
-                if constexpr (u == PER_TILE - 1) sprev = s;
                 if constexpr (t >= 1) {
-                    typedef std::integral_constant<int, t - 1> FT;
-                    if constexpr (u == 0) { upd_a(FT{}, R0{}); upd_a(FT{}, R1{}); }
-                    if constexpr (u == 1) { upd_a(FT{}, R2{}); upd_a(FT{}, R3{}); }
-                    if constexpr (u == 2) { upd_b(FT{}, R0{}, sprev); upd_b(FT{}, R1{}, sprev); }
-                    if constexpr (u == 3) { upd_b(FT{}, R2{}, sprev); upd_b(FT{}, R3{}, sprev); }
+                    // step u of the tile takes the operations [16 u / PER_TILE, 16 (u + 1) / PER_TILE)
+                    upd_ops(std::integral_constant<int, t - 1>{}, std::integral_constant<int, 16 * u / PER_TILE>{},
+                            std::integral_constant<int, 16 * (u + 1) / PER_TILE>{});
                 }
             } else {
                 // key products of the next pass: the last tile's update and the new operands meanwhile
                 constexpr int k = i - NT;
                 typedef std::integral_constant<int, 7> FT;
                 if constexpr (k == 0) {
-                    upd_a(FT{}, R0{}); upd_a(FT{}, R1{}); upd_a(FT{}, R2{}); upd_a(FT{}, R3{});
+                    upd_ops(FT{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 8>{});
                     pack_delta(std::integral_constant<int, 1>{});
                 }
                 if constexpr (k == NJ) {
-                    upd_b(FT{}, R0{}, s); upd_b(FT{}, R1{}, s); upd_b(FT{}, R2{}, s); upd_b(FT{}, R3{}, s);
+                    upd_ops(FT{}, std::integral_constant<int, 8>{}, std::integral_constant<int, 16>{});
                     pack_delta(std::integral_constant<int, 2>{});
                 }
                 if constexpr (k == 2 * NJ) pack_delta(std::integral_constant<int, 3>{});
@@ -588,6 +588,14 @@ __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, c
     const float rcp = __builtin_amdgcn_rcpf(L + mu);
     const float s0 = 2.0f * rcp;
     const float rho = (L - mu) * rcp;
+    // From here on the token's system and its readout are taken divided by zeta_c (see cheb_passes): the mask
+    // becomes m[j,c] / zeta_c and the results are multiplied by zeta_c at the end. zeta_c is floored for this purpose:
+    // behind a gate that wipes the state inside the chunk, what was before it keeps a weight of 2^-60 relative to
+    // the newest key (instead of less), far below the rounding of everything else, and 1 / zeta_c stays finite.
+    s.zeta = fmaxf(s.zeta, kMinSolveZeta);
+    const float rz = 1.0f / s.zeta;
+#pragma unroll
+    for (int js = 0; js < 4; ++js) s.mreg[js] *= rz;
     f32x4 xi[8], dl[8], gn[8];
 #pragma unroll
     for (int ft = 0; ft < 8; ++ft) {
@@ -597,10 +605,10 @@ __device__ __forceinline__ void solve_tokens(Ctx &c, Solver &s, int g, int ts, c
             const float qe = s.valid ? qv[r] : 0.0f;
             xi[ft][r] = 0.0f;
             dl[ft][r] = s0 * qe;
-            gn[ft][r] = -qe;
+            gn[ft][r] = -qe * rz;
         }
     }
-    cheb_passes<NJ, SPLIT>(sH, sK, sKT, xi, dl, gn, s.mreg, s.zeta, lam, s0, rho * rho, c.a.n_iter, c.lane, [&]() {
+    cheb_passes<NJ, SPLIT>(sH, sK, sKT, xi, dl, gn, s.mreg, s0 * s.zeta, s0 * lam, rho * rho, c.a.n_iter, c.lane, [&]() {
         // v rows of the iteration's chunks replace the k rows; they land during the passes
         copy_rows(c, c.a.v, 0, c0);
         if constexpr (!SPLIT) copy_rows(c, c.a.v, 1, c0 + 1);
@@ -665,7 +673,7 @@ __device__ __forceinline__ void store_output(const Ctx &c, const Solver &s, int 
 #pragma unroll
     for (int ft = 0; ft < 8; ++ft) {
         const f32x4 ys = sY[(ts * 8 + ft) * 64 + c.lane];
-        const f32x4 y = s.zeta * ys + s.yi[ft];
+        const f32x4 y = s.zeta * (ys + s.yi[ft]);          // (yi was formed with the mask divided by zeta)
         IOBF16::store4(c.a.o, off + 16 * ft + 4 * c.kg, y[0], y[1], y[2], y[3]);
     }
 }
@@ -980,14 +988,16 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 }
 
 // Summary (prod gamma, Delta H, Delta U from a zero state) of every segment but the last: the start states of the
-// fused kernel's workgroups follow from these by a short scan. Two chunks per iteration; their k and v rows are fetched
-// one iteration ahead into registers and stored into the other half of a double buffer, so an iteration is one barrier
-// followed by wave-local work: every wave reads the transposed operands of its tiles straight from the row tiles.
+// fused kernel's workgroups follow from these by a short scan. One chunk per iteration; its k and v rows were fetched
+// kSummaryAhead iterations earlier into registers and are stored into the other half of a double buffer, so an
+// iteration is one barrier followed by wave-local work: every wave reads the transposed operands of its tiles
+// straight from the row tiles. (The kernel is bound by the latency of its loads: what counts is the bytes in flight.)
 // The tiles are padded, not swizzled: the reads of a wave's eight tiles then differ by constant offsets.
 constexpr int kSummaryRowElems = kD + MmaBF16::kRowPad;    // rows 32 bytes apart modulo 256
 constexpr int kSummaryTile = kChunk * kSummaryRowElems * 2; // bytes
-constexpr int kSummaryTables = 2 * 2 * 2 * kSummaryTile;   // offset of the waves' tables of per-token weights
-constexpr int kSummaryLds = kSummaryTables + 8 * 4 * 64 * 4;   // [buffer][chunk of the pair][k, v] row tiles + tables
+constexpr int kSummaryAhead = 2;                           // chunks whose rows are in flight
+constexpr int kSummaryTables = 2 * 2 * kSummaryTile;       // offset of the waves' tables of per-token weights
+constexpr int kSummaryLds = kSummaryTables + 8 * 4 * 64 * 4;   // [buffer][k, v] row tiles + tables
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fused_summary_kernel(FusedArgs a)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -1008,55 +1018,57 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         accH[jt] = zero4();
         accU[jt] = zero4();
     }
-    // piece i of a thread: tile (g = i / 4, which = (i / 2) % 2), 16 bytes of row (i % 2) * 32 + tid / 16
-    u32x4 regs[8];                       // (a native vector type: arrays of HIP's uint4 struct stay in memory)
-    float gm[2], bm[2];                  // gates and write gates (1 if none) of the two chunks, lane j: token j
-    auto fetch = [&](int c0) {
+    // Rows of k and v travel global memory -> registers -> padded LDS tiles, kSummaryAhead chunks ahead of their use
+    // (one stage of registers per chunk in flight). Piece i of a thread: tile (i / 2: k, v), 16 bytes of row
+    // (i % 2) * 32 + tid / 16.
+    u32x4 regs[kSummaryAhead][4];        // (a native vector type: arrays of HIP's uint4 struct stay in memory)
+    float gm[kSummaryAhead], bm[kSummaryAhead];  // gates and write gates (1 if none) of the chunks, lane j: token j
+    auto fetch = [&](auto stagec, int chunk) {
+        constexpr int st = decltype(stagec)::value;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int g = i >> 2, which = (i >> 1) & 1;
+        for (int i = 0; i < 4; ++i) {
             const int row = (i & 1) * 32 + (c.tid >> 4), piece = c.tid & 15;
-            const int tok = min((c0 + g) * kChunk + row, a.T - 1);
-            const uint16_t *x = (const uint16_t *)(which ? a.v : a.k);
-            regs[i] = *(const u32x4 *)(x + c.base_bh + (int64_t)tok * a.stride_t + 8 * piece);
+            const int tok = min(chunk * kChunk + row, a.T - 1);
+            const uint16_t *x = (const uint16_t *)((i >> 1) ? a.v : a.k);
+            regs[st][i] = *(const u32x4 *)(x + c.base_bh + (int64_t)tok * a.stride_t + 8 * piece);
         }
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-            const int64_t at = c.gate_base + (int64_t)min((c0 + g) * kChunk + c.lane, a.T - 1) * a.H;
-            gm[g] = a.gate[at];
-            bm[g] = a.beta ? a.beta[at] : 1.0f;      // (uniform branch)
-        }
+        const int64_t at = c.gate_base + (int64_t)min(chunk * kChunk + c.lane, a.T - 1) * a.H;
+        gm[st] = a.gate[at];
+        bm[st] = a.beta ? a.beta[at] : 1.0f;         // (uniform branch)
     };
     float Gseg = 0.0f;
-    fetch(chunk_begin);
+    static_for<0, kSummaryAhead>([&](auto stagec) { fetch(stagec, chunk_begin + decltype(stagec)::value); });
     int buf = 0;
 #pragma unroll 1
-    for (int c0 = chunk_begin; c0 < chunk_end; c0 += 2, buf ^= 1) {
-        refresh_lane(c);
-        unsigned char *tiles = smem + buf * (4 * kSummaryTile);
-        const PaddedRows at{kSummaryRowElems};
+    for (int c0 = chunk_begin; c0 < chunk_end; c0 += kSummaryAhead) {
+        static_for<0, kSummaryAhead>([&](auto stagec) {
+            constexpr int st = decltype(stagec)::value;
+            const int chunk = c0 + st;
+            if (chunk >= chunk_end) return;          // (uniform)
+            refresh_lane(c);
+            unsigned char *tiles = smem + buf * (2 * kSummaryTile);
+            buf ^= 1;
+            const PaddedRows at{kSummaryRowElems};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = (i & 1) * 32 + (c.tid >> 4), piece = c.tid & 15;
-            *(u32x4 *)((uint16_t *)(tiles + (i >> 1) * kSummaryTile) + at(row, 8 * piece)) = regs[i];
-        }
-        const float gm0 = gm[0], gm1 = gm[1], bm0 = bm[0], bm1 = bm[1];
-        lds_barrier();                   // the tiles are complete; the other buffer's readers are done
-        fetch(c0 + 2);                   // (past the end of the segment: harmless reads of rows that exist)
-        // (the scheduler must not sink these loads to where their data is stored, one iteration later)
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-            const bool valid = (c0 + g) * kChunk + c.lane < c.T_eff;
-            const float G = wave_inclusive_scan(valid ? log2_gate(g ? gm1 : gm0) : 0.0f, c.lane);
+            for (int i = 0; i < 4; ++i) {
+                const int row = (i & 1) * 32 + (c.tid >> 4), piece = c.tid & 15;
+                *(u32x4 *)((uint16_t *)(tiles + (i >> 1) * kSummaryTile) + at(row, 8 * piece)) = regs[st][i];
+            }
+            const float gmc = gm[st], bmc = bm[st];
+            lds_barrier();               // the tiles are complete; the other buffer's readers are done
+            fetch(stagec, chunk + kSummaryAhead);    // (past the end of the segment: harmless reads of rows that exist)
+            // (the scheduler must not sink these loads to where their data is stored, kSummaryAhead chunks later)
+            __builtin_amdgcn_sched_barrier(0);
+            const bool valid = chunk * kChunk + c.lane < c.T_eff;
+            const float G = wave_inclusive_scan(valid ? log2_gate(gmc) : 0.0f, c.lane);
             const float Gtot = lane_value(G, 63);
             Gseg += Gtot;
-            const float wj = valid ? exp2f(Gtot - G) * (g ? bm1 : bm0) : 0.0f;
+            const float wj = valid ? exp2f(Gtot - G) * bmc : 0.0f;
             const float zetaC = exp2f(Gtot);
-            const uint16_t *rowsK = (const uint16_t *)(tiles + (2 * g + 0) * kSummaryTile);
-            const uint16_t *rowsV = (const uint16_t *)(tiles + (2 * g + 1) * kSummaryTile);
+            const uint16_t *rowsK = (const uint16_t *)tiles;
+            const uint16_t *rowsV = (const uint16_t *)(tiles + kSummaryTile);
             bf16x8 wK[2], wV[2];
-            float *wtab = wave_table(c, kSummaryTables, g);
+            float *wtab = wave_table(c, kSummaryTables, buf);
             wtab[c.lane] = wj;
             own_weighted_frags(c, rowsK, wtab, wK, at);
             own_weighted_frags(c, rowsV, wtab, wV, at);
@@ -1067,15 +1079,15 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
                 accH[jt] *= zetaC;
                 accU[jt] *= zetaC;
 #pragma unroll
-                for (int st = 0; st < 2; ++st) {
-                    const int t0 = 32 * st + 4 * c.kg;
+                for (int ks = 0; ks < 2; ++ks) {
+                    const int t0 = 32 * ks + 4 * c.kg;
                     const bf16x8 kt = gather_transposed_bf16(rowsK, at, 16 * jt, c.lane, t0, t0 + 16);
-                    accH[jt] = mma16(kt, wK[st], accH[jt]);
-                    accU[jt] = mma16(kt, wV[st], accU[jt]);
+                    accH[jt] = mma16(kt, wK[ks], accH[jt]);
+                    accU[jt] = mma16(kt, wV[ks], accU[jt]);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
     }
     f32x4 *t = (f32x4 *)a.seg_buf + ((int64_t)(pair * a.n_segs + seg) * 2) * 4096 + (c.w * 8) * 64 + c.lane;
 #pragma unroll

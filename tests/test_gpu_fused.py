@@ -44,7 +44,13 @@ def test_fused_shapes_around_chunk_boundaries(T, n_iter):
     ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], n_iter, return_fro=True, return_state=True)
     y = to_host(o)
     assert np.isfinite(y).all()
-    assert pair_rel_err(y, ref) <= TOL_BF16
+    if T == 1:
+        # A single token's output is v (k . xhat), a vector times one scalar, and a pair's scale is that scalar alone:
+        # where k . q happens to be near zero (0.01 for one pair of this seed) the roundings of the operands, which
+        # are relative to |q| = 1, are large relative to it. The scale is then taken over all pairs.
+        assert np.abs(y - ref).max() <= TOL_BF16 * np.abs(ref).max()
+    else:
+        assert pair_rel_err(y, ref) <= TOL_BF16
     assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
     for name in ("H_final", "U_final"):
         assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
@@ -142,6 +148,38 @@ def test_fused_packed_variable_length_sequences():
         part["gate"][:, 0] = 0.5
         ref = oracle.forward(part["q"], part["k"], part["v"], part["gate"], part["lam"], w.n_iter)
         assert pair_rel_err(y[:, s0:s0 + n], ref) <= TOL_BF16, (s0, n)
+
+
+@pytest.mark.parametrize("variants", [False, True])
+def test_fused_strong_decay_inside_a_chunk(variants):
+    """Cumulative decays far below 2^-60 inside one chunk (a run of small gates, an exact zero, two gates of 1e-20)
+    from a non-zero initial state, with and without the layer's variants. The kernel divides a token's system by its
+    zeta_c floored at 2^-60; what the floor adds is far below the tolerance."""
+    w = synth.CFG2.scaled(B=1, H=3, T=300, n_iter=8, seed=57)
+    x = {n: a.copy() for n, a in synth.make_inputs(w).items()}
+    x["gate"][:, 20:26] = 1e-6
+    x["gate"][:, 100] = 0.0
+    x["gate"][:, 140:142, 1] = 1e-20
+    Hi, Ui = spd_state(w, 58)
+    kw, okw = {}, {}
+    if variants:
+        g = synth.make_gates(w)
+        okw = dict(beta=g["beta"], alpha=g["alpha"], lambda_scale=0.05)
+        kw = dict(beta=to_device(g["beta"], "f32"), alpha=to_device(g["alpha"], "f32"), lambda_scale=0.05)
+    import torch
+    dev = upload_inputs(x, w.dtype)
+    o, ex = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], None if variants else dev["lam"], w.n_iter,
+                                H_init=to_device(Hi, "f32"), U_init=to_device(Ui, "f32"), path=FUSED, return_fro=True,
+                                return_state=True, **kw)
+    torch.cuda.synchronize()
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], None if variants else x["lam"], w.n_iter,
+                              H_init=Hi, U_init=Ui, return_fro=True, return_state=True, **okw)
+    y = to_host(o)
+    assert np.isfinite(y).all()
+    assert pair_rel_err(y, ref) <= TOL_BF16
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
+    for name in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
 
 
 def test_fused_degenerate_values():
@@ -242,7 +280,13 @@ def test_split_shapes_around_chunk_boundaries(T, n_iter):
     ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], x["lam"], n_iter, return_fro=True, return_state=True)
     y = to_host(o)
     assert np.isfinite(y).all()
-    assert pair_rel_err(y, ref) <= TOL_BF16
+    if T == 1:
+        # A single token's output is v (k . xhat), a vector times one scalar, and a pair's scale is that scalar alone:
+        # where k . q happens to be near zero (0.01 for one pair of this seed) the roundings of the operands, which
+        # are relative to |q| = 1, are large relative to it. The scale is then taken over all pairs.
+        assert np.abs(y - ref).max() <= TOL_BF16 * np.abs(ref).max()
+    else:
+        assert pair_rel_err(y, ref) <= TOL_BF16
     assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 5e-3 * rex["fro"].max()
     for name in ("H_final", "U_final"):
         assert np.abs(to_host(ex[name]) - rex[name]).max() <= 5e-3 * np.abs(rex[name]).max(), name
