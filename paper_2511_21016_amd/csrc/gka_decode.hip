@@ -186,7 +186,8 @@ __global__ __launch_bounds__(DecodeShape<D>::NTHR) void decode_step_kernel(Decod
 #pragma unroll
         for (int e = 0; e < 4; ++e) xc[e] = s_x[4 * col4 + e];
         // (streamed U: four pieces in flight; all sixteen would not fit beside H)
-#pragma unroll(STREAM_U ? 4 : ITS)
+        constexpr int kReadoutUnroll = STREAM_U ? 4 : ITS;
+#pragma unroll kReadoutUnroll
         for (int it = 0; it < ITS; ++it) {
             f32x4 u;
             if constexpr (STREAM_U) {

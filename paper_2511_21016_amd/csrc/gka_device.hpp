@@ -180,6 +180,38 @@ __device__ __forceinline__ void async_copy16_to_lds(void *lds_wave_base, buffer_
 }
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 
+// The same copy as an assembly statement, which the compiler does not track: it neither orders later LDS accesses
+// of the wave behind it (for a copy it knows of it does, whichever part of LDS they touch) nor counts it in the
+// vector-memory waits it inserts (those then wait for more than they need, never for less: the counter retires in
+// issue order). The caller waits for the copy itself, with wait_vector_memory_but<N> where at least N vector-memory
+// instructions of the wave are certain to follow it, and passes a barrier before other waves read the data.
+// `rsrc`: the four words of a raw buffer descriptor over the source (wave-uniform); `lds_wave_addr`: LDS byte
+// address of the wave's 1 KiB destination (wave-uniform; it travels through M0).
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4 raw_buffer_words(const void *base)
+{
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    return i32x4{(int32_t)(uint32_t)b, (int32_t)((uint32_t)(b >> 32) & 0xffffu), 0x7fffffff, 0x00020000};
+}
+__device__ __forceinline__ void async_copy16_to_lds_untracked(uint32_t lds_wave_addr, i32x4 rsrc, int lane_byte_offset)
+{
+    // (M0 is put back: the compiler does not take a clobber of it into account)
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "buffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "s"(lds_wave_addr), "v"(lane_byte_offset), "s"(rsrc)
+                 : "memory");
+}
+// At most N vector-memory instructions of this wave are still outstanding: everything issued before the last N has
+// completed.
+template <int N>
+__device__ __forceinline__ void wait_vector_memory_but()
+{
+    static_assert(N >= 0 && N < 64, "the counter holds 6 bits");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // Workgroup barrier that orders LDS traffic only: this wave's LDS operations have completed (lgkmcnt(0)), then
 // s_barrier. Unlike __syncthreads() it carries no global-memory fence, so vector-memory loads that are still in
 // flight (prefetches for later steps) are not waited for.

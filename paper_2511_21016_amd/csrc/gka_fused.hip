@@ -97,6 +97,7 @@ __device__ __forceinline__ float sum_over_kg(float x)
 // U is needed only for the state part of the readout and its own update, once per iteration; in between it is
 // parked in a scratch block of this workgroup in global memory (1 KiB per wave and tile, written and read by the same
 // lanes), so that the passes have its registers.
+constexpr int kParkStores = 8;           // vector-memory instructions of park_store
 __device__ __forceinline__ void park_store(f32x4 *slot, const f32x4 (&acc)[8])
 {
 #pragma unroll
@@ -684,11 +685,11 @@ __device__ __forceinline__ void store_output(const Ctx &c, const Solver &s, int 
 // (four rows) per wave instruction; the lane picks the 16 source bytes that belong at its place of the swizzled row.
 // Rows past the end of the sequence repeat the last row (finite values that only ever meet zero weights or masked
 // products). The copies complete in the background; the compiler waits for them before the next LDS read it knows of.
-__device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, int chunk)
+template <bool UNTRACKED = false>
+__device__ __forceinline__ void copy_rows_impl(const Ctx &c, const void *x, int g, int chunk)
 {
     const int tok_base = min(chunk * kChunk, c.a.T - 1);
     const uint16_t *base = (const uint16_t *)x + c.base_bh + (int64_t)tok_base * c.a.stride_t;
-    const buffer_rsrc rsrc = make_raw_buffer(base);
     const int last_row = c.a.T - 1 - tok_base;
     const int row_bytes = (int)c.a.stride_t * 2;
 #pragma unroll
@@ -696,8 +697,23 @@ __device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, in
         const int i = c.w + 8 * h;
         const int row = 4 * i + (c.lane >> 4);
         const int sbyte = ((c.lane & 15) * 16) ^ ((row & 7) << 5);
-        async_copy16_to_lds((char *)lds_rows(c, g) + i * 1024, rsrc, min(row, last_row) * row_bytes + sbyte, 0);
+        const int off = min(row, last_row) * row_bytes + sbyte;
+        if constexpr (UNTRACKED) {
+            async_copy16_to_lds_untracked(lds_address((char *)lds_rows(c, g) + i * 1024), raw_buffer_words(base), off);
+        } else {
+            async_copy16_to_lds((char *)lds_rows(c, g) + i * 1024, make_raw_buffer(base), off, 0);
+        }
     }
+}
+__device__ __forceinline__ void copy_rows(const Ctx &c, const void *x, int g, int chunk)
+{
+    copy_rows_impl<false>(c, x, g, chunk);
+}
+// The same as copies that the compiler does not track (see async_copy16_to_lds_untracked): for the k rows of the
+// next iteration, which are issued in the middle of an iteration and awaited at the top of the next.
+__device__ __forceinline__ void copy_rows_untracked(const Ctx &c, const void *x, int g, int chunk)
+{
+    copy_rows_impl<true>(c, x, g, chunk);
 }
 
 // A fragments of the keys of both chunks from their row tiles: rows (K[js][fb]) and transposed (KT[ft][jb]); each
@@ -842,6 +858,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         }
     };
     fetch_beta(chunk_begin);
+    wait_all_memory();                   // the first k rows (the loop's own wait counts on a whole iteration before it)
 #pragma unroll 1
     for (int c0 = chunk_begin; c0 < chunk_end; c0 += kChunksPerIter) {
         // Addresses are formed anew in every iteration from a copy of the lane index that the compiler cannot trace
@@ -866,7 +883,11 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             }
         };
         gate_scans();
-        wait_all_memory();               // this wave's copies of k rows have landed
+        // This wave's copies of the k rows have landed: they were issued before the loads of these gates and before
+        // the kParkStores stores of U that every wave issues in every iteration, so once no more than that many
+        // vector-memory instructions are outstanding the copies are complete. (The stores of the last tokens, which
+        // follow, need not be: waiting for them cost 3 % of the step.)
+        wait_vector_memory_but<kParkStores>();
         lds_barrier();                   // ... and everybody else's
         // ---- 2
         // this wave's table of the chunks' per-token scalars: in a part of LDS that is free until the next barrier
@@ -948,6 +969,10 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), wave_table(c, kTabAfter, 1), wVB);
         lds_barrier();                   // xhat of the chunks is visible; the key-row fragments are dead
         // ---- 6
+        // k rows of the next chunks: the row tiles are free from here on (every wave has formed its v fragments); the
+        // copies land during the readout
+        copy_rows_untracked(c, a.k, 0, c0 + kChunksPerIter);
+        if constexpr (!SPLIT) copy_rows_untracked(c, a.k, 1, c0 + 3);
         // gates of the next chunks
         gmA = a.gate[c.gate_base + (int64_t)min((c0 + kChunksPerIter) * kChunk + c.lane, a.T - 1) * a.H];
         if constexpr (!SPLIT) gmB = a.gate[c.gate_base + (int64_t)min((c0 + 3) * kChunk + c.lane, a.T - 1) * a.H];
@@ -967,10 +992,6 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             // ---- 8
             if (grp == 1) store_output(c, s, ts, kOffH);
         }
-        // k rows of the next chunks: the row tiles are free since the barrier before the readout; the copies land
-        // while the next iteration publishes H and scans its gates
-        copy_rows(c, a.k, 0, c0 + kChunksPerIter);
-        if constexpr (!SPLIT) copy_rows(c, a.k, 1, c0 + 3);
     }
     wait_all_memory();               // no copy into this workgroup's LDS may be in flight when it ends
 
