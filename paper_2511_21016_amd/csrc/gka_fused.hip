@@ -865,44 +865,53 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         // back: hoisted out of the loop they would occupy registers across the passes (or be spilled and reloaded).
         refresh_lane(c);
         // ---- 1
-        // gates of the chunks (fetched during the previous iteration): lane j holds G_j, the weight of token j in the
-        // chunk's update 2^(G_C - G_j), and the chunk's decay
-        float GA, GB = 0.0f, wjA, wjB = 0.0f, zetaA, zetaB = 1.0f;
-        auto gate_scans = [&]() {
-            const bool vA = c0 * kChunk + c.lane < c.T_eff;
-            GA = wave_inclusive_scan(vA ? log2_gate(gmA) : 0.0f, c.lane);
-            const float GtA = lane_value(GA, 63);
-            wjA = vA ? exp2f(GtA - GA) * bmA : 0.0f;
-            zetaA = exp2f(GtA);
-            if constexpr (!SPLIT) {
-                const bool vB = (c0 + 1) * kChunk + c.lane < c.T_eff;
-                GB = wave_inclusive_scan(vB ? log2_gate(gmB) : 0.0f, c.lane);
-                const float GtB = lane_value(GB, 63);
-                wjB = vB ? exp2f(GtB - GB) * bmB : 0.0f;
-                zetaB = exp2f(GtB);
-            }
-        };
-        gate_scans();
-        // This wave's copies of the k rows have landed: they were issued before the loads of these gates and before
-        // the kParkStores stores of U that every wave issues in every iteration, so once no more than that many
-        // vector-memory instructions are outstanding the copies are complete. (The stores of the last tokens, which
-        // follow, need not be: waiting for them cost 3 % of the step.)
-        wait_vector_memory_but<kParkStores>();
-        lds_barrier();                   // ... and everybody else's
-        // ---- 2
-        // this wave's table of the chunks' per-token scalars: in a part of LDS that is free until the next barrier
-        // (the second chunk's H_[n]; SPLIT: the second chunk's key fragments, which do not exist)
+        // Gates of the chunks (fetched during the previous iteration): G_j, the weight of token j in the chunk's
+        // update 2^(G_C - G_j) (times its write gate), and the chunk's decay 2^(G_C). Before the passes one wave per
+        // chunk scans (waves 0 and 1: among the first to arrive here, while others still store their tokens) and
+        // leaves the per-token scalars in a table that all waves read after the barrier; slots of 64 floats: weights
+        // of A, of B, G of A, of B, write gates of A, of B. The table lies in a part of LDS that is free from the last
+        // barrier of the previous iteration to the second of this one (the second chunk's H_[n]; SPLIT: the second
+        // chunk's key fragments, which do not exist).
         constexpr int kTabBefore = SPLIT ? kOffK + 16384 : kOffH + 32768;
         constexpr int kTabAfter = kOffK + 16384;             // after the passes: the key-row fragments are dead
-        wave_table(c, kTabBefore, 0)[c.lane] = wjA;
-        wave_table(c, kTabBefore, 2)[c.lane] = grp ? GB : GA;
-        if constexpr (!SPLIT) wave_table(c, kTabBefore, 1)[c.lane] = wjB;
-        if constexpr (GATED) wave_table(c, kTabBefore, 3)[c.lane] = grp ? bmB : bmA;
+        float *gtab = (float *)(smem + kTabBefore);
+        auto scan_chunk = [&](float gm, float bm, int chunk, float &wj, float &zeta) {
+            const bool valid = chunk * kChunk + c.lane < c.T_eff;
+            const float G = wave_inclusive_scan(valid ? log2_gate(gm) : 0.0f, c.lane);
+            const float Gt = lane_value(G, 63);
+            wj = valid ? exp2f(Gt - G) * bm : 0.0f;
+            zeta = exp2f(Gt);
+            return G;
+        };
+        float wjA, wjB = 0.0f, zetaA, zetaB = 1.0f;
+        if (c.w == 0) {
+            const float GA = scan_chunk(gmA, bmA, c0, wjA, zetaA);
+            gtab[0 * 64 + c.lane] = wjA;
+            gtab[2 * 64 + c.lane] = GA;
+            if constexpr (GATED) gtab[4 * 64 + c.lane] = bmA;
+        }
+        if constexpr (!SPLIT) {
+            if (c.w == 1) {
+                const float GB = scan_chunk(gmB, bmB, c0 + 1, wjB, zetaB);
+                gtab[1 * 64 + c.lane] = wjB;
+                gtab[3 * 64 + c.lane] = GB;
+                if constexpr (GATED) gtab[5 * 64 + c.lane] = bmB;
+            }
+        }
+        // This wave's copies of the k rows have landed: they were issued before the kParkStores stores of U that
+        // every wave issues in every iteration, so once no more than that many vector-memory instructions are
+        // outstanding the copies are complete. (The stores of the last tokens, which follow, need not be: waiting
+        // for them cost 3 % of the step.)
+        wait_vector_memory_but<kParkStores>();
+        lds_barrier();                   // ... and everybody else's; the table is complete
+        // ---- 2
+        zetaA = exp2f(gtab[2 * 64 + 63]);
+        if constexpr (!SPLIT) zetaB = exp2f(gtab[3 * 64 + 63]);
         const float hnA = publish_H<SPLIT>(c, accH, 0);
         build_key_frags<SPLIT>(c);
         bf16x8 wBA[2], wBB[2];
-        own_weighted_frags(c, lds_rows(c, 0), wave_table(c, kTabBefore, 0), wBA);
-        if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), wave_table(c, kTabBefore, 1), wBB);
+        own_weighted_frags(c, lds_rows(c, 0), gtab, wBA);
+        if constexpr (!SPLIT) own_weighted_frags(c, lds_rows(c, 1), gtab + 64, wBB);
         // solver inputs of this lane's token
         f32x4 accU[8];
         Solver s;
@@ -915,7 +924,7 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
             for (int ft = 0; ft < 8; ++ft) qraw[ft] = IOBF16::load_raw4(a.q, tok_off + 16 * ft + 4 * c.kg);
             if (!GATED || a.lambda) lam = a.lambda[c.gate_base + (int64_t)min(s.tok, a.T - 1) * a.H];
-            build_mask<GATED>(c, s, wave_table(c, kTabBefore, 2), wave_table(c, kTabBefore, 3), ts);
+            build_mask<GATED>(c, s, gtab + (2 + grp) * 64, gtab + (4 + grp) * 64, ts);
         }
         lds_barrier();
         // ---- 3
@@ -957,10 +966,12 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
             lds_barrier();
             park_load(c.park, accU);
         }
-        // (the gates are scanned again rather than kept across the passes: two registers instead of six; an opaque
-        // copy keeps the compiler from merging the two scans)
+        // (after the passes every wave scans the gates for itself: no barrier separates this from the use of the
+        // results, and the raw gates cost two registers across the passes; the opaque copy keeps the compiler from
+        // merging these scans with those of waves 0 and 1 above)
         asm volatile("" : "+v"(gmA), "+v"(gmB));
-        gate_scans();
+        scan_chunk(gmA, bmA, c0, wjA, zetaA);
+        if constexpr (!SPLIT) scan_chunk(gmB, bmB, c0 + 1, wjB, zetaB);
         // this wave's weighted v fragments of the chunks
         bf16x8 wVA[2], wVB[2];
         wave_table(c, kTabAfter, 0)[c.lane] = wjA;
