@@ -513,16 +513,22 @@ __device__ __forceinline__ void frobenius_terms(const Ctx &c, const Solver &s, i
     f32x4 kc[8];
 #pragma unroll
     for (int fb = 0; fb < 4; ++fb) unpack8(kB[0][fb], kc[2 * fb], kc[2 * fb + 1]);
-    // k_c^T H_[n] k_c
+    // k_c^T H_[n] k_c (the fragments of the next tile are requested before the products of this one: the scheduler
+    // would otherwise sink the reads to their uses, one LDS round trip per tile)
     f32x4 dot = zero4();
+    bf16x8 a[2][4];
+#pragma unroll
+    for (int fb = 0; fb < 4; ++fb) a[0][fb] = sH[fb * 64];
 #pragma unroll
     for (int ft = 0; ft < 8; ++ft) {
-        bf16x8 a[4];
+        if (ft + 1 < 8) {
 #pragma unroll
-        for (int fb = 0; fb < 4; ++fb) a[fb] = sH[(ft * 4 + fb) * 64];
+            for (int fb = 0; fb < 4; ++fb) a[(ft + 1) & 1][fb] = sH[((ft + 1) * 4 + fb) * 64];
+        }
+        __builtin_amdgcn_sched_barrier(0);
         f32x4 acc = zero4();
 #pragma unroll
-        for (int fb = 0; fb < 4; ++fb) acc = mma16(a[fb], kB[0][fb], acc);
+        for (int fb = 0; fb < 4; ++fb) acc = mma16(a[ft & 1][fb], kB[0][fb], acc);
         dot += acc * kc[ft];
     }
     float a_part = dot[0] + dot[1] + dot[2] + dot[3];
