@@ -249,8 +249,9 @@ gka_status gka_decode_tokens(const gka_params *p,
  * with bf16 tensors and operands; the paper's chunk-wise backward kernels are not reproduced.
  *   Supported: lambda given or NULL with p->lambda_scale > 0 (the rule lambda_t = a ||H_t||_F, whose w_t H_t terms
  *   of the Lemma in Section 4.2.2 cost two more readouts), zero initial states (gka_backward_from_state takes
- *   others), packed tensors (explicit strides:
- *   GKA_ERR_UNSUPPORTED), p->beta and p->alpha as in gka_forward. Packed sequences (a gate of 0 at a sequence's first token) are handled:
+ *   others), p->beta and p->alpha as in gka_forward. Explicit strides apply to q, k, v and dy (multiples of 16
+ *   bytes; they are copied into the packed layout first: four more tensors of workspace); the gradients are always
+ *   written packed. Packed sequences (a gate of 0 at a sequence's first token) are handled:
  *   dgate at such a gate is written as 0 (the formula divides by the gate), and the cumulative sum behind dgate
  *   restarts there.
  *   q, k, v, dy  [B,T,H,d] io_dtype, 16-byte aligned;  gate, lambda [B,T,H] float32

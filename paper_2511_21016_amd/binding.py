@@ -283,21 +283,26 @@ def backward_from_state_raw(params, q, k, v, gate, lam, dy, H_init, U_init, dq, 
 
 
 def gka_backward(q, k, v, gate, lam, dy, n_iter, *, compute=None, beta=None, alpha=None, lambda_scale=0.0,
-                 workspace=None, H_init=None, U_init=None, return_state_grads=False):
+                 workspace=None, H_init=None, U_init=None, return_state_grads=False, shape=None, strides=(0, 0, 0)):
     """gka_backward on torch CUDA tensors (packed [B,T,H,d] / [B,T,H]). lam None: the rule
     lambda_t = lambda_scale ||H_t||_F. Returns a dict of float32 gradients: dq, dk, dv, dgate, dlam (when lam is
     given) and, when given, dbeta, dalpha. H_init, U_init [B,H,d,d] float32: the sequence continues from these states
-    (gka_backward_from_state); return_state_grads: also dH_init, dU_init."""
+    (gka_backward_from_state); return_state_grads: also dH_init, dU_init. shape = (B, T, H, d) with strides = element
+    strides (batch, token, head): q, k, v, dy are stored in another layout with a contiguous head dimension (the
+    gradients come back packed [B,T,H,d])."""
     import torch
-    B, T, H, d = q.shape
-    for x in (q, k, v, dy):
-        if not x.is_contiguous():
-            raise ValueError("gka_backward takes packed tensors")
+    if shape is None:
+        B, T, H, d = q.shape
+        for x in (q, k, v, dy):
+            if not x.is_contiguous():
+                raise ValueError("gka_backward takes packed tensors unless shape and strides are given")
+    else:
+        B, T, H, d = shape
     io = _io_dtype(q)
     if compute is None:
         compute = GKA_COMPUTE_BF16 if io == GKA_BF16 else GKA_COMPUTE_F32
     params = make_params(B, H, T, d, n_iter, io, compute, lambda_scale=lambda_scale, beta=_ptr(beta),
-                         alpha=_ptr(alpha))
+                         alpha=_ptr(alpha), strides=strides)
     nbytes = backward_workspace_bytes(params)
     if workspace is None:
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=q.device)

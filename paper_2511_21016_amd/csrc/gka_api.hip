@@ -452,6 +452,8 @@ struct BackwardPlan {
     size_t off_m[6];          // gate_rev, zeros, s, fro, c, C
     size_t off_fin[3];        // final states of three reverse readouts (gradients at the initial states)
     size_t off_fwd, fwd_bytes, total;
+    bool strided;             // q, k, v, dy come with explicit strides
+    size_t off_pack[4];       // their packed copies
 };
 enum { IO_Y, IO_DXT, IO_RHS, IO_HX, IO_X, IO_XT, IO_KR, IO_VR, IO_DYR, IO_XR, IO_PR, IO_XTR, IO_R1, IO_R2, IO_R3, IO_R4,
        IO_SCRATCH, IO_HK, IO_VPR, IO_R5, IO_RHS_LO, IO_X_LO, IO_XT_LO };
@@ -461,12 +463,21 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     gka_status s = check_common(p, false);
     if (s != GKA_OK) return s;
     if (!chunked_dim(p->d_k) || p->path == GKA_PATH_RECURRENT) return GKA_ERR_UNSUPPORTED;
-    if (p->stride_b != 0 || p->stride_t != 0 || p->stride_h != 0) return GKA_ERR_UNSUPPORTED;
     if (p->phase != GKA_PHASE_ALL || p->compute == GKA_COMPUTE_BF16_SPLIT) return GKA_ERR_UNSUPPORTED;
     bp->n_tokens = (size_t)p->B * p->T * p->H;
     bp->n_elems = bp->n_tokens * p->d_k;
     bp->esz = p->io_dtype == GKA_BF16 ? 2 : 4;
+    // Strided q, k, v, dy are copied into the packed layout first (four tensors at the head of the workspace): every
+    // kernel of the pass works on packed tensors.
+    bp->strided = p->stride_b != 0 || p->stride_t != 0 || p->stride_h != 0;
     size_t off = 0;
+    if (bp->strided) {
+        const int64_t align = 16 / (int64_t)bp->esz;         // rows are copied 16 bytes at a time
+        if (p->stride_b <= 0 || p->stride_t <= 0 || p->stride_h <= 0) return GKA_ERR_SHAPE;
+        if (p->stride_h < p->d_k && p->H > 1) return GKA_ERR_SHAPE;
+        if (p->stride_b % align || p->stride_t % align || p->stride_h % align) return GKA_ERR_SHAPE;
+        for (int i = 0; i < 4; ++i) { bp->off_pack[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
+    }
     for (int i = 0; i < 9; ++i) { bp->off_f32[i] = off; off = align_up(off + bp->n_elems * 4, 256); }
     for (int i = 0; i < 23; ++i) { bp->off_io[i] = off; off = align_up(off + bp->n_elems * bp->esz, 256); }
     for (int i = 0; i < 6; ++i) { bp->off_m[i] = off; off = align_up(off + bp->n_tokens * 4, 256); }
@@ -477,6 +488,7 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     bp->off_fwd = off;
     gka_params pf = *p;
     pf.xhat_out = nullptr;
+    pf.stride_b = pf.stride_t = pf.stride_h = 0;
     Plan full, plain;                              // the plain readouts cut the scan into more segments
     if (make_plan(&pf, &full) != GKA_OK || make_plan(&pf, &plain, true) != GKA_OK) return GKA_ERR_SHAPE;
     bp->fwd_bytes = full.total > plain.total ? full.total : plain.total;
@@ -524,6 +536,19 @@ gka_status gka_backward_from_state(const gka_params *p, const void *q, const voi
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < bp.total) return GKA_ERR_WORKSPACE;
     hipStream_t stream = (hipStream_t)hip_stream;
     unsigned char *ws = (unsigned char *)workspace;
+    gka_params packed_params;
+    if (bp.strided) {
+        const void *src[4] = {q, k, v, dy};
+        for (int i = 0; i < 4; ++i) {
+            if (gka::launch_pack_rows(src[i], ws + bp.off_pack[i], p->B, p->T, p->H, p->d_k, (int)bp.esz, p->stride_b,
+                                      p->stride_t, p->stride_h, stream) != hipSuccess)
+                return GKA_ERR_LAUNCH;
+        }
+        q = ws + bp.off_pack[0]; k = ws + bp.off_pack[1]; v = ws + bp.off_pack[2]; dy = ws + bp.off_pack[3];
+        packed_params = *p;
+        packed_params.stride_b = packed_params.stride_t = packed_params.stride_h = 0;
+        p = &packed_params;
+    }
     auto io = [&](int i) { return (void *)(ws + bp.off_io[i]); };
     float *xf = (float *)(ws + bp.off_f32[0]), *pf32 = (float *)(ws + bp.off_f32[1]);
     auto f32buf = [&](int i) { return (float *)(ws + bp.off_f32[i]); };

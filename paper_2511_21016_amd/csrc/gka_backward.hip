@@ -330,6 +330,36 @@ static void launch_glue_t(const BackwardGlueArgs &a, int which, hipStream_t stre
     }
 }
 
+// Rows of a strided [B,T,H,d] tensor (head dimension contiguous, 16-byte aligned rows) to the packed layout, 16 bytes
+// per thread.
+__global__ __launch_bounds__(256) void pack_rows_kernel(const unsigned char *src, unsigned char *dst, int64_t n_pieces,
+                                                        int pieces_per_row, int T, int H, int64_t stride_b_bytes,
+                                                        int64_t stride_t_bytes, int64_t stride_h_bytes)
+{
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int64_t piece = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (piece >= n_pieces) return;
+    const int64_t row = piece / pieces_per_row;
+    const int part = (int)(piece - row * pieces_per_row);
+    const int h = (int)(row % H);
+    const int64_t bt = row / H;
+    const int t = (int)(bt % T);
+    const int64_t b = bt / T;
+    const unsigned char *from = src + b * stride_b_bytes + t * stride_t_bytes + h * stride_h_bytes + (int64_t)part * 16;
+    *(u32x4 *)(dst + piece * 16) = *(const u32x4 *)from;
+}
+
+hipError_t launch_pack_rows(const void *src, void *dst, int B, int T, int H, int d, int elem_bytes, int64_t stride_b,
+                            int64_t stride_t, int64_t stride_h, hipStream_t stream)
+{
+    const int pieces_per_row = d * elem_bytes / 16;
+    const int64_t n_pieces = (int64_t)B * T * H * pieces_per_row;
+    hipLaunchKernelGGL(pack_rows_kernel, dim3((unsigned)((n_pieces + 255) / 256)), dim3(256), 0, stream,
+                       (const unsigned char *)src, (unsigned char *)dst, n_pieces, pieces_per_row, T, H,
+                       stride_b * elem_bytes, stride_t * elem_bytes, stride_h * elem_bytes);
+    return hipGetLastError();
+}
+
 hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf16, hipStream_t stream)
 {
     if (io_bf16) launch_glue_t<IOBF16>(a, which, stream);

@@ -106,6 +106,9 @@ struct BackwardGlueArgs {
 // which: 0 mix, 1 right-hand side, 2 reverse, 3 combine, 4 gate scan, 5 rule scalars (c_t), 6 rule scan (C_t),
 // 7 gradients at the initial states
 hipError_t launch_backward_glue(const BackwardGlueArgs &a, int which, bool io_bf16, hipStream_t stream);
+// Copy of a strided [B,T,H,d] tensor (element strides; rows 16-byte aligned) into the packed layout.
+hipError_t launch_pack_rows(const void *src, void *dst, int B, int T, int H, int d, int elem_bytes, int64_t stride_b,
+                            int64_t stride_t, int64_t stride_h, hipStream_t stream);
 
 // Gated-linear-attention readout y_t = U_t q_t, U_t = gate_t U_{t-1} + beta_t v_t k_t^T with the state in registers
 // (bf16 tensors, packed or strided like the forward pass's; U is dv x dk). reverse: the recurrence runs from the last token to

@@ -245,6 +245,32 @@ def test_backward_from_initial_states(compute, rule, variants):
         assert max(errs[n] for n in ("dq", "dv", "dU_init")) <= 2e-3, errs
 
 
+@pytest.mark.parametrize("dtype,rule", [("bf16", False), ("f32", True)])
+def test_backward_strided_head_major_layout(dtype, rule):
+    """q, k, v, dy stored [B,H,T,d] and passed through the stride arguments: the same bits as from packed tensors
+    (the pass packs them first), gradients returned packed."""
+    import torch
+    base = synth.CFG2 if dtype == "bf16" else synth.CFG1
+    w = base.scaled(B=2, H=3, T=130, d=128 if dtype == "bf16" else 64, n_iter=6, seed=1717)
+    x = synth.make_inputs(w)
+    rng = np.random.default_rng(w.seed + 3)
+    dy = rng.standard_normal(x["v"].shape).astype(np.float32)
+    if dtype == "bf16":
+        dy = synth.round_to_bf16(dy)
+    dev = upload_inputs(x, w.dtype)
+    dyd = to_device(dy, dtype)
+    lam = None if rule else dev["lam"]
+    kw = dict(lambda_scale=0.05) if rule else {}
+    ref = binding.gka_backward(dev["q"], dev["k"], dev["v"], dev["gate"], lam, dyd, w.n_iter, **kw)
+    tr = {n: t.permute(0, 2, 1, 3).contiguous() for n, t in (("q", dev["q"]), ("k", dev["k"]), ("v", dev["v"]), ("dy", dyd))}
+    out = binding.gka_backward(tr["q"], tr["k"], tr["v"], dev["gate"], lam, tr["dy"], w.n_iter,
+                               shape=(w.B, w.T, w.H, w.d), strides=(w.H * w.T * w.d, w.d, w.T * w.d), **kw)
+    torch.cuda.synchronize()
+    assert set(out) == set(ref)
+    for n in ref:
+        assert torch.equal(out[n], ref[n]), n
+
+
 def test_backward_from_state_argument_checks():
     import torch
     w = synth.CFG1.scaled(B=1, H=1, T=64, d=64)

@@ -110,13 +110,16 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     # backward: workspace query and argument checks
     bws = binding.backward_workspace_bytes(_p())
     assert bws > ok_ws and bws % 256 == 0
-    assert binding.backward_workspace_bytes(_p(strides=(1 << 20, 2048, 128))) == 0
+    # strided inputs are packed into four more tensors at the head of the workspace
+    assert binding.backward_workspace_bytes(_p(strides=(1 << 20, 2048, 128))) == bws + 4 * 2 * 100 * 2 * 128 * 2
+    assert binding.backward_workspace_bytes(_p(strides=(1 << 20, 2048, 132))) == 0       # rows not 16-byte aligned
     bw = lambda p, **kw: binding.backward_raw(p, *[kw.get(n, fake) for n in ("q", "k", "v", "gate", "lam", "dy", "dq",
                                                                             "dk", "dv", "dgate")],
                                               workspace=kw.get("ws", 0x100000), workspace_bytes=kw.get("ws_bytes", bws))
     assert bw(_p(), dy=None) == binding.GKA_ERR_NULL
     assert bw(_p(), lam=None) == binding.GKA_ERR_NULL                 # no lambda and no rule (lambda_scale = 0)
-    assert bw(_p(strides=(1 << 20, 2048, 128))) == binding.GKA_ERR_UNSUPPORTED
+    assert bw(_p(strides=(1 << 20, 2048, 132))) == binding.GKA_ERR_SHAPE
+    assert bw(_p(strides=(1 << 20, 2048, 128))) == binding.GKA_ERR_WORKSPACE        # valid: needs the larger workspace
     assert bw(_p(), ws_bytes=bws - 1) == binding.GKA_ERR_WORKSPACE
     assert bw(_p(d=96)) == binding.GKA_ERR_UNSUPPORTED
     assert bw(_p(d=16)) == binding.GKA_ERR_UNSUPPORTED                # the backward pass runs on the chunk-wise kernels
