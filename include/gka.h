@@ -144,7 +144,8 @@ typedef struct {
  * chunks at a time: large problems are processed as a sequence of such launches, the running states
  * carried from slab to slab in float32, so that the workspace stays bounded (about 1 GiB of chunk
  * states; p->slab_state_bytes overrides that budget). The fused kernel (gka_path) needs only the segment summaries
- * of its chunk walk; the query returns the larger of the two sizes. Its contents after a call are unspecified. */
+ * of its chunk walk; the query returns the larger of the two sizes. The token-by-token path (GKA_PATH_RECURRENT) keeps
+ * its states in registers: 256 bytes, plus one U state per pair at d = 256. Its contents after a call are unspecified. */
 size_t gka_forward_workspace_bytes(const gka_params *p);
 
 /* Whole-sequence forward, Eq. (CH).
