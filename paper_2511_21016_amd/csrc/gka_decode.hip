@@ -10,7 +10,7 @@
 // i = it*RPI + t / C4 and columns 4*(t % C4) .. +3 (C4 = d/4 pieces per row, RPI = NTHR/C4 rows per sweep).
 // H is symmetric, so H x is evaluated column-wise, (H x)_j = sum_i H[i][j] x_i: every thread accumulates
 // its rows into its four columns, and the NTHR/C4 partial sums per column are combined through LDS.
-// NTHR = 256 threads; 64 for d = 16 (64 pieces); 1024 for d = 256, where a thread holds 16 pieces of H and U does
+// NTHR = 256 threads (d = 16 has a kernel of its own below); 1024 for d = 256, where a thread holds 16 pieces of H and U does
 // not fit beside them: U is then streamed, each piece read, advanced, used for the readout and written back
 // once per token (STREAM_U).
 #include "gka_device.hpp"
@@ -20,7 +20,7 @@ namespace gka {
 
 template <int D>
 struct DecodeShape {
-    static constexpr int NTHR = D == 16 ? 64 : (D == 256 ? 1024 : 256);
+    static constexpr int NTHR = D == 256 ? 1024 : 256;
     static constexpr int C4 = D / 4, RPI = NTHR / C4, ITS = D / RPI, NW = NTHR / 64;
     static constexpr bool STREAM_U = D == 256;
     static_assert(ITS * NTHR * 4 == D * D && ITS >= 1 && RPI * C4 == NTHR, "every thread holds ITS pieces of a state");
@@ -214,6 +214,101 @@ __global__ __launch_bounds__(DecodeShape<D>::NTHR) void decode_step_kernel(Decod
     }
 }
 
+// Head dimension 16 (the vision models of Appendix L: many pairs, short sequences): one wave per pair and no LDS. A
+// state is 64 float4 pieces, lane l holds columns 4 (l % 4) .. + 3 of row l / 4 of H and of U; per-component
+// quantities of the solve (xi, delta, residual) live in the four lanes of the component's row. A product H x is taken
+// row-wise: the lane's four elements times the four components of x it needs (fetched from the lanes that hold them by
+// lane shuffles), then a sum over the four lanes of the row. Four pairs share a workgroup only to fill it; the waves
+// never synchronise. The arithmetic is that of decode_step_kernel in another order of summation.
+template <class IO>
+__global__ __launch_bounds__(256) void decode_step_kernel_d16(DecodeArgs a, int n_pairs)
+{
+    constexpr int D = 16;
+    const int lane = threadIdx.x & 63;
+    const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (pair >= n_pairs) return;                 // (wave-uniform)
+    const int r = lane >> 2, c4 = lane & 3;
+    const int T = a.T;
+    const int64_t state_off = (int64_t)pair * D * D + lane * 4;
+    const int b = pair / a.H, h = pair - b * a.H;
+    f32x4 hreg = {0.0f, 0.0f, 0.0f, 0.0f}, ureg = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (a.H_in) hreg = *(const f32x4 *)(a.H_in + state_off);
+    if (a.U_in) ureg = *(const f32x4 *)(a.U_in + state_off);
+    // the components 4 c4 .. 4 c4 + 3 of a vector whose component i is held by the lanes of row i
+    auto my_columns = [&](float x, float (&out)[4]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[e] = __shfl(x, (4 * c4 + e) * 4, 64);
+    };
+    // sum over the four lanes of a row (a quad): two cross-lane moves within quads
+    auto row_sum = [&](float x) {
+        x += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+        x += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+        return x;
+    };
+    // inputs of a token are fetched while the token before it is solved
+    struct TokenIn { float q, k, v, gamma, beta, alpha, lam; };
+    auto fetch = [&](int tok) {
+        const int64_t bth = ((int64_t)b * T + tok) * a.H + h;
+        const int64_t row0 = b * a.stride_b + tok * a.stride_t + h * a.stride_h;
+        TokenIn t;
+        t.q = IO::load(a.q, row0 + r);
+        t.k = IO::load(a.k, row0 + r);
+        t.v = IO::load(a.v, row0 + r);
+        t.gamma = a.gate[bth];
+        t.beta = a.beta ? a.beta[bth] : 1.0f;
+        t.alpha = a.alpha ? a.alpha[bth] : 1.0f;
+        t.lam = a.lambda ? a.lambda[bth] : 0.0f;
+        return t;
+    };
+    TokenIn next = fetch(0);
+    for (int tok = 0; tok < T; ++tok) {
+        const int64_t bth = ((int64_t)b * T + tok) * a.H + h;
+        const int64_t row0 = b * a.stride_b + tok * a.stride_t + h * a.stride_h;
+        const TokenIn in = next;
+        next = fetch(min(tok + 1, T - 1));
+        const float qr = in.q, kr = in.k, vr = in.v, gamma = in.gamma, beta = in.beta, alpha = in.alpha;
+        float kc[4];
+        my_columns(kr, kc);
+        // ---- state update (Eq. (CH)) and ||H_t||_F
+        float ss = 0.0f;
+        const float bv = beta * vr;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            hreg[e] = gamma * hreg[e] + beta * (kr * kc[e]);
+            ureg[e] = gamma * ureg[e] + bv * kc[e];
+            ss += hreg[e] * hreg[e];
+        }
+        const float fro = sqrtf(wave_sum(ss));
+        const float lam = a.lambda ? in.lam : a.lambda_scale * fro;          // Section 4.1: lambda_t = a ||H_t||_F
+        if (a.fro_out && lane == 0) a.fro_out[bth] = fro;
+        // ---- Algorithm 1 in residual form, component r in the four lanes of row r
+        // (the kernel is bound by its instruction count: reciprocals by the hardware instruction, 1 ulp)
+        const float L = fro + lam, mu = lam;
+        const float rcp = __builtin_amdgcn_rcpf(L + mu);
+        const float s0 = 2.0f * rcp;
+        const float rho = (L - mu) * rcp;
+        const float rho2 = rho * rho;
+        float xi = s0 * qr, dl = xi, rs = qr, omega = 2.0f;
+        for (int i = 0; i < a.n_iter; ++i) {
+            float xc[4];
+            my_columns(dl, xc);
+            const float hx = row_sum(hreg[0] * xc[0] + hreg[1] * xc[1] + hreg[2] * xc[2] + hreg[3] * xc[3]);
+            omega = 4.0f * __builtin_amdgcn_rcpf(4.0f - rho2 * omega);
+            rs -= hx + lam * dl;
+            dl = (omega - 1.0f) * dl + (omega * s0) * rs;
+            xi += dl;
+        }
+        if (a.xhat_out && c4 == 0) a.xhat_out[bth * D + r] = xi;
+        // ---- readout y = U (alpha xhat + (1 - alpha) q)
+        float xc[4];
+        my_columns(alpha * xi + (1.0f - alpha) * qr, xc);
+        const float y = row_sum(ureg[0] * xc[0] + ureg[1] * xc[1] + ureg[2] * xc[2] + ureg[3] * xc[3]);
+        if (c4 == 0) IO::store1(a.o, row0 + r, y);
+    }
+    if (a.H_state) *(f32x4 *)(a.H_state + state_off) = hreg;
+    if (a.U_state) *(f32x4 *)(a.U_state + state_off) = ureg;
+}
+
 template <class IO, int D, bool MULTI, bool LOWER>
 static void launch_one(const DecodeArgs &a, int n_pairs, hipStream_t stream)
 {
@@ -231,7 +326,10 @@ static void launch_decode(const DecodeArgs &a, int n_pairs, int d, hipStream_t s
         return;
     }
     switch (d) {
-    case 16: launch_one<IO, 16, MULTI, false>(a, n_pairs, stream); break;
+    case 16:
+        hipLaunchKernelGGL((decode_step_kernel_d16<IO>), dim3((unsigned)((n_pairs + 3) / 4)), dim3(256), 0, stream, a,
+                           n_pairs);
+        break;
     case 32: launch_one<IO, 32, MULTI, false>(a, n_pairs, stream); break;
     case 64: launch_one<IO, 64, MULTI, false>(a, n_pairs, stream); break;
     case 128: launch_one<IO, 128, MULTI, false>(a, n_pairs, stream); break;
