@@ -183,7 +183,9 @@ gka_status gka_forward(const gka_params *p,
  *   B H <= 341 fits. Larger: GKA_ERR_STATIC_SCRATCH, nothing is launched.
  *   Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race and
  *   give wrong results; calls on one stream, or ordered by events, are safe. Nothing in the array needs clearing
- *   between calls: every word a call reads it has written before. */
+ *   between calls: every word a call reads it has written before.
+ *   Under stream capture the call records kernel launches only. The first call on a device looks up the array's address
+ *   and sets kernel attributes: make it outside a capture. */
 #define GKA_STATIC_SCRATCH_BYTES (64u << 20)
 gka_status gka_forward_static(const gka_params *p,
                               const void *q, const void *k, const void *v,
