@@ -452,6 +452,8 @@ struct BackwardPlan {
     size_t off_m[6];          // gate_rev, zeros, s, fro, c, C
     size_t off_fin[3];        // final states of three reverse readouts (gradients at the initial states)
     size_t off_fwd, fwd_bytes, total;
+    bool reuse_states;        // the second solve runs on the chunk states of the first
+    size_t off_rws;           // scratch of the readouts (the forward workspace itself unless reuse_states)
     bool strided;             // q, k, v, dy come with explicit strides
     size_t off_pack[4];       // their packed copies
 };
@@ -495,8 +497,17 @@ gka_status make_backward_plan(const gka_params *p, BackwardPlan *bp)
     int rs_n, rs_len;
     plan_readout_segments(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk, &rs_n, &rs_len);
     const size_t rbytes = align_up(gka::gla_readout_workspace_bytes(p->B * p->H, rs_n, p->d_k, p->d_v), 256);
-    if (rbytes > bp->fwd_bytes) bp->fwd_bytes = rbytes;
-    bp->total = off + bp->fwd_bytes;
+    // bf16 tensors, one launch per phase: the second solve reuses the chunk states H_[n] that the first one left in the
+    // forward workspace (the same H_t), so the readouts in between get a scratch region of their own
+    bp->reuse_states = p->io_dtype == GKA_BF16 && full.pairs_per_batch >= full.n_pairs && full.slab_chunks >= full.n_chunks;
+    if (bp->reuse_states) {
+        bp->off_rws = off + bp->fwd_bytes;
+        bp->total = bp->off_rws + rbytes;
+    } else {
+        if (rbytes > bp->fwd_bytes) bp->fwd_bytes = rbytes;
+        bp->off_rws = bp->off_fwd;
+        bp->total = off + bp->fwd_bytes;
+    }
     return GKA_OK;
 }
 }  // namespace
@@ -576,9 +587,9 @@ gka_status gka_backward_from_state(const gka_params *p, const void *q, const voi
     // recurrence U_t = gate_t U_{t-1} + beta_t v_t k_t^T (the solve is reduced to its starting point and discarded)
     auto fwd = [&](const void *qq, const void *kk, const void *vv, const float *gg, const float *beta,
                    const float *alpha, int n_iter, void *out, float *xhat, float *fro_out = nullptr,
-                   bool solve_only = false, const void *q_lo = nullptr) {
+                   bool solve_only = false, const void *q_lo = nullptr, int phase = GKA_PHASE_ALL) {
         gka_params pp = *p;                      // lambda (or its rule) as given: only the two solves use it
-        pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat;
+        pp.beta = beta; pp.alpha = alpha; pp.n_iter = n_iter; pp.xhat_out = xhat; pp.phase = phase;
         pp.state_layout = GKA_STATE_FULL;
         const bool plain_readout = alpha == zeros;
         // (initial states reach the two solves; the composition of plain readouts for float32 tensors has none)
@@ -611,7 +622,7 @@ gka_status gka_backward_from_state(const gka_params *p, const void *q, const voi
         r.qk_stride_h = r.stride_h; r.qk_stride_t = r.stride_t; r.qk_stride_b = r.stride_b;
         r.H = p->H; r.T = p->T; r.n_pairs = p->B * p->H;
         plan_readout_segments(r.n_pairs, (p->T + gka::kChunk - 1) / gka::kChunk, &r.n_segs, &r.seg_len);
-        r.seg_buf = (float *)fws;
+        r.seg_buf = (float *)(ws + bp.off_rws);
         r.seg_logdecay = r.seg_buf + (size_t)r.n_pairs * r.n_segs * p->d_k * p->d_v;
         r.reverse = reverse; r.seg_mode = seg_mode;
         return gka::launch_gla_readout(r, p->d_k, p->d_v, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
@@ -637,8 +648,9 @@ gka_status gka_backward_from_state(const gka_params *p, const void *q, const voi
     else GKA_TRY(fwd(dy, v, k, gate, p->beta, zeros, 0, io(IO_DXT), nullptr));
     GKA_TRY(glue(1));
     // p_t = CH(H_t + lambda_t I, alpha_t dxt_t, r)
+    // (the chunk states H_[n] of the first solve are still in the forward workspace where the plan says so)
     GKA_TRY(fwd(io(IO_RHS), k, v, gate, p->beta, nullptr, p->n_iter, io(IO_SCRATCH), pf32, nullptr, fused,
-                fused ? io(IO_RHS_LO) : nullptr));
+                fused ? io(IO_RHS_LO) : nullptr, fused && bp.reuse_states ? GKA_PHASE_SOLVE : GKA_PHASE_ALL));
     // H_t x_t
     if (fused) GKA_TRY(readout(io(IO_X), k, k, p->beta, false, nullptr, 0, f32buf(3), io(IO_X_LO), nullptr, nullptr,
                                H_init));
