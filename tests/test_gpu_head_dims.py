@@ -169,3 +169,57 @@ def test_decode_at_other_head_dims(d, dtype, variants):
     assert torch.equal(Hd, Hs) and torch.equal(Ud, Us)
     assert np.abs(to_host(Hd) - rex["H_final"]).max() <= 1e-5 * np.abs(rex["H_final"]).max()
     assert np.abs(to_host(Ud) - rex["U_final"]).max() <= 1e-5 * np.abs(rex["U_final"]).max()
+
+
+def _random_case(i):
+    rng = np.random.default_rng(7000 + i)
+    d = int(rng.choice([16, 16, 32, 64, 128, 256]))
+    dtype = str(rng.choice(["f32", "bf16"]))
+    T = int(rng.integers(1, 40 if d == 256 else 260))
+    return dict(d=d, dtype=dtype, T=T, B=int(rng.integers(1, 4)), H=int(rng.integers(1, 6)),
+                n_iter=int(rng.choice([0, 1, 3, 8, 15])), beta=bool(rng.integers(2)), alpha=bool(rng.integers(2)),
+                rule=bool(rng.integers(2)), init=bool(rng.integers(2)), seed=7100 + i)
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_recurrent_path_random_configurations(i):
+    """Random shapes, head dimensions, dtypes and variants on the token-by-token path, with and without initial states:
+    output, ||H_t||_F, the solve's result and the final states against the oracle."""
+    import torch
+    c = _random_case(i)
+    d, dtype = c["d"], c["dtype"]
+    w = _workload(d, dtype, B=c["B"], H=c["H"], T=c["T"], n_iter=c["n_iter"], seed=c["seed"])
+    x = synth.make_inputs(w)
+    g = synth.make_gates(w)
+    okw, dkw = {}, {}
+    if c["beta"]:
+        okw["beta"], dkw["beta"] = g["beta"], to_device(g["beta"], "f32")
+    if c["alpha"]:
+        okw["alpha"], dkw["alpha"] = g["alpha"], to_device(g["alpha"], "f32")
+    if c["rule"]:
+        okw["lambda_scale"] = dkw["lambda_scale"] = 0.04
+    if c["init"]:
+        rng = np.random.default_rng(c["seed"] + 1)
+        A = rng.standard_normal((w.B, w.H, d, d)) / np.sqrt(d)
+        H0 = (A @ np.transpose(A, (0, 1, 3, 2))).astype(np.float32)
+        U0 = (rng.standard_normal((w.B, w.H, d, d)) / np.sqrt(d)).astype(np.float32)
+        okw.update(H_init=H0, U_init=U0)
+        dkw.update(H_init=to_device(H0, "f32"), U_init=to_device(U0, "f32"))
+    dev = upload_inputs(x, w.dtype)
+    o, ex = binding.gka_forward(dev["q"], dev["k"], dev["v"], dev["gate"], None if c["rule"] else dev["lam"], w.n_iter,
+                                path=binding.GKA_PATH_RECURRENT, return_fro=True, return_state=True, return_xhat=True,
+                                **dkw)
+    torch.cuda.synchronize()
+    ref, rex = oracle.forward(x["q"], x["k"], x["v"], x["gate"], None if c["rule"] else x["lam"], w.n_iter,
+                              return_fro=True, return_state=True, return_xhat=True, **okw)
+    y = to_host(o)
+    assert np.isfinite(y).all(), c
+    # (a sequence of a few tokens has no scale of its own per pair: the whole tensor's is taken, as for one token)
+    if w.T < 16:
+        assert np.abs(y - ref).max() <= TOL[dtype] * np.abs(ref).max(), c
+    else:
+        assert pair_rel_err(y, ref) <= TOL[dtype], c
+    assert np.abs(to_host(ex["fro"]) - rex["fro"]).max() <= 1e-5 * max(rex["fro"].max(), 1e-30), c
+    assert np.abs(to_host(ex["xhat"]) - rex["xhat"]).max() <= 1e-4 * np.abs(rex["xhat"]).max(), c
+    for n in ("H_final", "U_final"):
+        assert np.abs(to_host(ex[n]) - rex[n]).max() <= 1e-5 * np.abs(rex[n]).max(), (n, c)
