@@ -97,11 +97,11 @@ __device__ __forceinline__ float sum_over_kg(float x)
 // U is needed only for the state part of the readout and its own update, once per iteration; in between it is
 // parked in a scratch block of this workgroup in global memory (1 KiB per wave and tile, written and read by the same
 // lanes), so that the passes have its registers.
-constexpr int kParkStores = 8;           // vector-memory instructions of park_store
-__device__ __forceinline__ void park_store(f32x4 *slot, const f32x4 (&acc)[8])
+constexpr int kParkStores = 8;           // vector-memory instructions of park_store (one 16-byte store per tile)
+__device__ __forceinline__ void park_store(f32x4 *slot, const f32x4 (&acc)[kParkStores])
 {
 #pragma unroll
-    for (int jt = 0; jt < 8; ++jt) slot[jt * 64] = acc[jt];
+    for (int jt = 0; jt < kParkStores; ++jt) slot[jt * 64] = acc[jt];
 }
 __device__ __forceinline__ void park_load(const f32x4 *slot, f32x4 (&acc)[8])
 {
