@@ -255,7 +255,7 @@ def main():
         torch.cuda.synchronize()
         ms_decode = d0.elapsed_time(d1) / d_steps
         state_bytes = dB * dH * 2 * dd * dd * 4 * 2          # H and U, read and written
-        dk = "decode_step_kernel<IOBF16,128,false,false>"
+        dk = "decode_step_kernel<IOBF16,128,false,false,true>"
         result["decode"] = {"workload": f"{w5.name}: {dB} seq x {dH} heads, d={dd}, n_iter={w5.n_iter}, states prefilled "
                                         f"from {w5.T} tokens by gka_forward ({ms_prefill:.1f} ms), {d_steps} steps",
                             "ms_per_step": ms_decode, "sequence_tokens_per_s": dB / (ms_decode * 1e-3),
@@ -281,10 +281,10 @@ def main():
         lower_bytes = dB * dH * (dd * dd + 10 * 32 * 32) * 4 * 2
         result["decode"]["h_lower_blocks"] = {
             "ms_per_step": ms_lower, "sequence_tokens_per_s": dB / (ms_lower * 1e-3),
-            "roofline": {"kernel": "decode_step_kernel<IOBF16,128,false,true>", "bound": "hbm",
+            "roofline": {"kernel": "decode_step_kernel<IOBF16,128,false,true,true>", "bound": "hbm",
                          "achieved": lower_bytes / (ms_lower * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": lower_bytes / (ms_lower * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": committed_traffic("decode_step_kernel<IOBF16,128,false,true>")}}
+                         "traffic": committed_traffic("decode_step_kernel<IOBF16,128,false,true,true>")}}
         # several tokens per call (gka_decode_tokens): the states still cross HBM once per call
         multi = {}
         for nt in (4, 8):

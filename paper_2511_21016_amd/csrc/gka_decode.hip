@@ -29,13 +29,16 @@ struct DecodeShape {
 // MULTI = false: the single-step kernel, a.T == 1 known at compile time.
 // LOWER: of H_in / H_state only the 32 x 32 blocks on and below the block diagonal are read and written; the blocks
 // above are rebuilt in registers from their mirror images (through LDS, once per call), so the arithmetic is the same.
-template <class IO, int D, bool MULTI, bool LOWER>
+// STREAM: U is streamed (as always at d = 256) although it would fit: the single-token kernel at d = 128, which
+// then has room for a fourth workgroup per CU.
+template <class IO, int D, bool MULTI, bool LOWER, bool STREAM = false>
 __global__ __launch_bounds__(DecodeShape<D>::NTHR) void decode_step_kernel(DecodeArgs a)
 {
     typedef DecodeShape<D> SH;
     const int T = MULTI ? a.T : 1;
     constexpr int NTHR = SH::NTHR, C4 = SH::C4, RPI = SH::RPI, ITS = SH::ITS, NW = SH::NW;
-    constexpr bool STREAM_U = SH::STREAM_U;
+    constexpr bool STREAM_U = SH::STREAM_U || STREAM;
+    static_assert(!STREAM || !MULTI, "U is streamed once per token: at d < 256 only where a call is one token");
     const int t = threadIdx.x;
     const int pair = blockIdx.x;
     const int col4 = t % C4, rgrp = t / C4;
@@ -118,7 +121,8 @@ __global__ __launch_bounds__(DecodeShape<D>::NTHR) void decode_step_kernel(Decod
                 // beta (k_i k_j): the product of the two k components first, so that both mirror images of an
                 // element get the same bits
                 hreg[it][e] = gamma * hreg[it][e] + beta * (kr * kc[e]);
-                if constexpr (!STREAM_U) ureg[it][e] = gamma * ureg[it][e] + vr * kc[e];
+                // (the multiply-add written out: held or streamed, U gets the same bits)
+                if constexpr (!STREAM_U) ureg[it][e] = __builtin_fmaf(gamma, ureg[it][e], vr * kc[e]);
                 ss += hreg[it][e] * hreg[it][e];
             }
             if (tok == T - 1) {              // the stores drain while the last token is solved
@@ -185,8 +189,8 @@ __global__ __launch_bounds__(DecodeShape<D>::NTHR) void decode_step_kernel(Decod
         float xc[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) xc[e] = s_x[4 * col4 + e];
-        // (streamed U: four pieces in flight; all sixteen would not fit beside H)
-        constexpr int kReadoutUnroll = STREAM_U ? 4 : ITS;
+        // (streamed U: four pieces in flight at d = 256, where all sixteen would not fit beside H; eight at d = 128)
+        constexpr int kReadoutUnroll = SH::STREAM_U ? 4 : STREAM ? 8 : ITS;
 #pragma unroll kReadoutUnroll
         for (int it = 0; it < ITS; ++it) {
             f32x4 u;
@@ -195,12 +199,17 @@ __global__ __launch_bounds__(DecodeShape<D>::NTHR) void decode_step_kernel(Decod
                 // same thread stored at the previous token
                 const int64_t at = (int64_t)(it * NTHR + tv) * 4;
                 u = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-                if (tok > 0) u = *(const f32x4 *)(Us + at);
-                else if (Uin) u = *(const f32x4 *)(Uin + at);
+                if constexpr (MULTI) {
+                    if (tok > 0) u = *(const f32x4 *)(Us + at);
+                    else if (Uin) u = *(const f32x4 *)(Uin + at);
+                } else {
+                    if (Uin) u = __builtin_nontemporal_load((const f32x4 *)(Uin + at));
+                }
                 const float vr = beta * s_v[it * RPI + rgrp];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) u[e] = gamma * u[e] + vr * kc[e];
-                *(f32x4 *)(Us + at) = u;
+                for (int e = 0; e < 4; ++e) u[e] = __builtin_fmaf(gamma, u[e], vr * kc[e]);
+                if constexpr (MULTI) *(f32x4 *)(Us + at) = u;
+                else __builtin_nontemporal_store(u, (f32x4 *)(Us + at));
             } else {
                 u = ureg[it];
             }
@@ -312,6 +321,16 @@ __global__ __launch_bounds__(256) void decode_step_kernel_d16(DecodeArgs a, int 
 template <class IO, int D, bool MULTI, bool LOWER>
 static void launch_one(const DecodeArgs &a, int n_pairs, hipStream_t stream)
 {
+    // One token at d = 128: U is streamed through the readout instead of being held beside H (102 registers instead
+    // of 158: four workgroups per CU instead of three). Measured on two boxes of the pool, 8192 pairs: full layout
+    // 0.380 / 0.389 ms against 0.423 / 0.386 ms, block-lower layout 0.310 / 0.313 ms against 0.368 / 0.330 ms.
+    if constexpr (D == 128 && !MULTI) {
+        if (a.U_state) {
+            hipLaunchKernelGGL((decode_step_kernel<IO, D, MULTI, LOWER, true>), dim3((unsigned)n_pairs),
+                               dim3(DecodeShape<D>::NTHR), 0, stream, a);
+            return;
+        }
+    }
     hipLaunchKernelGGL((decode_step_kernel<IO, D, MULTI, LOWER>), dim3((unsigned)n_pairs), dim3(DecodeShape<D>::NTHR), 0,
                        stream, a);
 }
