@@ -308,9 +308,10 @@ gka_status gka_backward_from_state(const gka_params *p,
  *   Supported: GKA_BF16 tensors with GKA_COMPUTE_BF16, packed layout, zero initial states (else GKA_ERR_UNSUPPORTED;
  *   d_s out of range: GKA_ERR_SHAPE).
  *   workspace: gka_forward_sketched_workspace_bytes(p, d_s) bytes, 256-byte aligned; contents unspecified afterwards.
- * The solve runs on the forward kernels in 64 sketched dimensions (rows of zeros are appended to S, which changes
- * nothing); the readout is a separate kernel that keeps its state in registers and, for d = 128, works in the
- * sketched space: y_t = (U_t S^T) z_t with the d_v x 64 state built from the stored sketched keys. */
+ * Up to d_s = 32 the solve has kernels of its own (a 32 x 32 state per chunk, every operand of a pass in registers);
+ * above, it runs on the forward kernels in 64 sketched dimensions (rows of zeros are appended to S, which changes
+ * nothing). The readout is a separate kernel that keeps its state in registers and, for d = 128, works in the
+ * sketched space: y_t = (U_t S^T) z_t with the d_v x 32 or d_v x 64 state built from the stored sketched keys. */
 size_t gka_forward_sketched_workspace_bytes(const gka_params *p, int d_s);
 gka_status gka_forward_sketched(const gka_params *p,
                                 const void *q, const void *k, const void *v,

@@ -702,8 +702,10 @@ struct SketchPlan {
     size_t off_qs, off_ks, off_scratch, off_z, off_xhat, off_xhat_lo, off_fwd, fwd_bytes, total;
     gka_params inner;             // the solve's problem: d = 64, packed
     int rs_n, rs_len;
+    bool small;                   // d_s <= 32: the solve runs on sketch_solve_kernel
 };
 constexpr int kSketchDim = 64;
+constexpr int kSketchSmall = 32;
 gka_status make_sketch_plan(const gka_params *p, int d_s, SketchPlan *sp)
 {
     gka_status s = check_common(p, false);
@@ -732,6 +734,12 @@ gka_status make_sketch_plan(const gka_params *p, int d_s, SketchPlan *sp)
     plan_readout_segments(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk, &sp->rs_n, &sp->rs_len);
     const size_t rbytes = align_up(gka::gla_readout_workspace_bytes(p->B * p->H, sp->rs_n, p->d_k, p->d_v), 256);
     if (rbytes > sp->fwd_bytes) sp->fwd_bytes = rbytes;
+    // up to 32 sketched dimensions the solve has kernels of its own (their chunk states: 2 x 4 KiB per chunk)
+    sp->small = d_s <= kSketchSmall;
+    if (sp->small) {
+        const size_t sbytes = gka::sketch_solve_workspace_bytes(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk);
+        if (sbytes > sp->fwd_bytes) sp->fwd_bytes = sbytes;
+    }
     sp->total = off + sp->fwd_bytes;
     return GKA_OK;
 }
@@ -765,11 +773,22 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
     if (gka::launch_sketch(sa, n_pairs, p->d_k, false, stream) != hipSuccess) return GKA_ERR_LAUNCH;
     // z_t = CH(S H_t S^T + lambda_t I, S q_t, r): the forward pass on the sketched keys and queries, its own readout
     // discarded (the sketched keys stand in for its values)
-    gka_params inner = sp.inner;
-    inner.xhat_out = (float *)(ws + sp.off_z);
-    st = forward_impl(&inner, sa.qs, sa.ks, sa.ks, gate, lambda, ws + sp.off_scratch, nullptr, nullptr, nullptr, nullptr,
-                      nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr, false, true);
-    if (st != GKA_OK) return st;
+    if (sp.small) {
+        gka::SketchSolveArgs ss = {};
+        ss.qs = sa.qs; ss.ks = sa.ks; ss.gate = gate; ss.lambda = lambda; ss.beta = p->beta;
+        ss.lambda_scale = p->lambda_scale;
+        ss.z = (float *)(ws + sp.off_z);
+        ss.zero_upper = p->d_v != 128;           // (the up-projection of the d = 64 path reads all 64 stored features)
+        ss.T = p->T; ss.H = p->H; ss.n_pairs = n_pairs; ss.n_chunks = (p->T + gka::kChunk - 1) / gka::kChunk;
+        ss.n_iter = p->n_iter;
+        if (gka::launch_sketch_solve(ss, ws + sp.off_fwd, stream) != hipSuccess) return GKA_ERR_LAUNCH;
+    } else {
+        gka_params inner = sp.inner;
+        inner.xhat_out = (float *)(ws + sp.off_z);
+        st = forward_impl(&inner, sa.qs, sa.ks, sa.ks, gate, lambda, ws + sp.off_scratch, nullptr, nullptr, nullptr,
+                          nullptr, nullptr, ws + sp.off_fwd, sp.fwd_bytes, hip_stream, nullptr, false, true);
+        if (st != GKA_OK) return st;
+    }
     gka::ReadoutArgs r = {};                     // (optional pointers default to nullptr)
     r.k_lo = nullptr; r.v_lo = nullptr;
     r.v = v; r.o = o; r.o_f32 = nullptr; r.gate = gate; r.beta = p->beta;
@@ -786,7 +805,9 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
         r.qk_stride_h = kSketchDim; r.qk_stride_t = (int64_t)p->H * kSketchDim;
         r.qk_stride_b = (int64_t)p->T * p->H * kSketchDim;
         r.seg_logdecay = r.seg_buf + (size_t)n_pairs * r.n_segs * kSketchDim * p->d_v;
-        return gka::launch_gla_readout(r, kSketchDim, p->d_v, stream) == hipSuccess ? GKA_OK : GKA_ERR_LAUNCH;
+        // (up to 32 sketched dimensions: a d_v x 32 state on the first 32 stored features)
+        return gka::launch_gla_readout(r, sp.small ? kSketchSmall : kSketchDim, p->d_v, stream) == hipSuccess
+                   ? GKA_OK : GKA_ERR_LAUNCH;
     }
     // d = 64: xhat_t = S^T z_t as value + remainder, then y_t = U_t xhat_t with the state of Eq. (CH)
     if (gka::launch_sketch(sa, n_pairs, p->d_k, true, stream) != hipSuccess) return GKA_ERR_LAUNCH;

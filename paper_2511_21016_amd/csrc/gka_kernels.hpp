@@ -155,6 +155,21 @@ struct SketchArgs {
 };
 hipError_t launch_sketch(const SketchArgs &a, int n_pairs, int d, bool up, hipStream_t stream);
 
+// The solve of latent sketching in at most 32 sketched dimensions (gka_sketch_solve.hip).
+struct SketchSolveArgs {
+    const void *qs, *ks;          // [B,T,H,64] bf16 (zeros at and above d_s <= 32)
+    const float *gate;            // [B,T,H]
+    const float *lambda;          // [B,T,H], or nullptr: lambda_t = lambda_scale ||H_t||_F
+    const float *beta;            // [B,T,H] write gate, or nullptr
+    float lambda_scale;
+    float *z;                     // [B,T,H,64] float32 out: features 0..31
+    bool zero_upper;              // also write zeros to features 32..63 (for a reader of all 64)
+    int T, H, n_pairs, n_chunks, n_iter;
+    float *deltas, *states, *chunk_log2_decay;   // carved from the workspace by the launcher
+};
+size_t sketch_solve_workspace_bytes(int n_pairs, int n_chunks);
+hipError_t launch_sketch_solve(SketchSolveArgs a, void *workspace, hipStream_t stream);
+
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
                              hipStream_t stream);
 // Workgroups the state pass launches per segment of the chunk scan (the plan sizes the segments with it).

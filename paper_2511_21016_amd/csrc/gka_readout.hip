@@ -492,8 +492,10 @@ static hipError_t launch_readout_square(const ReadoutArgs &a, hipStream_t stream
 
 hipError_t launch_gla_readout(const ReadoutArgs &a, int dk, int dv, hipStream_t stream)
 {
-    if (a.q_is_f32) {                          // the sketched readout: float32 q, 64 sketched features, full v
-        if (dk != 64 || dv != 128 || a.q_lo || a.k_lo || a.v_lo) return hipErrorInvalidValue;
+    if (a.q_is_f32) {                          // the sketched readout: float32 q, 64 or 32 sketched features, full v
+        if ((dk != 64 && dk != 32) || dv != 128 || a.q_lo || a.k_lo || a.v_lo) return hipErrorInvalidValue;
+        if (dk == 32)
+            return a.beta ? launch_readout_d<32, 128, true, 2>(a, stream) : launch_readout_d<32, 128, false, 2>(a, stream);
         return a.beta ? launch_readout_d<64, 128, true, 2>(a, stream) : launch_readout_d<64, 128, false, 2>(a, stream);
     }
     if (dk != dv) return hipErrorInvalidValue;
