@@ -367,14 +367,19 @@ def main():
     # d = 256 at the model width of the headline workload.
     if not args.no_head_dims:
         result["other_head_dims"] = {}
-        for name, shape in (("d16_197_tokens", dict(B=256, H=24, T=197, d=16)), ("d256", dict(B=4, H=8, T=1024, d=256))):
+        rec = binding.GKA_PATH_RECURRENT
+        for name, shape, path, kernel in (
+                ("d16_197_tokens", dict(B=256, H=24, T=197, d=16), binding.GKA_PATH_AUTO, "small_solve_kernel (chunk-wise, d <= 32)"),
+                ("d16_197_tokens_recurrent", dict(B=256, H=24, T=197, d=16), rec, "decode_step_kernel_d16 (path recurrent)"),
+                ("d256", dict(B=4, H=8, T=1024, d=256), binding.GKA_PATH_AUTO, "decode_step_kernel (path recurrent)")):
             wd = w.scaled(seed=w.seed + 50, **shape)
             xd = upload_inputs(synth.make_inputs(wd), "bf16")
             od = torch.empty_like(xd["v"])
-            pd = binding.make_params(wd.B, wd.H, wd.T, wd.d, wd.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16)
+            pd = binding.make_params(wd.B, wd.H, wd.T, wd.d, wd.n_iter, binding.GKA_BF16, binding.GKA_COMPUTE_BF16,
+                                     path=path)
             wsd = torch.empty(binding.forward_workspace_bytes(pd), dtype=torch.uint8, device="cuda")
             call = lambda: binding.gka_forward(xd["q"], xd["k"], xd["v"], xd["gate"], xd["lam"], wd.n_iter,
-                                               workspace=wsd, out=od)
+                                               workspace=wsd, out=od, path=path)
             call()
             torch.cuda.synchronize()
             d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -386,7 +391,7 @@ def main():
             ms_d = d0.elapsed_time(d1) / 3
             result["other_head_dims"][name] = {"B": wd.B, "H": wd.H, "T": wd.T, "d": wd.d, "ms_per_step": ms_d,
                                                "tokens_per_s": wd.B * wd.H * wd.T / (ms_d * 1e-3),
-                                               "kernel": "decode_step_kernel (path recurrent)"}
+                                               "kernel": kernel}
             del xd, od, wsd
 
     if not args.no_cpu_baseline:

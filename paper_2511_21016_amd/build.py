@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgka.so")
 SOURCES = ["gka_api.hip", "gka_state_pass.hip", "gka_chunk_solve.hip", "gka_fused.hip", "gka_decode.hip",
-           "gka_backward.hip", "gka_readout.hip", "gka_sketch.hip", "gka_sketch_solve.hip"]
+           "gka_backward.hip", "gka_readout.hip", "gka_sketch.hip", "gka_small_dim.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-FP32 instructions are kept out of the generated code on purpose

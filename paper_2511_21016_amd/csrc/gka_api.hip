@@ -18,6 +18,7 @@ struct Plan {
     int pairs_per_batch;          // (batch, head) pairs per launch
     int slab_chunks;              // chunks of every pair per launch
     bool recurrent;               // token-by-token kernel: no chunks, no launch plan
+    bool small;                   // chunk-wise kernels of the head dimensions 16 and 32 (bf16 tensors and operands)
     bool split;                   // GKA_COMPUTE_BF16_SPLIT (fused kernel only)
     bool fused_shape;             // dtype, operands and head dimension of the fused kernel
     int fused_n_segs, fused_seg_len;
@@ -71,7 +72,11 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
     pl->io_bf16 = p->io_dtype == GKA_BF16;
     pl->compute_bf16 = p->compute != GKA_COMPUTE_F32;
     pl->split = p->compute == GKA_COMPUTE_BF16_SPLIT;
-    pl->recurrent = p->path == GKA_PATH_RECURRENT || !chunked_dim(pl->d);
+    // d = 16, 32: chunk-wise kernels of their own for bf16 tensors with bf16 operands (what GKA_PATH_AUTO and
+    // GKA_PATH_TWO_PHASE select there), else token by token
+    pl->small = pl->d <= 32 && pl->io_bf16 && p->compute == GKA_COMPUTE_BF16 && !readout_only &&
+                (p->path == GKA_PATH_AUTO || p->path == GKA_PATH_TWO_PHASE);
+    pl->recurrent = !pl->small && (p->path == GKA_PATH_RECURRENT || !chunked_dim(pl->d));
     if (pl->recurrent && (p->path == GKA_PATH_TWO_PHASE || p->path == GKA_PATH_FUSED || readout_only))
         return GKA_ERR_UNSUPPORTED;
     if ((int64_t)pl->n_pairs * pl->n_chunks > (int64_t)0x7fffffff) return GKA_ERR_SHAPE;
@@ -89,6 +94,13 @@ gka_status make_plan(const gka_params *p, Plan *pl, bool readout_only = false)
         pl->stride_b = p->stride_b;
         pl->stride_t = p->stride_t;
         pl->stride_h = p->stride_h;
+    }
+    if (pl->small) {
+        if ((int64_t)pl->n_pairs * pl->n_chunks > (int64_t)0x7fffffff / 4) return GKA_ERR_SHAPE;
+        pl->fused_shape = false;
+        pl->fused_bytes = 0;
+        pl->total = align_up(gka::small_dim_workspace_bytes(pl->n_pairs, pl->n_chunks, pl->d, true), 256);
+        return GKA_OK;
     }
     if (pl->recurrent) {
         // states stay in registers; only d = 256 streams U through memory and needs room for it when the caller does
@@ -208,6 +220,23 @@ gka_status forward_impl(const gka_params *p, const void *q, const void *k, const
     hipStream_t stream = (hipStream_t)hip_stream;
     char *ws = (char *)workspace;
 
+    if (pl.small) {
+        if (p->phase != GKA_PHASE_ALL || solve_only || q_lo) return GKA_ERR_UNSUPPORTED;
+        gka::SmallArgs sm = {};
+        sm.q = q; sm.k = k; sm.v = v; sm.o = o;
+        sm.stride_b = pl.stride_b; sm.stride_t = pl.stride_t; sm.stride_h = pl.stride_h;
+        sm.d = pl.d;
+        sm.gate = gate; sm.lambda = lambda; sm.beta = p->beta; sm.alpha = p->alpha; sm.lambda_scale = p->lambda_scale;
+        sm.xhat_out = p->xhat_out; sm.xhat_row = pl.d; sm.xhat_zero_upper = false;
+        sm.fro_out = fro_out;
+        sm.H_init = H_init; sm.U_init = U_init; sm.H_final = H_final; sm.U_final = U_final;
+        sm.T = p->T; sm.H = p->H; sm.n_pairs = pl.n_pairs; sm.n_chunks = pl.n_chunks; sm.n_iter = p->n_iter;
+        // (profiling: all of it is reported as the solve phase)
+        if (prof) { prof->mark(stream); prof->mark(stream); }
+        if (gka::launch_small_dim_forward(sm, ws, stream) != hipSuccess) return GKA_ERR_LAUNCH;
+        if (prof) prof->mark(stream);
+        return GKA_OK;
+    }
     if (pl.recurrent) {
         if (p->phase != GKA_PHASE_ALL || pl.split || solve_only || q_lo) return GKA_ERR_UNSUPPORTED;
         gka::DecodeArgs da = {};
@@ -737,7 +766,7 @@ gka_status make_sketch_plan(const gka_params *p, int d_s, SketchPlan *sp)
     // up to 32 sketched dimensions the solve has kernels of its own (their chunk states: 2 x 4 KiB per chunk)
     sp->small = d_s <= kSketchSmall;
     if (sp->small) {
-        const size_t sbytes = gka::sketch_solve_workspace_bytes(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk);
+        const size_t sbytes = gka::small_dim_workspace_bytes(p->B * p->H, (p->T + gka::kChunk - 1) / gka::kChunk, kSketchSmall, false);
         if (sbytes > sp->fwd_bytes) sp->fwd_bytes = sbytes;
     }
     sp->total = off + sp->fwd_bytes;
@@ -774,14 +803,16 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
     // z_t = CH(S H_t S^T + lambda_t I, S q_t, r): the forward pass on the sketched keys and queries, its own readout
     // discarded (the sketched keys stand in for its values)
     if (sp.small) {
-        gka::SketchSolveArgs ss = {};
-        ss.qs = sa.qs; ss.ks = sa.ks; ss.gate = gate; ss.lambda = lambda; ss.beta = p->beta;
-        ss.lambda_scale = p->lambda_scale;
-        ss.z = (float *)(ws + sp.off_z);
-        ss.zero_upper = p->d_v != 128;           // (the up-projection of the d = 64 path reads all 64 stored features)
+        gka::SmallArgs ss = {};                  // (no values, no output: the solve alone)
+        ss.q = sa.qs; ss.k = sa.ks;
+        ss.stride_h = kSketchDim; ss.stride_t = (int64_t)p->H * kSketchDim; ss.stride_b = (int64_t)p->T * p->H * kSketchDim;
+        ss.d = kSketchSmall;
+        ss.gate = gate; ss.lambda = lambda; ss.beta = p->beta; ss.lambda_scale = p->lambda_scale;
+        ss.xhat_out = (float *)(ws + sp.off_z); ss.xhat_row = kSketchDim;
+        ss.xhat_zero_upper = p->d_v != 128;      // (the up-projection of the d = 64 path reads all 64 stored features)
         ss.T = p->T; ss.H = p->H; ss.n_pairs = n_pairs; ss.n_chunks = (p->T + gka::kChunk - 1) / gka::kChunk;
         ss.n_iter = p->n_iter;
-        if (gka::launch_sketch_solve(ss, ws + sp.off_fwd, stream) != hipSuccess) return GKA_ERR_LAUNCH;
+        if (gka::launch_small_dim_forward(ss, ws + sp.off_fwd, stream) != hipSuccess) return GKA_ERR_LAUNCH;
     } else {
         gka_params inner = sp.inner;
         inner.xhat_out = (float *)(ws + sp.off_z);

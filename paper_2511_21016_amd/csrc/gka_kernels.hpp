@@ -155,20 +155,29 @@ struct SketchArgs {
 };
 hipError_t launch_sketch(const SketchArgs &a, int n_pairs, int d, bool up, hipStream_t stream);
 
-// The solve of latent sketching in at most 32 sketched dimensions (gka_sketch_solve.hip).
-struct SketchSolveArgs {
-    const void *qs, *ks;          // [B,T,H,64] bf16 (zeros at and above d_s <= 32)
+// Chunk-wise forward pass for head dimensions up to 32 (gka_small_dim.hip): the layer at d = 16 and 32, and, without
+// values and output, the solve of latent sketching in at most 32 sketched dimensions. bf16 tensors.
+struct SmallArgs {
+    const void *q, *k;            // rows of d features
+    const void *v;                // rows of d features, or nullptr: no readout (then o is nullptr too)
+    void *o;
+    int64_t stride_b, stride_t, stride_h;   // of q, k, v, o, in elements (multiples of 8)
+    int d;                        // 16 or 32 features per row exist; the kernels work in 32
     const float *gate;            // [B,T,H]
     const float *lambda;          // [B,T,H], or nullptr: lambda_t = lambda_scale ||H_t||_F
-    const float *beta;            // [B,T,H] write gate, or nullptr
+    const float *beta, *alpha;    // [B,T,H] write gate / alpha-connection, or nullptr
     float lambda_scale;
-    float *z;                     // [B,T,H,64] float32 out: features 0..31
-    bool zero_upper;              // also write zeros to features 32..63 (for a reader of all 64)
+    float *xhat_out;              // optional float32 out, xhat_row elements per token, features 0 .. d - 1 written
+    int64_t xhat_row;
+    bool xhat_zero_upper;         // also write zeros to features 32..63 of a row (for a reader of 64 stored features)
+    float *fro_out;               // optional [B,T,H]
+    const float *H_init, *U_init; // optional [pairs, d, d] float32
+    float *H_final, *U_final;     // optional
     int T, H, n_pairs, n_chunks, n_iter;
-    float *deltas, *states, *chunk_log2_decay;   // carved from the workspace by the launcher
+    float *dH, *sH, *dU, *sU, *chunk_log2_decay;   // carved from the workspace by the launcher
 };
-size_t sketch_solve_workspace_bytes(int n_pairs, int n_chunks);
-hipError_t launch_sketch_solve(SketchSolveArgs a, void *workspace, hipStream_t stream);
+size_t small_dim_workspace_bytes(int n_pairs, int n_chunks, int d, bool with_readout);
+hipError_t launch_small_dim_forward(SmallArgs a, void *workspace, hipStream_t stream);
 
 hipError_t launch_state_pass(const StatePassArgs &a, int n_pairs, int d, bool io_bf16, bool compute_bf16,
                              hipStream_t stream);

@@ -46,8 +46,13 @@ def test_workspace_query(lib):
     # two chunks of a longer sequence need more scratch
     assert binding.forward_workspace_bytes(_p(T=1000)) > binding.forward_workspace_bytes(_p(T=100))
     assert binding.forward_workspace_bytes(_p(d=96)) == 0
+    # d = 16, 32 with bf16 operands: chunk-wise kernels with materialised d x d chunk states (two chunks of four
+    # pairs: deltas and states of H and U, and the chunks' decays)
+    assert binding.forward_workspace_bytes(_p(d=16)) == 4 * (2 * 4 * 16 * 16 * 4) + 256
+    assert binding.forward_workspace_bytes(_p(d=32)) == 4 * (2 * 4 * 32 * 32 * 4) + 256
     # the token-by-token path keeps the states in registers; only d = 256 streams U through memory
-    assert binding.forward_workspace_bytes(_p(d=16)) == 256
+    assert binding.forward_workspace_bytes(_p(d=16, path=binding.GKA_PATH_RECURRENT)) == 256
+    assert binding.forward_workspace_bytes(_p(d=16, io_dtype=binding.GKA_F32, compute=binding.GKA_COMPUTE_F32)) == 256
     assert binding.forward_workspace_bytes(_p(path=binding.GKA_PATH_RECURRENT)) == 256
     assert binding.forward_workspace_bytes(_p(d=256)) == 256 + 4 * 256 * 256 * 4
     assert binding.forward_workspace_bytes(_p(T=0)) == 0
@@ -86,8 +91,12 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(_p(state_layout=2)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(state_layout=binding.GKA_STATE_H_LOWER_BLOCKS), ws=None) == binding.GKA_ERR_WORKSPACE   # valid layout
     assert fwd(_p(), H_init=fake) == binding.GKA_ERR_NULL                        # H_init without U_init
-    # head dimensions 16, 32 and 256 run token by token only; that path has no phases and no split operands
-    assert fwd(_p(d=16, path=binding.GKA_PATH_TWO_PHASE)) == binding.GKA_ERR_UNSUPPORTED
+    # head dimension 256, and 16 and 32 with float32 operands, run token by token only; that path has no phases and
+    # no split operands; the chunk-wise kernels of 16 and 32 have no phases either
+    assert fwd(_p(d=16, path=binding.GKA_PATH_TWO_PHASE, io_dtype=binding.GKA_F32,
+                  compute=binding.GKA_COMPUTE_F32)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(d=16, path=binding.GKA_PATH_FUSED)) == binding.GKA_ERR_UNSUPPORTED
+    assert fwd(_p(d=16, compute=binding.GKA_COMPUTE_BF16_SPLIT, path=binding.GKA_PATH_TWO_PHASE)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(d=256, path=binding.GKA_PATH_FUSED)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(d=256, state_layout=binding.GKA_STATE_H_LOWER_BLOCKS)) == binding.GKA_ERR_UNSUPPORTED
     assert fwd(_p(d=32, phase=binding.GKA_PHASE_STATES)) == binding.GKA_ERR_UNSUPPORTED
