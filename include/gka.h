@@ -79,9 +79,12 @@ typedef enum { GKA_PHASE_ALL = 0, GKA_PHASE_STATES = 1, GKA_PHASE_SOLVE = 2 } gk
 typedef enum { GKA_STATE_FULL = 0, GKA_STATE_H_LOWER_BLOCKS = 1 } gka_state_layout;
 
 /* Which kernels gka_forward runs.
- * GKA_PATH_AUTO     : the library's choice (the fused kernel where it applies, else the two-phase kernels).
+ * GKA_PATH_AUTO     : the library's choice (the fused kernel where it applies, else the two-phase kernels; token by
+ *                     token where there are no chunk-wise kernels).
  * GKA_PATH_TWO_PHASE: chunk initial states H_[n], U_[n] of Section 4.2.1 are computed and stored in the workspace
- *                     first, then every chunk is solved independently (all dtypes, head dimensions and variants).
+ *                     first, then every chunk is solved independently. d = 64, 128: all dtypes and variants; d = 16,
+ *                     32: GKA_BF16 tensors with GKA_COMPUTE_BF16, all variants, GKA_PHASE_ALL (kernels of their own,
+ *                     whose matrix products cover a whole state in one instruction).
  * GKA_PATH_FUSED    : one kernel walks the chunks of a pair in order with H and U in registers, so that no chunk state
  *                     crosses HBM. Available for GKA_BF16 tensors with GKA_COMPUTE_BF16 (or _SPLIT), d = 128, with or without
  *                     the layer's variants (beta, alpha, the rule for lambda) but without xhat_out, GKA_PHASE_ALL;
@@ -89,11 +92,10 @@ typedef enum { GKA_STATE_FULL = 0, GKA_STATE_H_LOWER_BLOCKS = 1 } gka_state_layo
  * GKA_PATH_RECURRENT: Eq. (CH) token by token, one workgroup per (batch, head) pair with the states in registers (the
  *                     kernel of gka_decode_tokens), float32 arithmetic whatever p->compute says. Every head dimension,
  *                     dtype, stride and variant, with xhat_out and fro_out; GKA_PHASE_ALL only. It is the only path
- *                     for d = 16, 32 and 256 (what GKA_PATH_AUTO selects there; the two chunk-wise paths return
- *                     GKA_ERR_UNSUPPORTED) and its parallelism is the number of pairs: meant for short sequences over
- *                     many heads (head dimension 16 of the vision models, Appendix L) and as a float32 cross-check
- *                     of the chunk-wise kernels, not for long sequences over few pairs. Gates are used as given
- *                     (no floor at exp(-100)). */
+ *                     for d = 256 and for float32 tensors or operands at d = 16 and 32 (what GKA_PATH_AUTO selects
+ *                     there) and its parallelism is the number of pairs: meant for short sequences over many heads
+ *                     and as a float32 cross-check of the chunk-wise kernels, not for long sequences over few
+ *                     pairs. Gates are used as given (no floor at exp(-100)). */
 typedef enum { GKA_PATH_AUTO = 0, GKA_PATH_TWO_PHASE = 1, GKA_PATH_FUSED = 2, GKA_PATH_RECURRENT = 3 } gka_path;
 
 typedef struct {
@@ -144,7 +146,8 @@ typedef struct {
  * chunks at a time: large problems are processed as a sequence of such launches, the running states
  * carried from slab to slab in float32, so that the workspace stays bounded (about 1 GiB of chunk
  * states; p->slab_state_bytes overrides that budget). The fused kernel (gka_path) needs only the segment summaries
- * of its chunk walk; the query returns the larger of the two sizes. The token-by-token path (GKA_PATH_RECURRENT) keeps
+ * of its chunk walk; the query returns the larger of the two sizes. The chunk-wise kernels of d = 16 and 32 keep four
+ * d x d float32 states per chunk. The token-by-token path (GKA_PATH_RECURRENT) keeps
  * its states in registers: 256 bytes, plus one U state per pair at d = 256. Its contents after a call are unspecified. */
 size_t gka_forward_workspace_bytes(const gka_params *p);
 
