@@ -862,6 +862,6 @@ const char *gka_status_string(gka_status s)
     return "unknown status";
 }
 
-int gka_version(void) { return 800; }
+int gka_version(void) { return 810; }
 
 }  // extern "C"
