@@ -794,7 +794,9 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
     hipStream_t stream = (hipStream_t)hip_stream;
     unsigned char *ws = (unsigned char *)workspace;
     gka::SketchArgs sa = {};
-    sa.q = q; sa.k = k; sa.S = S; sa.d_s = d_s; sa.per_head = sketch_per_head != 0;
+    // stored width of the sketched tensors: 32 where everything downstream works in 32 dimensions
+    const int sw = sp.small && p->d_v == 128 ? kSketchSmall : kSketchDim;
+    sa.q = q; sa.k = k; sa.S = S; sa.d_s = d_s; sa.per_head = sketch_per_head != 0; sa.out_width = sw;
     sa.qs = ws + sp.off_qs; sa.ks = ws + sp.off_ks; sa.z = (const float *)(ws + sp.off_z);
     sa.xhat_hi = ws + sp.off_xhat; sa.xhat_lo = ws + sp.off_xhat_lo;
     sa.T = p->T; sa.H = p->H;
@@ -805,11 +807,11 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
     if (sp.small) {
         gka::SmallArgs ss = {};                  // (no values, no output: the solve alone)
         ss.q = sa.qs; ss.k = sa.ks;
-        ss.stride_h = kSketchDim; ss.stride_t = (int64_t)p->H * kSketchDim; ss.stride_b = (int64_t)p->T * p->H * kSketchDim;
+        ss.stride_h = sw; ss.stride_t = (int64_t)p->H * sw; ss.stride_b = (int64_t)p->T * p->H * sw;
         ss.d = kSketchSmall;
         ss.gate = gate; ss.lambda = lambda; ss.beta = p->beta; ss.lambda_scale = p->lambda_scale;
-        ss.xhat_out = (float *)(ws + sp.off_z); ss.xhat_row = kSketchDim;
-        ss.xhat_zero_upper = p->d_v != 128;      // (the up-projection of the d = 64 path reads all 64 stored features)
+        ss.xhat_out = (float *)(ws + sp.off_z); ss.xhat_row = sw;
+        ss.xhat_zero_upper = sw == kSketchDim;   // (the up-projection of the d = 64 path reads all 64 stored features)
         ss.T = p->T; ss.H = p->H; ss.n_pairs = n_pairs; ss.n_chunks = (p->T + gka::kChunk - 1) / gka::kChunk;
         ss.n_iter = p->n_iter;
         if (gka::launch_small_dim_forward(ss, ws + sp.off_fwd, stream) != hipSuccess) return GKA_ERR_LAUNCH;
@@ -833,8 +835,8 @@ gka_status gka_forward_sketched(const gka_params *p, const void *q, const void *
         // stored sketched keys and the float32 z_t (split into value + remainder inside the kernel), with a d_v x 64
         // state; the projected solution xhat_t is never formed
         r.q = sa.z; r.q_lo = nullptr; r.q_is_f32 = true; r.k = sa.ks;
-        r.qk_stride_h = kSketchDim; r.qk_stride_t = (int64_t)p->H * kSketchDim;
-        r.qk_stride_b = (int64_t)p->T * p->H * kSketchDim;
+        r.qk_stride_h = sw; r.qk_stride_t = (int64_t)p->H * sw;
+        r.qk_stride_b = (int64_t)p->T * p->H * sw;
         r.seg_logdecay = r.seg_buf + (size_t)n_pairs * r.n_segs * kSketchDim * p->d_v;
         // (up to 32 sketched dimensions: a d_v x 32 state on the first 32 stored features)
         return gka::launch_gla_readout(r, sp.small ? kSketchSmall : kSketchDim, p->d_v, stream) == hipSuccess

@@ -148,7 +148,8 @@ struct SketchArgs {
     const float *S;               // [d_s, d] float32, or [H, d_s, d] with per_head
     int d_s;
     bool per_head;
-    void *qs, *ks;                // [B,T,H,64] bf16
+    void *qs, *ks;                // [B,T,H,out_width] bf16
+    int out_width;                // stored sketched features per token: 64, or 32 (down-projection with d_s <= 32 only)
     const float *z;               // [B,T,H,64]
     void *xhat_hi, *xhat_lo;      // [B,T,H,d] bf16; xhat_lo may be nullptr
     int T, H;

@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void sketch_down_kernel(SketchArgs a)
     auto store = [&](void *out, const f32x16 &acc) {
         const int t = t0 + 32 * tb + n;
         if (t >= a.T) return;
-        const int64_t orow = (((int64_t)b * a.T + t) * a.H + h) * kSketchPad;
+        const int64_t orow = (((int64_t)b * a.T + t) * a.H + h) * a.out_width;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4)
             IOBF16::store4(out, orow + 32 * mt + 8 * q4 + 4 * g, acc[4 * q4], acc[4 * q4 + 1], acc[4 * q4 + 2],
@@ -101,14 +101,16 @@ __global__ __launch_bounds__(256) void sketch_down_kernel(SketchArgs a)
         __syncthreads();                           // S is staged; the previous group's k rows have been read
         stage(rq);
         __syncthreads();
+        // (32 stored features: the waves of the upper 32 have nothing to compute or store)
+        const bool mine = 32 * mt < a.out_width;   // (wave-uniform)
         f32x16 acc;
-        project(acc);
+        if (mine) project(acc);
         __syncthreads();                           // every wave has read its q rows
         stage(rk);
-        store(a.qs, acc);
+        if (mine) store(a.qs, acc);
         __syncthreads();
-        project(acc);
-        store(a.ks, acc);
+        if (mine) project(acc);
+        if (mine) store(a.ks, acc);
     }
 }
 
@@ -183,6 +185,7 @@ __global__ __launch_bounds__(256) void sketch_up_kernel(SketchArgs a)
 
 hipError_t launch_sketch(const SketchArgs &a, int n_pairs, int d, bool up, hipStream_t stream)
 {
+    if (!up && a.out_width != kSketchPad && !(a.out_width == 32 && a.d_s <= 32)) return hipErrorInvalidValue;
     const dim3 grid(n_pairs, (a.T + 127) / 128), grid_down(n_pairs, (a.T + 64 * kDownGroups - 1) / (64 * kDownGroups)), block(256);
     if (up) {
         if (d == 128) hipLaunchKernelGGL(sketch_up_kernel<128>, grid, block, 0, stream, a);
