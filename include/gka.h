@@ -102,8 +102,8 @@ typedef struct {
     int32_t B;            /* batch (gka_decode_step: number of sequences)                      */
     int32_t H;            /* heads                                                             */
     int32_t T;            /* tokens per sequence (ignored by gka_decode_step); any T >= 1      */
-    int32_t d_k;          /* head dimension of q, k: 16, 32, 64, 128 or 256 (chunk-wise kernels, */
-                          /*   gka_backward and gka_forward_sketched: 64 or 128; see gka_path)    */
+    int32_t d_k;          /* head dimension of q, k: 16, 32, 64, 128 or 256 (gka_backward and    */
+                          /*   gka_forward_sketched: 64 or 128; which kernels run: see gka_path)  */
     int32_t d_v;          /* head dimension of v, o: must equal d_k                            */
     int32_t chunk;        /* chunk size C of Section 4.2.1: 64 (T need not be a multiple)      */
     int32_t n_iter;       /* r of Algorithm 1 = number of loop passes; 0 returns U_t xi_0      */

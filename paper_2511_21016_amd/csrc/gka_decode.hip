@@ -3,7 +3,7 @@
 // all arithmetic fp32. The states are read once, advanced by a.T tokens in registers and written once, so the state
 // traffic of a call does not grow with the number of tokens. The same kernel is gka_forward's recurrent path (any
 // number of tokens, separate initial and final states, ||H_t||_F and the solve's result as optional outputs), the
-// only one for the head dimensions 16, 32 and 256.
+// only one for the head dimension 256 and for float32 tensors at 16 and 32.
 //
 // The d x d states are distributed as float4 pieces in flat row-major order, piece (it*NTHR + t) on thread
 // t, so that state reads and writes are fully coalesced: thread t holds, for each of its ITS pieces, row
