@@ -987,7 +987,11 @@ __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(2
         lds_barrier();                   // xhat of the chunks is visible; the key-row fragments are dead
         // ---- 6
         // k rows of the next chunks: the row tiles are free from here on (every wave has formed its v fragments); the
-        // copies land during the readout
+        // copies land during the readout.
+        // U, on its way back from its parking place since before the last barrier but one, is awaited first: the
+        // compiler does not count the copies, so the wait it would otherwise place before the first use of U (for all
+        // but the loads it knows to be younger) would also wait for copies to land (1 % of the kernel).
+        wait_all_memory();
         copy_rows_untracked(c, a.k, 0, c0 + kChunksPerIter);
         if constexpr (!SPLIT) copy_rows_untracked(c, a.k, 1, c0 + 3);
         // gates of the next chunks
