@@ -723,15 +723,16 @@ gka_status gka_backward_from_state(const gka_params *p, const void *q, const voi
     return GKA_OK;
 }
 
-// ---- latent sketching: down-projection, the solve in 64 (zero-padded) sketched dimensions on the forward kernels,
-// up-projection, plain readout with the full U_t
+// ---- latent sketching: down-projection, the solve in the sketched space (up to 32 dimensions on the kernels of
+// gka_small_dim.hip, else in 64 zero-padded dimensions on the forward kernels), readout in the sketched space (d = 128)
+// or up-projection and plain readout with the full U_t (d = 64)
 namespace {
 struct SketchPlan {
     size_t n_tokens;
     size_t off_qs, off_ks, off_scratch, off_z, off_xhat, off_xhat_lo, off_fwd, fwd_bytes, total;
     gka_params inner;             // the solve's problem: d = 64, packed
     int rs_n, rs_len;
-    bool small;                   // d_s <= 32: the solve runs on sketch_solve_kernel
+    bool small;                   // d_s <= 32: the solve runs on the kernels of gka_small_dim.hip
 };
 constexpr int kSketchDim = 64;
 constexpr int kSketchSmall = 32;
